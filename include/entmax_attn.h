@@ -1,0 +1,151 @@
+/*
+ * entmax_attn.h -- C ABI of the MI355X (gfx950) alpha-entmax / ASEntmax
+ * attention library.
+ *
+ * The operation (paper Sec. 2.1, Sec. 2.2 eq. (entmax), Sec. 4.1 eq. (asentmax)):
+ * for every batch b, head h and query row i
+ *
+ *     z_ij  = <q_i, k_j> / sqrt(D)                      visible keys j only
+ *     s_ij  = scale_i * z_ij,   scale_i = delta + beta * (ln n)^gamma
+ *     p_ij  = [ (alpha-1) s_ij - tau_i ]_+ ^ (1/(alpha-1)),   sum_j p_ij = 1
+ *     o_i   = sum_j p_ij v_j
+ *
+ * tau_i is the entmax threshold of row i (App. A); keys with
+ * (alpha-1) s_ij <= tau_i get exactly zero weight.  Under the causal flag key j
+ * is visible to query i iff j <= i + (Nk - Nq).  The backward pass applies the
+ * exact Jacobian of eq. (entmax): g = p^(2-alpha), dS = g * (dP - sum(g dP)/sum(g)),
+ * and the chain rule through scale_i to beta and gamma.
+ *
+ * Conventions common to all entry points
+ *   - Every pointer except `p` and `phase_events` is DEVICE memory owned by the
+ *     caller; the library allocates and frees nothing and keeps no state.
+ *   - All work is enqueued on `hip_stream` (a hipStream_t; NULL = default
+ *     stream); no entry point synchronises.
+ *   - Q, O, dO, dQ are [B,H,Nq,D]; K, V, dK, dV are [B,H,Nk,D]; the last
+ *     dimension is contiguous; batch/head/row strides are given in elements
+ *     (0 = contiguous default).  Element type per `dtype`.  Pointers and row
+ *     strides must be 16-byte aligned.
+ *   - tau is [B,H,Nq] fp32 contiguous, in the units of eq. (entmax).
+ *   - beta, gamma: fp32, [H] (scale_layout 1) or [B,H,Nq] (scale_layout 2),
+ *     ignored (may be NULL) for scale_layout 0 where scale_i = delta.
+ *   - Return value: 0 on success, a negative entmax_attn_status otherwise.
+ *     Arguments are validated on the host before anything is launched; on
+ *     error nothing has been enqueued.
+ */
+#ifndef ENTMAX_ATTN_H
+#define ENTMAX_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  ENTMAX_ATTN_OK = 0,
+  ENTMAX_ATTN_INVALID_ARG = -1,       /* NULL where a pointer is required, bad enum, non-positive size, alpha outside (1,2] */
+  ENTMAX_ATTN_UNSUPPORTED_SHAPE = -2, /* D not in {64,128}, sizes beyond the index range */
+  ENTMAX_ATTN_MISALIGNED = -3,        /* pointer or stride not 16-byte aligned */
+  ENTMAX_ATTN_WORKSPACE_TOO_SMALL = -4,
+  ENTMAX_ATTN_LAUNCH_FAILED = -5      /* the HIP runtime refused a launch */
+} entmax_attn_status;
+
+enum { ENTMAX_ATTN_BF16 = 0, ENTMAX_ATTN_FP32 = 1 };
+
+typedef struct {
+  int32_t B, H, Nq, Nk, D; /* D in {64, 128} */
+  int32_t dtype;           /* ENTMAX_ATTN_BF16 or ENTMAX_ATTN_FP32: type of Q,K,V,O,dO,dQ,dK,dV */
+  int32_t causal;          /* 1: key j visible to query i iff j <= i + (Nk - Nq); 0: all keys visible */
+  int32_t scale_layout;    /* 0: scale = delta; 1: beta,gamma per head [H]; 2: per query [B,H,Nq] */
+  int32_t logn_mode;       /* n in (ln n)^gamma: 0 = Nk for every row, 1 = number of keys visible to the row.
+                              A row with n <= 1 uses scale = delta and contributes no beta/gamma gradient. */
+  float alpha;             /* 1 < alpha <= 2; 1.5, 2.0 and 1.25 run on integer-power fast paths */
+  float delta;             /* ASEntmax delta (1.0 in the paper's experiments) */
+  int64_t q_stride_b, q_stride_h, q_stride_n;    /* strides of Q,O,dO,dQ in elements; all 0 = contiguous */
+  int64_t kv_stride_b, kv_stride_h, kv_stride_n; /* strides of K,V,dK,dV in elements; all 0 = contiguous */
+} entmax_attn_params;
+
+/* Indices into the optional device counter array `stats` (uint64, at least
+ * ENTMAX_ATTN_NUM_STATS entries, zeroed by the caller; the kernels add to it).
+ * A "tile" is one 32-query x 32-key block, the unit of one MFMA output block
+ * and of the zero-tile test. */
+enum {
+  ENTMAX_STAT_FWD_TILES_VISIBLE = 0, /* tiles holding at least one unmasked (i,j) pair */
+  ENTMAX_STAT_FWD_QK_MAX = 1,        /* score tiles computed by the row-max sweep */
+  ENTMAX_STAT_FWD_QK_SOLVE = 2,      /* score tiles computed by all threshold sweeps together */
+  ENTMAX_STAT_FWD_QK_PV = 3,         /* score tiles recomputed by the P.V sweep */
+  ENTMAX_STAT_FWD_PV_TILES = 4,      /* tiles whose P.V product ran (the others were all zero: skipped) */
+  ENTMAX_STAT_FWD_SOLVE_SWEEPS = 5,  /* threshold sweeps, summed over workgroups */
+  ENTMAX_STAT_FWD_BLOCKS = 6,        /* workgroups */
+  ENTMAX_STAT_FWD_EVAL_TILES = 7,    /* tiles on which the threshold function was evaluated element by element */
+  ENTMAX_STAT_BWD_TILES_VISIBLE = 8,
+  ENTMAX_STAT_BWD_QK_MASK = 9,       /* score tiles computed to find the non-zero tiles */
+  ENTMAX_STAT_BWD_ACTIVE_TILES = 10, /* tiles with some p_ij > 0 */
+  ENTMAX_STAT_BWD_DQ_TILES = 11,     /* tiles processed by the dQ / row-scalar kernel */
+  ENTMAX_STAT_BWD_DKV_TILES = 12,    /* tiles processed by the dK / dV kernel */
+  ENTMAX_ATTN_NUM_STATS = 16
+};
+
+/* Phases of one call, for the optional profiling hook `phase_events`: when not
+ * NULL it is a HOST array of hipEvent_t handles (created by the caller) with
+ * one more entry than the call has phases; entry 0 is recorded on the stream
+ * before the first kernel and entry k after the last kernel of phase k-1. */
+enum { ENTMAX_FWD_PHASE_TRANSPOSE = 0, ENTMAX_FWD_PHASE_MAIN = 1, ENTMAX_FWD_NUM_PHASES = 2 };
+enum {
+  ENTMAX_BWD_PHASE_TRANSPOSE = 0,
+  ENTMAX_BWD_PHASE_MASK = 1,
+  ENTMAX_BWD_PHASE_DQ = 2,
+  ENTMAX_BWD_PHASE_DKV = 3,
+  ENTMAX_BWD_PHASE_SCALE_GRAD = 4,
+  ENTMAX_BWD_NUM_PHASES = 5
+};
+
+/*
+ * Forward (Sec. 2.1 with pi = alpha-entmax on ASEntmax-scaled logits).
+ *   in : Q, K, V, beta, gamma
+ *   out: O (dtype, written for every row), tau [B,H,Nq] fp32 (saved for the backward).
+ *        A row with no visible key gets O = 0, tau = 0.
+ *   stats: NULL or device uint64[ENTMAX_ATTN_NUM_STATS], added to.
+ *   workspace: device scratch of at least entmax_attn_workspace_bytes(p, 0)
+ *        bytes, 256-byte aligned; contents are undefined afterwards.
+ * The row threshold is found by sweeps over the key tiles that recompute
+ * Q K^T each time (row max, then safeguarded Newton/Halley steps on
+ * f(tau) = sum_j [(alpha-1) s_ij - tau]_+^(1/(alpha-1)) - 1 inside the bracket of
+ * App. A eq. (bounds)); the n x n score matrix is never stored.
+ */
+int entmax_attn_fwd(const entmax_attn_params* p, const void* Q, const void* K, const void* V, const float* beta,
+                    const float* gamma, void* O, float* tau, uint64_t* stats, void* workspace,
+                    size_t workspace_bytes, void* hip_stream, void* const* phase_events);
+
+/*
+ * Backward (exact derivative of the forward; Jacobian of eq. (entmax)).
+ *   in : Q, K, V, dO, tau (as written by the forward), beta, gamma
+ *   out: dQ, dK, dV (dtype; every element written);
+ *        dbeta, dgamma fp32 in beta/gamma's layout, OVERWRITTEN (not
+ *        accumulated); ignored (may be NULL) for scale_layout 0.
+ *   O is accepted for symmetry with the usual attention backward and may be NULL
+ *   (the row term is rebuilt from tau, not from O).
+ *   workspace: at least entmax_attn_workspace_bytes(p, 1) bytes, 256-byte aligned.
+ * No atomics are used on the outputs: results are bitwise reproducible.
+ */
+int entmax_attn_bwd(const entmax_attn_params* p, const void* Q, const void* K, const void* V, const void* O,
+                    const void* dO, const float* tau, const float* beta, const float* gamma, void* dQ, void* dK,
+                    void* dV, float* dbeta, float* dgamma, uint64_t* stats, void* workspace, size_t workspace_bytes,
+                    void* hip_stream, void* const* phase_events);
+
+/* Scratch bytes the forward (is_bwd = 0) or backward (is_bwd != 0) needs for
+ * these parameters; 0 if the parameters are invalid. Host-only, no GPU call. */
+size_t entmax_attn_workspace_bytes(const entmax_attn_params* p, int is_bwd);
+
+/* Validates parameters without touching the GPU: returns the status the
+ * entry points would return for them (pointer checks excluded). */
+int entmax_attn_check_params(const entmax_attn_params* p);
+
+/* Static, NUL-terminated description of a status code. */
+const char* entmax_attn_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ENTMAX_ATTN_H */

@@ -1,0 +1,166 @@
+"""Thin ctypes binding of the C ABI in include/entmax_attn.h.
+
+Argument marshalling only: torch supplies device memory and the stream, every
+step of the computation runs in the HIP kernels of lib/libentmax_attn.so.
+There is no fallback: if the library is missing, importing this module fails.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "lib", "libentmax_attn.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        "libentmax_attn.so is not built: run `python -m paper_2506_16640_amd.build` "
+        "(or __graft_entry__.build()) first; there is no CPU fallback")
+
+_lib = ctypes.CDLL(LIB_PATH)
+
+NUM_STATS = 16
+STAT_NAMES = {
+    "fwd_tiles_visible": 0, "fwd_qk_max": 1, "fwd_qk_solve": 2, "fwd_qk_pv": 3, "fwd_pv_tiles": 4,
+    "fwd_solve_sweeps": 5, "fwd_blocks": 6, "fwd_eval_tiles": 7,
+    "bwd_tiles_visible": 8, "bwd_qk_mask": 9, "bwd_active_tiles": 10, "bwd_dq_tiles": 11, "bwd_dkv_tiles": 12,
+}
+FWD_NUM_PHASES = 2
+BWD_NUM_PHASES = 5
+FWD_PHASES = ("transpose", "main")
+BWD_PHASES = ("transpose", "mask", "dq", "dkv", "scale_grad")
+
+
+class Params(ctypes.Structure):
+    _fields_ = [
+        ("B", ctypes.c_int32), ("H", ctypes.c_int32), ("Nq", ctypes.c_int32), ("Nk", ctypes.c_int32),
+        ("D", ctypes.c_int32), ("dtype", ctypes.c_int32), ("causal", ctypes.c_int32),
+        ("scale_layout", ctypes.c_int32), ("logn_mode", ctypes.c_int32),
+        ("alpha", ctypes.c_float), ("delta", ctypes.c_float),
+        ("q_stride_b", ctypes.c_int64), ("q_stride_h", ctypes.c_int64), ("q_stride_n", ctypes.c_int64),
+        ("kv_stride_b", ctypes.c_int64), ("kv_stride_h", ctypes.c_int64), ("kv_stride_n", ctypes.c_int64),
+    ]
+
+
+_vp = ctypes.c_void_p
+_lib.entmax_attn_fwd.restype = ctypes.c_int
+_lib.entmax_attn_fwd.argtypes = [ctypes.POINTER(Params), _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp,
+                                 ctypes.c_size_t, _vp, _vp]
+_lib.entmax_attn_bwd.restype = ctypes.c_int
+_lib.entmax_attn_bwd.argtypes = [ctypes.POINTER(Params)] + [_vp] * 15 + [ctypes.c_size_t, _vp, _vp]
+_lib.entmax_attn_workspace_bytes.restype = ctypes.c_size_t
+_lib.entmax_attn_workspace_bytes.argtypes = [ctypes.POINTER(Params), ctypes.c_int]
+_lib.entmax_attn_check_params.restype = ctypes.c_int
+_lib.entmax_attn_check_params.argtypes = [ctypes.POINTER(Params)]
+_lib.entmax_attn_strerror.restype = ctypes.c_char_p
+_lib.entmax_attn_strerror.argtypes = [ctypes.c_int]
+
+
+class EntmaxAttnError(RuntimeError):
+    def __init__(self, code):
+        self.code = code
+        super().__init__("entmax_attn: %s (%d)" % (_lib.entmax_attn_strerror(code).decode(), code))
+
+
+def strerror(code):
+    return _lib.entmax_attn_strerror(int(code)).decode()
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def make_params(q, k, alpha, delta, causal, beta, logn_mode):
+    B, H, Nq, D = q.shape
+    Nk = k.shape[2]
+    if q.dtype == torch.bfloat16:
+        dt = 0
+    elif q.dtype == torch.float32:
+        dt = 1
+    else:
+        raise TypeError("Q must be bfloat16 or float32")
+    layout = 0 if beta is None else (1 if beta.dim() == 1 else 2)
+    p = Params(B, H, Nq, Nk, D, dt, int(bool(causal)), layout, int(logn_mode), float(alpha), float(delta),
+               0, 0, 0, 0, 0, 0)
+    if not q.is_contiguous():
+        assert q.stride(3) == 1
+        p.q_stride_b, p.q_stride_h, p.q_stride_n = q.stride(0), q.stride(1), q.stride(2)
+    if not k.is_contiguous():
+        assert k.stride(3) == 1
+        p.kv_stride_b, p.kv_stride_h, p.kv_stride_n = k.stride(0), k.stride(1), k.stride(2)
+    return p
+
+
+def workspace_bytes(params, is_bwd):
+    return int(_lib.entmax_attn_workspace_bytes(ctypes.byref(params), int(is_bwd)))
+
+
+def check_params(params):
+    return int(_lib.entmax_attn_check_params(ctypes.byref(params)))
+
+
+def _events_arg(events, n):
+    if events is None:
+        return None
+    assert len(events) == n + 1
+    arr = (ctypes.c_void_p * (n + 1))(*[ctypes.c_void_p(e) for e in events])
+    return arr
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def entmax_attn_fwd(q, k, v, alpha=1.5, beta=None, gamma=None, delta=1.0, causal=True, logn_mode=0,
+                    out=None, tau=None, stats=None, workspace=None, phase_events=None):
+    """O, tau = entmax attention forward.  q [B,H,Nq,D], k,v [B,H,Nk,D] on the GPU, bf16 or fp32;
+    beta,gamma fp32 [H] or [B,H,Nq] or None.  stats: optional uint64/int64 device tensor [16] (added to).
+    phase_events: optional list of 3 hipEvent_t handles (ints)."""
+    p = make_params(q, k, alpha, delta, causal, beta, logn_mode)
+    assert v.shape == k.shape and v.stride() == k.stride()
+    if out is None:
+        out = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device)
+    else:
+        assert out.stride() == q.stride()
+    if tau is None:
+        tau = torch.empty(q.shape[:3], dtype=torch.float32, device=q.device)
+    need = workspace_bytes(p, 0)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
+    ev = _events_arg(phase_events, FWD_NUM_PHASES)
+    rc = _lib.entmax_attn_fwd(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(beta), _ptr(gamma), _ptr(out),
+                              _ptr(tau), _ptr(stats), _ptr(workspace), workspace.numel(), _stream(), ev)
+    if rc != 0:
+        raise EntmaxAttnError(rc)
+    return out, tau
+
+
+def entmax_attn_bwd(q, k, v, o, do, tau, alpha=1.5, beta=None, gamma=None, delta=1.0, causal=True, logn_mode=0,
+                    stats=None, workspace=None, phase_events=None):
+    """dQ, dK, dV, dbeta, dgamma = entmax attention backward (dbeta/dgamma None without scale parameters)."""
+    p = make_params(q, k, alpha, delta, causal, beta, logn_mode)
+    assert v.stride() == k.stride() and do.stride() == q.stride()
+    dq = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device)
+    dk = torch.empty_strided(k.shape, k.stride(), dtype=k.dtype, device=k.device)
+    dv = torch.empty_strided(v.shape, v.stride(), dtype=v.dtype, device=v.device)
+    dbeta = torch.empty_like(beta) if beta is not None else None
+    dgamma = torch.empty_like(gamma) if gamma is not None else None
+    need = workspace_bytes(p, 1)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
+    ev = _events_arg(phase_events, BWD_NUM_PHASES)
+    rc = _lib.entmax_attn_bwd(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(do), _ptr(tau), _ptr(beta),
+                              _ptr(gamma), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(dbeta), _ptr(dgamma), _ptr(stats),
+                              _ptr(workspace), workspace.numel(), _stream(), ev)
+    if rc != 0:
+        raise EntmaxAttnError(rc)
+    return dq, dk, dv, dbeta, dgamma
+
+
+def new_stats(device="cuda"):
+    return torch.zeros(NUM_STATS, dtype=torch.int64, device=device)
+
+
+def stats_dict(stats):
+    vals = stats.cpu().tolist()
+    return {name: int(vals[i]) for name, i in STAT_NAMES.items()}

@@ -1,0 +1,500 @@
+// Backward kernels.  With x_ij = [(alpha-1) s_ij - tau_i]_+, r = 1/(alpha-1):
+//   p = x^r,  g = p^(2-alpha) = x^(r-1)            (derivative of eq. (entmax) on the support)
+//   dP_ij = <dO_i, v_j>,  mu_i = sum_j g dP / sum_j g,  dS_ij = g_ij (dP_ij - mu_i)
+//   dV_j = sum_i p_ij dO_i,   dQ_i = c_i sum_j dS_ij k_j,   dK_j = sum_i c_i dS_ij q_i,
+//   dscale_i = sum_j dS_ij z_ij,   c_i = scale_i / sqrt(D),  z_ij = <q_i,k_j>/sqrt(D)
+// and d beta, d gamma by the chain rule through eq. (asentmax).
+// Everything is multiplied by p or g, which vanish off the support, so only the
+// 32x32 tiles that hold some positive x are visited:
+//   bwd_mask_kernel  one Q K^T sweep that records those tiles (bit per tile);
+//   bwd_dq_kernel    query-block outer loop: row scalars mu_i, dscale_i and dQ.
+//                    dQ is linear in mu:  dQ_i = c_i (sum_j g dP k_j - mu_i sum_j g k_j),
+//                    so both sums are accumulated in the same pass and combined
+//                    once mu is known -- no second pass and no atomics;
+//   bwd_dkv_kernel   key-block outer loop: dK and dV (needs mu from the above);
+//   scale_grad_*     reduction of dscale into d beta, d gamma.
+#pragma once
+#include "qside.hip.h"
+
+namespace entmax {
+
+struct BwdArgs {
+  Geom g;
+  const void* Q;
+  const void* K;
+  const void* V;
+  const void* dO;
+  const void* Kt;   // transposed, row-permuted copies (see transpose.hip.h)
+  const void* Qt;
+  const void* dOt;
+  const float* tau;
+  void* dQ;
+  void* dK;
+  void* dV;
+  float* mu;        // [B*H*Nq] row term, written by bwd_dq_kernel
+  float* crow;      // [B*H*Nq] scale_i / sqrt(D)
+  float* dscale;    // [B*H*Nq] gradient with respect to scale_i
+  uint32_t* mask;   // [B*H][nqg][mask_words] bit jb of row ig: tile (ig, jb) holds some p > 0
+  unsigned long long* stats;
+  int nqb, nkb, nqg, mask_words;
+};
+
+// --------------------------------------------------------------- tile mask
+
+template <typename T, int D, int AM>
+__global__ __launch_bounds__(kThreads) void bwd_mask_kernel(BwdArgs A) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  using C = QCtx<T, D>;
+  constexpr int KT = C::KT, NSB = C::NSB, TB = C::kTileBytes;
+  const Geom& g = A.g;
+  WaveMask wm;
+  wm.words = reinterpret_cast<uint32_t*>(smem + 2 * TB);
+  wm.nwords = A.mask_words;
+  C q;
+  q.init(g, A.Q, xcd_remap(blockIdx.x, gridDim.x), A.nqb);
+  for (int w = q.tid; w < kWaves * A.mask_words; w += kThreads) wm.words[w] = 0u;
+  const float tau = q.valid ? A.tau[(long long)q.bh * g.Nq + q.i] : 0.f;
+  const bool live = q.valid && q.lim > 0;
+  Slot slots[1];
+  slots[0].base = reinterpret_cast<const char*>(reinterpret_cast<const T*>(A.K) + (long long)q.b * g.kv_sb +
+                                                (long long)q.h * g.kv_sh);
+  slots[0].row_bytes = g.kv_sn * (long long)sizeof(T);
+  unsigned n_vis = 0, n_act = 0;
+  sweep_tiles<T, D, 1, 0>(
+      smem, slots, q.ntiles, g.Nk, q.tid, [](int) { return true; },
+      [&](int kt, const char* tl) {
+#pragma unroll
+        for (int sb = 0; sb < NSB; ++sb) {
+          int j0 = kt * KT + sb * 32;
+          if (j0 >= q.wave_lim_max) continue;
+          f32x16_t acc = q.scores(tl, sb);
+          ++n_vis;
+          if (j0 + 32 > q.wave_lim_min) {
+            int rel = q.lim - j0;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[e] = (q.key_of(e) < rel) ? acc[e] : -kInf;
+          }
+          float lm = max16(acc);
+          bool cand = live && (lm > -kInf) && (fmaf(lm, q.a, -tau) > 0.f);
+          if (__ballot(cand) != 0ull) {
+            ++n_act;
+            if (q.lane == 0) wm.set(q.wave, kt * NSB + sb);
+          }
+        }
+      });
+  // sweep_tiles ends on a barrier: all bits are in LDS
+  int ig = q.q0 >> 5;
+  if (ig < A.nqg) {
+    uint32_t* dst = A.mask + ((long long)q.bh * A.nqg + ig) * A.mask_words;
+    for (int w = q.lane; w < A.mask_words; w += 64) dst[w] = wm.words[q.wave * A.mask_words + w];
+  }
+  if (A.stats && q.lane == 0) {
+    atomicAdd(&A.stats[ENTMAX_STAT_BWD_TILES_VISIBLE], (unsigned long long)n_vis);
+    atomicAdd(&A.stats[ENTMAX_STAT_BWD_QK_MASK], (unsigned long long)n_vis);
+    atomicAdd(&A.stats[ENTMAX_STAT_BWD_ACTIVE_TILES], (unsigned long long)n_act);
+  }
+}
+
+// ------------------------------------------------- row scalars, dscale and dQ
+
+template <typename T, int D, int AM>
+__global__ __launch_bounds__(kThreads) void bwd_dq_kernel(BwdArgs A) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  using C = QCtx<T, D>;
+  constexpr int KT = C::KT, NSB = C::NSB, NC = C::NC, NM = C::NM, TB = C::kTileBytes;
+  const Geom& g = A.g;
+  char* tiles = smem;  // 2 buffers x 3 slots: K, V, Kt
+  WaveMask wm;
+  wm.words = reinterpret_cast<uint32_t*>(smem + 6 * TB);
+  wm.nwords = A.mask_words;
+  float* xch = reinterpret_cast<float*>(wm.words + kWaves * A.mask_words);  // [kWaves][64]
+
+  C q;
+  q.init(g, A.Q, xcd_remap(blockIdx.x, gridDim.x), A.nqb);
+  const float r = 1.0f / (g.alpha - 1.0f);
+  const long long row_idx = (long long)q.bh * g.Nq + q.i;
+  const float tau = q.valid ? A.tau[row_idx] : 0.f;
+  const bool live = q.valid && q.lim > 0;
+  const long long q_base = (long long)q.b * g.q_sb + (long long)q.h * g.q_sh;
+
+  Frag<T> dof[NC];
+  {
+    const T* drow = reinterpret_cast<const T*>(A.dO) + q_base + (long long)q.i * g.q_sn;
+#pragma unroll
+    for (int cc = 0; cc < NC; ++cc) dof[cc] = q.valid ? Elem<T>::load(drow + 16 * cc + 8 * q.hh) : Elem<T>::zero();
+  }
+  {
+    int ig = q.q0 >> 5;
+    for (int w = q.lane; w < A.mask_words; w += 64)
+      wm.words[q.wave * A.mask_words + w] =
+          (ig < A.nqg) ? A.mask[((long long)q.bh * A.nqg + ig) * A.mask_words + w] : 0u;
+  }
+  __syncthreads();
+
+  const long long kv_base = (long long)q.b * g.kv_sb + (long long)q.h * g.kv_sh;
+  Slot slots[3];
+  slots[0].base = reinterpret_cast<const char*>(reinterpret_cast<const T*>(A.K) + kv_base);
+  slots[0].row_bytes = g.kv_sn * (long long)sizeof(T);
+  slots[1].base = reinterpret_cast<const char*>(reinterpret_cast<const T*>(A.V) + kv_base);
+  slots[1].row_bytes = g.kv_sn * (long long)sizeof(T);
+  slots[2].base = reinterpret_cast<const char*>(A.Kt) + (long long)q.bh * D * g.npad_k * (long long)sizeof(T);
+  slots[2].row_bytes = (long long)g.npad_k * (long long)sizeof(T);
+
+  f32x16_t acc1[NM], acc2[NM];
+#pragma unroll
+  for (int mm = 0; mm < NM; ++mm) {
+    acc1[mm] = f32x16_t{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    acc2[mm] = acc1[mm];
+  }
+  float Z = 0.f, N = 0.f, Aq = 0.f, Cq = 0.f;
+  unsigned n_tiles = 0;
+
+  auto needed = [&](int kt) {
+    bool n = false;
+    for (int w = 0; w < kWaves; ++w)
+      for (int sb = 0; sb < NSB; ++sb) n = n || wm.test(w, kt * NSB + sb);
+    return n;
+  };
+  sweep_tiles<T, D, 3, 4>(tiles, slots, q.ntiles, g.Nk, q.tid, needed, [&](int kt, const char* tl) {
+#pragma unroll
+    for (int sb = 0; sb < NSB; ++sb) {
+      int j0 = kt * KT + sb * 32;
+      if (j0 >= q.wave_lim_max) continue;
+      if (!wm.test(q.wave, kt * NSB + sb)) continue;
+      f32x16_t acc = q.scores(tl, sb);
+      const bool masked = j0 + 32 > q.wave_lim_min;
+      const int rel = q.lim - j0;
+      float x[16];
+      bool any = false;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        bool vis = live && (!masked || q.key_of(e) < rel);
+        float xp = fmaf(acc[e], q.a, -tau);
+        x[e] = vis ? fmaxf(xp, 0.f) : 0.f;
+        acc[e] = vis ? acc[e] : 0.f;
+        any = any || (x[e] > 0.f);
+      }
+      if (__ballot(any) == 0ull) continue;
+      ++n_tiles;
+      // dP^T = V_tile dO^T, same lane layout as the scores
+      f32x16_t dp = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int cc = 0; cc < NC; ++cc)
+        dp = Elem<T>::mma(C::KTile::frag(tl + TB, sb * 32 + q.li, 2 * cc + q.hh), dof[cc], dp);
+      float w1[16], w2[16];
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        float gg = pow_rm1<AM>(x[e], r);
+        float gd = (x[e] > 0.f) ? gg * dp[e] : 0.f;
+        Z += gg;
+        N += gd;
+        Aq = fmaf(gd, acc[e], Aq);
+        Cq = fmaf(gg, acc[e], Cq);
+        w1[e] = gd;
+        w2[e] = gg;
+      }
+      const char* ktt = tl + 2 * TB;
+#pragma unroll
+      for (int cc = 0; cc < 2; ++cc) {
+        Frag<T> f1 = Elem<T>::pack(w1 + 8 * cc);
+        Frag<T> f2 = Elem<T>::pack(w2 + 8 * cc);
+#pragma unroll
+        for (int mm = 0; mm < NM; ++mm) {
+          Frag<T> kf = C::XtTile::frag(ktt, mm * 32 + q.li, 2 * (2 * sb + cc) + q.hh);
+          acc1[mm] = Elem<T>::mma(f1, kf, acc1[mm]);
+          acc2[mm] = Elem<T>::mma(f2, kf, acc2[mm]);
+        }
+      }
+    }
+  });
+
+  Z += __shfl_xor(Z, 32);
+  N += __shfl_xor(N, 32);
+  Aq += __shfl_xor(Aq, 32);
+  Cq += __shfl_xor(Cq, 32);
+  const float mu = (Z > 0.f) ? N / Z : 0.f;
+  if (q.valid && q.hh == 0) {
+    // the scores were formed with q negated when scale_i < 0: undo the sign for z_ij
+    float sgn = (q.c < 0.f) ? -1.f : 1.f;
+    A.mu[row_idx] = mu;
+    A.crow[row_idx] = q.c;
+    A.dscale[row_idx] = sgn * (Aq - mu * Cq) * (1.0f / sqrtf((float)D));
+  }
+  if (q.hh == 0) {
+    xch[q.wave * 64 + q.li] = mu;
+    xch[q.wave * 64 + 32 + q.li] = q.c;
+  }
+  __syncthreads();
+  // acc[mm][4g + r] of lane l belongs to query row q0 + 8g + 4*(l/32) + r, feature 32 mm + l%32
+#pragma unroll
+  for (int mm = 0; mm < NM; ++mm) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      int rl = q.key_of(e);
+      int row = q.q0 + rl;
+      float mur = xch[q.wave * 64 + rl], cr = xch[q.wave * 64 + 32 + rl];
+      if (row < g.Nq)
+        Elem<T>::store(A.dQ, q_base + (long long)row * g.q_sn + mm * 32 + q.li, cr * (acc1[mm][e] - mur * acc2[mm][e]));
+    }
+  }
+  if (A.stats && q.lane == 0) atomicAdd(&A.stats[ENTMAX_STAT_BWD_DQ_TILES], (unsigned long long)n_tiles);
+}
+
+// ------------------------------------------------------------------ dK, dV
+
+template <typename T, int D, int AM>
+__global__ __launch_bounds__(kThreads) void bwd_dkv_kernel(BwdArgs A) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  using C = QCtx<T, D>;
+  constexpr int QT = C::KT, NSG = C::NSB, NC = C::NC, NM = C::NM, TB = C::kTileBytes;
+  const Geom& g = A.g;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 31, hh = lane >> 5;
+  const int item = xcd_remap(blockIdx.x, gridDim.x);
+  const int bh = item / A.nkb, kb = item % A.nkb;
+  const int b = bh / g.H, h = bh % g.H;
+  const float r = 1.0f / (g.alpha - 1.0f);
+  const float am1 = g.alpha - 1.0f;
+  const int off = g.Nk - g.Nq;
+
+  // smem: [2 buffers x 4 tiles: Q, dO, Qt, dOt][2 buffers x 3 row arrays x QT floats][need: nqg bytes]
+  char* tiles = smem;
+  float* rows = reinterpret_cast<float*>(smem + 8 * TB);
+  unsigned char* need = reinterpret_cast<unsigned char*>(rows + 2 * 4 * QT);
+
+  const int jw0 = kb * kBlockRows + wave * 32;  // first key of this wave
+  const int j = jw0 + li;                       // this lane's key (as the B-operand column)
+  const bool jvalid = j < g.Nk;
+  const long long kv_base = (long long)b * g.kv_sb + (long long)h * g.kv_sh;
+  const long long q_base = (long long)b * g.q_sb + (long long)h * g.q_sh;
+  Frag<T> kf[NC], vf[NC];
+  {
+    const T* krow = reinterpret_cast<const T*>(A.K) + kv_base + (long long)j * g.kv_sn;
+    const T* vrow = reinterpret_cast<const T*>(A.V) + kv_base + (long long)j * g.kv_sn;
+#pragma unroll
+    for (int cc = 0; cc < NC; ++cc) {
+      kf[cc] = jvalid ? Elem<T>::load(krow + 16 * cc + 8 * hh) : Elem<T>::zero();
+      vf[cc] = jvalid ? Elem<T>::load(vrow + 16 * cc + 8 * hh) : Elem<T>::zero();
+    }
+  }
+  {
+    int jb0 = kb * 4;  // the four 32-key blocks of this workgroup share one mask word
+    for (int ig = tid; ig < A.nqg; ig += kThreads) {
+      uint32_t w = A.mask[((long long)bh * A.nqg + ig) * A.mask_words + (jb0 >> 5)];
+      need[ig] = (unsigned char)((w >> (jb0 & 31)) & 0xFu);
+    }
+  }
+  __syncthreads();
+
+  // query tiles that can see this key block: row i sees key j iff j <= i + off
+  const int nqt = (g.Nq + QT - 1) / QT;
+  int qt_first = 0;
+  if (g.causal) {
+    int imin = kb * kBlockRows - off;
+    qt_first = imin > 0 ? imin / QT : 0;
+  }
+
+  f32x16_t dk[NM], dv[NM];
+#pragma unroll
+  for (int mm = 0; mm < NM; ++mm) {
+    dk[mm] = f32x16_t{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    dv[mm] = dk[mm];
+  }
+  unsigned n_tiles = 0;
+
+  using NTile = typename C::KTile;   // natural: rows = queries
+  using TTile = typename C::XtTile;  // transposed: rows = features
+  Stage<NTile> sq, sdo;
+  Stage<TTile> sqt, sdot;
+  float rv[3] = {0.f, 0.f, 0.f};  // staged row values (threads < QT): tau, (alpha-1) c, mu
+
+  const char* Qg = reinterpret_cast<const char*>(reinterpret_cast<const T*>(A.Q) + q_base);
+  const char* dOg = reinterpret_cast<const char*>(reinterpret_cast<const T*>(A.dO) + q_base);
+  const char* Qtg = reinterpret_cast<const char*>(A.Qt) + (long long)bh * D * g.npad_q * (long long)sizeof(T);
+  const char* dOtg = reinterpret_cast<const char*>(A.dOt) + (long long)bh * D * g.npad_q * (long long)sizeof(T);
+  const long long qrow_bytes = g.q_sn * (long long)sizeof(T);
+  const long long trow_bytes = (long long)g.npad_q * (long long)sizeof(T);
+
+  auto tile_needed = [&](int qt) {
+    bool n = false;
+    for (int sg = 0; sg < NSG; ++sg) {
+      int ig = qt * NSG + sg;
+      if (ig < A.nqg) n = n || (need[ig] != 0);
+    }
+    return n;
+  };
+  auto next_needed = [&](int qt) {
+    while (qt < nqt && !tile_needed(qt)) ++qt;
+    return qt;
+  };
+  auto fetch = [&](int qt) {
+    int rows_left = g.Nq - qt * QT;
+    sq.fetch(Qg + (long long)qt * QT * qrow_bytes, qrow_bytes, rows_left, tid);
+    sdo.fetch(dOg + (long long)qt * QT * qrow_bytes, qrow_bytes, rows_left, tid);
+    sqt.fetch(Qtg + (long long)qt * QT * (long long)sizeof(T), trow_bytes, D, tid);
+    sdot.fetch(dOtg + (long long)qt * QT * (long long)sizeof(T), trow_bytes, D, tid);
+    if (tid < QT) {
+      int i = qt * QT + tid;
+      if (i < g.Nq) {
+        long long ri = (long long)bh * g.Nq + i;
+        rv[0] = A.tau[ri];
+        rv[1] = am1 * A.crow[ri];
+        rv[2] = A.mu[ri];
+      } else {  // rows beyond Nq: x = -1 everywhere
+        rv[0] = 1.f;
+        rv[1] = 0.f;
+        rv[2] = 0.f;
+      }
+    }
+  };
+  auto commit = [&](int bufi) {
+    char* bf = tiles + bufi * 4 * TB;
+    sq.commit(bf, tid);
+    sdo.commit(bf + TB, tid);
+    sqt.commit(bf + 2 * TB, tid);
+    sdot.commit(bf + 3 * TB, tid);
+    if (tid < QT) {
+      float* rw = rows + bufi * 4 * QT;
+      rw[tid] = rv[0];
+      rw[QT + tid] = rv[1];
+      rw[2 * QT + tid] = rv[2];
+    }
+  };
+
+  int qt = next_needed(qt_first);
+  if (qt < nqt) {
+    fetch(qt);
+    commit(0);
+  }
+  __syncthreads();
+  int cur = 0;
+  while (qt < nqt) {
+    int nxt = next_needed(qt + 1);
+    if (nxt < nqt) fetch(nxt);
+    const char* tl = tiles + cur * 4 * TB;
+    const float* rw = rows + cur * 4 * QT;
+#pragma unroll
+    for (int sg = 0; sg < NSG; ++sg) {
+      int ig = qt * NSG + sg;
+      if (ig >= A.nqg || !((need[ig] >> wave) & 1)) continue;
+      int i0 = ig * 32;
+      // S block: rows = the 32 queries of the group, cols = the wave's 32 keys
+      f32x16_t s = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int cc = 0; cc < NC; ++cc) s = Elem<T>::mma(NTile::frag(tl, sg * 32 + li, 2 * cc + hh), kf[cc], s);
+      float x[16], mur[16], car[16];
+      bool any = false;
+#pragma unroll
+      for (int gq = 0; gq < 4; ++gq) {
+        int rl = sg * 32 + 8 * gq + 4 * hh;
+        f32x4_t t4 = *reinterpret_cast<const f32x4_t*>(rw + rl);
+        f32x4_t a4 = *reinterpret_cast<const f32x4_t*>(rw + QT + rl);
+        f32x4_t m4 = *reinterpret_cast<const f32x4_t*>(rw + 2 * QT + rl);
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) {
+          int e = 4 * gq + rr;
+          int i = i0 + 8 * gq + 4 * hh + rr;
+          bool vis = jvalid && (!g.causal || (j <= i + off));
+          float xp = fmaf(s[e], a4[rr], -t4[rr]);
+          x[e] = vis ? fmaxf(xp, 0.f) : 0.f;
+          mur[e] = m4[rr];
+          car[e] = a4[rr];
+          any = any || (x[e] > 0.f);
+        }
+      }
+      if (__ballot(any) == 0ull) continue;
+      ++n_tiles;
+      f32x16_t dp = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int cc = 0; cc < NC; ++cc) dp = Elem<T>::mma(NTile::frag(tl + TB, sg * 32 + li, 2 * cc + hh), vf[cc], dp);
+      float pp[16], ds[16];
+      const float inv_am1 = 1.0f / am1;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        pp[e] = pow_r<AM>(x[e], r);
+        float gg = pow_rm1<AM>(x[e], r);
+        ds[e] = (x[e] > 0.f) ? gg * (dp[e] - mur[e]) * (car[e] * inv_am1) : 0.f;
+      }
+#pragma unroll
+      for (int cc = 0; cc < 2; ++cc) {
+        Frag<T> pf = Elem<T>::pack(pp + 8 * cc);
+        Frag<T> df = Elem<T>::pack(ds + 8 * cc);
+#pragma unroll
+        for (int mm = 0; mm < NM; ++mm) {
+          int fidx = 2 * (2 * sg + cc) + hh;
+          dv[mm] = Elem<T>::mma(pf, TTile::frag(tl + 3 * TB, mm * 32 + li, fidx), dv[mm]);
+          dk[mm] = Elem<T>::mma(df, TTile::frag(tl + 2 * TB, mm * 32 + li, fidx), dk[mm]);
+        }
+      }
+    }
+    if (nxt < nqt) commit(cur ^ 1);
+    __syncthreads();
+    cur ^= 1;
+    qt = nxt;
+  }
+
+  // dk/dv[mm][4g + r] of lane l belongs to key jw0 + 8g + 4*(l/32) + r, feature 32 mm + l%32
+#pragma unroll
+  for (int mm = 0; mm < NM; ++mm) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      int row = jw0 + 8 * (e >> 2) + 4 * hh + (e & 3);
+      if (row < g.Nk) {
+        long long idx = kv_base + (long long)row * g.kv_sn + mm * 32 + li;
+        Elem<T>::store(A.dK, idx, dk[mm][e]);
+        Elem<T>::store(A.dV, idx, dv[mm][e]);
+      }
+    }
+  }
+  if (A.stats && lane == 0) atomicAdd(&A.stats[ENTMAX_STAT_BWD_DKV_TILES], (unsigned long long)n_tiles);
+}
+
+// ------------------------------------------------------- d beta, d gamma
+
+// Per-head parameters: dbeta_h = sum_{b,i} dscale L^gamma, dgamma_h = sum dscale beta L^gamma ln L,
+// L = ln n (eq. (asentmax)); one workgroup per head, fixed summation order.
+__global__ __launch_bounds__(kThreads) void scale_grad_head_kernel(Geom g, const float* dscale, float* dbeta,
+                                                                   float* dgamma) {
+  __shared__ float sb_[kThreads], sg_[kThreads];
+  const int h = blockIdx.x, tid = threadIdx.x;
+  float ab = 0.f, ag = 0.f;
+  for (int b = 0; b < g.B; ++b) {
+    for (int i = tid; i < g.Nq; i += kThreads) {
+      float Lg, lnL, bt;
+      row_scale(g, b, h, i, row_limit(g, i), &Lg, &lnL, &bt);
+      float ds = dscale[((long long)b * g.H + h) * g.Nq + i];
+      ab += ds * Lg;
+      ag += ds * bt * Lg * lnL;
+    }
+  }
+  sb_[tid] = ab;
+  sg_[tid] = ag;
+  __syncthreads();
+  for (int s = kThreads / 2; s > 0; s >>= 1) {
+    if (tid < s) {
+      sb_[tid] += sb_[tid + s];
+      sg_[tid] += sg_[tid + s];
+    }
+    __syncthreads();
+  }
+  if (tid == 0) {
+    dbeta[h] = sb_[0];
+    dgamma[h] = sg_[0];
+  }
+}
+
+// Per-query parameters: one value per row.
+__global__ void scale_grad_query_kernel(Geom g, const float* dscale, float* dbeta, float* dgamma) {
+  long long row = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  long long rows = (long long)g.B * g.H * g.Nq;
+  if (row >= rows) return;
+  int i = (int)(row % g.Nq);
+  int h = (int)((row / g.Nq) % g.H);
+  int b = (int)(row / ((long long)g.Nq * g.H));
+  float Lg, lnL, bt;
+  row_scale(g, b, h, i, row_limit(g, i), &Lg, &lnL, &bt);
+  float ds = dscale[row];
+  dbeta[row] = ds * Lg;
+  dgamma[row] = ds * bt * Lg * lnL;
+}
+
+}  // namespace entmax

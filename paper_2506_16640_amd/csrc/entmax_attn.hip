@@ -1,0 +1,415 @@
+// Host side of the C ABI declared in include/entmax_attn.h: argument
+// validation, workspace carving and kernel launches.  Nothing here allocates
+// device memory or synchronises.
+#include "entmax_attn.h"
+
+#include <hip/hip_runtime.h>
+#include <math.h>
+
+#include "bwd.hip.h"
+#include "fwd.hip.h"
+#include "transpose.hip.h"
+
+using namespace entmax;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+struct Layout {
+  size_t esize;
+  int npad_q, npad_k;
+  int nqb, nkb;       // 128-row query / key blocks per head
+  int nqg;            // 32-row query groups per head
+  int mask_words;     // uint32 words covering the 32-key blocks of a head
+  long long q_sb, q_sh, q_sn, kv_sb, kv_sh, kv_sn;
+  // workspace offsets
+  size_t off_vt, off_kt, off_qt, off_dot, off_mu, off_crow, off_dscale, off_mask, total_fwd, total_bwd;
+};
+
+int check(const entmax_attn_params* p) {
+  if (!p) return ENTMAX_ATTN_INVALID_ARG;
+  if (p->B < 0 || p->H < 0 || p->Nq < 0 || p->Nk < 0) return ENTMAX_ATTN_INVALID_ARG;
+  if (p->dtype != ENTMAX_ATTN_BF16 && p->dtype != ENTMAX_ATTN_FP32) return ENTMAX_ATTN_INVALID_ARG;
+  if (p->causal != 0 && p->causal != 1) return ENTMAX_ATTN_INVALID_ARG;
+  if (p->scale_layout < 0 || p->scale_layout > 2) return ENTMAX_ATTN_INVALID_ARG;
+  if (p->logn_mode != 0 && p->logn_mode != 1) return ENTMAX_ATTN_INVALID_ARG;
+  if (!(p->alpha > 1.0f) || !(p->alpha <= 2.0f)) return ENTMAX_ATTN_INVALID_ARG;
+  if (!isfinite(p->delta)) return ENTMAX_ATTN_INVALID_ARG;
+  if (p->D != 64 && p->D != 128) return ENTMAX_ATTN_UNSUPPORTED_SHAPE;
+  if (p->Nq > (1 << 24) || p->Nk > (1 << 24)) return ENTMAX_ATTN_UNSUPPORTED_SHAPE;
+  long long bh = (long long)p->B * p->H;
+  if (bh * (long long)ceil_div(p->Nq > p->Nk ? p->Nq : p->Nk, 32) > 0x7fffffffLL) return ENTMAX_ATTN_UNSUPPORTED_SHAPE;
+  if (bh > 65535) return ENTMAX_ATTN_UNSUPPORTED_SHAPE;
+  const int64_t s[6] = {p->q_stride_b, p->q_stride_h, p->q_stride_n, p->kv_stride_b, p->kv_stride_h, p->kv_stride_n};
+  bool q_zero = s[0] == 0 && s[1] == 0 && s[2] == 0, kv_zero = s[3] == 0 && s[4] == 0 && s[5] == 0;
+  size_t es = p->dtype == ENTMAX_ATTN_BF16 ? 2 : 4;
+  for (int k = 0; k < 6; ++k) {
+    if (s[k] < 0) return ENTMAX_ATTN_INVALID_ARG;
+    if ((s[k] * (int64_t)es) % 16 != 0) return ENTMAX_ATTN_MISALIGNED;
+  }
+  if (!q_zero && s[2] < p->D) return ENTMAX_ATTN_INVALID_ARG;
+  if (!kv_zero && s[5] < p->D) return ENTMAX_ATTN_INVALID_ARG;
+  return ENTMAX_ATTN_OK;
+}
+
+Layout make_layout(const entmax_attn_params* p) {
+  Layout L;
+  L.esize = p->dtype == ENTMAX_ATTN_BF16 ? 2 : 4;
+  L.npad_q = ceil_div(p->Nq, 64) * 64;
+  L.npad_k = ceil_div(p->Nk, 64) * 64;
+  L.nqb = ceil_div(p->Nq, kBlockRows);
+  L.nkb = ceil_div(p->Nk, kBlockRows);
+  L.nqg = ceil_div(p->Nq, 32);
+  L.mask_words = ceil_div(ceil_div(p->Nk, 32), 32);
+  if (L.mask_words < 1) L.mask_words = 1;
+  bool q_zero = p->q_stride_b == 0 && p->q_stride_h == 0 && p->q_stride_n == 0;
+  bool kv_zero = p->kv_stride_b == 0 && p->kv_stride_h == 0 && p->kv_stride_n == 0;
+  L.q_sn = q_zero ? p->D : p->q_stride_n;
+  L.q_sh = q_zero ? (long long)p->Nq * p->D : p->q_stride_h;
+  L.q_sb = q_zero ? (long long)p->H * p->Nq * p->D : p->q_stride_b;
+  L.kv_sn = kv_zero ? p->D : p->kv_stride_n;
+  L.kv_sh = kv_zero ? (long long)p->Nk * p->D : p->kv_stride_h;
+  L.kv_sb = kv_zero ? (long long)p->H * p->Nk * p->D : p->kv_stride_b;
+  size_t bh = (size_t)p->B * p->H;
+  size_t kt_bytes = align_up(bh * p->D * (size_t)L.npad_k * L.esize);
+  size_t qt_bytes = align_up(bh * p->D * (size_t)L.npad_q * L.esize);
+  size_t row_bytes = align_up(bh * (size_t)p->Nq * sizeof(float));
+  size_t mask_bytes = align_up(bh * (size_t)L.nqg * L.mask_words * sizeof(uint32_t));
+  L.off_vt = 0;
+  L.total_fwd = kt_bytes;
+  size_t o = 0;
+  L.off_kt = o;
+  o += kt_bytes;
+  L.off_qt = o;
+  o += qt_bytes;
+  L.off_dot = o;
+  o += qt_bytes;
+  L.off_mu = o;
+  o += row_bytes;
+  L.off_crow = o;
+  o += row_bytes;
+  L.off_dscale = o;
+  o += row_bytes;
+  L.off_mask = o;
+  o += mask_bytes;
+  L.total_bwd = o;
+  return L;
+}
+
+Geom make_geom(const entmax_attn_params* p, const Layout& L, const float* beta, const float* gamma) {
+  Geom g;
+  g.B = p->B;
+  g.H = p->H;
+  g.Nq = p->Nq;
+  g.Nk = p->Nk;
+  g.causal = p->causal;
+  g.scale_layout = p->scale_layout;
+  g.logn_mode = p->logn_mode;
+  g.alpha = p->alpha;
+  g.delta = p->delta;
+  g.q_sb = L.q_sb;
+  g.q_sh = L.q_sh;
+  g.q_sn = L.q_sn;
+  g.kv_sb = L.kv_sb;
+  g.kv_sh = L.kv_sh;
+  g.kv_sn = L.kv_sn;
+  g.npad_k = L.npad_k;
+  g.npad_q = L.npad_q;
+  g.beta = beta;
+  g.gamma = gamma;
+  return g;
+}
+
+inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+int alpha_mode(float alpha) {
+  if (alpha == 1.5f) return 1;
+  if (alpha == 2.0f) return 2;
+  if (alpha == 1.25f) return 3;
+  return 0;
+}
+
+inline bool launch_ok() { return hipGetLastError() == hipSuccess; }
+
+inline void record(void* const* ev, int k, hipStream_t st) {
+  if (ev) (void)hipEventRecord(reinterpret_cast<hipEvent_t>(ev[k]), st);
+}
+
+// writes zeros into every row of a [B,H,N,D] tensor given by strides
+template <typename T>
+__global__ void zero_rows_kernel(T* X, long long sb, long long sh, long long sn, int H, int N, int D) {
+  long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  long long per = (long long)N * D;
+  if (e >= per) return;
+  int bh = blockIdx.y;
+  T z{};
+  X[(long long)(bh / H) * sb + (long long)(bh % H) * sh + (e / D) * sn + e % D] = z;
+}
+
+template <typename T>
+bool zero_rows(void* X, long long sb, long long sh, long long sn, int B, int H, int N, int D, hipStream_t st) {
+  if ((long long)B * H * N == 0) return true;
+  long long per = (long long)N * D;
+  dim3 grid((unsigned)((per + 255) / 256), (unsigned)(B * H));
+  hipLaunchKernelGGL(zero_rows_kernel<T>, grid, dim3(256), 0, st, reinterpret_cast<T*>(X), sb, sh, sn, H, N, D);
+  return launch_ok();
+}
+
+bool zero_words(void* p, size_t bytes, hipStream_t st) {
+  long long n = (long long)(bytes / 4);
+  if (n == 0) return true;
+  hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
+                     reinterpret_cast<uint32_t*>(p), n);
+  return launch_ok();
+}
+
+template <typename T, int D>
+bool launch_transpose(const void* X, long long sb, long long sh, long long sn, int B, int H, int N, int npad, void* Xt,
+                      hipStream_t st) {
+  if (npad == 0) return true;
+  dim3 grid((unsigned)(npad / 64), (unsigned)(B * H));
+  hipLaunchKernelGGL((transpose_perm_kernel<T, D>), grid, dim3(kThreads), 0, st, reinterpret_cast<const T*>(X), sb, sh,
+                     sn, H, N, npad, reinterpret_cast<T*>(Xt));
+  return launch_ok();
+}
+
+template <typename T, int D, int AM>
+bool launch_fwd_main(const FwdArgs& a, int nblocks, hipStream_t st) {
+  size_t smem = 4 * (size_t)QCtx<T, D>::kTileBytes + (size_t)kWaves * a.mask_words * 4 + 64;
+  auto kern = fwd_kernel<T, D, AM>;
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) !=
+      hipSuccess)
+    return false;
+  hipLaunchKernelGGL(kern, dim3((unsigned)nblocks), dim3(kThreads), smem, st, a);
+  return launch_ok();
+}
+
+template <typename T, int D>
+bool launch_fwd_am(const FwdArgs& a, int am, int nblocks, hipStream_t st) {
+  switch (am) {
+    case 1: return launch_fwd_main<T, D, 1>(a, nblocks, st);
+    case 2: return launch_fwd_main<T, D, 2>(a, nblocks, st);
+    case 3: return launch_fwd_main<T, D, 3>(a, nblocks, st);
+    default: return launch_fwd_main<T, D, 0>(a, nblocks, st);
+  }
+}
+
+template <typename T, int D>
+int run_fwd(const entmax_attn_params* p, const Layout& L, const void* Q, const void* K, const void* V,
+            const float* beta, const float* gamma, void* O, float* tau, uint64_t* stats, char* ws, hipStream_t st,
+            void* const* ev) {
+  record(ev, 0, st);
+  if (p->Nk == 0) {
+    bool ok = zero_rows<T>(O, L.q_sb, L.q_sh, L.q_sn, p->B, p->H, p->Nq, p->D, st) &&
+              zero_words(tau, (size_t)p->B * p->H * p->Nq * 4, st);
+    record(ev, 1, st);
+    record(ev, 2, st);
+    return ok ? ENTMAX_ATTN_OK : ENTMAX_ATTN_LAUNCH_FAILED;
+  }
+  void* Vt = ws + L.off_vt;
+  if (!launch_transpose<T, D>(V, L.kv_sb, L.kv_sh, L.kv_sn, p->B, p->H, p->Nk, L.npad_k, Vt, st))
+    return ENTMAX_ATTN_LAUNCH_FAILED;
+  record(ev, 1, st);
+  FwdArgs a;
+  a.g = make_geom(p, L, beta, gamma);
+  a.Q = Q;
+  a.K = K;
+  a.Vt = Vt;
+  a.O = O;
+  a.tau = tau;
+  a.stats = reinterpret_cast<unsigned long long*>(stats);
+  a.nqb = L.nqb;
+  a.mask_words = L.mask_words;
+  if (!launch_fwd_am<T, D>(a, alpha_mode(p->alpha), p->B * p->H * L.nqb, st)) return ENTMAX_ATTN_LAUNCH_FAILED;
+  record(ev, 2, st);
+  return ENTMAX_ATTN_OK;
+}
+
+template <typename T, int D, int AM>
+bool launch_bwd_kernels(const BwdArgs& a, const Layout& L, int B, int H, hipStream_t st, void* const* ev) {
+  size_t smem_mask = 2 * (size_t)QCtx<T, D>::kTileBytes + (size_t)kWaves * a.mask_words * 4 + 64;
+  size_t smem_dq = 6 * (size_t)QCtx<T, D>::kTileBytes + (size_t)kWaves * a.mask_words * 4 + kWaves * 64 * 4 + 64;
+  size_t smem_dkv = 8 * (size_t)QCtx<T, D>::kTileBytes + 2 * 4 * (size_t)QCtx<T, D>::KT * 4 + (size_t)a.nqg + 64;
+  auto k_mask = bwd_mask_kernel<T, D, AM>;
+  auto k_dq = bwd_dq_kernel<T, D, AM>;
+  auto k_dkv = bwd_dkv_kernel<T, D, AM>;
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_dq), hipFuncAttributeMaxDynamicSharedMemorySize,
+                          (int)smem_dq) != hipSuccess)
+    return false;
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_dkv), hipFuncAttributeMaxDynamicSharedMemorySize,
+                          (int)smem_dkv) != hipSuccess)
+    return false;
+  hipLaunchKernelGGL(k_mask, dim3((unsigned)(B * H * L.nqb)), dim3(kThreads), smem_mask, st, a);
+  if (!launch_ok()) return false;
+  record(ev, 2, st);
+  hipLaunchKernelGGL(k_dq, dim3((unsigned)(B * H * L.nqb)), dim3(kThreads), smem_dq, st, a);
+  if (!launch_ok()) return false;
+  record(ev, 3, st);
+  hipLaunchKernelGGL(k_dkv, dim3((unsigned)(B * H * L.nkb)), dim3(kThreads), smem_dkv, st, a);
+  if (!launch_ok()) return false;
+  record(ev, 4, st);
+  return true;
+}
+
+template <typename T, int D>
+int run_bwd(const entmax_attn_params* p, const Layout& L, const void* Q, const void* K, const void* V, const void* dO,
+            const float* tau, const float* beta, const float* gamma, void* dQ, void* dK, void* dV, float* dbeta,
+            float* dgamma, uint64_t* stats, char* ws, hipStream_t st, void* const* ev) {
+  record(ev, 0, st);
+  const int B = p->B, H = p->H;
+  Geom g = make_geom(p, L, beta, gamma);
+  float* dscale = reinterpret_cast<float*>(ws + L.off_dscale);
+  bool ok = true;
+  if (p->Nk == 0 || p->Nq == 0) {
+    ok = ok && zero_rows<T>(dQ, L.q_sb, L.q_sh, L.q_sn, B, H, p->Nq, p->D, st);
+    ok = ok && zero_rows<T>(dK, L.kv_sb, L.kv_sh, L.kv_sn, B, H, p->Nk, p->D, st);
+    ok = ok && zero_rows<T>(dV, L.kv_sb, L.kv_sh, L.kv_sn, B, H, p->Nk, p->D, st);
+    ok = ok && zero_words(dscale, (size_t)B * H * p->Nq * 4, st);
+    for (int k = 1; k <= 4; ++k) record(ev, k, st);
+  } else {
+    void* Kt = ws + L.off_kt;
+    void* Qt = ws + L.off_qt;
+    void* dOt = ws + L.off_dot;
+    ok = ok && launch_transpose<T, D>(K, L.kv_sb, L.kv_sh, L.kv_sn, B, H, p->Nk, L.npad_k, Kt, st);
+    ok = ok && launch_transpose<T, D>(Q, L.q_sb, L.q_sh, L.q_sn, B, H, p->Nq, L.npad_q, Qt, st);
+    ok = ok && launch_transpose<T, D>(dO, L.q_sb, L.q_sh, L.q_sn, B, H, p->Nq, L.npad_q, dOt, st);
+    if (!ok) return ENTMAX_ATTN_LAUNCH_FAILED;
+    record(ev, 1, st);
+    BwdArgs a;
+    a.g = g;
+    a.Q = Q;
+    a.K = K;
+    a.V = V;
+    a.dO = dO;
+    a.Kt = Kt;
+    a.Qt = Qt;
+    a.dOt = dOt;
+    a.tau = tau;
+    a.dQ = dQ;
+    a.dK = dK;
+    a.dV = dV;
+    a.mu = reinterpret_cast<float*>(ws + L.off_mu);
+    a.crow = reinterpret_cast<float*>(ws + L.off_crow);
+    a.dscale = dscale;
+    a.mask = reinterpret_cast<uint32_t*>(ws + L.off_mask);
+    a.stats = reinterpret_cast<unsigned long long*>(stats);
+    a.nqb = L.nqb;
+    a.nkb = L.nkb;
+    a.nqg = L.nqg;
+    a.mask_words = L.mask_words;
+    switch (alpha_mode(p->alpha)) {
+      case 1: ok = launch_bwd_kernels<T, D, 1>(a, L, B, H, st, ev); break;
+      case 2: ok = launch_bwd_kernels<T, D, 2>(a, L, B, H, st, ev); break;
+      case 3: ok = launch_bwd_kernels<T, D, 3>(a, L, B, H, st, ev); break;
+      default: ok = launch_bwd_kernels<T, D, 0>(a, L, B, H, st, ev); break;
+    }
+  }
+  if (!ok) return ENTMAX_ATTN_LAUNCH_FAILED;
+  if (p->scale_layout == 1) {
+    hipLaunchKernelGGL(scale_grad_head_kernel, dim3((unsigned)H), dim3(kThreads), 0, st, g, dscale, dbeta, dgamma);
+    ok = launch_ok();
+  } else if (p->scale_layout == 2) {
+    long long rows = (long long)B * H * p->Nq;
+    if (rows > 0) {
+      hipLaunchKernelGGL(scale_grad_query_kernel, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, st, g, dscale,
+                         dbeta, dgamma);
+      ok = launch_ok();
+    }
+  }
+  record(ev, 5, st);
+  return ok ? ENTMAX_ATTN_OK : ENTMAX_ATTN_LAUNCH_FAILED;
+}
+
+}  // namespace
+
+extern "C" {
+
+int entmax_attn_check_params(const entmax_attn_params* p) { return check(p); }
+
+size_t entmax_attn_workspace_bytes(const entmax_attn_params* p, int is_bwd) {
+  if (check(p) != ENTMAX_ATTN_OK) return 0;
+  Layout L = make_layout(p);
+  size_t n = is_bwd ? L.total_bwd : L.total_fwd;
+  return n < kAlign ? kAlign : n;
+}
+
+const char* entmax_attn_strerror(int code) {
+  switch (code) {
+    case ENTMAX_ATTN_OK: return "success";
+    case ENTMAX_ATTN_INVALID_ARG: return "invalid argument";
+    case ENTMAX_ATTN_UNSUPPORTED_SHAPE: return "unsupported shape (D must be 64 or 128; sizes within index range)";
+    case ENTMAX_ATTN_MISALIGNED: return "pointer or stride not 16-byte aligned";
+    case ENTMAX_ATTN_WORKSPACE_TOO_SMALL: return "workspace too small";
+    case ENTMAX_ATTN_LAUNCH_FAILED: return "kernel launch failed";
+    default: return "unknown status";
+  }
+}
+
+int entmax_attn_fwd(const entmax_attn_params* p, const void* Q, const void* K, const void* V, const float* beta,
+                    const float* gamma, void* O, float* tau, uint64_t* stats, void* workspace, size_t workspace_bytes,
+                    void* hip_stream, void* const* phase_events) {
+  int rc = check(p);
+  if (rc != ENTMAX_ATTN_OK) return rc;
+  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  if ((long long)p->B * p->H * p->Nq == 0) {
+    for (int k = 0; k <= ENTMAX_FWD_NUM_PHASES; ++k) record(phase_events, k, st);
+    return ENTMAX_ATTN_OK;
+  }
+  if (!Q || !O || !tau || !workspace) return ENTMAX_ATTN_INVALID_ARG;
+  if (p->Nk > 0 && (!K || !V)) return ENTMAX_ATTN_INVALID_ARG;
+  if (p->scale_layout != 0 && (!beta || !gamma)) return ENTMAX_ATTN_INVALID_ARG;
+  if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O) || misaligned(workspace))
+    return ENTMAX_ATTN_MISALIGNED;
+  if ((reinterpret_cast<uintptr_t>(tau) & 3u) || (reinterpret_cast<uintptr_t>(stats) & 7u)) return ENTMAX_ATTN_MISALIGNED;
+  if (workspace_bytes < entmax_attn_workspace_bytes(p, 0)) return ENTMAX_ATTN_WORKSPACE_TOO_SMALL;
+  Layout L = make_layout(p);
+  char* ws = reinterpret_cast<char*>(workspace);
+  if (p->dtype == ENTMAX_ATTN_BF16) {
+    if (p->D == 64) return run_fwd<bf16_t, 64>(p, L, Q, K, V, beta, gamma, O, tau, stats, ws, st, phase_events);
+    return run_fwd<bf16_t, 128>(p, L, Q, K, V, beta, gamma, O, tau, stats, ws, st, phase_events);
+  }
+  if (p->D == 64) return run_fwd<float, 64>(p, L, Q, K, V, beta, gamma, O, tau, stats, ws, st, phase_events);
+  return run_fwd<float, 128>(p, L, Q, K, V, beta, gamma, O, tau, stats, ws, st, phase_events);
+}
+
+int entmax_attn_bwd(const entmax_attn_params* p, const void* Q, const void* K, const void* V, const void* O,
+                    const void* dO, const float* tau, const float* beta, const float* gamma, void* dQ, void* dK,
+                    void* dV, float* dbeta, float* dgamma, uint64_t* stats, void* workspace, size_t workspace_bytes,
+                    void* hip_stream, void* const* phase_events) {
+  (void)O;
+  int rc = check(p);
+  if (rc != ENTMAX_ATTN_OK) return rc;
+  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  if ((long long)p->B * p->H == 0 || (p->Nq == 0 && p->Nk == 0)) {
+    for (int k = 0; k <= ENTMAX_BWD_NUM_PHASES; ++k) record(phase_events, k, st);
+    return ENTMAX_ATTN_OK;
+  }
+  if (!workspace) return ENTMAX_ATTN_INVALID_ARG;
+  if (p->Nq > 0 && (!Q || !dO || !tau || !dQ)) return ENTMAX_ATTN_INVALID_ARG;
+  if (p->Nk > 0 && (!K || !V || !dK || !dV)) return ENTMAX_ATTN_INVALID_ARG;
+  if (p->scale_layout != 0 && (!beta || !gamma || !dbeta || !dgamma)) return ENTMAX_ATTN_INVALID_ARG;
+  if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(dO) || misaligned(dQ) || misaligned(dK) ||
+      misaligned(dV) || misaligned(workspace))
+    return ENTMAX_ATTN_MISALIGNED;
+  if ((reinterpret_cast<uintptr_t>(tau) & 3u) || (reinterpret_cast<uintptr_t>(stats) & 7u)) return ENTMAX_ATTN_MISALIGNED;
+  if (workspace_bytes < entmax_attn_workspace_bytes(p, 1)) return ENTMAX_ATTN_WORKSPACE_TOO_SMALL;
+  Layout L = make_layout(p);
+  char* ws = reinterpret_cast<char*>(workspace);
+  if (p->dtype == ENTMAX_ATTN_BF16) {
+    if (p->D == 64)
+      return run_bwd<bf16_t, 64>(p, L, Q, K, V, dO, tau, beta, gamma, dQ, dK, dV, dbeta, dgamma, stats, ws, st,
+                                 phase_events);
+    return run_bwd<bf16_t, 128>(p, L, Q, K, V, dO, tau, beta, gamma, dQ, dK, dV, dbeta, dgamma, stats, ws, st,
+                                phase_events);
+  }
+  if (p->D == 64)
+    return run_bwd<float, 64>(p, L, Q, K, V, dO, tau, beta, gamma, dQ, dK, dV, dbeta, dgamma, stats, ws, st,
+                              phase_events);
+  return run_bwd<float, 128>(p, L, Q, K, V, dO, tau, beta, gamma, dQ, dK, dV, dbeta, dgamma, stats, ws, st,
+                             phase_events);
+}
+
+}  // extern "C"

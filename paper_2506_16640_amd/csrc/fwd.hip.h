@@ -1,0 +1,333 @@
+// Forward kernel: alpha-entmax attention of Sec. 2.1 / eq. (entmax) on
+// ASEntmax-scaled logits (eq. (asentmax)), one workgroup per 128 query rows of
+// one (batch, head).
+//
+// Per workgroup, with every sweep recomputing Q K^T on the matrix cores from
+// K tiles staged in LDS (the n x n scores are never stored):
+//   1. row-max sweep                      -> bracket of App. A eq. (bounds):
+//        (alpha-1) max - 1 <= tau <= (alpha-1) max - n_i^(1-alpha)
+//   2. threshold sweeps: evaluate partial sums of
+//        f(tau) = sum_j [(alpha-1) s_ij - tau]_+^r - 1,  r = 1/(alpha-1)
+//      and take a safeguarded higher-order step inside the bracket (App. A,
+//      "alpha-entmax computation": root finding with bisection as the fallback).
+//      The first sweep runs at the lower bracket end, so the 32x32 tiles that
+//      hold no positive term there can never hold one later (tau only grows
+//      from that end): they are recorded per wave and skipped from then on.
+//   3. P.V sweep: p = x^r, tiles whose p is all zero are skipped, the others
+//      go through the matrix cores against the transposed V copy.
+#pragma once
+#include "qside.hip.h"
+
+namespace entmax {
+
+struct FwdArgs {
+  Geom g;
+  const void* Q;
+  const void* K;
+  const void* Vt;  // transposed, row-permuted copy of V: [B*H][D][npad_k]
+  void* O;
+  float* tau;
+  unsigned long long* stats;
+  int nqb;         // query blocks per head
+  int mask_words;  // uint32 words of one wave's tile mask
+};
+
+constexpr int kMaxSolveIters = 48;
+
+// Partial sums of the threshold function over the lane's keys.
+//   AM 1 (alpha 1.5, r 2): s0 = #positive, s1 = sum x,   s2 = sum x^2
+//   AM 2 (alpha 2,   r 1): s0 = #positive, s1 = sum x
+//   AM 3 (alpha 1.25,r 4): s0 = sum x^2,   s1 = sum x^3, s2 = sum x^4
+//   AM 0 (generic)       : s0 = sum x^(r-1), s1 = sum x^r
+// xmin is the smallest positive x (AM 1 and 2 only).
+struct RowSums {
+  float s0, s1, s2, xmin;
+  __device__ __forceinline__ void clear() {
+    s0 = s1 = s2 = 0.f;
+    xmin = kInf;
+  }
+  __device__ __forceinline__ void combine_halves() {
+    s0 += __shfl_xor(s0, 32);
+    s1 += __shfl_xor(s1, 32);
+    s2 += __shfl_xor(s2, 32);
+    xmin = fminf(xmin, __shfl_xor(xmin, 32));
+  }
+};
+
+template <int AM>
+__device__ __forceinline__ void accumulate(RowSums& s, float xp, float r) {
+  // xp = (alpha-1) s_ij - tau before clamping
+  if (AM == 1) {
+    bool pos = xp > 0.f;
+    float x = fmaxf(xp, 0.f);
+    s.s2 = fmaf(x, x, s.s2);
+    s.s1 += x;
+    s.s0 += pos ? 1.f : 0.f;
+    s.xmin = pos ? fminf(s.xmin, xp) : s.xmin;
+  } else if (AM == 2) {
+    bool pos = xp > 0.f;
+    float x = fmaxf(xp, 0.f);
+    s.s1 += x;
+    s.s0 += pos ? 1.f : 0.f;
+    s.xmin = pos ? fminf(s.xmin, xp) : s.xmin;
+  } else if (AM == 3) {
+    float x = fmaxf(xp, 0.f);
+    float x2 = x * x;
+    s.s0 += x2;
+    s.s1 = fmaf(x2, x, s.s1);
+    s.s2 = fmaf(x2, x2, s.s2);
+  } else {
+    if (xp > 0.f) {
+      float l = __builtin_amdgcn_logf(xp);
+      s.s1 += __builtin_amdgcn_exp2f(r * l);
+      s.s0 += __builtin_amdgcn_exp2f((r - 1.f) * l);
+    }
+  }
+}
+
+// One safeguarded root-finding step for a row.  [lo,hi] brackets the root
+// (f(lo) >= 0 >= f(hi)).  Returns true when the row is finished.
+//   AM 1 / AM 2: f is piecewise quadratic / linear, so the root of the local
+//     model is exact as soon as the support stops changing, which is the case
+//     when the step stays below the smallest positive term (xmin).
+//   AM 3: Halley step from f, f', f''.   AM 0: Newton step (f is convex and
+//     decreasing for alpha <= 2, so Newton from the left is monotone).
+template <int AM>
+__device__ __forceinline__ bool solve_step(const RowSums& s, float r, float& tau, float& lo, float& hi) {
+  float f, t;
+  bool exact = false;
+  if (AM == 1) {
+    f = s.s2 - 1.f;
+    float disc = fmaf(s.s1, s.s1, -s.s0 * f);
+    t = f / (s.s1 + sqrtf(fmaxf(disc, 0.f)));  // = (s1 - sqrt(disc)) / s0 without cancellation
+    exact = (f >= 0.f) && (t <= s.xmin);
+  } else if (AM == 2) {
+    f = s.s1 - 1.f;
+    t = f / s.s0;
+    exact = (f >= 0.f) && (t <= s.xmin);
+  } else if (AM == 3) {
+    f = s.s2 - 1.f;
+    // f' = -4 s1, f'' = 12 s0;  Halley: t = -2 f f' / (2 f'^2 - f f'') = 2 f s1 / (8 s1^2 - 3 f s0)
+    t = 2.f * f * s.s1 / (8.f * s.s1 * s.s1 - 3.f * f * s.s0);
+  } else {
+    f = s.s1 - 1.f;
+    t = f / (r * s.s0);
+  }
+  if (f >= 0.f)
+    lo = fmaxf(lo, tau);
+  else
+    hi = fminf(hi, tau);
+  float tn = tau + t;
+  if (exact) {
+    tau = fminf(tn, hi);
+    return true;
+  }
+  float tol = 2e-6f * fmaxf(1.f, fabsf(tau));
+  bool in = (tn >= lo) && (tn <= hi);  // false for NaN
+  if (!in) tn = 0.5f * (lo + hi);
+  bool fin = (fabsf(tn - tau) <= tol) || (hi - lo <= tol);
+  tau = tn;
+  return fin;
+}
+
+template <typename T, int D, int AM>
+__global__ __launch_bounds__(kThreads) void fwd_kernel(FwdArgs A) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  using C = QCtx<T, D>;
+  constexpr int KT = C::KT, NSB = C::NSB, NM = C::NM, TB = C::kTileBytes;
+  const Geom& g = A.g;
+  char* tiles = smem;  // 2 buffers x 2 slots
+  WaveMask wm;
+  wm.words = reinterpret_cast<uint32_t*>(smem + 4 * TB);
+  wm.nwords = A.mask_words;
+  int* wactive = reinterpret_cast<int*>(wm.words + kWaves * A.mask_words);
+
+  C q;
+  q.init(g, A.Q, xcd_remap(blockIdx.x, gridDim.x), A.nqb);
+  const float r = 1.0f / (g.alpha - 1.0f);
+  float* tau_out = A.tau + (long long)q.bh * g.Nq;
+  const long long o_base = (long long)q.b * g.q_sb + (long long)q.h * g.q_sh;
+
+  if (q.block_lim == 0) {  // no row of this workgroup sees any key
+    for (int e = q.tid; e < kBlockRows * D; e += kThreads) {
+      int row = q.qb * kBlockRows + e / D;
+      if (row < g.Nq) Elem<T>::store(A.O, o_base + (long long)row * g.q_sn + e % D, 0.f);
+    }
+    if (q.tid < kBlockRows && q.qb * kBlockRows + q.tid < g.Nq) tau_out[q.qb * kBlockRows + q.tid] = 0.f;
+    return;
+  }
+  for (int w = q.tid; w < kWaves * A.mask_words; w += kThreads) wm.words[w] = 0u;
+
+  const T* Kbh = reinterpret_cast<const T*>(A.K) + (long long)q.b * g.kv_sb + (long long)q.h * g.kv_sh;
+  Slot slots[2];
+  slots[0].base = reinterpret_cast<const char*>(Kbh);
+  slots[0].row_bytes = g.kv_sn * (long long)sizeof(T);
+  slots[1].base = reinterpret_cast<const char*>(A.Vt) + (long long)q.bh * D * g.npad_k * (long long)sizeof(T);
+  slots[1].row_bytes = (long long)g.npad_k * (long long)sizeof(T);
+
+  unsigned n_vis = 0, n_qk_max = 0, n_qk_solve = 0, n_eval = 0, n_qk_pv = 0, n_pv = 0, n_sweeps = 0;
+
+  // ------------------------------------------------------------ 1. row max
+  float m = -kInf;
+  sweep_tiles<T, D, 1, 0>(
+      tiles, slots, q.ntiles, g.Nk, q.tid, [](int) { return true; },
+      [&](int kt, const char* tl) {
+#pragma unroll
+        for (int sb = 0; sb < NSB; ++sb) {
+          int j0 = kt * KT + sb * 32;
+          if (j0 >= q.wave_lim_max) continue;
+          f32x16_t acc = q.scores(tl, sb);
+          ++n_vis;
+          if (j0 + 32 > q.wave_lim_min) {
+            int rel = q.lim - j0;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[e] = (q.key_of(e) < rel) ? acc[e] : -kInf;
+          }
+          m = fmaxf(m, max16(acc));
+        }
+      });
+  n_qk_max = n_vis;
+  m = fmaxf(m, __shfl_xor(m, 32));
+
+  // ------------------------------------------------------------ 2. threshold
+  bool live = q.valid && q.lim > 0;
+  float my = live ? q.a * m : 0.f;
+  float lo = my - 1.0f;
+  float hi = live ? my - __builtin_amdgcn_exp2f(-(g.alpha - 1.0f) * __builtin_amdgcn_logf((float)q.lim)) : 0.f;
+  float tau = lo;
+  bool done = !live;
+  int iter = 0;
+  int more;
+  do {
+    bool wave_on = __ballot(!done) != 0ull;
+    if (q.lane == 0) wactive[q.wave] = wave_on ? 1 : 0;
+    __syncthreads();
+    RowSums sums;
+    sums.clear();
+    const bool first = (iter == 0);
+    auto needed = [&](int kt) {
+      if (first) return true;
+      bool n = false;
+      for (int w = 0; w < kWaves; ++w) {
+        if (!wactive[w]) continue;
+        for (int sb = 0; sb < NSB; ++sb) n = n || wm.test(w, kt * NSB + sb);
+      }
+      return n;
+    };
+    sweep_tiles<T, D, 1, 0>(tiles, slots, q.ntiles, g.Nk, q.tid, needed, [&](int kt, const char* tl) {
+      if (!wave_on) return;
+#pragma unroll
+      for (int sb = 0; sb < NSB; ++sb) {
+        int j0 = kt * KT + sb * 32;
+        int jb = kt * NSB + sb;
+        if (j0 >= q.wave_lim_max) continue;
+        if (!first && !wm.test(q.wave, jb)) continue;
+        f32x16_t acc = q.scores(tl, sb);
+        ++n_qk_solve;
+        const bool masked = j0 + 32 > q.wave_lim_min;
+        int rel = q.lim - j0;
+        if (masked) {
+#pragma unroll
+          for (int e = 0; e < 16; ++e) acc[e] = (q.key_of(e) < rel) ? acc[e] : -kInf;
+        }
+        float lm = max16(acc);
+        bool cand = (lm > -kInf) && (fmaf(lm, q.a, -tau) > 0.f) && !done;
+        bool cand_any = (lm > -kInf) && (fmaf(lm, q.a, -lo) > 0.f) && live;  // could still matter at the bracket's left end
+        if (first) {
+          if (__ballot(cand_any) != 0ull && q.lane == 0) wm.set(q.wave, jb);
+        }
+        if (__ballot(cand) == 0ull) continue;
+        ++n_eval;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          float xp = (masked && !(q.key_of(e) < rel)) ? -1.f : fmaf(acc[e], q.a, -tau);
+          accumulate<AM>(sums, xp, r);
+        }
+      }
+    });
+    sums.combine_halves();
+    if (!done) done = solve_step<AM>(sums, r, tau, lo, hi);
+    ++iter;
+    ++n_sweeps;
+    more = __syncthreads_or(done ? 0 : 1);
+  } while (more && iter < kMaxSolveIters);
+
+  // ------------------------------------------------------------ 3. P.V
+  f32x16_t oacc[NM];
+#pragma unroll
+  for (int mm = 0; mm < NM; ++mm)
+    oacc[mm] = f32x16_t{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  auto needed_pv = [&](int kt) {
+    bool n = false;
+    for (int w = 0; w < kWaves; ++w)
+      for (int sb = 0; sb < NSB; ++sb) n = n || wm.test(w, kt * NSB + sb);
+    return n;
+  };
+  sweep_tiles<T, D, 2, 2>(tiles, slots, q.ntiles, g.Nk, q.tid, needed_pv, [&](int kt, const char* tl) {
+#pragma unroll
+    for (int sb = 0; sb < NSB; ++sb) {
+      int j0 = kt * KT + sb * 32;
+      int jb = kt * NSB + sb;
+      if (j0 >= q.wave_lim_max) continue;
+      if (!wm.test(q.wave, jb)) continue;
+      f32x16_t acc = q.scores(tl, sb);
+      ++n_qk_pv;
+      const bool masked = j0 + 32 > q.wave_lim_min;
+      int rel = q.lim - j0;
+      if (masked) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[e] = (q.key_of(e) < rel) ? acc[e] : -kInf;
+      }
+      float lm = max16(acc);
+      bool cand = live && (lm > -kInf) && (fmaf(lm, q.a, -tau) > 0.f);
+      if (__ballot(cand) == 0ull) continue;  // every probability of this tile is exactly zero
+      ++n_pv;
+      float p[16];
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        float xp = (masked && !(q.key_of(e) < rel)) ? 0.f : fmaf(acc[e], q.a, -tau);
+        p[e] = live ? pow_r<AM>(fmaxf(xp, 0.f), r) : 0.f;
+      }
+      const char* vt = tl + TB;
+#pragma unroll
+      for (int cc = 0; cc < 2; ++cc) {
+        // bf16 probabilities would cost up to 2^-9 |v| of output error; the hi + lo split keeps
+        // the product at fp32-level accuracy so that only the output rounding remains
+        Frag<T> pf, pl;
+        Elem<T>::pack_split(p + 8 * cc, pf, pl);
+#pragma unroll
+        for (int mm = 0; mm < NM; ++mm) {
+          Frag<T> vfr = C::XtTile::frag(vt, mm * 32 + q.li, 2 * (2 * sb + cc) + q.hh);
+          oacc[mm] = Elem<T>::mma(pf, vfr, oacc[mm]);
+          if (Elem<T>::kSplit) oacc[mm] = Elem<T>::mma(pl, vfr, oacc[mm]);
+        }
+      }
+    }
+  });
+
+  // oacc[mm][4g + r] of lane l is O[q0 + 8g + 4*(l/32) + r][32 mm + l%32]
+#pragma unroll
+  for (int mm = 0; mm < NM; ++mm) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      int row = q.q0 + q.key_of(e);
+      if (row < g.Nq) Elem<T>::store(A.O, o_base + (long long)row * g.q_sn + mm * 32 + q.li, oacc[mm][e]);
+    }
+  }
+  if (q.valid && q.hh == 0) tau_out[q.i] = live ? tau : 0.f;
+
+  if (A.stats && q.lane == 0) {
+    atomicAdd(&A.stats[ENTMAX_STAT_FWD_TILES_VISIBLE], (unsigned long long)n_vis);
+    atomicAdd(&A.stats[ENTMAX_STAT_FWD_QK_MAX], (unsigned long long)n_qk_max);
+    atomicAdd(&A.stats[ENTMAX_STAT_FWD_QK_SOLVE], (unsigned long long)n_qk_solve);
+    atomicAdd(&A.stats[ENTMAX_STAT_FWD_QK_PV], (unsigned long long)n_qk_pv);
+    atomicAdd(&A.stats[ENTMAX_STAT_FWD_PV_TILES], (unsigned long long)n_pv);
+    atomicAdd(&A.stats[ENTMAX_STAT_FWD_EVAL_TILES], (unsigned long long)n_eval);
+    if (q.wave == 0) {
+      atomicAdd(&A.stats[ENTMAX_STAT_FWD_SOLVE_SWEEPS], (unsigned long long)n_sweeps);
+      atomicAdd(&A.stats[ENTMAX_STAT_FWD_BLOCKS], 1ull);
+    }
+  }
+}
+
+}  // namespace entmax

@@ -1,0 +1,168 @@
+// Query-side machinery shared by the kernels whose workgroups own 128 query
+// rows and stream key tiles (forward, backward tile-mask, backward dQ):
+//   - QCtx: the per-lane row state.  Scores are produced TRANSPOSED,
+//     S^T = K_tile Q^T, so that lane l of a wave owns query row (l%32) and holds
+//     16 of the 32 keys of a tile; every per-row quantity (max, threshold,
+//     partial sums of the threshold function) is then a per-lane scalar and the
+//     inner loops need no cross-lane reduction.  The two lane halves are
+//     combined once per sweep.
+//   - sweep_tiles: double-buffered LDS pipeline over the key tiles a
+//     workgroup needs, with register-staged prefetch of the next tile.
+#pragma once
+#include "common.hip.h"
+
+#include <type_traits>
+
+namespace entmax {
+
+template <typename T, int D>
+struct QCtx {
+  static constexpr int KT = Elem<T>::kTile;  // keys per LDS tile
+  static constexpr int NSB = KT / 32;        // 32-key MFMA blocks per tile
+  static constexpr int NC = D / 16;          // 16-wide k chunks of a Q.K product
+  static constexpr int NM = D / 32;          // 32-wide feature blocks of an output
+  static constexpr int kTileBytes = KT * D * (int)sizeof(T);
+  using KTile = LdsTile<T, KT, D>;   // natural tile: rows = keys, cols = features
+  using XtTile = LdsTile<T, D, KT>;  // transposed tile: rows = features, cols = (permuted) keys
+
+  int tid, wave, lane, li, hh;
+  int b, h, bh, qb;
+  int q0;             // first query row of this wave
+  int i;              // this lane's query row
+  int lim;            // keys visible to row i are j < lim (0 for rows beyond Nq)
+  bool valid;         // i < Nq
+  int wave_lim_min;   // smallest / largest limit among the wave's rows
+  int wave_lim_max;
+  int block_lim;      // largest limit in the workgroup
+  int ntiles;         // key tiles the workgroup sweeps
+  float a;            // (alpha-1) |scale_i| / sqrt(D): y_ij = a * dot_ij are the entmax inputs times (alpha-1)
+  float c;            // scale_i / sqrt(D), signed
+  Frag<T> qf[NC];     // the row's query fragments (negated when scale_i < 0 so that a >= 0)
+
+  __device__ __forceinline__ void init(const Geom& g, const void* Q, int work_item, int nqb) {
+    tid = threadIdx.x;
+    wave = tid >> 6;
+    lane = tid & 63;
+    li = lane & 31;
+    hh = lane >> 5;
+    bh = work_item / nqb;
+    qb = nqb - 1 - (work_item % nqb);  // long (late) query blocks first: they carry the most causal work
+    b = bh / g.H;
+    h = bh % g.H;
+    q0 = qb * kBlockRows + wave * 32;
+    i = q0 + li;
+    valid = i < g.Nq;
+    lim = valid ? row_limit(g, i) : 0;
+    int last_blk = min(g.Nq, (qb + 1) * kBlockRows) - 1;
+    block_lim = row_limit(g, last_blk);
+    ntiles = (block_lim + KT - 1) / KT;
+    if (q0 < g.Nq) {
+      wave_lim_min = row_limit(g, q0);
+      wave_lim_max = row_limit(g, min(g.Nq, q0 + 32) - 1);
+    } else {
+      wave_lim_min = 0;
+      wave_lim_max = 0;
+    }
+    float scale = valid ? row_scale(g, b, h, i, lim, nullptr, nullptr, nullptr) : 0.f;
+    float inv_sqrt_d = 1.0f / sqrtf((float)D);
+    c = scale * inv_sqrt_d;
+    a = (g.alpha - 1.0f) * fabsf(c);
+    const T* qrow = reinterpret_cast<const T*>(Q) + (long long)b * g.q_sb + (long long)h * g.q_sh + (long long)i * g.q_sn;
+#pragma unroll
+    for (int cc = 0; cc < NC; ++cc) {
+      Frag<T> f = valid ? Elem<T>::load(qrow + 16 * cc + 8 * hh) : Elem<T>::zero();
+      qf[cc] = (c < 0.f) ? Elem<T>::negate(f) : f;
+    }
+  }
+
+  // S^T block: rows = 32 keys of sub-block sb of the K tile, cols = the wave's 32 queries.
+  // acc[4g + r] of lane l is the raw dot product with key 8g + 4*(l/32) + r of the block.
+  __device__ __forceinline__ f32x16_t scores(const char* ktile, int sb) const {
+    f32x16_t acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int cc = 0; cc < NC; ++cc) acc = Elem<T>::mma(KTile::frag(ktile, sb * 32 + li, 2 * cc + hh), qf[cc], acc);
+    return acc;
+  }
+
+  // key index (relative to the sub-block start) of accumulator element e of this lane
+  __device__ __forceinline__ int key_of(int e) const { return 8 * (e >> 2) + 4 * hh + (e & 3); }
+};
+
+struct Slot {
+  const char* base;     // tensor of this (batch, head): natural [N][row], transposed [D][npad]
+  long long row_bytes;  // bytes between consecutive rows in global memory
+};
+
+// Streams the tiles kt with needed(kt) (a workgroup-uniform predicate) through a
+// double-buffered LDS ring and calls body(kt, tiles) on each; `tiles` points at
+// NSLOT consecutive tiles.  Bit s of TMASK says slot s is a transposed copy.
+// All threads of the workgroup must call this together.
+template <typename T, int D, int NSLOT, int TMASK, class Needed, class Body>
+__device__ __forceinline__ void sweep_tiles(char* smem, const Slot* slots, int ntiles, int Nk, int tid, Needed needed,
+                                            Body body) {
+  using C = QCtx<T, D>;
+  constexpr int KT = C::KT;
+  constexpr int TB = C::kTileBytes;
+  using Tile0 = typename std::conditional<(TMASK & 1) != 0, typename C::XtTile, typename C::KTile>::type;
+  using Tile1 = typename std::conditional<(TMASK & 2) != 0, typename C::XtTile, typename C::KTile>::type;
+  using Tile2 = typename std::conditional<(TMASK & 4) != 0, typename C::XtTile, typename C::KTile>::type;
+  Stage<Tile0> s0;
+  Stage<Tile1> s1;
+  Stage<Tile2> s2;
+
+  auto fetch = [&](int kt) {
+    int rows_left = Nk - kt * KT;
+    {
+      bool tr = (TMASK & 1) != 0;
+      const char* gb = slots[0].base + (tr ? (long long)kt * KT * (long long)sizeof(T) : (long long)kt * KT * slots[0].row_bytes);
+      s0.fetch(gb, slots[0].row_bytes, tr ? D : rows_left, tid);
+    }
+    if constexpr (NSLOT > 1) {
+      bool tr = (TMASK & 2) != 0;
+      const char* gb = slots[1].base + (tr ? (long long)kt * KT * (long long)sizeof(T) : (long long)kt * KT * slots[1].row_bytes);
+      s1.fetch(gb, slots[1].row_bytes, tr ? D : rows_left, tid);
+    }
+    if constexpr (NSLOT > 2) {
+      bool tr = (TMASK & 4) != 0;
+      const char* gb = slots[2].base + (tr ? (long long)kt * KT * (long long)sizeof(T) : (long long)kt * KT * slots[2].row_bytes);
+      s2.fetch(gb, slots[2].row_bytes, tr ? D : rows_left, tid);
+    }
+  };
+  auto commit = [&](char* buf) {
+    s0.commit(buf, tid);
+    if constexpr (NSLOT > 1) s1.commit(buf + TB, tid);
+    if constexpr (NSLOT > 2) s2.commit(buf + 2 * TB, tid);
+  };
+  auto next_needed = [&](int kt) {
+    while (kt < ntiles && !needed(kt)) ++kt;
+    return kt;
+  };
+
+  int kt = next_needed(0);
+  if (kt < ntiles) {
+    fetch(kt);
+    commit(smem);
+  }
+  __syncthreads();
+  int cur = 0;
+  while (kt < ntiles) {
+    int nxt = next_needed(kt + 1);
+    if (nxt < ntiles) fetch(nxt);
+    body(kt, smem + cur * (NSLOT * TB));
+    if (nxt < ntiles) commit(smem + (cur ^ 1) * (NSLOT * TB));
+    __syncthreads();
+    cur ^= 1;
+    kt = nxt;
+  }
+}
+
+// Per-wave bit sets over the 32-key blocks of a head, kept in LDS: bit jb of
+// wave w says the block can hold a non-zero probability for some row of the wave.
+struct WaveMask {
+  uint32_t* words;  // [kWaves][nwords]
+  int nwords;
+  __device__ __forceinline__ bool test(int w, int jb) const { return (words[w * nwords + (jb >> 5)] >> (jb & 31)) & 1u; }
+  __device__ __forceinline__ void set(int w, int jb) { words[w * nwords + (jb >> 5)] |= (1u << (jb & 31)); }
+};
+
+}  // namespace entmax

@@ -1,0 +1,47 @@
+// Transposed, row-permuted copies of a [B,H,N,D] tensor, written once per call
+// into the workspace: Xt[bh][dc][16c + p] = X[bh][16c + perm(p)][dc] with
+//   perm(p) = 8*((p%8)/4) + 4*(p/8) + p%4,
+// zero beyond row N, N padded to a multiple of 64.  A lane of half hh then finds
+// the 8 rows {16c + 8*(e/4) + 4*hh + e%4 : e = 0..7} -- the rows whose
+// accumulator values it holds after a 32x32 MFMA -- contiguous at column
+// 16c + 8*hh of row dc, i.e. as one MFMA fragment of the product that contracts
+// over the rows of X (P.V, dS.K, P^T.dO, dS^T.Q).
+#pragma once
+#include "common.hip.h"
+
+namespace entmax {
+
+template <typename T, int D>
+__global__ __launch_bounds__(kThreads) void transpose_perm_kernel(const T* __restrict__ X, long long sb, long long sh,
+                                                                  long long sn, int H, int N, int npad,
+                                                                  T* __restrict__ Xt) {
+  constexpr int kPad = sizeof(T) == 2 ? 2 : 1;
+  __shared__ T tile[64][D + kPad];
+  const int tid = threadIdx.x;
+  const int bh = blockIdx.y, b = bh / H, h = bh % H;
+  const int j0 = blockIdx.x * 64;
+  const T* src = X + (long long)b * sb + (long long)h * sh;
+  for (int e = tid; e < 64 * D; e += kThreads) {
+    int row = e / D, col = e % D;
+    int j = j0 + row;
+    T v{};
+    if (j < N) v = src[(long long)j * sn + col];
+    tile[row][col] = v;
+  }
+  __syncthreads();
+  T* dst = Xt + (long long)bh * D * npad + j0;
+  for (int e = tid; e < D * 64; e += kThreads) {
+    int dc = e >> 6, pos = e & 63;
+    int p = pos & 15;
+    int srow = (pos & ~15) + 8 * ((p & 7) >> 2) + 4 * (p >> 3) + (p & 3);
+    dst[(long long)dc * npad + pos] = tile[srow][dc];
+  }
+}
+
+// O = 0, tau = 0 for problems without keys (Nk = 0), or any plain fill.
+__global__ void fill_zero_kernel(uint32_t* p, long long nwords) {
+  long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < nwords) p[i] = 0u;
+}
+
+}  // namespace entmax

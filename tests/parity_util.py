@@ -1,0 +1,71 @@
+"""Helpers for the GPU-vs-oracle parity tests: run the same seeded inputs through
+the HIP library (via the ctypes binding) and through the fp64 CPU oracle."""
+import numpy as np
+import torch
+
+TOL_O = 2e-2      # max-abs on outputs
+TOL_TAU = 1e-3    # max-abs on the threshold
+TOL_GRAD = 5e-2   # max|diff| / max|ref| per gradient tensor
+
+
+def to_dev(x, dtype):
+    if x is None:
+        return None
+    t = torch.from_numpy(np.ascontiguousarray(x)).cuda()
+    return t.to(torch.bfloat16) if dtype == "bf16" else t.float()
+
+
+def gpu_run(data, alpha, dtype, causal=True, logn_mode=0, bwd=True, stats=False, layout_bnhd=False):
+    from paper_2506_16640_amd import binding
+    q, k, v = (to_dev(data[n], dtype) for n in ("Q", "K", "V"))
+    if layout_bnhd:  # same values, [B,n,H,D] memory order viewed as [B,H,n,D]
+        q, k, v = (t.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3) for t in (q, k, v))
+    beta = None if data["beta"] is None else torch.from_numpy(data["beta"]).float().cuda()
+    gamma = None if data["gamma"] is None else torch.from_numpy(data["gamma"]).float().cuda()
+    st = binding.new_stats() if stats else None
+    kw = dict(alpha=alpha, beta=beta, gamma=gamma, delta=data["delta"], causal=causal, logn_mode=logn_mode, stats=st)
+    o, tau = binding.entmax_attn_fwd(q, k, v, **kw)
+    out = {"O": o.float().cpu().numpy().astype(np.float64), "tau": tau.cpu().numpy().astype(np.float64)}
+    if bwd:
+        do = to_dev(data["dO"], dtype)
+        if layout_bnhd:
+            do = do.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+        dq, dk, dv, db, dg = binding.entmax_attn_bwd(q, k, v, o, do, tau, **kw)
+        out.update(dQ=dq.float().cpu().numpy().astype(np.float64), dK=dk.float().cpu().numpy().astype(np.float64),
+                   dV=dv.float().cpu().numpy().astype(np.float64),
+                   dbeta=None if db is None else db.cpu().numpy().astype(np.float64),
+                   dgamma=None if dg is None else dg.cpu().numpy().astype(np.float64))
+    torch.cuda.synchronize()
+    if stats:
+        out["stats"] = binding.stats_dict(st)
+    return out
+
+
+def oracle_run(data, alpha, causal=True, logn_mode=0, bwd=True):
+    from oracle import oracle
+    kw = dict(beta=data["beta"], gamma=data["gamma"], delta=data["delta"], causal=causal, logn_mode=logn_mode)
+    out = oracle.attn_fwd(data["Q"], data["K"], data["V"], alpha, **kw)
+    if bwd:
+        out.update(oracle.attn_bwd(data["Q"], data["K"], data["V"], data["dO"], alpha, **kw))
+    return out
+
+
+def rel_err(a, b):
+    denom = np.abs(b).max()
+    return float(np.abs(a - b).max() / denom) if denom > 0 else float(np.abs(a).max())
+
+
+def compare(gpu, ref, bwd=True, tol_o=TOL_O, tol_tau=TOL_TAU, tol_grad=TOL_GRAD, label=""):
+    errs = {"tau": float(np.abs(gpu["tau"] - ref["tau"]).max()) if gpu["tau"].size else 0.0,
+            "O": float(np.abs(gpu["O"] - ref["O"]).max()) if gpu["O"].size else 0.0}
+    assert np.isfinite(gpu["O"]).all() and np.isfinite(gpu["tau"]).all(), label
+    assert errs["tau"] <= tol_tau, (label, errs)
+    assert errs["O"] <= tol_o, (label, errs)
+    if bwd:
+        for name in ("dQ", "dK", "dV", "dbeta", "dgamma"):
+            if ref.get(name) is None or ref[name].size == 0:
+                continue
+            assert np.isfinite(gpu[name]).all(), (label, name)
+            errs[name] = rel_err(gpu[name], ref[name])
+            assert errs[name] <= tol_grad, (label, name, errs)
+    return errs

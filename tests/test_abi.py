@@ -1,0 +1,95 @@
+"""Host-side checks of the C ABI: the library loads, exports every entry point the header
+declares, and validates arguments without touching a GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "entmax_attn.h")
+LIB = os.path.join(ROOT, "paper_2506_16640_amd", "lib", "libentmax_attn.so")
+
+
+@pytest.fixture(scope="module")
+def binding():
+    if not os.path.exists(LIB):
+        from paper_2506_16640_amd import build
+        build.build_library()
+    from paper_2506_16640_amd import binding as b
+    return b
+
+
+def test_exports_every_declared_symbol(binding):
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = set(re.findall(r"\b(entmax_attn_[a-z_]+)\s*\(", text))
+    assert {"entmax_attn_fwd", "entmax_attn_bwd", "entmax_attn_workspace_bytes", "entmax_attn_strerror",
+            "entmax_attn_check_params"} <= names
+    lib = ctypes.CDLL(LIB)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def _params(b, **kw):
+    base = dict(B=2, H=3, Nq=100, Nk=100, D=64, dtype=0, causal=1, scale_layout=1, logn_mode=0, alpha=1.5, delta=1.0)
+    base.update(kw)
+    p = b.Params()
+    for k, v in base.items():
+        setattr(p, k, v)
+    return p
+
+
+def test_parameter_validation(binding):
+    b = binding
+    assert b.check_params(_params(b)) == 0
+    assert b.check_params(_params(b, D=32)) == -2
+    assert b.check_params(_params(b, D=96)) == -2
+    assert b.check_params(_params(b, alpha=1.0)) == -1
+    assert b.check_params(_params(b, alpha=2.5)) == -1
+    assert b.check_params(_params(b, alpha=float("nan"))) == -1
+    assert b.check_params(_params(b, dtype=3)) == -1
+    assert b.check_params(_params(b, causal=2)) == -1
+    assert b.check_params(_params(b, scale_layout=5)) == -1
+    assert b.check_params(_params(b, Nq=-1)) == -1
+    assert b.check_params(_params(b, q_stride_b=64 * 100 * 3, q_stride_h=64, q_stride_n=3 * 64)) == 0
+    assert b.check_params(_params(b, q_stride_b=6400, q_stride_h=6400, q_stride_n=65)) == -3  # 130 bytes: misaligned
+    assert b.check_params(_params(b, q_stride_b=6400, q_stride_h=6400, q_stride_n=32)) == -1  # rows overlap
+    assert b.check_params(_params(b, Nq=1 << 25)) == -2
+    for code in (0, -1, -2, -3, -4, -5, -99):
+        assert isinstance(b.strerror(code), str) and b.strerror(code)
+
+
+def test_workspace_sizes(binding):
+    b = binding
+    p = _params(b, B=4, H=12, Nq=4096, Nk=4096)
+    fwd, bwd = b.workspace_bytes(p, 0), b.workspace_bytes(p, 1)
+    assert fwd == 48 * 64 * 4096 * 2  # one transposed copy of V
+    assert bwd > 3 * fwd
+    assert b.workspace_bytes(_params(b, D=32), 0) == 0
+    # ragged lengths are padded to 64 rows in the transposed copies
+    assert b.workspace_bytes(_params(b, B=1, H=1, Nq=65, Nk=65), 0) == 64 * 128 * 2
+
+
+def test_entry_points_reject_bad_arguments_before_any_launch(binding):
+    b = binding
+    lib = ctypes.CDLL(LIB)
+    lib.entmax_attn_fwd.restype = ctypes.c_int
+    p = _params(b)
+    null = ctypes.c_void_p(None)
+    fake = ctypes.c_void_p(4096)
+    bad = ctypes.c_void_p(4100)  # not 16-byte aligned
+    args = lambda **kw: [kw.get(k, fake) for k in ("Q", "K", "V", "beta", "gamma", "O", "tau", "stats", "ws")]  # noqa
+    call = lambda prm, a, wsb=1 << 30: lib.entmax_attn_fwd(ctypes.byref(prm), *a, ctypes.c_size_t(wsb), null, null)  # noqa
+    assert call(_params(b, D=32), args()) == -2
+    assert call(p, args(Q=null)) == -1
+    assert call(p, args(beta=null)) == -1
+    assert call(p, args(K=bad)) == -3
+    assert call(p, args(stats=null), wsb=16) == -4
+    lib.entmax_attn_bwd.restype = ctypes.c_int
+    a = [fake] * 15
+    assert lib.entmax_attn_bwd(ctypes.byref(_params(b, alpha=3.0)), *a, ctypes.c_size_t(1 << 30), null, null) == -1
+    a[5] = null  # tau
+    assert lib.entmax_attn_bwd(ctypes.byref(p), *a, ctypes.c_size_t(1 << 30), null, null) == -1
+    a[5] = fake
+    assert lib.entmax_attn_bwd(ctypes.byref(p), *a, ctypes.c_size_t(16), null, null) == -4
