@@ -12,6 +12,8 @@ HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     # packed fp32 arithmetic stays off: ordinary float code must not be fused into v_pk_* forms
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # MFMA results go straight to VGPRs (no AGPR round trip before the VALU work on the scores)
+    "-mllvm", "-amdgpu-mfma-vgpr-form=1",
 ]
 
 

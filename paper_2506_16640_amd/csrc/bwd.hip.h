@@ -60,21 +60,25 @@ __global__ __launch_bounds__(kThreads) void bwd_mask_kernel(BwdArgs A) {
                                                 (long long)q.h * g.kv_sh);
   slots[0].row_bytes = g.kv_sn * (long long)sizeof(T);
   unsigned n_vis = 0, n_act = 0;
-  sweep_tiles<T, D, 1, 0>(
+  sweep_tiles<C, T, D, 1, 0>(
       smem, slots, q.ntiles, g.Nk, q.tid, [](int) { return true; },
       [&](int kt, const char* tl) {
+        const uint32_t act = q.visible_bits(kt);
+        f32x16_t acc[NSB];
+#pragma unroll
+        for (int sb = 0; sb < NSB; ++sb)
+          if (act & (1u << sb)) acc[sb] = q.scores(tl, sb);
 #pragma unroll
         for (int sb = 0; sb < NSB; ++sb) {
+          if (!(act & (1u << sb))) continue;
           int j0 = kt * KT + sb * 32;
-          if (j0 >= q.wave_lim_max) continue;
-          f32x16_t acc = q.scores(tl, sb);
           ++n_vis;
           if (j0 + 32 > q.wave_lim_min) {
             int rel = q.lim - j0;
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc[e] = (q.key_of(e) < rel) ? acc[e] : -kInf;
+            for (int e = 0; e < 16; ++e) acc[sb][e] = (q.key_of(e) < rel) ? acc[sb][e] : -kInf;
           }
-          float lm = max16(acc);
+          float lm = max16(acc[sb]);
           bool cand = live && (lm > -kInf) && (fmaf(lm, q.a, -tau) > 0.f);
           if (__ballot(cand) != 0ull) {
             ++n_act;
@@ -107,7 +111,7 @@ __global__ __launch_bounds__(kThreads) void bwd_dq_kernel(BwdArgs A) {
   WaveMask wm;
   wm.words = reinterpret_cast<uint32_t*>(smem + 6 * TB);
   wm.nwords = A.mask_words;
-  float* xch = reinterpret_cast<float*>(wm.words + kWaves * A.mask_words);  // [kWaves][64]
+  float* xch = reinterpret_cast<float*>(wm.words + (kWaves + 1) * A.mask_words);  // [kWaves][64]
 
   C q;
   q.init(g, A.Q, xcd_remap(blockIdx.x, gridDim.x), A.nqb);
@@ -129,7 +133,7 @@ __global__ __launch_bounds__(kThreads) void bwd_dq_kernel(BwdArgs A) {
       wm.words[q.wave * A.mask_words + w] =
           (ig < A.nqg) ? A.mask[((long long)q.bh * A.nqg + ig) * A.mask_words + w] : 0u;
   }
-  __syncthreads();
+  wm.merge(q.tid);
 
   const long long kv_base = (long long)q.b * g.kv_sb + (long long)q.h * g.kv_sh;
   Slot slots[3];
@@ -149,18 +153,13 @@ __global__ __launch_bounds__(kThreads) void bwd_dq_kernel(BwdArgs A) {
   float Z = 0.f, N = 0.f, Aq = 0.f, Cq = 0.f;
   unsigned n_tiles = 0;
 
-  auto needed = [&](int kt) {
-    bool n = false;
-    for (int w = 0; w < kWaves; ++w)
-      for (int sb = 0; sb < NSB; ++sb) n = n || wm.test(w, kt * NSB + sb);
-    return n;
-  };
-  sweep_tiles<T, D, 3, 4>(tiles, slots, q.ntiles, g.Nk, q.tid, needed, [&](int kt, const char* tl) {
+  auto needed = [&](int kt) { return wm.tile_bits<NSB>(kWaves, kt) != 0u; };
+  sweep_tiles<C, T, D, 3, 4>(tiles, slots, q.ntiles, g.Nk, q.tid, needed, [&](int kt, const char* tl) {
+    const uint32_t act = q.visible_bits(kt) & wm.tile_bits<NSB>(q.wave, kt);
 #pragma unroll
     for (int sb = 0; sb < NSB; ++sb) {
+      if (!(act & (1u << sb))) continue;
       int j0 = kt * KT + sb * 32;
-      if (j0 >= q.wave_lim_max) continue;
-      if (!wm.test(q.wave, kt * NSB + sb)) continue;
       f32x16_t acc = q.scores(tl, sb);
       const bool masked = j0 + 32 > q.wave_lim_min;
       const int rel = q.lim - j0;
@@ -248,7 +247,8 @@ __global__ __launch_bounds__(kThreads) void bwd_dkv_kernel(BwdArgs A) {
   using C = QCtx<T, D>;
   constexpr int QT = C::KT, NSG = C::NSB, NC = C::NC, NM = C::NM, TB = C::kTileBytes;
   const Geom& g = A.g;
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 31, hh = lane >> 5;
+  const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, li = lane & 31,
+            hh = lane >> 5;
   const int item = xcd_remap(blockIdx.x, gridDim.x);
   const int bh = item / A.nkb, kb = item % A.nkb;
   const int b = bh / g.H, h = bh % g.H;
@@ -375,7 +375,8 @@ __global__ __launch_bounds__(kThreads) void bwd_dkv_kernel(BwdArgs A) {
 #pragma unroll
     for (int sg = 0; sg < NSG; ++sg) {
       int ig = qt * NSG + sg;
-      if (ig >= A.nqg || !((need[ig] >> wave) & 1)) continue;
+      if (ig >= A.nqg) continue;
+      if (!((__builtin_amdgcn_readfirstlane((int)need[ig]) >> wave) & 1)) continue;
       int i0 = ig * 32;
       // S block: rows = the 32 queries of the group, cols = the wave's 32 keys
       f32x16_t s = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};

@@ -178,6 +178,45 @@ __device__ __forceinline__ Frag<T> LdsTile<T, ROWS, COLS>::frag(const char* tile
   }
 }
 
+// Byte offset(s) of one fragment inside a tile, precomputed per lane so that the
+// inner loops issue ds_read_b128 with an immediate for everything that is
+// uniform (buffer, 32-row block).  Valid as long as the rows added later are
+// multiples of 32 (they do not change the swizzle).
+template <typename T>
+struct FragOff;
+template <>
+struct FragOff<bf16_t> {
+  int o;
+  template <typename TileT>
+  static __device__ __forceinline__ FragOff make(int row, int f) {
+    FragOff r;
+    r.o = TileT::off(row, f);
+    return r;
+  }
+  __device__ __forceinline__ Frag<bf16_t> load(const char* tile, int extra) const {
+    Frag<bf16_t> r;
+    r.v = *reinterpret_cast<const u32x4_t*>(tile + o + extra);
+    return r;
+  }
+};
+template <>
+struct FragOff<float> {
+  int o0, o1;
+  template <typename TileT>
+  static __device__ __forceinline__ FragOff make(int row, int f) {
+    FragOff r;
+    r.o0 = TileT::off(row, 2 * f);
+    r.o1 = TileT::off(row, 2 * f + 1);
+    return r;
+  }
+  __device__ __forceinline__ Frag<float> load(const char* tile, int extra) const {
+    Frag<float> r;
+    r.lo = *reinterpret_cast<const f32x4_t*>(tile + o0 + extra);
+    r.hi = *reinterpret_cast<const f32x4_t*>(tile + o1 + extra);
+    return r;
+  }
+};
+
 // Register staging for one tile: fetch() issues the global loads (rows at or
 // beyond valid_rows read as zero), commit() writes them to LDS.
 template <typename TileT>

@@ -58,8 +58,8 @@ int check(const entmax_attn_params* p) {
 Layout make_layout(const entmax_attn_params* p) {
   Layout L;
   L.esize = p->dtype == ENTMAX_ATTN_BF16 ? 2 : 4;
-  L.npad_q = ceil_div(p->Nq, 64) * 64;
-  L.npad_k = ceil_div(p->Nk, 64) * 64;
+  L.npad_q = ceil_div(p->Nq, 128) * 128;
+  L.npad_k = ceil_div(p->Nk, 128) * 128;
   L.nqb = ceil_div(p->Nq, kBlockRows);
   L.nkb = ceil_div(p->Nk, kBlockRows);
   L.nqg = ceil_div(p->Nq, 32);
@@ -178,7 +178,7 @@ bool launch_transpose(const void* X, long long sb, long long sh, long long sn, i
 
 template <typename T, int D, int AM>
 bool launch_fwd_main(const FwdArgs& a, int nblocks, hipStream_t st) {
-  size_t smem = 4 * (size_t)QCtx<T, D>::kTileBytes + (size_t)kWaves * a.mask_words * 4 + 64;
+  size_t smem = 4 * (size_t)QCtx<T, D, FwdTile<T>::value>::kTileBytes + (size_t)(kWaves + 1) * a.mask_words * 4 + 64;
   auto kern = fwd_kernel<T, D, AM>;
   if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) !=
       hipSuccess)
@@ -230,8 +230,8 @@ int run_fwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
 
 template <typename T, int D, int AM>
 bool launch_bwd_kernels(const BwdArgs& a, const Layout& L, int B, int H, hipStream_t st, void* const* ev) {
-  size_t smem_mask = 2 * (size_t)QCtx<T, D>::kTileBytes + (size_t)kWaves * a.mask_words * 4 + 64;
-  size_t smem_dq = 6 * (size_t)QCtx<T, D>::kTileBytes + (size_t)kWaves * a.mask_words * 4 + kWaves * 64 * 4 + 64;
+  size_t smem_mask = 2 * (size_t)QCtx<T, D>::kTileBytes + (size_t)(kWaves + 1) * a.mask_words * 4 + 64;
+  size_t smem_dq = 6 * (size_t)QCtx<T, D>::kTileBytes + (size_t)(kWaves + 1) * a.mask_words * 4 + kWaves * 64 * 4 + 64;
   size_t smem_dkv = 8 * (size_t)QCtx<T, D>::kTileBytes + 2 * 4 * (size_t)QCtx<T, D>::KT * 4 + (size_t)a.nqg + 64;
   auto k_mask = bwd_mask_kernel<T, D, AM>;
   auto k_dq = bwd_dq_kernel<T, D, AM>;

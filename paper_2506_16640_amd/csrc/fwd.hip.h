@@ -130,17 +130,22 @@ __device__ __forceinline__ bool solve_step(const RowSums& s, float r, float& tau
   return fin;
 }
 
+// keys per LDS tile of the forward kernel
+template <typename T>
+struct FwdTile {
+  static constexpr int value = sizeof(T) == 2 ? 128 : 32;
+};
+
 template <typename T, int D, int AM>
 __global__ __launch_bounds__(kThreads) void fwd_kernel(FwdArgs A) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  using C = QCtx<T, D>;
+  using C = QCtx<T, D, FwdTile<T>::value>;
   constexpr int KT = C::KT, NSB = C::NSB, NM = C::NM, TB = C::kTileBytes;
   const Geom& g = A.g;
   char* tiles = smem;  // 2 buffers x 2 slots
   WaveMask wm;
   wm.words = reinterpret_cast<uint32_t*>(smem + 4 * TB);
   wm.nwords = A.mask_words;
-  int* wactive = reinterpret_cast<int*>(wm.words + kWaves * A.mask_words);
 
   C q;
   q.init(g, A.Q, xcd_remap(blockIdx.x, gridDim.x), A.nqb);
@@ -156,7 +161,7 @@ __global__ __launch_bounds__(kThreads) void fwd_kernel(FwdArgs A) {
     if (q.tid < kBlockRows && q.qb * kBlockRows + q.tid < g.Nq) tau_out[q.qb * kBlockRows + q.tid] = 0.f;
     return;
   }
-  for (int w = q.tid; w < kWaves * A.mask_words; w += kThreads) wm.words[w] = 0u;
+  for (int w = q.tid; w < (kWaves + 1) * A.mask_words; w += kThreads) wm.words[w] = 0u;
 
   const T* Kbh = reinterpret_cast<const T*>(A.K) + (long long)q.b * g.kv_sb + (long long)q.h * g.kv_sh;
   Slot slots[2];
@@ -165,32 +170,38 @@ __global__ __launch_bounds__(kThreads) void fwd_kernel(FwdArgs A) {
   slots[1].base = reinterpret_cast<const char*>(A.Vt) + (long long)q.bh * D * g.npad_k * (long long)sizeof(T);
   slots[1].row_bytes = (long long)g.npad_k * (long long)sizeof(T);
 
-  unsigned n_vis = 0, n_qk_max = 0, n_qk_solve = 0, n_eval = 0, n_qk_pv = 0, n_pv = 0, n_sweeps = 0;
+  unsigned n_vis = 0, n_qk_solve = 0, n_eval = 0, n_qk_pv = 0, n_pv = 0, n_sweeps = 0;
+
+  // mask of a 32-key block whose keys are not all visible to all rows of the wave
+  auto mask_block = [&](f32x16_t& acc, int j0) {
+    int rel = q.lim - j0;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[e] = (q.key_of(e) < rel) ? acc[e] : -kInf;
+  };
 
   // ------------------------------------------------------------ 1. row max
   float m = -kInf;
-  sweep_tiles<T, D, 1, 0>(
+  sweep_tiles<C, T, D, 1, 0>(
       tiles, slots, q.ntiles, g.Nk, q.tid, [](int) { return true; },
       [&](int kt, const char* tl) {
+        const uint32_t act = q.visible_bits(kt);
+        f32x16_t acc[NSB];
+#pragma unroll
+        for (int sb = 0; sb < NSB; ++sb)
+          if (act & (1u << sb)) acc[sb] = q.scores(tl, sb);
 #pragma unroll
         for (int sb = 0; sb < NSB; ++sb) {
+          if (!(act & (1u << sb))) continue;
           int j0 = kt * KT + sb * 32;
-          if (j0 >= q.wave_lim_max) continue;
-          f32x16_t acc = q.scores(tl, sb);
           ++n_vis;
-          if (j0 + 32 > q.wave_lim_min) {
-            int rel = q.lim - j0;
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[e] = (q.key_of(e) < rel) ? acc[e] : -kInf;
-          }
-          m = fmaxf(m, max16(acc));
+          if (j0 + 32 > q.wave_lim_min) mask_block(acc[sb], j0);
+          m = fmaxf(m, max16(acc[sb]));
         }
       });
-  n_qk_max = n_vis;
   m = fmaxf(m, __shfl_xor(m, 32));
 
   // ------------------------------------------------------------ 2. threshold
-  bool live = q.valid && q.lim > 0;
+  const bool live = q.valid && q.lim > 0;
   float my = live ? q.a * m : 0.f;
   float lo = my - 1.0f;
   float hi = live ? my - __builtin_amdgcn_exp2f(-(g.alpha - 1.0f) * __builtin_amdgcn_logf((float)q.lim)) : 0.f;
@@ -199,52 +210,44 @@ __global__ __launch_bounds__(kThreads) void fwd_kernel(FwdArgs A) {
   int iter = 0;
   int more;
   do {
-    bool wave_on = __ballot(!done) != 0ull;
-    if (q.lane == 0) wactive[q.wave] = wave_on ? 1 : 0;
-    __syncthreads();
+    const bool wave_on = __ballot(!done) != 0ull;
     RowSums sums;
     sums.clear();
     const bool first = (iter == 0);
-    auto needed = [&](int kt) {
-      if (first) return true;
-      bool n = false;
-      for (int w = 0; w < kWaves; ++w) {
-        if (!wactive[w]) continue;
-        for (int sb = 0; sb < NSB; ++sb) n = n || wm.test(w, kt * NSB + sb);
-      }
-      return n;
-    };
-    sweep_tiles<T, D, 1, 0>(tiles, slots, q.ntiles, g.Nk, q.tid, needed, [&](int kt, const char* tl) {
+    auto needed = [&](int kt) { return first || wm.tile_bits<NSB>(kWaves, kt) != 0u; };
+    sweep_tiles<C, T, D, 1, 0>(tiles, slots, q.ntiles, g.Nk, q.tid, needed, [&](int kt, const char* tl) {
       if (!wave_on) return;
+      uint32_t act = q.visible_bits(kt);
+      if (!first) act &= wm.tile_bits<NSB>(q.wave, kt);
+      f32x16_t acc[NSB];
+#pragma unroll
+      for (int sb = 0; sb < NSB; ++sb)
+        if (act & (1u << sb)) acc[sb] = q.scores(tl, sb);
 #pragma unroll
       for (int sb = 0; sb < NSB; ++sb) {
+        if (!(act & (1u << sb))) continue;
         int j0 = kt * KT + sb * 32;
-        int jb = kt * NSB + sb;
-        if (j0 >= q.wave_lim_max) continue;
-        if (!first && !wm.test(q.wave, jb)) continue;
-        f32x16_t acc = q.scores(tl, sb);
         ++n_qk_solve;
         const bool masked = j0 + 32 > q.wave_lim_min;
-        int rel = q.lim - j0;
-        if (masked) {
-#pragma unroll
-          for (int e = 0; e < 16; ++e) acc[e] = (q.key_of(e) < rel) ? acc[e] : -kInf;
-        }
-        float lm = max16(acc);
+        if (masked) mask_block(acc[sb], j0);
+        float lm = max16(acc[sb]);
+        // masked entries are -inf: a = 0 (scale 0) must not turn them into NaN
         bool cand = (lm > -kInf) && (fmaf(lm, q.a, -tau) > 0.f) && !done;
-        bool cand_any = (lm > -kInf) && (fmaf(lm, q.a, -lo) > 0.f) && live;  // could still matter at the bracket's left end
         if (first) {
-          if (__ballot(cand_any) != 0ull && q.lane == 0) wm.set(q.wave, jb);
+          // at the bracket's left end: a tile without a positive term here never gets one later
+          bool cand_any = (lm > -kInf) && (fmaf(lm, q.a, -tau) > 0.f) && live;
+          if (__ballot(cand_any) != 0ull && q.lane == 0) wm.set(q.wave, kt * NSB + sb);
         }
         if (__ballot(cand) == 0ull) continue;
         ++n_eval;
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-          float xp = (masked && !(q.key_of(e) < rel)) ? -1.f : fmaf(acc[e], q.a, -tau);
+          float xp = (masked && acc[sb][e] == -kInf) ? -1.f : fmaf(acc[sb][e], q.a, -tau);
           accumulate<AM>(sums, xp, r);
         }
       }
     });
+    if (first) wm.merge(q.tid);
     sums.combine_halves();
     if (!done) done = solve_step<AM>(sums, r, tau, lo, hi);
     ++iter;
@@ -257,53 +260,52 @@ __global__ __launch_bounds__(kThreads) void fwd_kernel(FwdArgs A) {
 #pragma unroll
   for (int mm = 0; mm < NM; ++mm)
     oacc[mm] = f32x16_t{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  auto needed_pv = [&](int kt) {
-    bool n = false;
-    for (int w = 0; w < kWaves; ++w)
-      for (int sb = 0; sb < NSB; ++sb) n = n || wm.test(w, kt * NSB + sb);
-    return n;
-  };
-  sweep_tiles<T, D, 2, 2>(tiles, slots, q.ntiles, g.Nk, q.tid, needed_pv, [&](int kt, const char* tl) {
+  // lane offsets of the V^T fragments: row (l%32) of a 32-feature block, key chunk 2 sb + cc
+  FragOff<T> voff[2 * NSB];
 #pragma unroll
-    for (int sb = 0; sb < NSB; ++sb) {
-      int j0 = kt * KT + sb * 32;
-      int jb = kt * NSB + sb;
-      if (j0 >= q.wave_lim_max) continue;
-      if (!wm.test(q.wave, jb)) continue;
-      f32x16_t acc = q.scores(tl, sb);
-      ++n_qk_pv;
-      const bool masked = j0 + 32 > q.wave_lim_min;
-      int rel = q.lim - j0;
-      if (masked) {
+  for (int k = 0; k < 2 * NSB; ++k) voff[k] = FragOff<T>::template make<typename C::XtTile>(q.li, 2 * k + q.hh);
+
+  sweep_tiles<C, T, D, 2, 2>(
+      tiles, slots, q.ntiles, g.Nk, q.tid, [&](int kt) { return wm.tile_bits<NSB>(kWaves, kt) != 0u; },
+      [&](int kt, const char* tl) {
+        const uint32_t act = q.visible_bits(kt) & wm.tile_bits<NSB>(q.wave, kt);
+        f32x16_t acc[NSB];
 #pragma unroll
-        for (int e = 0; e < 16; ++e) acc[e] = (q.key_of(e) < rel) ? acc[e] : -kInf;
-      }
-      float lm = max16(acc);
-      bool cand = live && (lm > -kInf) && (fmaf(lm, q.a, -tau) > 0.f);
-      if (__ballot(cand) == 0ull) continue;  // every probability of this tile is exactly zero
-      ++n_pv;
-      float p[16];
+        for (int sb = 0; sb < NSB; ++sb)
+          if (act & (1u << sb)) acc[sb] = q.scores(tl, sb);
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        float xp = (masked && !(q.key_of(e) < rel)) ? 0.f : fmaf(acc[e], q.a, -tau);
-        p[e] = live ? pow_r<AM>(fmaxf(xp, 0.f), r) : 0.f;
-      }
-      const char* vt = tl + TB;
+        for (int sb = 0; sb < NSB; ++sb) {
+          if (!(act & (1u << sb))) continue;
+          int j0 = kt * KT + sb * 32;
+          ++n_qk_pv;
+          const bool masked = j0 + 32 > q.wave_lim_min;
+          if (masked) mask_block(acc[sb], j0);
+          float lm = max16(acc[sb]);
+          bool cand = live && (lm > -kInf) && (fmaf(lm, q.a, -tau) > 0.f);
+          if (__ballot(cand) == 0ull) continue;  // every probability of this tile is exactly zero
+          ++n_pv;
+          float p[16];
 #pragma unroll
-      for (int cc = 0; cc < 2; ++cc) {
-        // bf16 probabilities would cost up to 2^-9 |v| of output error; the hi + lo split keeps
-        // the product at fp32-level accuracy so that only the output rounding remains
-        Frag<T> pf, pl;
-        Elem<T>::pack_split(p + 8 * cc, pf, pl);
+          for (int e = 0; e < 16; ++e) {
+            float xp = (masked && acc[sb][e] == -kInf) ? 0.f : fmaf(acc[sb][e], q.a, -tau);
+            p[e] = live ? pow_r<AM>(fmaxf(xp, 0.f), r) : 0.f;
+          }
+          const char* vt = tl + TB;
 #pragma unroll
-        for (int mm = 0; mm < NM; ++mm) {
-          Frag<T> vfr = C::XtTile::frag(vt, mm * 32 + q.li, 2 * (2 * sb + cc) + q.hh);
-          oacc[mm] = Elem<T>::mma(pf, vfr, oacc[mm]);
-          if (Elem<T>::kSplit) oacc[mm] = Elem<T>::mma(pl, vfr, oacc[mm]);
+          for (int cc = 0; cc < 2; ++cc) {
+            // bf16 probabilities would cost up to 2^-9 |v| of output error; the hi + lo split keeps
+            // the product at fp32-level accuracy so that only the output rounding remains
+            Frag<T> pf, pl;
+            Elem<T>::pack_split(p + 8 * cc, pf, pl);
+#pragma unroll
+            for (int mm = 0; mm < NM; ++mm) {
+              Frag<T> vfr = voff[2 * sb + cc].load(vt, mm * 32 * C::XtTile::kRowBytes);
+              oacc[mm] = Elem<T>::mma(pf, vfr, oacc[mm]);
+              if (Elem<T>::kSplit) oacc[mm] = Elem<T>::mma(pl, vfr, oacc[mm]);
+            }
+          }
         }
-      }
-    }
-  });
+      });
 
   // oacc[mm][4g + r] of lane l is O[q0 + 8g + 4*(l/32) + r][32 mm + l%32]
 #pragma unroll
@@ -318,7 +320,7 @@ __global__ __launch_bounds__(kThreads) void fwd_kernel(FwdArgs A) {
 
   if (A.stats && q.lane == 0) {
     atomicAdd(&A.stats[ENTMAX_STAT_FWD_TILES_VISIBLE], (unsigned long long)n_vis);
-    atomicAdd(&A.stats[ENTMAX_STAT_FWD_QK_MAX], (unsigned long long)n_qk_max);
+    atomicAdd(&A.stats[ENTMAX_STAT_FWD_QK_MAX], (unsigned long long)n_vis);
     atomicAdd(&A.stats[ENTMAX_STAT_FWD_QK_SOLVE], (unsigned long long)n_qk_solve);
     atomicAdd(&A.stats[ENTMAX_STAT_FWD_QK_PV], (unsigned long long)n_qk_pv);
     atomicAdd(&A.stats[ENTMAX_STAT_FWD_PV_TILES], (unsigned long long)n_pv);

@@ -15,9 +15,9 @@
 
 namespace entmax {
 
-template <typename T, int D>
+template <typename T, int D, int KT_ = Elem<T>::kTile>
 struct QCtx {
-  static constexpr int KT = Elem<T>::kTile;  // keys per LDS tile
+  static constexpr int KT = KT_;             // keys per LDS tile
   static constexpr int NSB = KT / 32;        // 32-key MFMA blocks per tile
   static constexpr int NC = D / 16;          // 16-wide k chunks of a Q.K product
   static constexpr int NM = D / 32;          // 32-wide feature blocks of an output
@@ -38,10 +38,11 @@ struct QCtx {
   float a;            // (alpha-1) |scale_i| / sqrt(D): y_ij = a * dot_ij are the entmax inputs times (alpha-1)
   float c;            // scale_i / sqrt(D), signed
   Frag<T> qf[NC];     // the row's query fragments (negated when scale_i < 0 so that a >= 0)
+  FragOff<T> koff[NC];  // lane offsets of the K-tile fragments of row (l%32)
 
   __device__ __forceinline__ void init(const Geom& g, const void* Q, int work_item, int nqb) {
     tid = threadIdx.x;
-    wave = tid >> 6;
+    wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps everything derived from it scalar
     lane = tid & 63;
     li = lane & 31;
     hh = lane >> 5;
@@ -72,6 +73,7 @@ struct QCtx {
     for (int cc = 0; cc < NC; ++cc) {
       Frag<T> f = valid ? Elem<T>::load(qrow + 16 * cc + 8 * hh) : Elem<T>::zero();
       qf[cc] = (c < 0.f) ? Elem<T>::negate(f) : f;
+      koff[cc] = FragOff<T>::template make<KTile>(li, 2 * cc + hh);
     }
   }
 
@@ -80,8 +82,15 @@ struct QCtx {
   __device__ __forceinline__ f32x16_t scores(const char* ktile, int sb) const {
     f32x16_t acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int cc = 0; cc < NC; ++cc) acc = Elem<T>::mma(KTile::frag(ktile, sb * 32 + li, 2 * cc + hh), qf[cc], acc);
+    for (int cc = 0; cc < NC; ++cc) acc = Elem<T>::mma(koff[cc].load(ktile, sb * 32 * KTile::kRowBytes), qf[cc], acc);
     return acc;
+  }
+
+  // bits sb of the result: 32-key block sb of tile kt holds a key some row of this wave may see
+  __device__ __forceinline__ uint32_t visible_bits(int kt) const {
+    int nvis = (wave_lim_max - kt * KT + 31) >> 5;  // blocks of the tile that start below the wave's largest limit
+    nvis = nvis < 0 ? 0 : (nvis > NSB ? NSB : nvis);
+    return (1u << nvis) - 1u;
   }
 
   // key index (relative to the sub-block start) of accumulator element e of this lane
@@ -97,10 +106,9 @@ struct Slot {
 // double-buffered LDS ring and calls body(kt, tiles) on each; `tiles` points at
 // NSLOT consecutive tiles.  Bit s of TMASK says slot s is a transposed copy.
 // All threads of the workgroup must call this together.
-template <typename T, int D, int NSLOT, int TMASK, class Needed, class Body>
+template <typename C, typename T, int D, int NSLOT, int TMASK, class Needed, class Body>
 __device__ __forceinline__ void sweep_tiles(char* smem, const Slot* slots, int ntiles, int Nk, int tid, Needed needed,
                                             Body body) {
-  using C = QCtx<T, D>;
   constexpr int KT = C::KT;
   constexpr int TB = C::kTileBytes;
   using Tile0 = typename std::conditional<(TMASK & 1) != 0, typename C::XtTile, typename C::KTile>::type;
@@ -159,10 +167,26 @@ __device__ __forceinline__ void sweep_tiles(char* smem, const Slot* slots, int n
 // Per-wave bit sets over the 32-key blocks of a head, kept in LDS: bit jb of
 // wave w says the block can hold a non-zero probability for some row of the wave.
 struct WaveMask {
-  uint32_t* words;  // [kWaves][nwords]
+  uint32_t* words;  // [kWaves + 1][nwords]; row kWaves is the OR over the waves (see merge())
   int nwords;
-  __device__ __forceinline__ bool test(int w, int jb) const { return (words[w * nwords + (jb >> 5)] >> (jb & 31)) & 1u; }
   __device__ __forceinline__ void set(int w, int jb) { words[w * nwords + (jb >> 5)] |= (1u << (jb & 31)); }
+  // the NSB (<= 4, aligned) consecutive bits of row w that belong to key tile kt, as a wave-uniform scalar
+  template <int NSB>
+  __device__ __forceinline__ uint32_t tile_bits(int w, int kt) const {
+    int jb = kt * NSB;
+    uint32_t word = __builtin_amdgcn_readfirstlane(words[w * nwords + (jb >> 5)]);
+    return (word >> (jb & 31)) & ((1u << NSB) - 1u);
+  }
+  // all threads of the workgroup: row kWaves = OR of the wave rows; ends on a barrier
+  __device__ __forceinline__ void merge(int tid) {
+    __syncthreads();
+    for (int w = tid; w < nwords; w += kThreads) {
+      uint32_t v = 0u;
+      for (int k = 0; k < kWaves; ++k) v |= words[k * nwords + w];
+      words[kWaves * nwords + w] = v;
+    }
+    __syncthreads();
+  }
 };
 
 }  // namespace entmax

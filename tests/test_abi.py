@@ -67,8 +67,9 @@ def test_workspace_sizes(binding):
     assert fwd == 48 * 64 * 4096 * 2  # one transposed copy of V
     assert bwd > 3 * fwd
     assert b.workspace_bytes(_params(b, D=32), 0) == 0
-    # ragged lengths are padded to 64 rows in the transposed copies
+    # ragged lengths are padded to 128 rows in the transposed copies
     assert b.workspace_bytes(_params(b, B=1, H=1, Nq=65, Nk=65), 0) == 64 * 128 * 2
+    assert b.workspace_bytes(_params(b, B=1, H=1, Nq=129, Nk=129), 0) == 64 * 256 * 2
 
 
 def test_entry_points_reject_bad_arguments_before_any_launch(binding):

@@ -1,0 +1,91 @@
+"""Parity at the benchmark's full sizes, in the launch configuration bench.py times: the GPU runs the
+whole workload; the fp64 oracle recomputes a few whole heads (heads are independent, so a head of the
+full run is compared element by element with the oracle run on that head alone)."""
+import numpy as np
+import pytest
+
+from paper_2506_16640_amd import synth
+from tests.parity_util import TOL_GRAD, TOL_O, TOL_TAU, gpu_run, oracle_run, rel_err
+
+pytestmark = pytest.mark.gpu
+
+
+def _head_slice(data, b, h):
+    sub = {k: data[k][b:b + 1, h:h + 1] for k in ("Q", "K", "V", "dO") if k in data}
+    sub["beta"] = None if data["beta"] is None else data["beta"][h:h + 1]
+    sub["gamma"] = None if data["gamma"] is None else data["gamma"][h:h + 1]
+    sub["delta"] = data["delta"]
+    return sub
+
+
+def _check_heads(name, heads, alpha=None, bwd=None, seed=0):
+    data = synth.make_config(name, seed=seed)
+    cfg = data["cfg"]
+    alpha = cfg["alpha"] if alpha is None else alpha
+    bwd = cfg["bwd"] if bwd is None else bwd
+    g = gpu_run(data, alpha, cfg["dtype"], bwd=bwd, stats=True)
+    worst = {}
+    for (b, h) in heads:
+        r = oracle_run(_head_slice(data, b, h), alpha, bwd=bwd)
+        errs = {"tau": np.abs(g["tau"][b, h] - r["tau"][0, 0]).max(), "O": np.abs(g["O"][b, h] - r["O"][0, 0]).max()}
+        assert errs["tau"] <= TOL_TAU and errs["O"] <= TOL_O, (name, b, h, errs)
+        if bwd:
+            for t in ("dQ", "dK", "dV"):
+                errs[t] = rel_err(g[t][b, h], r[t][0, 0])
+                assert errs[t] <= TOL_GRAD, (name, b, h, t, errs)
+        for k, v in errs.items():
+            worst[k] = max(worst.get(k, 0.0), float(v))
+    print(name, alpha, "worst errors over heads", heads, worst)
+    return data, g
+
+
+def test_c2_full_forward():
+    data = synth.make_config("c2")
+    g = gpu_run(data, 1.5, "bf16", bwd=False)
+    r = oracle_run(data, 1.5, bwd=False)
+    assert np.abs(g["tau"] - r["tau"]).max() <= TOL_TAU
+    assert np.abs(g["O"] - r["O"]).max() <= TOL_O
+    assert np.abs(g["O"]).max() > 1.0
+
+
+def test_c3_headline_fwd_bwd_sampled_heads():
+    data, g = _check_heads("c3", [(0, 0), (1, 7), (3, 11)])
+    # per-head parameter gradients sum over the batch: oracle on all batches of one head
+    h = 4
+    sub = {k: data[k][:, h:h + 1] for k in ("Q", "K", "V", "dO")}
+    sub.update(beta=data["beta"][h:h + 1], gamma=data["gamma"][h:h + 1], delta=data["delta"])
+    r = oracle_run(sub, 1.5)
+    assert abs(g["dbeta"][h] - r["dbeta"][0]) <= TOL_GRAD * abs(r["dbeta"][0])
+    assert abs(g["dgamma"][h] - r["dgamma"][0]) <= TOL_GRAD * abs(r["dgamma"][0])
+    st = g["stats"]
+    assert st["fwd_pv_tiles"] <= st["fwd_qk_pv"] <= st["fwd_tiles_visible"]
+    assert st["bwd_active_tiles"] == st["bwd_dq_tiles"] == st["bwd_dkv_tiles"]
+
+
+def test_c3_dense_companion_sampled_heads():
+    _check_heads("c3d", [(0, 3), (2, 10)])
+
+
+def test_c4_long_context_forward_one_head_and_skip_rate():
+    from oracle import oracle
+    data = synth.make_config("c4")
+    g = gpu_run(data, 1.5, "bf16", bwd=False, stats=True)
+    h = 5
+    sub = _head_slice(data, 0, h)
+    r = oracle_run(sub, 1.5, bwd=False)
+    assert np.abs(g["tau"][0, h] - r["tau"][0, 0]).max() <= TOL_TAU
+    assert np.abs(g["O"][0, h] - r["O"][0, 0]).max() <= TOL_O
+    # tile-skip cross-check on that head: the kernel's executed P.V tiles against the oracle's block sparsity
+    gh = gpu_run(sub, 1.5, "bf16", bwd=False, stats=True)["stats"]
+    nz, vis = oracle.tile_map(sub["Q"], sub["K"], 1.5, 32, 32, sub["beta"], sub["gamma"], delta=sub["delta"])
+    assert gh["fwd_tiles_visible"] == int(vis.sum())
+    assert abs(gh["fwd_pv_tiles"] - int(nz.sum())) <= 1e-3 * int(nz.sum()) + 2
+    st = g["stats"]
+    skip = 1.0 - st["fwd_pv_tiles"] / st["fwd_tiles_visible"]
+    print("c4 tile-skip rate (32x32 tiles)", skip, "oracle head", 1.0 - nz.sum() / vis.sum())
+    assert skip > 0.5
+
+
+@pytest.mark.parametrize("alpha", [1.25, 1.5, 2.0])
+def test_c5_alpha_sweep_d128_sampled_heads(alpha):
+    _check_heads("c5", [(0, 2), (1, 13)], alpha=alpha)
