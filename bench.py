@@ -146,12 +146,13 @@ def main():
 
     F = tile_flops(d)
     algo = {
-        "fwd_main": F * (sd["fwd_qk_max"] + sd["fwd_qk_solve"] + sd["fwd_qk_pv"] + sd["fwd_pv_tiles"]),
+        "fwd_lists": F * sd["fwd_list_qk"],
+        "fwd_tiled": F * (sd["fwd_qk_max"] + sd["fwd_qk_solve"] + sd["fwd_qk_pv"] + sd["fwd_pv_tiles"]),
         "bwd_mask": F * sd["bwd_qk_mask"],
         "bwd_dq": F * 4 * sd["bwd_dq_tiles"],
         "bwd_dkv": F * 4 * sd["bwd_dkv_tiles"],
     }
-    kernel_ms = {"fwd_main": fwd_ms["main"]}
+    kernel_ms = {"fwd_lists": fwd_ms["lists"], "fwd_tiled": fwd_ms["tiled"]}
     if do_bwd:
         kernel_ms.update(bwd_mask=bwd_ms["mask"], bwd_dq=bwd_ms["dq"], bwd_dkv=bwd_ms["dkv"])
     dominant = max(kernel_ms, key=kernel_ms.get)
@@ -187,9 +188,13 @@ def main():
         "phase_ms": {"fwd": fwd_ms, "bwd": bwd_ms},
         "executed_tflops": total_exec / (sum(kernel_ms.values()) * 1e-3) / 1e12,
         "frac_bf16_mfma_peak_executed": total_exec / (sum(kernel_ms.values()) * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
-        "tile_skip_rate_fwd": 1.0 - sd["fwd_pv_tiles"] / vis,
-        "solve_sweeps_per_block": sd["fwd_solve_sweeps"] / max(sd["fwd_blocks"], 1),
-        "candidate_tile_fraction": sd["fwd_qk_pv"] / vis,
+        # tiles that can hold a non-zero probability: candidate tiles of the list kernel (an upper bound of the
+        # non-zero tiles) plus the P.V tiles the tiled kernel executed
+        "tile_skip_rate_fwd": 1.0 - (sd["fwd_cand_tiles"] + sd["fwd_pv_tiles"]) / vis,
+        "list_blocks_fraction": sd["fwd_sparse_blocks"] / max(B * H * ((n + 127) // 128), 1),
+        "support_per_row": sd["fwd_support"] / max(B * H * n, 1),
+        "candidates_per_row": sd["fwd_candidates"] / max(B * H * n, 1),
+        "solve_sweeps_per_tiled_block": sd["fwd_solve_sweeps"] / max(sd["fwd_blocks"], 1),
         "tile_stats": sd,
         "roofline": {"bound": "mfma", "kernel": dominant, "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None},
@@ -218,18 +223,20 @@ def main():
         torch.cuda.synchronize()
         tb = time.perf_counter()
         ms4 = (tb - ta) * 1e3 / k4
-        main4 = float(np.mean([hev.elapsed_ms(s[1], s[2]) for s in ev4]))
+        main4 = float(np.mean([hev.elapsed_ms(s[0], s[3]) for s in ev4]))
         F4 = tile_flops(cfg4["d"])
-        algo4 = F4 * (sd4["fwd_qk_max"] + sd4["fwd_qk_solve"] + sd4["fwd_qk_pv"] + sd4["fwd_pv_tiles"])
+        algo4 = F4 * (sd4["fwd_list_qk"] + sd4["fwd_qk_max"] + sd4["fwd_qk_solve"] + sd4["fwd_qk_pv"] + sd4["fwd_pv_tiles"])
         dense4 = synth.dense_equiv_flops(cfg4["B"], cfg4["H"], cfg4["n"], cfg4["d"], True, False)
         result["fwd_n32768"] = {
             "workload": "c4: B=1 H=12 n=32768 d=64 bf16 causal alpha=1.5 ASEntmax scale, 5% planted keys, fwd",
             "steps": k4, "ms": ms4, "dense_equiv_tflops": dense4 / (ms4 * 1e-3) / 1e12,
             "tokens_per_s": cfg4["B"] * cfg4["n"] / (ms4 * 1e-3),
-            "main_kernel_ms": main4, "executed_tflops": algo4 / (main4 * 1e-3) / 1e12,
+            "kernels_ms": main4, "executed_tflops": algo4 / (main4 * 1e-3) / 1e12,
             "frac_bf16_mfma_peak_executed": algo4 / (main4 * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
-            "tile_skip_rate": 1.0 - sd4["fwd_pv_tiles"] / max(sd4["fwd_tiles_visible"], 1),
-            "solve_sweeps_per_block": sd4["fwd_solve_sweeps"] / max(sd4["fwd_blocks"], 1),
+            "tile_skip_rate": 1.0 - (sd4["fwd_cand_tiles"] + sd4["fwd_pv_tiles"]) / max(sd4["fwd_tiles_visible"], 1),
+            "list_blocks_fraction": sd4["fwd_sparse_blocks"] / max(cfg4["B"] * cfg4["H"] * ((cfg4["n"] + 127) // 128), 1),
+            "support_per_row": sd4["fwd_support"] / max(cfg4["B"] * cfg4["H"] * cfg4["n"], 1),
+            "candidates_per_row": sd4["fwd_candidates"] / max(cfg4["B"] * cfg4["H"] * cfg4["n"], 1),
             "tile_stats": {k: v for k, v in sd4.items() if k.startswith("fwd")},
         }
     hev.close()

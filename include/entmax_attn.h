@@ -60,6 +60,8 @@ typedef struct {
   int32_t scale_layout;    /* 0: scale = delta; 1: beta,gamma per head [H]; 2: per query [B,H,Nq] */
   int32_t logn_mode;       /* n in (ln n)^gamma: 0 = Nk for every row, 1 = number of keys visible to the row.
                               A row with n <= 1 uses scale = delta and contributes no beta/gamma gradient. */
+  int32_t path;            /* forward path: 0 = automatic (candidate-list kernel first; workgroups that meet a row
+                              with too many candidates fall back to the tiled kernel), 1 = tiled kernel only */
   float alpha;             /* 1 < alpha <= 2; 1.5, 2.0 and 1.25 run on integer-power fast paths */
   float delta;             /* ASEntmax delta (1.0 in the paper's experiments) */
   int64_t q_stride_b, q_stride_h, q_stride_n;    /* strides of Q,O,dO,dQ in elements; all 0 = contiguous */
@@ -84,14 +86,24 @@ enum {
   ENTMAX_STAT_BWD_ACTIVE_TILES = 10, /* tiles with some p_ij > 0 */
   ENTMAX_STAT_BWD_DQ_TILES = 11,     /* tiles processed by the dQ / row-scalar kernel */
   ENTMAX_STAT_BWD_DKV_TILES = 12,    /* tiles processed by the dK / dV kernel */
-  ENTMAX_ATTN_NUM_STATS = 16
+  ENTMAX_STAT_FWD_CAND_TILES = 13,   /* candidate-list kernel: tiles holding at least one candidate key */
+  ENTMAX_STAT_FWD_CANDIDATES = 14,   /* candidate-list kernel: keys put on the lists */
+  ENTMAX_STAT_FWD_SUPPORT = 15,      /* candidate-list kernel: non-zero probabilities (exact support size, summed) */
+  ENTMAX_STAT_FWD_SPARSE_BLOCKS = 16, /* workgroups finished by the candidate-list kernel */
+  ENTMAX_STAT_FWD_LIST_QK = 17,      /* candidate-list kernel: score tiles computed (both sweeps) */
+  ENTMAX_ATTN_NUM_STATS = 24
 };
 
 /* Phases of one call, for the optional profiling hook `phase_events`: when not
  * NULL it is a HOST array of hipEvent_t handles (created by the caller) with
  * one more entry than the call has phases; entry 0 is recorded on the stream
  * before the first kernel and entry k after the last kernel of phase k-1. */
-enum { ENTMAX_FWD_PHASE_TRANSPOSE = 0, ENTMAX_FWD_PHASE_MAIN = 1, ENTMAX_FWD_NUM_PHASES = 2 };
+enum {
+  ENTMAX_FWD_PHASE_LISTS = 0,     /* candidate-list kernel (two Q K^T sweeps, threshold and output from the lists) */
+  ENTMAX_FWD_PHASE_TRANSPOSE = 1, /* V^T copy for the heads that need the tiled kernel */
+  ENTMAX_FWD_PHASE_TILED = 2,     /* tiled kernel on the workgroups the list kernel left over */
+  ENTMAX_FWD_NUM_PHASES = 3
+};
 enum {
   ENTMAX_BWD_PHASE_TRANSPOSE = 0,
   ENTMAX_BWD_PHASE_MASK = 1,
@@ -109,10 +121,13 @@ enum {
  *   stats: NULL or device uint64[ENTMAX_ATTN_NUM_STATS], added to.
  *   workspace: device scratch of at least entmax_attn_workspace_bytes(p, 0)
  *        bytes, 256-byte aligned; contents are undefined afterwards.
- * The row threshold is found by sweeps over the key tiles that recompute
+ * The row threshold is found from sweeps over the key tiles that recompute
  * Q K^T each time (row max, then safeguarded Newton/Halley steps on
  * f(tau) = sum_j [(alpha-1) s_ij - tau]_+^(1/(alpha-1)) - 1 inside the bracket of
- * App. A eq. (bounds)); the n x n score matrix is never stored.
+ * App. A eq. (bounds)); the n x n score matrix is never stored.  Rows with few
+ * candidates above a lower bound of tau are finished from a short per-row list
+ * after two sweeps; denser rows run the tile-wise iteration and P.V on the
+ * matrix cores with zero tiles skipped.
  */
 int entmax_attn_fwd(const entmax_attn_params* p, const void* Q, const void* K, const void* V, const float* beta,
                     const float* gamma, void* O, float* tau, uint64_t* stats, void* workspace,

@@ -19,15 +19,16 @@ if not os.path.exists(LIB_PATH):
 
 _lib = ctypes.CDLL(LIB_PATH)
 
-NUM_STATS = 16
+NUM_STATS = 24
 STAT_NAMES = {
     "fwd_tiles_visible": 0, "fwd_qk_max": 1, "fwd_qk_solve": 2, "fwd_qk_pv": 3, "fwd_pv_tiles": 4,
     "fwd_solve_sweeps": 5, "fwd_blocks": 6, "fwd_eval_tiles": 7,
     "bwd_tiles_visible": 8, "bwd_qk_mask": 9, "bwd_active_tiles": 10, "bwd_dq_tiles": 11, "bwd_dkv_tiles": 12,
+    "fwd_cand_tiles": 13, "fwd_candidates": 14, "fwd_support": 15, "fwd_sparse_blocks": 16, "fwd_list_qk": 17,
 }
-FWD_NUM_PHASES = 2
+FWD_NUM_PHASES = 3
 BWD_NUM_PHASES = 5
-FWD_PHASES = ("transpose", "main")
+FWD_PHASES = ("lists", "transpose", "tiled")
 BWD_PHASES = ("transpose", "mask", "dq", "dkv", "scale_grad")
 
 
@@ -35,7 +36,7 @@ class Params(ctypes.Structure):
     _fields_ = [
         ("B", ctypes.c_int32), ("H", ctypes.c_int32), ("Nq", ctypes.c_int32), ("Nk", ctypes.c_int32),
         ("D", ctypes.c_int32), ("dtype", ctypes.c_int32), ("causal", ctypes.c_int32),
-        ("scale_layout", ctypes.c_int32), ("logn_mode", ctypes.c_int32),
+        ("scale_layout", ctypes.c_int32), ("logn_mode", ctypes.c_int32), ("path", ctypes.c_int32),
         ("alpha", ctypes.c_float), ("delta", ctypes.c_float),
         ("q_stride_b", ctypes.c_int64), ("q_stride_h", ctypes.c_int64), ("q_stride_n", ctypes.c_int64),
         ("kv_stride_b", ctypes.c_int64), ("kv_stride_h", ctypes.c_int64), ("kv_stride_n", ctypes.c_int64),
@@ -70,7 +71,7 @@ def _ptr(t):
     return None if t is None else ctypes.c_void_p(t.data_ptr())
 
 
-def make_params(q, k, alpha, delta, causal, beta, logn_mode):
+def make_params(q, k, alpha, delta, causal, beta, logn_mode, path=0):
     B, H, Nq, D = q.shape
     Nk = k.shape[2]
     if q.dtype == torch.bfloat16:
@@ -80,7 +81,7 @@ def make_params(q, k, alpha, delta, causal, beta, logn_mode):
     else:
         raise TypeError("Q must be bfloat16 or float32")
     layout = 0 if beta is None else (1 if beta.dim() == 1 else 2)
-    p = Params(B, H, Nq, Nk, D, dt, int(bool(causal)), layout, int(logn_mode), float(alpha), float(delta),
+    p = Params(B, H, Nq, Nk, D, dt, int(bool(causal)), layout, int(logn_mode), int(path), float(alpha), float(delta),
                0, 0, 0, 0, 0, 0)
     if not q.is_contiguous():
         assert q.stride(3) == 1
@@ -111,12 +112,12 @@ def _stream():
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 
 
-def entmax_attn_fwd(q, k, v, alpha=1.5, beta=None, gamma=None, delta=1.0, causal=True, logn_mode=0,
+def entmax_attn_fwd(q, k, v, alpha=1.5, beta=None, gamma=None, delta=1.0, causal=True, logn_mode=0, path=0,
                     out=None, tau=None, stats=None, workspace=None, phase_events=None):
     """O, tau = entmax attention forward.  q [B,H,Nq,D], k,v [B,H,Nk,D] on the GPU, bf16 or fp32;
     beta,gamma fp32 [H] or [B,H,Nq] or None.  stats: optional uint64/int64 device tensor [16] (added to).
-    phase_events: optional list of 3 hipEvent_t handles (ints)."""
-    p = make_params(q, k, alpha, delta, causal, beta, logn_mode)
+    path: 0 automatic, 1 tiled kernel only.  phase_events: optional list of FWD_NUM_PHASES + 1 hipEvent_t handles."""
+    p = make_params(q, k, alpha, delta, causal, beta, logn_mode, path)
     assert v.shape == k.shape and v.stride() == k.stride()
     if out is None:
         out = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device)
@@ -135,10 +136,10 @@ def entmax_attn_fwd(q, k, v, alpha=1.5, beta=None, gamma=None, delta=1.0, causal
     return out, tau
 
 
-def entmax_attn_bwd(q, k, v, o, do, tau, alpha=1.5, beta=None, gamma=None, delta=1.0, causal=True, logn_mode=0,
+def entmax_attn_bwd(q, k, v, o, do, tau, alpha=1.5, beta=None, gamma=None, delta=1.0, causal=True, logn_mode=0, path=0,
                     stats=None, workspace=None, phase_events=None):
     """dQ, dK, dV, dbeta, dgamma = entmax attention backward (dbeta/dgamma None without scale parameters)."""
-    p = make_params(q, k, alpha, delta, causal, beta, logn_mode)
+    p = make_params(q, k, alpha, delta, causal, beta, logn_mode, path)
     assert v.stride() == k.stride() and do.stride() == q.stride()
     dq = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device)
     dk = torch.empty_strided(k.shape, k.stride(), dtype=k.dtype, device=k.device)

@@ -41,17 +41,21 @@ struct BwdArgs {
 
 // --------------------------------------------------------------- tile mask
 
+template <typename T>
+struct MaskTile {
+  static constexpr int value = sizeof(T) == 2 ? 128 : 32;
+};
+
 template <typename T, int D, int AM>
-__global__ __launch_bounds__(kThreads) void bwd_mask_kernel(BwdArgs A) {
-  extern __shared__ __attribute__((aligned(16))) char smem[];
-  using C = QCtx<T, D>;
+__device__ __forceinline__ void bwd_mask_block(const BwdArgs& A, int bh_, int blk_, char* smem) {
+  using C = QCtx<T, D, MaskTile<T>::value>;
   constexpr int KT = C::KT, NSB = C::NSB, TB = C::kTileBytes;
   const Geom& g = A.g;
   WaveMask wm;
   wm.words = reinterpret_cast<uint32_t*>(smem + 2 * TB);
   wm.nwords = A.mask_words;
   C q;
-  q.init(g, A.Q, xcd_remap(blockIdx.x, gridDim.x), A.nqb);
+  q.init(g, A.Q, bh_, blk_);
   for (int w = q.tid; w < kWaves * A.mask_words; w += kThreads) wm.words[w] = 0u;
   const float tau = q.valid ? A.tau[(long long)q.bh * g.Nq + q.i] : 0.f;
   const bool live = q.valid && q.lim > 0;
@@ -63,6 +67,27 @@ __global__ __launch_bounds__(kThreads) void bwd_mask_kernel(BwdArgs A) {
   sweep_tiles<C, T, D, 1, 0>(
       smem, slots, q.ntiles, g.Nk, q.tid, [](int) { return true; },
       [&](int kt, const char* tl) {
+#ifdef ENTMAX_EXP_NO_COMPUTE
+        n_vis += __builtin_popcount(q.visible_bits(kt));
+        return;
+#endif
+        if ((kt + 1) * KT <= q.wave_lim_min) {
+          // interior tile: every key is visible to every row of the wave
+          f32x16_t acc[NSB];
+#pragma unroll
+          for (int sb = 0; sb < NSB; ++sb) acc[sb] = q.scores(tl, sb);
+#pragma unroll
+          for (int sb = 0; sb < NSB; ++sb) {
+            float lm = max16(acc[sb]);
+            bool cand = live && (fmaf(lm, q.a, -tau) > 0.f);
+            if (__ballot(cand) != 0ull) {
+              ++n_act;
+              if (q.lane == 0) wm.set(q.wave, kt * NSB + sb);
+            }
+          }
+          n_vis += NSB;
+          return;
+        }
         const uint32_t act = q.visible_bits(kt);
         f32x16_t acc[NSB];
 #pragma unroll
@@ -102,8 +127,7 @@ __global__ __launch_bounds__(kThreads) void bwd_mask_kernel(BwdArgs A) {
 // ------------------------------------------------- row scalars, dscale and dQ
 
 template <typename T, int D, int AM>
-__global__ __launch_bounds__(kThreads) void bwd_dq_kernel(BwdArgs A) {
-  extern __shared__ __attribute__((aligned(16))) char smem[];
+__device__ __forceinline__ void bwd_dq_block(const BwdArgs& A, int bh_, int blk_, char* smem) {
   using C = QCtx<T, D>;
   constexpr int KT = C::KT, NSB = C::NSB, NC = C::NC, NM = C::NM, TB = C::kTileBytes;
   const Geom& g = A.g;
@@ -114,7 +138,7 @@ __global__ __launch_bounds__(kThreads) void bwd_dq_kernel(BwdArgs A) {
   float* xch = reinterpret_cast<float*>(wm.words + (kWaves + 1) * A.mask_words);  // [kWaves][64]
 
   C q;
-  q.init(g, A.Q, xcd_remap(blockIdx.x, gridDim.x), A.nqb);
+  q.init(g, A.Q, bh_, blk_);
   const float r = 1.0f / (g.alpha - 1.0f);
   const long long row_idx = (long long)q.bh * g.Nq + q.i;
   const float tau = q.valid ? A.tau[row_idx] : 0.f;
@@ -242,16 +266,14 @@ __global__ __launch_bounds__(kThreads) void bwd_dq_kernel(BwdArgs A) {
 // ------------------------------------------------------------------ dK, dV
 
 template <typename T, int D, int AM>
-__global__ __launch_bounds__(kThreads) void bwd_dkv_kernel(BwdArgs A) {
-  extern __shared__ __attribute__((aligned(16))) char smem[];
+__device__ __forceinline__ void bwd_dkv_block(const BwdArgs& A, int bh_, int blk_, char* smem) {
   using C = QCtx<T, D>;
   constexpr int QT = C::KT, NSG = C::NSB, NC = C::NC, NM = C::NM, TB = C::kTileBytes;
   const Geom& g = A.g;
   const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, li = lane & 31,
             hh = lane >> 5;
-  const int item = xcd_remap(blockIdx.x, gridDim.x);
-  const int bh = item / A.nkb, kb = item % A.nkb;
-  const int b = bh / g.H, h = bh % g.H;
+  const int bh = __builtin_amdgcn_readfirstlane(bh_), kb = __builtin_amdgcn_readfirstlane(blk_);
+  const int b = __builtin_amdgcn_readfirstlane(bh / g.H), h = __builtin_amdgcn_readfirstlane(bh % g.H);
   const float r = 1.0f / (g.alpha - 1.0f);
   const float am1 = g.alpha - 1.0f;
   const int off = g.Nk - g.Nq;
@@ -313,6 +335,10 @@ __global__ __launch_bounds__(kThreads) void bwd_dkv_kernel(BwdArgs A) {
   const char* dOtg = reinterpret_cast<const char*>(A.dOt) + (long long)bh * D * g.npad_q * (long long)sizeof(T);
   const long long qrow_bytes = g.q_sn * (long long)sizeof(T);
   const long long trow_bytes = (long long)g.npad_q * (long long)sizeof(T);
+  sq.init(qrow_bytes, tid);
+  sdo.init(qrow_bytes, tid);
+  sqt.init(trow_bytes, tid);
+  sdot.init(trow_bytes, tid);
 
   auto tile_needed = [&](int qt) {
     bool n = false;
@@ -328,10 +354,15 @@ __global__ __launch_bounds__(kThreads) void bwd_dkv_kernel(BwdArgs A) {
   };
   auto fetch = [&](int qt) {
     int rows_left = g.Nq - qt * QT;
-    sq.fetch(Qg + (long long)qt * QT * qrow_bytes, qrow_bytes, rows_left, tid);
-    sdo.fetch(dOg + (long long)qt * QT * qrow_bytes, qrow_bytes, rows_left, tid);
-    sqt.fetch(Qtg + (long long)qt * QT * (long long)sizeof(T), trow_bytes, D, tid);
-    sdot.fetch(dOtg + (long long)qt * QT * (long long)sizeof(T), trow_bytes, D, tid);
+    if (rows_left >= QT) {
+      sq.fetch_full(Qg + (long long)qt * QT * qrow_bytes);
+      sdo.fetch_full(dOg + (long long)qt * QT * qrow_bytes);
+    } else {
+      sq.fetch(Qg + (long long)qt * QT * qrow_bytes, rows_left);
+      sdo.fetch(dOg + (long long)qt * QT * qrow_bytes, rows_left);
+    }
+    sqt.fetch_full(Qtg + (long long)qt * QT * (long long)sizeof(T));
+    sdot.fetch_full(dOtg + (long long)qt * QT * (long long)sizeof(T));
     if (tid < QT) {
       int i = qt * QT + tid;
       if (i < g.Nq) {
@@ -348,10 +379,10 @@ __global__ __launch_bounds__(kThreads) void bwd_dkv_kernel(BwdArgs A) {
   };
   auto commit = [&](int bufi) {
     char* bf = tiles + bufi * 4 * TB;
-    sq.commit(bf, tid);
-    sdo.commit(bf + TB, tid);
-    sqt.commit(bf + 2 * TB, tid);
-    sdot.commit(bf + 3 * TB, tid);
+    sq.commit(bf);
+    sdo.commit(bf + TB);
+    sqt.commit(bf + 2 * TB);
+    sdot.commit(bf + 3 * TB);
     if (tid < QT) {
       float* rw = rows + bufi * 4 * QT;
       rw[tid] = rv[0];
@@ -447,6 +478,35 @@ __global__ __launch_bounds__(kThreads) void bwd_dkv_kernel(BwdArgs A) {
     }
   }
   if (A.stats && lane == 0) atomicAdd(&A.stats[ENTMAX_STAT_BWD_DKV_TILES], (unsigned long long)n_tiles);
+}
+
+#define ENTMAX_PAIRED_KERNEL(NAME, BLOCKFN, NBLK, OCC)                              \
+  template <typename T, int D, int AM>                                              \
+  __global__ __launch_bounds__(kThreads, OCC) void NAME(BwdArgs A) {                \
+    extern __shared__ __attribute__((aligned(16))) char smem[];                     \
+    const PairItem it = pair_item(NBLK);                                            \
+    for (int part = 0; part < 2; ++part) {                                          \
+      const int blk = part ? it.second : it.first;                                  \
+      if (blk < 0) break;                                                           \
+      if (part) __syncthreads();                                                    \
+      BLOCKFN<T, D, AM>(A, it.bh, blk, smem);                                       \
+    }                                                                               \
+  }
+ENTMAX_PAIRED_KERNEL(bwd_mask_kernel, bwd_mask_block, A.nqb, 3)
+#undef ENTMAX_PAIRED_KERNEL
+
+// The register-heavy kernels hold two workgroups per CU; one block per workgroup, long blocks first.
+template <typename T, int D, int AM>
+__global__ __launch_bounds__(kThreads) void bwd_dq_kernel(BwdArgs A) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const int item = xcd_remap(blockIdx.x, gridDim.x);
+  bwd_dq_block<T, D, AM>(A, item / A.nqb, A.nqb - 1 - item % A.nqb, smem);
+}
+template <typename T, int D, int AM>
+__global__ __launch_bounds__(kThreads) void bwd_dkv_kernel(BwdArgs A) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const int item = xcd_remap(blockIdx.x, gridDim.x);
+  bwd_dkv_block<T, D, AM>(A, item / A.nkb, item % A.nkb, smem);
 }
 
 // ------------------------------------------------------- d beta, d gamma

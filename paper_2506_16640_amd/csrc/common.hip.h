@@ -217,29 +217,46 @@ struct FragOff<float> {
   }
 };
 
-// Register staging for one tile: fetch() issues the global loads (rows at or
-// beyond valid_rows read as zero), commit() writes them to LDS.
+// Register staging for one tile: init() fixes, per thread, which 16-byte chunks
+// it moves (global byte offset inside the tile, swizzled LDS offset); fetch()
+// issues the global loads (rows at or beyond valid_rows read as zero),
+// fetch_full() does the same for a tile known to lie wholly inside the tensor,
+// commit() writes the staged chunks to LDS.
 template <typename TileT>
 struct Stage {
-  u32x4_t r[TileT::kPerThread];
-  __device__ __forceinline__ void fetch(const char* gbase, long long grow_bytes, int valid_rows, int tid) {
+  static_assert(TileT::kChunks % kThreads == 0, "tile must be a whole number of 4 KiB passes");
+  static constexpr int kPer = TileT::kChunks / kThreads;
+  u32x4_t r[kPer];
+  uint32_t goff[kPer];
+  int loff[kPer];
+  int row0;  // row of the first chunk; chunk `it` sits kThreads / kCpr rows further per step
+  __device__ __forceinline__ void init(long long grow_bytes, int tid) {
+    row0 = tid / TileT::kCpr;
+    int ch = tid % TileT::kCpr;
 #pragma unroll
-    for (int it = 0; it < TileT::kPerThread; ++it) {
-      int q = tid + it * kThreads;
-      int row = q / TileT::kCpr, ch = q % TileT::kCpr;
-      if (q < TileT::kChunks && row < valid_rows)
-        r[it] = *reinterpret_cast<const u32x4_t*>(gbase + (long long)row * grow_bytes + ch * 16);
+    for (int it = 0; it < kPer; ++it) {
+      int row = row0 + it * (kThreads / TileT::kCpr);
+      goff[it] = (uint32_t)row * (uint32_t)grow_bytes + (uint32_t)(ch * 16);
+      loff[it] = TileT::off(row, ch);
+    }
+  }
+  __device__ __forceinline__ void fetch_full(const char* gtile) {
+#pragma unroll
+    for (int it = 0; it < kPer; ++it) r[it] = *reinterpret_cast<const u32x4_t*>(gtile + goff[it]);
+  }
+  __device__ __forceinline__ void fetch(const char* gtile, int valid_rows) {
+#pragma unroll
+    for (int it = 0; it < kPer; ++it) {
+      int row = row0 + it * (kThreads / TileT::kCpr);
+      if (row < valid_rows)
+        r[it] = *reinterpret_cast<const u32x4_t*>(gtile + goff[it]);
       else
         r[it] = u32x4_t{0u, 0u, 0u, 0u};
     }
   }
-  __device__ __forceinline__ void commit(char* tile, int tid) const {
+  __device__ __forceinline__ void commit(char* tile) const {
 #pragma unroll
-    for (int it = 0; it < TileT::kPerThread; ++it) {
-      int q = tid + it * kThreads;
-      int row = q / TileT::kCpr, ch = q % TileT::kCpr;
-      if (q < TileT::kChunks) *reinterpret_cast<u32x4_t*>(tile + TileT::off(row, ch)) = r[it];
-    }
+    for (int it = 0; it < kPer; ++it) *reinterpret_cast<u32x4_t*>(tile + loff[it]) = r[it];
   }
 };
 

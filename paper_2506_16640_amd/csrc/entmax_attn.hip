@@ -8,6 +8,7 @@
 
 #include "bwd.hip.h"
 #include "fwd.hip.h"
+#include "fwd_sparse.hip.h"
 #include "transpose.hip.h"
 
 using namespace entmax;
@@ -26,7 +27,7 @@ struct Layout {
   int mask_words;     // uint32 words covering the 32-key blocks of a head
   long long q_sb, q_sh, q_sn, kv_sb, kv_sh, kv_sn;
   // workspace offsets
-  size_t off_vt, off_kt, off_qt, off_dot, off_mu, off_crow, off_dscale, off_mask, total_fwd, total_bwd;
+  size_t off_vt, off_cand, off_flags, off_kt, off_qt, off_dot, off_mu, off_crow, off_dscale, off_mask, total_fwd, total_bwd;
 };
 
 int check(const entmax_attn_params* p) {
@@ -36,10 +37,11 @@ int check(const entmax_attn_params* p) {
   if (p->causal != 0 && p->causal != 1) return ENTMAX_ATTN_INVALID_ARG;
   if (p->scale_layout < 0 || p->scale_layout > 2) return ENTMAX_ATTN_INVALID_ARG;
   if (p->logn_mode != 0 && p->logn_mode != 1) return ENTMAX_ATTN_INVALID_ARG;
+  if (p->path != 0 && p->path != 1) return ENTMAX_ATTN_INVALID_ARG;
   if (!(p->alpha > 1.0f) || !(p->alpha <= 2.0f)) return ENTMAX_ATTN_INVALID_ARG;
   if (!isfinite(p->delta)) return ENTMAX_ATTN_INVALID_ARG;
   if (p->D != 64 && p->D != 128) return ENTMAX_ATTN_UNSUPPORTED_SHAPE;
-  if (p->Nq > (1 << 24) || p->Nk > (1 << 24)) return ENTMAX_ATTN_UNSUPPORTED_SHAPE;
+  if (p->Nq > (1 << 22) || p->Nk > (1 << 22)) return ENTMAX_ATTN_UNSUPPORTED_SHAPE;  // 32-bit offsets inside a tile
   long long bh = (long long)p->B * p->H;
   if (bh * (long long)ceil_div(p->Nq > p->Nk ? p->Nq : p->Nk, 32) > 0x7fffffffLL) return ENTMAX_ATTN_UNSUPPORTED_SHAPE;
   if (bh > 65535) return ENTMAX_ATTN_UNSUPPORTED_SHAPE;
@@ -50,6 +52,7 @@ int check(const entmax_attn_params* p) {
     if (s[k] < 0) return ENTMAX_ATTN_INVALID_ARG;
     if ((s[k] * (int64_t)es) % 16 != 0) return ENTMAX_ATTN_MISALIGNED;
   }
+  if (s[2] * (int64_t)es > (1 << 24) || s[5] * (int64_t)es > (1 << 24)) return ENTMAX_ATTN_UNSUPPORTED_SHAPE;
   if (!q_zero && s[2] < p->D) return ENTMAX_ATTN_INVALID_ARG;
   if (!kv_zero && s[5] < p->D) return ENTMAX_ATTN_INVALID_ARG;
   return ENTMAX_ATTN_OK;
@@ -78,8 +81,12 @@ Layout make_layout(const entmax_attn_params* p) {
   size_t qt_bytes = align_up(bh * p->D * (size_t)L.npad_q * L.esize);
   size_t row_bytes = align_up(bh * (size_t)p->Nq * sizeof(float));
   size_t mask_bytes = align_up(bh * (size_t)L.nqg * L.mask_words * sizeof(uint32_t));
+  // forward: V^T copy | candidate lists | per-workgroup and per-head fallback flags
   L.off_vt = 0;
-  L.total_fwd = kt_bytes;
+  L.off_cand = kt_bytes;
+  size_t cand_bytes = align_up(bh * (size_t)p->Nq * 2 * kCandCap * sizeof(uint2));
+  L.off_flags = L.off_cand + cand_bytes;
+  L.total_fwd = L.off_flags + align_up((bh * (size_t)L.nqb + bh) * sizeof(int));
   size_t o = 0;
   L.off_kt = o;
   o += kt_bytes;
@@ -168,11 +175,11 @@ bool zero_words(void* p, size_t bytes, hipStream_t st) {
 
 template <typename T, int D>
 bool launch_transpose(const void* X, long long sb, long long sh, long long sn, int B, int H, int N, int npad, void* Xt,
-                      hipStream_t st) {
+                      hipStream_t st, const int* head_flag = nullptr) {
   if (npad == 0) return true;
   dim3 grid((unsigned)(npad / 64), (unsigned)(B * H));
   hipLaunchKernelGGL((transpose_perm_kernel<T, D>), grid, dim3(kThreads), 0, st, reinterpret_cast<const T*>(X), sb, sh,
-                     sn, H, N, npad, reinterpret_cast<T*>(Xt));
+                     sn, H, N, npad, reinterpret_cast<T*>(Xt), head_flag);
   return launch_ok();
 }
 
@@ -197,6 +204,23 @@ bool launch_fwd_am(const FwdArgs& a, int am, int nblocks, hipStream_t st) {
   }
 }
 
+template <typename T, int D, int AM>
+bool launch_fwd_sparse(const FwdSparseArgs& a, int nblocks, hipStream_t st) {
+  size_t smem = 2 * (size_t)QCtx<T, D, FwdTile<T>::value>::kTileBytes + 64;
+  hipLaunchKernelGGL((fwd_sparse_kernel<T, D, AM>), dim3((unsigned)nblocks), dim3(kThreads), smem, st, a);
+  return launch_ok();
+}
+
+template <typename T, int D>
+bool launch_fwd_sparse_am(const FwdSparseArgs& a, int am, int nblocks, hipStream_t st) {
+  switch (am) {
+    case 1: return launch_fwd_sparse<T, D, 1>(a, nblocks, st);
+    case 2: return launch_fwd_sparse<T, D, 2>(a, nblocks, st);
+    case 3: return launch_fwd_sparse<T, D, 3>(a, nblocks, st);
+    default: return launch_fwd_sparse<T, D, 0>(a, nblocks, st);
+  }
+}
+
 template <typename T, int D>
 int run_fwd(const entmax_attn_params* p, const Layout& L, const void* Q, const void* K, const void* V,
             const float* beta, const float* gamma, void* O, float* tau, uint64_t* stats, char* ws, hipStream_t st,
@@ -207,12 +231,35 @@ int run_fwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
               zero_words(tau, (size_t)p->B * p->H * p->Nq * 4, st);
     record(ev, 1, st);
     record(ev, 2, st);
+    record(ev, 3, st);
     return ok ? ENTMAX_ATTN_OK : ENTMAX_ATTN_LAUNCH_FAILED;
   }
   void* Vt = ws + L.off_vt;
-  if (!launch_transpose<T, D>(V, L.kv_sb, L.kv_sh, L.kv_sn, p->B, p->H, p->Nk, L.npad_k, Vt, st))
-    return ENTMAX_ATTN_LAUNCH_FAILED;
+  int* dense_flag = reinterpret_cast<int*>(ws + L.off_flags);
+  int* head_flag = dense_flag + (size_t)p->B * p->H * L.nqb;
+  const int nblocks = p->B * p->H * ((L.nqb + 1) / 2);  // workgroups take query blocks in pairs
+  const bool lists = p->path == 0;
+  if (lists) {
+    if (!zero_words(head_flag, (size_t)p->B * p->H * sizeof(int), st)) return ENTMAX_ATTN_LAUNCH_FAILED;
+    FwdSparseArgs sa;
+    sa.g = make_geom(p, L, beta, gamma);
+    sa.Q = Q;
+    sa.K = K;
+    sa.V = V;
+    sa.O = O;
+    sa.tau = tau;
+    sa.cand = reinterpret_cast<uint2*>(ws + L.off_cand);
+    sa.dense_flag = dense_flag;
+    sa.head_flag = head_flag;
+    sa.stats = reinterpret_cast<unsigned long long*>(stats);
+    sa.nqb = L.nqb;
+    if (!launch_fwd_sparse_am<T, D>(sa, alpha_mode(p->alpha), nblocks, st)) return ENTMAX_ATTN_LAUNCH_FAILED;
+  }
   record(ev, 1, st);
+  if (!launch_transpose<T, D>(V, L.kv_sb, L.kv_sh, L.kv_sn, p->B, p->H, p->Nk, L.npad_k, Vt, st,
+                              lists ? head_flag : nullptr))
+    return ENTMAX_ATTN_LAUNCH_FAILED;
+  record(ev, 2, st);
   FwdArgs a;
   a.g = make_geom(p, L, beta, gamma);
   a.Q = Q;
@@ -223,14 +270,15 @@ int run_fwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
   a.stats = reinterpret_cast<unsigned long long*>(stats);
   a.nqb = L.nqb;
   a.mask_words = L.mask_words;
-  if (!launch_fwd_am<T, D>(a, alpha_mode(p->alpha), p->B * p->H * L.nqb, st)) return ENTMAX_ATTN_LAUNCH_FAILED;
-  record(ev, 2, st);
+  a.dense_flag = lists ? dense_flag : nullptr;
+  if (!launch_fwd_am<T, D>(a, alpha_mode(p->alpha), nblocks, st)) return ENTMAX_ATTN_LAUNCH_FAILED;
+  record(ev, 3, st);
   return ENTMAX_ATTN_OK;
 }
 
 template <typename T, int D, int AM>
 bool launch_bwd_kernels(const BwdArgs& a, const Layout& L, int B, int H, hipStream_t st, void* const* ev) {
-  size_t smem_mask = 2 * (size_t)QCtx<T, D>::kTileBytes + (size_t)(kWaves + 1) * a.mask_words * 4 + 64;
+  size_t smem_mask = 2 * (size_t)QCtx<T, D, MaskTile<T>::value>::kTileBytes + (size_t)(kWaves + 1) * a.mask_words * 4 + 64;
   size_t smem_dq = 6 * (size_t)QCtx<T, D>::kTileBytes + (size_t)(kWaves + 1) * a.mask_words * 4 + kWaves * 64 * 4 + 64;
   size_t smem_dkv = 8 * (size_t)QCtx<T, D>::kTileBytes + 2 * 4 * (size_t)QCtx<T, D>::KT * 4 + (size_t)a.nqg + 64;
   auto k_mask = bwd_mask_kernel<T, D, AM>;
@@ -242,7 +290,7 @@ bool launch_bwd_kernels(const BwdArgs& a, const Layout& L, int B, int H, hipStre
   if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_dkv), hipFuncAttributeMaxDynamicSharedMemorySize,
                           (int)smem_dkv) != hipSuccess)
     return false;
-  hipLaunchKernelGGL(k_mask, dim3((unsigned)(B * H * L.nqb)), dim3(kThreads), smem_mask, st, a);
+  hipLaunchKernelGGL(k_mask, dim3((unsigned)(B * H * ((L.nqb + 1) / 2))), dim3(kThreads), smem_mask, st, a);
   if (!launch_ok()) return false;
   record(ev, 2, st);
   hipLaunchKernelGGL(k_dq, dim3((unsigned)(B * H * L.nqb)), dim3(kThreads), smem_dq, st, a);

@@ -40,30 +40,28 @@ struct QCtx {
   Frag<T> qf[NC];     // the row's query fragments (negated when scale_i < 0 so that a >= 0)
   FragOff<T> koff[NC];  // lane offsets of the K-tile fragments of row (l%32)
 
-  __device__ __forceinline__ void init(const Geom& g, const void* Q, int work_item, int nqb) {
+  __device__ __forceinline__ void init(const Geom& g, const void* Q, int bh_, int qb_) {
     tid = threadIdx.x;
     wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps everything derived from it scalar
     lane = tid & 63;
     li = lane & 31;
     hh = lane >> 5;
-    bh = work_item / nqb;
-    qb = nqb - 1 - (work_item % nqb);  // long (late) query blocks first: they carry the most causal work
-    b = bh / g.H;
-    h = bh % g.H;
-    q0 = qb * kBlockRows + wave * 32;
+    // blockIdx-derived values are uniform; readfirstlane pins them (and everything computed from
+    // them) to SGPRs even where the compiler merges them with per-lane code
+    auto uni = [](int v) { return __builtin_amdgcn_readfirstlane(v); };
+    bh = uni(bh_);
+    qb = uni(qb_);
+    b = uni(bh / g.H);
+    h = uni(bh % g.H);
+    q0 = uni(qb * kBlockRows + wave * 32);
     i = q0 + li;
     valid = i < g.Nq;
     lim = valid ? row_limit(g, i) : 0;
     int last_blk = min(g.Nq, (qb + 1) * kBlockRows) - 1;
-    block_lim = row_limit(g, last_blk);
-    ntiles = (block_lim + KT - 1) / KT;
-    if (q0 < g.Nq) {
-      wave_lim_min = row_limit(g, q0);
-      wave_lim_max = row_limit(g, min(g.Nq, q0 + 32) - 1);
-    } else {
-      wave_lim_min = 0;
-      wave_lim_max = 0;
-    }
+    block_lim = uni(row_limit(g, last_blk));
+    ntiles = uni((block_lim + KT - 1) / KT);
+    wave_lim_min = uni(q0 < g.Nq ? row_limit(g, q0) : 0);
+    wave_lim_max = uni(q0 < g.Nq ? row_limit(g, min(g.Nq, q0 + 32) - 1) : 0);
     float scale = valid ? row_scale(g, b, h, i, lim, nullptr, nullptr, nullptr) : 0.f;
     float inv_sqrt_d = 1.0f / sqrtf((float)D);
     c = scale * inv_sqrt_d;
@@ -97,6 +95,23 @@ struct QCtx {
   __device__ __forceinline__ int key_of(int e) const { return 8 * (e >> 2) + 4 * hh + (e & 3); }
 };
 
+// Causal work grows linearly with the block index, so a workgroup takes block (n-1-p) and then
+// block p of the same head: every workgroup of a launch carries the same amount of work, whatever
+// order the hardware starts them in.  `second` is -1 when the pair is the middle block alone.
+struct PairItem {
+  int bh, first, second;
+};
+__device__ __forceinline__ PairItem pair_item(int nblk) {
+  const int npair = (nblk + 1) >> 1;
+  const int item = xcd_remap(blockIdx.x, gridDim.x);
+  PairItem it;
+  it.bh = __builtin_amdgcn_readfirstlane(item / npair);
+  const int pp = __builtin_amdgcn_readfirstlane(item % npair);
+  it.first = nblk - 1 - pp;
+  it.second = (pp == it.first) ? -1 : pp;
+  return it;
+}
+
 struct Slot {
   const char* base;     // tensor of this (batch, head): natural [N][row], transposed [D][npad]
   long long row_bytes;  // bytes between consecutive rows in global memory
@@ -106,9 +121,16 @@ struct Slot {
 // double-buffered LDS ring and calls body(kt, tiles) on each; `tiles` points at
 // NSLOT consecutive tiles.  Bit s of TMASK says slot s is a transposed copy.
 // All threads of the workgroup must call this together.
-template <typename C, typename T, int D, int NSLOT, int TMASK, class Needed, class Body>
+struct NeverAbort {
+  __device__ __forceinline__ bool operator()(int) const { return false; }
+};
+
+// abort(kt), evaluated by every thread at the start of the iteration that processes tile kt, may end
+// the sweep after that tile.  It must be workgroup-uniform: it may only read state that was complete
+// before the barrier that ended the previous iteration.
+template <typename C, typename T, int D, int NSLOT, int TMASK, class Needed, class Body, class Abort = NeverAbort>
 __device__ __forceinline__ void sweep_tiles(char* smem, const Slot* slots, int ntiles, int Nk, int tid, Needed needed,
-                                            Body body) {
+                                            Body body, Abort abort = Abort()) {
   constexpr int KT = C::KT;
   constexpr int TB = C::kTileBytes;
   using Tile0 = typename std::conditional<(TMASK & 1) != 0, typename C::XtTile, typename C::KTile>::type;
@@ -117,29 +139,41 @@ __device__ __forceinline__ void sweep_tiles(char* smem, const Slot* slots, int n
   Stage<Tile0> s0;
   Stage<Tile1> s1;
   Stage<Tile2> s2;
+  s0.init(slots[0].row_bytes, tid);
+  if constexpr (NSLOT > 1) s1.init(slots[1].row_bytes, tid);
+  if constexpr (NSLOT > 2) s2.init(slots[2].row_bytes, tid);
 
+  // tile kt of slot s starts at: natural copy -> row kt*KT; transposed copy -> column kt*KT
+  auto tile_ptr = [&](int s, bool tr, int kt) {
+    return slots[s].base + (tr ? (long long)kt * KT * (long long)sizeof(T) : (long long)kt * KT * slots[s].row_bytes);
+  };
   auto fetch = [&](int kt) {
-    int rows_left = Nk - kt * KT;
-    {
-      bool tr = (TMASK & 1) != 0;
-      const char* gb = slots[0].base + (tr ? (long long)kt * KT * (long long)sizeof(T) : (long long)kt * KT * slots[0].row_bytes);
-      s0.fetch(gb, slots[0].row_bytes, tr ? D : rows_left, tid);
+    const int rows_left = Nk - kt * KT;
+    const bool full = rows_left >= KT;  // uniform
+    if constexpr ((TMASK & 1) != 0) {
+      s0.fetch_full(tile_ptr(0, true, kt));
+    } else {
+      if (full) s0.fetch_full(tile_ptr(0, false, kt)); else s0.fetch(tile_ptr(0, false, kt), rows_left);
     }
     if constexpr (NSLOT > 1) {
-      bool tr = (TMASK & 2) != 0;
-      const char* gb = slots[1].base + (tr ? (long long)kt * KT * (long long)sizeof(T) : (long long)kt * KT * slots[1].row_bytes);
-      s1.fetch(gb, slots[1].row_bytes, tr ? D : rows_left, tid);
+      if constexpr ((TMASK & 2) != 0) {
+        s1.fetch_full(tile_ptr(1, true, kt));
+      } else {
+        if (full) s1.fetch_full(tile_ptr(1, false, kt)); else s1.fetch(tile_ptr(1, false, kt), rows_left);
+      }
     }
     if constexpr (NSLOT > 2) {
-      bool tr = (TMASK & 4) != 0;
-      const char* gb = slots[2].base + (tr ? (long long)kt * KT * (long long)sizeof(T) : (long long)kt * KT * slots[2].row_bytes);
-      s2.fetch(gb, slots[2].row_bytes, tr ? D : rows_left, tid);
+      if constexpr ((TMASK & 4) != 0) {
+        s2.fetch_full(tile_ptr(2, true, kt));
+      } else {
+        if (full) s2.fetch_full(tile_ptr(2, false, kt)); else s2.fetch(tile_ptr(2, false, kt), rows_left);
+      }
     }
   };
   auto commit = [&](char* buf) {
-    s0.commit(buf, tid);
-    if constexpr (NSLOT > 1) s1.commit(buf + TB, tid);
-    if constexpr (NSLOT > 2) s2.commit(buf + 2 * TB, tid);
+    s0.commit(buf);
+    if constexpr (NSLOT > 1) s1.commit(buf + TB);
+    if constexpr (NSLOT > 2) s2.commit(buf + 2 * TB);
   };
   auto next_needed = [&](int kt) {
     while (kt < ntiles && !needed(kt)) ++kt;
@@ -154,11 +188,15 @@ __device__ __forceinline__ void sweep_tiles(char* smem, const Slot* slots, int n
   __syncthreads();
   int cur = 0;
   while (kt < ntiles) {
-    int nxt = next_needed(kt + 1);
+    int nxt = abort(kt) ? ntiles : next_needed(kt + 1);
+#ifdef ENTMAX_EXP_NO_LOADS
+    body(kt, smem + cur * (NSLOT * TB));
+#else
     if (nxt < ntiles) fetch(nxt);
     body(kt, smem + cur * (NSLOT * TB));
     if (nxt < ntiles) commit(smem + (cur ^ 1) * (NSLOT * TB));
     __syncthreads();
+#endif
     cur ^= 1;
     kt = nxt;
   }

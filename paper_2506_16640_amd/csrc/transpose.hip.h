@@ -14,11 +14,12 @@ namespace entmax {
 template <typename T, int D>
 __global__ __launch_bounds__(kThreads) void transpose_perm_kernel(const T* __restrict__ X, long long sb, long long sh,
                                                                   long long sn, int H, int N, int npad,
-                                                                  T* __restrict__ Xt) {
+                                                                  T* __restrict__ Xt, const int* head_flag) {
   constexpr int kPad = sizeof(T) == 2 ? 2 : 1;
   __shared__ T tile[64][D + kPad];
   const int tid = threadIdx.x;
   const int bh = blockIdx.y, b = bh / H, h = bh % H;
+  if (head_flag && head_flag[bh] == 0) return;  // no consumer for this head's copy
   const int j0 = blockIdx.x * 64;
   const T* src = X + (long long)b * sb + (long long)h * sh;
   for (int e = tid; e < 64 * D; e += kThreads) {

@@ -6,6 +6,7 @@ import torch
 TOL_O = 2e-2      # max-abs on outputs
 TOL_TAU = 1e-3    # max-abs on the threshold
 TOL_GRAD = 5e-2   # max|diff| / max|ref| per gradient tensor
+DEFAULT_PATH = 0   # forward path the tests run when they do not say: 0 automatic, 1 tiled kernel only
 
 
 def to_dev(x, dtype):
@@ -15,15 +16,17 @@ def to_dev(x, dtype):
     return t.to(torch.bfloat16) if dtype == "bf16" else t.float()
 
 
-def gpu_run(data, alpha, dtype, causal=True, logn_mode=0, bwd=True, stats=False, layout_bnhd=False):
+def gpu_run(data, alpha, dtype, causal=True, logn_mode=0, bwd=True, stats=False, layout_bnhd=False, path=None):
     from paper_2506_16640_amd import binding
+    path = DEFAULT_PATH if path is None else path
     q, k, v = (to_dev(data[n], dtype) for n in ("Q", "K", "V"))
     if layout_bnhd:  # same values, [B,n,H,D] memory order viewed as [B,H,n,D]
         q, k, v = (t.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3) for t in (q, k, v))
     beta = None if data["beta"] is None else torch.from_numpy(data["beta"]).float().cuda()
     gamma = None if data["gamma"] is None else torch.from_numpy(data["gamma"]).float().cuda()
     st = binding.new_stats() if stats else None
-    kw = dict(alpha=alpha, beta=beta, gamma=gamma, delta=data["delta"], causal=causal, logn_mode=logn_mode, stats=st)
+    kw = dict(alpha=alpha, beta=beta, gamma=gamma, delta=data["delta"], causal=causal, logn_mode=logn_mode, stats=st,
+              path=path)
     o, tau = binding.entmax_attn_fwd(q, k, v, **kw)
     out = {"O": o.float().cpu().numpy().astype(np.float64), "tau": tau.cpu().numpy().astype(np.float64)}
     if bwd:

@@ -32,7 +32,8 @@ def test_exports_every_declared_symbol(binding):
 
 
 def _params(b, **kw):
-    base = dict(B=2, H=3, Nq=100, Nk=100, D=64, dtype=0, causal=1, scale_layout=1, logn_mode=0, alpha=1.5, delta=1.0)
+    base = dict(B=2, H=3, Nq=100, Nk=100, D=64, dtype=0, causal=1, scale_layout=1, logn_mode=0, path=0, alpha=1.5,
+                delta=1.0)
     base.update(kw)
     p = b.Params()
     for k, v in base.items():
@@ -52,10 +53,11 @@ def test_parameter_validation(binding):
     assert b.check_params(_params(b, causal=2)) == -1
     assert b.check_params(_params(b, scale_layout=5)) == -1
     assert b.check_params(_params(b, Nq=-1)) == -1
+    assert b.check_params(_params(b, path=2)) == -1
     assert b.check_params(_params(b, q_stride_b=64 * 100 * 3, q_stride_h=64, q_stride_n=3 * 64)) == 0
     assert b.check_params(_params(b, q_stride_b=6400, q_stride_h=6400, q_stride_n=65)) == -3  # 130 bytes: misaligned
     assert b.check_params(_params(b, q_stride_b=6400, q_stride_h=6400, q_stride_n=32)) == -1  # rows overlap
-    assert b.check_params(_params(b, Nq=1 << 25)) == -2
+    assert b.check_params(_params(b, Nq=1 << 23)) == -2
     for code in (0, -1, -2, -3, -4, -5, -99):
         assert isinstance(b.strerror(code), str) and b.strerror(code)
 
@@ -64,12 +66,12 @@ def test_workspace_sizes(binding):
     b = binding
     p = _params(b, B=4, H=12, Nq=4096, Nk=4096)
     fwd, bwd = b.workspace_bytes(p, 0), b.workspace_bytes(p, 1)
-    assert fwd == 48 * 64 * 4096 * 2  # one transposed copy of V
-    assert bwd > 3 * fwd
+    assert fwd >= 48 * 64 * 4096 * 2  # one transposed copy of V plus candidate lists and flags
+    assert bwd > 3 * 48 * 64 * 4096 * 2
     assert b.workspace_bytes(_params(b, D=32), 0) == 0
     # ragged lengths are padded to 128 rows in the transposed copies
-    assert b.workspace_bytes(_params(b, B=1, H=1, Nq=65, Nk=65), 0) == 64 * 128 * 2
-    assert b.workspace_bytes(_params(b, B=1, H=1, Nq=129, Nk=129), 0) == 64 * 256 * 2
+    small = b.workspace_bytes(_params(b, B=1, H=1, Nq=65, Nk=65), 0)
+    assert small >= 64 * 128 * 2 and b.workspace_bytes(_params(b, B=1, H=1, Nq=65, Nk=129), 0) - small == 64 * 128 * 2
 
 
 def test_entry_points_reject_bad_arguments_before_any_launch(binding):

@@ -58,7 +58,7 @@ def test_c3_headline_fwd_bwd_sampled_heads():
     assert abs(g["dbeta"][h] - r["dbeta"][0]) <= TOL_GRAD * abs(r["dbeta"][0])
     assert abs(g["dgamma"][h] - r["dgamma"][0]) <= TOL_GRAD * abs(r["dgamma"][0])
     st = g["stats"]
-    assert st["fwd_pv_tiles"] <= st["fwd_qk_pv"] <= st["fwd_tiles_visible"]
+    assert st["fwd_sparse_blocks"] > 0.9 * 4 * 12 * 32  # the headline workload is sparse: the list kernel finishes it
     assert st["bwd_active_tiles"] == st["bwd_dq_tiles"] == st["bwd_dkv_tiles"]
 
 
@@ -76,12 +76,19 @@ def test_c4_long_context_forward_one_head_and_skip_rate():
     assert np.abs(g["tau"][0, h] - r["tau"][0, 0]).max() <= TOL_TAU
     assert np.abs(g["O"][0, h] - r["O"][0, 0]).max() <= TOL_O
     # tile-skip cross-check on that head: the kernel's executed P.V tiles against the oracle's block sparsity
-    gh = gpu_run(sub, 1.5, "bf16", bwd=False, stats=True)["stats"]
     nz, vis = oracle.tile_map(sub["Q"], sub["K"], 1.5, 32, 32, sub["beta"], sub["gamma"], delta=sub["delta"])
-    assert gh["fwd_tiles_visible"] == int(vis.sum())
-    assert abs(gh["fwd_pv_tiles"] - int(nz.sum())) <= 1e-3 * int(nz.sum()) + 2
+    # tiled kernel alone: the P.V tiles it executes are exactly the oracle's non-zero tiles
+    gt = gpu_run(sub, 1.5, "bf16", bwd=False, stats=True, path=1)["stats"]
+    assert gt["fwd_tiles_visible"] == int(vis.sum())
+    assert abs(gt["fwd_pv_tiles"] - int(nz.sum())) <= 1e-3 * int(nz.sum()) + 2
+    # list kernel: its candidate tiles cover the non-zero tiles, and its support count is the oracle's
+    gl = gpu_run(sub, 1.5, "bf16", bwd=False, stats=True, path=0)["stats"]
+    assert gl["fwd_tiles_visible"] == int(vis.sum())
+    if gl["fwd_sparse_blocks"] == 32768 // 128:
+        assert gl["fwd_cand_tiles"] >= int(nz.sum())
+        assert abs(gl["fwd_support"] - int(r["support"].sum())) <= 1e-3 * int(r["support"].sum()) + 2
     st = g["stats"]
-    skip = 1.0 - st["fwd_pv_tiles"] / st["fwd_tiles_visible"]
+    skip = 1.0 - (st["fwd_cand_tiles"] + st["fwd_pv_tiles"]) / st["fwd_tiles_visible"]
     print("c4 tile-skip rate (32x32 tiles)", skip, "oracle head", 1.0 - nz.sum() / vis.sum())
     assert skip > 0.5
 

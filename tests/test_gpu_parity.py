@@ -12,6 +12,16 @@ from tests.parity_util import compare, gpu_run, oracle_run
 pytestmark = pytest.mark.gpu
 
 
+@pytest.fixture(autouse=True, params=[0, 1], ids=["auto", "tiled"])
+def forward_path(request):
+    """Every case runs twice: with the automatic forward path (candidate-list kernel, tiled fallback)
+    and with the tiled kernel alone."""
+    from tests import parity_util
+    parity_util.DEFAULT_PATH = request.param
+    yield request.param
+    parity_util.DEFAULT_PATH = 0
+
+
 def _case(B, H, nq, nk, d, dtype, scale, seed=0, planted=0.0):
     return synth.make_inputs(B=B, H=H, n=nq, nk=nk, d=d, dtype=dtype, scale=scale, seed=seed,
                              planted=planted if nq == nk else 0.0)
