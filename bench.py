@@ -148,13 +148,16 @@ def main():
     algo = {
         "fwd_lists": F * sd["fwd_list_qk"],
         "fwd_tiled": F * (sd["fwd_qk_max"] + sd["fwd_qk_solve"] + sd["fwd_qk_pv"] + sd["fwd_pv_tiles"]),
+        "bwd_rows": F * sd["bwd_list_qk"],
+        "bwd_keys": 0.0,
         "bwd_mask": F * sd["bwd_qk_mask"],
         "bwd_dq": F * 4 * sd["bwd_dq_tiles"],
         "bwd_dkv": F * 4 * sd["bwd_dkv_tiles"],
     }
     kernel_ms = {"fwd_lists": fwd_ms["lists"], "fwd_tiled": fwd_ms["tiled"]}
     if do_bwd:
-        kernel_ms.update(bwd_mask=bwd_ms["mask"], bwd_dq=bwd_ms["dq"], bwd_dkv=bwd_ms["dkv"])
+        kernel_ms.update(bwd_rows=bwd_ms["rows"], bwd_keys=bwd_ms["keys"], bwd_mask=bwd_ms["mask"], bwd_dq=bwd_ms["dq"],
+                         bwd_dkv=bwd_ms["dkv"])
     dominant = max(kernel_ms, key=kernel_ms.get)
     achieved = algo[dominant] / (kernel_ms[dominant] * 1e-3) / 1e12
     total_exec = sum(algo[k] for k in kernel_ms)

@@ -91,6 +91,8 @@ enum {
   ENTMAX_STAT_FWD_SUPPORT = 15,      /* candidate-list kernel: non-zero probabilities (exact support size, summed) */
   ENTMAX_STAT_FWD_SPARSE_BLOCKS = 16, /* workgroups finished by the candidate-list kernel */
   ENTMAX_STAT_FWD_LIST_QK = 17,      /* candidate-list kernel: score tiles computed (both sweeps) */
+  ENTMAX_STAT_BWD_LIST_QK = 18,      /* support-list backward: score tiles computed by its one sweep */
+  ENTMAX_STAT_BWD_SUPPORT = 19,      /* support-list backward: (row, key) entries with p > 0 */
   ENTMAX_ATTN_NUM_STATS = 24
 };
 
@@ -105,12 +107,14 @@ enum {
   ENTMAX_FWD_NUM_PHASES = 3
 };
 enum {
-  ENTMAX_BWD_PHASE_TRANSPOSE = 0,
-  ENTMAX_BWD_PHASE_MASK = 1,
-  ENTMAX_BWD_PHASE_DQ = 2,
-  ENTMAX_BWD_PHASE_DKV = 3,
-  ENTMAX_BWD_PHASE_SCALE_GRAD = 4,
-  ENTMAX_BWD_NUM_PHASES = 5
+  ENTMAX_BWD_PHASE_ROWS = 0,       /* support-list kernel: one Q K^T sweep, then mu, dscale, dQ from the lists */
+  ENTMAX_BWD_PHASE_TRANSPOSE = 1,  /* tiled path (heads the list kernel left over): operand copies */
+  ENTMAX_BWD_PHASE_MASK = 2,       /* tiled path: non-zero tile map */
+  ENTMAX_BWD_PHASE_DQ = 3,         /* tiled path: row scalars and dQ */
+  ENTMAX_BWD_PHASE_DKV = 4,        /* tiled path: dK, dV */
+  ENTMAX_BWD_PHASE_KEYS = 5,       /* support-list path: key-major reordering, dK and dV per key */
+  ENTMAX_BWD_PHASE_SCALE_GRAD = 6,
+  ENTMAX_BWD_NUM_PHASES = 7
 };
 
 /*
@@ -142,7 +146,10 @@ int entmax_attn_fwd(const entmax_attn_params* p, const void* Q, const void* K, c
  *   O is accepted for symmetry with the usual attention backward and may be NULL
  *   (the row term is rebuilt from tau, not from O).
  *   workspace: at least entmax_attn_workspace_bytes(p, 1) bytes, 256-byte aligned.
- * No atomics are used on the outputs: results are bitwise reproducible.
+ * `path` selects as in the forward: 0 = support lists per row and per key for heads whose rows
+ * have few non-zero probabilities, tiled kernels for the other heads; 1 = tiled kernels only.
+ * No floating-point atomics touch the outputs.  The tiled path is bitwise reproducible; the
+ * list path sums each key's entries in query order whenever a key has at most 64 of them.
  */
 int entmax_attn_bwd(const entmax_attn_params* p, const void* Q, const void* K, const void* V, const void* O,
                     const void* dO, const float* tau, const float* beta, const float* gamma, void* dQ, void* dK,

@@ -24,12 +24,12 @@ STAT_NAMES = {
     "fwd_tiles_visible": 0, "fwd_qk_max": 1, "fwd_qk_solve": 2, "fwd_qk_pv": 3, "fwd_pv_tiles": 4,
     "fwd_solve_sweeps": 5, "fwd_blocks": 6, "fwd_eval_tiles": 7,
     "bwd_tiles_visible": 8, "bwd_qk_mask": 9, "bwd_active_tiles": 10, "bwd_dq_tiles": 11, "bwd_dkv_tiles": 12,
-    "fwd_cand_tiles": 13, "fwd_candidates": 14, "fwd_support": 15, "fwd_sparse_blocks": 16, "fwd_list_qk": 17,
+    "fwd_cand_tiles": 13, "fwd_candidates": 14, "fwd_support": 15, "fwd_sparse_blocks": 16, "fwd_list_qk": 17, "bwd_list_qk": 18, "bwd_support": 19,
 }
 FWD_NUM_PHASES = 3
-BWD_NUM_PHASES = 5
+BWD_NUM_PHASES = 7
 FWD_PHASES = ("lists", "transpose", "tiled")
-BWD_PHASES = ("transpose", "mask", "dq", "dkv", "scale_grad")
+BWD_PHASES = ("rows", "transpose", "mask", "dq", "dkv", "keys", "scale_grad")
 
 
 class Params(ctypes.Structure):

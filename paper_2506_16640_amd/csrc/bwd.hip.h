@@ -36,6 +36,7 @@ struct BwdArgs {
   float* dscale;    // [B*H*Nq] gradient with respect to scale_i
   uint32_t* mask;   // [B*H][nqg][mask_words] bit jb of row ig: tile (ig, jb) holds some p > 0
   unsigned long long* stats;
+  const int* head_flag;  // NULL: every head; else [B*H], only heads whose flag is set
   int nqb, nkb, nqg, mask_words;
 };
 
@@ -56,6 +57,7 @@ __device__ __forceinline__ void bwd_mask_block(const BwdArgs& A, int bh_, int bl
   wm.nwords = A.mask_words;
   C q;
   q.init(g, A.Q, bh_, blk_);
+  if (A.head_flag && __builtin_amdgcn_readfirstlane(A.head_flag[q.bh]) == 0) return;
   for (int w = q.tid; w < kWaves * A.mask_words; w += kThreads) wm.words[w] = 0u;
   const float tau = q.valid ? A.tau[(long long)q.bh * g.Nq + q.i] : 0.f;
   const bool live = q.valid && q.lim > 0;
@@ -139,6 +141,7 @@ __device__ __forceinline__ void bwd_dq_block(const BwdArgs& A, int bh_, int blk_
 
   C q;
   q.init(g, A.Q, bh_, blk_);
+  if (A.head_flag && __builtin_amdgcn_readfirstlane(A.head_flag[q.bh]) == 0) return;
   const float r = 1.0f / (g.alpha - 1.0f);
   const long long row_idx = (long long)q.bh * g.Nq + q.i;
   const float tau = q.valid ? A.tau[row_idx] : 0.f;
@@ -274,6 +277,7 @@ __device__ __forceinline__ void bwd_dkv_block(const BwdArgs& A, int bh_, int blk
             hh = lane >> 5;
   const int bh = __builtin_amdgcn_readfirstlane(bh_), kb = __builtin_amdgcn_readfirstlane(blk_);
   const int b = __builtin_amdgcn_readfirstlane(bh / g.H), h = __builtin_amdgcn_readfirstlane(bh % g.H);
+  if (A.head_flag && __builtin_amdgcn_readfirstlane(A.head_flag[bh]) == 0) return;
   const float r = 1.0f / (g.alpha - 1.0f);
   const float am1 = g.alpha - 1.0f;
   const int off = g.Nk - g.Nq;
@@ -518,13 +522,26 @@ __global__ __launch_bounds__(kThreads) void scale_grad_head_kernel(Geom g, const
   __shared__ float sb_[kThreads], sg_[kThreads];
   const int h = blockIdx.x, tid = threadIdx.x;
   float ab = 0.f, ag = 0.f;
-  for (int b = 0; b < g.B; ++b) {
-    for (int i = tid; i < g.Nq; i += kThreads) {
-      float Lg, lnL, bt;
-      row_scale(g, b, h, i, row_limit(g, i), &Lg, &lnL, &bt);
-      float ds = dscale[((long long)b * g.H + h) * g.Nq + i];
-      ab += ds * Lg;
-      ag += ds * bt * Lg * lnL;
+  if (g.logn_mode == 0) {
+    // n = Nk for every row: (ln n)^gamma is one number per head, only dscale has to be summed
+    float Lg, lnL, bt;
+    row_scale(g, 0, h, 0, g.Nk, &Lg, &lnL, &bt);
+    float s = 0.f;
+    for (int b = 0; b < g.B; ++b) {
+      const float* ds = dscale + ((long long)b * g.H + h) * g.Nq;
+      for (int i = tid; i < g.Nq; i += kThreads) s += ds[i];
+    }
+    ab = s * Lg;
+    ag = s * bt * Lg * lnL;
+  } else {
+    for (int b = 0; b < g.B; ++b) {
+      for (int i = tid; i < g.Nq; i += kThreads) {
+        float Lg, lnL, bt;
+        row_scale(g, b, h, i, row_limit(g, i), &Lg, &lnL, &bt);
+        float ds = dscale[((long long)b * g.H + h) * g.Nq + i];
+        ab += ds * Lg;
+        ag += ds * bt * Lg * lnL;
+      }
     }
   }
   sb_[tid] = ab;

@@ -1,0 +1,361 @@
+// Backward kernels for rows with a small support (the regime of the paper's
+// ASEntmax workloads: a few non-zero probabilities per row).  With
+// x_ij = [(alpha-1) s_ij - tau_i]_+, r = 1/(alpha-1), on the support only:
+//   p = x^r, g = x^(r-1), dP_ij = <dO_i, v_j>, mu_i = sum g dP / sum g,
+//   dS_ij = g (dP - mu_i), dQ_i = c_i sum_j dS_ij k_j, dscale_i = sum_j dS_ij z_ij,
+//   dV_j = sum_i p_ij dO_i,  dK_j = sum_i c_i dS_ij q_i.
+// The Jacobian of eq. (entmax) vanishes off the support, so the whole backward
+// is a sparse problem once the support is known:
+//   bwd_lists_kernel   one Q K^T sweep on the matrix cores at the saved tau lists
+//                      each row's support (key index + raw score);
+//   bwd_rows_kernel    everything row-wise (mu, dscale, dQ) from the lists, by
+//                      gathering the few K and V rows (one lane pair per row).
+//                      Each entry's (p, c dS) is stored and the per-key entry
+//                      counts are accumulated;
+//   csc_offsets_kernel prefix sums of the per-key counts (one workgroup per head);
+//   csc_scatter_kernel moves the entries into key-major order;
+//   bwd_keys_kernel    one wave per key: dV_j and dK_j as sums over the key's
+//                      entries, reading whole dO / Q rows (one feature per lane).
+// A head in which some half row holds more than kBwdCap support entries is
+// flagged and left, as a whole, to the tiled kernels of bwd.hip.h.
+#pragma once
+#include "bwd.hip.h"
+#include "fwd_sparse.hip.h"
+
+namespace entmax {
+
+constexpr int kBwdCap = 16;  // support entries per lane = per half row
+
+struct BwdSparseArgs {
+  Geom g;
+  const void* Q;
+  const void* K;
+  const void* V;
+  const void* dO;
+  const float* tau;
+  void* dQ;
+  void* dK;
+  void* dV;
+  float* dscale;       // [B*H*Nq]
+  uint2* jlist;        // [B*H*Nq][2][kBwdCap] (key index, raw dot product bits)
+  float2* pw;          // [B*H*Nq][2][kBwdCap] (p_ij, c_i dS_ij)
+  int* lcnt;           // [B*H*Nq][2] entries per half row
+  int* kcount;         // [B*H*Nk] entries per key (zeroed before bwd_rows_kernel)
+  int* koffs;          // [B*H*Nk] exclusive prefix sums of kcount within the head
+  int* kcursor;        // [B*H*Nk] running insert positions (starts as a copy of koffs)
+  int* csc_i;          // [B*H][Nq*2*kBwdCap] query row of each entry, key-major
+  float2* csc_pw;      // same order: (p, c dS)
+  int* head_flag;      // [B*H] pre-zeroed; 1: head left to the tiled kernels
+  unsigned long long* stats;
+  int nqb;
+};
+
+// ------------------------------------------------------------------ rows
+
+// One Q K^T sweep at the saved threshold: the lists it writes are the rows' exact supports.
+template <typename T, int D, int AM>
+__device__ __forceinline__ void bwd_lists_block(const BwdSparseArgs& A, int bh_, int blk_, char* smem) {
+  using C = QCtx<T, D, FwdTile<T>::value>;
+  constexpr int TB = C::kTileBytes;
+  const Geom& g = A.g;
+  int* ovf = reinterpret_cast<int*>(smem + 2 * TB);
+  C q;
+  q.init(g, A.Q, bh_, blk_);
+  const long long row_idx = (long long)q.bh * g.Nq + (q.valid ? q.i : 0);
+  const float tau = q.valid ? A.tau[row_idx] : 0.f;
+  const bool live = q.valid && q.lim > 0;
+  uint2* mylist = A.jlist + (row_idx * 2 + q.hh) * kBwdCap;
+  int cnt = 0;
+  unsigned n_qk = 0, n_cand_tiles = 0;
+  bool fits = true;
+  if (q.block_lim > 0) fits = collect_sweep<C, T, D, kBwdCap>(q, g, A.K, smem, ovf, live, tau, mylist, cnt, n_qk, n_cand_tiles);
+  if (!fits) {
+    if (q.tid == 0) A.head_flag[q.bh] = 1;
+  } else if (q.valid) {
+    A.lcnt[row_idx * 2 + q.hh] = cnt;
+  }
+  if (A.stats && q.lane == 0) {
+    atomicAdd(&A.stats[ENTMAX_STAT_BWD_TILES_VISIBLE], (unsigned long long)n_qk);
+    atomicAdd(&A.stats[ENTMAX_STAT_BWD_LIST_QK], (unsigned long long)n_qk);
+  }
+}
+
+template <typename T, int D, int AM>
+__global__ __launch_bounds__(kThreads, 3) void bwd_lists_kernel(BwdSparseArgs A) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const PairItem it = pair_item(A.nqb);
+  for (int part = 0; part < 2; ++part) {
+    const int blk = part ? it.second : it.first;
+    if (blk < 0) break;
+    if (part) __syncthreads();
+    bwd_lists_block<T, D, AM>(A, it.bh, blk, smem);
+  }
+}
+
+// Everything row-wise from the lists: one lane pair per row, each lane half of the features.
+template <typename T, int D, int AM>
+__global__ __launch_bounds__(kThreads) void bwd_rows_kernel(BwdSparseArgs A) {
+  const Geom& g = A.g;
+  RowLane rl;
+  rl.init(g, A.nqb);
+  if (A.head_flag[rl.bh] != 0) return;  // the tiled kernels own this head
+  constexpr int DH = D / 2;
+  const float r = 1.0f / (g.alpha - 1.0f);
+  const long long row_idx = (long long)rl.bh * g.Nq + (rl.valid ? rl.i : 0);
+  const int lim = rl.valid ? row_limit(g, rl.i) : 0;
+  const bool live = rl.valid && lim > 0;
+  const float scale = rl.valid ? row_scale(g, rl.b, rl.h, rl.i, lim, nullptr, nullptr, nullptr) : 0.f;
+  const float inv_sqrt_d = 1.0f / sqrtf((float)D);
+  const float c = scale * inv_sqrt_d;
+  const float a = (g.alpha - 1.0f) * fabsf(c);  // same arithmetic as the sweep that made the lists
+  const float sgn = (c < 0.f) ? -1.f : 1.f;
+  const float tau = live ? A.tau[row_idx] : 0.f;
+  const int cnt = live ? A.lcnt[row_idx * 2 + rl.hh] : 0;
+  const long long q_base = (long long)rl.b * g.q_sb + (long long)rl.h * g.q_sh;
+  const long long kv_base = (long long)rl.b * g.kv_sb + (long long)rl.h * g.kv_sh;
+  const uint2* mylist = A.jlist + (row_idx * 2 + rl.hh) * kBwdCap;
+  float2* mypw = A.pw + (row_idx * 2 + rl.hh) * kBwdCap;
+  const T* Kbh = reinterpret_cast<const T*>(A.K) + kv_base;
+  const T* Vbh = reinterpret_cast<const T*>(A.V) + kv_base;
+
+  // the row's dO, this lane's half of the features, widened to fp32
+  float dov[DH];
+  if (rl.valid) {
+    load_row_f32<T>(reinterpret_cast<const T*>(A.dO) + q_base + (long long)rl.i * g.q_sn + rl.hh * DH, DH, dov);
+  } else {
+#pragma unroll
+    for (int t = 0; t < DH; ++t) dov[t] = 0.f;
+  }
+  unsigned n_entries = 0;
+
+  auto finish = [&](auto ne_tag) {
+    constexpr int NE = decltype(ne_tag)::value;
+    unsigned jv[NE];
+    float dv[NE];  // raw dot products (sign-folded), -inf for empty slots
+#pragma unroll
+    for (int e = 0; e < NE; ++e) {
+      uint2 en = (e < cnt) ? mylist[e] : make_uint2(0u, 0u);
+      jv[e] = en.x;
+      dv[e] = (e < cnt) ? __uint_as_float(en.y) : -kInf;
+    }
+    // pass 1: dP of every entry of the row (both halves), row sums
+    float dpv[2][NE];
+    float Z = 0.f, N = 0.f;
+#pragma unroll
+    for (int e = 0; e < NE; ++e) {
+      unsigned pj = (unsigned)__shfl_xor((int)jv[e], 32);
+      float pd = __shfl_xor(dv[e], 32);
+#pragma unroll
+      for (int src = 0; src < 2; ++src) {
+        // both lanes of the pair look at the same entry: entry e of the lane whose half index is src
+        unsigned j = (rl.hh == src) ? jv[e] : pj;
+        float d = (rl.hh == src) ? dv[e] : pd;
+        float x = (d > -kInf) ? fmaxf(fmaf(d, a, -tau), 0.f) : 0.f;
+        dpv[src][e] = 0.f;
+        if (__ballot(x > 0.f) == 0ull) continue;
+        float part = 0.f;
+        if (x > 0.f) {
+          float vv[DH];
+          load_row_f32<T>(Vbh + (long long)j * g.kv_sn + rl.hh * DH, DH, vv);
+#pragma unroll
+          for (int t = 0; t < DH; ++t) part = fmaf(dov[t], vv[t], part);
+        }
+        float dp = part + __shfl_xor(part, 32);
+        dpv[src][e] = dp;
+        float gg = pow_rm1<AM>(x, r);
+        Z += gg;
+        N = fmaf(gg, (x > 0.f) ? dp : 0.f, N);
+      }
+    }
+    const float mu = (Z > 0.f) ? N / Z : 0.f;
+    // pass 2: dS, dQ, dscale and the per-entry records
+    float dq[DH];
+#pragma unroll
+    for (int t = 0; t < DH; ++t) dq[t] = 0.f;
+    float dsc = 0.f;
+#pragma unroll
+    for (int e = 0; e < NE; ++e) {
+      unsigned pj = (unsigned)__shfl_xor((int)jv[e], 32);
+      float pd = __shfl_xor(dv[e], 32);
+#pragma unroll
+      for (int src = 0; src < 2; ++src) {
+        unsigned j = (rl.hh == src) ? jv[e] : pj;
+        float d = (rl.hh == src) ? dv[e] : pd;
+        float x = (d > -kInf) ? fmaxf(fmaf(d, a, -tau), 0.f) : 0.f;
+        if (__ballot(x > 0.f) == 0ull) continue;
+        if (x > 0.f) {
+          float gg = pow_rm1<AM>(x, r);
+          float ds = gg * (dpv[src][e] - mu);
+          float w = c * ds;
+          dsc = fmaf(ds, d, dsc);
+          float kk[DH];
+          load_row_f32<T>(Kbh + (long long)j * g.kv_sn + rl.hh * DH, DH, kk);
+#pragma unroll
+          for (int t = 0; t < DH; ++t) dq[t] = fmaf(w, kk[t], dq[t]);
+          if (rl.hh == src) {  // the entry's owner records it for the key side
+            mypw[e] = make_float2(pow_r<AM>(x, r), w);
+            atomicAdd(&A.kcount[(long long)rl.bh * g.Nk + j], 1);
+            ++n_entries;
+          }
+        }
+      }
+    }
+    if (rl.valid) {
+      store_row<T>(reinterpret_cast<T*>(A.dQ) + q_base + (long long)rl.i * g.q_sn + rl.hh * DH, DH, dq);
+      // the scores were formed with q negated when scale_i < 0: undo the sign for z_ij
+      if (rl.hh == 0) A.dscale[row_idx] = sgn * dsc * inv_sqrt_d;
+    }
+  };
+  if (__ballot(cnt > 4) == 0ull)
+    finish(std::integral_constant<int, 4>());
+  else
+    finish(std::integral_constant<int, kBwdCap>());
+
+  if (A.stats) {
+    unsigned ent = n_entries;
+    for (int s = 32; s > 0; s >>= 1) ent += __shfl_xor((int)ent, s);
+    if ((threadIdx.x & 63) == 0) atomicAdd(&A.stats[ENTMAX_STAT_BWD_SUPPORT], (unsigned long long)ent);
+  }
+}
+
+// ------------------------------------------------------------ key-major order
+
+// One workgroup per head: exclusive prefix sums of the per-key entry counts.
+__global__ __launch_bounds__(kThreads) void csc_offsets_kernel(const int* kcount, int* koffs, int* kcursor, int Nk,
+                                                               const int* head_flag) {
+  __shared__ int part[kThreads];
+  const int bh = blockIdx.x, tid = threadIdx.x;
+  if (head_flag[bh] != 0) return;
+  const int per = (Nk + kThreads - 1) / kThreads;
+  const int beg = tid * per, end = min(Nk, beg + per);
+  const int* c = kcount + (long long)bh * Nk;
+  int s = 0;
+  for (int j = beg; j < end; ++j) s += c[j];
+  part[tid] = s;
+  __syncthreads();
+  // Hillis-Steele inclusive scan over the 256 partial sums
+  for (int off = 1; off < kThreads; off <<= 1) {
+    int v = (tid >= off) ? part[tid - off] : 0;
+    __syncthreads();
+    part[tid] += v;
+    __syncthreads();
+  }
+  int run = part[tid] - s;
+  for (int j = beg; j < end; ++j) {
+    koffs[(long long)bh * Nk + j] = run;
+    kcursor[(long long)bh * Nk + j] = run;
+    run += c[j];
+  }
+}
+
+// One thread per half row: moves its entries into the key-major arrays.
+__global__ __launch_bounds__(kThreads) void csc_scatter_kernel(BwdSparseArgs A) {
+  const Geom& g = A.g;
+  long long slot = (long long)blockIdx.x * kThreads + threadIdx.x;  // (row, half)
+  long long rows = (long long)g.B * g.H * g.Nq;
+  if (slot >= rows * 2) return;
+  long long row = slot >> 1;
+  int bh = (int)(row / g.Nq);
+  if (A.head_flag[bh] != 0) return;
+  int i = (int)(row % g.Nq);
+  int cnt = A.lcnt[slot];
+  long long base = (long long)bh * g.Nq * 2 * kBwdCap;
+  for (int e = 0; e < cnt; ++e) {
+    unsigned j = A.jlist[slot * kBwdCap + e].x;
+    int pos = atomicAdd(&A.kcursor[(long long)bh * g.Nk + j], 1);
+    if (pos < g.Nq * 2 * kBwdCap) {  // always true when the counts are consistent; keeps a stray entry inside the head
+      A.csc_i[base + pos] = i;
+      A.csc_pw[base + pos] = A.pw[slot * kBwdCap + e];
+    }
+  }
+}
+
+// dV_j = sum_i p_ij dO_i,  dK_j = sum_i (c_i dS_ij) q_i  over the key's entries.
+// One wave handles kKeysPerWave consecutive keys, one (D = 64) or two (D = 128) features per lane;
+// the loads of the keys' segment headers and entries are issued together so that their latencies
+// overlap.  Entries sit in arrival order; they are summed in query-row order (rank within chunks of
+// 64), which makes the result reproducible for every key with at most 64 entries.
+constexpr int kKeysPerWave = 4;
+
+template <typename T, int D>
+__global__ __launch_bounds__(kThreads) void bwd_keys_kernel(BwdSparseArgs A) {
+  constexpr int PER = D / 64;
+  const Geom& g = A.g;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const long long nkeys = (long long)g.B * g.H * g.Nk;
+  const long long key0 = ((long long)blockIdx.x * kWaves + wave) * kKeysPerWave;
+  if (key0 >= nkeys) return;
+
+  int beg[kKeysPerWave], n[kKeysPerWave], bh[kKeysPerWave];
+  bool on[kKeysPerWave];
+#pragma unroll
+  for (int kk = 0; kk < kKeysPerWave; ++kk) {
+    long long key = key0 + kk;
+    on[kk] = key < nkeys;
+    bh[kk] = on[kk] ? (int)(key / g.Nk) : 0;
+    on[kk] = on[kk] && A.head_flag[bh[kk]] == 0;
+    beg[kk] = on[kk] ? A.koffs[key] : 0;
+    n[kk] = on[kk] ? A.kcount[key] : 0;
+  }
+  int my_i[kKeysPerWave];
+  float2 my_pw[kKeysPerWave];
+#pragma unroll
+  for (int kk = 0; kk < kKeysPerWave; ++kk) {
+    const long long base = (long long)bh[kk] * g.Nq * 2 * kBwdCap + beg[kk];
+    bool has = lane < n[kk];
+    my_i[kk] = has ? A.csc_i[base + lane] : 0x7fffffff;
+    my_pw[kk] = has ? A.csc_pw[base + lane] : make_float2(0.f, 0.f);
+  }
+#pragma unroll
+  for (int kk = 0; kk < kKeysPerWave; ++kk) {
+    if (!on[kk]) continue;
+    const long long key = key0 + kk;
+    const int j = (int)(key % g.Nk);
+    const int b = bh[kk] / g.H, h = bh[kk] % g.H;
+    const long long base = (long long)bh[kk] * g.Nq * 2 * kBwdCap + beg[kk];
+    const long long q_base = (long long)b * g.q_sb + (long long)h * g.q_sh;
+    float av[PER], ak[PER];
+#pragma unroll
+    for (int t = 0; t < PER; ++t) av[t] = ak[t] = 0.f;
+    for (int e0 = 0; e0 < n[kk]; e0 += 64) {
+      const int m = min(64, n[kk] - e0);
+      int ci = my_i[kk];
+      float2 cpw = my_pw[kk];
+      if (e0 > 0) {  // later chunks of a long segment
+        ci = (lane < m) ? A.csc_i[base + e0 + lane] : 0x7fffffff;
+        cpw = (lane < m) ? A.csc_pw[base + e0 + lane] : make_float2(0.f, 0.f);
+      }
+      int rank = 0;
+      for (int k = 0; k < m; ++k) rank += (__shfl(ci, k) < ci) ? 1 : 0;
+      for (int k = 0; k < m; ++k) {
+        unsigned long long sel = __ballot(lane < m && rank == k);  // rows of a key are distinct: one lane
+        int src = __builtin_ctzll(sel);
+        int i = __shfl(ci, src);
+        float p = __shfl(cpw.x, src), w = __shfl(cpw.y, src);
+        const T* dorow = reinterpret_cast<const T*>(A.dO) + q_base + (long long)i * g.q_sn;
+        const T* qrow = reinterpret_cast<const T*>(A.Q) + q_base + (long long)i * g.q_sn;
+#pragma unroll
+        for (int t = 0; t < PER; ++t) {
+          float dov, qv;
+          if constexpr (sizeof(T) == 2) {
+            dov = __uint_as_float((unsigned)reinterpret_cast<const unsigned short*>(dorow)[lane + 64 * t] << 16);
+            qv = __uint_as_float((unsigned)reinterpret_cast<const unsigned short*>(qrow)[lane + 64 * t] << 16);
+          } else {
+            dov = reinterpret_cast<const float*>(dorow)[lane + 64 * t];
+            qv = reinterpret_cast<const float*>(qrow)[lane + 64 * t];
+          }
+          av[t] = fmaf(p, dov, av[t]);
+          ak[t] = fmaf(w, qv, ak[t]);
+        }
+      }
+    }
+    const long long o = (long long)b * g.kv_sb + (long long)h * g.kv_sh + (long long)j * g.kv_sn;
+#pragma unroll
+    for (int t = 0; t < PER; ++t) {
+      Elem<T>::store(A.dV, o + lane + 64 * t, av[t]);
+      Elem<T>::store(A.dK, o + lane + 64 * t, ak[t]);
+    }
+  }
+}
+
+}  // namespace entmax

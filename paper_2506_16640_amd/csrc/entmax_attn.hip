@@ -7,6 +7,7 @@
 #include <math.h>
 
 #include "bwd.hip.h"
+#include "bwd_sparse.hip.h"
 #include "fwd.hip.h"
 #include "fwd_sparse.hip.h"
 #include "transpose.hip.h"
@@ -27,7 +28,9 @@ struct Layout {
   int mask_words;     // uint32 words covering the 32-key blocks of a head
   long long q_sb, q_sh, q_sn, kv_sb, kv_sh, kv_sn;
   // workspace offsets
-  size_t off_vt, off_cand, off_flags, off_kt, off_qt, off_dot, off_mu, off_crow, off_dscale, off_mask, total_fwd, total_bwd;
+  size_t off_vt, off_cand, off_flcnt, off_bounds, off_flags, off_kt, off_qt, off_dot, off_mu, off_crow, off_dscale, off_mask,
+      off_jlist, off_pw, off_lcnt, off_kcount, off_koffs, off_kcursor, off_csc_i, off_csc_pw, off_hflag, total_fwd,
+      total_bwd;
 };
 
 int check(const entmax_attn_params* p) {
@@ -85,7 +88,9 @@ Layout make_layout(const entmax_attn_params* p) {
   L.off_vt = 0;
   L.off_cand = kt_bytes;
   size_t cand_bytes = align_up(bh * (size_t)p->Nq * 2 * kCandCap * sizeof(uint2));
-  L.off_flags = L.off_cand + cand_bytes;
+  L.off_flcnt = L.off_cand + cand_bytes;
+  L.off_bounds = L.off_flcnt + align_up(bh * (size_t)p->Nq * 2 * sizeof(int));
+  L.off_flags = L.off_bounds + align_up(bh * (size_t)p->Nq * sizeof(float2));
   L.total_fwd = L.off_flags + align_up((bh * (size_t)L.nqb + bh) * sizeof(int));
   size_t o = 0;
   L.off_kt = o;
@@ -102,6 +107,27 @@ Layout make_layout(const entmax_attn_params* p) {
   o += row_bytes;
   L.off_mask = o;
   o += mask_bytes;
+  // support-list backward
+  size_t rows = bh * (size_t)p->Nq;
+  L.off_jlist = o;
+  o += align_up(rows * 2 * kBwdCap * sizeof(uint2));
+  L.off_pw = o;
+  o += align_up(rows * 2 * kBwdCap * sizeof(float2));
+  L.off_lcnt = o;
+  o += align_up(rows * 2 * sizeof(int));
+  size_t key_bytes = align_up(bh * (size_t)p->Nk * sizeof(int));
+  L.off_kcount = o;
+  o += key_bytes;
+  L.off_koffs = o;
+  o += key_bytes;
+  L.off_kcursor = o;
+  o += key_bytes;
+  L.off_csc_i = o;
+  o += align_up(rows * 2 * kBwdCap * sizeof(int));
+  L.off_csc_pw = o;
+  o += align_up(rows * 2 * kBwdCap * sizeof(float2));
+  L.off_hflag = o;
+  o += align_up(bh * sizeof(int));
   L.total_bwd = o;
   return L;
 }
@@ -207,7 +233,9 @@ bool launch_fwd_am(const FwdArgs& a, int am, int nblocks, hipStream_t st) {
 template <typename T, int D, int AM>
 bool launch_fwd_sparse(const FwdSparseArgs& a, int nblocks, hipStream_t st) {
   size_t smem = 2 * (size_t)QCtx<T, D, FwdTile<T>::value>::kTileBytes + 64;
-  hipLaunchKernelGGL((fwd_sparse_kernel<T, D, AM>), dim3((unsigned)nblocks), dim3(kThreads), smem, st, a);
+  hipLaunchKernelGGL((fwd_lists_kernel<T, D, AM>), dim3((unsigned)nblocks), dim3(kThreads), smem, st, a);
+  if (!launch_ok()) return false;
+  hipLaunchKernelGGL((fwd_finish_kernel<T, D, AM>), dim3((unsigned)(a.g.B * a.g.H * a.nqb)), dim3(kThreads), 0, st, a);
   return launch_ok();
 }
 
@@ -249,6 +277,8 @@ int run_fwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
     sa.O = O;
     sa.tau = tau;
     sa.cand = reinterpret_cast<uint2*>(ws + L.off_cand);
+    sa.lcnt = reinterpret_cast<int*>(ws + L.off_flcnt);
+    sa.bounds = reinterpret_cast<float2*>(ws + L.off_bounds);
     sa.dense_flag = dense_flag;
     sa.head_flag = head_flag;
     sa.stats = reinterpret_cast<unsigned long long*>(stats);
@@ -292,14 +322,33 @@ bool launch_bwd_kernels(const BwdArgs& a, const Layout& L, int B, int H, hipStre
     return false;
   hipLaunchKernelGGL(k_mask, dim3((unsigned)(B * H * ((L.nqb + 1) / 2))), dim3(kThreads), smem_mask, st, a);
   if (!launch_ok()) return false;
-  record(ev, 2, st);
+  record(ev, 3, st);
   hipLaunchKernelGGL(k_dq, dim3((unsigned)(B * H * L.nqb)), dim3(kThreads), smem_dq, st, a);
   if (!launch_ok()) return false;
-  record(ev, 3, st);
+  record(ev, 4, st);
   hipLaunchKernelGGL(k_dkv, dim3((unsigned)(B * H * L.nkb)), dim3(kThreads), smem_dkv, st, a);
   if (!launch_ok()) return false;
-  record(ev, 4, st);
+  record(ev, 5, st);
   return true;
+}
+
+template <typename T, int D, int AM>
+bool launch_bwd_rows(const BwdSparseArgs& a, int nblocks, hipStream_t st) {
+  size_t smem = 2 * (size_t)QCtx<T, D, FwdTile<T>::value>::kTileBytes + 64;
+  hipLaunchKernelGGL((bwd_lists_kernel<T, D, AM>), dim3((unsigned)nblocks), dim3(kThreads), smem, st, a);
+  if (!launch_ok()) return false;
+  hipLaunchKernelGGL((bwd_rows_kernel<T, D, AM>), dim3((unsigned)(a.g.B * a.g.H * a.nqb)), dim3(kThreads), 0, st, a);
+  return launch_ok();
+}
+
+template <typename T, int D>
+bool launch_bwd_rows_am(const BwdSparseArgs& a, int am, int nblocks, hipStream_t st) {
+  switch (am) {
+    case 1: return launch_bwd_rows<T, D, 1>(a, nblocks, st);
+    case 2: return launch_bwd_rows<T, D, 2>(a, nblocks, st);
+    case 3: return launch_bwd_rows<T, D, 3>(a, nblocks, st);
+    default: return launch_bwd_rows<T, D, 0>(a, nblocks, st);
+  }
 }
 
 template <typename T, int D>
@@ -316,16 +365,48 @@ int run_bwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
     ok = ok && zero_rows<T>(dK, L.kv_sb, L.kv_sh, L.kv_sn, B, H, p->Nk, p->D, st);
     ok = ok && zero_rows<T>(dV, L.kv_sb, L.kv_sh, L.kv_sn, B, H, p->Nk, p->D, st);
     ok = ok && zero_words(dscale, (size_t)B * H * p->Nq * 4, st);
-    for (int k = 1; k <= 4; ++k) record(ev, k, st);
+    for (int k = 1; k <= 6; ++k) record(ev, k, st);
   } else {
+    const bool lists = p->path == 0;
+    int* head_flag = reinterpret_cast<int*>(ws + L.off_hflag);
+    BwdSparseArgs sa;
+    if (lists) {
+      sa.g = g;
+      sa.Q = Q;
+      sa.K = K;
+      sa.V = V;
+      sa.dO = dO;
+      sa.tau = tau;
+      sa.dQ = dQ;
+      sa.dK = dK;
+      sa.dV = dV;
+      sa.dscale = dscale;
+      sa.jlist = reinterpret_cast<uint2*>(ws + L.off_jlist);
+      sa.pw = reinterpret_cast<float2*>(ws + L.off_pw);
+      sa.lcnt = reinterpret_cast<int*>(ws + L.off_lcnt);
+      sa.kcount = reinterpret_cast<int*>(ws + L.off_kcount);
+      sa.koffs = reinterpret_cast<int*>(ws + L.off_koffs);
+      sa.kcursor = reinterpret_cast<int*>(ws + L.off_kcursor);
+      sa.csc_i = reinterpret_cast<int*>(ws + L.off_csc_i);
+      sa.csc_pw = reinterpret_cast<float2*>(ws + L.off_csc_pw);
+      sa.head_flag = head_flag;
+      sa.stats = reinterpret_cast<unsigned long long*>(stats);
+      sa.nqb = L.nqb;
+      ok = ok && zero_words(head_flag, (size_t)B * H * sizeof(int), st);
+      ok = ok && zero_words(sa.kcount, (size_t)B * H * p->Nk * sizeof(int), st);
+      ok = ok && launch_bwd_rows_am<T, D>(sa, alpha_mode(p->alpha), B * H * ((L.nqb + 1) / 2), st);
+      if (!ok) return ENTMAX_ATTN_LAUNCH_FAILED;
+    }
+    record(ev, 1, st);
+    const int* hf = lists ? head_flag : nullptr;
     void* Kt = ws + L.off_kt;
     void* Qt = ws + L.off_qt;
     void* dOt = ws + L.off_dot;
-    ok = ok && launch_transpose<T, D>(K, L.kv_sb, L.kv_sh, L.kv_sn, B, H, p->Nk, L.npad_k, Kt, st);
-    ok = ok && launch_transpose<T, D>(Q, L.q_sb, L.q_sh, L.q_sn, B, H, p->Nq, L.npad_q, Qt, st);
-    ok = ok && launch_transpose<T, D>(dO, L.q_sb, L.q_sh, L.q_sn, B, H, p->Nq, L.npad_q, dOt, st);
+    ok = ok && launch_transpose<T, D>(K, L.kv_sb, L.kv_sh, L.kv_sn, B, H, p->Nk, L.npad_k, Kt, st, hf);
+    ok = ok && launch_transpose<T, D>(Q, L.q_sb, L.q_sh, L.q_sn, B, H, p->Nq, L.npad_q, Qt, st, hf);
+    ok = ok && launch_transpose<T, D>(dO, L.q_sb, L.q_sh, L.q_sn, B, H, p->Nq, L.npad_q, dOt, st, hf);
     if (!ok) return ENTMAX_ATTN_LAUNCH_FAILED;
-    record(ev, 1, st);
+    record(ev, 2, st);
     BwdArgs a;
     a.g = g;
     a.Q = Q;
@@ -344,6 +425,7 @@ int run_bwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
     a.dscale = dscale;
     a.mask = reinterpret_cast<uint32_t*>(ws + L.off_mask);
     a.stats = reinterpret_cast<unsigned long long*>(stats);
+    a.head_flag = hf;
     a.nqb = L.nqb;
     a.nkb = L.nkb;
     a.nqg = L.nqg;
@@ -354,6 +436,22 @@ int run_bwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
       case 3: ok = launch_bwd_kernels<T, D, 3>(a, L, B, H, st, ev); break;
       default: ok = launch_bwd_kernels<T, D, 0>(a, L, B, H, st, ev); break;
     }
+    if (!ok) return ENTMAX_ATTN_LAUNCH_FAILED;
+    if (lists) {
+      hipLaunchKernelGGL(csc_offsets_kernel, dim3((unsigned)(B * H)), dim3(kThreads), 0, st, sa.kcount, sa.koffs,
+                         sa.kcursor, p->Nk, head_flag);
+      ok = ok && launch_ok();
+      long long slots = (long long)B * H * p->Nq * 2;
+      hipLaunchKernelGGL(csc_scatter_kernel, dim3((unsigned)((slots + kThreads - 1) / kThreads)), dim3(kThreads), 0, st,
+                         sa);
+      ok = ok && launch_ok();
+      long long keys = (long long)B * H * p->Nk;
+      hipLaunchKernelGGL((bwd_keys_kernel<T, D>),
+                         dim3((unsigned)((keys + kWaves * kKeysPerWave - 1) / (kWaves * kKeysPerWave))), dim3(kThreads), 0, st,
+                         sa);
+      ok = ok && launch_ok();
+    }
+    record(ev, 6, st);
   }
   if (!ok) return ENTMAX_ATTN_LAUNCH_FAILED;
   if (p->scale_layout == 1) {
@@ -367,7 +465,7 @@ int run_bwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
       ok = launch_ok();
     }
   }
-  record(ev, 5, st);
+  record(ev, 7, st);
   return ok ? ENTMAX_ATTN_OK : ENTMAX_ATTN_LAUNCH_FAILED;
 }
 

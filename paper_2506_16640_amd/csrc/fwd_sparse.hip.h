@@ -1,21 +1,22 @@
-// Forward kernel for rows whose support is small (the regime the paper's
+// Forward path for rows whose support is small (the regime the paper's
 // ASEntmax workloads live in: a handful of non-zero probabilities per row).
 //
 // alpha-entmax gives exact zeros below the threshold (Sec. 2.2, App. A), and the
 // threshold is bounded below by any sub-problem: solving eq. (entmax) on a
 // subset S of the row's scores gives tau_S <= tau, because dropping terms can
-// only lower f(tau) = sum_j [(alpha-1) s_j - tau]_+^r - 1.  So after
-//   1. a row-max sweep (Q K^T on the matrix cores) that also keeps the second
-//      largest per-cell maximum, tau_lb = max(bracket's left end of App. A
-//      eq. (bounds), two-element solution) is a valid lower bound, and
-//   2. a second Q K^T sweep appends every key with (alpha-1) s_ij > tau_lb to
-//      the row's candidate list (index + raw score) -- every key of the support
-//      is on that list, nothing else of the row can matter --
-// the rest is done on the lists alone, with no further sweep:
-//   3. the threshold by the same safeguarded steps as the tiled kernel
-//      (closed-form local-model root for alpha 1.5 / 2, Halley / Newton
-//      otherwise), summing over the list instead of over key tiles,
-//   4. O_i = sum over the list of p_ij v_j by gathering the few value rows.
+// only lower f(tau) = sum_j [(alpha-1) s_j - tau]_+^r - 1.  So
+//   fwd_lists_kernel (matrix cores, K tiles through LDS, two sweeps)
+//     1. row-max sweep that also keeps the second largest per-cell maximum:
+//        tau_lb = max(left end of the bracket of App. A eq. (bounds),
+//                     solution of the two-element sub-problem) <= tau;
+//     2. second Q K^T sweep: every key with (alpha-1) s_ij > tau_lb goes on the
+//        row's candidate list (key index + raw score).  Every key of the
+//        support is on that list; nothing else of the row can matter.
+//   fwd_finish_kernel (no matrix work, one lane pair per row)
+//     3. the threshold by the same safeguarded steps as the tiled kernel
+//        (closed-form local-model root for alpha 1.5 / 2, Halley / Newton
+//        otherwise), summing over the list instead of over key tiles;
+//     4. O_i = sum over the list of p_ij v_j, gathering the few value rows.
 // A workgroup that meets a row with more candidates than a list holds raises
 // its flag and leaves the whole block to the tiled kernel (fwd.hip.h), which
 // handles any density.
@@ -33,15 +34,73 @@ struct FwdSparseArgs {
   const void* V;
   void* O;
   float* tau;
-  uint2* cand;          // [B*H*Nq][2][kCandCap] (key index, raw dot product bits)
-  int* dense_flag;      // [B*H*nqb] 1: block left to the tiled kernel
-  int* head_flag;       // [B*H] pre-zeroed; set to 1 when some block of the head is left to the tiled kernel
+  uint2* cand;      // [B*H*Nq][2][kCandCap] (key index, raw dot product bits)
+  int* lcnt;        // [B*H*Nq][2] list lengths
+  float2* bounds;   // [B*H*Nq] (tau_lb, right end of the bracket)
+  int* dense_flag;  // [B*H*nqb] 1: block left to the tiled kernel
+  int* head_flag;   // [B*H] pre-zeroed; set to 1 when some block of the head is left to the tiled kernel
   unsigned long long* stats;
   int nqb;
 };
 
+// One sweep over the visible key tiles of the block: every key whose shifted score
+// a * dot - thr is positive is appended to the lane's list.  Returns false (workgroup-uniform) if
+// some list overflowed; the sweep is abandoned early in that case.
+template <typename C, typename T, int D, int CAP>
+__device__ __forceinline__ bool collect_sweep(const C& q, const Geom& g, const void* K, char* tiles, int* ovf, bool live,
+                                              float thr, uint2* mylist, int& cnt, unsigned& n_qk,
+                                              unsigned& n_cand_tiles) {
+  constexpr int KT = C::KT, NSB = C::NSB;
+  if (q.tid < 2) ovf[q.tid] = 0;
+  Slot slots[1];
+  slots[0].base = reinterpret_cast<const char*>(reinterpret_cast<const T*>(K) + (long long)q.b * g.kv_sb +
+                                                (long long)q.h * g.kv_sh);
+  slots[0].row_bytes = g.kv_sn * (long long)sizeof(T);
+  sweep_tiles<C, T, D, 1, 0>(
+      tiles, slots, q.ntiles, g.Nk, q.tid, [](int) { return true; },
+      [&](int kt, const char* tl) {
+        const bool interior = (kt + 1) * KT <= q.wave_lim_min;
+        const uint32_t act = interior ? ((1u << NSB) - 1u) : q.visible_bits(kt);
+        f32x16_t acc[NSB];
+#pragma unroll
+        for (int sb = 0; sb < NSB; ++sb)
+          if (act & (1u << sb)) acc[sb] = q.scores(tl, sb);
+#pragma unroll
+        for (int sb = 0; sb < NSB; ++sb) {
+          if (!(act & (1u << sb))) continue;
+          int j0 = kt * KT + sb * 32;
+          ++n_qk;
+          if (!interior && j0 + 32 > q.wave_lim_min) {
+            int rel = q.lim - j0;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[sb][e] = (q.key_of(e) < rel) ? acc[sb][e] : -kInf;
+          }
+          float lm = max16(acc[sb]);
+          // masked entries are -inf: a = 0 (scale 0) must not turn them into NaN
+          bool cand = live && (lm > -kInf) && (fmaf(lm, q.a, -thr) > 0.f);
+          if (__ballot(cand) == 0ull) continue;
+          ++n_cand_tiles;
+          if (cand) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+              float d = acc[sb][e];
+              if ((d > -kInf) && (fmaf(d, q.a, -thr) > 0.f)) {
+                if (cnt < CAP) mylist[cnt] = make_uint2((unsigned)(j0 + q.key_of(e)), __float_as_uint(d));
+                ++cnt;
+              }
+            }
+          }
+          if (__ballot(cnt > CAP) != 0ull && q.lane == 0) ovf[kt & 1] = 1;
+        }
+      },
+      // flags of the previous tile's parity were final before the barrier that ended that tile
+      [&](int kt) { return kt > 0 && ovf[(kt - 1) & 1] != 0; });
+  // the sweep ended on a barrier: both flags are final
+  return (ovf[0] | ovf[1]) == 0;
+}
+
 template <typename T, int D, int AM>
-__device__ __forceinline__ void fwd_sparse_block(const FwdSparseArgs& A, int bh_, int blk_, char* smem) {
+__device__ __forceinline__ void fwd_lists_block(const FwdSparseArgs& A, int bh_, int blk_, char* smem) {
   using C = QCtx<T, D, FwdTile<T>::value>;
   constexpr int KT = C::KT, NSB = C::NSB, TB = C::kTileBytes;
   const Geom& g = A.g;
@@ -50,32 +109,23 @@ __device__ __forceinline__ void fwd_sparse_block(const FwdSparseArgs& A, int bh_
 
   C q;
   q.init(g, A.Q, bh_, blk_);
-  const float r = 1.0f / (g.alpha - 1.0f);
-  float* tau_out = A.tau + (long long)q.bh * g.Nq;
-  const long long o_base = (long long)q.b * g.q_sb + (long long)q.h * g.q_sh;
   const int flag_idx = q.bh * A.nqb + q.qb;
+  const long long row_idx = (long long)q.bh * g.Nq + (q.valid ? q.i : 0);
+  const bool live = q.valid && q.lim > 0;
 
-  if (q.block_lim == 0) {  // no row of this workgroup sees any key
-    for (int e = q.tid; e < kBlockRows * D; e += kThreads) {
-      int row = q.qb * kBlockRows + e / D;
-      if (row < g.Nq) Elem<T>::store(A.O, o_base + (long long)row * g.q_sn + e % D, 0.f);
+  if (q.block_lim == 0) {  // no row of this workgroup sees any key: the finish kernel writes the zeros
+    if (q.valid) {
+      A.lcnt[row_idx * 2 + q.hh] = 0;
+      if (q.hh == 0) A.bounds[row_idx] = make_float2(0.f, 0.f);
     }
-    if (q.tid < kBlockRows && q.qb * kBlockRows + q.tid < g.Nq) tau_out[q.qb * kBlockRows + q.tid] = 0.f;
     if (q.tid == 0) A.dense_flag[flag_idx] = 0;
     return;
   }
-  if (q.tid < 2) ovf[q.tid] = 0;
 
   Slot slots[1];
   slots[0].base = reinterpret_cast<const char*>(reinterpret_cast<const T*>(A.K) + (long long)q.b * g.kv_sb +
                                                 (long long)q.h * g.kv_sh);
   slots[0].row_bytes = g.kv_sn * (long long)sizeof(T);
-
-  auto mask_block = [&](f32x16_t& acc, int j0) {
-    int rel = q.lim - j0;
-#pragma unroll
-    for (int e = 0; e < 16; ++e) acc[e] = (q.key_of(e) < rel) ? acc[e] : -kInf;
-  };
   unsigned n_vis = 0, n_qk2 = 0, n_cand_tiles = 0;
 
   // ---------------------------------------------- 1. row max and runner-up
@@ -104,7 +154,11 @@ __device__ __forceinline__ void fwd_sparse_block(const FwdSparseArgs& A, int bh_
           int j0 = kt * KT + sb * 32;
           f32x16_t acc = q.scores(tl, sb);
           ++n_vis;
-          if (j0 + 32 > q.wave_lim_min) mask_block(acc, j0);
+          if (j0 + 32 > q.wave_lim_min) {
+            int rel = q.lim - j0;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[e] = (q.key_of(e) < rel) ? acc[e] : -kInf;
+          }
           float lm = max16(acc);
           m2 = fmaxf(m2, fminf(m1, lm));
           m1 = fmaxf(m1, lm);
@@ -116,78 +170,128 @@ __device__ __forceinline__ void fwd_sparse_block(const FwdSparseArgs& A, int bh_
     m2 = fmaxf(fminf(m1, p1), fmaxf(m2, p2));
     m1 = hi1;
   }
-
-  const bool live = q.valid && q.lim > 0;
   const float y1 = live ? q.a * m1 : 0.f;
   float lo = y1 - 1.0f;  // App. A eq. (bounds), left end
   float hi = live ? y1 - __builtin_amdgcn_exp2f(-(g.alpha - 1.0f) * __builtin_amdgcn_logf((float)q.lim)) : 0.f;
   if (live && m2 > -kInf) {
     // two-element sub-problem {y1, y2}: its threshold is a lower bound of the row's
-    float dlt = y1 - q.a * m2;
-    if (AM == 1 && dlt < 1.0f) lo = fmaxf(lo, 0.5f * (y1 + q.a * m2) - sqrtf(0.5f * (1.0f - 0.5f * dlt * dlt)));
-    if (AM == 2 && dlt < 1.0f) lo = fmaxf(lo, 0.5f * (y1 + q.a * m2 - 1.0f));
+    float y2 = q.a * m2, dlt = y1 - y2;
+    if (AM == 1 && dlt < 1.0f) lo = fmaxf(lo, 0.5f * (y1 + y2) - sqrtf(0.5f * (1.0f - 0.5f * dlt * dlt)));
+    if (AM == 2 && dlt < 1.0f) lo = fmaxf(lo, 0.5f * (y1 + y2 - 1.0f));
   }
   lo = fminf(lo, hi);
-  const float tau_lb = lo;
 
   // ---------------------------------------------- 2. candidate lists at tau_lb
-  uint2* mylist = A.cand + (((long long)q.bh * g.Nq + (q.valid ? q.i : 0)) * 2 + q.hh) * kCandCap;
+  uint2* mylist = A.cand + (row_idx * 2 + q.hh) * kCandCap;
   int cnt = 0;
-  sweep_tiles<C, T, D, 1, 0>(
-      tiles, slots, q.ntiles, g.Nk, q.tid, [](int) { return true; },
-      [&](int kt, const char* tl) {
-        const bool interior = (kt + 1) * KT <= q.wave_lim_min;
-        const uint32_t act = interior ? ((1u << NSB) - 1u) : q.visible_bits(kt);
-        f32x16_t acc[NSB];
-#pragma unroll
-        for (int sb = 0; sb < NSB; ++sb)
-          if (act & (1u << sb)) acc[sb] = q.scores(tl, sb);
-#pragma unroll
-        for (int sb = 0; sb < NSB; ++sb) {
-          if (!(act & (1u << sb))) continue;
-          int j0 = kt * KT + sb * 32;
-          ++n_qk2;
-          if (!interior && j0 + 32 > q.wave_lim_min) mask_block(acc[sb], j0);
-          float lm = max16(acc[sb]);
-          bool cand = live && (lm > -kInf) && (fmaf(lm, q.a, -tau_lb) > 0.f);
-          if (__ballot(cand) == 0ull) continue;
-          ++n_cand_tiles;
-          if (cand) {
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-              float d = acc[sb][e];
-              if ((d > -kInf) && (fmaf(d, q.a, -tau_lb) > 0.f)) {
-                if (cnt < kCandCap) mylist[cnt] = make_uint2((unsigned)(j0 + q.key_of(e)), __float_as_uint(d));
-                ++cnt;
-              }
-            }
-          }
-          if (__ballot(cnt > kCandCap) != 0ull && q.lane == 0) ovf[kt & 1] = 1;
-        }
-      },
-      // flags of the previous tile's parity were final before the barrier that ended that tile
-      [&](int kt) { return kt > 0 && ovf[(kt - 1) & 1] != 0; });
-  // the sweep ended on a barrier: both flags are final
-  const bool overflow = (ovf[0] | ovf[1]) != 0;
-  if (overflow) {
+  const bool fits = collect_sweep<C, T, D, kCandCap>(q, g, A.K, tiles, ovf, live, lo, mylist, cnt, n_qk2, n_cand_tiles);
+  if (!fits) {
     if (q.tid == 0) {
       A.dense_flag[flag_idx] = 1;
       A.head_flag[q.bh] = 1;
     }
-    if (A.stats && q.lane == 0) {
-      atomicAdd(&A.stats[ENTMAX_STAT_FWD_TILES_VISIBLE], (unsigned long long)n_vis);
-      atomicAdd(&A.stats[ENTMAX_STAT_FWD_LIST_QK], (unsigned long long)(n_vis + n_qk2));
+  } else {
+    if (q.tid == 0) A.dense_flag[flag_idx] = 0;
+    if (q.valid) {
+      A.lcnt[row_idx * 2 + q.hh] = cnt;
+      if (q.hh == 0) A.bounds[row_idx] = make_float2(lo, hi);
     }
-    return;
   }
-  if (q.tid == 0) A.dense_flag[flag_idx] = 0;
+  if (A.stats && q.lane == 0) {
+    atomicAdd(&A.stats[ENTMAX_STAT_FWD_TILES_VISIBLE], (unsigned long long)n_vis);
+    atomicAdd(&A.stats[ENTMAX_STAT_FWD_LIST_QK], (unsigned long long)(n_vis + n_qk2));
+    if (fits) {
+      atomicAdd(&A.stats[ENTMAX_STAT_FWD_CAND_TILES], (unsigned long long)n_cand_tiles);
+      if (q.wave == 0) atomicAdd(&A.stats[ENTMAX_STAT_FWD_SPARSE_BLOCKS], 1ull);
+    }
+  }
+}
 
-  // ---------------------------------------------- 3 + 4. threshold and output from the lists
-  // make this wave's own list stores visible to its own loads
-  __threadfence_block();
-  const T* Vbh = reinterpret_cast<const T*>(A.V) + (long long)q.b * g.kv_sb + (long long)q.h * g.kv_sh;
+template <typename T, int D, int AM>
+__global__ __launch_bounds__(kThreads, 3) void fwd_lists_kernel(FwdSparseArgs A) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const PairItem it = pair_item(A.nqb);
+  for (int part = 0; part < 2; ++part) {
+    const int blk = part ? it.second : it.first;
+    if (blk < 0) break;
+    if (part) __syncthreads();
+    fwd_lists_block<T, D, AM>(A, it.bh, blk, smem);
+  }
+}
+
+// widen 8 (bf16) or 4 (fp32) consecutive elements to fp32
+template <typename T>
+__device__ __forceinline__ void load_row_f32(const T* row, int n, float* out) {
+  if constexpr (sizeof(T) == 2) {
+#pragma unroll
+    for (int c8 = 0; c8 < n / 8; ++c8) {
+      u32x4_t w = *reinterpret_cast<const u32x4_t*>(row + 8 * c8);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        out[8 * c8 + 2 * k] = __uint_as_float(w[k] << 16);
+        out[8 * c8 + 2 * k + 1] = __uint_as_float(w[k] & 0xffff0000u);
+      }
+    }
+  } else {
+#pragma unroll
+    for (int c4 = 0; c4 < n / 4; ++c4) {
+      f32x4_t w = *reinterpret_cast<const f32x4_t*>(row + 4 * c4);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) out[4 * c4 + k] = w[k];
+    }
+  }
+}
+template <typename T>
+__device__ __forceinline__ void store_row(T* row, int n, const float* v) {
+  if constexpr (sizeof(T) == 2) {
+#pragma unroll
+    for (int c8 = 0; c8 < n / 8; ++c8) *reinterpret_cast<u32x4_t*>(row + 8 * c8) = Elem<T>::pack(v + 8 * c8).v;
+  } else {
+#pragma unroll
+    for (int c4 = 0; c4 < n / 4; ++c4)
+      *reinterpret_cast<f32x4_t*>(row + 4 * c4) = f32x4_t{v[4 * c4], v[4 * c4 + 1], v[4 * c4 + 2], v[4 * c4 + 3]};
+  }
+}
+
+// Row coordinates of a lane in the list kernels: wave w of block qb owns rows qb*128 + 32 w .. + 31,
+// lane l row (l % 32), half (l / 32) -- the same assignment as in the sweeps that wrote the lists.
+struct RowLane {
+  int bh, b, h, qb, i, li, hh;
+  bool valid;
+  __device__ __forceinline__ void init(const Geom& g, int nqb) {
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    bh = blockIdx.x / nqb;
+    qb = blockIdx.x % nqb;
+    b = bh / g.H;
+    h = bh % g.H;
+    li = lane & 31;
+    hh = lane >> 5;
+    i = qb * kBlockRows + wave * 32 + li;
+    valid = i < g.Nq;
+  }
+};
+
+template <typename T, int D, int AM>
+__global__ __launch_bounds__(kThreads) void fwd_finish_kernel(FwdSparseArgs A) {
+  const Geom& g = A.g;
+  RowLane rl;
+  rl.init(g, A.nqb);
+  if (A.dense_flag[rl.bh * A.nqb + rl.qb] != 0) return;  // the tiled kernel owns this block
+  constexpr int DH = D / 2;
+  const float r = 1.0f / (g.alpha - 1.0f);
+  const long long row_idx = (long long)rl.bh * g.Nq + (rl.valid ? rl.i : 0);
+  const int lim = rl.valid ? row_limit(g, rl.i) : 0;
+  const bool live = rl.valid && lim > 0;
+  const float scale = rl.valid ? row_scale(g, rl.b, rl.h, rl.i, lim, nullptr, nullptr, nullptr) : 0.f;
+  const float c = scale * (1.0f / sqrtf((float)D));
+  const float a = (g.alpha - 1.0f) * fabsf(c);  // same arithmetic as the sweeps that made the lists
+  const int cnt = live ? A.lcnt[row_idx * 2 + rl.hh] : 0;
+  const float2 bd = live ? A.bounds[row_idx] : make_float2(0.f, 0.f);
+  const uint2* mylist = A.cand + (row_idx * 2 + rl.hh) * kCandCap;
+  const T* Vbh = reinterpret_cast<const T*>(A.V) + (long long)rl.b * g.kv_sb + (long long)rl.h * g.kv_sh;
+  float lo = bd.x, hi = bd.y, tau = bd.x;
   unsigned n_support = 0;
-  float tau = tau_lb;
+
   // NE: list entries per lane held in registers; chosen per wave from the longest list it holds
   auto finish = [&](auto ne_tag) {
     constexpr int NE = decltype(ne_tag)::value;
@@ -197,7 +301,7 @@ __device__ __forceinline__ void fwd_sparse_block(const FwdSparseArgs& A, int bh_
     for (int e = 0; e < NE; ++e) {
       uint2 en = (e < cnt) ? mylist[e] : make_uint2(0u, 0u);
       jv[e] = en.x;
-      yv[e] = (e < cnt) ? q.a * __uint_as_float(en.y) : -kInf;  // -inf: never positive
+      yv[e] = (e < cnt) ? a * __uint_as_float(en.y) : -kInf;  // -inf: never positive
     }
     bool done = !live;
     int iter = 0;
@@ -211,89 +315,53 @@ __device__ __forceinline__ void fwd_sparse_block(const FwdSparseArgs& A, int bh_
       ++iter;
     }
     // O = sum p_j v_j: each lane of a pair takes half of the features of every entry of the row
-    constexpr int DH = D / 2;
     float oacc[DH];
 #pragma unroll
     for (int t = 0; t < DH; ++t) oacc[t] = 0.f;
 #pragma unroll
-    for (int half = 0; half < 2; ++half) {
+    for (int e = 0; e < NE; ++e) {
+      float p_own = live ? pow_r<AM>(fmaxf(yv[e] - tau, 0.f), r) : 0.f;
+      float p_oth = __shfl_xor(p_own, 32);
+      unsigned j_oth = (unsigned)__shfl_xor((int)jv[e], 32);
+      if (p_own > 0.f) ++n_support;
 #pragma unroll
-      for (int e = 0; e < NE; ++e) {
-        float p_own = live ? pow_r<AM>(fmaxf(yv[e] - tau, 0.f), r) : 0.f;
-        // half 0: the lane's own entry; half 1: its partner's entry
-        float p = half == 0 ? p_own : __shfl_xor(p_own, 32);
-        unsigned j = half == 0 ? jv[e] : (unsigned)__shfl_xor((int)jv[e], 32);
+      for (int src = 0; src < 2; ++src) {
+        // both lanes of the pair take the same entry: entry e of the lane whose half index is src
+        float p = (rl.hh == src) ? p_own : p_oth;
+        unsigned j = (rl.hh == src) ? jv[e] : j_oth;
         if (__ballot(p > 0.f) == 0ull) continue;
-        if (half == 0 && p > 0.f) ++n_support;
         if (p > 0.f) {
-          const T* vrow = Vbh + (long long)j * g.kv_sn + q.hh * DH;
-          if constexpr (sizeof(T) == 2) {
+          float vv[DH];
+          load_row_f32<T>(Vbh + (long long)j * g.kv_sn + rl.hh * DH, DH, vv);
 #pragma unroll
-            for (int c8 = 0; c8 < DH / 8; ++c8) {
-              u32x4_t w = *reinterpret_cast<const u32x4_t*>(vrow + 8 * c8);
-#pragma unroll
-              for (int k = 0; k < 4; ++k) {
-                oacc[8 * c8 + 2 * k] = fmaf(p, __uint_as_float(w[k] << 16), oacc[8 * c8 + 2 * k]);
-                oacc[8 * c8 + 2 * k + 1] = fmaf(p, __uint_as_float(w[k] & 0xffff0000u), oacc[8 * c8 + 2 * k + 1]);
-              }
-            }
-          } else {
-#pragma unroll
-            for (int c4 = 0; c4 < DH / 4; ++c4) {
-              f32x4_t w = *reinterpret_cast<const f32x4_t*>(vrow + 4 * c4);
-#pragma unroll
-              for (int k = 0; k < 4; ++k) oacc[4 * c4 + k] = fmaf(p, w[k], oacc[4 * c4 + k]);
-            }
-          }
+          for (int t = 0; t < DH; ++t) oacc[t] = fmaf(p, vv[t], oacc[t]);
         }
       }
     }
-    if (q.valid) {
-      T* orow = reinterpret_cast<T*>(A.O) + o_base + (long long)q.i * g.q_sn + q.hh * DH;
-      if constexpr (sizeof(T) == 2) {
-#pragma unroll
-        for (int c8 = 0; c8 < DH / 8; ++c8) *reinterpret_cast<u32x4_t*>(orow + 8 * c8) = Elem<T>::pack(oacc + 8 * c8).v;
-      } else {
-#pragma unroll
-        for (int c4 = 0; c4 < DH / 4; ++c4)
-          *reinterpret_cast<f32x4_t*>(orow + 4 * c4) =
-              f32x4_t{oacc[4 * c4], oacc[4 * c4 + 1], oacc[4 * c4 + 2], oacc[4 * c4 + 3]};
-      }
-      if (q.hh == 0) tau_out[q.i] = live ? tau : 0.f;
+    if (rl.valid) {
+      T* orow = reinterpret_cast<T*>(A.O) + (long long)rl.b * g.q_sb + (long long)rl.h * g.q_sh +
+                (long long)rl.i * g.q_sn + rl.hh * DH;
+      store_row<T>(orow, DH, oacc);
+      if (rl.hh == 0) A.tau[row_idx] = live ? tau : 0.f;
     }
   };
-  if (__ballot(cnt > 8) == 0ull)
-    finish(std::integral_constant<int, 8>());
+  if (__ballot(cnt > 4) == 0ull)
+    finish(std::integral_constant<int, 4>());
+  else if (__ballot(cnt > 12) == 0ull)
+    finish(std::integral_constant<int, 12>());
   else
     finish(std::integral_constant<int, kCandCap>());
 
   if (A.stats) {
-    // per-wave totals of the per-lane counters
     unsigned sup = n_support, cands = (unsigned)cnt;
     for (int s = 32; s > 0; s >>= 1) {
       sup += __shfl_xor((int)sup, s);
       cands += __shfl_xor((int)cands, s);
     }
-    if (q.lane == 0) {
-      atomicAdd(&A.stats[ENTMAX_STAT_FWD_TILES_VISIBLE], (unsigned long long)n_vis);
-      atomicAdd(&A.stats[ENTMAX_STAT_FWD_LIST_QK], (unsigned long long)(n_vis + n_qk2));
-      atomicAdd(&A.stats[ENTMAX_STAT_FWD_CAND_TILES], (unsigned long long)n_cand_tiles);
+    if ((threadIdx.x & 63) == 0) {
       atomicAdd(&A.stats[ENTMAX_STAT_FWD_CANDIDATES], (unsigned long long)cands);
       atomicAdd(&A.stats[ENTMAX_STAT_FWD_SUPPORT], (unsigned long long)sup);
-      if (q.wave == 0) atomicAdd(&A.stats[ENTMAX_STAT_FWD_SPARSE_BLOCKS], 1ull);
     }
-  }
-}
-
-template <typename T, int D, int AM>
-__global__ __launch_bounds__(kThreads, 3) void fwd_sparse_kernel(FwdSparseArgs A) {
-  extern __shared__ __attribute__((aligned(16))) char smem[];
-  const PairItem it = pair_item(A.nqb);
-  for (int part = 0; part < 2; ++part) {
-    const int blk = part ? it.second : it.first;
-    if (blk < 0) break;
-    if (part) __syncthreads();
-    fwd_sparse_block<T, D, AM>(A, it.bh, blk, smem);
   }
 }
 

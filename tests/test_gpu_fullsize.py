@@ -59,7 +59,8 @@ def test_c3_headline_fwd_bwd_sampled_heads():
     assert abs(g["dgamma"][h] - r["dgamma"][0]) <= TOL_GRAD * abs(r["dgamma"][0])
     st = g["stats"]
     assert st["fwd_sparse_blocks"] > 0.9 * 4 * 12 * 32  # the headline workload is sparse: the list kernel finishes it
-    assert st["bwd_active_tiles"] == st["bwd_dq_tiles"] == st["bwd_dkv_tiles"]
+    assert st["bwd_active_tiles"] == st["bwd_dq_tiles"] == st["bwd_dkv_tiles"] == 0  # no head needed the tiled backward
+    assert st["bwd_support"] == st["fwd_support"]
 
 
 def test_c3_dense_companion_sampled_heads():
