@@ -25,6 +25,7 @@
 namespace entmax {
 
 constexpr int kBwdCap = 16;  // support entries per lane = per half row
+constexpr unsigned kNoKey = 0xffffffffu;  // list slot whose entry is not part of the support
 
 struct BwdSparseArgs {
   Geom g;
@@ -37,12 +38,12 @@ struct BwdSparseArgs {
   void* dK;
   void* dV;
   float* dscale;       // [B*H*Nq]
-  uint2* jlist;        // [B*H*Nq][2][kBwdCap] (key index, raw dot product bits)
+  uint2* jlist;        // [B*H*Nq][2][kBwdCap] (key index, raw dot product bits); bwd_rows_kernel replaces the
+                       // second word by the entry's arrival number within its key (key index kNoKey: dropped)
   float2* pw;          // [B*H*Nq][2][kBwdCap] (p_ij, c_i dS_ij)
   int* lcnt;           // [B*H*Nq][2] entries per half row
   int* kcount;         // [B*H*Nk] entries per key (zeroed before bwd_rows_kernel)
   int* koffs;          // [B*H*Nk] exclusive prefix sums of kcount within the head
-  int* kcursor;        // [B*H*Nk] running insert positions (starts as a copy of koffs)
   int* csc_i;          // [B*H][Nq*2*kBwdCap] query row of each entry, key-major
   float2* csc_pw;      // same order: (p, c dS)
   int* head_flag;      // [B*H] pre-zeroed; 1: head left to the tiled kernels
@@ -113,7 +114,7 @@ __global__ __launch_bounds__(kThreads) void bwd_rows_kernel(BwdSparseArgs A) {
   const int cnt = live ? A.lcnt[row_idx * 2 + rl.hh] : 0;
   const long long q_base = (long long)rl.b * g.q_sb + (long long)rl.h * g.q_sh;
   const long long kv_base = (long long)rl.b * g.kv_sb + (long long)rl.h * g.kv_sh;
-  const uint2* mylist = A.jlist + (row_idx * 2 + rl.hh) * kBwdCap;
+  uint2* mylist = A.jlist + (row_idx * 2 + rl.hh) * kBwdCap;
   float2* mypw = A.pw + (row_idx * 2 + rl.hh) * kBwdCap;
   const T* Kbh = reinterpret_cast<const T*>(A.K) + kv_base;
   const T* Vbh = reinterpret_cast<const T*>(A.V) + kv_base;
@@ -173,6 +174,9 @@ __global__ __launch_bounds__(kThreads) void bwd_rows_kernel(BwdSparseArgs A) {
 #pragma unroll
     for (int t = 0; t < DH; ++t) dq[t] = 0.f;
     float dsc = 0.f;
+    int slotv[NE];  // arrival numbers of the lane's own entries; -1: not part of the support
+#pragma unroll
+    for (int e = 0; e < NE; ++e) slotv[e] = -1;
 #pragma unroll
     for (int e = 0; e < NE; ++e) {
       unsigned pj = (unsigned)__shfl_xor((int)jv[e], 32);
@@ -194,12 +198,18 @@ __global__ __launch_bounds__(kThreads) void bwd_rows_kernel(BwdSparseArgs A) {
           for (int t = 0; t < DH; ++t) dq[t] = fmaf(w, kk[t], dq[t]);
           if (rl.hh == src) {  // the entry's owner records it for the key side
             mypw[e] = make_float2(pow_r<AM>(x, r), w);
-            atomicAdd(&A.kcount[(long long)rl.bh * g.Nk + j], 1);
+            // arrival number of this entry among the key's entries: its place in the key's segment
+            slotv[e] = atomicAdd(&A.kcount[(long long)rl.bh * g.Nk + j], 1);
             ++n_entries;
           }
         }
       }
     }
+    // the returned arrival numbers are only needed now: the atomics above overlap each other
+    // (a listed key whose probability rounds to zero here is dropped from the key side)
+#pragma unroll
+    for (int e = 0; e < NE; ++e)
+      if (e < cnt) mylist[e] = slotv[e] >= 0 ? make_uint2(jv[e], (unsigned)slotv[e]) : make_uint2(kNoKey, 0u);
     if (rl.valid) {
       store_row<T>(reinterpret_cast<T*>(A.dQ) + q_base + (long long)rl.i * g.q_sn + rl.hh * DH, DH, dq);
       // the scores were formed with q negated when scale_i < 0: undo the sign for z_ij
@@ -221,7 +231,7 @@ __global__ __launch_bounds__(kThreads) void bwd_rows_kernel(BwdSparseArgs A) {
 // ------------------------------------------------------------ key-major order
 
 // One workgroup per head: exclusive prefix sums of the per-key entry counts.
-__global__ __launch_bounds__(kThreads) void csc_offsets_kernel(const int* kcount, int* koffs, int* kcursor, int Nk,
+__global__ __launch_bounds__(kThreads) void csc_offsets_kernel(const int* kcount, int* koffs, int Nk,
                                                                const int* head_flag) {
   __shared__ int part[kThreads];
   const int bh = blockIdx.x, tid = threadIdx.x;
@@ -243,12 +253,12 @@ __global__ __launch_bounds__(kThreads) void csc_offsets_kernel(const int* kcount
   int run = part[tid] - s;
   for (int j = beg; j < end; ++j) {
     koffs[(long long)bh * Nk + j] = run;
-    kcursor[(long long)bh * Nk + j] = run;
     run += c[j];
   }
 }
 
-// One thread per half row: moves its entries into the key-major arrays.
+// One thread per half row: moves its entries into the key-major arrays.  An entry's place is its
+// key's segment start plus its arrival number, so no atomics are needed here.
 __global__ __launch_bounds__(kThreads) void csc_scatter_kernel(BwdSparseArgs A) {
   const Geom& g = A.g;
   long long slot = (long long)blockIdx.x * kThreads + threadIdx.x;  // (row, half)
@@ -261,100 +271,145 @@ __global__ __launch_bounds__(kThreads) void csc_scatter_kernel(BwdSparseArgs A) 
   int cnt = A.lcnt[slot];
   long long base = (long long)bh * g.Nq * 2 * kBwdCap;
   for (int e = 0; e < cnt; ++e) {
-    unsigned j = A.jlist[slot * kBwdCap + e].x;
-    int pos = atomicAdd(&A.kcursor[(long long)bh * g.Nk + j], 1);
-    if (pos < g.Nq * 2 * kBwdCap) {  // always true when the counts are consistent; keeps a stray entry inside the head
-      A.csc_i[base + pos] = i;
-      A.csc_pw[base + pos] = A.pw[slot * kBwdCap + e];
-    }
+    uint2 en = A.jlist[slot * kBwdCap + e];
+    if (en.x == kNoKey) continue;
+    int pos = A.koffs[(long long)bh * g.Nk + en.x] + (int)en.y;
+    A.csc_i[base + pos] = i;
+    A.csc_pw[base + pos] = A.pw[slot * kBwdCap + e];
   }
 }
 
 // dV_j = sum_i p_ij dO_i,  dK_j = sum_i (c_i dS_ij) q_i  over the key's entries.
-// One wave handles kKeysPerWave consecutive keys, one (D = 64) or two (D = 128) features per lane;
-// the loads of the keys' segment headers and entries are issued together so that their latencies
-// overlap.  Entries sit in arrival order; they are summed in query-row order (rank within chunks of
-// 64), which makes the result reproducible for every key with at most 64 entries.
-constexpr int kKeysPerWave = 4;
+// One lane pair per key, each lane half of the features (the mirror image of bwd_rows_kernel).
+// A key's entries sit in arrival order; they are summed in query-row order (selection by repeated
+// minimum over the entries held in registers), which makes the result independent of the arrival
+// order.  Keys with more than kSortedKeyEntries entries are left to bwd_long_keys_kernel.
+constexpr int kSortedKeyEntries = 8;
 
 template <typename T, int D>
-__global__ __launch_bounds__(kThreads) void bwd_keys_kernel(BwdSparseArgs A) {
+__global__ __launch_bounds__(kThreads, 3) void bwd_keys_kernel(BwdSparseArgs A) {
+  constexpr int DH = D / 2;
+  const Geom& g = A.g;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 31, hh = lane >> 5;
+  const long long nkeys = (long long)g.B * g.H * g.Nk;
+  const long long key = (long long)blockIdx.x * kBlockRows + wave * 32 + li;
+  bool on = key < nkeys;
+  const int bh = on ? (int)(key / g.Nk) : 0;
+  const int j = on ? (int)(key % g.Nk) : 0;
+  on = on && A.head_flag[bh] == 0;
+  const int b = bh / g.H, h = bh % g.H;
+  int n = on ? A.kcount[key] : 0;
+  if (n > kSortedKeyEntries) {  // longer segments belong to bwd_long_keys_kernel
+    on = false;
+    n = 0;
+  }
+  const long long base = (long long)bh * g.Nq * 2 * kBwdCap + (on ? A.koffs[key] : 0);
+  const long long q_base = (long long)b * g.q_sb + (long long)h * g.q_sh;
+  const T* dObh = reinterpret_cast<const T*>(A.dO) + q_base + hh * DH;
+  const T* Qbh = reinterpret_cast<const T*>(A.Q) + q_base + hh * DH;
+  float dv[DH], dk[DH];
+#pragma unroll
+  for (int t = 0; t < DH; ++t) dv[t] = dk[t] = 0.f;
+  auto add_entry = [&](int i, float2 pw) {
+    float rd[DH], rq[DH];
+    load_row_f32<T>(dObh + (long long)i * g.q_sn, DH, rd);
+    load_row_f32<T>(Qbh + (long long)i * g.q_sn, DH, rq);
+#pragma unroll
+    for (int u = 0; u < DH; ++u) {
+      dv[u] = fmaf(pw.x, rd[u], dv[u]);
+      dk[u] = fmaf(pw.y, rq[u], dk[u]);
+    }
+  };
+  // the first kSortedKeyEntries entries are held in registers
+  int ci[kSortedKeyEntries];
+  float2 cpw[kSortedKeyEntries];
+#pragma unroll
+  for (int e = 0; e < kSortedKeyEntries; ++e) {
+    ci[e] = (e < n) ? A.csc_i[base + e] : 0x7fffffff;
+    cpw[e] = (e < n) ? A.csc_pw[base + e] : make_float2(0.f, 0.f);
+  }
+  {
+    int last = -1;
+#pragma unroll
+    for (int t = 0; t < kSortedKeyEntries; ++t) {
+      if (__ballot(t < n) == 0ull) break;
+      // the smallest row above the last one taken (rows of a key are distinct)
+      int i = 0x7fffffff;
+      float2 pw = make_float2(0.f, 0.f);
+#pragma unroll
+      for (int e = 0; e < kSortedKeyEntries; ++e) {
+        bool better = ci[e] > last && ci[e] < i;
+        i = better ? ci[e] : i;
+        pw = better ? cpw[e] : pw;
+      }
+      last = i;
+      if (t < n) add_entry(i, pw);
+    }
+  }
+  if (on) {
+    const long long o = (long long)b * g.kv_sb + (long long)h * g.kv_sh + (long long)j * g.kv_sn + hh * DH;
+    store_row<T>(reinterpret_cast<T*>(A.dV) + o, DH, dv);
+    store_row<T>(reinterpret_cast<T*>(A.dK) + o, DH, dk);
+  }
+}
+
+// Keys with more than kSortedKeyEntries entries: one wave per key, one (D = 64) or two (D = 128)
+// features per lane, whole dO / Q rows per entry.  Within chunks of 64 entries the sum runs in
+// query-row order (rank by comparison across the wave), so keys with up to 64 entries get an
+// order-independent result; only longer segments depend on the arrival order of their chunks.
+template <typename T, int D>
+__global__ __launch_bounds__(kThreads) void bwd_long_keys_kernel(BwdSparseArgs A) {
   constexpr int PER = D / 64;
   const Geom& g = A.g;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-  const long long nkeys = (long long)g.B * g.H * g.Nk;
-  const long long key0 = ((long long)blockIdx.x * kWaves + wave) * kKeysPerWave;
-  if (key0 >= nkeys) return;
-
-  int beg[kKeysPerWave], n[kKeysPerWave], bh[kKeysPerWave];
-  bool on[kKeysPerWave];
+  const long long key = (long long)blockIdx.x * kWaves + wave;
+  if (key >= (long long)g.B * g.H * g.Nk) return;
+  const int n = __builtin_amdgcn_readfirstlane(A.kcount[key]);
+  if (n <= kSortedKeyEntries) return;
+  const int bh = (int)(key / g.Nk), j = (int)(key % g.Nk);
+  if (__builtin_amdgcn_readfirstlane(A.head_flag[bh]) != 0) return;
+  const int b = bh / g.H, h = bh % g.H;
+  const long long base = (long long)bh * g.Nq * 2 * kBwdCap + __builtin_amdgcn_readfirstlane(A.koffs[key]);
+  const long long q_base = (long long)b * g.q_sb + (long long)h * g.q_sh;
+  float av[PER], ak[PER];
 #pragma unroll
-  for (int kk = 0; kk < kKeysPerWave; ++kk) {
-    long long key = key0 + kk;
-    on[kk] = key < nkeys;
-    bh[kk] = on[kk] ? (int)(key / g.Nk) : 0;
-    on[kk] = on[kk] && A.head_flag[bh[kk]] == 0;
-    beg[kk] = on[kk] ? A.koffs[key] : 0;
-    n[kk] = on[kk] ? A.kcount[key] : 0;
-  }
-  int my_i[kKeysPerWave];
-  float2 my_pw[kKeysPerWave];
+  for (int t = 0; t < PER; ++t) av[t] = ak[t] = 0.f;
+  for (int e0 = 0; e0 < n; e0 += 64) {
+    const int m = min(64, n - e0);
+    int ci = (lane < m) ? A.csc_i[base + e0 + lane] : 0x7fffffff;
+    float2 cpw = (lane < m) ? A.csc_pw[base + e0 + lane] : make_float2(0.f, 0.f);
+    int rank = 0;
+    for (int k = 0; k < m; ++k) rank += (__shfl(ci, k) < ci) ? 1 : 0;
+    // push every entry to the lane of its rank: lane k then holds the k-th smallest row
+    int si = __builtin_amdgcn_ds_permute(rank << 2, ci);
+    float sp = __int_as_float(__builtin_amdgcn_ds_permute(rank << 2, __float_as_int(cpw.x)));
+    float sw = __int_as_float(__builtin_amdgcn_ds_permute(rank << 2, __float_as_int(cpw.y)));
+#pragma unroll 4
+    for (int k = 0; k < m; ++k) {
+      int i = __shfl(si, k);
+      float p = __shfl(sp, k), w = __shfl(sw, k);
+      const T* dorow = reinterpret_cast<const T*>(A.dO) + q_base + (long long)i * g.q_sn;
+      const T* qrow = reinterpret_cast<const T*>(A.Q) + q_base + (long long)i * g.q_sn;
 #pragma unroll
-  for (int kk = 0; kk < kKeysPerWave; ++kk) {
-    const long long base = (long long)bh[kk] * g.Nq * 2 * kBwdCap + beg[kk];
-    bool has = lane < n[kk];
-    my_i[kk] = has ? A.csc_i[base + lane] : 0x7fffffff;
-    my_pw[kk] = has ? A.csc_pw[base + lane] : make_float2(0.f, 0.f);
-  }
-#pragma unroll
-  for (int kk = 0; kk < kKeysPerWave; ++kk) {
-    if (!on[kk]) continue;
-    const long long key = key0 + kk;
-    const int j = (int)(key % g.Nk);
-    const int b = bh[kk] / g.H, h = bh[kk] % g.H;
-    const long long base = (long long)bh[kk] * g.Nq * 2 * kBwdCap + beg[kk];
-    const long long q_base = (long long)b * g.q_sb + (long long)h * g.q_sh;
-    float av[PER], ak[PER];
-#pragma unroll
-    for (int t = 0; t < PER; ++t) av[t] = ak[t] = 0.f;
-    for (int e0 = 0; e0 < n[kk]; e0 += 64) {
-      const int m = min(64, n[kk] - e0);
-      int ci = my_i[kk];
-      float2 cpw = my_pw[kk];
-      if (e0 > 0) {  // later chunks of a long segment
-        ci = (lane < m) ? A.csc_i[base + e0 + lane] : 0x7fffffff;
-        cpw = (lane < m) ? A.csc_pw[base + e0 + lane] : make_float2(0.f, 0.f);
-      }
-      int rank = 0;
-      for (int k = 0; k < m; ++k) rank += (__shfl(ci, k) < ci) ? 1 : 0;
-      for (int k = 0; k < m; ++k) {
-        unsigned long long sel = __ballot(lane < m && rank == k);  // rows of a key are distinct: one lane
-        int src = __builtin_ctzll(sel);
-        int i = __shfl(ci, src);
-        float p = __shfl(cpw.x, src), w = __shfl(cpw.y, src);
-        const T* dorow = reinterpret_cast<const T*>(A.dO) + q_base + (long long)i * g.q_sn;
-        const T* qrow = reinterpret_cast<const T*>(A.Q) + q_base + (long long)i * g.q_sn;
-#pragma unroll
-        for (int t = 0; t < PER; ++t) {
-          float dov, qv;
-          if constexpr (sizeof(T) == 2) {
-            dov = __uint_as_float((unsigned)reinterpret_cast<const unsigned short*>(dorow)[lane + 64 * t] << 16);
-            qv = __uint_as_float((unsigned)reinterpret_cast<const unsigned short*>(qrow)[lane + 64 * t] << 16);
-          } else {
-            dov = reinterpret_cast<const float*>(dorow)[lane + 64 * t];
-            qv = reinterpret_cast<const float*>(qrow)[lane + 64 * t];
-          }
-          av[t] = fmaf(p, dov, av[t]);
-          ak[t] = fmaf(w, qv, ak[t]);
+      for (int t = 0; t < PER; ++t) {
+        float dov, qv;
+        if constexpr (sizeof(T) == 2) {
+          dov = __uint_as_float((unsigned)reinterpret_cast<const unsigned short*>(dorow)[lane + 64 * t] << 16);
+          qv = __uint_as_float((unsigned)reinterpret_cast<const unsigned short*>(qrow)[lane + 64 * t] << 16);
+        } else {
+          dov = reinterpret_cast<const float*>(dorow)[lane + 64 * t];
+          qv = reinterpret_cast<const float*>(qrow)[lane + 64 * t];
         }
+        av[t] = fmaf(p, dov, av[t]);
+        ak[t] = fmaf(w, qv, ak[t]);
       }
     }
-    const long long o = (long long)b * g.kv_sb + (long long)h * g.kv_sh + (long long)j * g.kv_sn;
+  }
+  const long long o = (long long)b * g.kv_sb + (long long)h * g.kv_sh + (long long)j * g.kv_sn;
 #pragma unroll
-    for (int t = 0; t < PER; ++t) {
-      Elem<T>::store(A.dV, o + lane + 64 * t, av[t]);
-      Elem<T>::store(A.dK, o + lane + 64 * t, ak[t]);
-    }
+  for (int t = 0; t < PER; ++t) {
+    Elem<T>::store(A.dV, o + lane + 64 * t, av[t]);
+    Elem<T>::store(A.dK, o + lane + 64 * t, ak[t]);
   }
 }
 

@@ -386,7 +386,6 @@ int run_bwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
       sa.lcnt = reinterpret_cast<int*>(ws + L.off_lcnt);
       sa.kcount = reinterpret_cast<int*>(ws + L.off_kcount);
       sa.koffs = reinterpret_cast<int*>(ws + L.off_koffs);
-      sa.kcursor = reinterpret_cast<int*>(ws + L.off_kcursor);
       sa.csc_i = reinterpret_cast<int*>(ws + L.off_csc_i);
       sa.csc_pw = reinterpret_cast<float2*>(ws + L.off_csc_pw);
       sa.head_flag = head_flag;
@@ -439,16 +438,18 @@ int run_bwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
     if (!ok) return ENTMAX_ATTN_LAUNCH_FAILED;
     if (lists) {
       hipLaunchKernelGGL(csc_offsets_kernel, dim3((unsigned)(B * H)), dim3(kThreads), 0, st, sa.kcount, sa.koffs,
-                         sa.kcursor, p->Nk, head_flag);
+                         p->Nk, head_flag);
       ok = ok && launch_ok();
       long long slots = (long long)B * H * p->Nq * 2;
       hipLaunchKernelGGL(csc_scatter_kernel, dim3((unsigned)((slots + kThreads - 1) / kThreads)), dim3(kThreads), 0, st,
                          sa);
       ok = ok && launch_ok();
       long long keys = (long long)B * H * p->Nk;
-      hipLaunchKernelGGL((bwd_keys_kernel<T, D>),
-                         dim3((unsigned)((keys + kWaves * kKeysPerWave - 1) / (kWaves * kKeysPerWave))), dim3(kThreads), 0, st,
+      hipLaunchKernelGGL((bwd_keys_kernel<T, D>), dim3((unsigned)((keys + kBlockRows - 1) / kBlockRows)), dim3(kThreads), 0, st,
                          sa);
+      ok = ok && launch_ok();
+      hipLaunchKernelGGL((bwd_long_keys_kernel<T, D>), dim3((unsigned)((keys + kWaves - 1) / kWaves)), dim3(kThreads),
+                         0, st, sa);
       ok = ok && launch_ok();
     }
     record(ev, 6, st);

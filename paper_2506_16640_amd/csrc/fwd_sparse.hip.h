@@ -51,6 +51,10 @@ __device__ __forceinline__ bool collect_sweep(const C& q, const Geom& g, const v
                                               float thr, uint2* mylist, int& cnt, unsigned& n_qk,
                                               unsigned& n_cand_tiles) {
   constexpr int KT = C::KT, NSB = C::NSB;
+  // candidates are the keys with a * dot > thr: in raw units, dot > cut.  Rounding may move a key that
+  // sits on the threshold (probability ~ 0) in or out of the list; the consumers recompute its value.
+  // Scale 0 (a = 0): every visible key ties; they all qualify iff thr < 0.
+  const float cut = !live ? kInf : (q.a > 0.f ? thr / q.a : (thr < 0.f ? -3.0e38f : kInf));
   if (q.tid < 2) ovf[q.tid] = 0;
   Slot slots[1];
   slots[0].base = reinterpret_cast<const char*>(reinterpret_cast<const T*>(K) + (long long)q.b * g.kv_sb +
@@ -75,18 +79,27 @@ __device__ __forceinline__ bool collect_sweep(const C& q, const Geom& g, const v
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[sb][e] = (q.key_of(e) < rel) ? acc[sb][e] : -kInf;
           }
-          float lm = max16(acc[sb]);
-          // masked entries are -inf: a = 0 (scale 0) must not turn them into NaN
-          bool cand = live && (lm > -kInf) && (fmaf(lm, q.a, -thr) > 0.f);
-          if (__ballot(cand) == 0ull) continue;
-          ++n_cand_tiles;
-          if (cand) {
+          // maxima of the four 4-key groups of the lane, then of the block
+          float gm[4];
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-              float d = acc[sb][e];
-              if ((d > -kInf) && (fmaf(d, q.a, -thr) > 0.f)) {
-                if (cnt < CAP) mylist[cnt] = make_uint2((unsigned)(j0 + q.key_of(e)), __float_as_uint(d));
-                ++cnt;
+          for (int gq = 0; gq < 4; ++gq)
+            gm[gq] = fmaxf(fmaxf(acc[sb][4 * gq], acc[sb][4 * gq + 1]), fmaxf(acc[sb][4 * gq + 2], acc[sb][4 * gq + 3]));
+          float lm = fmaxf(fmaxf(gm[0], gm[1]), fmaxf(gm[2], gm[3]));
+          // masked entries are -inf and never exceed the cutoff
+          if (__ballot(lm > cut) == 0ull) continue;
+          ++n_cand_tiles;
+          // only the groups that hold a candidate are looked at element by element
+#pragma unroll
+          for (int gq = 0; gq < 4; ++gq) {
+            if (__ballot(gm[gq] > cut) == 0ull) continue;
+            if (gm[gq] > cut) {
+#pragma unroll
+              for (int rr = 0; rr < 4; ++rr) {
+                float d = acc[sb][4 * gq + rr];
+                if (d > cut) {
+                  if (cnt < CAP) mylist[cnt] = make_uint2((unsigned)(j0 + q.key_of(4 * gq + rr)), __float_as_uint(d));
+                  ++cnt;
+                }
               }
             }
           }
