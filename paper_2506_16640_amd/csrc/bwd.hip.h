@@ -36,7 +36,7 @@ struct BwdArgs {
   float* dscale;    // [B*H*Nq] gradient with respect to scale_i
   uint32_t* mask;   // [B*H][nqg][mask_words] bit jb of row ig: tile (ig, jb) holds some p > 0
   unsigned long long* stats;
-  const int* head_flag;  // NULL: every head; else [B*H], only heads whose flag is set
+  const int* head_flag;  // NULL: every head; else [B*H + 1], only heads whose flag is set; the last entry is the OR
   int nqb, nkb, nqg, mask_words;
 };
 
@@ -362,8 +362,8 @@ __device__ __forceinline__ void bwd_dkv_block(const BwdArgs& A, int bh_, int blk
       sq.fetch_full(Qg + (long long)qt * QT * qrow_bytes);
       sdo.fetch_full(dOg + (long long)qt * QT * qrow_bytes);
     } else {
-      sq.fetch(Qg + (long long)qt * QT * qrow_bytes, rows_left);
-      sdo.fetch(dOg + (long long)qt * QT * qrow_bytes, rows_left);
+      sq.fetch(Qg + (long long)qt * QT * qrow_bytes, rows_left, qrow_bytes);
+      sdo.fetch(dOg + (long long)qt * QT * qrow_bytes, rows_left, qrow_bytes);
     }
     sqt.fetch_full(Qtg + (long long)qt * QT * (long long)sizeof(T));
     sdot.fetch_full(dOtg + (long long)qt * QT * (long long)sizeof(T));
@@ -488,6 +488,7 @@ __device__ __forceinline__ void bwd_dkv_block(const BwdArgs& A, int bh_, int blk
   template <typename T, int D, int AM>                                              \
   __global__ __launch_bounds__(kThreads, OCC) void NAME(BwdArgs A) {                \
     extern __shared__ __attribute__((aligned(16))) char smem[];                     \
+    if (A.head_flag && __builtin_amdgcn_readfirstlane(A.head_flag[A.g.B * A.g.H]) == 0) return; \
     const PairItem it = pair_item(NBLK);                                            \
     for (int part = 0; part < 2; ++part) {                                          \
       const int blk = part ? it.second : it.first;                                  \
@@ -503,23 +504,27 @@ ENTMAX_PAIRED_KERNEL(bwd_mask_kernel, bwd_mask_block, A.nqb, 3)
 template <typename T, int D, int AM>
 __global__ __launch_bounds__(kThreads) void bwd_dq_kernel(BwdArgs A) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
+  if (A.head_flag && __builtin_amdgcn_readfirstlane(A.head_flag[A.g.B * A.g.H]) == 0) return;
   const int item = xcd_remap(blockIdx.x, gridDim.x);
   bwd_dq_block<T, D, AM>(A, item / A.nqb, A.nqb - 1 - item % A.nqb, smem);
 }
 template <typename T, int D, int AM>
 __global__ __launch_bounds__(kThreads) void bwd_dkv_kernel(BwdArgs A) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
+  if (A.head_flag && __builtin_amdgcn_readfirstlane(A.head_flag[A.g.B * A.g.H]) == 0) return;
   const int item = xcd_remap(blockIdx.x, gridDim.x);
   bwd_dkv_block<T, D, AM>(A, item / A.nkb, item % A.nkb, smem);
 }
 
 // ------------------------------------------------------- d beta, d gamma
 
+constexpr int kScaleGradThreads = 1024;
+
 // Per-head parameters: dbeta_h = sum_{b,i} dscale L^gamma, dgamma_h = sum dscale beta L^gamma ln L,
 // L = ln n (eq. (asentmax)); one workgroup per head, fixed summation order.
-__global__ __launch_bounds__(kThreads) void scale_grad_head_kernel(Geom g, const float* dscale, float* dbeta,
+__global__ __launch_bounds__(kScaleGradThreads) void scale_grad_head_kernel(Geom g, const float* dscale, float* dbeta,
                                                                    float* dgamma) {
-  __shared__ float sb_[kThreads], sg_[kThreads];
+  __shared__ float sb_[kScaleGradThreads], sg_[kScaleGradThreads];
   const int h = blockIdx.x, tid = threadIdx.x;
   float ab = 0.f, ag = 0.f;
   if (g.logn_mode == 0) {
@@ -529,13 +534,13 @@ __global__ __launch_bounds__(kThreads) void scale_grad_head_kernel(Geom g, const
     float s = 0.f;
     for (int b = 0; b < g.B; ++b) {
       const float* ds = dscale + ((long long)b * g.H + h) * g.Nq;
-      for (int i = tid; i < g.Nq; i += kThreads) s += ds[i];
+      for (int i = tid; i < g.Nq; i += kScaleGradThreads) s += ds[i];
     }
     ab = s * Lg;
     ag = s * bt * Lg * lnL;
   } else {
     for (int b = 0; b < g.B; ++b) {
-      for (int i = tid; i < g.Nq; i += kThreads) {
+      for (int i = tid; i < g.Nq; i += kScaleGradThreads) {
         float Lg, lnL, bt;
         row_scale(g, b, h, i, row_limit(g, i), &Lg, &lnL, &bt);
         float ds = dscale[((long long)b * g.H + h) * g.Nq + i];
@@ -547,7 +552,7 @@ __global__ __launch_bounds__(kThreads) void scale_grad_head_kernel(Geom g, const
   sb_[tid] = ab;
   sg_[tid] = ag;
   __syncthreads();
-  for (int s = kThreads / 2; s > 0; s >>= 1) {
+  for (int s = kScaleGradThreads / 2; s > 0; s >>= 1) {
     if (tid < s) {
       sb_[tid] += sb_[tid + s];
       sg_[tid] += sg_[tid + s];

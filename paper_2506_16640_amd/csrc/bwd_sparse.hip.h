@@ -25,6 +25,7 @@
 namespace entmax {
 
 constexpr int kBwdCap = 16;  // support entries per lane = per half row
+constexpr int kLongCountOffset = 64;  // the long-key counter sits in a cache line of its own, away from the flags
 constexpr unsigned kNoKey = 0xffffffffu;  // list slot whose entry is not part of the support
 
 struct BwdSparseArgs {
@@ -46,7 +47,9 @@ struct BwdSparseArgs {
   int* koffs;          // [B*H*Nk] exclusive prefix sums of kcount within the head
   int* csc_i;          // [B*H][Nq*2*kBwdCap] query row of each entry, key-major
   float2* csc_pw;      // same order: (p, c dS)
-  int* head_flag;      // [B*H] pre-zeroed; 1: head left to the tiled kernels
+  int* head_flag;      // [B*H + kLongCountOffset + 1] pre-zeroed; 1: head left to the tiled kernels; entry B*H: some head is;
+                       // entry B*H + kLongCountOffset: number of keys on the long-segment list
+  int* long_keys;      // [B*H*Nk] keys with more than kSortedKeyEntries entries
   unsigned long long* stats;
   int nqb;
 };
@@ -71,7 +74,10 @@ __device__ __forceinline__ void bwd_lists_block(const BwdSparseArgs& A, int bh_,
   bool fits = true;
   if (q.block_lim > 0) fits = collect_sweep<C, T, D, kBwdCap>(q, g, A.K, smem, ovf, live, tau, mylist, cnt, n_qk, n_cand_tiles);
   if (!fits) {
-    if (q.tid == 0) A.head_flag[q.bh] = 1;
+    if (q.tid == 0) {
+      A.head_flag[q.bh] = 1;
+      A.head_flag[g.B * g.H] = 1;
+    }
   } else if (q.valid) {
     A.lcnt[row_idx * 2 + q.hh] = cnt;
   }
@@ -299,9 +305,19 @@ __global__ __launch_bounds__(kThreads, 3) void bwd_keys_kernel(BwdSparseArgs A) 
   on = on && A.head_flag[bh] == 0;
   const int b = bh / g.H, h = bh % g.H;
   int n = on ? A.kcount[key] : 0;
-  if (n > kSortedKeyEntries) {  // longer segments belong to bwd_long_keys_kernel
-    on = false;
-    n = 0;
+  {  // longer segments belong to bwd_long_keys_kernel: one list append per wave
+    const bool is_long = n > kSortedKeyEntries && hh == 0;
+    const unsigned long long lm = __ballot(is_long);
+    if (lm != 0ull) {
+      int first = 0;
+      if (lane == 0) first = atomicAdd(&A.head_flag[g.B * g.H + kLongCountOffset], __builtin_popcountll(lm));
+      first = __shfl(first, 0);
+      if (is_long) A.long_keys[first + __builtin_popcountll(lm & ((1ull << lane) - 1ull))] = (int)key;
+    }
+    if (n > kSortedKeyEntries) {
+      on = false;
+      n = 0;
+    }
   }
   const long long base = (long long)bh * g.Nq * 2 * kBwdCap + (on ? A.koffs[key] : 0);
   const long long q_base = (long long)b * g.q_sb + (long long)h * g.q_sh;
@@ -362,12 +378,12 @@ __global__ __launch_bounds__(kThreads) void bwd_long_keys_kernel(BwdSparseArgs A
   constexpr int PER = D / 64;
   const Geom& g = A.g;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-  const long long key = (long long)blockIdx.x * kWaves + wave;
-  if (key >= (long long)g.B * g.H * g.Nk) return;
+  // persistent grid: the waves share out the list bwd_keys_kernel made
+  const int nlong = __builtin_amdgcn_readfirstlane(A.head_flag[g.B * g.H + kLongCountOffset]);
+  for (int idx = blockIdx.x * kWaves + wave; idx < nlong; idx += gridDim.x * kWaves) {
+  const long long key = __builtin_amdgcn_readfirstlane(A.long_keys[idx]);
   const int n = __builtin_amdgcn_readfirstlane(A.kcount[key]);
-  if (n <= kSortedKeyEntries) return;
   const int bh = (int)(key / g.Nk), j = (int)(key % g.Nk);
-  if (__builtin_amdgcn_readfirstlane(A.head_flag[bh]) != 0) return;
   const int b = bh / g.H, h = bh % g.H;
   const long long base = (long long)bh * g.Nq * 2 * kBwdCap + __builtin_amdgcn_readfirstlane(A.koffs[key]);
   const long long q_base = (long long)b * g.q_sb + (long long)h * g.q_sh;
@@ -384,24 +400,36 @@ __global__ __launch_bounds__(kThreads) void bwd_long_keys_kernel(BwdSparseArgs A
     int si = __builtin_amdgcn_ds_permute(rank << 2, ci);
     float sp = __int_as_float(__builtin_amdgcn_ds_permute(rank << 2, __float_as_int(cpw.x)));
     float sw = __int_as_float(__builtin_amdgcn_ds_permute(rank << 2, __float_as_int(cpw.y)));
-#pragma unroll 4
-    for (int k = 0; k < m; ++k) {
-      int i = __shfl(si, k);
-      float p = __shfl(sp, k), w = __shfl(sw, k);
-      const T* dorow = reinterpret_cast<const T*>(A.dO) + q_base + (long long)i * g.q_sn;
-      const T* qrow = reinterpret_cast<const T*>(A.Q) + q_base + (long long)i * g.q_sn;
+    // rows, weights and addresses are wave-uniform (readlane): batches of 8 entries keep 16 row
+    // loads in flight
+    for (int k0 = 0; k0 < m; k0 += 8) {
+      float dov[8][PER], qv[8][PER], pp[8], ww[8];
 #pragma unroll
-      for (int t = 0; t < PER; ++t) {
-        float dov, qv;
-        if constexpr (sizeof(T) == 2) {
-          dov = __uint_as_float((unsigned)reinterpret_cast<const unsigned short*>(dorow)[lane + 64 * t] << 16);
-          qv = __uint_as_float((unsigned)reinterpret_cast<const unsigned short*>(qrow)[lane + 64 * t] << 16);
-        } else {
-          dov = reinterpret_cast<const float*>(dorow)[lane + 64 * t];
-          qv = reinterpret_cast<const float*>(qrow)[lane + 64 * t];
+      for (int u = 0; u < 8; ++u) {
+        const int k = min(k0 + u, m - 1);
+        const int i = __builtin_amdgcn_readlane(si, k);
+        pp[u] = (k0 + u < m) ? __int_as_float(__builtin_amdgcn_readlane(__float_as_int(sp), k)) : 0.f;
+        ww[u] = (k0 + u < m) ? __int_as_float(__builtin_amdgcn_readlane(__float_as_int(sw), k)) : 0.f;
+        const T* dorow = reinterpret_cast<const T*>(A.dO) + q_base + (long long)i * g.q_sn;
+        const T* qrow = reinterpret_cast<const T*>(A.Q) + q_base + (long long)i * g.q_sn;
+#pragma unroll
+        for (int t = 0; t < PER; ++t) {
+          if constexpr (sizeof(T) == 2) {
+            dov[u][t] = __uint_as_float((unsigned)reinterpret_cast<const unsigned short*>(dorow)[lane + 64 * t] << 16);
+            qv[u][t] = __uint_as_float((unsigned)reinterpret_cast<const unsigned short*>(qrow)[lane + 64 * t] << 16);
+          } else {
+            dov[u][t] = reinterpret_cast<const float*>(dorow)[lane + 64 * t];
+            qv[u][t] = reinterpret_cast<const float*>(qrow)[lane + 64 * t];
+          }
         }
-        av[t] = fmaf(p, dov, av[t]);
-        ak[t] = fmaf(w, qv, ak[t]);
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+#pragma unroll
+        for (int t = 0; t < PER; ++t) {
+          av[t] = fmaf(pp[u], dov[u][t], av[t]);
+          ak[t] = fmaf(ww[u], qv[u][t], ak[t]);
+        }
       }
     }
   }
@@ -410,6 +438,7 @@ __global__ __launch_bounds__(kThreads) void bwd_long_keys_kernel(BwdSparseArgs A
   for (int t = 0; t < PER; ++t) {
     Elem<T>::store(A.dV, o + lane + 64 * t, av[t]);
     Elem<T>::store(A.dK, o + lane + 64 * t, ak[t]);
+  }
   }
 }
 

@@ -219,7 +219,7 @@ struct FragOff<float> {
 
 // Register staging for one tile: init() fixes, per thread, which 16-byte chunks
 // it moves (global byte offset inside the tile, swizzled LDS offset); fetch()
-// issues the global loads (rows at or beyond valid_rows read as zero),
+// issues the global loads of a ragged tile (rows at or beyond valid_rows repeat the last valid row),
 // fetch_full() does the same for a tile known to lie wholly inside the tensor,
 // commit() writes the staged chunks to LDS.
 template <typename TileT>
@@ -244,14 +244,16 @@ struct Stage {
 #pragma unroll
     for (int it = 0; it < kPer; ++it) r[it] = *reinterpret_cast<const u32x4_t*>(gtile + goff[it]);
   }
-  __device__ __forceinline__ void fetch(const char* gtile, int valid_rows) {
+  // Ragged last tile: rows at or beyond valid_rows re-read the last valid row instead of being
+  // zero-filled.  Every consumer masks those rows (they lie beyond the tensor), and a finite
+  // stand-in keeps "0 x value" products finite; above all the loads stay unconditional, so the
+  // compiler has no reason to wait for them before the tile that is computed meanwhile.
+  __device__ __forceinline__ void fetch(const char* gtile, int valid_rows, long long grow_bytes) {
 #pragma unroll
     for (int it = 0; it < kPer; ++it) {
-      int row = row0 + it * (kThreads / TileT::kCpr);
-      if (row < valid_rows)
-        r[it] = *reinterpret_cast<const u32x4_t*>(gtile + goff[it]);
-      else
-        r[it] = u32x4_t{0u, 0u, 0u, 0u};
+      int row = min(row0 + it * (kThreads / TileT::kCpr), valid_rows - 1);
+      uint32_t off = (uint32_t)row * (uint32_t)grow_bytes + (goff[0] - (uint32_t)row0 * (uint32_t)grow_bytes);
+      r[it] = *reinterpret_cast<const u32x4_t*>(gtile + off);
     }
   }
   __device__ __forceinline__ void commit(char* tile) const {

@@ -29,7 +29,7 @@ struct Layout {
   long long q_sb, q_sh, q_sn, kv_sb, kv_sh, kv_sn;
   // workspace offsets
   size_t off_vt, off_cand, off_flcnt, off_bounds, off_flags, off_kt, off_qt, off_dot, off_mu, off_crow, off_dscale, off_mask,
-      off_jlist, off_pw, off_lcnt, off_kcount, off_koffs, off_kcursor, off_csc_i, off_csc_pw, off_hflag, total_fwd,
+      off_jlist, off_pw, off_lcnt, off_kcount, off_koffs, off_kcursor, off_csc_i, off_csc_pw, off_hflag, off_longkeys, total_fwd,
       total_bwd;
 };
 
@@ -91,7 +91,7 @@ Layout make_layout(const entmax_attn_params* p) {
   L.off_flcnt = L.off_cand + cand_bytes;
   L.off_bounds = L.off_flcnt + align_up(bh * (size_t)p->Nq * 2 * sizeof(int));
   L.off_flags = L.off_bounds + align_up(bh * (size_t)p->Nq * sizeof(float2));
-  L.total_fwd = L.off_flags + align_up((bh * (size_t)L.nqb + bh) * sizeof(int));
+  L.total_fwd = L.off_flags + align_up((bh * (size_t)L.nqb + bh + 1) * sizeof(int));
   size_t o = 0;
   L.off_kt = o;
   o += kt_bytes;
@@ -127,7 +127,9 @@ Layout make_layout(const entmax_attn_params* p) {
   L.off_csc_pw = o;
   o += align_up(rows * 2 * kBwdCap * sizeof(float2));
   L.off_hflag = o;
-  o += align_up(bh * sizeof(int));
+  o += align_up((bh + kLongCountOffset + 1) * sizeof(int));
+  L.off_longkeys = o;
+  o += key_bytes;
   L.total_bwd = o;
   return L;
 }
@@ -268,7 +270,7 @@ int run_fwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
   const int nblocks = p->B * p->H * ((L.nqb + 1) / 2);  // workgroups take query blocks in pairs
   const bool lists = p->path == 0;
   if (lists) {
-    if (!zero_words(head_flag, (size_t)p->B * p->H * sizeof(int), st)) return ENTMAX_ATTN_LAUNCH_FAILED;
+    if (!zero_words(head_flag, ((size_t)p->B * p->H + 1) * sizeof(int), st)) return ENTMAX_ATTN_LAUNCH_FAILED;
     FwdSparseArgs sa;
     sa.g = make_geom(p, L, beta, gamma);
     sa.Q = Q;
@@ -301,6 +303,7 @@ int run_fwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
   a.nqb = L.nqb;
   a.mask_words = L.mask_words;
   a.dense_flag = lists ? dense_flag : nullptr;
+  a.any_flag = lists ? head_flag + (size_t)p->B * p->H : nullptr;
   if (!launch_fwd_am<T, D>(a, alpha_mode(p->alpha), nblocks, st)) return ENTMAX_ATTN_LAUNCH_FAILED;
   record(ev, 3, st);
   return ENTMAX_ATTN_OK;
@@ -389,9 +392,10 @@ int run_bwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
       sa.csc_i = reinterpret_cast<int*>(ws + L.off_csc_i);
       sa.csc_pw = reinterpret_cast<float2*>(ws + L.off_csc_pw);
       sa.head_flag = head_flag;
+      sa.long_keys = reinterpret_cast<int*>(ws + L.off_longkeys);
       sa.stats = reinterpret_cast<unsigned long long*>(stats);
       sa.nqb = L.nqb;
-      ok = ok && zero_words(head_flag, (size_t)B * H * sizeof(int), st);
+      ok = ok && zero_words(head_flag, ((size_t)B * H + kLongCountOffset + 1) * sizeof(int), st);
       ok = ok && zero_words(sa.kcount, (size_t)B * H * p->Nk * sizeof(int), st);
       ok = ok && launch_bwd_rows_am<T, D>(sa, alpha_mode(p->alpha), B * H * ((L.nqb + 1) / 2), st);
       if (!ok) return ENTMAX_ATTN_LAUNCH_FAILED;
@@ -448,15 +452,15 @@ int run_bwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
       hipLaunchKernelGGL((bwd_keys_kernel<T, D>), dim3((unsigned)((keys + kBlockRows - 1) / kBlockRows)), dim3(kThreads), 0, st,
                          sa);
       ok = ok && launch_ok();
-      hipLaunchKernelGGL((bwd_long_keys_kernel<T, D>), dim3((unsigned)((keys + kWaves - 1) / kWaves)), dim3(kThreads),
-                         0, st, sa);
+      hipLaunchKernelGGL((bwd_long_keys_kernel<T, D>), dim3(1024u), dim3(kThreads), 0, st, sa);
       ok = ok && launch_ok();
     }
     record(ev, 6, st);
   }
   if (!ok) return ENTMAX_ATTN_LAUNCH_FAILED;
   if (p->scale_layout == 1) {
-    hipLaunchKernelGGL(scale_grad_head_kernel, dim3((unsigned)H), dim3(kThreads), 0, st, g, dscale, dbeta, dgamma);
+    hipLaunchKernelGGL(scale_grad_head_kernel, dim3((unsigned)H), dim3(kScaleGradThreads), 0, st, g, dscale, dbeta,
+                       dgamma);
     ok = launch_ok();
   } else if (p->scale_layout == 2) {
     long long rows = (long long)B * H * p->Nq;

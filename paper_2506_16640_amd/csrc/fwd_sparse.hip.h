@@ -38,7 +38,8 @@ struct FwdSparseArgs {
   int* lcnt;        // [B*H*Nq][2] list lengths
   float2* bounds;   // [B*H*Nq] (tau_lb, right end of the bracket)
   int* dense_flag;  // [B*H*nqb] 1: block left to the tiled kernel
-  int* head_flag;   // [B*H] pre-zeroed; set to 1 when some block of the head is left to the tiled kernel
+  int* head_flag;   // [B*H + 1] pre-zeroed; set to 1 when some block of the head is left to the tiled kernel;
+                    // the last entry is set when any head is
   unsigned long long* stats;
   int nqb;
 };
@@ -202,6 +203,7 @@ __device__ __forceinline__ void fwd_lists_block(const FwdSparseArgs& A, int bh_,
     if (q.tid == 0) {
       A.dense_flag[flag_idx] = 1;
       A.head_flag[q.bh] = 1;
+      A.head_flag[g.B * g.H] = 1;
     }
   } else {
     if (q.tid == 0) A.dense_flag[flag_idx] = 0;

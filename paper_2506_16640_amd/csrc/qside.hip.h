@@ -153,20 +153,20 @@ __device__ __forceinline__ void sweep_tiles(char* smem, const Slot* slots, int n
     if constexpr ((TMASK & 1) != 0) {
       s0.fetch_full(tile_ptr(0, true, kt));
     } else {
-      if (full) s0.fetch_full(tile_ptr(0, false, kt)); else s0.fetch(tile_ptr(0, false, kt), rows_left);
+      if (full) s0.fetch_full(tile_ptr(0, false, kt)); else s0.fetch(tile_ptr(0, false, kt), rows_left, slots[0].row_bytes);
     }
     if constexpr (NSLOT > 1) {
       if constexpr ((TMASK & 2) != 0) {
         s1.fetch_full(tile_ptr(1, true, kt));
       } else {
-        if (full) s1.fetch_full(tile_ptr(1, false, kt)); else s1.fetch(tile_ptr(1, false, kt), rows_left);
+        if (full) s1.fetch_full(tile_ptr(1, false, kt)); else s1.fetch(tile_ptr(1, false, kt), rows_left, slots[1].row_bytes);
       }
     }
     if constexpr (NSLOT > 2) {
       if constexpr ((TMASK & 4) != 0) {
         s2.fetch_full(tile_ptr(2, true, kt));
       } else {
-        if (full) s2.fetch_full(tile_ptr(2, false, kt)); else s2.fetch(tile_ptr(2, false, kt), rows_left);
+        if (full) s2.fetch_full(tile_ptr(2, false, kt)); else s2.fetch(tile_ptr(2, false, kt), rows_left, slots[2].row_bytes);
       }
     }
   };
