@@ -69,10 +69,6 @@ __device__ __forceinline__ void bwd_mask_block(const BwdArgs& A, int bh_, int bl
   sweep_tiles<C, T, D, 1, 0>(
       smem, slots, q.ntiles, g.Nk, q.tid, [](int) { return true; },
       [&](int kt, const char* tl) {
-#ifdef ENTMAX_EXP_NO_COMPUTE
-        n_vis += __builtin_popcount(q.visible_bits(kt));
-        return;
-#endif
         if ((kt + 1) * KT <= q.wave_lim_min) {
           // interior tile: every key is visible to every row of the wave
           f32x16_t acc[NSB];

@@ -110,7 +110,8 @@ __device__ __forceinline__ bool solve_step(const RowSums& s, float r, float& tau
   } else if (AM == 3) {
     f = s.s2 - 1.f;
     // f' = -4 s1, f'' = 12 s0;  Halley: t = -2 f f' / (2 f'^2 - f f'') = 2 f s1 / (8 s1^2 - 3 f s0)
-    t = 2.f * f * s.s1 / (8.f * s.s1 * s.s1 - 3.f * f * s.s0);
+    float den = 8.f * s.s1 * s.s1 - 3.f * f * s.s0;
+    t = (den != 0.f) ? 2.f * f * s.s1 / den : -kInf;  // no positive term at all: leave the bracket (bisect)
   } else {
     f = s.s1 - 1.f;
     t = f / (r * s.s0);
@@ -125,7 +126,7 @@ __device__ __forceinline__ bool solve_step(const RowSums& s, float r, float& tau
     return true;
   }
   float tol = 2e-6f * fmaxf(1.f, fabsf(tau));
-  bool in = (tn >= lo) && (tn <= hi);  // false for NaN
+  bool in = (tn >= lo) && (tn <= hi);
   if (!in) tn = 0.5f * (lo + hi);
   bool fin = (fabsf(tn - tau) <= tol) || (hi - lo <= tol);
   tau = tn;

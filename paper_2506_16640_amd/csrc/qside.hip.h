@@ -189,14 +189,10 @@ __device__ __forceinline__ void sweep_tiles(char* smem, const Slot* slots, int n
   int cur = 0;
   while (kt < ntiles) {
     int nxt = abort(kt) ? ntiles : next_needed(kt + 1);
-#ifdef ENTMAX_EXP_NO_LOADS
-    body(kt, smem + cur * (NSLOT * TB));
-#else
     if (nxt < ntiles) fetch(nxt);
     body(kt, smem + cur * (NSLOT * TB));
     if (nxt < ntiles) commit(smem + (cur ^ 1) * (NSLOT * TB));
     __syncthreads();
-#endif
     cur ^= 1;
     kt = nxt;
   }
