@@ -278,10 +278,12 @@ __global__ __launch_bounds__(kThreads) void csc_scatter_kernel(BwdSparseArgs A) 
   long long base = (long long)bh * g.Nq * 2 * kBwdCap;
   for (int e = 0; e < cnt; ++e) {
     uint2 en = A.jlist[slot * kBwdCap + e];
-    if (en.x == kNoKey) continue;
+    if (en.x >= (unsigned)g.Nk) continue;  // kNoKey, or anything that is not a key
     int pos = A.koffs[(long long)bh * g.Nk + en.x] + (int)en.y;
-    A.csc_i[base + pos] = i;
-    A.csc_pw[base + pos] = A.pw[slot * kBwdCap + e];
+    if (pos >= 0 && pos < g.Nq * 2 * kBwdCap) {  // holds by construction; keeps any stray entry inside the head
+      A.csc_i[base + pos] = i;
+      A.csc_pw[base + pos] = A.pw[slot * kBwdCap + e];
+    }
   }
 }
 
@@ -327,6 +329,7 @@ __global__ __launch_bounds__(kThreads, 3) void bwd_keys_kernel(BwdSparseArgs A) 
 #pragma unroll
   for (int t = 0; t < DH; ++t) dv[t] = dk[t] = 0.f;
   auto add_entry = [&](int i, float2 pw) {
+    i = min(max(i, 0), g.Nq - 1);  // a valid row by construction; never index outside the tensor
     float rd[DH], rq[DH];
     load_row_f32<T>(dObh + (long long)i * g.q_sn, DH, rd);
     load_row_f32<T>(Qbh + (long long)i * g.q_sn, DH, rq);
@@ -407,7 +410,7 @@ __global__ __launch_bounds__(kThreads) void bwd_long_keys_kernel(BwdSparseArgs A
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
         const int k = min(k0 + u, m - 1);
-        const int i = __builtin_amdgcn_readlane(si, k);
+        const int i = min(max(__builtin_amdgcn_readlane(si, k), 0), g.Nq - 1);
         pp[u] = (k0 + u < m) ? __int_as_float(__builtin_amdgcn_readlane(__float_as_int(sp), k)) : 0.f;
         ww[u] = (k0 + u < m) ? __int_as_float(__builtin_amdgcn_readlane(__float_as_int(sw), k)) : 0.f;
         const T* dorow = reinterpret_cast<const T*>(A.dO) + q_base + (long long)i * g.q_sn;
