@@ -67,9 +67,13 @@ __device__ __forceinline__ bool collect_sweep(const C& q, const Geom& g, const v
         const bool interior = (kt + 1) * KT <= q.wave_lim_min;
         const uint32_t act = interior ? ((1u << NSB) - 1u) : q.visible_bits(kt);
         f32x16_t acc[NSB];
+        if (interior) {
+          q.scores_all(tl, acc);
+        } else {
 #pragma unroll
-        for (int sb = 0; sb < NSB; ++sb)
-          if (act & (1u << sb)) acc[sb] = q.scores(tl, sb);
+          for (int sb = 0; sb < NSB; ++sb)
+            if (act & (1u << sb)) acc[sb] = q.scores(tl, sb);
+        }
 #pragma unroll
         for (int sb = 0; sb < NSB; ++sb) {
           if (!(act & (1u << sb))) continue;
@@ -150,8 +154,7 @@ __device__ __forceinline__ void fwd_lists_block(const FwdSparseArgs& A, int bh_,
       [&](int kt, const char* tl) {
         if ((kt + 1) * KT <= q.wave_lim_min) {
           f32x16_t acc[NSB];
-#pragma unroll
-          for (int sb = 0; sb < NSB; ++sb) acc[sb] = q.scores(tl, sb);
+          q.scores_all(tl, acc);
 #pragma unroll
           for (int sb = 0; sb < NSB; ++sb) {
             float lm = max16(acc[sb]);

@@ -84,6 +84,42 @@ struct QCtx {
     return acc;
   }
 
+  // All NSB blocks of a tile.  The K fragments of block sb+1 are requested before the products of
+  // block sb are issued, so that LDS latency overlaps the matrix pipeline inside one wave.
+  __device__ __forceinline__ void scores_all(const char* ktile, f32x16_t (&acc)[NSB]) const {
+    if constexpr (NC > 4) {  // two fragment sets would not fit the register budget
+#pragma unroll
+      for (int sb = 0; sb < NSB; ++sb) acc[sb] = scores(ktile, sb);
+      return;
+    }
+    Frag<T> kf[2][NC];
+#pragma unroll
+    for (int cc = 0; cc < NC; ++cc) kf[0][cc] = koff[cc].load(ktile, 0);
+#pragma unroll
+    for (int sb = 0; sb < NSB; ++sb) {
+      if (sb + 1 < NSB) {
+#pragma unroll
+        for (int cc = 0; cc < NC; ++cc) kf[(sb + 1) & 1][cc] = koff[cc].load(ktile, (sb + 1) * 32 * KTile::kRowBytes);
+      }
+      f32x16_t a0 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int cc = 0; cc < NC; ++cc) a0 = Elem<T>::mma(kf[sb & 1][cc], qf[cc], a0);
+      acc[sb] = a0;
+    }
+    // keep that order through instruction scheduling: one LDS read behind each matrix instruction
+    if constexpr (sizeof(T) == 2) {
+      __builtin_amdgcn_sched_group_barrier(0x100, NC, 0);
+#pragma unroll
+      for (int sb = 0; sb < NSB; ++sb) {
+#pragma unroll
+        for (int cc = 0; cc < NC; ++cc) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          if (sb + 1 < NSB) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+      }
+    }
+  }
+
   // bits sb of the result: 32-key block sb of tile kt holds a key some row of this wave may see
   __device__ __forceinline__ uint32_t visible_bits(int kt) const {
     int nvis = (wave_lim_max - kt * KT + 31) >> 5;  // blocks of the tile that start below the wave's largest limit
