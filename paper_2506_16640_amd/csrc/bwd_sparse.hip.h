@@ -42,6 +42,7 @@ struct BwdSparseArgs {
   uint2* jlist;        // [B*H*Nq][2][kBwdCap] (key index, raw dot product bits); bwd_rows_kernel replaces the
                        // second word by the entry's arrival number within its key (key index kNoKey: dropped)
   float2* pw;          // [B*H*Nq][2][kBwdCap] (p_ij, c_i dS_ij)
+  void* cells;         // sweep scratch: per workgroup and lane, kBwdCap cells
   int* lcnt;           // [B*H*Nq][2] entries per half row
   int* kcount;         // [B*H*Nk] entries per key (zeroed before bwd_rows_kernel)
   int* koffs;          // [B*H*Nk] exclusive prefix sums of kcount within the head
@@ -72,7 +73,7 @@ __device__ __forceinline__ void bwd_lists_block(const BwdSparseArgs& A, int bh_,
   int cnt = 0;
   unsigned n_qk = 0, n_cand_tiles = 0;
   bool fits = true;
-  if (q.block_lim > 0) fits = collect_sweep<C, T, D, kBwdCap>(q, g, A.K, smem, ovf, live, tau, mylist, cnt, n_qk, n_cand_tiles);
+  if (q.block_lim > 0) fits = collect_sweep<C, T, D, kBwdCap>(q, g, A.K, smem, ovf, live, tau, A.cells, mylist, cnt, n_qk, n_cand_tiles);
   if (!fits) {
     if (q.tid == 0) {
       A.head_flag[q.bh] = 1;

@@ -29,7 +29,7 @@ struct Layout {
   long long q_sb, q_sh, q_sn, kv_sb, kv_sh, kv_sn;
   // workspace offsets
   size_t off_vt, off_cand, off_flcnt, off_bounds, off_flags, off_kt, off_qt, off_dot, off_mu, off_crow, off_dscale, off_mask,
-      off_jlist, off_pw, off_lcnt, off_kcount, off_koffs, off_kcursor, off_csc_i, off_csc_pw, off_hflag, off_longkeys, total_fwd,
+      off_jlist, off_pw, off_lcnt, off_kcount, off_koffs, off_kcursor, off_csc_i, off_csc_pw, off_hflag, off_longkeys, off_fcells, off_bcells, total_fwd,
       total_bwd;
 };
 
@@ -91,7 +91,9 @@ Layout make_layout(const entmax_attn_params* p) {
   L.off_flcnt = L.off_cand + cand_bytes;
   L.off_bounds = L.off_flcnt + align_up(bh * (size_t)p->Nq * 2 * sizeof(int));
   L.off_flags = L.off_bounds + align_up(bh * (size_t)p->Nq * sizeof(float2));
-  L.total_fwd = L.off_flags + align_up((bh * (size_t)L.nqb + bh + 1) * sizeof(int));
+  L.off_fcells = L.off_flags + align_up((bh * (size_t)L.nqb + bh + 1) * sizeof(int));
+  const size_t list_groups = bh * (size_t)((L.nqb + 1) / 2);  // workgroups of the list sweeps
+  L.total_fwd = L.off_fcells + align_up(list_groups * CellBuf<kCandCap>::kBytesPerWorkgroup);
   size_t o = 0;
   L.off_kt = o;
   o += kt_bytes;
@@ -130,6 +132,8 @@ Layout make_layout(const entmax_attn_params* p) {
   o += align_up((bh + kLongCountOffset + 1) * sizeof(int));
   L.off_longkeys = o;
   o += key_bytes;
+  L.off_bcells = o;
+  o += align_up(list_groups * CellBuf<kBwdCap>::kBytesPerWorkgroup);
   L.total_bwd = o;
   return L;
 }
@@ -279,6 +283,7 @@ int run_fwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
     sa.O = O;
     sa.tau = tau;
     sa.cand = reinterpret_cast<uint2*>(ws + L.off_cand);
+    sa.cells = ws + L.off_fcells;
     sa.lcnt = reinterpret_cast<int*>(ws + L.off_flcnt);
     sa.bounds = reinterpret_cast<float2*>(ws + L.off_bounds);
     sa.dense_flag = dense_flag;
@@ -385,6 +390,7 @@ int run_bwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
       sa.dV = dV;
       sa.dscale = dscale;
       sa.jlist = reinterpret_cast<uint2*>(ws + L.off_jlist);
+      sa.cells = ws + L.off_bcells;
       sa.pw = reinterpret_cast<float2*>(ws + L.off_pw);
       sa.lcnt = reinterpret_cast<int*>(ws + L.off_lcnt);
       sa.kcount = reinterpret_cast<int*>(ws + L.off_kcount);

@@ -35,6 +35,7 @@ struct FwdSparseArgs {
   void* O;
   float* tau;
   uint2* cand;      // [B*H*Nq][2][kCandCap] (key index, raw dot product bits)
+  void* cells;      // sweep scratch: per workgroup and lane, kCandCap cells (see CellBuf)
   int* lcnt;        // [B*H*Nq][2] list lengths
   float2* bounds;   // [B*H*Nq] (tau_lb, right end of the bracket)
   int* dense_flag;  // [B*H*nqb] 1: block left to the tiled kernel
@@ -44,19 +45,43 @@ struct FwdSparseArgs {
   int nqb;
 };
 
+// A cell is the group of kCellKeys consecutive accumulator registers of a lane (keys j, j+1, j+2, j+3 of
+// one row, and 8 keys further for each additional group).  During a sweep a lane appends whole cells
+// -- all their raw scores and the first key index -- to a private strip of scratch memory whenever the
+// cell maximum passes the cutoff: one short divergent region per cell instead of one per score.  After
+// the sweep each lane walks its own cells and writes the scores above the cutoff to its list.
+constexpr int kCellGroups = 1;              // 4-key accumulator groups per cell
+constexpr int kCellKeys = 4 * kCellGroups;
+constexpr int kCellsPerBlock = 16 / kCellKeys;
+
+template <int CAP>
+struct CellBuf {
+  f32x4_t* d;  // [CAP][kCellGroups] raw scores
+  int* j;      // [CAP] key of the cell's first score
+  static constexpr size_t kBytesPerWorkgroup = (size_t)kThreads * CAP * (16 * kCellGroups + 4);
+  __device__ __forceinline__ void init(void* base, int tid) {
+    char* wg = reinterpret_cast<char*>(base) + (size_t)blockIdx.x * kBytesPerWorkgroup;
+    d = reinterpret_cast<f32x4_t*>(wg) + (size_t)tid * CAP * kCellGroups;
+    j = reinterpret_cast<int*>(wg + (size_t)kThreads * CAP * 16 * kCellGroups) + (size_t)tid * CAP;
+  }
+};
+
 // One sweep over the visible key tiles of the block: every key whose shifted score
-// a * dot - thr is positive is appended to the lane's list.  Returns false (workgroup-uniform) if
-// some list overflowed; the sweep is abandoned early in that case.
+// a * dot - thr is positive ends up in the lane's list.  Returns false (workgroup-uniform) if
+// some list overflowed; the sweep is abandoned early in that case.  ovf: three ints of LDS.
 template <typename C, typename T, int D, int CAP>
 __device__ __forceinline__ bool collect_sweep(const C& q, const Geom& g, const void* K, char* tiles, int* ovf, bool live,
-                                              float thr, uint2* mylist, int& cnt, unsigned& n_qk,
+                                              float thr, void* cells, uint2* mylist, int& cnt, unsigned& n_qk,
                                               unsigned& n_cand_tiles) {
   constexpr int KT = C::KT, NSB = C::NSB;
   // candidates are the keys with a * dot > thr: in raw units, dot > cut.  Rounding may move a key that
   // sits on the threshold (probability ~ 0) in or out of the list; the consumers recompute its value.
   // Scale 0 (a = 0): every visible key ties; they all qualify iff thr < 0.
   const float cut = !live ? kInf : (q.a > 0.f ? thr / q.a : (thr < 0.f ? -3.0e38f : kInf));
-  if (q.tid < 2) ovf[q.tid] = 0;
+  if (q.tid < 3) ovf[q.tid] = 0;
+  CellBuf<CAP> cb;
+  cb.init(cells, q.tid);
+  int ncell = 0;
   Slot slots[1];
   slots[0].base = reinterpret_cast<const char*>(reinterpret_cast<const T*>(K) + (long long)q.b * g.kv_sb +
                                                 (long long)q.h * g.kv_sh);
@@ -93,28 +118,51 @@ __device__ __forceinline__ bool collect_sweep(const C& q, const Geom& g, const v
           // masked entries are -inf and never exceed the cutoff
           if (__ballot(lm > cut) == 0ull) continue;
           ++n_cand_tiles;
-          // only the groups that hold a candidate are looked at element by element
 #pragma unroll
-          for (int gq = 0; gq < 4; ++gq) {
-            if (__ballot(gm[gq] > cut) == 0ull) continue;
-            if (gm[gq] > cut) {
+          for (int cl = 0; cl < kCellsPerBlock; ++cl) {
+            float cm = gm[cl * kCellGroups];
 #pragma unroll
-              for (int rr = 0; rr < 4; ++rr) {
-                float d = acc[sb][4 * gq + rr];
-                if (d > cut) {
-                  if (cnt < CAP) mylist[cnt] = make_uint2((unsigned)(j0 + q.key_of(4 * gq + rr)), __float_as_uint(d));
-                  ++cnt;
-                }
+            for (int u = 1; u < kCellGroups; ++u) cm = fmaxf(cm, gm[cl * kCellGroups + u]);
+            if (cm > cut) {
+              // a strip that is full keeps overwriting its last cell; the flag below discards the lists
+              const int slot = min(ncell, CAP - 1);
+#pragma unroll
+              for (int u = 0; u < kCellGroups; ++u) {
+                const int e0 = 4 * (cl * kCellGroups + u);
+                cb.d[slot * kCellGroups + u] = f32x4_t{acc[sb][e0], acc[sb][e0 + 1], acc[sb][e0 + 2], acc[sb][e0 + 3]};
               }
+              cb.j[slot] = j0 + q.key_of(4 * cl * kCellGroups);
+              ++ncell;
             }
           }
-          if (__ballot(cnt > CAP) != 0ull && q.lane == 0) ovf[kt & 1] = 1;
+          if (__ballot(ncell > CAP) != 0ull && q.lane == 0) ovf[kt & 1] = 1;
         }
       },
       // flags of the previous tile's parity were final before the barrier that ended that tile
       [&](int kt) { return kt > 0 && ovf[(kt - 1) & 1] != 0; });
   // the sweep ended on a barrier: both flags are final
-  return (ovf[0] | ovf[1]) == 0;
+  bool fits = (ovf[0] | ovf[1]) == 0;
+  if (fits) {
+    // a cell holds at most kCellKeys candidates, so there are at least as many candidates as cells
+    for (int k = 0; k < ncell; ++k) {
+      const int jc = cb.j[k];
+#pragma unroll
+      for (int u = 0; u < kCellGroups; ++u) {
+        const f32x4_t dv = cb.d[k * kCellGroups + u];
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) {
+          if (dv[rr] > cut) {
+            if (cnt < CAP) mylist[cnt] = make_uint2((unsigned)(jc + 8 * u + rr), __float_as_uint(dv[rr]));
+            ++cnt;
+          }
+        }
+      }
+    }
+    if (cnt > CAP) ovf[2] = 1;
+    __syncthreads();
+    fits = ovf[2] == 0;
+  }
+  return fits;
 }
 
 template <typename T, int D, int AM>
@@ -123,7 +171,7 @@ __device__ __forceinline__ void fwd_lists_block(const FwdSparseArgs& A, int bh_,
   constexpr int KT = C::KT, NSB = C::NSB, TB = C::kTileBytes;
   const Geom& g = A.g;
   char* tiles = smem;  // 2 buffers x 1 slot
-  int* ovf = reinterpret_cast<int*>(smem + 2 * TB);  // [2] sticky overflow flags, by tile parity
+  int* ovf = reinterpret_cast<int*>(smem + 2 * TB);  // sticky overflow flags: [0], [1] by tile parity, [2] list
 
   C q;
   q.init(g, A.Q, bh_, blk_);
@@ -201,7 +249,7 @@ __device__ __forceinline__ void fwd_lists_block(const FwdSparseArgs& A, int bh_,
   // ---------------------------------------------- 2. candidate lists at tau_lb
   uint2* mylist = A.cand + (row_idx * 2 + q.hh) * kCandCap;
   int cnt = 0;
-  const bool fits = collect_sweep<C, T, D, kCandCap>(q, g, A.K, tiles, ovf, live, lo, mylist, cnt, n_qk2, n_cand_tiles);
+  const bool fits = collect_sweep<C, T, D, kCandCap>(q, g, A.K, tiles, ovf, live, lo, A.cells, mylist, cnt, n_qk2, n_cand_tiles);
   if (!fits) {
     if (q.tid == 0) {
       A.dense_flag[flag_idx] = 1;
