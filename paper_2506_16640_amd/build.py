@@ -15,8 +15,9 @@ HIPCC_FLAGS = [
     # MFMA results go straight to VGPRs (no AGPR round trip before the VALU work on the scores)
     "-mllvm", "-amdgpu-mfma-vgpr-form=1",
     # the kernels never produce or consume NaN (masked scores are -inf and are tested before use):
-    # lets max/min chains compile to v_max3 / v_min3 without a canonicalising self-max per operand
-    "-fno-honor-nans",
+    # lets max/min chains compile to v_max3 / v_min3 without a canonicalising self-max per operand.
+    # Device code only: the host-side argument checks must keep rejecting NaN parameters.
+    "-Xarch_device", "-fno-honor-nans",
 ]
 
 

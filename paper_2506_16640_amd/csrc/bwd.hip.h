@@ -36,7 +36,7 @@ struct BwdArgs {
   float* dscale;    // [B*H*Nq] gradient with respect to scale_i
   uint32_t* mask;   // [B*H][nqg][mask_words] bit jb of row ig: tile (ig, jb) holds some p > 0
   unsigned long long* stats;
-  const int* head_flag;  // NULL: every head; else [B*H + 1], only heads whose flag is set; the last entry is the OR
+  const int* head_flag;  // NULL: every head; else [B*H], only heads whose flag is set
   int nqb, nkb, nqg, mask_words;
 };
 
@@ -484,8 +484,8 @@ __device__ __forceinline__ void bwd_dkv_block(const BwdArgs& A, int bh_, int blk
   template <typename T, int D, int AM>                                              \
   __global__ __launch_bounds__(kThreads, OCC) void NAME(BwdArgs A) {                \
     extern __shared__ __attribute__((aligned(16))) char smem[];                     \
-    if (A.head_flag && __builtin_amdgcn_readfirstlane(A.head_flag[A.g.B * A.g.H]) == 0) return; \
     const PairItem it = pair_item(NBLK);                                            \
+    if (A.head_flag && __builtin_amdgcn_readfirstlane(A.head_flag[it.bh]) == 0) return; \
     for (int part = 0; part < 2; ++part) {                                          \
       const int blk = part ? it.second : it.first;                                  \
       if (blk < 0) break;                                                           \
@@ -500,15 +500,15 @@ ENTMAX_PAIRED_KERNEL(bwd_mask_kernel, bwd_mask_block, A.nqb, 3)
 template <typename T, int D, int AM>
 __global__ __launch_bounds__(kThreads) void bwd_dq_kernel(BwdArgs A) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  if (A.head_flag && __builtin_amdgcn_readfirstlane(A.head_flag[A.g.B * A.g.H]) == 0) return;
   const int item = xcd_remap(blockIdx.x, gridDim.x);
+  if (A.head_flag && __builtin_amdgcn_readfirstlane(A.head_flag[item / A.nqb]) == 0) return;
   bwd_dq_block<T, D, AM>(A, item / A.nqb, A.nqb - 1 - item % A.nqb, smem);
 }
 template <typename T, int D, int AM>
 __global__ __launch_bounds__(kThreads) void bwd_dkv_kernel(BwdArgs A) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  if (A.head_flag && __builtin_amdgcn_readfirstlane(A.head_flag[A.g.B * A.g.H]) == 0) return;
   const int item = xcd_remap(blockIdx.x, gridDim.x);
+  if (A.head_flag && __builtin_amdgcn_readfirstlane(A.head_flag[item / A.nkb]) == 0) return;
   bwd_dkv_block<T, D, AM>(A, item / A.nkb, item % A.nkb, smem);
 }
 

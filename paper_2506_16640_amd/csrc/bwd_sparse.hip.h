@@ -44,12 +44,14 @@ struct BwdSparseArgs {
   float2* pw;          // [B*H*Nq][2][kBwdCap] (p_ij, c_i dS_ij)
   void* cells;         // sweep scratch: per workgroup and lane, kBwdCap cells
   int* lcnt;           // [B*H*Nq][2] entries per half row
-  int* kcount;         // [B*H*Nk] entries per key (zeroed before bwd_rows_kernel)
+  int* kcount;         // [B*H*Nk] entries per key (zeroed by bwd_lists_kernel)
   int* koffs;          // [B*H*Nk] exclusive prefix sums of kcount within the head
   int* csc_i;          // [B*H][Nq*2*kBwdCap] query row of each entry, key-major
   float2* csc_pw;      // same order: (p, c dS)
-  int* head_flag;      // [B*H + kLongCountOffset + 1] pre-zeroed; 1: head left to the tiled kernels; entry B*H: some head is;
-                       // entry B*H + kLongCountOffset: number of keys on the long-segment list
+  int* block_flag;     // [B*H*nqb] written by bwd_lists_kernel: 1 when a list of the block overflowed
+  int* head_flag;      // [B*H + kLongCountOffset + 1]; entries < B*H written by bwd_rows_kernel: 1: head left to the
+                       // tiled kernels; entry B*H + kLongCountOffset (zeroed by bwd_lists_kernel): number of keys on
+                       // the long-segment list
   int* long_keys;      // [B*H*Nk] keys with more than kSortedKeyEntries entries
   unsigned long long* stats;
   int nqb;
@@ -74,14 +76,15 @@ __device__ __forceinline__ void bwd_lists_block(const BwdSparseArgs& A, int bh_,
   unsigned n_qk = 0, n_cand_tiles = 0;
   bool fits = true;
   if (q.block_lim > 0) fits = collect_sweep<C, T, D, kBwdCap>(q, g, A.K, smem, ovf, live, tau, A.cells, mylist, cnt, n_qk, n_cand_tiles);
-  if (!fits) {
-    if (q.tid == 0) {
-      A.head_flag[q.bh] = 1;
-      A.head_flag[g.B * g.H] = 1;
-    }
-  } else if (q.valid) {
-    A.lcnt[row_idx * 2 + q.hh] = cnt;
+  if (q.tid == 0) A.block_flag[q.bh * A.nqb + q.qb] = fits ? 0 : 1;
+  if (fits && q.valid) A.lcnt[row_idx * 2 + q.hh] = cnt;
+  // this block's share of the per-key entry counters starts at zero for bwd_rows_kernel
+  {
+    const int chunk = (g.Nk + A.nqb - 1) / A.nqb;
+    const int j_end = min(g.Nk, (q.qb + 1) * chunk);
+    for (int j = q.qb * chunk + q.tid; j < j_end; j += kThreads) A.kcount[(long long)q.bh * g.Nk + j] = 0;
   }
+  if (blockIdx.x == 0 && q.tid == 0) A.head_flag[g.B * g.H + kLongCountOffset] = 0;
   if (A.stats && q.lane == 0) {
     atomicAdd(&A.stats[ENTMAX_STAT_BWD_TILES_VISIBLE], (unsigned long long)n_qk);
     atomicAdd(&A.stats[ENTMAX_STAT_BWD_LIST_QK], (unsigned long long)n_qk);
@@ -106,7 +109,14 @@ __global__ __launch_bounds__(kThreads) void bwd_rows_kernel(BwdSparseArgs A) {
   const Geom& g = A.g;
   RowLane rl;
   rl.init(g, A.nqb);
-  if (A.head_flag[rl.bh] != 0) return;  // the tiled kernels own this head
+  {
+    // OR of the head's block flags; the head's first workgroup publishes it for the kernels that follow
+    bool any = false;
+    for (int k = threadIdx.x; k < A.nqb; k += kThreads) any = any || A.block_flag[rl.bh * A.nqb + k] != 0;
+    const int head_any = __syncthreads_or(any ? 1 : 0);
+    if (rl.qb == 0 && threadIdx.x == 0) A.head_flag[rl.bh] = head_any ? 1 : 0;
+    if (head_any) return;  // the tiled kernels own this head
+  }
   constexpr int DH = D / 2;
   const float r = 1.0f / (g.alpha - 1.0f);
   const long long row_idx = (long long)rl.bh * g.Nq + (rl.valid ? rl.i : 0);

@@ -129,7 +129,7 @@ Layout make_layout(const entmax_attn_params* p) {
   L.off_csc_pw = o;
   o += align_up(rows * 2 * kBwdCap * sizeof(float2));
   L.off_hflag = o;
-  o += align_up((bh + kLongCountOffset + 1) * sizeof(int));
+  o += align_up((bh * (size_t)L.nqb + bh + kLongCountOffset + 1) * sizeof(int));  // block flags, head flags, counter
   L.off_longkeys = o;
   o += key_bytes;
   L.off_bcells = o;
@@ -206,13 +206,25 @@ bool zero_words(void* p, size_t bytes, hipStream_t st) {
 }
 
 template <typename T, int D>
-bool launch_transpose(const void* X, long long sb, long long sh, long long sn, int B, int H, int N, int npad, void* Xt,
-                      hipStream_t st, const int* head_flag = nullptr) {
+bool launch_transposes(const TransposeJobs& jobs, int njobs, int B, int H, hipStream_t st, const int* head_flag = nullptr) {
+  int npad = 0;
+  for (int k = 0; k < njobs; ++k) npad = jobs.job[k].npad > npad ? jobs.job[k].npad : npad;
   if (npad == 0) return true;
-  dim3 grid((unsigned)(npad / 64), (unsigned)(B * H));
-  hipLaunchKernelGGL((transpose_perm_kernel<T, D>), grid, dim3(kThreads), 0, st, reinterpret_cast<const T*>(X), sb, sh,
-                     sn, H, N, npad, reinterpret_cast<T*>(Xt), head_flag);
+  dim3 grid((unsigned)(npad / 64), (unsigned)(B * H), (unsigned)njobs);
+  hipLaunchKernelGGL((transpose_perm_kernel<T, D>), grid, dim3(kThreads), 0, st, jobs, H, head_flag);
   return launch_ok();
+}
+
+inline TransposeJob transpose_job(const void* X, long long sb, long long sh, long long sn, int N, int npad, void* Xt) {
+  TransposeJob j;
+  j.X = X;
+  j.Xt = Xt;
+  j.sb = sb;
+  j.sh = sh;
+  j.sn = sn;
+  j.N = N;
+  j.npad = npad;
+  return j;
 }
 
 template <typename T, int D, int AM>
@@ -274,7 +286,6 @@ int run_fwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
   const int nblocks = p->B * p->H * ((L.nqb + 1) / 2);  // workgroups take query blocks in pairs
   const bool lists = p->path == 0;
   if (lists) {
-    if (!zero_words(head_flag, ((size_t)p->B * p->H + 1) * sizeof(int), st)) return ENTMAX_ATTN_LAUNCH_FAILED;
     FwdSparseArgs sa;
     sa.g = make_geom(p, L, beta, gamma);
     sa.Q = Q;
@@ -293,9 +304,11 @@ int run_fwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
     if (!launch_fwd_sparse_am<T, D>(sa, alpha_mode(p->alpha), nblocks, st)) return ENTMAX_ATTN_LAUNCH_FAILED;
   }
   record(ev, 1, st);
-  if (!launch_transpose<T, D>(V, L.kv_sb, L.kv_sh, L.kv_sn, p->B, p->H, p->Nk, L.npad_k, Vt, st,
-                              lists ? head_flag : nullptr))
-    return ENTMAX_ATTN_LAUNCH_FAILED;
+  {
+    TransposeJobs jobs{};
+    jobs.job[0] = transpose_job(V, L.kv_sb, L.kv_sh, L.kv_sn, p->Nk, L.npad_k, Vt);
+    if (!launch_transposes<T, D>(jobs, 1, p->B, p->H, st, lists ? head_flag : nullptr)) return ENTMAX_ATTN_LAUNCH_FAILED;
+  }
   record(ev, 2, st);
   FwdArgs a;
   a.g = make_geom(p, L, beta, gamma);
@@ -308,7 +321,7 @@ int run_fwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
   a.nqb = L.nqb;
   a.mask_words = L.mask_words;
   a.dense_flag = lists ? dense_flag : nullptr;
-  a.any_flag = lists ? head_flag + (size_t)p->B * p->H : nullptr;
+  a.head_flag = lists ? head_flag : nullptr;
   if (!launch_fwd_am<T, D>(a, alpha_mode(p->alpha), nblocks, st)) return ENTMAX_ATTN_LAUNCH_FAILED;
   record(ev, 3, st);
   return ENTMAX_ATTN_OK;
@@ -376,7 +389,8 @@ int run_bwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
     for (int k = 1; k <= 6; ++k) record(ev, k, st);
   } else {
     const bool lists = p->path == 0;
-    int* head_flag = reinterpret_cast<int*>(ws + L.off_hflag);
+    int* block_flag = reinterpret_cast<int*>(ws + L.off_hflag);
+    int* head_flag = block_flag + (size_t)B * H * L.nqb;
     BwdSparseArgs sa;
     if (lists) {
       sa.g = g;
@@ -397,12 +411,11 @@ int run_bwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
       sa.koffs = reinterpret_cast<int*>(ws + L.off_koffs);
       sa.csc_i = reinterpret_cast<int*>(ws + L.off_csc_i);
       sa.csc_pw = reinterpret_cast<float2*>(ws + L.off_csc_pw);
+      sa.block_flag = block_flag;
       sa.head_flag = head_flag;
       sa.long_keys = reinterpret_cast<int*>(ws + L.off_longkeys);
       sa.stats = reinterpret_cast<unsigned long long*>(stats);
       sa.nqb = L.nqb;
-      ok = ok && zero_words(head_flag, ((size_t)B * H + kLongCountOffset + 1) * sizeof(int), st);
-      ok = ok && zero_words(sa.kcount, (size_t)B * H * p->Nk * sizeof(int), st);
       ok = ok && launch_bwd_rows_am<T, D>(sa, alpha_mode(p->alpha), B * H * ((L.nqb + 1) / 2), st);
       if (!ok) return ENTMAX_ATTN_LAUNCH_FAILED;
     }
@@ -411,9 +424,13 @@ int run_bwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
     void* Kt = ws + L.off_kt;
     void* Qt = ws + L.off_qt;
     void* dOt = ws + L.off_dot;
-    ok = ok && launch_transpose<T, D>(K, L.kv_sb, L.kv_sh, L.kv_sn, B, H, p->Nk, L.npad_k, Kt, st, hf);
-    ok = ok && launch_transpose<T, D>(Q, L.q_sb, L.q_sh, L.q_sn, B, H, p->Nq, L.npad_q, Qt, st, hf);
-    ok = ok && launch_transpose<T, D>(dO, L.q_sb, L.q_sh, L.q_sn, B, H, p->Nq, L.npad_q, dOt, st, hf);
+    {
+      TransposeJobs jobs{};
+      jobs.job[0] = transpose_job(K, L.kv_sb, L.kv_sh, L.kv_sn, p->Nk, L.npad_k, Kt);
+      jobs.job[1] = transpose_job(Q, L.q_sb, L.q_sh, L.q_sn, p->Nq, L.npad_q, Qt);
+      jobs.job[2] = transpose_job(dO, L.q_sb, L.q_sh, L.q_sn, p->Nq, L.npad_q, dOt);
+      ok = ok && launch_transposes<T, D>(jobs, 3, B, H, st, hf);
+    }
     if (!ok) return ENTMAX_ATTN_LAUNCH_FAILED;
     record(ev, 2, st);
     BwdArgs a;

@@ -31,7 +31,7 @@ struct FwdArgs {
   int nqb;         // query blocks per head
   int mask_words;  // uint32 words of one wave's tile mask
   const int* dense_flag;  // NULL: run every workgroup; else [B*H*nqb], run only where the flag is set
-  const int* any_flag;    // NULL, or one int: 0 means no workgroup at all is flagged
+  const int* head_flag;   // NULL, or [B*H]: 0 means no workgroup of the head is flagged
 };
 
 constexpr int kMaxSolveIters = 48;
@@ -338,8 +338,8 @@ __device__ __forceinline__ void fwd_block(const FwdArgs& A, int bh_, int blk_, c
 template <typename T, int D, int AM>
 __global__ __launch_bounds__(kThreads) void fwd_kernel(FwdArgs A) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  if (A.any_flag && __builtin_amdgcn_readfirstlane(*A.any_flag) == 0) return;
   const PairItem it = pair_item(A.nqb);
+  if (A.head_flag && __builtin_amdgcn_readfirstlane(A.head_flag[it.bh]) == 0) return;
   for (int part = 0; part < 2; ++part) {
     const int blk = part ? it.second : it.first;
     if (blk < 0) break;

@@ -39,8 +39,7 @@ struct FwdSparseArgs {
   int* lcnt;        // [B*H*Nq][2] list lengths
   float2* bounds;   // [B*H*Nq] (tau_lb, right end of the bracket)
   int* dense_flag;  // [B*H*nqb] 1: block left to the tiled kernel
-  int* head_flag;   // [B*H + 1] pre-zeroed; set to 1 when some block of the head is left to the tiled kernel;
-                    // the last entry is set when any head is
+  int* head_flag;   // [B*H] written by fwd_finish_kernel: 1 when some block of the head is left to the tiled kernel
   unsigned long long* stats;
   int nqb;
 };
@@ -251,11 +250,7 @@ __device__ __forceinline__ void fwd_lists_block(const FwdSparseArgs& A, int bh_,
   int cnt = 0;
   const bool fits = collect_sweep<C, T, D, kCandCap>(q, g, A.K, tiles, ovf, live, lo, A.cells, mylist, cnt, n_qk2, n_cand_tiles);
   if (!fits) {
-    if (q.tid == 0) {
-      A.dense_flag[flag_idx] = 1;
-      A.head_flag[q.bh] = 1;
-      A.head_flag[g.B * g.H] = 1;
-    }
+    if (q.tid == 0) A.dense_flag[flag_idx] = 1;
   } else {
     if (q.tid == 0) A.dense_flag[flag_idx] = 0;
     if (q.valid) {
@@ -342,6 +337,13 @@ __global__ __launch_bounds__(kThreads) void fwd_finish_kernel(FwdSparseArgs A) {
   const Geom& g = A.g;
   RowLane rl;
   rl.init(g, A.nqb);
+  if (rl.qb == 0 && threadIdx.x < 64) {
+    // first workgroup of the head: OR of the head's block flags, for the kernels that follow
+    bool any = false;
+    for (int k = threadIdx.x; k < A.nqb; k += 64) any = any || A.dense_flag[rl.bh * A.nqb + k] != 0;
+    const bool head_any = __ballot(any) != 0ull;
+    if (threadIdx.x == 0) A.head_flag[rl.bh] = head_any ? 1 : 0;
+  }
   if (A.dense_flag[rl.bh * A.nqb + rl.qb] != 0) return;  // the tiled kernel owns this block
   constexpr int DH = D / 2;
   const float r = 1.0f / (g.alpha - 1.0f);

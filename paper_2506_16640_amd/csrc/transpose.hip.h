@@ -11,17 +11,30 @@
 
 namespace entmax {
 
+struct TransposeJob {
+  const void* X;
+  void* Xt;
+  long long sb, sh, sn;
+  int N, npad;
+};
+struct TransposeJobs {
+  TransposeJob job[3];  // blockIdx.z picks one
+};
+
 template <typename T, int D>
-__global__ __launch_bounds__(kThreads) void transpose_perm_kernel(const T* __restrict__ X, long long sb, long long sh,
-                                                                  long long sn, int H, int N, int npad,
-                                                                  T* __restrict__ Xt, const int* head_flag) {
+__global__ __launch_bounds__(kThreads) void transpose_perm_kernel(TransposeJobs jobs, int H, const int* head_flag) {
   constexpr int kPad = sizeof(T) == 2 ? 2 : 1;
   __shared__ T tile[64][D + kPad];
   const int tid = threadIdx.x;
   const int bh = blockIdx.y, b = bh / H, h = bh % H;
   if (head_flag && head_flag[bh] == 0) return;  // no consumer for this head's copy
+  const TransposeJob& jb = jobs.job[blockIdx.z];
+  const int N = jb.N, npad = jb.npad;
+  const long long sn = jb.sn;
   const int j0 = blockIdx.x * 64;
-  const T* src = X + (long long)b * sb + (long long)h * sh;
+  if (j0 >= npad) return;  // the grid covers the longest job
+  const T* src = reinterpret_cast<const T*>(jb.X) + (long long)b * jb.sb + (long long)h * jb.sh;
+  T* Xt = reinterpret_cast<T*>(jb.Xt);
   for (int e = tid; e < 64 * D; e += kThreads) {
     int row = e / D, col = e % D;
     int j = j0 + row;

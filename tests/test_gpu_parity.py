@@ -55,6 +55,16 @@ def test_bf16_dense_regime(alpha):
     print(alpha, compare(g, r, label=f"dense a{alpha}"))
 
 
+@pytest.mark.parametrize("scale,alpha,dtype", [("none", 1.5, "bf16"), ("none", 1.7, "bf16"), ("head", 1.25, "bf16"),
+                                               ("none", 1.7, "fp32")])
+def test_moderate_support(scale, alpha, dtype):
+    # supports of 5..40 keys per row: long candidate lists, some half rows beyond the list capacities
+    data = _case(1, 2, 768, 768, 64, dtype, scale, seed=7)
+    g = gpu_run(data, alpha, dtype, stats=True)
+    r = oracle_run(data, alpha)
+    print(scale, alpha, dtype, compare(g, r, label=f"moderate {scale} a{alpha}"), {k: v for k, v in g["stats"].items() if v})
+
+
 @pytest.mark.parametrize("causal,nq,nk", [(False, 200, 333), (True, 200, 333), (True, 333, 200), (False, 129, 64),
                                            (True, 1, 1), (True, 1, 70), (True, 33, 33)])
 @pytest.mark.parametrize("dtype", ["bf16", "fp32"])
