@@ -249,21 +249,22 @@ bool launch_fwd_am(const FwdArgs& a, int am, int nblocks, hipStream_t st) {
 }
 
 template <typename T, int D, int AM>
-bool launch_fwd_sparse(const FwdSparseArgs& a, int nblocks, hipStream_t st) {
+bool launch_fwd_sparse(const FwdSparseArgs& a, int nblocks, hipStream_t st, void* const* ev) {
   size_t smem = 2 * (size_t)QCtx<T, D, FwdTile<T>::value>::kTileBytes + 64;
   hipLaunchKernelGGL((fwd_lists_kernel<T, D, AM>), dim3((unsigned)nblocks), dim3(kThreads), smem, st, a);
   if (!launch_ok()) return false;
+  record(ev, ENTMAX_FWD_PHASE_LISTS + 1, st);
   hipLaunchKernelGGL((fwd_finish_kernel<T, D, AM>), dim3((unsigned)(a.g.B * a.g.H * a.nqb)), dim3(kThreads), 0, st, a);
   return launch_ok();
 }
 
 template <typename T, int D>
-bool launch_fwd_sparse_am(const FwdSparseArgs& a, int am, int nblocks, hipStream_t st) {
+bool launch_fwd_sparse_am(const FwdSparseArgs& a, int am, int nblocks, hipStream_t st, void* const* ev) {
   switch (am) {
-    case 1: return launch_fwd_sparse<T, D, 1>(a, nblocks, st);
-    case 2: return launch_fwd_sparse<T, D, 2>(a, nblocks, st);
-    case 3: return launch_fwd_sparse<T, D, 3>(a, nblocks, st);
-    default: return launch_fwd_sparse<T, D, 0>(a, nblocks, st);
+    case 1: return launch_fwd_sparse<T, D, 1>(a, nblocks, st, ev);
+    case 2: return launch_fwd_sparse<T, D, 2>(a, nblocks, st, ev);
+    case 3: return launch_fwd_sparse<T, D, 3>(a, nblocks, st, ev);
+    default: return launch_fwd_sparse<T, D, 0>(a, nblocks, st, ev);
   }
 }
 
@@ -275,9 +276,7 @@ int run_fwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
   if (p->Nk == 0) {
     bool ok = zero_rows<T>(O, L.q_sb, L.q_sh, L.q_sn, p->B, p->H, p->Nq, p->D, st) &&
               zero_words(tau, (size_t)p->B * p->H * p->Nq * 4, st);
-    record(ev, 1, st);
-    record(ev, 2, st);
-    record(ev, 3, st);
+    for (int k = 1; k <= ENTMAX_FWD_NUM_PHASES; ++k) record(ev, k, st);
     return ok ? ENTMAX_ATTN_OK : ENTMAX_ATTN_LAUNCH_FAILED;
   }
   void* Vt = ws + L.off_vt;
@@ -301,15 +300,17 @@ int run_fwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
     sa.head_flag = head_flag;
     sa.stats = reinterpret_cast<unsigned long long*>(stats);
     sa.nqb = L.nqb;
-    if (!launch_fwd_sparse_am<T, D>(sa, alpha_mode(p->alpha), nblocks, st)) return ENTMAX_ATTN_LAUNCH_FAILED;
+    if (!launch_fwd_sparse_am<T, D>(sa, alpha_mode(p->alpha), nblocks, st, ev)) return ENTMAX_ATTN_LAUNCH_FAILED;
+  } else {
+    record(ev, ENTMAX_FWD_PHASE_LISTS + 1, st);
   }
-  record(ev, 1, st);
+  record(ev, ENTMAX_FWD_PHASE_FINISH + 1, st);
   {
     TransposeJobs jobs{};
     jobs.job[0] = transpose_job(V, L.kv_sb, L.kv_sh, L.kv_sn, p->Nk, L.npad_k, Vt);
     if (!launch_transposes<T, D>(jobs, 1, p->B, p->H, st, lists ? head_flag : nullptr)) return ENTMAX_ATTN_LAUNCH_FAILED;
   }
-  record(ev, 2, st);
+  record(ev, ENTMAX_FWD_PHASE_TRANSPOSE + 1, st);
   FwdArgs a;
   a.g = make_geom(p, L, beta, gamma);
   a.Q = Q;
@@ -323,7 +324,7 @@ int run_fwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
   a.dense_flag = lists ? dense_flag : nullptr;
   a.head_flag = lists ? head_flag : nullptr;
   if (!launch_fwd_am<T, D>(a, alpha_mode(p->alpha), nblocks, st)) return ENTMAX_ATTN_LAUNCH_FAILED;
-  record(ev, 3, st);
+  record(ev, ENTMAX_FWD_PHASE_TILED + 1, st);
   return ENTMAX_ATTN_OK;
 }
 
@@ -343,32 +344,33 @@ bool launch_bwd_kernels(const BwdArgs& a, const Layout& L, int B, int H, hipStre
     return false;
   hipLaunchKernelGGL(k_mask, dim3((unsigned)(B * H * ((L.nqb + 1) / 2))), dim3(kThreads), smem_mask, st, a);
   if (!launch_ok()) return false;
-  record(ev, 3, st);
+  record(ev, ENTMAX_BWD_PHASE_MASK + 1, st);
   hipLaunchKernelGGL(k_dq, dim3((unsigned)(B * H * L.nqb)), dim3(kThreads), smem_dq, st, a);
   if (!launch_ok()) return false;
-  record(ev, 4, st);
+  record(ev, ENTMAX_BWD_PHASE_DQ + 1, st);
   hipLaunchKernelGGL(k_dkv, dim3((unsigned)(B * H * L.nkb)), dim3(kThreads), smem_dkv, st, a);
   if (!launch_ok()) return false;
-  record(ev, 5, st);
+  record(ev, ENTMAX_BWD_PHASE_DKV + 1, st);
   return true;
 }
 
 template <typename T, int D, int AM>
-bool launch_bwd_rows(const BwdSparseArgs& a, int nblocks, hipStream_t st) {
+bool launch_bwd_rows(const BwdSparseArgs& a, int nblocks, hipStream_t st, void* const* ev) {
   size_t smem = 2 * (size_t)QCtx<T, D, FwdTile<T>::value>::kTileBytes + 64;
   hipLaunchKernelGGL((bwd_lists_kernel<T, D, AM>), dim3((unsigned)nblocks), dim3(kThreads), smem, st, a);
   if (!launch_ok()) return false;
+  record(ev, ENTMAX_BWD_PHASE_LISTS + 1, st);
   hipLaunchKernelGGL((bwd_rows_kernel<T, D, AM>), dim3((unsigned)(a.g.B * a.g.H * a.nqb)), dim3(kThreads), 0, st, a);
   return launch_ok();
 }
 
 template <typename T, int D>
-bool launch_bwd_rows_am(const BwdSparseArgs& a, int am, int nblocks, hipStream_t st) {
+bool launch_bwd_rows_am(const BwdSparseArgs& a, int am, int nblocks, hipStream_t st, void* const* ev) {
   switch (am) {
-    case 1: return launch_bwd_rows<T, D, 1>(a, nblocks, st);
-    case 2: return launch_bwd_rows<T, D, 2>(a, nblocks, st);
-    case 3: return launch_bwd_rows<T, D, 3>(a, nblocks, st);
-    default: return launch_bwd_rows<T, D, 0>(a, nblocks, st);
+    case 1: return launch_bwd_rows<T, D, 1>(a, nblocks, st, ev);
+    case 2: return launch_bwd_rows<T, D, 2>(a, nblocks, st, ev);
+    case 3: return launch_bwd_rows<T, D, 3>(a, nblocks, st, ev);
+    default: return launch_bwd_rows<T, D, 0>(a, nblocks, st, ev);
   }
 }
 
@@ -386,7 +388,7 @@ int run_bwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
     ok = ok && zero_rows<T>(dK, L.kv_sb, L.kv_sh, L.kv_sn, B, H, p->Nk, p->D, st);
     ok = ok && zero_rows<T>(dV, L.kv_sb, L.kv_sh, L.kv_sn, B, H, p->Nk, p->D, st);
     ok = ok && zero_words(dscale, (size_t)B * H * p->Nq * 4, st);
-    for (int k = 1; k <= 6; ++k) record(ev, k, st);
+    for (int k = 1; k <= ENTMAX_BWD_PHASE_KEYS + 1; ++k) record(ev, k, st);
   } else {
     const bool lists = p->path == 0;
     int* block_flag = reinterpret_cast<int*>(ws + L.off_hflag);
@@ -416,10 +418,12 @@ int run_bwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
       sa.long_keys = reinterpret_cast<int*>(ws + L.off_longkeys);
       sa.stats = reinterpret_cast<unsigned long long*>(stats);
       sa.nqb = L.nqb;
-      ok = ok && launch_bwd_rows_am<T, D>(sa, alpha_mode(p->alpha), B * H * ((L.nqb + 1) / 2), st);
+      ok = ok && launch_bwd_rows_am<T, D>(sa, alpha_mode(p->alpha), B * H * ((L.nqb + 1) / 2), st, ev);
       if (!ok) return ENTMAX_ATTN_LAUNCH_FAILED;
+    } else {
+      record(ev, ENTMAX_BWD_PHASE_LISTS + 1, st);
     }
-    record(ev, 1, st);
+    record(ev, ENTMAX_BWD_PHASE_ROWS + 1, st);
     const int* hf = lists ? head_flag : nullptr;
     void* Kt = ws + L.off_kt;
     void* Qt = ws + L.off_qt;
@@ -432,7 +436,7 @@ int run_bwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
       ok = ok && launch_transposes<T, D>(jobs, 3, B, H, st, hf);
     }
     if (!ok) return ENTMAX_ATTN_LAUNCH_FAILED;
-    record(ev, 2, st);
+    record(ev, ENTMAX_BWD_PHASE_TRANSPOSE + 1, st);
     BwdArgs a;
     a.g = g;
     a.Q = Q;
@@ -478,7 +482,7 @@ int run_bwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
       hipLaunchKernelGGL((bwd_long_keys_kernel<T, D>), dim3(1024u), dim3(kThreads), 0, st, sa);
       ok = ok && launch_ok();
     }
-    record(ev, 6, st);
+    record(ev, ENTMAX_BWD_PHASE_KEYS + 1, st);
   }
   if (!ok) return ENTMAX_ATTN_LAUNCH_FAILED;
   if (p->scale_layout == 1) {
@@ -493,7 +497,7 @@ int run_bwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
       ok = launch_ok();
     }
   }
-  record(ev, 7, st);
+  record(ev, ENTMAX_BWD_PHASE_SCALE_GRAD + 1, st);
   return ok ? ENTMAX_ATTN_OK : ENTMAX_ATTN_LAUNCH_FAILED;
 }
 
