@@ -22,6 +22,11 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak
+# HBM bytes per launch at the c3 workload, from rocprofv3 FETCH_SIZE + WRITE_SIZE runs of this same command scaled by
+# what the counters read for a conversion kernel of known size (profiles/pmc_c3_fwd_bwd.md).  Other workloads: null.
+MEASURED_HBM_BYTES_C3 = {
+    "fwd_lists": 191.6e6, "fwd_finish": 98.3e6, "bwd_lists": 151.9e6, "bwd_rows": 188.0e6,
+}
 
 
 class HipEvents:
@@ -211,7 +216,8 @@ def main():
         "solve_sweeps_per_tiled_block": sd["fwd_solve_sweeps"] / max(sd["fwd_blocks"], 1),
         "tile_stats": sd,
         "roofline": {"bound": "mfma", "kernel": dominant, "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
-                     "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None},
+                     "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
+                     "traffic": MEASURED_HBM_BYTES_C3.get(dominant) if args.workload == "c3" else None},
     }
 
     if not args.no_c4 and args.workload == "c3":
