@@ -39,9 +39,9 @@ struct BwdSparseArgs {
   void* dK;
   void* dV;
   float* dscale;       // [B*H*Nq]
-  uint2* jlist;        // [B*H*Nq][2][kBwdCap] (key index, raw dot product bits); bwd_rows_kernel replaces the
+  uint2* jlist;        // [B*H*nqb*4 waves][kBwdCap][64 lanes], see list_entry(): (key index, raw dot product bits); bwd_rows_kernel replaces the
                        // second word by the entry's arrival number within its key (key index kNoKey: dropped)
-  float2* pw;          // [B*H*Nq][2][kBwdCap] (p_ij, c_i dS_ij)
+  float2* pw;          // same layout: (p_ij, c_i dS_ij)
   void* cells;         // sweep scratch: per workgroup and lane, kBwdCap cells
   int* lcnt;           // [B*H*Nq][2] entries per half row
   int* kcount;         // [B*H*Nk] entries per key (zeroed by bwd_lists_kernel)
@@ -71,7 +71,7 @@ __device__ __forceinline__ void bwd_lists_block(const BwdSparseArgs& A, int bh_,
   const long long row_idx = (long long)q.bh * g.Nq + (q.valid ? q.i : 0);
   const float tau = q.valid ? A.tau[row_idx] : 0.f;
   const bool live = q.valid && q.lim > 0;
-  uint2* mylist = A.jlist + (row_idx * 2 + q.hh) * kBwdCap;
+  uint2* mylist = A.jlist + list_entry<kBwdCap>(q.bh, A.nqb, q.qb, q.wave, q.lane);
   int cnt = 0;
   unsigned n_qk = 0, n_cand_tiles = 0;
   bool fits = true;
@@ -131,8 +131,9 @@ __global__ __launch_bounds__(kThreads) void bwd_rows_kernel(BwdSparseArgs A) {
   const int cnt = live ? A.lcnt[row_idx * 2 + rl.hh] : 0;
   const long long q_base = (long long)rl.b * g.q_sb + (long long)rl.h * g.q_sh;
   const long long kv_base = (long long)rl.b * g.kv_sb + (long long)rl.h * g.kv_sh;
-  uint2* mylist = A.jlist + (row_idx * 2 + rl.hh) * kBwdCap;
-  float2* mypw = A.pw + (row_idx * 2 + rl.hh) * kBwdCap;
+  const long long list0 = list_entry<kBwdCap>(rl.bh, A.nqb, rl.qb, threadIdx.x >> 6, threadIdx.x & 63);
+  uint2* mylist = A.jlist + list0;
+  float2* mypw = A.pw + list0;
   const T* Kbh = reinterpret_cast<const T*>(A.K) + kv_base;
   const T* Vbh = reinterpret_cast<const T*>(A.V) + kv_base;
 
@@ -152,7 +153,7 @@ __global__ __launch_bounds__(kThreads) void bwd_rows_kernel(BwdSparseArgs A) {
     float dv[NE];  // raw dot products (sign-folded), -inf for empty slots
 #pragma unroll
     for (int e = 0; e < NE; ++e) {
-      uint2 en = (e < cnt) ? mylist[e] : make_uint2(0u, 0u);
+      uint2 en = (e < cnt) ? mylist[e * kListStride] : make_uint2(0u, 0u);
       jv[e] = en.x;
       dv[e] = (e < cnt) ? __uint_as_float(en.y) : -kInf;
     }
@@ -214,7 +215,7 @@ __global__ __launch_bounds__(kThreads) void bwd_rows_kernel(BwdSparseArgs A) {
 #pragma unroll
           for (int t = 0; t < DH; ++t) dq[t] = fmaf(w, kk[t], dq[t]);
           if (rl.hh == src) {  // the entry's owner records it for the key side
-            mypw[e] = make_float2(pow_r<AM>(x, r), w);
+            mypw[e * kListStride] = make_float2(pow_r<AM>(x, r), w);
             // arrival number of this entry among the key's entries: its place in the key's segment
             slotv[e] = atomicAdd(&A.kcount[(long long)rl.bh * g.Nk + j], 1);
             ++n_entries;
@@ -226,7 +227,7 @@ __global__ __launch_bounds__(kThreads) void bwd_rows_kernel(BwdSparseArgs A) {
     // (a listed key whose probability rounds to zero here is dropped from the key side)
 #pragma unroll
     for (int e = 0; e < NE; ++e)
-      if (e < cnt) mylist[e] = slotv[e] >= 0 ? make_uint2(jv[e], (unsigned)slotv[e]) : make_uint2(kNoKey, 0u);
+      if (e < cnt) mylist[e * kListStride] = slotv[e] >= 0 ? make_uint2(jv[e], (unsigned)slotv[e]) : make_uint2(kNoKey, 0u);
     if (rl.valid) {
       store_row<T>(reinterpret_cast<T*>(A.dQ) + q_base + (long long)rl.i * g.q_sn + rl.hh * DH, DH, dq);
       // the scores were formed with q negated when scale_i < 0: undo the sign for z_ij
@@ -274,26 +275,27 @@ __global__ __launch_bounds__(kThreads) void csc_offsets_kernel(const int* kcount
   }
 }
 
-// One thread per half row: moves its entries into the key-major arrays.  An entry's place is its
+// One thread per half row, threads laid out like the lanes of the list kernels (workgroup = query block,
+// wave = 32 rows x 2 halves): moves its entries into the key-major arrays.  An entry's place is its
 // key's segment start plus its arrival number, so no atomics are needed here.
 __global__ __launch_bounds__(kThreads) void csc_scatter_kernel(BwdSparseArgs A) {
   const Geom& g = A.g;
-  long long slot = (long long)blockIdx.x * kThreads + threadIdx.x;  // (row, half)
-  long long rows = (long long)g.B * g.H * g.Nq;
-  if (slot >= rows * 2) return;
-  long long row = slot >> 1;
-  int bh = (int)(row / g.Nq);
+  const int bh = blockIdx.x / A.nqb, qb = blockIdx.x % A.nqb;
   if (A.head_flag[bh] != 0) return;
-  int i = (int)(row % g.Nq);
-  int cnt = A.lcnt[slot];
-  long long base = (long long)bh * g.Nq * 2 * kBwdCap;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int i = qb * kBlockRows + wave * 32 + (lane & 31);
+  if (i >= g.Nq) return;
+  const long long half_row = ((long long)bh * g.Nq + i) * 2 + (lane >> 5);
+  const int cnt = min(A.lcnt[half_row], kBwdCap);
+  const long long list0 = list_entry<kBwdCap>(bh, A.nqb, qb, wave, lane);
+  const long long base = (long long)bh * g.Nq * 2 * kBwdCap;
   for (int e = 0; e < cnt; ++e) {
-    uint2 en = A.jlist[slot * kBwdCap + e];
+    uint2 en = A.jlist[list0 + (long long)e * kListStride];
     if (en.x >= (unsigned)g.Nk) continue;  // kNoKey, or anything that is not a key
     int pos = A.koffs[(long long)bh * g.Nk + en.x] + (int)en.y;
     if (pos >= 0 && pos < g.Nq * 2 * kBwdCap) {  // holds by construction; keeps any stray entry inside the head
       A.csc_i[base + pos] = i;
-      A.csc_pw[base + pos] = A.pw[slot * kBwdCap + e];
+      A.csc_pw[base + pos] = A.pw[list0 + (long long)e * kListStride];
     }
   }
 }

@@ -87,7 +87,7 @@ Layout make_layout(const entmax_attn_params* p) {
   // forward: V^T copy | candidate lists | per-workgroup and per-head fallback flags
   L.off_vt = 0;
   L.off_cand = kt_bytes;
-  size_t cand_bytes = align_up(bh * (size_t)p->Nq * 2 * kCandCap * sizeof(uint2));
+  size_t cand_bytes = align_up(bh * (size_t)L.nqb * kThreads * kCandCap * sizeof(uint2));  // one list per lane of the list grid
   L.off_flcnt = L.off_cand + cand_bytes;
   L.off_bounds = L.off_flcnt + align_up(bh * (size_t)p->Nq * 2 * sizeof(int));
   L.off_flags = L.off_bounds + align_up(bh * (size_t)p->Nq * sizeof(float2));
@@ -112,9 +112,9 @@ Layout make_layout(const entmax_attn_params* p) {
   // support-list backward
   size_t rows = bh * (size_t)p->Nq;
   L.off_jlist = o;
-  o += align_up(rows * 2 * kBwdCap * sizeof(uint2));
+  o += align_up(bh * (size_t)L.nqb * kThreads * kBwdCap * sizeof(uint2));
   L.off_pw = o;
-  o += align_up(rows * 2 * kBwdCap * sizeof(float2));
+  o += align_up(bh * (size_t)L.nqb * kThreads * kBwdCap * sizeof(float2));
   L.off_lcnt = o;
   o += align_up(rows * 2 * sizeof(int));
   size_t key_bytes = align_up(bh * (size_t)p->Nk * sizeof(int));
@@ -471,9 +471,7 @@ int run_bwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
       hipLaunchKernelGGL(csc_offsets_kernel, dim3((unsigned)(B * H)), dim3(kThreads), 0, st, sa.kcount, sa.koffs,
                          p->Nk, head_flag);
       ok = ok && launch_ok();
-      long long slots = (long long)B * H * p->Nq * 2;
-      hipLaunchKernelGGL(csc_scatter_kernel, dim3((unsigned)((slots + kThreads - 1) / kThreads)), dim3(kThreads), 0, st,
-                         sa);
+      hipLaunchKernelGGL(csc_scatter_kernel, dim3((unsigned)(B * H * L.nqb)), dim3(kThreads), 0, st, sa);
       ok = ok && launch_ok();
       long long keys = (long long)B * H * p->Nk;
       hipLaunchKernelGGL((bwd_keys_kernel<T, D>), dim3((unsigned)((keys + kBlockRows - 1) / kBlockRows)), dim3(kThreads), 0, st,

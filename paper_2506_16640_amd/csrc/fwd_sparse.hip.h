@@ -25,7 +25,17 @@
 
 namespace entmax {
 
-constexpr int kCandCap = 32;  // candidates per lane = per half row; a row holds up to 2 * kCandCap
+constexpr int kCandCap = 32;
+
+// Row lists (candidates, supports, per-entry records) are stored per wave of 32 rows x 2 halves with
+// entry s of all 64 lanes together: short lists then touch only the first few 512-byte groups of a
+// wave's region instead of one cache line per half row.  Wave w = ((bh * nqb + qb) * 4 + wave in block);
+// entry (lane, s) sits at list_entry<CAP>(w, lane) + s * kListStride.
+constexpr int kListStride = 64;
+template <int CAP>
+__device__ __forceinline__ long long list_entry(int bh, int nqb, int qb, int wave, int lane) {
+  return (((long long)bh * nqb + qb) * kWaves + wave) * CAP * kListStride + lane;
+}  // candidates per lane = per half row; a row holds up to 2 * kCandCap
 
 struct FwdSparseArgs {
   Geom g;
@@ -34,7 +44,7 @@ struct FwdSparseArgs {
   const void* V;
   void* O;
   float* tau;
-  uint2* cand;      // [B*H*Nq][2][kCandCap] (key index, raw dot product bits)
+  uint2* cand;      // [B*H*nqb*4 waves][kCandCap][64 lanes] (key index, raw dot product bits), see list_entry()
   void* cells;      // sweep scratch: per workgroup and lane, kCandCap cells (see CellBuf)
   int* lcnt;        // [B*H*Nq][2] list lengths
   float2* bounds;   // [B*H*Nq] (tau_lb, right end of the bracket)
@@ -151,7 +161,7 @@ __device__ __forceinline__ bool collect_sweep(const C& q, const Geom& g, const v
 #pragma unroll
         for (int rr = 0; rr < 4; ++rr) {
           if (dv[rr] > cut) {
-            if (cnt < CAP) mylist[cnt] = make_uint2((unsigned)(jc + 8 * u + rr), __float_as_uint(dv[rr]));
+            if (cnt < CAP) mylist[cnt * kListStride] = make_uint2((unsigned)(jc + 8 * u + rr), __float_as_uint(dv[rr]));
             ++cnt;
           }
         }
@@ -246,7 +256,7 @@ __device__ __forceinline__ void fwd_lists_block(const FwdSparseArgs& A, int bh_,
   lo = fminf(lo, hi);
 
   // ---------------------------------------------- 2. candidate lists at tau_lb
-  uint2* mylist = A.cand + (row_idx * 2 + q.hh) * kCandCap;
+  uint2* mylist = A.cand + list_entry<kCandCap>(q.bh, A.nqb, q.qb, q.wave, q.lane);
   int cnt = 0;
   const bool fits = collect_sweep<C, T, D, kCandCap>(q, g, A.K, tiles, ovf, live, lo, A.cells, mylist, cnt, n_qk2, n_cand_tiles);
   if (!fits) {
@@ -355,7 +365,7 @@ __global__ __launch_bounds__(kThreads) void fwd_finish_kernel(FwdSparseArgs A) {
   const float a = (g.alpha - 1.0f) * fabsf(c);  // same arithmetic as the sweeps that made the lists
   const int cnt = live ? A.lcnt[row_idx * 2 + rl.hh] : 0;
   const float2 bd = live ? A.bounds[row_idx] : make_float2(0.f, 0.f);
-  const uint2* mylist = A.cand + (row_idx * 2 + rl.hh) * kCandCap;
+  const uint2* mylist = A.cand + list_entry<kCandCap>(rl.bh, A.nqb, rl.qb, threadIdx.x >> 6, threadIdx.x & 63);
   const T* Vbh = reinterpret_cast<const T*>(A.V) + (long long)rl.b * g.kv_sb + (long long)rl.h * g.kv_sh;
   float lo = bd.x, hi = bd.y, tau = bd.x;
   unsigned n_support = 0;
@@ -367,7 +377,7 @@ __global__ __launch_bounds__(kThreads) void fwd_finish_kernel(FwdSparseArgs A) {
     unsigned jv[NE];
 #pragma unroll
     for (int e = 0; e < NE; ++e) {
-      uint2 en = (e < cnt) ? mylist[e] : make_uint2(0u, 0u);
+      uint2 en = (e < cnt) ? mylist[e * kListStride] : make_uint2(0u, 0u);
       jv[e] = en.x;
       yv[e] = (e < cnt) ? a * __uint_as_float(en.y) : -kInf;  // -inf: never positive
     }
