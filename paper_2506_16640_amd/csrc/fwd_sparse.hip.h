@@ -65,13 +65,14 @@ constexpr int kCellsPerBlock = 16 / kCellKeys;
 
 template <int CAP>
 struct CellBuf {
-  f32x4_t* d;  // [CAP][kCellGroups] raw scores
-  int* j;      // [CAP] key of the cell's first score
+  // cell s of the 256 threads of a workgroup together (s-major), for the same reason as the row lists
+  f32x4_t* d;  // cell s, group u at d[(s * kCellGroups + u) * kThreads]: raw scores
+  int* j;      // cell s at j[s * kThreads]: key of the cell's first score
   static constexpr size_t kBytesPerWorkgroup = (size_t)kThreads * CAP * (16 * kCellGroups + 4);
   __device__ __forceinline__ void init(void* base, int tid) {
     char* wg = reinterpret_cast<char*>(base) + (size_t)blockIdx.x * kBytesPerWorkgroup;
-    d = reinterpret_cast<f32x4_t*>(wg) + (size_t)tid * CAP * kCellGroups;
-    j = reinterpret_cast<int*>(wg + (size_t)kThreads * CAP * 16 * kCellGroups) + (size_t)tid * CAP;
+    d = reinterpret_cast<f32x4_t*>(wg) + tid;
+    j = reinterpret_cast<int*>(wg + (size_t)kThreads * CAP * 16 * kCellGroups) + tid;
   }
 };
 
@@ -138,9 +139,9 @@ __device__ __forceinline__ bool collect_sweep(const C& q, const Geom& g, const v
 #pragma unroll
               for (int u = 0; u < kCellGroups; ++u) {
                 const int e0 = 4 * (cl * kCellGroups + u);
-                cb.d[slot * kCellGroups + u] = f32x4_t{acc[sb][e0], acc[sb][e0 + 1], acc[sb][e0 + 2], acc[sb][e0 + 3]};
+                cb.d[(slot * kCellGroups + u) * kThreads] = f32x4_t{acc[sb][e0], acc[sb][e0 + 1], acc[sb][e0 + 2], acc[sb][e0 + 3]};
               }
-              cb.j[slot] = j0 + q.key_of(4 * cl * kCellGroups);
+              cb.j[slot * kThreads] = j0 + q.key_of(4 * cl * kCellGroups);
               ++ncell;
             }
           }
@@ -154,10 +155,10 @@ __device__ __forceinline__ bool collect_sweep(const C& q, const Geom& g, const v
   if (fits) {
     // a cell holds at most kCellKeys candidates, so there are at least as many candidates as cells
     for (int k = 0; k < ncell; ++k) {
-      const int jc = cb.j[k];
+      const int jc = cb.j[k * kThreads];
 #pragma unroll
       for (int u = 0; u < kCellGroups; ++u) {
-        const f32x4_t dv = cb.d[k * kCellGroups + u];
+        const f32x4_t dv = cb.d[(k * kCellGroups + u) * kThreads];
 #pragma unroll
         for (int rr = 0; rr < 4; ++rr) {
           if (dv[rr] > cut) {
