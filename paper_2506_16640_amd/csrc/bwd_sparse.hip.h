@@ -109,14 +109,6 @@ __global__ __launch_bounds__(kThreads) void bwd_rows_kernel(BwdSparseArgs A) {
   const Geom& g = A.g;
   RowLane rl;
   rl.init(g, A.nqb);
-  {
-    // OR of the head's block flags; the head's first workgroup publishes it for the kernels that follow
-    bool any = false;
-    for (int k = threadIdx.x; k < A.nqb; k += kThreads) any = any || A.block_flag[rl.bh * A.nqb + k] != 0;
-    const int head_any = __syncthreads_or(any ? 1 : 0);
-    if (rl.qb == 0 && threadIdx.x == 0) A.head_flag[rl.bh] = head_any ? 1 : 0;
-    if (head_any) return;  // the tiled kernels own this head
-  }
   constexpr int DH = D / 2;
   const float r = 1.0f / (g.alpha - 1.0f);
   const long long row_idx = (long long)rl.bh * g.Nq + (rl.valid ? rl.i : 0);
@@ -127,8 +119,11 @@ __global__ __launch_bounds__(kThreads) void bwd_rows_kernel(BwdSparseArgs A) {
   const float c = scale * inv_sqrt_d;
   const float a = (g.alpha - 1.0f) * fabsf(c);  // same arithmetic as the sweep that made the lists
   const float sgn = (c < 0.f) ? -1.f : 1.f;
-  const float tau = live ? A.tau[row_idx] : 0.f;
-  const int cnt = live ? A.lcnt[row_idx * 2 + rl.hh] : 0;
+  // every load that does not depend on another is issued before the first wait (the head's flags included)
+  const float tau_raw = A.tau[row_idx];
+  const int cnt_raw = A.lcnt[row_idx * 2 + rl.hh];
+  const float tau = live ? tau_raw : 0.f;
+  const int cnt = live ? cnt_raw : 0;
   const long long q_base = (long long)rl.b * g.q_sb + (long long)rl.h * g.q_sh;
   const long long kv_base = (long long)rl.b * g.kv_sb + (long long)rl.h * g.kv_sh;
   const long long list0 = list_entry<kBwdCap>(rl.bh, A.nqb, rl.qb, threadIdx.x >> 6, threadIdx.x & 63);
@@ -146,6 +141,19 @@ __global__ __launch_bounds__(kThreads) void bwd_rows_kernel(BwdSparseArgs A) {
     for (int t = 0; t < DH; ++t) dov[t] = 0.f;
   }
   unsigned n_entries = 0;
+  // the first entries are requested before the list length is known (the slots exist whatever they hold)
+  constexpr int kEarly = 4;
+  uint2 early[kEarly];
+#pragma unroll
+  for (int e = 0; e < kEarly; ++e) early[e] = mylist[e * kListStride];
+  {
+    // OR of the head's block flags; the head's first workgroup publishes it for the kernels that follow
+    bool any = false;
+    for (int k = threadIdx.x; k < A.nqb; k += kThreads) any = any || A.block_flag[rl.bh * A.nqb + k] != 0;
+    const int head_any = __syncthreads_or(any ? 1 : 0);
+    if (rl.qb == 0 && threadIdx.x == 0) A.head_flag[rl.bh] = head_any ? 1 : 0;
+    if (head_any) return;  // the tiled kernels own this head
+  }
 
   auto finish = [&](auto ne_tag) {
     constexpr int NE = decltype(ne_tag)::value;
@@ -153,8 +161,12 @@ __global__ __launch_bounds__(kThreads) void bwd_rows_kernel(BwdSparseArgs A) {
     float dv[NE];  // raw dot products (sign-folded), -inf for empty slots
 #pragma unroll
     for (int e = 0; e < NE; ++e) {
-      uint2 en = (e < cnt) ? mylist[e * kListStride] : make_uint2(0u, 0u);
-      jv[e] = en.x;
+      uint2 en = make_uint2(0u, 0u);
+      if (e < kEarly)
+        en = early[e];
+      else if (e < cnt)
+        en = mylist[e * kListStride];
+      jv[e] = (e < cnt) ? en.x : 0u;
       dv[e] = (e < cnt) ? __uint_as_float(en.y) : -kInf;
     }
     // pass 1: dP of every entry of the row (both halves), row sums

@@ -355,7 +355,8 @@ __global__ __launch_bounds__(kThreads) void fwd_finish_kernel(FwdSparseArgs A) {
     const bool head_any = __ballot(any) != 0ull;
     if (threadIdx.x == 0) A.head_flag[rl.bh] = head_any ? 1 : 0;
   }
-  if (A.dense_flag[rl.bh * A.nqb + rl.qb] != 0) return;  // the tiled kernel owns this block
+  // (the flag is tested further down: every load that does not depend on another is issued first)
+  const int block_dense = A.dense_flag[rl.bh * A.nqb + rl.qb];
   constexpr int DH = D / 2;
   const float r = 1.0f / (g.alpha - 1.0f);
   const long long row_idx = (long long)rl.bh * g.Nq + (rl.valid ? rl.i : 0);
@@ -364,12 +365,21 @@ __global__ __launch_bounds__(kThreads) void fwd_finish_kernel(FwdSparseArgs A) {
   const float scale = rl.valid ? row_scale(g, rl.b, rl.h, rl.i, lim, nullptr, nullptr, nullptr) : 0.f;
   const float c = scale * (1.0f / sqrtf((float)D));
   const float a = (g.alpha - 1.0f) * fabsf(c);  // same arithmetic as the sweeps that made the lists
-  const int cnt = live ? A.lcnt[row_idx * 2 + rl.hh] : 0;
-  const float2 bd = live ? A.bounds[row_idx] : make_float2(0.f, 0.f);
+  const int cnt_raw = A.lcnt[row_idx * 2 + rl.hh];
+  const float2 bd_raw = A.bounds[row_idx];
+  const int cnt = live ? cnt_raw : 0;
+  const float2 bd = live ? bd_raw : make_float2(0.f, 0.f);
   const uint2* mylist = A.cand + list_entry<kCandCap>(rl.bh, A.nqb, rl.qb, threadIdx.x >> 6, threadIdx.x & 63);
   const T* Vbh = reinterpret_cast<const T*>(A.V) + (long long)rl.b * g.kv_sb + (long long)rl.h * g.kv_sh;
   float lo = bd.x, hi = bd.y, tau = bd.x;
   unsigned n_support = 0;
+  // the first entries are requested before the list length is known (the slots exist whatever they hold):
+  // one memory round trip less on the critical path of this latency-bound kernel
+  constexpr int kEarly = 4;
+  uint2 early[kEarly];
+#pragma unroll
+  for (int e = 0; e < kEarly; ++e) early[e] = mylist[e * kListStride];
+  if (block_dense != 0) return;  // the tiled kernel owns this block
 
   // NE: list entries per lane held in registers; chosen per wave from the longest list it holds
   auto finish = [&](auto ne_tag) {
@@ -378,8 +388,12 @@ __global__ __launch_bounds__(kThreads) void fwd_finish_kernel(FwdSparseArgs A) {
     unsigned jv[NE];
 #pragma unroll
     for (int e = 0; e < NE; ++e) {
-      uint2 en = (e < cnt) ? mylist[e * kListStride] : make_uint2(0u, 0u);
-      jv[e] = en.x;
+      uint2 en = make_uint2(0u, 0u);
+      if (e < kEarly)
+        en = early[e];
+      else if (e < cnt)
+        en = mylist[e * kListStride];
+      jv[e] = (e < cnt) ? en.x : 0u;
       yv[e] = (e < cnt) ? a * __uint_as_float(en.y) : -kInf;  // -inf: never positive
     }
     bool done = !live;
