@@ -105,7 +105,7 @@ __global__ __launch_bounds__(kThreads, 3) void bwd_lists_kernel(BwdSparseArgs A)
 
 // Everything row-wise from the lists: one lane pair per row, each lane half of the features.
 template <typename T, int D, int AM>
-__global__ __launch_bounds__(kThreads) void bwd_rows_kernel(BwdSparseArgs A) {
+__global__ __launch_bounds__(kThreads, 2) void bwd_rows_kernel(BwdSparseArgs A) {
   const Geom& g = A.g;
   RowLane rl;
   rl.init(g, A.nqb);
@@ -169,9 +169,21 @@ __global__ __launch_bounds__(kThreads) void bwd_rows_kernel(BwdSparseArgs A) {
       jv[e] = (e < cnt) ? en.x : 0u;
       dv[e] = (e < cnt) ? __uint_as_float(en.y) : -kInf;
     }
-    // pass 1: dP of every entry of the row (both halves), row sums
-    float dpv[2][NE];
-    float Z = 0.f, N = 0.f;
+    // One gather pass over the entries of the row (both halves): dP = <dO, v_j> and, because dQ and dscale
+    // are linear in mu,
+    //   dQ_i = c (sum_j g dP k_j - mu sum_j g k_j),   dscale_i = sum_j g dP d_j - mu sum_j g d_j,
+    // the K rows are gathered in the same pass as the V rows: one memory round trip for both.
+    float dpv[NE];  // dP of the lane's own entries
+    float Z = 0.f, N = 0.f, sd1 = 0.f, sd0 = 0.f;
+    float qa[DH], qb[DH];  // this lane's half of sum g dP k and of sum g k
+#pragma unroll
+    for (int t = 0; t < DH; ++t) qa[t] = qb[t] = 0.f;
+    int slotv[NE];  // arrival numbers of the lane's own entries; -1: not part of the support
+#pragma unroll
+    for (int e = 0; e < NE; ++e) {
+      slotv[e] = -1;
+      dpv[e] = 0.f;
+    }
 #pragma unroll
     for (int e = 0; e < NE; ++e) {
       unsigned pj = (unsigned)__shfl_xor((int)jv[e], 32);
@@ -182,57 +194,50 @@ __global__ __launch_bounds__(kThreads) void bwd_rows_kernel(BwdSparseArgs A) {
         unsigned j = (rl.hh == src) ? jv[e] : pj;
         float d = (rl.hh == src) ? dv[e] : pd;
         float x = (d > -kInf) ? fmaxf(fmaf(d, a, -tau), 0.f) : 0.f;
-        dpv[src][e] = 0.f;
         if (__ballot(x > 0.f) == 0ull) continue;
         float part = 0.f;
+        float kk[DH];
         if (x > 0.f) {
           float vv[DH];
           load_row_f32<T>(Vbh + (long long)j * g.kv_sn + rl.hh * DH, DH, vv);
+          load_row_f32<T>(Kbh + (long long)j * g.kv_sn + rl.hh * DH, DH, kk);
+          // the entry's owner takes its arrival number among the key's entries: its place in the key's segment
+          if (rl.hh == src) {
+            slotv[e] = atomicAdd(&A.kcount[(long long)rl.bh * g.Nk + j], 1);
+            ++n_entries;
+          }
 #pragma unroll
           for (int t = 0; t < DH; ++t) part = fmaf(dov[t], vv[t], part);
         }
         float dp = part + __shfl_xor(part, 32);
-        dpv[src][e] = dp;
-        float gg = pow_rm1<AM>(x, r);
-        Z += gg;
-        N = fmaf(gg, (x > 0.f) ? dp : 0.f, N);
+        if (x > 0.f) {
+          float gg = pow_rm1<AM>(x, r);
+          float gdp = gg * dp;
+          Z += gg;
+          N += gdp;
+          sd1 = fmaf(gdp, d, sd1);
+          sd0 = fmaf(gg, d, sd0);
+#pragma unroll
+          for (int t = 0; t < DH; ++t) {
+            qa[t] = fmaf(gdp, kk[t], qa[t]);
+            qb[t] = fmaf(gg, kk[t], qb[t]);
+          }
+          if (rl.hh == src) dpv[e] = dp;
+        }
       }
     }
     const float mu = (Z > 0.f) ? N / Z : 0.f;
-    // pass 2: dS, dQ, dscale and the per-entry records
     float dq[DH];
 #pragma unroll
-    for (int t = 0; t < DH; ++t) dq[t] = 0.f;
-    float dsc = 0.f;
-    int slotv[NE];  // arrival numbers of the lane's own entries; -1: not part of the support
-#pragma unroll
-    for (int e = 0; e < NE; ++e) slotv[e] = -1;
+    for (int t = 0; t < DH; ++t) dq[t] = c * fmaf(-mu, qb[t], qa[t]);
+    const float dsc = fmaf(-mu, sd0, sd1);
+    // the per-entry records for the key side
 #pragma unroll
     for (int e = 0; e < NE; ++e) {
-      unsigned pj = (unsigned)__shfl_xor((int)jv[e], 32);
-      float pd = __shfl_xor(dv[e], 32);
-#pragma unroll
-      for (int src = 0; src < 2; ++src) {
-        unsigned j = (rl.hh == src) ? jv[e] : pj;
-        float d = (rl.hh == src) ? dv[e] : pd;
-        float x = (d > -kInf) ? fmaxf(fmaf(d, a, -tau), 0.f) : 0.f;
-        if (__ballot(x > 0.f) == 0ull) continue;
-        if (x > 0.f) {
-          float gg = pow_rm1<AM>(x, r);
-          float ds = gg * (dpv[src][e] - mu);
-          float w = c * ds;
-          dsc = fmaf(ds, d, dsc);
-          float kk[DH];
-          load_row_f32<T>(Kbh + (long long)j * g.kv_sn + rl.hh * DH, DH, kk);
-#pragma unroll
-          for (int t = 0; t < DH; ++t) dq[t] = fmaf(w, kk[t], dq[t]);
-          if (rl.hh == src) {  // the entry's owner records it for the key side
-            mypw[e * kListStride] = make_float2(pow_r<AM>(x, r), w);
-            // arrival number of this entry among the key's entries: its place in the key's segment
-            slotv[e] = atomicAdd(&A.kcount[(long long)rl.bh * g.Nk + j], 1);
-            ++n_entries;
-          }
-        }
+      if (slotv[e] >= 0) {
+        float x = fmaxf(fmaf(dv[e], a, -tau), 0.f);
+        float ds = pow_rm1<AM>(x, r) * (dpv[e] - mu);
+        mypw[e * kListStride] = make_float2(pow_r<AM>(x, r), c * ds);
       }
     }
     // the returned arrival numbers are only needed now: the atomics above overlap each other
