@@ -108,13 +108,15 @@ def main():
                      device=dev)
     out = torch.empty_like(t["Q"])
     tau = torch.empty(B, H, n, dtype=torch.float32, device=dev)
+    # what a training step keeps between forward and backward: O, tau and the rows' candidate lists
+    saved = binding.new_saved(prm, dev) if do_bwd else None
 
     def step(fwd_ev=None, bwd_ev=None, stats=None):
         binding.entmax_attn_fwd(t["Q"], t["K"], t["V"], out=out, tau=tau, workspace=ws, stats=stats,
-                                phase_events=fwd_ev, **kw)
+                                phase_events=fwd_ev, saved=saved, **kw)
         if do_bwd:
             return binding.entmax_attn_bwd(t["Q"], t["K"], t["V"], out, t["dO"], tau, workspace=ws, stats=stats,
-                                           phase_events=bwd_ev, **kw)
+                                           phase_events=bwd_ev, saved=saved, **kw)
         return None
 
     # tile counters (one untimed step): executed work and tile-skip rate

@@ -108,7 +108,7 @@ enum {
   ENTMAX_FWD_NUM_PHASES = 4
 };
 enum {
-  ENTMAX_BWD_PHASE_LISTS = 0,      /* support-list kernel: one Q K^T sweep at the saved threshold */
+  ENTMAX_BWD_PHASE_LISTS = 0,      /* support-list kernel: one Q K^T sweep at the saved threshold (without `saved`) */
   ENTMAX_BWD_PHASE_ROWS = 1,       /* mu, dscale, dQ and the per-entry (p, dS) from the lists */
   ENTMAX_BWD_PHASE_TRANSPOSE = 2,  /* tiled path (heads the list kernel left over): operand copies */
   ENTMAX_BWD_PHASE_MASK = 3,       /* tiled path: non-zero tile map */
@@ -125,6 +125,10 @@ enum {
  *   out: O (dtype, written for every row), tau [B,H,Nq] fp32 (saved for the backward).
  *        A row with no visible key gets O = 0, tau = 0.
  *   stats: NULL or device uint64[ENTMAX_ATTN_NUM_STATS], added to.
+ *   saved: NULL, or device memory of entmax_attn_saved_bytes(p) bytes, 256-byte aligned, owned by the
+ *        caller: receives the rows' candidate lists (key, raw score) -- a superset of each row's support
+ *        (Sec. 2.2: the keys with non-zero probability) -- for the backward, which then skips its own
+ *        Q K^T sweep.  Opaque; valid only together with this call's tau and the same params and inputs.
  *   workspace: device scratch of at least entmax_attn_workspace_bytes(p, 0)
  *        bytes, 256-byte aligned; contents are undefined afterwards.
  * The row threshold is found from sweeps over the key tiles that recompute
@@ -136,7 +140,7 @@ enum {
  * matrix cores with zero tiles skipped.
  */
 int entmax_attn_fwd(const entmax_attn_params* p, const void* Q, const void* K, const void* V, const float* beta,
-                    const float* gamma, void* O, float* tau, uint64_t* stats, void* workspace,
+                    const float* gamma, void* O, float* tau, void* saved, uint64_t* stats, void* workspace,
                     size_t workspace_bytes, void* hip_stream, void* const* phase_events);
 
 /*
@@ -147,6 +151,10 @@ int entmax_attn_fwd(const entmax_attn_params* p, const void* Q, const void* K, c
  *        accumulated); ignored (may be NULL) for scale_layout 0.
  *   O is accepted for symmetry with the usual attention backward and may be NULL
  *   (the row term is rebuilt from tau, not from O).
+ *   saved: NULL, or the buffer the forward filled for these same inputs (read only).  With it the
+ *        rows' supports are taken from the forward's lists (entries whose probability is zero at tau
+ *        are dropped); without it one Q K^T sweep at tau rebuilds them.  Same results either way up
+ *        to the summation order inside a row.
  *   workspace: at least entmax_attn_workspace_bytes(p, 1) bytes, 256-byte aligned.
  * `path` selects as in the forward: 0 = support lists per row and per key for heads whose rows
  * have few non-zero probabilities, tiled kernels for the other heads; 1 = tiled kernels only.
@@ -154,13 +162,17 @@ int entmax_attn_fwd(const entmax_attn_params* p, const void* Q, const void* K, c
  * list path sums each key's entries in query order whenever a key has at most 64 of them.
  */
 int entmax_attn_bwd(const entmax_attn_params* p, const void* Q, const void* K, const void* V, const void* O,
-                    const void* dO, const float* tau, const float* beta, const float* gamma, void* dQ, void* dK,
-                    void* dV, float* dbeta, float* dgamma, uint64_t* stats, void* workspace, size_t workspace_bytes,
-                    void* hip_stream, void* const* phase_events);
+                    const void* dO, const float* tau, const void* saved, const float* beta, const float* gamma,
+                    void* dQ, void* dK, void* dV, float* dbeta, float* dgamma, uint64_t* stats, void* workspace,
+                    size_t workspace_bytes, void* hip_stream, void* const* phase_events);
 
 /* Scratch bytes the forward (is_bwd = 0) or backward (is_bwd != 0) needs for
  * these parameters; 0 if the parameters are invalid. Host-only, no GPU call. */
 size_t entmax_attn_workspace_bytes(const entmax_attn_params* p, int is_bwd);
+
+/* Bytes of the optional `saved` buffer that carries the forward's lists to the backward;
+ * 0 if the parameters are invalid. Host-only, no GPU call. */
+size_t entmax_attn_saved_bytes(const entmax_attn_params* p);
 
 /* Validates parameters without touching the GPU: returns the status the
  * entry points would return for them (pointer checks excluded). */

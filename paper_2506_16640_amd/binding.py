@@ -45,12 +45,14 @@ class Params(ctypes.Structure):
 
 _vp = ctypes.c_void_p
 _lib.entmax_attn_fwd.restype = ctypes.c_int
-_lib.entmax_attn_fwd.argtypes = [ctypes.POINTER(Params), _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp,
+_lib.entmax_attn_fwd.argtypes = [ctypes.POINTER(Params), _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp,
                                  ctypes.c_size_t, _vp, _vp]
 _lib.entmax_attn_bwd.restype = ctypes.c_int
-_lib.entmax_attn_bwd.argtypes = [ctypes.POINTER(Params)] + [_vp] * 15 + [ctypes.c_size_t, _vp, _vp]
+_lib.entmax_attn_bwd.argtypes = [ctypes.POINTER(Params)] + [_vp] * 16 + [ctypes.c_size_t, _vp, _vp]
 _lib.entmax_attn_workspace_bytes.restype = ctypes.c_size_t
 _lib.entmax_attn_workspace_bytes.argtypes = [ctypes.POINTER(Params), ctypes.c_int]
+_lib.entmax_attn_saved_bytes.restype = ctypes.c_size_t
+_lib.entmax_attn_saved_bytes.argtypes = [ctypes.POINTER(Params)]
 _lib.entmax_attn_check_params.restype = ctypes.c_int
 _lib.entmax_attn_check_params.argtypes = [ctypes.POINTER(Params)]
 _lib.entmax_attn_strerror.restype = ctypes.c_char_p
@@ -96,6 +98,15 @@ def workspace_bytes(params, is_bwd):
     return int(_lib.entmax_attn_workspace_bytes(ctypes.byref(params), int(is_bwd)))
 
 
+def saved_bytes(params):
+    return int(_lib.entmax_attn_saved_bytes(ctypes.byref(params)))
+
+
+def new_saved(params, device="cuda"):
+    """Buffer that carries the forward's lists to the backward (pass it to both as `saved`)."""
+    return torch.empty(max(saved_bytes(params), 256), dtype=torch.uint8, device=device)
+
+
 def check_params(params):
     return int(_lib.entmax_attn_check_params(ctypes.byref(params)))
 
@@ -113,10 +124,11 @@ def _stream():
 
 
 def entmax_attn_fwd(q, k, v, alpha=1.5, beta=None, gamma=None, delta=1.0, causal=True, logn_mode=0, path=0,
-                    out=None, tau=None, stats=None, workspace=None, phase_events=None):
+                    out=None, tau=None, stats=None, workspace=None, phase_events=None, saved=None):
     """O, tau = entmax attention forward.  q [B,H,Nq,D], k,v [B,H,Nk,D] on the GPU, bf16 or fp32;
     beta,gamma fp32 [H] or [B,H,Nq] or None.  stats: optional uint64/int64 device tensor [16] (added to).
-    path: 0 automatic, 1 tiled kernel only.  phase_events: optional list of FWD_NUM_PHASES + 1 hipEvent_t handles."""
+    path: 0 automatic, 1 tiled kernel only.  phase_events: optional list of FWD_NUM_PHASES + 1 hipEvent_t handles.
+    saved: optional uint8 device tensor of saved_bytes(params) bytes, filled for the backward."""
     p = make_params(q, k, alpha, delta, causal, beta, logn_mode, path)
     assert v.shape == k.shape and v.stride() == k.stride()
     if out is None:
@@ -130,15 +142,16 @@ def entmax_attn_fwd(q, k, v, alpha=1.5, beta=None, gamma=None, delta=1.0, causal
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
     ev = _events_arg(phase_events, FWD_NUM_PHASES)
     rc = _lib.entmax_attn_fwd(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(beta), _ptr(gamma), _ptr(out),
-                              _ptr(tau), _ptr(stats), _ptr(workspace), workspace.numel(), _stream(), ev)
+                              _ptr(tau), _ptr(saved), _ptr(stats), _ptr(workspace), workspace.numel(), _stream(), ev)
     if rc != 0:
         raise EntmaxAttnError(rc)
     return out, tau
 
 
 def entmax_attn_bwd(q, k, v, o, do, tau, alpha=1.5, beta=None, gamma=None, delta=1.0, causal=True, logn_mode=0, path=0,
-                    stats=None, workspace=None, phase_events=None):
-    """dQ, dK, dV, dbeta, dgamma = entmax attention backward (dbeta/dgamma None without scale parameters)."""
+                    stats=None, workspace=None, phase_events=None, saved=None):
+    """dQ, dK, dV, dbeta, dgamma = entmax attention backward (dbeta/dgamma None without scale parameters).
+    saved: the buffer the forward filled for the same inputs, or None."""
     p = make_params(q, k, alpha, delta, causal, beta, logn_mode, path)
     assert v.stride() == k.stride() and do.stride() == q.stride()
     dq = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device)
@@ -150,8 +163,8 @@ def entmax_attn_bwd(q, k, v, o, do, tau, alpha=1.5, beta=None, gamma=None, delta
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
     ev = _events_arg(phase_events, BWD_NUM_PHASES)
-    rc = _lib.entmax_attn_bwd(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(do), _ptr(tau), _ptr(beta),
-                              _ptr(gamma), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(dbeta), _ptr(dgamma), _ptr(stats),
+    rc = _lib.entmax_attn_bwd(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(do), _ptr(tau), _ptr(saved),
+                              _ptr(beta), _ptr(gamma), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(dbeta), _ptr(dgamma), _ptr(stats),
                               _ptr(workspace), workspace.numel(), _stream(), ev)
     if rc != 0:
         raise EntmaxAttnError(rc)

@@ -43,7 +43,11 @@ struct BwdSparseArgs {
                        // second word by the entry's arrival number within its key (key index kNoKey: dropped)
   float2* pw;          // same layout: (p_ij, c_i dS_ij)
   void* cells;         // sweep scratch: per workgroup and lane, kBwdCap cells
-  int* lcnt;           // [B*H*Nq][2] entries per half row
+  int* lcnt;           // [B*H*Nq][2] entries per half row, written by bwd_lists_kernel or bwd_prepare_kernel
+  const uint2* src_list;  // what bwd_rows_kernel reads: jlist, or the forward's candidate lists (`saved` buffer,
+                          // kCandCap entries per lane)
+  const int* src_lcnt;    // forward's list lengths   } only with the forward's lists,
+  const int* src_dense;   // forward's block flags    } read by bwd_prepare_kernel
   int* kcount;         // [B*H*Nk] entries per key (zeroed by bwd_lists_kernel)
   int* koffs;          // [B*H*Nk] exclusive prefix sums of kcount within the head
   int* csc_i;          // [B*H][Nq*2*kBwdCap] query row of each entry, key-major
@@ -103,8 +107,55 @@ __global__ __launch_bounds__(kThreads, 3) void bwd_lists_kernel(BwdSparseArgs A)
   }
 }
 
+// With the forward's lists there is no sweep: this kernel does the sweep kernel's bookkeeping.  One
+// workgroup per query block: the list lengths bwd_rows_kernel will use, the block's flag (a support
+// longer than kBwdCap, or a block the forward left to its tiled kernel), the block's share of the
+// per-key counters, the long-key counter.  A candidate list longer than kBwdCap is rare: its entries
+// with non-zero probability at tau are copied to the lane's own list, and the length carries
+// kListInWorkspace to say so.
+constexpr int kListInWorkspace = 1 << 30;
+constexpr int kListCountMask = 0xffff;
+
+template <int D>
+__global__ __launch_bounds__(kThreads) void bwd_prepare_kernel(BwdSparseArgs A) {
+  const Geom& g = A.g;
+  RowLane rl;
+  rl.init(g, A.nqb);
+  const long long row_idx = (long long)rl.bh * g.Nq + (rl.valid ? rl.i : 0);
+  const int lim = rl.valid ? row_limit(g, rl.i) : 0;
+  const bool dense = A.src_dense[rl.bh * A.nqb + rl.qb] != 0;  // (its list lengths mean nothing)
+  int cnt = (rl.valid && lim > 0 && !dense) ? A.src_lcnt[row_idx * 2 + rl.hh] : 0;
+  bool over = dense;
+  if (cnt > kBwdCap) {
+    const float scale = row_scale(g, rl.b, rl.h, rl.i, lim, nullptr, nullptr, nullptr);
+    const float a = (g.alpha - 1.0f) * fabsf(scale * (1.0f / sqrtf((float)D)));  // as in the kernels that made the lists
+    const float tau = A.tau[row_idx];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint2* src = A.src_list + list_entry<kCandCap>(rl.bh, A.nqb, rl.qb, wave, lane);
+    uint2* dst = A.jlist + list_entry<kBwdCap>(rl.bh, A.nqb, rl.qb, wave, lane);
+    int m = 0;
+    for (int e = 0; e < min(cnt, kCandCap); ++e) {
+      const uint2 en = src[e * kListStride];
+      if (fmaf(__uint_as_float(en.y), a, -tau) > 0.f) {
+        if (m < kBwdCap) dst[m * kListStride] = en;
+        ++m;
+      }
+    }
+    over = m > kBwdCap;
+    cnt = min(m, kBwdCap) | kListInWorkspace;
+  }
+  if (rl.valid) A.lcnt[row_idx * 2 + rl.hh] = cnt;
+  const int any_over = __syncthreads_or(over ? 1 : 0);
+  if (threadIdx.x == 0) A.block_flag[rl.bh * A.nqb + rl.qb] = any_over ? 1 : 0;
+  const int chunk = (g.Nk + A.nqb - 1) / A.nqb;
+  const int j_end = min(g.Nk, (rl.qb + 1) * chunk);
+  for (int j = rl.qb * chunk + (int)threadIdx.x; j < j_end; j += kThreads) A.kcount[(long long)rl.bh * g.Nk + j] = 0;
+  if (blockIdx.x == 0 && threadIdx.x == 0) A.head_flag[g.B * g.H + kLongCountOffset] = 0;
+}
+
 // Everything row-wise from the lists: one lane pair per row, each lane half of the features.
-template <typename T, int D, int AM>
+// SRC_CAP: capacity (slot count) of the lists that are read.
+template <typename T, int D, int AM, int SRC_CAP>
 __global__ __launch_bounds__(kThreads, 2) void bwd_rows_kernel(BwdSparseArgs A) {
   const Geom& g = A.g;
   RowLane rl;
@@ -123,12 +174,14 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_rows_kernel(BwdSparseArgs A) 
   const float tau_raw = A.tau[row_idx];
   const int cnt_raw = A.lcnt[row_idx * 2 + rl.hh];
   const float tau = live ? tau_raw : 0.f;
-  const int cnt = live ? cnt_raw : 0;
+  const int cnt = live ? min(cnt_raw & kListCountMask, kBwdCap) : 0;
+  const bool in_ws = SRC_CAP != kBwdCap && live && (cnt_raw & kListInWorkspace) != 0;  // entries in this lane's own list
   const long long q_base = (long long)rl.b * g.q_sb + (long long)rl.h * g.q_sh;
   const long long kv_base = (long long)rl.b * g.kv_sb + (long long)rl.h * g.kv_sh;
   const long long list0 = list_entry<kBwdCap>(rl.bh, A.nqb, rl.qb, threadIdx.x >> 6, threadIdx.x & 63);
   uint2* mylist = A.jlist + list0;
   float2* mypw = A.pw + list0;
+  const uint2* srclist = A.src_list + list_entry<SRC_CAP>(rl.bh, A.nqb, rl.qb, threadIdx.x >> 6, threadIdx.x & 63);
   const T* Kbh = reinterpret_cast<const T*>(A.K) + kv_base;
   const T* Vbh = reinterpret_cast<const T*>(A.V) + kv_base;
 
@@ -145,7 +198,12 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_rows_kernel(BwdSparseArgs A) 
   constexpr int kEarly = 4;
   uint2 early[kEarly];
 #pragma unroll
-  for (int e = 0; e < kEarly; ++e) early[e] = mylist[e * kListStride];
+  for (int e = 0; e < kEarly; ++e) early[e] = srclist[e * kListStride];
+  const uint2* rdlist = in_ws ? mylist : srclist;
+  if (SRC_CAP != kBwdCap && __ballot(in_ws) != 0ull) {
+#pragma unroll
+    for (int e = 0; e < kEarly; ++e) early[e] = rdlist[e * kListStride];
+  }
   {
     // OR of the head's block flags; the head's first workgroup publishes it for the kernels that follow
     bool any = false;
@@ -165,7 +223,7 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_rows_kernel(BwdSparseArgs A) 
       if (e < kEarly)
         en = early[e];
       else if (e < cnt)
-        en = mylist[e * kListStride];
+        en = rdlist[e * kListStride];
       jv[e] = (e < cnt) ? en.x : 0u;
       dv[e] = (e < cnt) ? __uint_as_float(en.y) : -kInf;
     }
@@ -303,7 +361,7 @@ __global__ __launch_bounds__(kThreads) void csc_scatter_kernel(BwdSparseArgs A) 
   const int i = qb * kBlockRows + wave * 32 + (lane & 31);
   if (i >= g.Nq) return;
   const long long half_row = ((long long)bh * g.Nq + i) * 2 + (lane >> 5);
-  const int cnt = min(A.lcnt[half_row], kBwdCap);
+  const int cnt = min(A.lcnt[half_row] & kListCountMask, kBwdCap);
   const long long list0 = list_entry<kBwdCap>(bh, A.nqb, qb, wave, lane);
   const long long base = (long long)bh * g.Nq * 2 * kBwdCap;
   for (int e = 0; e < cnt; ++e) {

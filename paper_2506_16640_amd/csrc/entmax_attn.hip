@@ -29,7 +29,7 @@ struct Layout {
   long long q_sb, q_sh, q_sn, kv_sb, kv_sh, kv_sn;
   // workspace offsets
   size_t off_vt, off_cand, off_flcnt, off_bounds, off_flags, off_kt, off_qt, off_dot, off_mu, off_crow, off_dscale, off_mask,
-      off_jlist, off_pw, off_lcnt, off_kcount, off_koffs, off_kcursor, off_csc_i, off_csc_pw, off_hflag, off_longkeys, off_fcells, off_bcells, total_fwd,
+      off_jlist, off_pw, off_lcnt, off_kcount, off_koffs, off_kcursor, off_csc_i, off_csc_pw, off_hflag, off_longkeys, off_fcells, off_bcells, sv_cand, sv_lcnt, sv_flags, total_saved, total_fwd,
       total_bwd;
 };
 
@@ -88,6 +88,11 @@ Layout make_layout(const entmax_attn_params* p) {
   L.off_vt = 0;
   L.off_cand = kt_bytes;
   size_t cand_bytes = align_up(bh * (size_t)L.nqb * kThreads * kCandCap * sizeof(uint2));  // one list per lane of the list grid
+  // the `saved` buffer: the same three arrays, for the backward
+  L.sv_cand = 0;
+  L.sv_lcnt = cand_bytes;
+  L.sv_flags = L.sv_lcnt + align_up(bh * (size_t)p->Nq * 2 * sizeof(int));
+  L.total_saved = L.sv_flags + align_up(bh * (size_t)L.nqb * sizeof(int));
   L.off_flcnt = L.off_cand + cand_bytes;
   L.off_bounds = L.off_flcnt + align_up(bh * (size_t)p->Nq * 2 * sizeof(int));
   L.off_flags = L.off_bounds + align_up(bh * (size_t)p->Nq * sizeof(float2));
@@ -197,13 +202,14 @@ bool zero_rows(void* X, long long sb, long long sh, long long sn, int B, int H, 
   return launch_ok();
 }
 
-bool zero_words(void* p, size_t bytes, hipStream_t st) {
+bool fill_words(void* p, size_t bytes, uint32_t value, hipStream_t st) {
   long long n = (long long)(bytes / 4);
   if (n == 0) return true;
-  hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
-                     reinterpret_cast<uint32_t*>(p), n);
+  hipLaunchKernelGGL(fill_words_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
+                     reinterpret_cast<uint32_t*>(p), n, value);
   return launch_ok();
 }
+bool zero_words(void* p, size_t bytes, hipStream_t st) { return fill_words(p, bytes, 0u, st); }
 
 template <typename T, int D>
 bool launch_transposes(const TransposeJobs& jobs, int njobs, int B, int H, hipStream_t st, const int* head_flag = nullptr) {
@@ -270,8 +276,8 @@ bool launch_fwd_sparse_am(const FwdSparseArgs& a, int am, int nblocks, hipStream
 
 template <typename T, int D>
 int run_fwd(const entmax_attn_params* p, const Layout& L, const void* Q, const void* K, const void* V,
-            const float* beta, const float* gamma, void* O, float* tau, uint64_t* stats, char* ws, hipStream_t st,
-            void* const* ev) {
+            const float* beta, const float* gamma, void* O, float* tau, char* saved, uint64_t* stats, char* ws,
+            hipStream_t st, void* const* ev) {
   record(ev, 0, st);
   if (p->Nk == 0) {
     bool ok = zero_rows<T>(O, L.q_sb, L.q_sh, L.q_sn, p->B, p->H, p->Nq, p->D, st) &&
@@ -280,8 +286,9 @@ int run_fwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
     return ok ? ENTMAX_ATTN_OK : ENTMAX_ATTN_LAUNCH_FAILED;
   }
   void* Vt = ws + L.off_vt;
-  int* dense_flag = reinterpret_cast<int*>(ws + L.off_flags);
-  int* head_flag = dense_flag + (size_t)p->B * p->H * L.nqb;
+  // with a `saved` buffer the lists, their lengths and the block flags are written there
+  int* dense_flag = reinterpret_cast<int*>(saved ? saved + L.sv_flags : ws + L.off_flags);
+  int* head_flag = reinterpret_cast<int*>(ws + L.off_flags) + (size_t)p->B * p->H * L.nqb;
   const int nblocks = p->B * p->H * ((L.nqb + 1) / 2);  // workgroups take query blocks in pairs
   const bool lists = p->path == 0;
   if (lists) {
@@ -292,9 +299,9 @@ int run_fwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
     sa.V = V;
     sa.O = O;
     sa.tau = tau;
-    sa.cand = reinterpret_cast<uint2*>(ws + L.off_cand);
+    sa.cand = reinterpret_cast<uint2*>(saved ? saved + L.sv_cand : ws + L.off_cand);
     sa.cells = ws + L.off_fcells;
-    sa.lcnt = reinterpret_cast<int*>(ws + L.off_flcnt);
+    sa.lcnt = reinterpret_cast<int*>(saved ? saved + L.sv_lcnt : ws + L.off_flcnt);
     sa.bounds = reinterpret_cast<float2*>(ws + L.off_bounds);
     sa.dense_flag = dense_flag;
     sa.head_flag = head_flag;
@@ -302,6 +309,8 @@ int run_fwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
     sa.nqb = L.nqb;
     if (!launch_fwd_sparse_am<T, D>(sa, alpha_mode(p->alpha), nblocks, st, ev)) return ENTMAX_ATTN_LAUNCH_FAILED;
   } else {
+    // no lists: tell the backward that every block belongs to its tiled kernels
+    if (saved && !fill_words(dense_flag, (size_t)p->B * p->H * L.nqb * sizeof(int), 1u, st)) return ENTMAX_ATTN_LAUNCH_FAILED;
     record(ev, ENTMAX_FWD_PHASE_LISTS + 1, st);
   }
   record(ev, ENTMAX_FWD_PHASE_FINISH + 1, st);
@@ -355,29 +364,37 @@ bool launch_bwd_kernels(const BwdArgs& a, const Layout& L, int B, int H, hipStre
 }
 
 template <typename T, int D, int AM>
-bool launch_bwd_rows(const BwdSparseArgs& a, int nblocks, hipStream_t st, void* const* ev) {
-  size_t smem = 2 * (size_t)QCtx<T, D, FwdTile<T>::value>::kTileBytes + 64;
-  hipLaunchKernelGGL((bwd_lists_kernel<T, D, AM>), dim3((unsigned)nblocks), dim3(kThreads), smem, st, a);
+bool launch_bwd_rows(const BwdSparseArgs& a, int nblocks, hipStream_t st, void* const* ev, bool from_saved) {
+  const dim3 row_grid((unsigned)(a.g.B * a.g.H * a.nqb));
+  if (from_saved) {
+    hipLaunchKernelGGL(bwd_prepare_kernel<D>, row_grid, dim3(kThreads), 0, st, a);
+  } else {
+    size_t smem = 2 * (size_t)QCtx<T, D, FwdTile<T>::value>::kTileBytes + 64;
+    hipLaunchKernelGGL((bwd_lists_kernel<T, D, AM>), dim3((unsigned)nblocks), dim3(kThreads), smem, st, a);
+  }
   if (!launch_ok()) return false;
   record(ev, ENTMAX_BWD_PHASE_LISTS + 1, st);
-  hipLaunchKernelGGL((bwd_rows_kernel<T, D, AM>), dim3((unsigned)(a.g.B * a.g.H * a.nqb)), dim3(kThreads), 0, st, a);
+  if (from_saved)
+    hipLaunchKernelGGL((bwd_rows_kernel<T, D, AM, kCandCap>), row_grid, dim3(kThreads), 0, st, a);
+  else
+    hipLaunchKernelGGL((bwd_rows_kernel<T, D, AM, kBwdCap>), row_grid, dim3(kThreads), 0, st, a);
   return launch_ok();
 }
 
 template <typename T, int D>
-bool launch_bwd_rows_am(const BwdSparseArgs& a, int am, int nblocks, hipStream_t st, void* const* ev) {
+bool launch_bwd_rows_am(const BwdSparseArgs& a, int am, int nblocks, hipStream_t st, void* const* ev, bool from_saved) {
   switch (am) {
-    case 1: return launch_bwd_rows<T, D, 1>(a, nblocks, st, ev);
-    case 2: return launch_bwd_rows<T, D, 2>(a, nblocks, st, ev);
-    case 3: return launch_bwd_rows<T, D, 3>(a, nblocks, st, ev);
-    default: return launch_bwd_rows<T, D, 0>(a, nblocks, st, ev);
+    case 1: return launch_bwd_rows<T, D, 1>(a, nblocks, st, ev, from_saved);
+    case 2: return launch_bwd_rows<T, D, 2>(a, nblocks, st, ev, from_saved);
+    case 3: return launch_bwd_rows<T, D, 3>(a, nblocks, st, ev, from_saved);
+    default: return launch_bwd_rows<T, D, 0>(a, nblocks, st, ev, from_saved);
   }
 }
 
 template <typename T, int D>
 int run_bwd(const entmax_attn_params* p, const Layout& L, const void* Q, const void* K, const void* V, const void* dO,
-            const float* tau, const float* beta, const float* gamma, void* dQ, void* dK, void* dV, float* dbeta,
-            float* dgamma, uint64_t* stats, char* ws, hipStream_t st, void* const* ev) {
+            const float* tau, const char* saved, const float* beta, const float* gamma, void* dQ, void* dK, void* dV,
+            float* dbeta, float* dgamma, uint64_t* stats, char* ws, hipStream_t st, void* const* ev) {
   record(ev, 0, st);
   const int B = p->B, H = p->H;
   Geom g = make_geom(p, L, beta, gamma);
@@ -409,6 +426,9 @@ int run_bwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
       sa.cells = ws + L.off_bcells;
       sa.pw = reinterpret_cast<float2*>(ws + L.off_pw);
       sa.lcnt = reinterpret_cast<int*>(ws + L.off_lcnt);
+      sa.src_list = saved ? reinterpret_cast<const uint2*>(saved + L.sv_cand) : sa.jlist;
+      sa.src_lcnt = saved ? reinterpret_cast<const int*>(saved + L.sv_lcnt) : nullptr;
+      sa.src_dense = saved ? reinterpret_cast<const int*>(saved + L.sv_flags) : nullptr;
       sa.kcount = reinterpret_cast<int*>(ws + L.off_kcount);
       sa.koffs = reinterpret_cast<int*>(ws + L.off_koffs);
       sa.csc_i = reinterpret_cast<int*>(ws + L.off_csc_i);
@@ -418,7 +438,7 @@ int run_bwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
       sa.long_keys = reinterpret_cast<int*>(ws + L.off_longkeys);
       sa.stats = reinterpret_cast<unsigned long long*>(stats);
       sa.nqb = L.nqb;
-      ok = ok && launch_bwd_rows_am<T, D>(sa, alpha_mode(p->alpha), B * H * ((L.nqb + 1) / 2), st, ev);
+      ok = ok && launch_bwd_rows_am<T, D>(sa, alpha_mode(p->alpha), B * H * ((L.nqb + 1) / 2), st, ev, saved != nullptr);
       if (!ok) return ENTMAX_ATTN_LAUNCH_FAILED;
     } else {
       record(ev, ENTMAX_BWD_PHASE_LISTS + 1, st);
@@ -505,6 +525,12 @@ extern "C" {
 
 int entmax_attn_check_params(const entmax_attn_params* p) { return check(p); }
 
+size_t entmax_attn_saved_bytes(const entmax_attn_params* p) {
+  if (check(p) != ENTMAX_ATTN_OK) return 0;
+  Layout L = make_layout(p);
+  return L.total_saved < kAlign ? kAlign : L.total_saved;
+}
+
 size_t entmax_attn_workspace_bytes(const entmax_attn_params* p, int is_bwd) {
   if (check(p) != ENTMAX_ATTN_OK) return 0;
   Layout L = make_layout(p);
@@ -525,8 +551,8 @@ const char* entmax_attn_strerror(int code) {
 }
 
 int entmax_attn_fwd(const entmax_attn_params* p, const void* Q, const void* K, const void* V, const float* beta,
-                    const float* gamma, void* O, float* tau, uint64_t* stats, void* workspace, size_t workspace_bytes,
-                    void* hip_stream, void* const* phase_events) {
+                    const float* gamma, void* O, float* tau, void* saved, uint64_t* stats, void* workspace,
+                    size_t workspace_bytes, void* hip_stream, void* const* phase_events) {
   int rc = check(p);
   if (rc != ENTMAX_ATTN_OK) return rc;
   hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
@@ -537,24 +563,25 @@ int entmax_attn_fwd(const entmax_attn_params* p, const void* Q, const void* K, c
   if (!Q || !O || !tau || !workspace) return ENTMAX_ATTN_INVALID_ARG;
   if (p->Nk > 0 && (!K || !V)) return ENTMAX_ATTN_INVALID_ARG;
   if (p->scale_layout != 0 && (!beta || !gamma)) return ENTMAX_ATTN_INVALID_ARG;
-  if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O) || misaligned(workspace))
+  if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O) || misaligned(workspace) || misaligned(saved))
     return ENTMAX_ATTN_MISALIGNED;
   if ((reinterpret_cast<uintptr_t>(tau) & 3u) || (reinterpret_cast<uintptr_t>(stats) & 7u)) return ENTMAX_ATTN_MISALIGNED;
   if (workspace_bytes < entmax_attn_workspace_bytes(p, 0)) return ENTMAX_ATTN_WORKSPACE_TOO_SMALL;
   Layout L = make_layout(p);
   char* ws = reinterpret_cast<char*>(workspace);
+  char* sv = reinterpret_cast<char*>(saved);
   if (p->dtype == ENTMAX_ATTN_BF16) {
-    if (p->D == 64) return run_fwd<bf16_t, 64>(p, L, Q, K, V, beta, gamma, O, tau, stats, ws, st, phase_events);
-    return run_fwd<bf16_t, 128>(p, L, Q, K, V, beta, gamma, O, tau, stats, ws, st, phase_events);
+    if (p->D == 64) return run_fwd<bf16_t, 64>(p, L, Q, K, V, beta, gamma, O, tau, sv, stats, ws, st, phase_events);
+    return run_fwd<bf16_t, 128>(p, L, Q, K, V, beta, gamma, O, tau, sv, stats, ws, st, phase_events);
   }
-  if (p->D == 64) return run_fwd<float, 64>(p, L, Q, K, V, beta, gamma, O, tau, stats, ws, st, phase_events);
-  return run_fwd<float, 128>(p, L, Q, K, V, beta, gamma, O, tau, stats, ws, st, phase_events);
+  if (p->D == 64) return run_fwd<float, 64>(p, L, Q, K, V, beta, gamma, O, tau, sv, stats, ws, st, phase_events);
+  return run_fwd<float, 128>(p, L, Q, K, V, beta, gamma, O, tau, sv, stats, ws, st, phase_events);
 }
 
 int entmax_attn_bwd(const entmax_attn_params* p, const void* Q, const void* K, const void* V, const void* O,
-                    const void* dO, const float* tau, const float* beta, const float* gamma, void* dQ, void* dK,
-                    void* dV, float* dbeta, float* dgamma, uint64_t* stats, void* workspace, size_t workspace_bytes,
-                    void* hip_stream, void* const* phase_events) {
+                    const void* dO, const float* tau, const void* saved, const float* beta, const float* gamma,
+                    void* dQ, void* dK, void* dV, float* dbeta, float* dgamma, uint64_t* stats, void* workspace,
+                    size_t workspace_bytes, void* hip_stream, void* const* phase_events) {
   (void)O;
   int rc = check(p);
   if (rc != ENTMAX_ATTN_OK) return rc;
@@ -568,23 +595,24 @@ int entmax_attn_bwd(const entmax_attn_params* p, const void* Q, const void* K, c
   if (p->Nk > 0 && (!K || !V || !dK || !dV)) return ENTMAX_ATTN_INVALID_ARG;
   if (p->scale_layout != 0 && (!beta || !gamma || !dbeta || !dgamma)) return ENTMAX_ATTN_INVALID_ARG;
   if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(dO) || misaligned(dQ) || misaligned(dK) ||
-      misaligned(dV) || misaligned(workspace))
+      misaligned(dV) || misaligned(workspace) || misaligned(saved))
     return ENTMAX_ATTN_MISALIGNED;
   if ((reinterpret_cast<uintptr_t>(tau) & 3u) || (reinterpret_cast<uintptr_t>(stats) & 7u)) return ENTMAX_ATTN_MISALIGNED;
   if (workspace_bytes < entmax_attn_workspace_bytes(p, 1)) return ENTMAX_ATTN_WORKSPACE_TOO_SMALL;
   Layout L = make_layout(p);
   char* ws = reinterpret_cast<char*>(workspace);
+  const char* sv = reinterpret_cast<const char*>(saved);
   if (p->dtype == ENTMAX_ATTN_BF16) {
     if (p->D == 64)
-      return run_bwd<bf16_t, 64>(p, L, Q, K, V, dO, tau, beta, gamma, dQ, dK, dV, dbeta, dgamma, stats, ws, st,
+      return run_bwd<bf16_t, 64>(p, L, Q, K, V, dO, tau, sv, beta, gamma, dQ, dK, dV, dbeta, dgamma, stats, ws, st,
                                  phase_events);
-    return run_bwd<bf16_t, 128>(p, L, Q, K, V, dO, tau, beta, gamma, dQ, dK, dV, dbeta, dgamma, stats, ws, st,
+    return run_bwd<bf16_t, 128>(p, L, Q, K, V, dO, tau, sv, beta, gamma, dQ, dK, dV, dbeta, dgamma, stats, ws, st,
                                 phase_events);
   }
   if (p->D == 64)
-    return run_bwd<float, 64>(p, L, Q, K, V, dO, tau, beta, gamma, dQ, dK, dV, dbeta, dgamma, stats, ws, st,
+    return run_bwd<float, 64>(p, L, Q, K, V, dO, tau, sv, beta, gamma, dQ, dK, dV, dbeta, dgamma, stats, ws, st,
                               phase_events);
-  return run_bwd<float, 128>(p, L, Q, K, V, dO, tau, beta, gamma, dQ, dK, dV, dbeta, dgamma, stats, ws, st,
+  return run_bwd<float, 128>(p, L, Q, K, V, dO, tau, sv, beta, gamma, dQ, dK, dV, dbeta, dgamma, stats, ws, st,
                              phase_events);
 }
 

@@ -7,6 +7,7 @@ TOL_O = 2e-2      # max-abs on outputs
 TOL_TAU = 1e-3    # max-abs on the threshold
 TOL_GRAD = 5e-2   # max|diff| / max|ref| per gradient tensor
 DEFAULT_PATH = 0   # forward path the tests run when they do not say: 0 automatic, 1 tiled kernel only
+DEFAULT_SAVED = False  # whether the backward gets the forward's lists (`saved` buffer)
 
 
 def to_dev(x, dtype):
@@ -16,9 +17,11 @@ def to_dev(x, dtype):
     return t.to(torch.bfloat16) if dtype == "bf16" else t.float()
 
 
-def gpu_run(data, alpha, dtype, causal=True, logn_mode=0, bwd=True, stats=False, layout_bnhd=False, path=None):
+def gpu_run(data, alpha, dtype, causal=True, logn_mode=0, bwd=True, stats=False, layout_bnhd=False, path=None,
+            use_saved=None):
     from paper_2506_16640_amd import binding
     path = DEFAULT_PATH if path is None else path
+    use_saved = DEFAULT_SAVED if use_saved is None else use_saved
     q, k, v = (to_dev(data[n], dtype) for n in ("Q", "K", "V"))
     if layout_bnhd:  # same values, [B,n,H,D] memory order viewed as [B,H,n,D]
         q, k, v = (t.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3) for t in (q, k, v))
@@ -27,13 +30,17 @@ def gpu_run(data, alpha, dtype, causal=True, logn_mode=0, bwd=True, stats=False,
     st = binding.new_stats() if stats else None
     kw = dict(alpha=alpha, beta=beta, gamma=gamma, delta=data["delta"], causal=causal, logn_mode=logn_mode, stats=st,
               path=path)
-    o, tau = binding.entmax_attn_fwd(q, k, v, **kw)
+    saved = None
+    if use_saved:  # the forward's lists go to the backward, which then skips its own sweep
+        prm = binding.make_params(q, k, alpha, data["delta"], causal, beta, logn_mode, path)
+        saved = binding.new_saved(prm)
+    o, tau = binding.entmax_attn_fwd(q, k, v, saved=saved, **kw)
     out = {"O": o.float().cpu().numpy().astype(np.float64), "tau": tau.cpu().numpy().astype(np.float64)}
     if bwd:
         do = to_dev(data["dO"], dtype)
         if layout_bnhd:
             do = do.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
-        dq, dk, dv, db, dg = binding.entmax_attn_bwd(q, k, v, o, do, tau, **kw)
+        dq, dk, dv, db, dg = binding.entmax_attn_bwd(q, k, v, o, do, tau, saved=saved, **kw)
         out.update(dQ=dq.float().cpu().numpy().astype(np.float64), dK=dk.float().cpu().numpy().astype(np.float64),
                    dV=dv.float().cpu().numpy().astype(np.float64),
                    dbeta=None if db is None else db.cpu().numpy().astype(np.float64),

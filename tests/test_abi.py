@@ -24,8 +24,8 @@ def test_exports_every_declared_symbol(binding):
     text = open(HEADER).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = set(re.findall(r"\b(entmax_attn_[a-z_]+)\s*\(", text))
-    assert {"entmax_attn_fwd", "entmax_attn_bwd", "entmax_attn_workspace_bytes", "entmax_attn_strerror",
-            "entmax_attn_check_params"} <= names
+    assert {"entmax_attn_fwd", "entmax_attn_bwd", "entmax_attn_workspace_bytes", "entmax_attn_saved_bytes",
+            "entmax_attn_strerror", "entmax_attn_check_params"} <= names
     lib = ctypes.CDLL(LIB)
     for n in names:
         assert hasattr(lib, n), n
@@ -69,6 +69,9 @@ def test_workspace_sizes(binding):
     assert fwd >= 48 * 64 * 4096 * 2  # one transposed copy of V plus candidate lists and flags
     assert bwd > 3 * 48 * 64 * 4096 * 2
     assert b.workspace_bytes(_params(b, D=32), 0) == 0
+    # the buffer that carries the forward's lists: 32 (key, score) slots per half row, lengths, block flags
+    assert b.saved_bytes(p) >= 48 * 4096 * 2 * 32 * 8 + 48 * 4096 * 2 * 4 + 48 * 32 * 4
+    assert b.saved_bytes(_params(b, D=32)) == 0
     # ragged lengths are padded to 128 rows in the transposed copies
     small = b.workspace_bytes(_params(b, B=1, H=1, Nq=65, Nk=65), 0)
     assert small >= 64 * 128 * 2 and b.workspace_bytes(_params(b, B=1, H=1, Nq=65, Nk=129), 0) - small == 64 * 128 * 2
@@ -82,15 +85,18 @@ def test_entry_points_reject_bad_arguments_before_any_launch(binding):
     null = ctypes.c_void_p(None)
     fake = ctypes.c_void_p(4096)
     bad = ctypes.c_void_p(4100)  # not 16-byte aligned
-    args = lambda **kw: [kw.get(k, fake) for k in ("Q", "K", "V", "beta", "gamma", "O", "tau", "stats", "ws")]  # noqa
+    args = lambda **kw: [kw.get(k, null if k == "saved" else fake)  # noqa
+                         for k in ("Q", "K", "V", "beta", "gamma", "O", "tau", "saved", "stats", "ws")]
     call = lambda prm, a, wsb=1 << 30: lib.entmax_attn_fwd(ctypes.byref(prm), *a, ctypes.c_size_t(wsb), null, null)  # noqa
     assert call(_params(b, D=32), args()) == -2
     assert call(p, args(Q=null)) == -1
     assert call(p, args(beta=null)) == -1
     assert call(p, args(K=bad)) == -3
     assert call(p, args(stats=null), wsb=16) == -4
+    assert call(p, args(saved=bad)) == -3
     lib.entmax_attn_bwd.restype = ctypes.c_int
-    a = [fake] * 15
+    a = [fake] * 16
+    a[6] = null  # saved is optional
     assert lib.entmax_attn_bwd(ctypes.byref(_params(b, alpha=3.0)), *a, ctypes.c_size_t(1 << 30), null, null) == -1
     a[5] = null  # tau
     assert lib.entmax_attn_bwd(ctypes.byref(p), *a, ctypes.c_size_t(1 << 30), null, null) == -1

@@ -12,14 +12,15 @@ from tests.parity_util import compare, gpu_run, oracle_run
 pytestmark = pytest.mark.gpu
 
 
-@pytest.fixture(autouse=True, params=[0, 1], ids=["auto", "tiled"])
+@pytest.fixture(autouse=True, params=[(0, False), (0, True), (1, False)], ids=["auto", "auto-saved", "tiled"])
 def forward_path(request):
-    """Every case runs twice: with the automatic forward path (candidate-list kernel, tiled fallback)
-    and with the tiled kernel alone."""
+    """Every case runs three times: with the automatic path (list kernels, tiled fallback) where the backward
+    rebuilds the supports itself, the same with the forward's lists handed to the backward, and with the
+    tiled kernels alone."""
     from tests import parity_util
-    parity_util.DEFAULT_PATH = request.param
-    yield request.param
-    parity_util.DEFAULT_PATH = 0
+    parity_util.DEFAULT_PATH, parity_util.DEFAULT_SAVED = request.param
+    yield request.param[0]
+    parity_util.DEFAULT_PATH, parity_util.DEFAULT_SAVED = 0, False
 
 
 def _case(B, H, nq, nk, d, dtype, scale, seed=0, planted=0.0):
