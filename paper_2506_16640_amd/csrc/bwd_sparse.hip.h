@@ -324,29 +324,47 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_rows_kernel(BwdSparseArgs A) 
 // ------------------------------------------------------------ key-major order
 
 // One workgroup per head: exclusive prefix sums of the per-key entry counts.
+// Keys with more than kSortedKeyEntries entries are put on the long-key list (any order).
+constexpr int kSortedKeyEntries = 8;
+
 __global__ __launch_bounds__(kThreads) void csc_offsets_kernel(const int* kcount, int* koffs, int Nk,
-                                                               const int* head_flag) {
-  __shared__ int part[kThreads];
+                                                               const int* head_flag, int* long_keys, int* long_count) {
+  __shared__ int part[kThreads];   // entries in the thread's range of keys
+  __shared__ int partl[kThreads];  // long keys in it
+  __shared__ int long_base;
   const int bh = blockIdx.x, tid = threadIdx.x;
   if (head_flag[bh] != 0) return;
   const int per = (Nk + kThreads - 1) / kThreads;
   const int beg = tid * per, end = min(Nk, beg + per);
   const int* c = kcount + (long long)bh * Nk;
-  int s = 0;
-  for (int j = beg; j < end; ++j) s += c[j];
+  int s = 0, nl = 0;
+  for (int j = beg; j < end; ++j) {
+    const int cj = c[j];
+    s += cj;
+    nl += cj > kSortedKeyEntries ? 1 : 0;
+  }
   part[tid] = s;
+  partl[tid] = nl;
   __syncthreads();
-  // Hillis-Steele inclusive scan over the 256 partial sums
+  // Hillis-Steele inclusive scans over the 256 partial sums
   for (int off = 1; off < kThreads; off <<= 1) {
     int v = (tid >= off) ? part[tid - off] : 0;
+    int vl = (tid >= off) ? partl[tid - off] : 0;
     __syncthreads();
     part[tid] += v;
+    partl[tid] += vl;
     __syncthreads();
   }
+  // one list reservation per head
+  if (tid == kThreads - 1) long_base = partl[tid] > 0 ? atomicAdd(long_count, partl[tid]) : 0;
+  __syncthreads();
   int run = part[tid] - s;
+  int lpos = long_base + partl[tid] - nl;
   for (int j = beg; j < end; ++j) {
     koffs[(long long)bh * Nk + j] = run;
-    run += c[j];
+    const int cj = c[j];
+    run += cj;
+    if (cj > kSortedKeyEntries) long_keys[lpos++] = bh * Nk + j;
   }
 }
 
@@ -379,35 +397,33 @@ __global__ __launch_bounds__(kThreads) void csc_scatter_kernel(BwdSparseArgs A) 
 // One lane pair per key, each lane half of the features (the mirror image of bwd_rows_kernel).
 // A key's entries sit in arrival order; they are summed in query-row order (selection by repeated
 // minimum over the entries held in registers), which makes the result independent of the arrival
-// order.  Keys with more than kSortedKeyEntries entries are left to bwd_long_keys_kernel.
-constexpr int kSortedKeyEntries = 8;
+// order.  Keys with more than kSortedKeyEntries entries are served by the first kLongKeyBlocks
+// workgroups of the same launch (bwd_long_keys_part), which run alongside the others.
+constexpr int kLongKeyBlocks = 1024;
+
+template <typename T, int D>
+__device__ __forceinline__ void bwd_long_keys_part(const BwdSparseArgs& A, int vblock, int vgrid);
 
 template <typename T, int D>
 __global__ __launch_bounds__(kThreads, 3) void bwd_keys_kernel(BwdSparseArgs A) {
   constexpr int DH = D / 2;
   const Geom& g = A.g;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 31, hh = lane >> 5;
+  if (blockIdx.x < kLongKeyBlocks) {
+    bwd_long_keys_part<T, D>(A, blockIdx.x, kLongKeyBlocks);
+    return;
+  }
   const long long nkeys = (long long)g.B * g.H * g.Nk;
-  const long long key = (long long)blockIdx.x * kBlockRows + wave * 32 + li;
+  const long long key = (long long)(blockIdx.x - kLongKeyBlocks) * kBlockRows + wave * 32 + li;
   bool on = key < nkeys;
   const int bh = on ? (int)(key / g.Nk) : 0;
   const int j = on ? (int)(key % g.Nk) : 0;
   on = on && A.head_flag[bh] == 0;
   const int b = bh / g.H, h = bh % g.H;
   int n = on ? A.kcount[key] : 0;
-  {  // longer segments belong to bwd_long_keys_kernel: one list append per wave
-    const bool is_long = n > kSortedKeyEntries && hh == 0;
-    const unsigned long long lm = __ballot(is_long);
-    if (lm != 0ull) {
-      int first = 0;
-      if (lane == 0) first = atomicAdd(&A.head_flag[g.B * g.H + kLongCountOffset], __builtin_popcountll(lm));
-      first = __shfl(first, 0);
-      if (is_long) A.long_keys[first + __builtin_popcountll(lm & ((1ull << lane) - 1ull))] = (int)key;
-    }
-    if (n > kSortedKeyEntries) {
-      on = false;
-      n = 0;
-    }
+  if (n > kSortedKeyEntries) {  // on the long-key list
+    on = false;
+    n = 0;
   }
   const long long base = (long long)bh * g.Nq * 2 * kBwdCap + (on ? A.koffs[key] : 0);
   const long long q_base = (long long)b * g.q_sb + (long long)h * g.q_sh;
@@ -465,13 +481,13 @@ __global__ __launch_bounds__(kThreads, 3) void bwd_keys_kernel(BwdSparseArgs A) 
 // query-row order (rank by comparison across the wave), so keys with up to 64 entries get an
 // order-independent result; only longer segments depend on the arrival order of their chunks.
 template <typename T, int D>
-__global__ __launch_bounds__(kThreads) void bwd_long_keys_kernel(BwdSparseArgs A) {
+__device__ __forceinline__ void bwd_long_keys_part(const BwdSparseArgs& A, int vblock, int vgrid) {
   constexpr int PER = D / 64;
   const Geom& g = A.g;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-  // persistent grid: the waves share out the list bwd_keys_kernel made
+  // persistent workgroups: the waves share out the list csc_offsets_kernel made
   const int nlong = __builtin_amdgcn_readfirstlane(A.head_flag[g.B * g.H + kLongCountOffset]);
-  for (int idx = blockIdx.x * kWaves + wave; idx < nlong; idx += gridDim.x * kWaves) {
+  for (int idx = vblock * kWaves + wave; idx < nlong; idx += vgrid * kWaves) {
   const long long key = __builtin_amdgcn_readfirstlane(A.long_keys[idx]);
   const int n = __builtin_amdgcn_readfirstlane(A.kcount[key]);
   const int bh = (int)(key / g.Nk), j = (int)(key % g.Nk);

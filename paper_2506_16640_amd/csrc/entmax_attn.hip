@@ -489,15 +489,13 @@ int run_bwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
     if (!ok) return ENTMAX_ATTN_LAUNCH_FAILED;
     if (lists) {
       hipLaunchKernelGGL(csc_offsets_kernel, dim3((unsigned)(B * H)), dim3(kThreads), 0, st, sa.kcount, sa.koffs,
-                         p->Nk, head_flag);
+                         p->Nk, head_flag, sa.long_keys, head_flag + (size_t)B * H + kLongCountOffset);
       ok = ok && launch_ok();
       hipLaunchKernelGGL(csc_scatter_kernel, dim3((unsigned)(B * H * L.nqb)), dim3(kThreads), 0, st, sa);
       ok = ok && launch_ok();
       long long keys = (long long)B * H * p->Nk;
-      hipLaunchKernelGGL((bwd_keys_kernel<T, D>), dim3((unsigned)((keys + kBlockRows - 1) / kBlockRows)), dim3(kThreads), 0, st,
-                         sa);
-      ok = ok && launch_ok();
-      hipLaunchKernelGGL((bwd_long_keys_kernel<T, D>), dim3(1024u), dim3(kThreads), 0, st, sa);
+      hipLaunchKernelGGL((bwd_keys_kernel<T, D>), dim3((unsigned)(kLongKeyBlocks + (keys + kBlockRows - 1) / kBlockRows)),
+                         dim3(kThreads), 0, st, sa);
       ok = ok && launch_ok();
     }
     record(ev, ENTMAX_BWD_PHASE_KEYS + 1, st);
