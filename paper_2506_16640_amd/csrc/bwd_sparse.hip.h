@@ -156,7 +156,7 @@ __global__ __launch_bounds__(kThreads) void bwd_prepare_kernel(BwdSparseArgs A) 
 // Everything row-wise from the lists: one lane pair per row, each lane half of the features.
 // SRC_CAP: capacity (slot count) of the lists that are read.
 template <typename T, int D, int AM, int SRC_CAP>
-__global__ __launch_bounds__(kThreads, 2) void bwd_rows_kernel(BwdSparseArgs A) {
+__global__ __launch_bounds__(kThreads, D == 64 ? 2 : 1) void bwd_rows_kernel(BwdSparseArgs A) {
   const Geom& g = A.g;
   RowLane rl;
   rl.init(g, A.nqb);
@@ -254,18 +254,18 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_rows_kernel(BwdSparseArgs A) 
         float x = (d > -kInf) ? fmaxf(fmaf(d, a, -tau), 0.f) : 0.f;
         if (__ballot(x > 0.f) == 0ull) continue;
         float part = 0.f;
-        float kk[DH];
+        RawRow<T, DH> kk;
         if (x > 0.f) {
-          float vv[DH];
-          load_row_f32<T>(Vbh + (long long)j * g.kv_sn + rl.hh * DH, DH, vv);
-          load_row_f32<T>(Kbh + (long long)j * g.kv_sn + rl.hh * DH, DH, kk);
+          RawRow<T, DH> vv;
+          vv.load(Vbh + (long long)j * g.kv_sn + rl.hh * DH);
+          kk.load(Kbh + (long long)j * g.kv_sn + rl.hh * DH);
           // the entry's owner takes its arrival number among the key's entries: its place in the key's segment
           if (rl.hh == src) {
             slotv[e] = atomicAdd(&A.kcount[(long long)rl.bh * g.Nk + j], 1);
             ++n_entries;
           }
 #pragma unroll
-          for (int t = 0; t < DH; ++t) part = fmaf(dov[t], vv[t], part);
+          for (int t = 0; t < DH; ++t) part = fmaf(dov[t], vv.get(t), part);
         }
         float dp = part + __shfl_xor(part, 32);
         if (x > 0.f) {
@@ -277,8 +277,9 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_rows_kernel(BwdSparseArgs A) 
           sd0 = fmaf(gg, d, sd0);
 #pragma unroll
           for (int t = 0; t < DH; ++t) {
-            qa[t] = fmaf(gdp, kk[t], qa[t]);
-            qb[t] = fmaf(gg, kk[t], qb[t]);
+            const float kt = kk.get(t);
+            qa[t] = fmaf(gdp, kt, qa[t]);
+            qb[t] = fmaf(gg, kt, qb[t]);
           }
           if (rl.hh == src) dpv[e] = dp;
         }
@@ -405,7 +406,7 @@ template <typename T, int D>
 __device__ __forceinline__ void bwd_long_keys_part(const BwdSparseArgs& A, int vblock, int vgrid);
 
 template <typename T, int D>
-__global__ __launch_bounds__(kThreads, 3) void bwd_keys_kernel(BwdSparseArgs A) {
+__global__ __launch_bounds__(kThreads, D == 64 ? 3 : 2) void bwd_keys_kernel(BwdSparseArgs A) {
   constexpr int DH = D / 2;
   const Geom& g = A.g;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 31, hh = lane >> 5;
@@ -434,13 +435,13 @@ __global__ __launch_bounds__(kThreads, 3) void bwd_keys_kernel(BwdSparseArgs A) 
   for (int t = 0; t < DH; ++t) dv[t] = dk[t] = 0.f;
   auto add_entry = [&](int i, float2 pw) {
     i = min(max(i, 0), g.Nq - 1);  // a valid row by construction; never index outside the tensor
-    float rd[DH], rq[DH];
-    load_row_f32<T>(dObh + (long long)i * g.q_sn, DH, rd);
-    load_row_f32<T>(Qbh + (long long)i * g.q_sn, DH, rq);
+    RawRow<T, DH> rd, rq;  // widened where used: fewer registers per gather in flight
+    rd.load(dObh + (long long)i * g.q_sn);
+    rq.load(Qbh + (long long)i * g.q_sn);
 #pragma unroll
     for (int u = 0; u < DH; ++u) {
-      dv[u] = fmaf(pw.x, rd[u], dv[u]);
-      dk[u] = fmaf(pw.y, rq[u], dk[u]);
+      dv[u] = fmaf(pw.x, rd.get(u), dv[u]);
+      dk[u] = fmaf(pw.y, rq.get(u), dk[u]);
     }
   };
   // the first kSortedKeyEntries entries are held in registers

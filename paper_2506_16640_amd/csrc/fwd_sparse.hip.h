@@ -313,6 +313,27 @@ __device__ __forceinline__ void load_row_f32(const T* row, int n, float* out) {
     }
   }
 }
+// The same row kept as loaded (16-byte words) and widened only where it is used: a gather in flight
+// costs half (bf16) of the registers of a widened row.
+template <typename T, int N>
+struct RawRow {
+  static constexpr int kWords = N * (int)sizeof(T) / 16;
+  u32x4_t w[kWords];
+  __device__ __forceinline__ void load(const T* row) {
+#pragma unroll
+    for (int c = 0; c < kWords; ++c) w[c] = *reinterpret_cast<const u32x4_t*>(reinterpret_cast<const char*>(row) + 16 * c);
+  }
+  // element t (a compile-time index once the caller's loop is unrolled)
+  __device__ __forceinline__ float get(int t) const {
+    if constexpr (sizeof(T) == 2) {
+      const uint32_t word = w[t >> 3][(t >> 1) & 3];
+      return __uint_as_float((t & 1) ? (word & 0xffff0000u) : (word << 16));
+    } else {
+      return __uint_as_float(w[t >> 2][t & 3]);
+    }
+  }
+};
+
 template <typename T>
 __device__ __forceinline__ void store_row(T* row, int n, const float* v) {
   if constexpr (sizeof(T) == 2) {
@@ -424,10 +445,10 @@ __global__ __launch_bounds__(kThreads) void fwd_finish_kernel(FwdSparseArgs A) {
         unsigned j = (rl.hh == src) ? jv[e] : j_oth;
         if (__ballot(p > 0.f) == 0ull) continue;
         if (p > 0.f) {
-          float vv[DH];
-          load_row_f32<T>(Vbh + (long long)j * g.kv_sn + rl.hh * DH, DH, vv);
+          RawRow<T, DH> vv;
+          vv.load(Vbh + (long long)j * g.kv_sn + rl.hh * DH);
 #pragma unroll
-          for (int t = 0; t < DH; ++t) oacc[t] = fmaf(p, vv[t], oacc[t]);
+          for (int t = 0; t < DH; ++t) oacc[t] = fmaf(p, vv.get(t), oacc[t]);
         }
       }
     }
