@@ -402,7 +402,8 @@ __global__ __launch_bounds__(kThreads) void fwd_finish_kernel(FwdSparseArgs A) {
   for (int e = 0; e < kEarly; ++e) early[e] = mylist[e * kListStride];
   if (block_dense != 0) return;  // the tiled kernel owns this block
 
-  // NE: list entries per lane held in registers; chosen per wave from the longest list it holds
+  // NE: list entries per lane held in registers; chosen per wave from the longest list it holds.
+  // (Same sums in the same order whichever NE is chosen: entry order.)
   auto finish = [&](auto ne_tag) {
     constexpr int NE = decltype(ne_tag)::value;
     float yv[NE];
@@ -417,6 +418,8 @@ __global__ __launch_bounds__(kThreads) void fwd_finish_kernel(FwdSparseArgs A) {
       jv[e] = (e < cnt) ? en.x : 0u;
       yv[e] = (e < cnt) ? a * __uint_as_float(en.y) : -kInf;  // -inf: never positive
     }
+    // entries beyond the NE held in registers (few lanes) are read again wherever they are needed
+    const bool has_tail = __ballot(cnt > NE) != 0ull;
     bool done = !live;
     int iter = 0;
     while (__ballot(!done) != 0ull && iter < kMaxSolveIters) {
@@ -424,6 +427,8 @@ __global__ __launch_bounds__(kThreads) void fwd_finish_kernel(FwdSparseArgs A) {
       sums.clear();
 #pragma unroll
       for (int e = 0; e < NE; ++e) accumulate<AM>(sums, yv[e] - tau, r);
+      if (has_tail)
+        for (int e = NE; e < cnt; ++e) accumulate<AM>(sums, a * __uint_as_float(mylist[e * kListStride].y) - tau, r);
       sums.combine_halves();
       if (!done) done = solve_step<AM>(sums, r, tau, lo, hi);
       ++iter;
@@ -452,6 +457,27 @@ __global__ __launch_bounds__(kThreads) void fwd_finish_kernel(FwdSparseArgs A) {
         }
       }
     }
+    if (has_tail) {
+      for (int e = NE; __ballot(e < cnt) != 0ull; ++e) {
+        uint2 en = make_uint2(0u, 0u);
+        if (e < cnt) en = mylist[e * kListStride];
+        float p_own = (live && e < cnt) ? pow_r<AM>(fmaxf(a * __uint_as_float(en.y) - tau, 0.f), r) : 0.f;
+        float p_oth = __shfl_xor(p_own, 32);
+        unsigned j_oth = (unsigned)__shfl_xor((int)en.x, 32);
+        if (p_own > 0.f) ++n_support;
+#pragma unroll
+        for (int src = 0; src < 2; ++src) {
+          float p = (rl.hh == src) ? p_own : p_oth;
+          unsigned j = (rl.hh == src) ? en.x : j_oth;
+          if (p > 0.f) {
+            RawRow<T, DH> vv;
+            vv.load(Vbh + (long long)j * g.kv_sn + rl.hh * DH);
+#pragma unroll
+            for (int t = 0; t < DH; ++t) oacc[t] = fmaf(p, vv.get(t), oacc[t]);
+          }
+        }
+      }
+    }
     if (rl.valid) {
       T* orow = reinterpret_cast<T*>(A.O) + (long long)rl.b * g.q_sb + (long long)rl.h * g.q_sh +
                 (long long)rl.i * g.q_sn + rl.hh * DH;
@@ -461,10 +487,8 @@ __global__ __launch_bounds__(kThreads) void fwd_finish_kernel(FwdSparseArgs A) {
   };
   if (__ballot(cnt > 4) == 0ull)
     finish(std::integral_constant<int, 4>());
-  else if (__ballot(cnt > 12) == 0ull)
-    finish(std::integral_constant<int, 12>());
   else
-    finish(std::integral_constant<int, kCandCap>());
+    finish(std::integral_constant<int, 8>());
 
   if (A.stats) {
     unsigned sup = n_support, cands = (unsigned)cnt;
