@@ -25,7 +25,7 @@ PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak
 # HBM bytes per launch at the c3 workload, from rocprofv3 FETCH_SIZE + WRITE_SIZE runs of this same command scaled by
 # what the counters read for a conversion kernel of known size (profiles/pmc_c3_fwd_bwd.md).  Other workloads: null.
 MEASURED_HBM_BYTES_C3 = {
-    "fwd_lists": 191.6e6, "fwd_finish": 98.3e6, "bwd_lists": 151.9e6, "bwd_rows": 188.0e6,
+    "fwd_lists": 126.5e6, "fwd_finish": 78.5e6, "bwd_rows": 163.7e6, "bwd_keys": 152.8e6,
 }
 
 
