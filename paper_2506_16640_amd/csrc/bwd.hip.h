@@ -518,10 +518,11 @@ constexpr int kScaleGradThreads = 1024;
 
 // Per-head parameters: dbeta_h = sum_{b,i} dscale L^gamma, dgamma_h = sum dscale beta L^gamma ln L,
 // L = ln n (eq. (asentmax)); one workgroup per head, fixed summation order.
-__global__ __launch_bounds__(kScaleGradThreads) void scale_grad_head_kernel(Geom g, const float* dscale, float* dbeta,
-                                                                   float* dgamma) {
-  __shared__ float sb_[kScaleGradThreads], sg_[kScaleGradThreads];
-  const int h = blockIdx.x, tid = threadIdx.x;
+// NT threads of one workgroup; sb_, sg_: NT floats of LDS each.
+template <int NT>
+__device__ __forceinline__ void scale_grad_head_part(const Geom& g, const float* dscale, float* dbeta, float* dgamma, int h,
+                                                     float* sb_, float* sg_) {
+  const int tid = threadIdx.x;
   float ab = 0.f, ag = 0.f;
   if (g.logn_mode == 0) {
     // n = Nk for every row: (ln n)^gamma is one number per head, only dscale has to be summed
@@ -530,13 +531,13 @@ __global__ __launch_bounds__(kScaleGradThreads) void scale_grad_head_kernel(Geom
     float s = 0.f;
     for (int b = 0; b < g.B; ++b) {
       const float* ds = dscale + ((long long)b * g.H + h) * g.Nq;
-      for (int i = tid; i < g.Nq; i += kScaleGradThreads) s += ds[i];
+      for (int i = tid; i < g.Nq; i += NT) s += ds[i];
     }
     ab = s * Lg;
     ag = s * bt * Lg * lnL;
   } else {
     for (int b = 0; b < g.B; ++b) {
-      for (int i = tid; i < g.Nq; i += kScaleGradThreads) {
+      for (int i = tid; i < g.Nq; i += NT) {
         float Lg, lnL, bt;
         row_scale(g, b, h, i, row_limit(g, i), &Lg, &lnL, &bt);
         float ds = dscale[((long long)b * g.H + h) * g.Nq + i];
@@ -548,7 +549,7 @@ __global__ __launch_bounds__(kScaleGradThreads) void scale_grad_head_kernel(Geom
   sb_[tid] = ab;
   sg_[tid] = ag;
   __syncthreads();
-  for (int s = kScaleGradThreads / 2; s > 0; s >>= 1) {
+  for (int s = NT / 2; s > 0; s >>= 1) {
     if (tid < s) {
       sb_[tid] += sb_[tid + s];
       sg_[tid] += sg_[tid + s];
@@ -559,6 +560,12 @@ __global__ __launch_bounds__(kScaleGradThreads) void scale_grad_head_kernel(Geom
     dbeta[h] = sb_[0];
     dgamma[h] = sg_[0];
   }
+}
+
+__global__ __launch_bounds__(kScaleGradThreads) void scale_grad_head_kernel(Geom g, const float* dscale, float* dbeta,
+                                                                   float* dgamma) {
+  __shared__ float sb_[kScaleGradThreads], sg_[kScaleGradThreads];
+  scale_grad_head_part<kScaleGradThreads>(g, dscale, dbeta, dgamma, blockIdx.x, sb_, sg_);
 }
 
 // Per-query parameters: one value per row.

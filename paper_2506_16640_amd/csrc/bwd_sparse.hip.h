@@ -57,6 +57,9 @@ struct BwdSparseArgs {
                        // tiled kernels; entry B*H + kLongCountOffset (zeroed by bwd_lists_kernel): number of keys on
                        // the long-segment list
   int* long_keys;      // [B*H*Nk] keys with more than kSortedKeyEntries entries
+  float* dbeta;        // per-head scale gradients, reduced by extra workgroups of the keys launch
+  float* dgamma;       //   (scale_heads = 0: not here)
+  int scale_heads;     // H for per-head scale parameters, else 0
   unsigned long long* stats;
   int nqb;
 };
@@ -414,8 +417,14 @@ __global__ __launch_bounds__(kThreads, D == 64 ? 3 : 2) void bwd_keys_kernel(Bwd
     bwd_long_keys_part<T, D>(A, blockIdx.x, kLongKeyBlocks);
     return;
   }
+  if (blockIdx.x < kLongKeyBlocks + A.scale_heads) {
+    // dscale is complete by now (row kernel, tiled dQ kernel): its reduction to d beta, d gamma rides along
+    __shared__ float sb_[kThreads], sg_[kThreads];
+    scale_grad_head_part<kThreads>(g, A.dscale, A.dbeta, A.dgamma, blockIdx.x - kLongKeyBlocks, sb_, sg_);
+    return;
+  }
   const long long nkeys = (long long)g.B * g.H * g.Nk;
-  const long long key = (long long)(blockIdx.x - kLongKeyBlocks) * kBlockRows + wave * 32 + li;
+  const long long key = (long long)(blockIdx.x - kLongKeyBlocks - A.scale_heads) * kBlockRows + wave * 32 + li;
   bool on = key < nkeys;
   const int bh = on ? (int)(key / g.Nk) : 0;
   const int j = on ? (int)(key % g.Nk) : 0;

@@ -438,6 +438,9 @@ int run_bwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
       sa.long_keys = reinterpret_cast<int*>(ws + L.off_longkeys);
       sa.stats = reinterpret_cast<unsigned long long*>(stats);
       sa.nqb = L.nqb;
+      sa.dbeta = dbeta;
+      sa.dgamma = dgamma;
+      sa.scale_heads = p->scale_layout == 1 ? H : 0;
       ok = ok && launch_bwd_rows_am<T, D>(sa, alpha_mode(p->alpha), B * H * ((L.nqb + 1) / 2), st, ev, saved != nullptr);
       if (!ok) return ENTMAX_ATTN_LAUNCH_FAILED;
     } else {
@@ -494,14 +497,15 @@ int run_bwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
       hipLaunchKernelGGL(csc_scatter_kernel, dim3((unsigned)(B * H * L.nqb)), dim3(kThreads), 0, st, sa);
       ok = ok && launch_ok();
       long long keys = (long long)B * H * p->Nk;
-      hipLaunchKernelGGL((bwd_keys_kernel<T, D>), dim3((unsigned)(kLongKeyBlocks + (keys + kBlockRows - 1) / kBlockRows)),
+      hipLaunchKernelGGL((bwd_keys_kernel<T, D>),
+                         dim3((unsigned)(kLongKeyBlocks + sa.scale_heads + (keys + kBlockRows - 1) / kBlockRows)),
                          dim3(kThreads), 0, st, sa);
       ok = ok && launch_ok();
     }
     record(ev, ENTMAX_BWD_PHASE_KEYS + 1, st);
   }
   if (!ok) return ENTMAX_ATTN_LAUNCH_FAILED;
-  if (p->scale_layout == 1) {
+  if (p->scale_layout == 1 && !(p->path == 0 && p->Nk > 0 && p->Nq > 0)) {  // (else done inside the keys launch)
     hipLaunchKernelGGL(scale_grad_head_kernel, dim3((unsigned)H), dim3(kScaleGradThreads), 0, st, g, dscale, dbeta,
                        dgamma);
     ok = launch_ok();
