@@ -8,14 +8,15 @@
 // is a sparse problem once the support is known:
 //   bwd_lists_kernel   one Q K^T sweep on the matrix cores at the saved tau lists
 //                      each row's support (key index + raw score);
+//   key_offsets_kernel one workgroup per head: how many listed entries name each key, prefix sums
+//                      of these counts (every key gets a segment that can hold all its entries), and
+//                      the list of keys with long segments;
 //   bwd_rows_kernel    everything row-wise (mu, dscale, dQ) from the lists, by
 //                      gathering the few K and V rows (one lane pair per row).
-//                      Each entry's (p, c dS) is stored and the per-key entry
-//                      counts are accumulated;
-//   csc_offsets_kernel prefix sums of the per-key counts (one workgroup per head);
-//   csc_scatter_kernel moves the entries into key-major order;
-//   bwd_keys_kernel    one wave per key: dV_j and dK_j as sums over the key's
-//                      entries, reading whole dO / Q rows (one feature per lane).
+//                      Each entry's (query, p, c dS) goes straight into its key's segment, at the
+//                      place a returning atomic on the key's cursor hands out;
+//   bwd_keys_kernel    lane pair per key (one wave per key for long segments): dV_j and dK_j as
+//                      sums over the key's entries, in query order.
 // A head in which some half row holds more than kBwdCap support entries is
 // flagged and left, as a whole, to the tiled kernels of bwd.hip.h.
 #pragma once
@@ -26,7 +27,9 @@ namespace entmax {
 
 constexpr int kBwdCap = 16;  // support entries per lane = per half row
 constexpr int kLongCountOffset = 64;  // the long-key counter sits in a cache line of its own, away from the flags
-constexpr unsigned kNoKey = 0xffffffffu;  // list slot whose entry is not part of the support
+constexpr int kSortedKeyEntries = 8;        // a key with at most this many entries is summed by one lane pair
+constexpr int kListInWorkspace = 1 << 30;   // list length flag: the entries sit in the lane's own list (jlist)
+constexpr int kListCountMask = 0xffff;
 
 struct BwdSparseArgs {
   Geom g;
@@ -39,17 +42,17 @@ struct BwdSparseArgs {
   void* dK;
   void* dV;
   float* dscale;       // [B*H*Nq]
-  uint2* jlist;        // [B*H*nqb*4 waves][kBwdCap][64 lanes], see list_entry(): (key index, raw dot product bits); bwd_rows_kernel replaces the
-                       // second word by the entry's arrival number within its key (key index kNoKey: dropped)
-  float2* pw;          // same layout: (p_ij, c_i dS_ij)
+  uint2* jlist;        // [B*H*nqb*4 waves][kBwdCap][64 lanes], see list_entry(): (key index, raw dot product bits) bwd_rows_kernel replaces the
   void* cells;         // sweep scratch: per workgroup and lane, kBwdCap cells
   int* lcnt;           // [B*H*Nq][2] entries per half row, written by bwd_lists_kernel or bwd_prepare_kernel
   const uint2* src_list;  // what bwd_rows_kernel reads: jlist, or the forward's candidate lists (`saved` buffer,
                           // kCandCap entries per lane)
   const int* src_lcnt;    // forward's list lengths   } only with the forward's lists,
   const int* src_dense;   // forward's block flags    } read by bwd_prepare_kernel
-  int* kcount;         // [B*H*Nk] entries per key (zeroed by bwd_lists_kernel)
-  int* koffs;          // [B*H*Nk] exclusive prefix sums of kcount within the head
+  int* kcount;         // [B*H*Nk] listed entries per key = size of the key's segment (key_offsets_kernel, or the
+                       // forward's counts in the `saved` buffer: then read only)
+  int* kcursor;        // [B*H*Nk] entries placed so far; after bwd_rows_kernel: the key's entries with p > 0
+  int* koffs;          // [B*H*Nk] exclusive prefix sums of kcount within the head: segment starts
   int* csc_i;          // [B*H][Nq*2*kBwdCap] query row of each entry, key-major
   float2* csc_pw;      // same order: (p, c dS)
   int* block_flag;     // [B*H*nqb] written by bwd_lists_kernel: 1 when a list of the block overflowed
@@ -85,12 +88,6 @@ __device__ __forceinline__ void bwd_lists_block(const BwdSparseArgs& A, int bh_,
   if (q.block_lim > 0) fits = collect_sweep<C, T, D, kBwdCap>(q, g, A.K, smem, ovf, live, tau, A.cells, mylist, cnt, n_qk, n_cand_tiles);
   if (q.tid == 0) A.block_flag[q.bh * A.nqb + q.qb] = fits ? 0 : 1;
   if (fits && q.valid) A.lcnt[row_idx * 2 + q.hh] = cnt;
-  // this block's share of the per-key entry counters starts at zero for bwd_rows_kernel
-  {
-    const int chunk = (g.Nk + A.nqb - 1) / A.nqb;
-    const int j_end = min(g.Nk, (q.qb + 1) * chunk);
-    for (int j = q.qb * chunk + q.tid; j < j_end; j += kThreads) A.kcount[(long long)q.bh * g.Nk + j] = 0;
-  }
   if (blockIdx.x == 0 && q.tid == 0) A.head_flag[g.B * g.H + kLongCountOffset] = 0;
   if (A.stats && q.lane == 0) {
     atomicAdd(&A.stats[ENTMAX_STAT_BWD_TILES_VISIBLE], (unsigned long long)n_qk);
@@ -112,13 +109,9 @@ __global__ __launch_bounds__(kThreads, 3) void bwd_lists_kernel(BwdSparseArgs A)
 
 // With the forward's lists there is no sweep: this kernel does the sweep kernel's bookkeeping.  One
 // workgroup per query block: the list lengths bwd_rows_kernel will use, the block's flag (a support
-// longer than kBwdCap, or a block the forward left to its tiled kernel), the block's share of the
-// per-key counters, the long-key counter.  A candidate list longer than kBwdCap is rare: its entries
+// longer than kBwdCap, or a block the forward left to its tiled kernel), the long-key counter.  A candidate list longer than kBwdCap is rare: its entries
 // with non-zero probability at tau are copied to the lane's own list, and the length carries
 // kListInWorkspace to say so.
-constexpr int kListInWorkspace = 1 << 30;
-constexpr int kListCountMask = 0xffff;
-
 template <int D>
 __global__ __launch_bounds__(kThreads) void bwd_prepare_kernel(BwdSparseArgs A) {
   const Geom& g = A.g;
@@ -150,9 +143,6 @@ __global__ __launch_bounds__(kThreads) void bwd_prepare_kernel(BwdSparseArgs A) 
   if (rl.valid) A.lcnt[row_idx * 2 + rl.hh] = cnt;
   const int any_over = __syncthreads_or(over ? 1 : 0);
   if (threadIdx.x == 0) A.block_flag[rl.bh * A.nqb + rl.qb] = any_over ? 1 : 0;
-  const int chunk = (g.Nk + A.nqb - 1) / A.nqb;
-  const int j_end = min(g.Nk, (rl.qb + 1) * chunk);
-  for (int j = rl.qb * chunk + (int)threadIdx.x; j < j_end; j += kThreads) A.kcount[(long long)rl.bh * g.Nk + j] = 0;
   if (blockIdx.x == 0 && threadIdx.x == 0) A.head_flag[g.B * g.H + kLongCountOffset] = 0;
 }
 
@@ -174,6 +164,7 @@ __global__ __launch_bounds__(kThreads, D == 64 ? 2 : 1) void bwd_rows_kernel(Bwd
   const float a = (g.alpha - 1.0f) * fabsf(c);  // same arithmetic as the sweep that made the lists
   const float sgn = (c < 0.f) ? -1.f : 1.f;
   // every load that does not depend on another is issued before the first wait (the head's flags included)
+  const int head_dense = A.head_flag[rl.bh];
   const float tau_raw = A.tau[row_idx];
   const int cnt_raw = A.lcnt[row_idx * 2 + rl.hh];
   const float tau = live ? tau_raw : 0.f;
@@ -182,8 +173,7 @@ __global__ __launch_bounds__(kThreads, D == 64 ? 2 : 1) void bwd_rows_kernel(Bwd
   const long long q_base = (long long)rl.b * g.q_sb + (long long)rl.h * g.q_sh;
   const long long kv_base = (long long)rl.b * g.kv_sb + (long long)rl.h * g.kv_sh;
   const long long list0 = list_entry<kBwdCap>(rl.bh, A.nqb, rl.qb, threadIdx.x >> 6, threadIdx.x & 63);
-  uint2* mylist = A.jlist + list0;
-  float2* mypw = A.pw + list0;
+  const uint2* mylist = A.jlist + list0;
   const uint2* srclist = A.src_list + list_entry<SRC_CAP>(rl.bh, A.nqb, rl.qb, threadIdx.x >> 6, threadIdx.x & 63);
   const T* Kbh = reinterpret_cast<const T*>(A.K) + kv_base;
   const T* Vbh = reinterpret_cast<const T*>(A.V) + kv_base;
@@ -207,14 +197,7 @@ __global__ __launch_bounds__(kThreads, D == 64 ? 2 : 1) void bwd_rows_kernel(Bwd
 #pragma unroll
     for (int e = 0; e < kEarly; ++e) early[e] = rdlist[e * kListStride];
   }
-  {
-    // OR of the head's block flags; the head's first workgroup publishes it for the kernels that follow
-    bool any = false;
-    for (int k = threadIdx.x; k < A.nqb; k += kThreads) any = any || A.block_flag[rl.bh * A.nqb + k] != 0;
-    const int head_any = __syncthreads_or(any ? 1 : 0);
-    if (rl.qb == 0 && threadIdx.x == 0) A.head_flag[rl.bh] = head_any ? 1 : 0;
-    if (head_any) return;  // the tiled kernels own this head
-  }
+  if (head_dense != 0) return;  // the tiled kernels own this head
 
   auto finish = [&](auto ne_tag) {
     constexpr int NE = decltype(ne_tag)::value;
@@ -239,7 +222,7 @@ __global__ __launch_bounds__(kThreads, D == 64 ? 2 : 1) void bwd_rows_kernel(Bwd
     float qa[DH], qb[DH];  // this lane's half of sum g dP k and of sum g k
 #pragma unroll
     for (int t = 0; t < DH; ++t) qa[t] = qb[t] = 0.f;
-    int slotv[NE];  // arrival numbers of the lane's own entries; -1: not part of the support
+    int slotv[NE];  // place in the key-major arrays of the lane's own entries; -1: not part of the support
 #pragma unroll
     for (int e = 0; e < NE; ++e) {
       slotv[e] = -1;
@@ -264,7 +247,8 @@ __global__ __launch_bounds__(kThreads, D == 64 ? 2 : 1) void bwd_rows_kernel(Bwd
           kk.load(Kbh + (long long)j * g.kv_sn + rl.hh * DH);
           // the entry's owner takes its arrival number among the key's entries: its place in the key's segment
           if (rl.hh == src) {
-            slotv[e] = atomicAdd(&A.kcount[(long long)rl.bh * g.Nk + j], 1);
+            const long long kidx = (long long)rl.bh * g.Nk + j;
+            slotv[e] = A.koffs[kidx] + atomicAdd(&A.kcursor[kidx], 1);
             ++n_entries;
           }
 #pragma unroll
@@ -293,20 +277,18 @@ __global__ __launch_bounds__(kThreads, D == 64 ? 2 : 1) void bwd_rows_kernel(Bwd
 #pragma unroll
     for (int t = 0; t < DH; ++t) dq[t] = c * fmaf(-mu, qb[t], qa[t]);
     const float dsc = fmaf(-mu, sd0, sd1);
-    // the per-entry records for the key side
+    // the per-entry records (query, p, c dS) go straight to their place in the key-major arrays
+    // (a listed key whose probability rounds to zero here has no place and is dropped)
+    const long long cap = (long long)g.Nq * 2 * kBwdCap;  // entries a head can hold
 #pragma unroll
     for (int e = 0; e < NE; ++e) {
-      if (slotv[e] >= 0) {
+      if (slotv[e] >= 0 && slotv[e] < cap) {  // (below cap by construction; never index outside the head)
         float x = fmaxf(fmaf(dv[e], a, -tau), 0.f);
         float ds = pow_rm1<AM>(x, r) * (dpv[e] - mu);
-        mypw[e * kListStride] = make_float2(pow_r<AM>(x, r), c * ds);
+        A.csc_i[rl.bh * cap + slotv[e]] = rl.i;
+        A.csc_pw[rl.bh * cap + slotv[e]] = make_float2(pow_r<AM>(x, r), c * ds);
       }
     }
-    // the returned arrival numbers are only needed now: the atomics above overlap each other
-    // (a listed key whose probability rounds to zero here is dropped from the key side)
-#pragma unroll
-    for (int e = 0; e < NE; ++e)
-      if (e < cnt) mylist[e * kListStride] = slotv[e] >= 0 ? make_uint2(jv[e], (unsigned)slotv[e]) : make_uint2(kNoKey, 0u);
     if (rl.valid) {
       store_row<T>(reinterpret_cast<T*>(A.dQ) + q_base + (long long)rl.i * g.q_sn + rl.hh * DH, DH, dq);
       // the scores were formed with q negated when scale_i < 0: undo the sign for z_ij
@@ -327,31 +309,63 @@ __global__ __launch_bounds__(kThreads, D == 64 ? 2 : 1) void bwd_rows_kernel(Bwd
 
 // ------------------------------------------------------------ key-major order
 
-// One workgroup per head: exclusive prefix sums of the per-key entry counts.
-// Keys with more than kSortedKeyEntries entries are put on the long-key list (any order).
-constexpr int kSortedKeyEntries = 8;
+// One workgroup per head, before the row kernel.  Counts, per key, the list entries that name it (a
+// superset of the entries with p > 0), and gives every key a segment of that size in the key-major
+// arrays: koffs = exclusive prefix sums of the counts.  The row kernel then places an entry at
+// koffs[key] + (arrival number from the key's cursor) -- no reordering pass.  Also: the head's flag (OR of
+// its block flags), zeroed cursors, and the list of keys whose segment exceeds kSortedKeyEntries.
+// counters: LDS when a head's keys fit (use_lds), else the kcount array itself.
+constexpr int kOffsThreads = 1024;
 
-__global__ __launch_bounds__(kThreads) void csc_offsets_kernel(const int* kcount, int* koffs, int Nk,
-                                                               const int* head_flag, int* long_keys, int* long_count) {
-  __shared__ int part[kThreads];   // entries in the thread's range of keys
-  __shared__ int partl[kThreads];  // long keys in it
+// precounted: A.kcount already holds the counts (the forward's, read only): only the prefix sums are left.
+__global__ __launch_bounds__(kOffsThreads) void key_offsets_kernel(BwdSparseArgs A, int src_cap, int use_lds,
+                                                                  int precounted) {
+  extern __shared__ int offs_lds[];
+  int* part = offs_lds;                   // entries in the thread's range of keys
+  int* partl = offs_lds + kOffsThreads;   // long segments in it
   __shared__ int long_base;
-  const int bh = blockIdx.x, tid = threadIdx.x;
-  if (head_flag[bh] != 0) return;
-  const int per = (Nk + kThreads - 1) / kThreads;
+  const Geom& g = A.g;
+  const int bh = blockIdx.x, tid = threadIdx.x, Nk = g.Nk;
+  {
+    int any = 0;
+    for (int k = tid; k < A.nqb; k += kOffsThreads) any |= A.block_flag[bh * A.nqb + k] != 0 ? 1 : 0;
+    any = __syncthreads_or(any);
+    if (tid == 0) A.head_flag[bh] = any ? 1 : 0;
+    if (any) return;  // the tiled kernels own this head
+  }
+  int* gcount = A.kcount + (long long)bh * Nk;
+  int* cnt = (use_lds && !precounted) ? offs_lds + 2 * kOffsThreads : gcount;
+  if (!precounted) {
+  for (int j = tid; j < Nk; j += kOffsThreads) cnt[j] = 0;
+  __syncthreads();
+  for (int hr = tid; hr < g.Nq * 2; hr += kOffsThreads) {
+    const int i = hr >> 1, hh = hr & 1;
+    const int v = A.lcnt[((long long)bh * g.Nq + i) * 2 + hh];
+    const int n = min(v & kListCountMask, kBwdCap);
+    const int qb = i / kBlockRows, wave = (i % kBlockRows) >> 5, lane = hh * 32 + (i & 31);
+    const uint2* src = (src_cap == kBwdCap || (v & kListInWorkspace) != 0)
+                           ? A.jlist + list_entry<kBwdCap>(bh, A.nqb, qb, wave, lane)
+                           : A.src_list + list_entry<kCandCap>(bh, A.nqb, qb, wave, lane);
+    for (int e = 0; e < n; ++e) {
+      const unsigned key = src[e * kListStride].x;
+      if (key < (unsigned)Nk) atomicAdd(&cnt[key], 1);
+    }
+  }
+  __syncthreads();
+  }
+  const int per = (Nk + kOffsThreads - 1) / kOffsThreads;
   const int beg = tid * per, end = min(Nk, beg + per);
-  const int* c = kcount + (long long)bh * Nk;
   int s = 0, nl = 0;
   for (int j = beg; j < end; ++j) {
-    const int cj = c[j];
+    const int cj = cnt[j];
     s += cj;
     nl += cj > kSortedKeyEntries ? 1 : 0;
   }
   part[tid] = s;
   partl[tid] = nl;
   __syncthreads();
-  // Hillis-Steele inclusive scans over the 256 partial sums
-  for (int off = 1; off < kThreads; off <<= 1) {
+  // Hillis-Steele inclusive scans over the partial sums
+  for (int off = 1; off < kOffsThreads; off <<= 1) {
     int v = (tid >= off) ? part[tid - off] : 0;
     int vl = (tid >= off) ? partl[tid - off] : 0;
     __syncthreads();
@@ -360,40 +374,18 @@ __global__ __launch_bounds__(kThreads) void csc_offsets_kernel(const int* kcount
     __syncthreads();
   }
   // one list reservation per head
-  if (tid == kThreads - 1) long_base = partl[tid] > 0 ? atomicAdd(long_count, partl[tid]) : 0;
+  if (tid == kOffsThreads - 1)
+    long_base = partl[tid] > 0 ? atomicAdd(&A.head_flag[g.B * g.H + kLongCountOffset], partl[tid]) : 0;
   __syncthreads();
   int run = part[tid] - s;
   int lpos = long_base + partl[tid] - nl;
   for (int j = beg; j < end; ++j) {
-    koffs[(long long)bh * Nk + j] = run;
-    const int cj = c[j];
+    const int cj = cnt[j];
+    A.koffs[(long long)bh * Nk + j] = run;
+    A.kcursor[(long long)bh * Nk + j] = 0;
+    if (cnt != gcount) gcount[j] = cj;
     run += cj;
-    if (cj > kSortedKeyEntries) long_keys[lpos++] = bh * Nk + j;
-  }
-}
-
-// One thread per half row, threads laid out like the lanes of the list kernels (workgroup = query block,
-// wave = 32 rows x 2 halves): moves its entries into the key-major arrays.  An entry's place is its
-// key's segment start plus its arrival number, so no atomics are needed here.
-__global__ __launch_bounds__(kThreads) void csc_scatter_kernel(BwdSparseArgs A) {
-  const Geom& g = A.g;
-  const int bh = blockIdx.x / A.nqb, qb = blockIdx.x % A.nqb;
-  if (A.head_flag[bh] != 0) return;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int i = qb * kBlockRows + wave * 32 + (lane & 31);
-  if (i >= g.Nq) return;
-  const long long half_row = ((long long)bh * g.Nq + i) * 2 + (lane >> 5);
-  const int cnt = min(A.lcnt[half_row] & kListCountMask, kBwdCap);
-  const long long list0 = list_entry<kBwdCap>(bh, A.nqb, qb, wave, lane);
-  const long long base = (long long)bh * g.Nq * 2 * kBwdCap;
-  for (int e = 0; e < cnt; ++e) {
-    uint2 en = A.jlist[list0 + (long long)e * kListStride];
-    if (en.x >= (unsigned)g.Nk) continue;  // kNoKey, or anything that is not a key
-    int pos = A.koffs[(long long)bh * g.Nk + en.x] + (int)en.y;
-    if (pos >= 0 && pos < g.Nq * 2 * kBwdCap) {  // holds by construction; keeps any stray entry inside the head
-      A.csc_i[base + pos] = i;
-      A.csc_pw[base + pos] = A.pw[list0 + (long long)e * kListStride];
-    }
+    if (cj > kSortedKeyEntries) A.long_keys[lpos++] = bh * Nk + j;
   }
 }
 
@@ -401,8 +393,8 @@ __global__ __launch_bounds__(kThreads) void csc_scatter_kernel(BwdSparseArgs A) 
 // One lane pair per key, each lane half of the features (the mirror image of bwd_rows_kernel).
 // A key's entries sit in arrival order; they are summed in query-row order (selection by repeated
 // minimum over the entries held in registers), which makes the result independent of the arrival
-// order.  Keys with more than kSortedKeyEntries entries are served by the first kLongKeyBlocks
-// workgroups of the same launch (bwd_long_keys_part), which run alongside the others.
+// order.  Keys whose segment holds more than kSortedKeyEntries entries are served by the first
+// kLongKeyBlocks workgroups of the same launch (bwd_long_keys_part), which run alongside the others.
 constexpr int kLongKeyBlocks = 1024;
 
 template <typename T, int D>
@@ -430,8 +422,9 @@ __global__ __launch_bounds__(kThreads, D == 64 ? 3 : 2) void bwd_keys_kernel(Bwd
   const int j = on ? (int)(key % g.Nk) : 0;
   on = on && A.head_flag[bh] == 0;
   const int b = bh / g.H, h = bh % g.H;
-  int n = on ? A.kcount[key] : 0;
-  if (n > kSortedKeyEntries) {  // on the long-key list
+  const int seg = on ? A.kcount[key] : 0;            // size of the key's segment
+  int n = on ? min(A.kcursor[key], seg) : 0;         // entries with p > 0 placed in it
+  if (seg > kSortedKeyEntries) {  // on the long-key list
     on = false;
     n = 0;
   }
@@ -495,11 +488,11 @@ __device__ __forceinline__ void bwd_long_keys_part(const BwdSparseArgs& A, int v
   constexpr int PER = D / 64;
   const Geom& g = A.g;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-  // persistent workgroups: the waves share out the list csc_offsets_kernel made
+  // persistent workgroups: the waves share out the list key_offsets_kernel made
   const int nlong = __builtin_amdgcn_readfirstlane(A.head_flag[g.B * g.H + kLongCountOffset]);
   for (int idx = vblock * kWaves + wave; idx < nlong; idx += vgrid * kWaves) {
   const long long key = __builtin_amdgcn_readfirstlane(A.long_keys[idx]);
-  const int n = __builtin_amdgcn_readfirstlane(A.kcount[key]);
+  const int n = __builtin_amdgcn_readfirstlane(min(A.kcursor[key], A.kcount[key]));
   const int bh = (int)(key / g.Nk), j = (int)(key % g.Nk);
   const int b = bh / g.H, h = bh % g.H;
   const long long base = (long long)bh * g.Nq * 2 * kBwdCap + __builtin_amdgcn_readfirstlane(A.koffs[key]);

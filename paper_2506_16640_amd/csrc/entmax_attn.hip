@@ -29,7 +29,7 @@ struct Layout {
   long long q_sb, q_sh, q_sn, kv_sb, kv_sh, kv_sn;
   // workspace offsets
   size_t off_vt, off_cand, off_flcnt, off_bounds, off_flags, off_kt, off_qt, off_dot, off_mu, off_crow, off_dscale, off_mask,
-      off_jlist, off_pw, off_lcnt, off_kcount, off_koffs, off_kcursor, off_csc_i, off_csc_pw, off_hflag, off_longkeys, off_fcells, off_bcells, sv_cand, sv_lcnt, sv_flags, total_saved, total_fwd,
+      off_jlist, off_lcnt, off_kcount, off_koffs, off_kcursor, off_csc_i, off_csc_pw, off_hflag, off_longkeys, off_fcells, off_bcells, sv_cand, sv_lcnt, sv_flags, sv_kcand, total_saved, total_fwd,
       total_bwd;
 };
 
@@ -92,7 +92,8 @@ Layout make_layout(const entmax_attn_params* p) {
   L.sv_cand = 0;
   L.sv_lcnt = cand_bytes;
   L.sv_flags = L.sv_lcnt + align_up(bh * (size_t)p->Nq * 2 * sizeof(int));
-  L.total_saved = L.sv_flags + align_up(bh * (size_t)L.nqb * sizeof(int));
+  L.sv_kcand = L.sv_flags + align_up(bh * (size_t)L.nqb * sizeof(int));
+  L.total_saved = L.sv_kcand + align_up(bh * (size_t)p->Nk * sizeof(int));
   L.off_flcnt = L.off_cand + cand_bytes;
   L.off_bounds = L.off_flcnt + align_up(bh * (size_t)p->Nq * 2 * sizeof(int));
   L.off_flags = L.off_bounds + align_up(bh * (size_t)p->Nq * sizeof(float2));
@@ -118,8 +119,6 @@ Layout make_layout(const entmax_attn_params* p) {
   size_t rows = bh * (size_t)p->Nq;
   L.off_jlist = o;
   o += align_up(bh * (size_t)L.nqb * kThreads * kBwdCap * sizeof(uint2));
-  L.off_pw = o;
-  o += align_up(bh * (size_t)L.nqb * kThreads * kBwdCap * sizeof(float2));
   L.off_lcnt = o;
   o += align_up(rows * 2 * sizeof(int));
   size_t key_bytes = align_up(bh * (size_t)p->Nk * sizeof(int));
@@ -302,6 +301,7 @@ int run_fwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
     sa.cand = reinterpret_cast<uint2*>(saved ? saved + L.sv_cand : ws + L.off_cand);
     sa.cells = ws + L.off_fcells;
     sa.lcnt = reinterpret_cast<int*>(saved ? saved + L.sv_lcnt : ws + L.off_flcnt);
+    sa.kcand = saved ? reinterpret_cast<int*>(saved + L.sv_kcand) : nullptr;
     sa.bounds = reinterpret_cast<float2*>(ws + L.off_bounds);
     sa.dense_flag = dense_flag;
     sa.head_flag = head_flag;
@@ -374,6 +374,18 @@ bool launch_bwd_rows(const BwdSparseArgs& a, int nblocks, hipStream_t st, void* 
   }
   if (!launch_ok()) return false;
   record(ev, ENTMAX_BWD_PHASE_LISTS + 1, st);
+  {
+    // per-key counters in LDS when a head's keys fit beside the scan arrays
+    const size_t scan_bytes = 2 * (size_t)kOffsThreads * sizeof(int);
+    const bool use_lds = !from_saved && scan_bytes + (size_t)a.g.Nk * sizeof(int) <= 150 * 1024;
+    const size_t smem = scan_bytes + (use_lds ? (size_t)a.g.Nk * sizeof(int) : 0);
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(key_offsets_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)smem) != hipSuccess)
+      return false;
+    hipLaunchKernelGGL(key_offsets_kernel, dim3((unsigned)(a.g.B * a.g.H)), dim3(kOffsThreads), smem, st, a,
+                       from_saved ? kCandCap : kBwdCap, use_lds ? 1 : 0, from_saved ? 1 : 0);
+    if (!launch_ok()) return false;
+  }
   if (from_saved)
     hipLaunchKernelGGL((bwd_rows_kernel<T, D, AM, kCandCap>), row_grid, dim3(kThreads), 0, st, a);
   else
@@ -424,12 +436,13 @@ int run_bwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
       sa.dscale = dscale;
       sa.jlist = reinterpret_cast<uint2*>(ws + L.off_jlist);
       sa.cells = ws + L.off_bcells;
-      sa.pw = reinterpret_cast<float2*>(ws + L.off_pw);
+      sa.kcursor = reinterpret_cast<int*>(ws + L.off_kcursor);
       sa.lcnt = reinterpret_cast<int*>(ws + L.off_lcnt);
       sa.src_list = saved ? reinterpret_cast<const uint2*>(saved + L.sv_cand) : sa.jlist;
       sa.src_lcnt = saved ? reinterpret_cast<const int*>(saved + L.sv_lcnt) : nullptr;
       sa.src_dense = saved ? reinterpret_cast<const int*>(saved + L.sv_flags) : nullptr;
-      sa.kcount = reinterpret_cast<int*>(ws + L.off_kcount);
+      // with the forward's lists come the forward's per-key counts (read only here)
+      sa.kcount = saved ? reinterpret_cast<int*>(const_cast<char*>(saved) + L.sv_kcand) : reinterpret_cast<int*>(ws + L.off_kcount);
       sa.koffs = reinterpret_cast<int*>(ws + L.off_koffs);
       sa.csc_i = reinterpret_cast<int*>(ws + L.off_csc_i);
       sa.csc_pw = reinterpret_cast<float2*>(ws + L.off_csc_pw);
@@ -491,11 +504,6 @@ int run_bwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
     }
     if (!ok) return ENTMAX_ATTN_LAUNCH_FAILED;
     if (lists) {
-      hipLaunchKernelGGL(csc_offsets_kernel, dim3((unsigned)(B * H)), dim3(kThreads), 0, st, sa.kcount, sa.koffs,
-                         p->Nk, head_flag, sa.long_keys, head_flag + (size_t)B * H + kLongCountOffset);
-      ok = ok && launch_ok();
-      hipLaunchKernelGGL(csc_scatter_kernel, dim3((unsigned)(B * H * L.nqb)), dim3(kThreads), 0, st, sa);
-      ok = ok && launch_ok();
       long long keys = (long long)B * H * p->Nk;
       hipLaunchKernelGGL((bwd_keys_kernel<T, D>),
                          dim3((unsigned)(kLongKeyBlocks + sa.scale_heads + (keys + kBlockRows - 1) / kBlockRows)),

@@ -45,6 +45,8 @@ struct FwdSparseArgs {
   void* O;
   float* tau;
   uint2* cand;      // [B*H*nqb*4 waves][kCandCap][64 lanes] (key index, raw dot product bits), see list_entry()
+  int* kcand;       // NULL, or [B*H*Nk]: per key, the number of list entries that name it (for the backward's
+                    // key-major layout); zeroed by fwd_lists_kernel, counted by fwd_finish_kernel
   void* cells;      // sweep scratch: per workgroup and lane, kCandCap cells (see CellBuf)
   int* lcnt;        // [B*H*Nq][2] list lengths
   float2* bounds;   // [B*H*Nq] (tau_lb, right end of the bracket)
@@ -189,6 +191,11 @@ __device__ __forceinline__ void fwd_lists_block(const FwdSparseArgs& A, int bh_,
   const long long row_idx = (long long)q.bh * g.Nq + (q.valid ? q.i : 0);
   const bool live = q.valid && q.lim > 0;
 
+  if (A.kcand) {  // this block's share of the per-key counters starts at zero for the finish kernel
+    const int chunk = (g.Nk + A.nqb - 1) / A.nqb;
+    const int j_end = min(g.Nk, (q.qb + 1) * chunk);
+    for (int j = q.qb * chunk + q.tid; j < j_end; j += kThreads) A.kcand[(long long)q.bh * g.Nk + j] = 0;
+  }
   if (q.block_lim == 0) {  // no row of this workgroup sees any key: the finish kernel writes the zeros
     if (q.valid) {
       A.lcnt[row_idx * 2 + q.hh] = 0;
@@ -417,7 +424,13 @@ __global__ __launch_bounds__(kThreads) void fwd_finish_kernel(FwdSparseArgs A) {
         en = mylist[e * kListStride];
       jv[e] = (e < cnt) ? en.x : 0u;
       yv[e] = (e < cnt) ? a * __uint_as_float(en.y) : -kInf;  // -inf: never positive
+      if (A.kcand && e < cnt && en.x < (unsigned)g.Nk) atomicAdd(&A.kcand[(long long)rl.bh * g.Nk + en.x], 1);
     }
+    if (A.kcand)
+      for (int e = NE; e < cnt; ++e) {
+        const unsigned j = mylist[e * kListStride].x;
+        if (j < (unsigned)g.Nk) atomicAdd(&A.kcand[(long long)rl.bh * g.Nk + j], 1);
+      }
     // entries beyond the NE held in registers (few lanes) are read again wherever they are needed
     const bool has_tail = __ballot(cnt > NE) != 0ull;
     bool done = !live;
