@@ -302,6 +302,7 @@ int run_fwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
     sa.cells = ws + L.off_fcells;
     sa.lcnt = reinterpret_cast<int*>(saved ? saved + L.sv_lcnt : ws + L.off_flcnt);
     sa.kcand = saved ? reinterpret_cast<int*>(saved + L.sv_kcand) : nullptr;
+    if (sa.kcand && !zero_words(sa.kcand, (size_t)p->B * p->H * p->Nk * sizeof(int), st)) return ENTMAX_ATTN_LAUNCH_FAILED;
     sa.bounds = reinterpret_cast<float2*>(ws + L.off_bounds);
     sa.dense_flag = dense_flag;
     sa.head_flag = head_flag;

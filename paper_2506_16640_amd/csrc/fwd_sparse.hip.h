@@ -45,8 +45,8 @@ struct FwdSparseArgs {
   void* O;
   float* tau;
   uint2* cand;      // [B*H*nqb*4 waves][kCandCap][64 lanes] (key index, raw dot product bits), see list_entry()
-  int* kcand;       // NULL, or [B*H*Nk]: per key, the number of list entries that name it (for the backward's
-                    // key-major layout); zeroed by fwd_lists_kernel, counted by fwd_finish_kernel
+  int* kcand;       // NULL, or [B*H*Nk] pre-zeroed: per key, the number of list entries that name it (for the
+                    // backward's key-major layout), counted as the lists are written
   void* cells;      // sweep scratch: per workgroup and lane, kCandCap cells (see CellBuf)
   int* lcnt;        // [B*H*Nq][2] list lengths
   float2* bounds;   // [B*H*Nq] (tau_lb, right end of the bracket)
@@ -84,7 +84,7 @@ struct CellBuf {
 template <typename C, typename T, int D, int CAP>
 __device__ __forceinline__ bool collect_sweep(const C& q, const Geom& g, const void* K, char* tiles, int* ovf, bool live,
                                               float thr, void* cells, uint2* mylist, int& cnt, unsigned& n_qk,
-                                              unsigned& n_cand_tiles) {
+                                              unsigned& n_cand_tiles, int* kcand = nullptr) {
   constexpr int KT = C::KT, NSB = C::NSB;
   // candidates are the keys with a * dot > thr: in raw units, dot > cut.  Rounding may move a key that
   // sits on the threshold (probability ~ 0) in or out of the list; the consumers recompute its value.
@@ -164,7 +164,11 @@ __device__ __forceinline__ bool collect_sweep(const C& q, const Geom& g, const v
 #pragma unroll
         for (int rr = 0; rr < 4; ++rr) {
           if (dv[rr] > cut) {
-            if (cnt < CAP) mylist[cnt * kListStride] = make_uint2((unsigned)(jc + 8 * u + rr), __float_as_uint(dv[rr]));
+            if (cnt < CAP) {
+              mylist[cnt * kListStride] = make_uint2((unsigned)(jc + 8 * u + rr), __float_as_uint(dv[rr]));
+              // (counts of a block that overflows later stay in: the counters are upper bounds)
+              if (kcand) atomicAdd(&kcand[(long long)q.bh * g.Nk + jc + 8 * u + rr], 1);
+            }
             ++cnt;
           }
         }
@@ -191,11 +195,6 @@ __device__ __forceinline__ void fwd_lists_block(const FwdSparseArgs& A, int bh_,
   const long long row_idx = (long long)q.bh * g.Nq + (q.valid ? q.i : 0);
   const bool live = q.valid && q.lim > 0;
 
-  if (A.kcand) {  // this block's share of the per-key counters starts at zero for the finish kernel
-    const int chunk = (g.Nk + A.nqb - 1) / A.nqb;
-    const int j_end = min(g.Nk, (q.qb + 1) * chunk);
-    for (int j = q.qb * chunk + q.tid; j < j_end; j += kThreads) A.kcand[(long long)q.bh * g.Nk + j] = 0;
-  }
   if (q.block_lim == 0) {  // no row of this workgroup sees any key: the finish kernel writes the zeros
     if (q.valid) {
       A.lcnt[row_idx * 2 + q.hh] = 0;
@@ -266,7 +265,7 @@ __device__ __forceinline__ void fwd_lists_block(const FwdSparseArgs& A, int bh_,
   // ---------------------------------------------- 2. candidate lists at tau_lb
   uint2* mylist = A.cand + list_entry<kCandCap>(q.bh, A.nqb, q.qb, q.wave, q.lane);
   int cnt = 0;
-  const bool fits = collect_sweep<C, T, D, kCandCap>(q, g, A.K, tiles, ovf, live, lo, A.cells, mylist, cnt, n_qk2, n_cand_tiles);
+  const bool fits = collect_sweep<C, T, D, kCandCap>(q, g, A.K, tiles, ovf, live, lo, A.cells, mylist, cnt, n_qk2, n_cand_tiles, A.kcand);
   if (!fits) {
     if (q.tid == 0) A.dense_flag[flag_idx] = 1;
   } else {
@@ -424,13 +423,7 @@ __global__ __launch_bounds__(kThreads) void fwd_finish_kernel(FwdSparseArgs A) {
         en = mylist[e * kListStride];
       jv[e] = (e < cnt) ? en.x : 0u;
       yv[e] = (e < cnt) ? a * __uint_as_float(en.y) : -kInf;  // -inf: never positive
-      if (A.kcand && e < cnt && en.x < (unsigned)g.Nk) atomicAdd(&A.kcand[(long long)rl.bh * g.Nk + en.x], 1);
     }
-    if (A.kcand)
-      for (int e = NE; e < cnt; ++e) {
-        const unsigned j = mylist[e * kListStride].x;
-        if (j < (unsigned)g.Nk) atomicAdd(&A.kcand[(long long)rl.bh * g.Nk + j], 1);
-      }
     // entries beyond the NE held in registers (few lanes) are read again wherever they are needed
     const bool has_tail = __ballot(cnt > NE) != 0ull;
     bool done = !live;
