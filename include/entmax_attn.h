@@ -101,20 +101,21 @@ enum {
  * one more entry than the call has phases; entry 0 is recorded on the stream
  * before the first kernel and entry k after the last kernel of phase k-1. */
 enum {
-  ENTMAX_FWD_PHASE_LISTS = 0,     /* candidate-list kernel: two Q K^T sweeps (row maximum, candidates) */
-  ENTMAX_FWD_PHASE_FINISH = 1,    /* threshold and output from the candidate lists */
-  ENTMAX_FWD_PHASE_TRANSPOSE = 2, /* V^T copy for the heads that need the tiled kernel */
-  ENTMAX_FWD_PHASE_TILED = 3,     /* tiled kernel on the workgroups the list kernel left over */
-  ENTMAX_FWD_NUM_PHASES = 4
+  ENTMAX_FWD_PHASE_PREPARE = 0,   /* with `saved`: zero fill of its per-key counters (else empty) */
+  ENTMAX_FWD_PHASE_LISTS = 1,     /* candidate-list kernel: two Q K^T sweeps (row maximum, candidates) */
+  ENTMAX_FWD_PHASE_FINISH = 2,    /* threshold and output from the candidate lists */
+  ENTMAX_FWD_PHASE_TRANSPOSE = 3, /* V^T copy for the heads that need the tiled kernel */
+  ENTMAX_FWD_PHASE_TILED = 4,     /* tiled kernel on the workgroups the list kernel left over */
+  ENTMAX_FWD_NUM_PHASES = 5
 };
 enum {
-  ENTMAX_BWD_PHASE_LISTS = 0,      /* support-list kernel: one Q K^T sweep at the saved threshold (without `saved`) */
-  ENTMAX_BWD_PHASE_ROWS = 1,       /* mu, dscale, dQ and the per-entry (p, dS) from the lists */
+  ENTMAX_BWD_PHASE_LISTS = 0,      /* one Q K^T sweep at the saved threshold, or with `saved` only bookkeeping */
+  ENTMAX_BWD_PHASE_ROWS = 1,       /* per-key segment offsets; mu, dscale, dQ and the per-entry (p, dS) from the lists */
   ENTMAX_BWD_PHASE_TRANSPOSE = 2,  /* tiled path (heads the list kernel left over): operand copies */
   ENTMAX_BWD_PHASE_MASK = 3,       /* tiled path: non-zero tile map */
   ENTMAX_BWD_PHASE_DQ = 4,         /* tiled path: row scalars and dQ */
   ENTMAX_BWD_PHASE_DKV = 5,        /* tiled path: dK, dV */
-  ENTMAX_BWD_PHASE_KEYS = 6,       /* support-list path: key-major reordering, dK and dV per key */
+  ENTMAX_BWD_PHASE_KEYS = 6,       /* support-list path: dK and dV per key (and d beta, d gamma per head) */
   ENTMAX_BWD_PHASE_SCALE_GRAD = 7,
   ENTMAX_BWD_NUM_PHASES = 8
 };

@@ -26,9 +26,9 @@ STAT_NAMES = {
     "bwd_tiles_visible": 8, "bwd_qk_mask": 9, "bwd_active_tiles": 10, "bwd_dq_tiles": 11, "bwd_dkv_tiles": 12,
     "fwd_cand_tiles": 13, "fwd_candidates": 14, "fwd_support": 15, "fwd_sparse_blocks": 16, "fwd_list_qk": 17, "bwd_list_qk": 18, "bwd_support": 19,
 }
-FWD_NUM_PHASES = 4
+FWD_NUM_PHASES = 5
 BWD_NUM_PHASES = 8
-FWD_PHASES = ("lists", "finish", "transpose", "tiled")
+FWD_PHASES = ("prepare", "lists", "finish", "transpose", "tiled")
 BWD_PHASES = ("lists", "rows", "transpose", "mask", "dq", "dkv", "keys", "scale_grad")
 
 

@@ -303,6 +303,7 @@ int run_fwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
     sa.lcnt = reinterpret_cast<int*>(saved ? saved + L.sv_lcnt : ws + L.off_flcnt);
     sa.kcand = saved ? reinterpret_cast<int*>(saved + L.sv_kcand) : nullptr;
     if (sa.kcand && !zero_words(sa.kcand, (size_t)p->B * p->H * p->Nk * sizeof(int), st)) return ENTMAX_ATTN_LAUNCH_FAILED;
+    record(ev, ENTMAX_FWD_PHASE_PREPARE + 1, st);
     sa.bounds = reinterpret_cast<float2*>(ws + L.off_bounds);
     sa.dense_flag = dense_flag;
     sa.head_flag = head_flag;
@@ -312,6 +313,7 @@ int run_fwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
   } else {
     // no lists: tell the backward that every block belongs to its tiled kernels
     if (saved && !fill_words(dense_flag, (size_t)p->B * p->H * L.nqb * sizeof(int), 1u, st)) return ENTMAX_ATTN_LAUNCH_FAILED;
+    record(ev, ENTMAX_FWD_PHASE_PREPARE + 1, st);
     record(ev, ENTMAX_FWD_PHASE_LISTS + 1, st);
   }
   record(ev, ENTMAX_FWD_PHASE_FINISH + 1, st);

@@ -155,28 +155,37 @@ __device__ __forceinline__ bool collect_sweep(const C& q, const Geom& g, const v
   // the sweep ended on a barrier: both flags are final
   bool fits = (ovf[0] | ovf[1]) == 0;
   if (fits) {
-    // a cell holds at most kCellKeys candidates, so there are at least as many candidates as cells
+    // a cell holds at most kCellKeys candidates, so there are at least as many candidates as cells.
+    // First count: nothing is written (and no key counted) for a block one of whose lists is too long.
+    int total = 0;
     for (int k = 0; k < ncell; ++k) {
-      const int jc = cb.j[k * kThreads];
 #pragma unroll
       for (int u = 0; u < kCellGroups; ++u) {
         const f32x4_t dv = cb.d[(k * kCellGroups + u) * kThreads];
 #pragma unroll
-        for (int rr = 0; rr < 4; ++rr) {
-          if (dv[rr] > cut) {
-            if (cnt < CAP) {
+        for (int rr = 0; rr < 4; ++rr) total += dv[rr] > cut ? 1 : 0;
+      }
+    }
+    if (total > CAP) ovf[2] = 1;
+    __syncthreads();
+    fits = ovf[2] == 0;
+    if (fits) {
+      for (int k = 0; k < ncell; ++k) {
+        const int jc = cb.j[k * kThreads];
+#pragma unroll
+        for (int u = 0; u < kCellGroups; ++u) {
+          const f32x4_t dv = cb.d[(k * kCellGroups + u) * kThreads];
+#pragma unroll
+          for (int rr = 0; rr < 4; ++rr) {
+            if (dv[rr] > cut && cnt < CAP) {
               mylist[cnt * kListStride] = make_uint2((unsigned)(jc + 8 * u + rr), __float_as_uint(dv[rr]));
-              // (counts of a block that overflows later stay in: the counters are upper bounds)
               if (kcand) atomicAdd(&kcand[(long long)q.bh * g.Nk + jc + 8 * u + rr], 1);
+              ++cnt;
             }
-            ++cnt;
           }
         }
       }
     }
-    if (cnt > CAP) ovf[2] = 1;
-    __syncthreads();
-    fits = ovf[2] == 0;
   }
   return fits;
 }
