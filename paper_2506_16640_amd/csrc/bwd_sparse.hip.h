@@ -42,8 +42,8 @@ struct BwdSparseArgs {
   void* dK;
   void* dV;
   float* dscale;       // [B*H*Nq]
-  uint2* jlist;        // [B*H*nqb*4 waves][kBwdCap][64 lanes], see list_entry(): (key index, raw dot product bits) bwd_rows_kernel replaces the
-  void* cells;         // sweep scratch: per workgroup and lane, kBwdCap cells
+  uint2* jlist;        // [B*H*nqb*4 waves][kBwdCap][64 lanes], see list_entry(): (key index, raw dot product bits)
+  void* cells;         // sweep scratch: one CellBuf<kBwdCap> per workgroup of the list sweep's grid
   int* lcnt;           // [B*H*Nq][2] entries per half row, written by bwd_lists_kernel or bwd_prepare_kernel
   const uint2* src_list;  // what bwd_rows_kernel reads: jlist, or the forward's candidate lists (`saved` buffer,
                           // kCandCap entries per lane)
@@ -55,11 +55,12 @@ struct BwdSparseArgs {
   int* koffs;          // [B*H*Nk] exclusive prefix sums of kcount within the head: segment starts
   int* csc_i;          // [B*H][Nq*2*kBwdCap] query row of each entry, key-major
   float2* csc_pw;      // same order: (p, c dS)
-  int* block_flag;     // [B*H*nqb] written by bwd_lists_kernel: 1 when a list of the block overflowed
-  int* head_flag;      // [B*H + kLongCountOffset + 1]; entries < B*H written by bwd_rows_kernel: 1: head left to the
-                       // tiled kernels; entry B*H + kLongCountOffset (zeroed by bwd_lists_kernel): number of keys on
-                       // the long-segment list
-  int* long_keys;      // [B*H*Nk] keys with more than kSortedKeyEntries entries
+  int* block_flag;     // [B*H*nqb] written by bwd_lists_kernel / bwd_prepare_kernel: 1 when the block cannot take
+                       // the list path (a list too long, or no lists from the forward)
+  int* head_flag;      // [B*H + kLongCountOffset + 1]; entries < B*H written by key_offsets_kernel: 1: head left to
+                       // the tiled kernels; entry B*H + kLongCountOffset (zeroed by the first kernel): number of
+                       // keys on the long-segment list
+  int* long_keys;      // [B*H*Nk] keys whose segment holds more than kSortedKeyEntries entries
   float* dbeta;        // per-head scale gradients, reduced by extra workgroups of the keys launch
   float* dgamma;       //   (scale_heads = 0: not here)
   int scale_heads;     // H for per-head scale parameters, else 0

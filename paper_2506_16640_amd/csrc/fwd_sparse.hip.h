@@ -47,7 +47,7 @@ struct FwdSparseArgs {
   uint2* cand;      // [B*H*nqb*4 waves][kCandCap][64 lanes] (key index, raw dot product bits), see list_entry()
   int* kcand;       // NULL, or [B*H*Nk] pre-zeroed: per key, the number of list entries that name it (for the
                     // backward's key-major layout), counted as the lists are written
-  void* cells;      // sweep scratch: per workgroup and lane, kCandCap cells (see CellBuf)
+  void* cells;      // sweep scratch: one CellBuf<kCandCap> per workgroup of the list sweep's grid
   int* lcnt;        // [B*H*Nq][2] list lengths
   float2* bounds;   // [B*H*Nq] (tau_lb, right end of the bracket)
   int* dense_flag;  // [B*H*nqb] 1: block left to the tiled kernel

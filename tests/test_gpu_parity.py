@@ -138,6 +138,29 @@ def test_empty_inputs():
     assert float(dk.float().abs().max()) == 0.0 and float(dv.float().abs().max()) == 0.0
 
 
+def test_saved_from_tiled_forward_sends_backward_to_tiled_kernels():
+    # a forward that made no lists (path 1) marks every block in `saved`: the backward, although on the automatic
+    # path, must then take the tiled kernels for every head and still match the oracle
+    import torch
+    from paper_2506_16640_amd import binding
+    from tests.parity_util import to_dev
+    data = _case(1, 2, 300, 300, 64, "bf16", "head", seed=11)
+    q, k, v, do = (to_dev(data[n], "bf16") for n in ("Q", "K", "V", "dO"))
+    beta, gamma = (torch.from_numpy(data[n]).float().cuda() for n in ("beta", "gamma"))
+    kw = dict(alpha=1.5, beta=beta, gamma=gamma, delta=data["delta"], causal=True)
+    saved = binding.new_saved(binding.make_params(q, k, 1.5, data["delta"], True, beta, 0, 0))
+    o, tau = binding.entmax_attn_fwd(q, k, v, path=1, saved=saved, **kw)
+    st = binding.new_stats()
+    dq, dk, dv, db, dg = binding.entmax_attn_bwd(q, k, v, o, do, tau, path=0, saved=saved, stats=st, **kw)
+    torch.cuda.synchronize()
+    sd = binding.stats_dict(st)
+    assert sd["bwd_support"] == 0 and sd["bwd_dq_tiles"] > 0  # no list work, tiled work
+    r = oracle_run(data, 1.5)
+    g = {"O": o, "tau": tau, "dQ": dq, "dK": dk, "dV": dv, "dbeta": db, "dgamma": dg}
+    g = {n: t.float().cpu().numpy().astype(np.float64) for n, t in g.items()}
+    print(compare(g, r, label="saved from tiled forward"))
+
+
 def test_bitwise_reproducible():
     data = _case(1, 2, 300, 300, 64, "bf16", "head", seed=8)
     a = gpu_run(data, 1.5, "bf16")
