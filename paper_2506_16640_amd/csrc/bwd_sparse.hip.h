@@ -391,21 +391,24 @@ __global__ __launch_bounds__(kOffsThreads) void key_offsets_kernel(BwdSparseArgs
 }
 
 // dV_j = sum_i p_ij dO_i,  dK_j = sum_i (c_i dS_ij) q_i  over the key's entries.
-// One lane pair per key, each lane half of the features (the mirror image of bwd_rows_kernel).
-// A key's entries sit in arrival order; they are summed in query-row order (selection by repeated
-// minimum over the entries held in registers), which makes the result independent of the arrival
-// order.  Keys whose segment holds more than kSortedKeyEntries entries are served by the first
-// kLongKeyBlocks workgroups of the same launch (bwd_long_keys_part), which run alongside the others.
+// Eight lanes per key, each lane an eighth of the features: a gathered dO or Q row is then one
+// fully used cache line per load instruction and key, instead of four instructions that each touch a
+// quarter of it.  A key's entries sit in arrival order; lane k of the eight takes entry k, the entries
+// are ranked by query row inside the group and summed in that order, which makes the result independent
+// of the arrival order.  Keys whose segment holds more than kSortedKeyEntries (= 8) entries are served
+// by the first kLongKeyBlocks workgroups of the same launch (bwd_long_keys_part), which run alongside
+// the others; scale_heads more workgroups reduce dscale to d beta, d gamma.
 constexpr int kLongKeyBlocks = 1024;
+constexpr int kKeysPerBlock = kThreads / kSortedKeyEntries;  // 32
 
 template <typename T, int D>
 __device__ __forceinline__ void bwd_long_keys_part(const BwdSparseArgs& A, int vblock, int vgrid);
 
 template <typename T, int D>
-__global__ __launch_bounds__(kThreads, D == 64 ? 3 : 2) void bwd_keys_kernel(BwdSparseArgs A) {
-  constexpr int DH = D / 2;
+__global__ __launch_bounds__(kThreads) void bwd_keys_kernel(BwdSparseArgs A) {
+  static_assert(kSortedKeyEntries == 8, "one entry per lane of a group of eight");
+  constexpr int DL = D / 8;  // features per lane
   const Geom& g = A.g;
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 31, hh = lane >> 5;
   if (blockIdx.x < kLongKeyBlocks) {
     bwd_long_keys_part<T, D>(A, blockIdx.x, kLongKeyBlocks);
     return;
@@ -416,8 +419,9 @@ __global__ __launch_bounds__(kThreads, D == 64 ? 3 : 2) void bwd_keys_kernel(Bwd
     scale_grad_head_part<kThreads>(g, A.dscale, A.dbeta, A.dgamma, blockIdx.x - kLongKeyBlocks, sb_, sg_);
     return;
   }
+  const int tid = threadIdx.x, lane = tid & 63, k = tid & 7, group0 = lane & ~7;
   const long long nkeys = (long long)g.B * g.H * g.Nk;
-  const long long key = (long long)(blockIdx.x - kLongKeyBlocks - A.scale_heads) * kBlockRows + wave * 32 + li;
+  const long long key = (long long)(blockIdx.x - kLongKeyBlocks - A.scale_heads) * kKeysPerBlock + (tid >> 3);
   bool on = key < nkeys;
   const int bh = on ? (int)(key / g.Nk) : 0;
   const int j = on ? (int)(key % g.Nk) : 0;
@@ -430,53 +434,48 @@ __global__ __launch_bounds__(kThreads, D == 64 ? 3 : 2) void bwd_keys_kernel(Bwd
     n = 0;
   }
   const long long base = (long long)bh * g.Nq * 2 * kBwdCap + (on ? A.koffs[key] : 0);
-  const long long q_base = (long long)b * g.q_sb + (long long)h * g.q_sh;
-  const T* dObh = reinterpret_cast<const T*>(A.dO) + q_base + hh * DH;
-  const T* Qbh = reinterpret_cast<const T*>(A.Q) + q_base + hh * DH;
-  float dv[DH], dk[DH];
+  const long long q_base = (long long)b * g.q_sb + (long long)h * g.q_sh + k * DL;
+  const T* dObh = reinterpret_cast<const T*>(A.dO) + q_base;
+  const T* Qbh = reinterpret_cast<const T*>(A.Q) + q_base;
+  // entry k of the key, then its rank by query row within the group (rows of a key are distinct;
+  // empty slots rank last, among themselves by lane)
+  const int ci = (k < n) ? A.csc_i[base + k] : 0x7fffffff;
+  const float2 cpw = (k < n) ? A.csc_pw[base + k] : make_float2(0.f, 0.f);
+  int rank = 0;
 #pragma unroll
-  for (int t = 0; t < DH; ++t) dv[t] = dk[t] = 0.f;
-  auto add_entry = [&](int i, float2 pw) {
-    i = min(max(i, 0), g.Nq - 1);  // a valid row by construction; never index outside the tensor
-    RawRow<T, DH> rd, rq;  // widened where used: fewer registers per gather in flight
-    rd.load(dObh + (long long)i * g.q_sn);
-    rq.load(Qbh + (long long)i * g.q_sn);
-#pragma unroll
-    for (int u = 0; u < DH; ++u) {
-      dv[u] = fmaf(pw.x, rd.get(u), dv[u]);
-      dk[u] = fmaf(pw.y, rq.get(u), dk[u]);
-    }
-  };
-  // the first kSortedKeyEntries entries are held in registers
-  int ci[kSortedKeyEntries];
-  float2 cpw[kSortedKeyEntries];
-#pragma unroll
-  for (int e = 0; e < kSortedKeyEntries; ++e) {
-    ci[e] = (e < n) ? A.csc_i[base + e] : 0x7fffffff;
-    cpw[e] = (e < n) ? A.csc_pw[base + e] : make_float2(0.f, 0.f);
+  for (int m = 0; m < 8; ++m) {
+    const int cm = __shfl(ci, group0 + m);
+    rank += (cm < ci || (cm == ci && m < k)) ? 1 : 0;
   }
-  {
-    int last = -1;
+  // lane t of the group then holds the entry with the t-th smallest row
+  const int dst = (group0 + rank) << 2;
+  const int si = __builtin_amdgcn_ds_permute(dst, ci);
+  const float sp = __int_as_float(__builtin_amdgcn_ds_permute(dst, __float_as_int(cpw.x)));
+  const float sw = __int_as_float(__builtin_amdgcn_ds_permute(dst, __float_as_int(cpw.y)));
+  float dv[DL], dk[DL];
 #pragma unroll
-    for (int t = 0; t < kSortedKeyEntries; ++t) {
-      if (__ballot(t < n) == 0ull) break;
-      // the smallest row above the last one taken (rows of a key are distinct)
-      int i = 0x7fffffff;
-      float2 pw = make_float2(0.f, 0.f);
+  for (int t = 0; t < DL; ++t) dv[t] = dk[t] = 0.f;
 #pragma unroll
-      for (int e = 0; e < kSortedKeyEntries; ++e) {
-        bool better = ci[e] > last && ci[e] < i;
-        i = better ? ci[e] : i;
-        pw = better ? cpw[e] : pw;
+  for (int t = 0; t < 8; ++t) {
+    if (__ballot(t < n) == 0ull) break;
+    int i = __shfl(si, group0 + t);
+    const float p = __shfl(sp, group0 + t), w = __shfl(sw, group0 + t);
+    if (t < n) {
+      i = min(max(i, 0), g.Nq - 1);  // a valid row by construction; never index outside the tensor
+      RawRow<T, DL> rd, rq;
+      rd.load(dObh + (long long)i * g.q_sn);
+      rq.load(Qbh + (long long)i * g.q_sn);
+#pragma unroll
+      for (int u = 0; u < DL; ++u) {
+        dv[u] = fmaf(p, rd.get(u), dv[u]);
+        dk[u] = fmaf(w, rq.get(u), dk[u]);
       }
-      last = i;
-      if (t < n) add_entry(i, pw);
     }
   }
   if (on) {
-    const long long o = (long long)b * g.kv_sb + (long long)h * g.kv_sh + (long long)j * g.kv_sn + hh * DH;
-    store_row<T>(reinterpret_cast<T*>(A.dV) + o, DH, dv);
-    store_row<T>(reinterpret_cast<T*>(A.dK) + o, DH, dk);
+    const long long o = (long long)b * g.kv_sb + (long long)h * g.kv_sh + (long long)j * g.kv_sn + k * DL;
+    store_row<T>(reinterpret_cast<T*>(A.dV) + o, DL, dv);
+    store_row<T>(reinterpret_cast<T*>(A.dK) + o, DL, dk);
   }
 }
 

@@ -509,7 +509,7 @@ int run_bwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
     if (lists) {
       long long keys = (long long)B * H * p->Nk;
       hipLaunchKernelGGL((bwd_keys_kernel<T, D>),
-                         dim3((unsigned)(kLongKeyBlocks + sa.scale_heads + (keys + kBlockRows - 1) / kBlockRows)),
+                         dim3((unsigned)(kLongKeyBlocks + sa.scale_heads + (keys + kKeysPerBlock - 1) / kKeysPerBlock)),
                          dim3(kThreads), 0, st, sa);
       ok = ok && launch_ok();
     }
