@@ -147,157 +147,164 @@ __global__ __launch_bounds__(kThreads) void bwd_prepare_kernel(BwdSparseArgs A) 
   if (blockIdx.x == 0 && threadIdx.x == 0) A.head_flag[g.B * g.H + kLongCountOffset] = 0;
 }
 
-// Everything row-wise from the lists.  Eight lanes per row, each lane an eighth of the features: a
-// gathered K or V row is one fully used cache line per load instruction and row.  The row's two half
-// lists are spread over the eight lanes (lanes 0-3 take entries t, t+4, ... of half 0, lanes 4-7 of
-// half 1); the entries are then taken in turn, broadcast inside the group of eight.
-//
-// One gather pass: dP = <dO, v_j> and, because dQ and dscale are linear in mu,
-//   dQ_i = c (sum_j g dP k_j - mu sum_j g k_j),   dscale_i = sum_j g dP d_j - mu sum_j g d_j,
-// the K rows are gathered in the same pass as the V rows: one memory round trip for both.
+// Everything row-wise from the lists: one lane pair per row, each lane half of the features.
 // SRC_CAP: capacity (slot count) of the lists that are read.
-constexpr int kRowsPerBlock = kThreads / 8;  // 32
-constexpr int kRowRounds = kBwdCap / 4;      // entries per lane: 4 lanes share a half list
-
 template <typename T, int D, int AM, int SRC_CAP>
-__global__ __launch_bounds__(kThreads) void bwd_rows_kernel(BwdSparseArgs A) {
-  constexpr int DL = D / 8;  // features per lane
+__global__ __launch_bounds__(kThreads, D == 64 ? 2 : 1) void bwd_rows_kernel(BwdSparseArgs A) {
   const Geom& g = A.g;
-  const int tid = threadIdx.x, lane = tid & 63, k = tid & 7, group0 = lane & ~7;
-  const int h2 = k >> 2, t4 = k & 3;  // half list and first entry this lane takes
-  const long long rows = (long long)g.B * g.H * g.Nq;
-  const long long row = (long long)blockIdx.x * kRowsPerBlock + (tid >> 3);
-  const bool valid = row < rows;
-  const long long row_idx = valid ? row : 0;
-  const int bh = (int)(row_idx / g.Nq), i = (int)(row_idx % g.Nq);
-  const int b = bh / g.H, h = bh % g.H;
+  RowLane rl;
+  rl.init(g, A.nqb);
+  constexpr int DH = D / 2;
   const float r = 1.0f / (g.alpha - 1.0f);
-  const int lim = valid ? row_limit(g, i) : 0;
-  const float scale = valid ? row_scale(g, b, h, i, lim, nullptr, nullptr, nullptr) : 0.f;
+  const long long row_idx = (long long)rl.bh * g.Nq + (rl.valid ? rl.i : 0);
+  const int lim = rl.valid ? row_limit(g, rl.i) : 0;
+  const bool live = rl.valid && lim > 0;
+  const float scale = rl.valid ? row_scale(g, rl.b, rl.h, rl.i, lim, nullptr, nullptr, nullptr) : 0.f;
   const float inv_sqrt_d = 1.0f / sqrtf((float)D);
   const float c = scale * inv_sqrt_d;
   const float a = (g.alpha - 1.0f) * fabsf(c);  // same arithmetic as the sweep that made the lists
   const float sgn = (c < 0.f) ? -1.f : 1.f;
-  // every load that does not depend on another is issued before the first wait
-  const int head_dense = A.head_flag[bh];
+  // every load that does not depend on another is issued before the first wait (the head's flags included)
+  const int head_dense = A.head_flag[rl.bh];
   const float tau_raw = A.tau[row_idx];
-  const int cnt_raw = A.lcnt[row_idx * 2 + h2];
-  const bool live = valid && lim > 0 && head_dense == 0;  // (a head left to the tiled kernels: nothing to do here)
+  const int cnt_raw = A.lcnt[row_idx * 2 + rl.hh];
   const float tau = live ? tau_raw : 0.f;
   const int cnt = live ? min(cnt_raw & kListCountMask, kBwdCap) : 0;
-  const bool in_ws = SRC_CAP != kBwdCap && live && (cnt_raw & kListInWorkspace) != 0;  // entries in the row's own list
-  const int qb = i / kBlockRows, lwave = (i % kBlockRows) >> 5, llane = h2 * 32 + (i & 31);
-  const uint2* srclist = A.src_list + list_entry<SRC_CAP>(bh, A.nqb, qb, lwave, llane);
-  const uint2* rdlist = in_ws ? A.jlist + list_entry<kBwdCap>(bh, A.nqb, qb, lwave, llane) : srclist;
-  const long long q_off = (long long)b * g.q_sb + (long long)h * g.q_sh + (long long)i * g.q_sn + k * DL;
-  const long long kv_base = (long long)b * g.kv_sb + (long long)h * g.kv_sh + k * DL;
+  const bool in_ws = SRC_CAP != kBwdCap && live && (cnt_raw & kListInWorkspace) != 0;  // entries in this lane's own list
+  const long long q_base = (long long)rl.b * g.q_sb + (long long)rl.h * g.q_sh;
+  const long long kv_base = (long long)rl.b * g.kv_sb + (long long)rl.h * g.kv_sh;
+  const long long list0 = list_entry<kBwdCap>(rl.bh, A.nqb, rl.qb, threadIdx.x >> 6, threadIdx.x & 63);
+  const uint2* mylist = A.jlist + list0;
+  const uint2* srclist = A.src_list + list_entry<SRC_CAP>(rl.bh, A.nqb, rl.qb, threadIdx.x >> 6, threadIdx.x & 63);
   const T* Kbh = reinterpret_cast<const T*>(A.K) + kv_base;
   const T* Vbh = reinterpret_cast<const T*>(A.V) + kv_base;
-  // the first entry is requested before the list length is known (the slot exists whatever it holds)
-  uint2 first = srclist[t4 * kListStride];
-  float dov[DL];
-  {
-    RawRow<T, DL> w;
-    if (valid) w.load(reinterpret_cast<const T*>(A.dO) + q_off);
-#pragma unroll
-    for (int u = 0; u < DL; ++u) dov[u] = valid ? w.get(u) : 0.f;
-  }
-  if (SRC_CAP != kBwdCap && __ballot(in_ws) != 0ull) first = rdlist[t4 * kListStride];
 
-  float Z = 0.f, N = 0.f, sd1 = 0.f, sd0 = 0.f;  // the same in all eight lanes
-  float qa[DL], qb_[DL];                          // this lane's part of sum g dP k and of sum g k
+  // the row's dO, this lane's half of the features, widened to fp32
+  float dov[DH];
+  if (rl.valid) {
+    load_row_f32<T>(reinterpret_cast<const T*>(A.dO) + q_base + (long long)rl.i * g.q_sn + rl.hh * DH, DH, dov);
+  } else {
 #pragma unroll
-  for (int u = 0; u < DL; ++u) qa[u] = qb_[u] = 0.f;
-  // this lane's own entries: raw score, dP, place in the key-major arrays (-1: not part of the support)
-  float dvv[kRowRounds], dpv[kRowRounds];
-  int slotv[kRowRounds];
+    for (int t = 0; t < DH; ++t) dov[t] = 0.f;
+  }
   unsigned n_entries = 0;
+  // the first entries are requested before the list length is known (the slots exist whatever they hold)
+  constexpr int kEarly = 4;
+  uint2 early[kEarly];
 #pragma unroll
-  for (int rd = 0; rd < kRowRounds; ++rd) {
-    dvv[rd] = -kInf;
-    dpv[rd] = 0.f;
-    slotv[rd] = -1;
+  for (int e = 0; e < kEarly; ++e) early[e] = srclist[e * kListStride];
+  const uint2* rdlist = in_ws ? mylist : srclist;
+  if (SRC_CAP != kBwdCap && __ballot(in_ws) != 0ull) {
+#pragma unroll
+    for (int e = 0; e < kEarly; ++e) early[e] = rdlist[e * kListStride];
   }
+  if (head_dense != 0) return;  // the tiled kernels own this head
+
+  auto finish = [&](auto ne_tag) {
+    constexpr int NE = decltype(ne_tag)::value;
+    unsigned jv[NE];
+    float dv[NE];  // raw dot products (sign-folded), -inf for empty slots
 #pragma unroll
-  for (int rd = 0; rd < kRowRounds; ++rd) {
-    const int e = t4 + 4 * rd;
-    if (__ballot(e < cnt) == 0ull) break;
-    uint2 en = make_uint2(0u, 0u);
-    if (rd == 0)
-      en = first;
-    else if (e < cnt)
-      en = rdlist[e * kListStride];
-    const bool used = e < cnt && en.x < (unsigned)g.Nk;  // (a key index is always below Nk; never index outside)
-    const unsigned jmine = used ? en.x : 0u;
-    const float dmine = used ? __uint_as_float(en.y) : -kInf;
-    dvv[rd] = dmine;
+    for (int e = 0; e < NE; ++e) {
+      uint2 en = make_uint2(0u, 0u);
+      if (e < kEarly)
+        en = early[e];
+      else if (e < cnt)
+        en = rdlist[e * kListStride];
+      jv[e] = (e < cnt) ? en.x : 0u;
+      dv[e] = (e < cnt) ? __uint_as_float(en.y) : -kInf;
+    }
+    // One gather pass over the entries of the row (both halves): dP = <dO, v_j> and, because dQ and dscale
+    // are linear in mu,
+    //   dQ_i = c (sum_j g dP k_j - mu sum_j g k_j),   dscale_i = sum_j g dP d_j - mu sum_j g d_j,
+    // the K rows are gathered in the same pass as the V rows: one memory round trip for both.
+    float dpv[NE];  // dP of the lane's own entries
+    float Z = 0.f, N = 0.f, sd1 = 0.f, sd0 = 0.f;
+    float qa[DH], qb[DH];  // this lane's half of sum g dP k and of sum g k
 #pragma unroll
-    for (int m = 0; m < 8; ++m) {
-      // the entry of lane m of the group, looked at by all eight lanes
-      const unsigned j = (unsigned)__shfl((int)jmine, group0 + m);
-      const float d = __shfl(dmine, group0 + m);
-      const float x = (d > -kInf) ? fmaxf(fmaf(d, a, -tau), 0.f) : 0.f;
-      if (__ballot(x > 0.f) == 0ull) continue;
-      float part = 0.f;
-      RawRow<T, DL> kk;
-      if (x > 0.f) {
-        RawRow<T, DL> vv;
-        vv.load(Vbh + (long long)j * g.kv_sn);
-        kk.load(Kbh + (long long)j * g.kv_sn);
-        if (k == m) {  // the entry's owner: its place in the key's segment
-          const long long kidx = (long long)bh * g.Nk + j;
-          slotv[rd] = A.koffs[kidx] + atomicAdd(&A.kcursor[kidx], 1);
-          ++n_entries;
+    for (int t = 0; t < DH; ++t) qa[t] = qb[t] = 0.f;
+    int slotv[NE];  // place in the key-major arrays of the lane's own entries; -1: not part of the support
+#pragma unroll
+    for (int e = 0; e < NE; ++e) {
+      slotv[e] = -1;
+      dpv[e] = 0.f;
+    }
+#pragma unroll
+    for (int e = 0; e < NE; ++e) {
+      unsigned pj = (unsigned)__shfl_xor((int)jv[e], 32);
+      float pd = __shfl_xor(dv[e], 32);
+#pragma unroll
+      for (int src = 0; src < 2; ++src) {
+        // both lanes of the pair look at the same entry: entry e of the lane whose half index is src
+        unsigned j = (rl.hh == src) ? jv[e] : pj;
+        float d = (rl.hh == src) ? dv[e] : pd;
+        float x = (d > -kInf) ? fmaxf(fmaf(d, a, -tau), 0.f) : 0.f;
+        if (__ballot(x > 0.f) == 0ull) continue;
+        float part = 0.f;
+        RawRow<T, DH> kk;
+        if (x > 0.f) {
+          RawRow<T, DH> vv;
+          vv.load(Vbh + (long long)j * g.kv_sn + rl.hh * DH);
+          kk.load(Kbh + (long long)j * g.kv_sn + rl.hh * DH);
+          // the entry's owner takes its arrival number among the key's entries: its place in the key's segment
+          if (rl.hh == src) {
+            const long long kidx = (long long)rl.bh * g.Nk + j;
+            slotv[e] = A.koffs[kidx] + atomicAdd(&A.kcursor[kidx], 1);
+            ++n_entries;
+          }
+#pragma unroll
+          for (int t = 0; t < DH; ++t) part = fmaf(dov[t], vv.get(t), part);
         }
+        float dp = part + __shfl_xor(part, 32);
+        if (x > 0.f) {
+          float gg = pow_rm1<AM>(x, r);
+          float gdp = gg * dp;
+          Z += gg;
+          N += gdp;
+          sd1 = fmaf(gdp, d, sd1);
+          sd0 = fmaf(gg, d, sd0);
 #pragma unroll
-        for (int u = 0; u < DL; ++u) part = fmaf(dov[u], vv.get(u), part);
-      }
-      // sum over the eight lanes of the group
-      part += __shfl_xor(part, 1);
-      part += __shfl_xor(part, 2);
-      const float dp = part + __shfl_xor(part, 4);
-      if (x > 0.f) {
-        const float gg = pow_rm1<AM>(x, r);
-        const float gdp = gg * dp;
-        Z += gg;
-        N += gdp;
-        sd1 = fmaf(gdp, d, sd1);
-        sd0 = fmaf(gg, d, sd0);
-#pragma unroll
-        for (int u = 0; u < DL; ++u) {
-          const float kt = kk.get(u);
-          qa[u] = fmaf(gdp, kt, qa[u]);
-          qb_[u] = fmaf(gg, kt, qb_[u]);
+          for (int t = 0; t < DH; ++t) {
+            const float kt = kk.get(t);
+            qa[t] = fmaf(gdp, kt, qa[t]);
+            qb[t] = fmaf(gg, kt, qb[t]);
+          }
+          if (rl.hh == src) dpv[e] = dp;
         }
-        if (k == m) dpv[rd] = dp;
       }
     }
-  }
-  const float mu = (Z > 0.f) ? N / Z : 0.f;
-  // the per-entry records (query, p, c dS) go straight to their place in the key-major arrays
-  // (a listed key whose probability rounds to zero here has no place and is dropped)
-  const long long cap = (long long)g.Nq * 2 * kBwdCap;  // entries a head can hold
+    const float mu = (Z > 0.f) ? N / Z : 0.f;
+    float dq[DH];
 #pragma unroll
-  for (int rd = 0; rd < kRowRounds; ++rd) {
-    if (slotv[rd] >= 0 && slotv[rd] < cap) {  // (below cap by construction; never index outside the head)
-      const float x = fmaxf(fmaf(dvv[rd], a, -tau), 0.f);
-      const float ds = pow_rm1<AM>(x, r) * (dpv[rd] - mu);
-      A.csc_i[bh * cap + slotv[rd]] = i;
-      A.csc_pw[bh * cap + slotv[rd]] = make_float2(pow_r<AM>(x, r), c * ds);
+    for (int t = 0; t < DH; ++t) dq[t] = c * fmaf(-mu, qb[t], qa[t]);
+    const float dsc = fmaf(-mu, sd0, sd1);
+    // the per-entry records (query, p, c dS) go straight to their place in the key-major arrays
+    // (a listed key whose probability rounds to zero here has no place and is dropped)
+    const long long cap = (long long)g.Nq * 2 * kBwdCap;  // entries a head can hold
+#pragma unroll
+    for (int e = 0; e < NE; ++e) {
+      if (slotv[e] >= 0 && slotv[e] < cap) {  // (below cap by construction; never index outside the head)
+        float x = fmaxf(fmaf(dv[e], a, -tau), 0.f);
+        float ds = pow_rm1<AM>(x, r) * (dpv[e] - mu);
+        A.csc_i[rl.bh * cap + slotv[e]] = rl.i;
+        A.csc_pw[rl.bh * cap + slotv[e]] = make_float2(pow_r<AM>(x, r), c * ds);
+      }
     }
-  }
-  if (valid && head_dense == 0) {
-    float dq[DL];
-#pragma unroll
-    for (int u = 0; u < DL; ++u) dq[u] = c * fmaf(-mu, qb_[u], qa[u]);
-    store_row<T>(reinterpret_cast<T*>(A.dQ) + q_off, DL, dq);
-    // the scores were formed with q negated when scale_i < 0: undo the sign for z_ij
-    if (k == 0) A.dscale[row_idx] = sgn * fmaf(-mu, sd0, sd1) * inv_sqrt_d;
-  }
+    if (rl.valid) {
+      store_row<T>(reinterpret_cast<T*>(A.dQ) + q_base + (long long)rl.i * g.q_sn + rl.hh * DH, DH, dq);
+      // the scores were formed with q negated when scale_i < 0: undo the sign for z_ij
+      if (rl.hh == 0) A.dscale[row_idx] = sgn * dsc * inv_sqrt_d;
+    }
+  };
+  if (__ballot(cnt > 4) == 0ull)
+    finish(std::integral_constant<int, 4>());
+  else
+    finish(std::integral_constant<int, kBwdCap>());
+
   if (A.stats) {
     unsigned ent = n_entries;
     for (int s = 32; s > 0; s >>= 1) ent += __shfl_xor((int)ent, s);
-    if (lane == 0 && ent) atomicAdd(&A.stats[ENTMAX_STAT_BWD_SUPPORT], (unsigned long long)ent);
+    if ((threadIdx.x & 63) == 0) atomicAdd(&A.stats[ENTMAX_STAT_BWD_SUPPORT], (unsigned long long)ent);
   }
 }
 

@@ -368,9 +368,7 @@ bool launch_bwd_kernels(const BwdArgs& a, const Layout& L, int B, int H, hipStre
 
 template <typename T, int D, int AM>
 bool launch_bwd_rows(const BwdSparseArgs& a, int nblocks, hipStream_t st, void* const* ev, bool from_saved) {
-  const dim3 row_grid((unsigned)(a.g.B * a.g.H * a.nqb));  // one workgroup per query block (prepare kernel)
-  const long long nrows = (long long)a.g.B * a.g.H * a.g.Nq;
-  const dim3 rows8_grid((unsigned)((nrows + kRowsPerBlock - 1) / kRowsPerBlock));  // eight lanes per row
+  const dim3 row_grid((unsigned)(a.g.B * a.g.H * a.nqb));
   if (from_saved) {
     hipLaunchKernelGGL(bwd_prepare_kernel<D>, row_grid, dim3(kThreads), 0, st, a);
   } else {
@@ -392,9 +390,9 @@ bool launch_bwd_rows(const BwdSparseArgs& a, int nblocks, hipStream_t st, void* 
     if (!launch_ok()) return false;
   }
   if (from_saved)
-    hipLaunchKernelGGL((bwd_rows_kernel<T, D, AM, kCandCap>), rows8_grid, dim3(kThreads), 0, st, a);
+    hipLaunchKernelGGL((bwd_rows_kernel<T, D, AM, kCandCap>), row_grid, dim3(kThreads), 0, st, a);
   else
-    hipLaunchKernelGGL((bwd_rows_kernel<T, D, AM, kBwdCap>), rows8_grid, dim3(kThreads), 0, st, a);
+    hipLaunchKernelGGL((bwd_rows_kernel<T, D, AM, kBwdCap>), row_grid, dim3(kThreads), 0, st, a);
   return launch_ok();
 }
 
