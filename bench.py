@@ -25,7 +25,7 @@ PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak
 # HBM bytes per launch at the c3 workload, from rocprofv3 FETCH_SIZE + WRITE_SIZE runs of this same command scaled by
 # what the counters read for a conversion kernel of known size (profiles/pmc_c3_fwd_bwd.md).  Other workloads: null.
 MEASURED_HBM_BYTES_C3 = {
-    "fwd_lists": 141.4e6, "fwd_finish": 78.5e6, "bwd_rows": 177.3e6, "bwd_keys": 155.6e6,
+    "fwd_lists": 141.1e6, "fwd_finish": 78.5e6, "bwd_rows": 177.2e6, "bwd_keys": 156.3e6,
 }
 
 

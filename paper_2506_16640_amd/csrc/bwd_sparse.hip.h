@@ -15,7 +15,7 @@
 //                      gathering the few K and V rows (one lane pair per row).
 //                      Each entry's (query, p, c dS) goes straight into its key's segment, at the
 //                      place a returning atomic on the key's cursor hands out;
-//   bwd_keys_kernel    lane pair per key (one wave per key for long segments): dV_j and dK_j as
+//   bwd_keys_kernel    eight lanes per key (one wave per key for long segments): dV_j and dK_j as
 //                      sums over the key's entries, in query order.
 // A head in which some half row holds more than kBwdCap support entries is
 // flagged and left, as a whole, to the tiled kernels of bwd.hip.h.
