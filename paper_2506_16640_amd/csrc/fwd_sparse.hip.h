@@ -147,8 +147,9 @@ __device__ __forceinline__ bool collect_sweep(const C& q, const Geom& g, const v
               ++ncell;
             }
           }
-          if (__ballot(ncell > CAP) != 0ull && q.lane == 0) ovf[kt & 1] = 1;
         }
+        // once per tile: a strip that overflowed (its last cell was overwritten: the lists are discarded)
+        if (__ballot(ncell > CAP) != 0ull && q.lane == 0) ovf[kt & 1] = 1;
       },
       // flags of the previous tile's parity were final before the barrier that ended that tile
       [&](int kt) { return kt > 0 && ovf[(kt - 1) & 1] != 0; });
