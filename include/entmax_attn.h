@@ -61,7 +61,8 @@ typedef struct {
   int32_t logn_mode;       /* n in (ln n)^gamma: 0 = Nk for every row, 1 = number of keys visible to the row.
                               A row with n <= 1 uses scale = delta and contributes no beta/gamma gradient. */
   int32_t path;            /* forward path: 0 = automatic (candidate-list kernel first; workgroups that meet a row
-                              with too many candidates fall back to the tiled kernel), 1 = tiled kernel only */
+                              with too many candidates fall back to the tiled kernel; with Nq <= 8, the decoding
+                              shape, kernels that split the keys instead), 1 = tiled kernel only */
   float alpha;             /* 1 < alpha <= 2; 1.5, 2.0 and 1.25 run on integer-power fast paths */
   float delta;             /* ASEntmax delta (1.0 in the paper's experiments) */
   int64_t q_stride_b, q_stride_h, q_stride_n;    /* strides of Q,O,dO,dQ in elements; all 0 = contiguous */
@@ -102,8 +103,10 @@ enum {
  * before the first kernel and entry k after the last kernel of phase k-1. */
 enum {
   ENTMAX_FWD_PHASE_PREPARE = 0,   /* with `saved`: zero fill of its per-key counters (else empty) */
-  ENTMAX_FWD_PHASE_LISTS = 1,     /* candidate-list kernel: two Q K^T sweeps (row maximum, candidates) */
-  ENTMAX_FWD_PHASE_FINISH = 2,    /* threshold and output from the candidate lists */
+  ENTMAX_FWD_PHASE_LISTS = 1,     /* candidate-list kernel: two Q K^T sweeps (row maximum, candidates);
+                                     decoding shape: the score rows, one pass over K */
+  ENTMAX_FWD_PHASE_FINISH = 2,    /* threshold and output from the candidate lists (decoding shape: from the
+                                     score rows) */
   ENTMAX_FWD_PHASE_TRANSPOSE = 3, /* V^T copy for the heads that need the tiled kernel */
   ENTMAX_FWD_PHASE_TILED = 4,     /* tiled kernel on the workgroups the list kernel left over */
   ENTMAX_FWD_NUM_PHASES = 5
@@ -139,6 +142,11 @@ enum {
  * candidates above a lower bound of tau are finished from a short per-row list
  * after two sweeps; denser rows run the tile-wise iteration and P.V on the
  * matrix cores with zero tiles skipped.
+ * Decoding shape (path 0, Nq <= 8: a few query rows against a long key sequence, the regime of the
+ * long-context evaluation of Sec. 4): the keys, not the queries, are split over the chip; K is
+ * read once, the rows' scores (Nq x Nk fp32 per head) go to the workspace, and each row's
+ * threshold and output come from its score row.  `saved` then only tells the backward to rebuild
+ * the supports itself.
  */
 int entmax_attn_fwd(const entmax_attn_params* p, const void* Q, const void* K, const void* V, const float* beta,
                     const float* gamma, void* O, float* tau, void* saved, uint64_t* stats, void* workspace,

@@ -1,0 +1,211 @@
+// Forward for a handful of query rows against a long key sequence (decoding:
+// Nq <= kDecodeRows).  The tiled and list kernels give a workgroup 128 query
+// rows and one head's whole key sequence; with a few rows that is one
+// workgroup per head streaming megabytes of K.  Here the keys are split
+// instead, and the path is bound by reading K once from HBM:
+//   decode_scores_kernel  grid (key chunks, heads): z_ij = (alpha-1) scale_i <q_i,k_j>/sqrt(d)
+//                         (Sec. 2.1 scores, eq. (asentmax) scale) for the visible keys, fp32, to
+//                         the workspace;
+//   decode_solve_kernel   one workgroup per query row: row maximum, the keys that can be in the
+//                         support (z > max - 1: everything else is zero already at the lowest
+//                         possible threshold), the threshold of eq. (entmax) by Newton steps from
+//                         that lowest threshold (sum_j [z_j - tau]_+^r - 1 is convex and decreasing
+//                         in tau, so the steps rise to the root and never pass it), and
+//                         O_i = sum_j p_ij v_j over the support.
+#pragma once
+#include "common.hip.h"
+#include "fwd_sparse.hip.h"
+
+namespace entmax {
+
+constexpr int kDecodeRows = 8;          // most query rows the decode kernels take
+constexpr int kDecodeChunk = 512;       // keys per workgroup of decode_scores_kernel
+constexpr int kDecodeSolveThreads = 1024;
+constexpr int kDecodeListCap = 4096;    // support candidates kept in LDS; longer ones are re-read from the score row
+
+struct DecodeArgs {
+  Geom g;
+  const void* Q;
+  const void* K;
+  const void* V;
+  void* O;
+  float* tau;     // [B*H*Nq]
+  float* scores;  // [B*H*Nq][Nk] workspace, entries j < row_limit(i) written
+};
+
+// Eight lanes share a key row (each a contiguous eighth of its features), so a wave's load
+// instruction covers eight whole rows; a thread keeps four rows in flight.
+template <typename T, int D>
+__global__ __launch_bounds__(kThreads) void decode_scores_kernel(DecodeArgs A) {
+  constexpr int kSlice = D / 8;
+  __shared__ __align__(16) float qs[kDecodeRows * D];
+  __shared__ float coef[kDecodeRows];
+  __shared__ int limit[kDecodeRows];
+  const Geom& g = A.g;
+  const int tid = threadIdx.x, bh = blockIdx.y, b = bh / g.H, h = bh % g.H;
+  const int j0 = blockIdx.x * kDecodeChunk;
+  const T* Qh = reinterpret_cast<const T*>(A.Q) + (long long)b * g.q_sb + (long long)h * g.q_sh;
+  const T* Kh = reinterpret_cast<const T*>(A.K) + (long long)b * g.kv_sb + (long long)h * g.kv_sh;
+  for (int e = tid; e < g.Nq * D; e += kThreads) {
+    const int i = e / D, c = e % D;
+    if constexpr (sizeof(T) == 2)
+      qs[e] = __uint_as_float((uint32_t)reinterpret_cast<const uint16_t*>(Qh)[(long long)i * g.q_sn + c] << 16);
+    else
+      qs[e] = reinterpret_cast<const float*>(Qh)[(long long)i * g.q_sn + c];
+  }
+  if (tid < g.Nq) {
+    const int lim = row_limit(g, tid);
+    limit[tid] = lim;
+    coef[tid] = (g.alpha - 1.0f) * row_scale(g, b, h, tid, lim, nullptr, nullptr, nullptr) * (1.0f / sqrtf((float)D));
+  }
+  __syncthreads();
+  const int grp = tid >> 3, sub = tid & 7;
+  for (int base = j0; base < min(j0 + kDecodeChunk, g.Nk); base += 128) {
+    RawRow<T, kSlice> kk[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int j = min(base + u * 32 + grp, g.Nk - 1);  // rows past the end repeat the last one and are not written
+      kk[u].load(Kh + (long long)j * g.kv_sn + sub * kSlice);
+    }
+    for (int i = 0; i < g.Nq; ++i) {
+      float qv[kSlice];
+#pragma unroll
+      for (int t = 0; t < kSlice; t += 4) {
+        const f32x4_t w = *reinterpret_cast<const f32x4_t*>(&qs[i * D + sub * kSlice + t]);
+        qv[t] = w[0];
+        qv[t + 1] = w[1];
+        qv[t + 2] = w[2];
+        qv[t + 3] = w[3];
+      }
+      const float c = coef[i];
+      const int lim = limit[i];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        float dot = 0.f;
+#pragma unroll
+        for (int t = 0; t < kSlice; ++t) dot = fmaf(kk[u].get(t), qv[t], dot);
+        dot += __shfl_xor(dot, 1);
+        dot += __shfl_xor(dot, 2);
+        dot += __shfl_xor(dot, 4);
+        const int j = base + u * 32 + grp;
+        if (sub == u && j < lim) A.scores[((long long)bh * g.Nq + i) * g.Nk + j] = dot * c;
+      }
+    }
+  }
+}
+
+// Sum of two values over the workgroup; every thread gets the totals.  `buf` holds 2 * 2 * 16
+// floats: calls alternate between its halves (parity), so one barrier per call is enough.
+__device__ __forceinline__ float2 decode_block_sum(float a, float b, float* buf, int parity) {
+  constexpr int kW = kDecodeSolveThreads / 64;
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    a += __shfl_xor(a, off);
+    b += __shfl_xor(b, off);
+  }
+  float* mine = buf + parity * 2 * kW;
+  if ((threadIdx.x & 63) == 0) {
+    mine[threadIdx.x >> 6] = a;
+    mine[kW + (threadIdx.x >> 6)] = b;
+  }
+  __syncthreads();
+  float sa = 0.f, sb = 0.f;
+#pragma unroll
+  for (int w = 0; w < kW; ++w) {
+    sa += mine[w];
+    sb += mine[kW + w];
+  }
+  return make_float2(sa, sb);
+}
+
+template <typename T, int D, int AM>
+__global__ __launch_bounds__(kDecodeSolveThreads) void decode_solve_kernel(DecodeArgs A) {
+  constexpr int kW = kDecodeSolveThreads / 64;
+  constexpr int kSlots = kDecodeSolveThreads / D;  // threads with the same feature share out the support
+  __shared__ float2 list[kDecodeListCap];          // (key index bits, z)
+  __shared__ float red[2 * 2 * kW];
+  __shared__ float wmax[kW];
+  __shared__ int count;
+  __shared__ float osum[kSlots * D];
+  const Geom& g = A.g;
+  const int tid = threadIdx.x;
+  const int row = blockIdx.x, i = row % g.Nq, bh = row / g.Nq, b = bh / g.H, h = bh % g.H;
+  const int lim = row_limit(g, i);
+  const long long o_idx = (long long)b * g.q_sb + (long long)h * g.q_sh + (long long)i * g.q_sn;
+  if (lim == 0) {  // no visible key: an empty sum
+    if (tid < D) Elem<T>::store(A.O, o_idx + tid, 0.f);
+    if (tid == 0) A.tau[row] = 0.f;
+    return;
+  }
+  const float* z = A.scores + (long long)row * g.Nk;
+  const float r = 1.0f / (g.alpha - 1.0f);
+  // row maximum
+  float m = -kInf;
+  for (int j = tid; j < lim; j += kDecodeSolveThreads) m = fmaxf(m, z[j]);
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
+  if ((tid & 63) == 0) wmax[tid >> 6] = m;
+  if (tid == 0) count = 0;
+  __syncthreads();
+#pragma unroll
+  for (int w = 0; w < kW; ++w) m = fmaxf(m, wmax[w]);
+  // keys with a non-zero term at the lowest threshold tau_lo = max - 1 (there the maximum's own term is 1,
+  // so the sum is >= 1 and the root is >= tau_lo)
+  const float tau_lo = m - 1.0f;
+  for (int j = tid; j < lim; j += kDecodeSolveThreads) {
+    const float zj = z[j];
+    if (zj > tau_lo) {
+      const int pos = atomicAdd(&count, 1);
+      if (pos < kDecodeListCap) list[pos] = make_float2(__int_as_float(j), zj);
+    }
+  }
+  __syncthreads();
+  const int total = count;
+  const bool in_lds = total <= kDecodeListCap;
+  const int n_items = in_lds ? total : lim;
+  float tau = tau_lo;
+  for (int it = 0; it < 96; ++it) {
+    float F = 0.f, G = 0.f;
+    for (int e = tid; e < n_items; e += kDecodeSolveThreads) {
+      const float x = (in_lds ? list[e].y : z[e]) - tau;
+      if (x > 0.f) {
+        F += pow_r<AM>(x, r);
+        G += pow_rm1<AM>(x, r);
+      }
+    }
+    const float2 s = decode_block_sum(F, G, red, it & 1);
+    if (!(s.y > 0.f)) break;
+    const float step = (s.x - 1.0f) / (r * s.y);  // Newton: f = F - 1, f' = -r G; G > 0 while tau < max
+    if (!(step > 0.f)) break;
+    tau += step;
+    if (step <= 1e-6f * fmaxf(1.0f, fabsf(tau))) break;  // what is left is a small multiple of the last step
+  }
+  if (tid == 0) A.tau[row] = tau;
+  // O_i = sum_j p_ij v_j
+  const T* Vh = reinterpret_cast<const T*>(A.V) + (long long)b * g.kv_sb + (long long)h * g.kv_sh;
+  const int slot = tid / D, c = tid % D;
+  float acc = 0.f;
+  for (int e = slot; e < n_items; e += kSlots) {
+    const float2 en = in_lds ? list[e] : make_float2(__int_as_float(e), z[e]);
+    const float x = en.y - tau;
+    if (x > 0.f) {
+      const long long vi = (long long)__float_as_int(en.x) * g.kv_sn + c;
+      float v;
+      if constexpr (sizeof(T) == 2)
+        v = __uint_as_float((uint32_t)reinterpret_cast<const uint16_t*>(Vh)[vi] << 16);
+      else
+        v = reinterpret_cast<const float*>(Vh)[vi];
+      acc = fmaf(pow_r<AM>(x, r), v, acc);
+    }
+  }
+  osum[slot * D + c] = acc;
+  __syncthreads();
+  if (tid < D) {
+    float o = 0.f;
+#pragma unroll
+    for (int s = 0; s < kSlots; ++s) o += osum[s * D + tid];
+    Elem<T>::store(A.O, o_idx + tid, o);
+  }
+}
+
+}  // namespace entmax

@@ -8,6 +8,7 @@
 
 #include "bwd.hip.h"
 #include "bwd_sparse.hip.h"
+#include "decode.hip.h"
 #include "fwd.hip.h"
 #include "fwd_sparse.hip.h"
 #include "transpose.hip.h"
@@ -100,6 +101,11 @@ Layout make_layout(const entmax_attn_params* p) {
   L.off_fcells = L.off_flags + align_up((bh * (size_t)L.nqb + bh + 1) * sizeof(int));
   const size_t list_groups = bh * (size_t)((L.nqb + 1) / 2);  // workgroups of the list sweeps
   L.total_fwd = L.off_fcells + align_up(list_groups * CellBuf<kCandCap>::kBytesPerWorkgroup);
+  // the decode kernels' score rows take the place of everything above
+  if (p->Nq <= kDecodeRows) {
+    const size_t score_bytes = align_up(bh * (size_t)p->Nq * p->Nk * sizeof(float));
+    if (score_bytes > L.total_fwd) L.total_fwd = score_bytes;
+  }
   size_t o = 0;
   L.off_kt = o;
   o += kt_bytes;
@@ -274,6 +280,23 @@ bool launch_fwd_sparse_am(const FwdSparseArgs& a, int am, int nblocks, hipStream
 }
 
 template <typename T, int D>
+bool launch_decode(const DecodeArgs& a, int am, hipStream_t st, void* const* ev) {
+  const Geom& g = a.g;
+  hipLaunchKernelGGL((decode_scores_kernel<T, D>), dim3((unsigned)ceil_div(g.Nk, kDecodeChunk), (unsigned)(g.B * g.H)),
+                     dim3(kThreads), 0, st, a);
+  if (!launch_ok()) return false;
+  record(ev, ENTMAX_FWD_PHASE_LISTS + 1, st);
+  const dim3 grid((unsigned)(g.B * g.H * g.Nq)), block(kDecodeSolveThreads);
+  switch (am) {
+    case 1: hipLaunchKernelGGL((decode_solve_kernel<T, D, 1>), grid, block, 0, st, a); break;
+    case 2: hipLaunchKernelGGL((decode_solve_kernel<T, D, 2>), grid, block, 0, st, a); break;
+    case 3: hipLaunchKernelGGL((decode_solve_kernel<T, D, 3>), grid, block, 0, st, a); break;
+    default: hipLaunchKernelGGL((decode_solve_kernel<T, D, 0>), grid, block, 0, st, a); break;
+  }
+  return launch_ok();
+}
+
+template <typename T, int D>
 int run_fwd(const entmax_attn_params* p, const Layout& L, const void* Q, const void* K, const void* V,
             const float* beta, const float* gamma, void* O, float* tau, char* saved, uint64_t* stats, char* ws,
             hipStream_t st, void* const* ev) {
@@ -283,6 +306,29 @@ int run_fwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
               zero_words(tau, (size_t)p->B * p->H * p->Nq * 4, st);
     for (int k = 1; k <= ENTMAX_FWD_NUM_PHASES; ++k) record(ev, k, st);
     return ok ? ENTMAX_ATTN_OK : ENTMAX_ATTN_LAUNCH_FAILED;
+  }
+  if (p->path == 0 && p->Nq <= kDecodeRows) {
+    // a few query rows against the whole key sequence: split the keys over the chip
+    if (p->Nq > 0 && p->B * p->H > 0) {
+      // no lists for the backward: every block belongs to its tiled kernels
+      if (saved && !fill_words(saved + L.sv_flags, (size_t)p->B * p->H * L.nqb * sizeof(int), 1u, st))
+        return ENTMAX_ATTN_LAUNCH_FAILED;
+      record(ev, ENTMAX_FWD_PHASE_PREPARE + 1, st);
+      DecodeArgs da;
+      da.g = make_geom(p, L, beta, gamma);
+      da.Q = Q;
+      da.K = K;
+      da.V = V;
+      da.O = O;
+      da.tau = tau;
+      da.scores = reinterpret_cast<float*>(ws);
+      if (!launch_decode<T, D>(da, alpha_mode(p->alpha), st, ev)) return ENTMAX_ATTN_LAUNCH_FAILED;
+    } else {
+      record(ev, ENTMAX_FWD_PHASE_PREPARE + 1, st);
+      record(ev, ENTMAX_FWD_PHASE_LISTS + 1, st);
+    }
+    for (int k = ENTMAX_FWD_PHASE_FINISH; k < ENTMAX_FWD_NUM_PHASES; ++k) record(ev, k + 1, st);
+    return ENTMAX_ATTN_OK;
   }
   void* Vt = ws + L.off_vt;
   // with a `saved` buffer the lists, their lengths and the block flags are written there
