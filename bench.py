@@ -7,7 +7,7 @@ the 120M-class LM attention layer at training length (B=4, H=12, n=4096, d=64,
 bf16, causal, alpha=1.5, per-head ASEntmax scale, 5% planted keys), seeded and
 synthetic, resident in HBM before the timed region.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3] [--no-cpu-baseline] [--no-c4]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3] [--no-cpu-baseline] [--no-c4] [--no-decode]
 """
 import argparse
 import ctypes
@@ -75,6 +75,7 @@ def main():
     ap.add_argument("--workload", default="c3")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-c4", action="store_true", help="skip the n=32768 forward-only measurement")
+    ap.add_argument("--no-decode", action="store_true", help="skip the decode-shape (Nq = 1 and 8, Nk = 32768) measurement")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); --gpus %d is not supported"
@@ -262,6 +263,41 @@ def main():
             "candidates_per_row": sd4["fwd_candidates"] / max(cfg4["B"] * cfg4["H"] * cfg4["n"], 1),
             "tile_stats": {k: v for k, v in sd4.items() if k.startswith("fwd")},
         }
+    if not args.no_decode and args.workload == "c3":
+        # decode shapes: a few new query rows against a 32768-key cache; bound by one read of K from HBM
+        result["decode_nk32768"] = {}
+        for nq in (1, 8):
+            dd = synth.make_inputs(B=4, H=12, n=nq, nk=32768, d=64, dtype="bf16", scale="head", seed=0, want_dO=False)
+            td = {k: torch.from_numpy(dd[k]).to(dev).to(torch.bfloat16) for k in ("Q", "K", "V")}
+            bd, gd = (torch.from_numpy(dd[k]).to(dev) for k in ("beta", "gamma"))
+            kwd = dict(alpha=1.5, beta=bd, gamma=gd, delta=dd["delta"], causal=True)
+            prmd = binding.make_params(td["Q"], td["K"], 1.5, dd["delta"], True, bd, 0)
+            wsd = torch.empty(binding.workspace_bytes(prmd, 0), dtype=torch.uint8, device=dev)
+            outd = torch.empty_like(td["Q"])
+            taud = torch.empty(4, 12, nq, dtype=torch.float32, device=dev)
+            # two copies of K (2 x 201 MB), taken in turn: a step must not find its K in the 256 MB last-level cache
+            kcopies = [td["K"], td["K"].clone()]
+            for _ in range(4):
+                binding.entmax_attn_fwd(td["Q"], kcopies[_ % 2], td["V"], out=outd, tau=taud, workspace=wsd, **kwd)
+            kd = max(5, args.steps)
+            evd = [hev.make(binding.FWD_NUM_PHASES + 1) for _ in range(kd)]
+            torch.cuda.synchronize()
+            ta = time.perf_counter()
+            for k in range(kd):
+                binding.entmax_attn_fwd(td["Q"], kcopies[k % 2], td["V"], out=outd, tau=taud, workspace=wsd,
+                                        phase_events=evd[k], **kwd)
+            torch.cuda.synchronize()
+            tb = time.perf_counter()
+            scores_ms = float(np.mean([hev.elapsed_ms(s[1], s[2]) for s in evd]))
+            solve_ms = float(np.mean([hev.elapsed_ms(s[2], s[3]) for s in evd]))
+            algo_bytes = 4 * 12 * 32768 * (64 * 2 + nq * 4)  # K read once, the score rows written once
+            result["decode_nk32768"]["nq%d" % nq] = {
+                "workload": "B=4 H=12 Nq=%d Nk=32768 d=64 bf16 causal alpha=1.5 ASEntmax scale, fwd" % nq,
+                "steps": kd, "ms": (tb - ta) * 1e3 / kd, "scores_kernel_ms": scores_ms, "solve_kernel_ms": solve_ms,
+                "roofline": {"bound": "hbm", "kernel": "decode_scores", "achieved": algo_bytes / (scores_ms * 1e-3) / 1e9,
+                             "peak": 8000.0, "unit": "GB/s", "frac": algo_bytes / (scores_ms * 1e-3) / 1e9 / 8000.0},
+            }
+            del td, wsd, kcopies
     hev.close()
 
     if not args.no_cpu_baseline:

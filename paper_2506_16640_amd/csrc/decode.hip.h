@@ -19,7 +19,6 @@
 namespace entmax {
 
 constexpr int kDecodeRows = 8;          // most query rows the decode kernels take
-constexpr int kDecodeChunk = 512;       // keys per workgroup of decode_scores_kernel
 constexpr int kDecodeSolveThreads = 1024;
 constexpr int kDecodeListCap = 4096;    // support candidates kept in LDS; longer ones are re-read from the score row
 
@@ -30,7 +29,10 @@ struct DecodeArgs {
   const void* V;
   void* O;
   float* tau;     // [B*H*Nq]
-  float* scores;  // [B*H*Nq][Nk] workspace, entries j < row_limit(i) written
+  float* scores;  // [B*H*Nq][nks] workspace, entries j < row_limit(i) written; nks = Nk rounded up to 4
+  float* cmax;    // [B*H*Nq][nchunks] largest score of each chunk of `chunk` keys (-inf: none visible)
+  int nks, nchunks;
+  int chunk;      // keys per workgroup of decode_scores_kernel, a multiple of 256
 };
 
 // Eight lanes share a key row (each a contiguous eighth of its features), so a wave's load
@@ -41,11 +43,24 @@ __global__ __launch_bounds__(kThreads) void decode_scores_kernel(DecodeArgs A) {
   __shared__ __align__(16) float qs[kDecodeRows * D];
   __shared__ float coef[kDecodeRows];
   __shared__ int limit[kDecodeRows];
+  __shared__ float wave_max[kDecodeRows][kWaves];  // entry [i][w] is wave w's alone
   const Geom& g = A.g;
   const int tid = threadIdx.x, bh = blockIdx.y, b = bh / g.H, h = bh % g.H;
-  const int j0 = blockIdx.x * kDecodeChunk;
+  const int j0 = blockIdx.x * A.chunk;
   const T* Qh = reinterpret_cast<const T*>(A.Q) + (long long)b * g.q_sb + (long long)h * g.q_sh;
   const T* Kh = reinterpret_cast<const T*>(A.K) + (long long)b * g.kv_sb + (long long)h * g.kv_sh;
+  // the first key rows are requested before anything else: their addresses need nothing from the queries
+  const int grp = tid >> 3, sub = tid & 7;
+  const int jend = min(j0 + A.chunk, g.Nk);
+  RawRow<T, kSlice> kk[4], nx[4];
+  auto fetch = [&](RawRow<T, kSlice>* dst, int base) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int j = min(base + u * 32 + grp, g.Nk - 1);  // rows past the end repeat the last one and are not written
+      dst[u].load(Kh + (long long)j * g.kv_sn + sub * kSlice);
+    }
+  };
+  fetch(nx, j0);
   for (int e = tid; e < g.Nq * D; e += kThreads) {
     const int i = e / D, c = e % D;
     if constexpr (sizeof(T) == 2)
@@ -56,17 +71,14 @@ __global__ __launch_bounds__(kThreads) void decode_scores_kernel(DecodeArgs A) {
   if (tid < g.Nq) {
     const int lim = row_limit(g, tid);
     limit[tid] = lim;
+    for (int w = 0; w < kWaves; ++w) wave_max[tid][w] = -kInf;
     coef[tid] = (g.alpha - 1.0f) * row_scale(g, b, h, tid, lim, nullptr, nullptr, nullptr) * (1.0f / sqrtf((float)D));
   }
   __syncthreads();
-  const int grp = tid >> 3, sub = tid & 7;
-  for (int base = j0; base < min(j0 + kDecodeChunk, g.Nk); base += 128) {
-    RawRow<T, kSlice> kk[4];
+  for (int base = j0; base < jend; base += 128) {
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int j = min(base + u * 32 + grp, g.Nk - 1);  // rows past the end repeat the last one and are not written
-      kk[u].load(Kh + (long long)j * g.kv_sn + sub * kSlice);
-    }
+    for (int u = 0; u < 4; ++u) kk[u] = nx[u];
+    if (base + 128 < jend) fetch(nx, base + 128);  // the next rows are on their way during the arithmetic
     for (int i = 0; i < g.Nq; ++i) {
       float qv[kSlice];
 #pragma unroll
@@ -79,6 +91,7 @@ __global__ __launch_bounds__(kThreads) void decode_scores_kernel(DecodeArgs A) {
       }
       const float c = coef[i];
       const int lim = limit[i];
+      float best = -kInf;
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         float dot = 0.f;
@@ -88,9 +101,21 @@ __global__ __launch_bounds__(kThreads) void decode_scores_kernel(DecodeArgs A) {
         dot += __shfl_xor(dot, 2);
         dot += __shfl_xor(dot, 4);
         const int j = base + u * 32 + grp;
-        if (sub == u && j < lim) A.scores[((long long)bh * g.Nq + i) * g.Nk + j] = dot * c;
+        const float zj = dot * c;
+        if (j < lim) best = fmaxf(best, zj);
+        if (sub == u && j < lim) A.scores[((long long)bh * g.Nq + i) * A.nks + j] = zj;
       }
+      best = fmaxf(best, __shfl_xor(best, 8));
+      best = fmaxf(best, __shfl_xor(best, 16));
+      best = fmaxf(best, __shfl_xor(best, 32));
+      if ((tid & 63) == 0) wave_max[i][tid >> 6] = fmaxf(wave_max[i][tid >> 6], best);
     }
+  }
+  __syncthreads();
+  if (tid < g.Nq) {
+    float mx = wave_max[tid][0];
+    for (int w = 1; w < kWaves; ++w) mx = fmaxf(mx, wave_max[tid][w]);
+    A.cmax[((long long)bh * g.Nq + tid) * A.nchunks + blockIdx.x] = mx;
   }
 }
 
@@ -137,11 +162,12 @@ __global__ __launch_bounds__(kDecodeSolveThreads) void decode_solve_kernel(Decod
     if (tid == 0) A.tau[row] = 0.f;
     return;
   }
-  const float* z = A.scores + (long long)row * g.Nk;
+  const float* z = A.scores + (long long)row * A.nks;
+  const float* cmax = A.cmax + (long long)row * A.nchunks;
   const float r = 1.0f / (g.alpha - 1.0f);
-  // row maximum
+  // row maximum from the chunks' maxima
   float m = -kInf;
-  for (int j = tid; j < lim; j += kDecodeSolveThreads) m = fmaxf(m, z[j]);
+  for (int c = tid; c < A.nchunks; c += kDecodeSolveThreads) m = fmaxf(m, cmax[c]);
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
   if ((tid & 63) == 0) wmax[tid >> 6] = m;
@@ -150,13 +176,22 @@ __global__ __launch_bounds__(kDecodeSolveThreads) void decode_solve_kernel(Decod
 #pragma unroll
   for (int w = 0; w < kW; ++w) m = fmaxf(m, wmax[w]);
   // keys with a non-zero term at the lowest threshold tau_lo = max - 1 (there the maximum's own term is 1,
-  // so the sum is >= 1 and the root is >= tau_lo)
+  // so the sum is >= 1 and the root is >= tau_lo); a wave takes a chunk at a time and skips those whose
+  // maximum is out of reach
   const float tau_lo = m - 1.0f;
-  for (int j = tid; j < lim; j += kDecodeSolveThreads) {
-    const float zj = z[j];
-    if (zj > tau_lo) {
-      const int pos = atomicAdd(&count, 1);
-      if (pos < kDecodeListCap) list[pos] = make_float2(__int_as_float(j), zj);
+  for (int c = tid >> 6; c < A.nchunks; c += kW) {
+    if (!(cmax[c] > tau_lo)) continue;
+    for (int v = 0; v < A.chunk / 256; ++v) {
+      const int j = c * A.chunk + (v * 64 + (tid & 63)) * 4;
+      if (j >= lim) continue;
+      const f32x4_t zv = *reinterpret_cast<const f32x4_t*>(z + j);  // nks is a multiple of 4: the word is inside the row
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        if (j + k < lim && zv[k] > tau_lo) {
+          const int pos = atomicAdd(&count, 1);
+          if (pos < kDecodeListCap) list[pos] = make_float2(__int_as_float(j + k), zv[k]);
+        }
+      }
     }
   }
   __syncthreads();

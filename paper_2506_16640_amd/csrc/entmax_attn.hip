@@ -32,6 +32,8 @@ struct Layout {
   size_t off_vt, off_cand, off_flcnt, off_bounds, off_flags, off_kt, off_qt, off_dot, off_mu, off_crow, off_dscale, off_mask,
       off_jlist, off_lcnt, off_kcount, off_koffs, off_kcursor, off_csc_i, off_csc_pw, off_hflag, off_longkeys, off_fcells, off_bcells, sv_cand, sv_lcnt, sv_flags, sv_kcand, total_saved, total_fwd,
       total_bwd;
+  size_t off_dec_cmax;  // decode kernels: score rows at offset 0, then the chunk maxima
+  int dec_nks, dec_nchunks, dec_chunk;
 };
 
 int check(const entmax_attn_params* p) {
@@ -103,8 +105,12 @@ Layout make_layout(const entmax_attn_params* p) {
   L.total_fwd = L.off_fcells + align_up(list_groups * CellBuf<kCandCap>::kBytesPerWorkgroup);
   // the decode kernels' score rows take the place of everything above
   if (p->Nq <= kDecodeRows) {
-    const size_t score_bytes = align_up(bh * (size_t)p->Nq * p->Nk * sizeof(float));
-    if (score_bytes > L.total_fwd) L.total_fwd = score_bytes;
+    L.dec_nks = (p->Nk + 3) / 4 * 4;
+    L.dec_chunk = 512;  // 64 to 128 KB of K per workgroup; 256 to 2048 keys measured alike at Nk = 32768
+    L.dec_nchunks = ceil_div(p->Nk, L.dec_chunk);
+    L.off_dec_cmax = align_up(bh * (size_t)p->Nq * L.dec_nks * sizeof(float));
+    const size_t dec_bytes = L.off_dec_cmax + align_up(bh * (size_t)p->Nq * L.dec_nchunks * sizeof(float));
+    if (dec_bytes > L.total_fwd) L.total_fwd = dec_bytes;
   }
   size_t o = 0;
   L.off_kt = o;
@@ -282,7 +288,7 @@ bool launch_fwd_sparse_am(const FwdSparseArgs& a, int am, int nblocks, hipStream
 template <typename T, int D>
 bool launch_decode(const DecodeArgs& a, int am, hipStream_t st, void* const* ev) {
   const Geom& g = a.g;
-  hipLaunchKernelGGL((decode_scores_kernel<T, D>), dim3((unsigned)ceil_div(g.Nk, kDecodeChunk), (unsigned)(g.B * g.H)),
+  hipLaunchKernelGGL((decode_scores_kernel<T, D>), dim3((unsigned)a.nchunks, (unsigned)(g.B * g.H)),
                      dim3(kThreads), 0, st, a);
   if (!launch_ok()) return false;
   record(ev, ENTMAX_FWD_PHASE_LISTS + 1, st);
@@ -322,6 +328,10 @@ int run_fwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
       da.O = O;
       da.tau = tau;
       da.scores = reinterpret_cast<float*>(ws);
+      da.cmax = reinterpret_cast<float*>(ws + L.off_dec_cmax);
+      da.nks = L.dec_nks;
+      da.nchunks = L.dec_nchunks;
+      da.chunk = L.dec_chunk;
       if (!launch_decode<T, D>(da, alpha_mode(p->alpha), st, ev)) return ENTMAX_ATTN_LAUNCH_FAILED;
     } else {
       record(ev, ENTMAX_FWD_PHASE_PREPARE + 1, st);
