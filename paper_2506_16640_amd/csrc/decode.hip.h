@@ -35,6 +35,20 @@ struct DecodeArgs {
   int chunk;      // keys per workgroup of decode_scores_kernel, a multiple of 256
 };
 
+// x + (x of the lane that the DPP control CTRL pairs this lane with): one VALU instruction, no LDS traffic.
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float x) {
+  return x + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, false));
+}
+// Sum over each aligned group of eight lanes, in every lane of the group: lane k adds lane 7-k
+// (row_half_mirror), then its neighbour in the pair (quad_perm [1,0,3,2]), then the other pair of its quad
+// (quad_perm [2,3,0,1]).  The additions form the same tree in all eight lanes, so they agree to the bit.
+__device__ __forceinline__ float sum8(float x) {
+  x = dpp_add<0x141>(x);
+  x = dpp_add<0xB1>(x);
+  return dpp_add<0x4E>(x);
+}
+
 // Eight lanes share a key row (each a contiguous eighth of its features), so a wave's load
 // instruction covers eight whole rows; a thread keeps four rows in flight.
 template <typename T, int D>
@@ -43,7 +57,7 @@ __global__ __launch_bounds__(kThreads) void decode_scores_kernel(DecodeArgs A) {
   __shared__ __align__(16) float qs[kDecodeRows * D];
   __shared__ float coef[kDecodeRows];
   __shared__ int limit[kDecodeRows];
-  __shared__ float wave_max[kDecodeRows][kWaves];  // entry [i][w] is wave w's alone
+  __shared__ float group_max[kDecodeRows][kThreads / 8];  // entry [i][grp]: touched by the group's first lane only
   const Geom& g = A.g;
   const int tid = threadIdx.x, bh = blockIdx.y, b = bh / g.H, h = bh % g.H;
   const int j0 = blockIdx.x * A.chunk;
@@ -52,7 +66,7 @@ __global__ __launch_bounds__(kThreads) void decode_scores_kernel(DecodeArgs A) {
   // the first key rows are requested before anything else: their addresses need nothing from the queries
   const int grp = tid >> 3, sub = tid & 7;
   const int jend = min(j0 + A.chunk, g.Nk);
-  RawRow<T, kSlice> kk[4], nx[4];
+  RawRow<T, kSlice> nx[4];
   auto fetch = [&](RawRow<T, kSlice>* dst, int base) {
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
@@ -71,13 +85,17 @@ __global__ __launch_bounds__(kThreads) void decode_scores_kernel(DecodeArgs A) {
   if (tid < g.Nq) {
     const int lim = row_limit(g, tid);
     limit[tid] = lim;
-    for (int w = 0; w < kWaves; ++w) wave_max[tid][w] = -kInf;
+    for (int w = 0; w < kThreads / 8; ++w) group_max[tid][w] = -kInf;
     coef[tid] = (g.alpha - 1.0f) * row_scale(g, b, h, tid, lim, nullptr, nullptr, nullptr) * (1.0f / sqrtf((float)D));
   }
   __syncthreads();
   for (int base = j0; base < jend; base += 128) {
+    float kf[4][kSlice];  // widened once, used by every query row
 #pragma unroll
-    for (int u = 0; u < 4; ++u) kk[u] = nx[u];
+    for (int u = 0; u < 4; ++u) {
+#pragma unroll
+      for (int t = 0; t < kSlice; ++t) kf[u][t] = nx[u].get(t);
+    }
     if (base + 128 < jend) fetch(nx, base + 128);  // the next rows are on their way during the arithmetic
     for (int i = 0; i < g.Nq; ++i) {
       float qv[kSlice];
@@ -96,26 +114,23 @@ __global__ __launch_bounds__(kThreads) void decode_scores_kernel(DecodeArgs A) {
       for (int u = 0; u < 4; ++u) {
         float dot = 0.f;
 #pragma unroll
-        for (int t = 0; t < kSlice; ++t) dot = fmaf(kk[u].get(t), qv[t], dot);
-        dot += __shfl_xor(dot, 1);
-        dot += __shfl_xor(dot, 2);
-        dot += __shfl_xor(dot, 4);
+        for (int t = 0; t < kSlice; ++t) dot = fmaf(kf[u][t], qv[t], dot);
+        const float zj = sum8(dot) * c;
         const int j = base + u * 32 + grp;
-        const float zj = dot * c;
         if (j < lim) best = fmaxf(best, zj);
         if (sub == u && j < lim) A.scores[((long long)bh * g.Nq + i) * A.nks + j] = zj;
       }
-      best = fmaxf(best, __shfl_xor(best, 8));
-      best = fmaxf(best, __shfl_xor(best, 16));
-      best = fmaxf(best, __shfl_xor(best, 32));
-      if ((tid & 63) == 0) wave_max[i][tid >> 6] = fmaxf(wave_max[i][tid >> 6], best);
+      if (sub == 0) group_max[i][grp] = fmaxf(group_max[i][grp], best);
     }
   }
   __syncthreads();
-  if (tid < g.Nq) {
-    float mx = wave_max[tid][0];
-    for (int w = 1; w < kWaves; ++w) mx = fmaxf(mx, wave_max[tid][w]);
-    A.cmax[((long long)bh * g.Nq + tid) * A.nchunks + blockIdx.x] = mx;
+  {
+    // thread (i, grp) of an 8 x 32 arrangement: the row's maximum over the 32 groups
+    const int i = tid >> 5;
+    float mx = i < g.Nq ? group_max[i][tid & 31] : -kInf;
+#pragma unroll
+    for (int off = 16; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+    if ((tid & 31) == 0 && i < g.Nq) A.cmax[((long long)bh * g.Nq + i) * A.nchunks + blockIdx.x] = mx;
   }
 }
 
