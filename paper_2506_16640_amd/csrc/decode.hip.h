@@ -49,6 +49,12 @@ __device__ __forceinline__ float sum8(float x) {
   return dpp_add<0x4E>(x);
 }
 
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+// acc + a.lo * b.lo + a.hi * b.hi for two packed bf16 pairs, in fp32
+__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float acc) {
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a), __builtin_bit_cast(bf16x2_t, b), acc, false);
+}
+
 // Eight lanes share a key row (each a contiguous eighth of its features), so a wave's load
 // instruction covers eight whole rows; a thread keeps four rows in flight.
 template <typename T, int D>
@@ -75,12 +81,12 @@ __global__ __launch_bounds__(kThreads) void decode_scores_kernel(DecodeArgs A) {
     }
   };
   fetch(nx, j0);
-  for (int e = tid; e < g.Nq * D; e += kThreads) {
-    const int i = e / D, c = e % D;
-    if constexpr (sizeof(T) == 2)
-      qs[e] = __uint_as_float((uint32_t)reinterpret_cast<const uint16_t*>(Qh)[(long long)i * g.q_sn + c] << 16);
-    else
-      qs[e] = reinterpret_cast<const float*>(Qh)[(long long)i * g.q_sn + c];
+  // Q in LDS as it is in memory: fp32, or bf16 pairs (then row i starts at word i * D/2)
+  uint32_t* qw = reinterpret_cast<uint32_t*>(qs);
+  constexpr int kRowWords = D * (int)sizeof(T) / 4;
+  for (int e = tid; e < g.Nq * kRowWords; e += kThreads) {
+    const int i = e / kRowWords, c = e % kRowWords;
+    qw[e] = reinterpret_cast<const uint32_t*>(Qh + (long long)i * g.q_sn)[c];
   }
   if (tid < g.Nq) {
     const int lim = row_limit(g, tid);
@@ -90,23 +96,16 @@ __global__ __launch_bounds__(kThreads) void decode_scores_kernel(DecodeArgs A) {
   }
   __syncthreads();
   for (int base = j0; base < jend; base += 128) {
-    float kf[4][kSlice];  // widened once, used by every query row
+    RawRow<T, kSlice> kk[4];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-#pragma unroll
-      for (int t = 0; t < kSlice; ++t) kf[u][t] = nx[u].get(t);
-    }
+    for (int u = 0; u < 4; ++u) kk[u] = nx[u];
     if (base + 128 < jend) fetch(nx, base + 128);  // the next rows are on their way during the arithmetic
     for (int i = 0; i < g.Nq; ++i) {
-      float qv[kSlice];
+      constexpr int kWords = RawRow<T, kSlice>::kWords;
+      u32x4_t qv[kWords];  // the lane's slice of query row i
 #pragma unroll
-      for (int t = 0; t < kSlice; t += 4) {
-        const f32x4_t w = *reinterpret_cast<const f32x4_t*>(&qs[i * D + sub * kSlice + t]);
-        qv[t] = w[0];
-        qv[t + 1] = w[1];
-        qv[t + 2] = w[2];
-        qv[t + 3] = w[3];
-      }
+      for (int w = 0; w < kWords; ++w)
+        qv[w] = *reinterpret_cast<const u32x4_t*>(&qw[i * kRowWords + sub * (kRowWords / 8) + 4 * w]);
       const float c = coef[i];
       const int lim = limit[i];
       float best = -kInf;
@@ -114,7 +113,15 @@ __global__ __launch_bounds__(kThreads) void decode_scores_kernel(DecodeArgs A) {
       for (int u = 0; u < 4; ++u) {
         float dot = 0.f;
 #pragma unroll
-        for (int t = 0; t < kSlice; ++t) dot = fmaf(kf[u][t], qv[t], dot);
+        for (int w = 0; w < kWords; ++w) {
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            if constexpr (sizeof(T) == 2)
+              dot = dot2_bf16(kk[u].w[w][k], qv[w][k], dot);  // two features per instruction, nothing to widen
+            else
+              dot = fmaf(__uint_as_float(kk[u].w[w][k]), __uint_as_float(qv[w][k]), dot);
+          }
+        }
         const float zj = sum8(dot) * c;
         const int j = base + u * 32 + grp;
         if (j < lim) best = fmaxf(best, zj);

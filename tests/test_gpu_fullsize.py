@@ -108,3 +108,15 @@ def test_c4_long_context_forward_one_head_and_skip_rate():
 @pytest.mark.parametrize("alpha", [1.25, 1.5, 2.0])
 def test_c5_alpha_sweep_d128_sampled_heads(alpha):
     _check_heads("c5", [(0, 2), (1, 13)], alpha=alpha)
+
+
+@pytest.mark.parametrize("nq", [1, 8])
+def test_decode_full_size(nq):
+    """The decode workload bench.py times (B=4, H=12, Nk=32768, d=64, bf16): every row against the oracle,
+    which needs only Nq rows per head."""
+    data = synth.make_inputs(B=4, H=12, n=nq, nk=32768, d=64, dtype="bf16", scale="head", seed=0, want_dO=False)
+    g = gpu_run(data, 1.5, "bf16", bwd=False)
+    r = oracle_run(data, 1.5, bwd=False)
+    errs = {"tau": float(np.abs(g["tau"] - r["tau"]).max()), "O": float(np.abs(g["O"] - r["O"]).max())}
+    print("decode full size", nq, errs, "support per row", float(r["support"].mean()))
+    assert errs["tau"] <= TOL_TAU and errs["O"] <= TOL_O, errs
