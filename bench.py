@@ -7,7 +7,7 @@ the 120M-class LM attention layer at training length (B=4, H=12, n=4096, d=64,
 bf16, causal, alpha=1.5, per-head ASEntmax scale, 5% planted keys), seeded and
 synthetic, resident in HBM before the timed region.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3] [--no-cpu-baseline] [--no-c4] [--no-decode]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3] [--alpha A] [--no-cpu-baseline] [--no-c4] [--no-decode]
 """
 import argparse
 import ctypes
@@ -73,6 +73,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="c3")
+    ap.add_argument("--alpha", type=float, default=None, help="entmax alpha instead of the workload's own (1.5)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-c4", action="store_true", help="skip the n=32768 forward-only measurement")
     ap.add_argument("--no-decode", action="store_true", help="skip the decode-shape (Nq = 1 and 8, Nk = 32768) measurement")
@@ -102,6 +103,8 @@ def main():
 
     data, cfg, t = upload(args.workload)
     B, H, n, d, alpha = cfg["B"], cfg["H"], cfg["n"], cfg["d"], cfg["alpha"]
+    if args.alpha is not None:
+        alpha = args.alpha
     do_bwd = bool(cfg["bwd"])
     kw = dict(alpha=alpha, beta=t["beta"], gamma=t["gamma"], delta=data["delta"], causal=True, logn_mode=0)
     prm = binding.make_params(t["Q"], t["K"], alpha, data["delta"], True, t["beta"], 0)
