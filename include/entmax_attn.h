@@ -61,8 +61,9 @@ typedef struct {
   int32_t logn_mode;       /* n in (ln n)^gamma: 0 = Nk for every row, 1 = number of keys visible to the row.
                               A row with n <= 1 uses scale = delta and contributes no beta/gamma gradient. */
   int32_t path;            /* forward path: 0 = automatic (candidate-list kernel first; workgroups that meet a row
-                              with too many candidates fall back to the tiled kernel; with Nq <= 8, the decoding
-                              shape, kernels that split the keys instead), 1 = tiled kernel only */
+                              with too many candidates fall back to the tiled kernel; with Nq <= 8, or Nq <= 64 and
+                              Nk >= 64 Nq -- the decoding shape -- kernels that split the keys instead),
+                              1 = tiled kernel only */
   float alpha;             /* 1 < alpha <= 2; 1.5, 2.0 and 1.25 run on integer-power fast paths */
   float delta;             /* ASEntmax delta (1.0 in the paper's experiments) */
   int64_t q_stride_b, q_stride_h, q_stride_n;    /* strides of Q,O,dO,dQ in elements; all 0 = contiguous */
@@ -142,7 +143,7 @@ enum {
  * candidates above a lower bound of tau are finished from a short per-row list
  * after two sweeps; denser rows run the tile-wise iteration and P.V on the
  * matrix cores with zero tiles skipped.
- * Decoding shape (path 0, Nq <= 8: a few query rows against a long key sequence, the regime of the
+ * Decoding shape (path 0; Nq <= 8, or Nq <= 64 with Nk >= 64 Nq: a few query rows against a long key sequence, the regime of the
  * long-context evaluation of Sec. 4): the keys, not the queries, are split over the chip; K is
  * read once, the rows' scores (Nq x Nk fp32 per head) go to the workspace, and each row's
  * threshold and output come from its score row.  `saved` then only tells the backward to rebuild

@@ -1,5 +1,5 @@
 // Forward for a handful of query rows against a long key sequence (decoding:
-// Nq <= kDecodeRows).  The tiled and list kernels give a workgroup 128 query
+// see decode_shape()).  The tiled and list kernels give a workgroup 128 query
 // rows and one head's whole key sequence; with a few rows that is one
 // workgroup per head streaming megabytes of K.  Here the keys are split
 // instead, and the path is bound by reading K once from HBM:
@@ -18,7 +18,14 @@
 
 namespace entmax {
 
-constexpr int kDecodeRows = 8;          // most query rows the decode kernels take
+constexpr int kDecodeRows = 8;          // up to this many query rows always take the decode kernels,
+constexpr int kDecodeRowsLong = 64;     // up to this many when the keys are at least kDecodeLongRatio times as many
+constexpr int kDecodeLongRatio = 64;
+inline bool decode_shape(int Nq, int Nk) {
+  return Nq <= kDecodeRows || (Nq <= kDecodeRowsLong && (long long)Nk >= (long long)kDecodeLongRatio * Nq);
+}
+// dynamic LDS of decode_scores_kernel: Q rows as in memory, the groups' maxima, a coefficient and a limit per row
+inline size_t decode_scores_lds(int Nq, int D, size_t esize) { return (size_t)Nq * (D * esize + (kThreads / 8) * 4 + 8); }
 constexpr int kDecodeSolveThreads = 1024;
 constexpr int kDecodeListCap = 4096;    // support candidates kept in LDS; longer ones are re-read from the score row
 
@@ -60,11 +67,15 @@ __device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float acc) {
 template <typename T, int D>
 __global__ __launch_bounds__(kThreads) void decode_scores_kernel(DecodeArgs A) {
   constexpr int kSlice = D / 8;
-  __shared__ __align__(16) float qs[kDecodeRows * D];
-  __shared__ float coef[kDecodeRows];
-  __shared__ int limit[kDecodeRows];
-  __shared__ float group_max[kDecodeRows][kThreads / 8];  // entry [i][grp]: touched by the group's first lane only
+  extern __shared__ __align__(16) char decode_lds[];
   const Geom& g = A.g;
+  constexpr int kRowWords = D * (int)sizeof(T) / 4;
+  constexpr int kGroups = kThreads / 8;
+  uint32_t* qw = reinterpret_cast<uint32_t*>(decode_lds);                  // [Nq][kRowWords]
+  float* group_max = reinterpret_cast<float*>(qw + g.Nq * kRowWords);      // [Nq][kGroups]: entry [i][grp] is touched
+                                                                           // by the group's first lane only
+  float* coef = group_max + g.Nq * kGroups;                                // [Nq]
+  int* limit = reinterpret_cast<int*>(coef + g.Nq);                        // [Nq]
   const int tid = threadIdx.x, bh = blockIdx.y, b = bh / g.H, h = bh % g.H;
   const int j0 = blockIdx.x * A.chunk;
   const T* Qh = reinterpret_cast<const T*>(A.Q) + (long long)b * g.q_sb + (long long)h * g.q_sh;
@@ -82,8 +93,6 @@ __global__ __launch_bounds__(kThreads) void decode_scores_kernel(DecodeArgs A) {
   };
   fetch(nx, j0);
   // Q in LDS as it is in memory: fp32, or bf16 pairs (then row i starts at word i * D/2)
-  uint32_t* qw = reinterpret_cast<uint32_t*>(qs);
-  constexpr int kRowWords = D * (int)sizeof(T) / 4;
   for (int e = tid; e < g.Nq * kRowWords; e += kThreads) {
     const int i = e / kRowWords, c = e % kRowWords;
     qw[e] = reinterpret_cast<const uint32_t*>(Qh + (long long)i * g.q_sn)[c];
@@ -91,7 +100,7 @@ __global__ __launch_bounds__(kThreads) void decode_scores_kernel(DecodeArgs A) {
   if (tid < g.Nq) {
     const int lim = row_limit(g, tid);
     limit[tid] = lim;
-    for (int w = 0; w < kThreads / 8; ++w) group_max[tid][w] = -kInf;
+    for (int w = 0; w < kGroups; ++w) group_max[tid * kGroups + w] = -kInf;
     coef[tid] = (g.alpha - 1.0f) * row_scale(g, b, h, tid, lim, nullptr, nullptr, nullptr) * (1.0f / sqrtf((float)D));
   }
   __syncthreads();
@@ -127,14 +136,14 @@ __global__ __launch_bounds__(kThreads) void decode_scores_kernel(DecodeArgs A) {
         if (j < lim) best = fmaxf(best, zj);
         if (sub == u && j < lim) A.scores[((long long)bh * g.Nq + i) * A.nks + j] = zj;
       }
-      if (sub == 0) group_max[i][grp] = fmaxf(group_max[i][grp], best);
+      if (sub == 0) group_max[i * kGroups + grp] = fmaxf(group_max[i * kGroups + grp], best);
     }
   }
   __syncthreads();
-  {
+  for (int i0 = 0; i0 < g.Nq; i0 += 8) {
     // thread (i, grp) of an 8 x 32 arrangement: the row's maximum over the 32 groups
-    const int i = tid >> 5;
-    float mx = i < g.Nq ? group_max[i][tid & 31] : -kInf;
+    const int i = i0 + (tid >> 5);
+    float mx = i < g.Nq ? group_max[i * kGroups + (tid & 31)] : -kInf;
 #pragma unroll
     for (int off = 16; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
     if ((tid & 31) == 0 && i < g.Nq) A.cmax[((long long)bh * g.Nq + i) * A.nchunks + blockIdx.x] = mx;

@@ -104,7 +104,7 @@ Layout make_layout(const entmax_attn_params* p) {
   const size_t list_groups = bh * (size_t)((L.nqb + 1) / 2);  // workgroups of the list sweeps
   L.total_fwd = L.off_fcells + align_up(list_groups * CellBuf<kCandCap>::kBytesPerWorkgroup);
   // the decode kernels' score rows take the place of everything above
-  if (p->Nq <= kDecodeRows) {
+  if (decode_shape(p->Nq, p->Nk)) {
     L.dec_nks = (p->Nk + 3) / 4 * 4;
     L.dec_chunk = 512;  // 64 to 128 KB of K per workgroup; 256 to 2048 keys measured alike at Nk = 32768
     L.dec_nchunks = ceil_div(p->Nk, L.dec_chunk);
@@ -289,7 +289,7 @@ template <typename T, int D>
 bool launch_decode(const DecodeArgs& a, int am, hipStream_t st, void* const* ev) {
   const Geom& g = a.g;
   hipLaunchKernelGGL((decode_scores_kernel<T, D>), dim3((unsigned)a.nchunks, (unsigned)(g.B * g.H)),
-                     dim3(kThreads), 0, st, a);
+                     dim3(kThreads), decode_scores_lds(g.Nq, D, sizeof(T)), st, a);
   if (!launch_ok()) return false;
   record(ev, ENTMAX_FWD_PHASE_LISTS + 1, st);
   const dim3 grid((unsigned)(g.B * g.H * g.Nq)), block(kDecodeSolveThreads);
@@ -313,7 +313,7 @@ int run_fwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
     for (int k = 1; k <= ENTMAX_FWD_NUM_PHASES; ++k) record(ev, k, st);
     return ok ? ENTMAX_ATTN_OK : ENTMAX_ATTN_LAUNCH_FAILED;
   }
-  if (p->path == 0 && p->Nq <= kDecodeRows) {
+  if (p->path == 0 && decode_shape(p->Nq, p->Nk)) {
     // a few query rows against the whole key sequence: split the keys over the chip
     if (p->Nq > 0 && p->B * p->H > 0) {
       // no lists for the backward: every block belongs to its tiled kernels

@@ -75,8 +75,8 @@ def test_workspace_sizes(binding):
     # ragged lengths are padded to 128 rows in the transposed copies
     small = b.workspace_bytes(_params(b, B=1, H=1, Nq=65, Nk=65), 0)
     assert small >= 64 * 128 * 2 and b.workspace_bytes(_params(b, B=1, H=1, Nq=65, Nk=129), 0) - small == 64 * 128 * 2
-    # decode shapes (Nq <= 8): fp32 score rows (Nk rounded up to 4) and one maximum per chunk of 512 keys
-    for nq, nk, dt in ((1, 32768, 0), (8, 32768, 0), (8, 1001, 1), (3, 5, 1)):
+    # decode shapes (Nq <= 8, or Nq <= 64 with Nk >= 64 Nq): fp32 score rows (Nk rounded up to 4) and one maximum per chunk of 512 keys
+    for nq, nk, dt in ((1, 32768, 0), (8, 32768, 0), (8, 1001, 1), (3, 5, 1), (64, 4096, 1), (32, 32768, 0)):
         need = 48 * nq * ((nk + 3) // 4 * 4) * 4 + 48 * nq * ((nk + 511) // 512) * 4
         assert b.workspace_bytes(_params(b, B=4, H=12, Nq=nq, Nk=nk, dtype=dt), 0) >= need
 

@@ -24,10 +24,23 @@ def test_decode_forward(nq, nk, alpha):
     print(nq, nk, alpha, compare(g, r, bwd=False, label=f"decode {nq}x{nk} a{alpha}"))
 
 
+@pytest.mark.parametrize("nq,nk,decode", [(9, 600, True), (33, 2200, True), (64, 4133, True), (64, 4000, False),
+                                          (65, 5000, False)])
+def test_decode_more_rows_against_long_keys(nq, nk, decode):
+    # up to 64 rows take the split-key kernels when the keys are at least 64 times as many; the tile counters
+    # (which only the training kernels keep) tell which path ran
+    data = _case(nq, nk, 64, "bf16", "head", seed=18, B=1, H=2)
+    g = gpu_run(data, 1.5, "bf16", bwd=False, stats=True)
+    r = oracle_run(data, 1.5, bwd=False)
+    print(nq, nk, compare(g, r, bwd=False, label=f"decode {nq}x{nk}"))
+    assert (g["stats"]["fwd_list_qk"] + g["stats"]["fwd_qk_max"] == 0) == decode
+
+
 @pytest.mark.parametrize("d,dtype", [(64, "fp32"), (128, "bf16"), (128, "fp32")])
 @pytest.mark.parametrize("causal", [True, False])
-def test_decode_dtypes_and_head_dims(d, dtype, causal):
-    data = _case(5, 1300, d, dtype, "head", seed=12)
+@pytest.mark.parametrize("nq", [5, 20])
+def test_decode_dtypes_and_head_dims(d, dtype, causal, nq):
+    data = _case(nq, 1300, d, dtype, "head", seed=12)
     g = gpu_run(data, 1.5, dtype, causal=causal, bwd=False)
     r = oracle_run(data, 1.5, causal=causal, bwd=False)
     print(d, dtype, causal, compare(g, r, bwd=False, label=f"decode d{d} {dtype}"))
