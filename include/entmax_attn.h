@@ -29,8 +29,13 @@
  *   - beta, gamma: fp32, [H] (scale_layout 1) or [B,H,Nq] (scale_layout 2),
  *     ignored (may be NULL) for scale_layout 0 where scale_i = delta.
  *   - Return value: 0 on success, a negative entmax_attn_status otherwise.
- *     Arguments are validated on the host before anything is launched; on
- *     error nothing has been enqueued.
+ *     Arguments are validated on the host before anything is launched: with
+ *     INVALID_ARG, UNSUPPORTED_SHAPE, MISALIGNED or WORKSPACE_TOO_SMALL nothing has
+ *     been enqueued.  LAUNCH_FAILED means the HIP runtime refused one of the
+ *     call's launches: the kernels before it are already on the stream and will
+ *     run, so the outputs, the workspace and `saved` are then undefined.
+ *   - `stats`, `phase_events` and `params.path` are optional instrumentation for
+ *     tests and measurement (NULL, NULL and 0 in production use).
  */
 #ifndef ENTMAX_ATTN_H
 #define ENTMAX_ATTN_H
@@ -47,7 +52,7 @@ typedef enum {
   ENTMAX_ATTN_INVALID_ARG = -1,       /* NULL where a pointer is required, bad enum, non-positive size, alpha outside (1,2] */
   ENTMAX_ATTN_UNSUPPORTED_SHAPE = -2, /* D not in {64,128}, sizes beyond the index range */
   ENTMAX_ATTN_MISALIGNED = -3,        /* pointer or stride not 16-byte aligned */
-  ENTMAX_ATTN_WORKSPACE_TOO_SMALL = -4,
+  ENTMAX_ATTN_WORKSPACE_TOO_SMALL = -4, /* workspace_bytes or saved_bytes below what the parameters need */
   ENTMAX_ATTN_LAUNCH_FAILED = -5      /* the HIP runtime refused a launch */
 } entmax_attn_status;
 
@@ -134,6 +139,8 @@ enum {
  *        caller: receives the rows' candidate lists (key, raw score) -- a superset of each row's support
  *        (Sec. 2.2: the keys with non-zero probability) -- for the backward, which then skips its own
  *        Q K^T sweep.  Opaque; valid only together with this call's tau and the same params and inputs.
+ *   saved_bytes: size of `saved` (ignored when saved is NULL); less than entmax_attn_saved_bytes(p) is
+ *        refused with WORKSPACE_TOO_SMALL before anything is launched.
  *   workspace: device scratch of at least entmax_attn_workspace_bytes(p, 0)
  *        bytes, 256-byte aligned; contents are undefined afterwards.
  * The row threshold is found from sweeps over the key tiles that recompute
@@ -150,8 +157,8 @@ enum {
  * the supports itself.
  */
 int entmax_attn_fwd(const entmax_attn_params* p, const void* Q, const void* K, const void* V, const float* beta,
-                    const float* gamma, void* O, float* tau, void* saved, uint64_t* stats, void* workspace,
-                    size_t workspace_bytes, void* hip_stream, void* const* phase_events);
+                    const float* gamma, void* O, float* tau, void* saved, size_t saved_bytes, uint64_t* stats,
+                    void* workspace, size_t workspace_bytes, void* hip_stream, void* const* phase_events);
 
 /*
  * Backward (exact derivative of the forward; Jacobian of eq. (entmax)).
@@ -165,6 +172,7 @@ int entmax_attn_fwd(const entmax_attn_params* p, const void* Q, const void* K, c
  *        rows' supports are taken from the forward's lists (entries whose probability is zero at tau
  *        are dropped); without it one Q K^T sweep at tau rebuilds them.  Same results either way up
  *        to the summation order inside a row.
+ *   saved_bytes: size of `saved`, checked as in the forward.
  *   workspace: at least entmax_attn_workspace_bytes(p, 1) bytes, 256-byte aligned.
  * `path` selects as in the forward: 0 = support lists per row and per key for heads whose rows
  * have few non-zero probabilities, tiled kernels for the other heads; 1 = tiled kernels only.
@@ -172,9 +180,9 @@ int entmax_attn_fwd(const entmax_attn_params* p, const void* Q, const void* K, c
  * list path sums each key's entries in query order whenever a key has at most 64 of them.
  */
 int entmax_attn_bwd(const entmax_attn_params* p, const void* Q, const void* K, const void* V, const void* O,
-                    const void* dO, const float* tau, const void* saved, const float* beta, const float* gamma,
-                    void* dQ, void* dK, void* dV, float* dbeta, float* dgamma, uint64_t* stats, void* workspace,
-                    size_t workspace_bytes, void* hip_stream, void* const* phase_events);
+                    const void* dO, const float* tau, const void* saved, size_t saved_bytes, const float* beta,
+                    const float* gamma, void* dQ, void* dK, void* dV, float* dbeta, float* dgamma, uint64_t* stats,
+                    void* workspace, size_t workspace_bytes, void* hip_stream, void* const* phase_events);
 
 /* Scratch bytes the forward (is_bwd = 0) or backward (is_bwd != 0) needs for
  * these parameters; 0 if the parameters are invalid. Host-only, no GPU call. */

@@ -45,10 +45,11 @@ class Params(ctypes.Structure):
 
 _vp = ctypes.c_void_p
 _lib.entmax_attn_fwd.restype = ctypes.c_int
-_lib.entmax_attn_fwd.argtypes = [ctypes.POINTER(Params), _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp,
-                                 ctypes.c_size_t, _vp, _vp]
+_lib.entmax_attn_fwd.argtypes = [ctypes.POINTER(Params), _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp,
+                                 _vp, ctypes.c_size_t, _vp, _vp]
 _lib.entmax_attn_bwd.restype = ctypes.c_int
-_lib.entmax_attn_bwd.argtypes = [ctypes.POINTER(Params)] + [_vp] * 16 + [ctypes.c_size_t, _vp, _vp]
+_lib.entmax_attn_bwd.argtypes = ([ctypes.POINTER(Params)] + [_vp] * 7 + [ctypes.c_size_t] + [_vp] * 9 +
+                                 [ctypes.c_size_t, _vp, _vp])
 _lib.entmax_attn_workspace_bytes.restype = ctypes.c_size_t
 _lib.entmax_attn_workspace_bytes.argtypes = [ctypes.POINTER(Params), ctypes.c_int]
 _lib.entmax_attn_saved_bytes.restype = ctypes.c_size_t
@@ -74,6 +75,8 @@ def _ptr(t):
 
 
 def make_params(q, k, alpha, delta, causal, beta, logn_mode, path=0):
+    if q.dim() != 4 or k.dim() != 4 or q.shape[:2] != k.shape[:2] or q.shape[3] != k.shape[3]:
+        raise ValueError("Q must be [B,H,Nq,D] and K [B,H,Nk,D]")
     B, H, Nq, D = q.shape
     Nk = k.shape[2]
     if q.dtype == torch.bfloat16:
@@ -86,12 +89,42 @@ def make_params(q, k, alpha, delta, causal, beta, logn_mode, path=0):
     p = Params(B, H, Nq, Nk, D, dt, int(bool(causal)), layout, int(logn_mode), int(path), float(alpha), float(delta),
                0, 0, 0, 0, 0, 0)
     if not q.is_contiguous():
-        assert q.stride(3) == 1
+        if q.stride(3) != 1:
+            raise ValueError("the last dimension of Q must be contiguous")
         p.q_stride_b, p.q_stride_h, p.q_stride_n = q.stride(0), q.stride(1), q.stride(2)
     if not k.is_contiguous():
-        assert k.stride(3) == 1
+        if k.stride(3) != 1:
+            raise ValueError("the last dimension of K must be contiguous")
         p.kv_stride_b, p.kv_stride_h, p.kv_stride_n = k.stride(0), k.stride(1), k.stride(2)
     return p
+
+
+def _check_like(name, t, ref):
+    """t must have ref's shape, strides, dtype and device (the ABI passes one set of strides per tensor family)."""
+    if t.shape != ref.shape or t.stride() != ref.stride():
+        raise ValueError("%s must have the shape and strides of its reference tensor" % name)
+    if t.dtype != ref.dtype or t.device != ref.device:
+        raise TypeError("%s must have the dtype and device of Q" % name)
+
+
+def _check_scale(p, q, beta, gamma):
+    if (beta is None) != (gamma is None):
+        raise ValueError("beta and gamma come together")
+    if beta is None:
+        return
+    want = (p.H,) if p.scale_layout == 1 else (p.B, p.H, p.Nq)
+    for name, t in (("beta", beta), ("gamma", gamma)):
+        if t.dtype != torch.float32 or not t.is_contiguous() or tuple(t.shape) != want or t.device != q.device:
+            raise ValueError("%s must be a contiguous float32 tensor of shape %s on Q's device" % (name, want))
+
+
+def _check_aux(p, stats, saved, workspace, is_bwd):
+    if stats is not None and (stats.numel() < NUM_STATS or stats.element_size() != 8 or not stats.is_contiguous()):
+        raise ValueError("stats must be a contiguous 64-bit integer tensor with at least %d entries" % NUM_STATS)
+    if saved is not None and (saved.dtype != torch.uint8 or not saved.is_contiguous()):
+        raise ValueError("saved must be a contiguous uint8 tensor")
+    if workspace is not None and (workspace.dtype != torch.uint8 or not workspace.is_contiguous()):
+        raise ValueError("workspace must be a contiguous uint8 tensor")
 
 
 def workspace_bytes(params, is_bwd):
@@ -114,7 +147,8 @@ def check_params(params):
 def _events_arg(events, n):
     if events is None:
         return None
-    assert len(events) == n + 1
+    if len(events) != n + 1:
+        raise ValueError("phase_events needs %d handles" % (n + 1))
     arr = (ctypes.c_void_p * (n + 1))(*[ctypes.c_void_p(e) for e in events])
     return arr
 
@@ -126,23 +160,30 @@ def _stream():
 def entmax_attn_fwd(q, k, v, alpha=1.5, beta=None, gamma=None, delta=1.0, causal=True, logn_mode=0, path=0,
                     out=None, tau=None, stats=None, workspace=None, phase_events=None, saved=None):
     """O, tau = entmax attention forward.  q [B,H,Nq,D], k,v [B,H,Nk,D] on the GPU, bf16 or fp32;
-    beta,gamma fp32 [H] or [B,H,Nq] or None.  stats: optional uint64/int64 device tensor [16] (added to).
+    beta,gamma fp32 [H] or [B,H,Nq] or None.  stats: optional uint64/int64 device tensor [NUM_STATS] (added to).
     path: 0 automatic, 1 tiled kernel only.  phase_events: optional list of FWD_NUM_PHASES + 1 hipEvent_t handles.
     saved: optional uint8 device tensor of saved_bytes(params) bytes, filled for the backward."""
     p = make_params(q, k, alpha, delta, causal, beta, logn_mode, path)
-    assert v.shape == k.shape and v.stride() == k.stride()
+    if k.dtype != q.dtype or k.device != q.device:
+        raise TypeError("K must have the dtype and device of Q")
+    _check_like("V", v, k)
+    _check_scale(p, q, beta, gamma)
+    _check_aux(p, stats, saved, workspace, False)
     if out is None:
         out = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device)
     else:
-        assert out.stride() == q.stride()
+        _check_like("out", out, q)
     if tau is None:
         tau = torch.empty(q.shape[:3], dtype=torch.float32, device=q.device)
+    elif tau.dtype != torch.float32 or not tau.is_contiguous() or tau.shape != q.shape[:3]:
+        raise ValueError("tau must be a contiguous float32 tensor [B,H,Nq]")
     need = workspace_bytes(p, 0)
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
     ev = _events_arg(phase_events, FWD_NUM_PHASES)
     rc = _lib.entmax_attn_fwd(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(beta), _ptr(gamma), _ptr(out),
-                              _ptr(tau), _ptr(saved), _ptr(stats), _ptr(workspace), workspace.numel(), _stream(), ev)
+                              _ptr(tau), _ptr(saved), 0 if saved is None else saved.numel(), _ptr(stats),
+                              _ptr(workspace), workspace.numel(), _stream(), ev)
     if rc != 0:
         raise EntmaxAttnError(rc)
     return out, tau
@@ -153,7 +194,14 @@ def entmax_attn_bwd(q, k, v, o, do, tau, alpha=1.5, beta=None, gamma=None, delta
     """dQ, dK, dV, dbeta, dgamma = entmax attention backward (dbeta/dgamma None without scale parameters).
     saved: the buffer the forward filled for the same inputs, or None."""
     p = make_params(q, k, alpha, delta, causal, beta, logn_mode, path)
-    assert v.stride() == k.stride() and do.stride() == q.stride()
+    if k.dtype != q.dtype or k.device != q.device:
+        raise TypeError("K must have the dtype and device of Q")
+    _check_like("V", v, k)
+    _check_like("dO", do, q)
+    _check_scale(p, q, beta, gamma)
+    _check_aux(p, stats, saved, workspace, True)
+    if tau.dtype != torch.float32 or not tau.is_contiguous() or tau.shape != q.shape[:3]:
+        raise ValueError("tau must be a contiguous float32 tensor [B,H,Nq]")
     dq = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device)
     dk = torch.empty_strided(k.shape, k.stride(), dtype=k.dtype, device=k.device)
     dv = torch.empty_strided(v.shape, v.stride(), dtype=v.dtype, device=v.device)
@@ -164,7 +212,7 @@ def entmax_attn_bwd(q, k, v, o, do, tau, alpha=1.5, beta=None, gamma=None, delta
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
     ev = _events_arg(phase_events, BWD_NUM_PHASES)
     rc = _lib.entmax_attn_bwd(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(do), _ptr(tau), _ptr(saved),
-                              _ptr(beta), _ptr(gamma), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(dbeta), _ptr(dgamma), _ptr(stats),
+                              0 if saved is None else saved.numel(), _ptr(beta), _ptr(gamma), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(dbeta), _ptr(dgamma), _ptr(stats),
                               _ptr(workspace), workspace.numel(), _stream(), ev)
     if rc != 0:
         raise EntmaxAttnError(rc)

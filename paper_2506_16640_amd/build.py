@@ -1,15 +1,20 @@
-"""Builds the C-ABI library (csrc/ -> lib/libentmax_attn.so) with hipcc for gfx950."""
+"""Builds the C-ABI library (csrc/ -> lib/libentmax_attn.so) with hipcc for gfx950.
+
+The kernels of each (launcher, element type, head dimension) combination are a translation unit of
+their own (csrc/inst.hip compiled with different -D flags), so the units compile in parallel."""
+import concurrent.futures
 import os
 import subprocess
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(_HERE)
-SRC = os.path.join(_HERE, "csrc", "entmax_attn.hip")
+CSRC = os.path.join(_HERE, "csrc")
 LIB_DIR = os.path.join(_HERE, "lib")
+OBJ_DIR = os.path.join(LIB_DIR, "obj")
 LIB = os.path.join(LIB_DIR, "libentmax_attn.so")
 
 HIPCC_FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     # packed fp32 arithmetic stays off: ordinary float code must not be fused into v_pk_* forms
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     # MFMA results go straight to VGPRs (no AGPR round trip before the VALU work on the scores)
@@ -21,17 +26,52 @@ HIPCC_FLAGS = [
 ]
 
 
-def build_library(verbose=False):
-    """Compile every HIP source into lib/libentmax_attn.so (always recompiles)."""
-    os.makedirs(LIB_DIR, exist_ok=True)
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + HIPCC_FLAGS + ["-I", os.path.join(ROOT, "include"), "-o", LIB, SRC]
+def translation_units():
+    """(object name, source, extra flags) of every unit of the library."""
+    units = [("api", "entmax_attn.hip", [])]
+    for leg in ("FWD", "BWD"):
+        for tname, ctype in (("bf16", "bf16_t"), ("f32", "float")):
+            for d in (64, 128):
+                units.append(("%s_%s_%d" % (leg.lower(), tname, d), "inst.hip",
+                              ["-DENTMAX_INST_%s" % leg, "-DENTMAX_INST_T=%s" % ctype, "-DENTMAX_INST_D=%d" % d]))
+    return units
+
+
+def _run(cmd):
     res = subprocess.run(cmd, capture_output=True, text=True)
-    if verbose or res.returncode != 0:
-        print(res.stdout)
-        print("\n".join(l for l in res.stderr.splitlines() if "not a recognized feature" not in l))
-    if res.returncode != 0:
+    err = "\n".join(l for l in res.stderr.splitlines() if "not a recognized feature" not in l)
+    return res.returncode, res.stdout, err
+
+
+def build_library(verbose=False, jobs=None):
+    """Compile every HIP source into lib/libentmax_attn.so (always recompiles)."""
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    inc = ["-I", os.path.join(ROOT, "include"), "-I", CSRC]
+    jobs = jobs or min(8, os.cpu_count() or 1)
+    cmds = []
+    objs = []
+    for name, src, extra in translation_units():
+        obj = os.path.join(OBJ_DIR, name + ".o")
+        objs.append(obj)
+        cmds.append([hipcc] + HIPCC_FLAGS + extra + inc + ["-c", os.path.join(CSRC, src), "-o", obj])
+    with concurrent.futures.ThreadPoolExecutor(max_workers=jobs) as pool:
+        results = list(pool.map(_run, cmds))
+    failed = False
+    for cmd, (rc, out, err) in zip(cmds, results):
+        if verbose or rc != 0:
+            print(" ".join(cmd[-4:]))
+            print(out)
+            print(err)
+        failed = failed or rc != 0
+    if failed:
         raise RuntimeError("hipcc failed building " + LIB)
+    rc, out, err = _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs)
+    if verbose or rc != 0:
+        print(out)
+        print(err)
+    if rc != 0:
+        raise RuntimeError("hipcc failed linking " + LIB)
     return LIB
 
 

@@ -562,14 +562,14 @@ __device__ __forceinline__ void scale_grad_head_part(const Geom& g, const float*
   }
 }
 
-__global__ __launch_bounds__(kScaleGradThreads) void scale_grad_head_kernel(Geom g, const float* dscale, float* dbeta,
+static __global__ __launch_bounds__(kScaleGradThreads) void scale_grad_head_kernel(Geom g, const float* dscale, float* dbeta,
                                                                    float* dgamma) {
   __shared__ float sb_[kScaleGradThreads], sg_[kScaleGradThreads];
   scale_grad_head_part<kScaleGradThreads>(g, dscale, dbeta, dgamma, blockIdx.x, sb_, sg_);
 }
 
 // Per-query parameters: one value per row.
-__global__ void scale_grad_query_kernel(Geom g, const float* dscale, float* dbeta, float* dgamma) {
+static __global__ void scale_grad_query_kernel(Geom g, const float* dscale, float* dbeta, float* dgamma) {
   long long row = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   long long rows = (long long)g.B * g.H * g.Nq;
   if (row >= rows) return;

@@ -25,8 +25,6 @@
 
 namespace entmax {
 
-constexpr int kBwdCap = 16;  // support entries per lane = per half row
-constexpr int kLongCountOffset = 64;  // the long-key counter sits in a cache line of its own, away from the flags
 constexpr int kSortedKeyEntries = 8;        // a key with at most this many entries is summed by one lane pair
 constexpr int kListInWorkspace = 1 << 30;   // list length flag: the entries sit in the lane's own list (jlist)
 constexpr int kListCountMask = 0xffff;
@@ -283,7 +281,7 @@ __global__ __launch_bounds__(kThreads, D == 64 ? 2 : 1) void bwd_rows_kernel(Bwd
     const long long cap = (long long)g.Nq * 2 * kBwdCap;  // entries a head can hold
 #pragma unroll
     for (int e = 0; e < NE; ++e) {
-      if (slotv[e] >= 0 && slotv[e] < cap) {  // (below cap by construction; never index outside the head)
+      if (slotv[e] >= 0 && slotv[e] < cap) {  // (key_offsets_kernel flags heads whose segments would not fit)
         float x = fmaxf(fmaf(dv[e], a, -tau), 0.f);
         float ds = pow_rm1<AM>(x, r) * (dpv[e] - mu);
         A.csc_i[rl.bh * cap + slotv[e]] = rl.i;
@@ -319,7 +317,7 @@ __global__ __launch_bounds__(kThreads, D == 64 ? 2 : 1) void bwd_rows_kernel(Bwd
 constexpr int kOffsThreads = 1024;
 
 // precounted: A.kcount already holds the counts (the forward's, read only): only the prefix sums are left.
-__global__ __launch_bounds__(kOffsThreads) void key_offsets_kernel(BwdSparseArgs A, int src_cap, int use_lds,
+static __global__ __launch_bounds__(kOffsThreads) void key_offsets_kernel(BwdSparseArgs A, int src_cap, int use_lds,
                                                                   int precounted) {
   extern __shared__ int offs_lds[];
   int* part = offs_lds;                   // entries in the thread's range of keys
@@ -373,6 +371,13 @@ __global__ __launch_bounds__(kOffsThreads) void key_offsets_kernel(BwdSparseArgs
     part[tid] += v;
     partl[tid] += vl;
     __syncthreads();
+  }
+  // The key-major arrays hold kBwdCap entries per half row and head.  Counts taken from the rows' own
+  // support lists stay within that; the forward's candidate counts (precounted) can exceed it when the
+  // candidates far outnumber the supports: such a head is left to the tiled kernels.
+  if (part[kOffsThreads - 1] > g.Nq * 2 * kBwdCap) {
+    if (tid == 0) A.head_flag[bh] = 1;
+    return;
   }
   // one list reservation per head
   if (tid == kOffsThreads - 1)

@@ -19,6 +19,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "constants.h"
+#include "entmax_attn.h"
+
 namespace entmax {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
@@ -26,9 +29,6 @@ typedef float f32x16_t __attribute__((ext_vector_type(16)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
-constexpr int kThreads = 256;    // 4 wave64 per workgroup
-constexpr int kWaves = 4;
-constexpr int kBlockRows = 128;  // rows (queries or keys) owned by a workgroup: 32 per wave
 constexpr float kInf = __builtin_inff();
 
 struct bf16_t {
@@ -222,20 +222,20 @@ struct FragOff<float> {
 // issues the global loads of a ragged tile (rows at or beyond valid_rows repeat the last valid row),
 // fetch_full() does the same for a tile known to lie wholly inside the tensor,
 // commit() writes the staged chunks to LDS.
-template <typename TileT>
+template <typename TileT, int NT = kThreads>
 struct Stage {
-  static_assert(TileT::kChunks % kThreads == 0, "tile must be a whole number of 4 KiB passes");
-  static constexpr int kPer = TileT::kChunks / kThreads;
+  static_assert(TileT::kChunks % NT == 0, "every thread must move the same number of chunks");
+  static constexpr int kPer = TileT::kChunks / NT;
   u32x4_t r[kPer];
   uint32_t goff[kPer];
   int loff[kPer];
-  int row0;  // row of the first chunk; chunk `it` sits kThreads / kCpr rows further per step
+  int row0;  // row of the first chunk; chunk `it` sits NT / kCpr rows further per step
   __device__ __forceinline__ void init(long long grow_bytes, int tid) {
     row0 = tid / TileT::kCpr;
     int ch = tid % TileT::kCpr;
 #pragma unroll
     for (int it = 0; it < kPer; ++it) {
-      int row = row0 + it * (kThreads / TileT::kCpr);
+      int row = row0 + it * (NT / TileT::kCpr);
       goff[it] = (uint32_t)row * (uint32_t)grow_bytes + (uint32_t)(ch * 16);
       loff[it] = TileT::off(row, ch);
     }
@@ -251,7 +251,7 @@ struct Stage {
   __device__ __forceinline__ void fetch(const char* gtile, int valid_rows, long long grow_bytes) {
 #pragma unroll
     for (int it = 0; it < kPer; ++it) {
-      int row = min(row0 + it * (kThreads / TileT::kCpr), valid_rows - 1);
+      int row = min(row0 + it * (NT / TileT::kCpr), valid_rows - 1);
       uint32_t off = (uint32_t)row * (uint32_t)grow_bytes + (goff[0] - (uint32_t)row0 * (uint32_t)grow_bytes);
       r[it] = *reinterpret_cast<const u32x4_t*>(gtile + off);
     }

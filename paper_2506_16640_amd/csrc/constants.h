@@ -1,0 +1,30 @@
+// Sizes shared by the host-side layout code (plain C++, no HIP) and the kernels.
+#pragma once
+#include <stddef.h>
+
+namespace entmax {
+
+constexpr int kThreads = 256;    // 4 wave64 per workgroup
+constexpr int kWaves = 4;
+constexpr int kBlockRows = 128;  // rows (queries or keys) owned by a workgroup: 32 per wave
+
+constexpr int kCandCap = 32;     // candidate entries per lane = per half row (forward lists)
+constexpr int kBwdCap = 16;      // support entries per lane = per half row (backward lists)
+constexpr int kListStride = 64;  // lists are stored slot-major per wave: entry s of the 64 lanes together
+constexpr int kLongCountOffset = 64;  // the long-key counter sits in a cache line of its own, away from the flags
+
+// Sweep scratch of the list kernels: CAP cells of (4 raw scores, first key) per thread.
+constexpr int kCellGroups = 1;  // 4-key accumulator groups per cell
+constexpr size_t cell_bytes_per_workgroup(int cap) { return (size_t)kThreads * cap * (16 * kCellGroups + 4); }
+
+// Decode shapes: up to kDecodeRows query rows always take the split-key kernels, up to kDecodeRowsLong
+// when the keys are at least kDecodeLongRatio times as many.
+constexpr int kDecodeRows = 8;
+constexpr int kDecodeRowsLong = 64;
+constexpr int kDecodeLongRatio = 64;
+constexpr int kDecodeChunk = 512;  // keys per workgroup of the score kernel (64 to 128 KB of K); 256 to 2048 measured alike
+inline bool decode_shape(int Nq, int Nk) {
+  return Nq <= kDecodeRows || (Nq <= kDecodeRowsLong && (long long)Nk >= (long long)kDecodeLongRatio * Nq);
+}
+
+}  // namespace entmax

@@ -18,12 +18,6 @@
 
 namespace entmax {
 
-constexpr int kDecodeRows = 8;          // up to this many query rows always take the decode kernels,
-constexpr int kDecodeRowsLong = 64;     // up to this many when the keys are at least kDecodeLongRatio times as many
-constexpr int kDecodeLongRatio = 64;
-inline bool decode_shape(int Nq, int Nk) {
-  return Nq <= kDecodeRows || (Nq <= kDecodeRowsLong && (long long)Nk >= (long long)kDecodeLongRatio * Nq);
-}
 // dynamic LDS of decode_scores_kernel: Q rows as in memory, the groups' maxima, a coefficient and a limit per row
 inline size_t decode_scores_lds(int Nq, int D, size_t esize) { return (size_t)Nq * (D * esize + (kThreads / 8) * 4 + 8); }
 constexpr int kDecodeSolveThreads = 1024;

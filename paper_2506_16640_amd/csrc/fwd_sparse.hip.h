@@ -25,13 +25,10 @@
 
 namespace entmax {
 
-constexpr int kCandCap = 32;
-
 // Row lists (candidates, supports, per-entry records) are stored per wave of 32 rows x 2 halves with
 // entry s of all 64 lanes together: short lists then touch only the first few 512-byte groups of a
 // wave's region instead of one cache line per half row.  Wave w = ((bh * nqb + qb) * 4 + wave in block);
 // entry (lane, s) sits at list_entry<CAP>(w, lane) + s * kListStride.
-constexpr int kListStride = 64;
 template <int CAP>
 __device__ __forceinline__ long long list_entry(int bh, int nqb, int qb, int wave, int lane) {
   return (((long long)bh * nqb + qb) * kWaves + wave) * CAP * kListStride + lane;
@@ -61,7 +58,6 @@ struct FwdSparseArgs {
 // -- all their raw scores and the first key index -- to a private strip of scratch memory whenever the
 // cell maximum passes the cutoff: one short divergent region per cell instead of one per score.  After
 // the sweep each lane walks its own cells and writes the scores above the cutoff to its list.
-constexpr int kCellGroups = 1;              // 4-key accumulator groups per cell
 constexpr int kCellKeys = 4 * kCellGroups;
 constexpr int kCellsPerBlock = 16 / kCellKeys;
 
@@ -70,7 +66,7 @@ struct CellBuf {
   // cell s of the 256 threads of a workgroup together (s-major), for the same reason as the row lists
   f32x4_t* d;  // cell s, group u at d[(s * kCellGroups + u) * kThreads]: raw scores
   int* j;      // cell s at j[s * kThreads]: key of the cell's first score
-  static constexpr size_t kBytesPerWorkgroup = (size_t)kThreads * CAP * (16 * kCellGroups + 4);
+  static constexpr size_t kBytesPerWorkgroup = cell_bytes_per_workgroup(CAP);
   __device__ __forceinline__ void init(void* base, int tid) {
     char* wg = reinterpret_cast<char*>(base) + (size_t)blockIdx.x * kBytesPerWorkgroup;
     d = reinterpret_cast<f32x4_t*>(wg) + tid;

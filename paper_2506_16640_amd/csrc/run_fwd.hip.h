@@ -1,0 +1,164 @@
+// Forward launcher: candidate-list kernels with the tiled kernel as fallback, or the
+// split-key kernels for decode shapes.
+#pragma once
+#include "decode.hip.h"
+#include "fwd.hip.h"
+#include "fwd_sparse.hip.h"
+#include "launch.hip.h"
+
+namespace entmax {
+namespace {
+
+template <typename T, int D, int AM>
+bool launch_fwd_main(const FwdArgs& a, int nblocks, hipStream_t st) {
+  size_t smem = 4 * (size_t)QCtx<T, D, FwdTile<T>::value>::kTileBytes + (size_t)(kWaves + 1) * a.mask_words * 4 + 64;
+  constexpr auto kern = fwd_kernel<T, D, AM>;
+  if (!ensure_dynamic_lds<kern>(smem)) return false;
+  hipLaunchKernelGGL(kern, dim3((unsigned)nblocks), dim3(kThreads), smem, st, a);
+  return launch_ok();
+}
+
+template <typename T, int D>
+bool launch_fwd_am(const FwdArgs& a, int am, int nblocks, hipStream_t st) {
+  switch (am) {
+    case 1: return launch_fwd_main<T, D, 1>(a, nblocks, st);
+    case 2: return launch_fwd_main<T, D, 2>(a, nblocks, st);
+    case 3: return launch_fwd_main<T, D, 3>(a, nblocks, st);
+    default: return launch_fwd_main<T, D, 0>(a, nblocks, st);
+  }
+}
+
+template <typename T, int D, int AM>
+bool launch_fwd_sparse(const FwdSparseArgs& a, int nblocks, hipStream_t st, void* const* ev) {
+  size_t smem = 2 * (size_t)QCtx<T, D, FwdTile<T>::value>::kTileBytes + 64;
+  hipLaunchKernelGGL((fwd_lists_kernel<T, D, AM>), dim3((unsigned)nblocks), dim3(kThreads), smem, st, a);
+  if (!launch_ok()) return false;
+  record(ev, ENTMAX_FWD_PHASE_LISTS + 1, st);
+  hipLaunchKernelGGL((fwd_finish_kernel<T, D, AM>), dim3((unsigned)(a.g.B * a.g.H * a.nqb)), dim3(kThreads), 0, st, a);
+  return launch_ok();
+}
+
+template <typename T, int D>
+bool launch_fwd_sparse_am(const FwdSparseArgs& a, int am, int nblocks, hipStream_t st, void* const* ev) {
+  switch (am) {
+    case 1: return launch_fwd_sparse<T, D, 1>(a, nblocks, st, ev);
+    case 2: return launch_fwd_sparse<T, D, 2>(a, nblocks, st, ev);
+    case 3: return launch_fwd_sparse<T, D, 3>(a, nblocks, st, ev);
+    default: return launch_fwd_sparse<T, D, 0>(a, nblocks, st, ev);
+  }
+}
+
+template <typename T, int D>
+bool launch_decode(const DecodeArgs& a, int am, hipStream_t st, void* const* ev) {
+  const Geom& g = a.g;
+  hipLaunchKernelGGL((decode_scores_kernel<T, D>), dim3((unsigned)a.nchunks, (unsigned)(g.B * g.H)),
+                     dim3(kThreads), decode_scores_lds(g.Nq, D, sizeof(T)), st, a);
+  if (!launch_ok()) return false;
+  record(ev, ENTMAX_FWD_PHASE_LISTS + 1, st);
+  const dim3 grid((unsigned)(g.B * g.H * g.Nq)), block(kDecodeSolveThreads);
+  switch (am) {
+    case 1: hipLaunchKernelGGL((decode_solve_kernel<T, D, 1>), grid, block, 0, st, a); break;
+    case 2: hipLaunchKernelGGL((decode_solve_kernel<T, D, 2>), grid, block, 0, st, a); break;
+    case 3: hipLaunchKernelGGL((decode_solve_kernel<T, D, 3>), grid, block, 0, st, a); break;
+    default: hipLaunchKernelGGL((decode_solve_kernel<T, D, 0>), grid, block, 0, st, a); break;
+  }
+  return launch_ok();
+}
+
+}  // namespace
+
+template <typename T, int D>
+int run_fwd(const entmax_attn_params* p, const Layout& L, const void* Q, const void* K, const void* V,
+            const float* beta, const float* gamma, void* O, float* tau, char* saved, uint64_t* stats, char* ws,
+            hipStream_t st, void* const* ev) {
+  record(ev, 0, st);
+  if (p->Nk == 0) {
+    bool ok = zero_rows<T>(O, L.q_sb, L.q_sh, L.q_sn, p->B, p->H, p->Nq, p->D, st) &&
+              zero_words(tau, (size_t)p->B * p->H * p->Nq * 4, st);
+    for (int k = 1; k <= ENTMAX_FWD_NUM_PHASES; ++k) record(ev, k, st);
+    return ok ? ENTMAX_ATTN_OK : ENTMAX_ATTN_LAUNCH_FAILED;
+  }
+  if (p->path == 0 && decode_shape(p->Nq, p->Nk)) {
+    // a few query rows against the whole key sequence: split the keys over the chip
+    if (p->Nq > 0 && p->B * p->H > 0) {
+      // no lists for the backward: every block belongs to its tiled kernels
+      if (saved && !fill_words(saved + L.sv_flags, (size_t)p->B * p->H * L.nqb * sizeof(int), 1u, st))
+        return ENTMAX_ATTN_LAUNCH_FAILED;
+      record(ev, ENTMAX_FWD_PHASE_PREPARE + 1, st);
+      DecodeArgs da;
+      da.g = make_geom(p, L, beta, gamma);
+      da.Q = Q;
+      da.K = K;
+      da.V = V;
+      da.O = O;
+      da.tau = tau;
+      da.scores = reinterpret_cast<float*>(ws);
+      da.cmax = reinterpret_cast<float*>(ws + L.off_dec_cmax);
+      da.nks = L.dec_nks;
+      da.nchunks = L.dec_nchunks;
+      da.chunk = L.dec_chunk;
+      if (!launch_decode<T, D>(da, alpha_mode(p->alpha), st, ev)) return ENTMAX_ATTN_LAUNCH_FAILED;
+    } else {
+      record(ev, ENTMAX_FWD_PHASE_PREPARE + 1, st);
+      record(ev, ENTMAX_FWD_PHASE_LISTS + 1, st);
+    }
+    for (int k = ENTMAX_FWD_PHASE_FINISH; k < ENTMAX_FWD_NUM_PHASES; ++k) record(ev, k + 1, st);
+    return ENTMAX_ATTN_OK;
+  }
+  void* Vt = ws + L.off_vt;
+  // with a `saved` buffer the lists, their lengths and the block flags are written there
+  int* dense_flag = reinterpret_cast<int*>(saved ? saved + L.sv_flags : ws + L.off_flags);
+  int* head_flag = reinterpret_cast<int*>(ws + L.off_flags) + (size_t)p->B * p->H * L.nqb;
+  const int nblocks = p->B * p->H * ((L.nqb + 1) / 2);  // workgroups take query blocks in pairs
+  const bool lists = p->path == 0;
+  if (lists) {
+    FwdSparseArgs sa;
+    sa.g = make_geom(p, L, beta, gamma);
+    sa.Q = Q;
+    sa.K = K;
+    sa.V = V;
+    sa.O = O;
+    sa.tau = tau;
+    sa.cand = reinterpret_cast<uint2*>(saved ? saved + L.sv_cand : ws + L.off_cand);
+    sa.cells = ws + L.off_fcells;
+    sa.lcnt = reinterpret_cast<int*>(saved ? saved + L.sv_lcnt : ws + L.off_flcnt);
+    sa.kcand = saved ? reinterpret_cast<int*>(saved + L.sv_kcand) : nullptr;
+    if (sa.kcand && !zero_words(sa.kcand, (size_t)p->B * p->H * p->Nk * sizeof(int), st)) return ENTMAX_ATTN_LAUNCH_FAILED;
+    record(ev, ENTMAX_FWD_PHASE_PREPARE + 1, st);
+    sa.bounds = reinterpret_cast<float2*>(ws + L.off_bounds);
+    sa.dense_flag = dense_flag;
+    sa.head_flag = head_flag;
+    sa.stats = reinterpret_cast<unsigned long long*>(stats);
+    sa.nqb = L.nqb;
+    if (!launch_fwd_sparse_am<T, D>(sa, alpha_mode(p->alpha), nblocks, st, ev)) return ENTMAX_ATTN_LAUNCH_FAILED;
+  } else {
+    // no lists: tell the backward that every block belongs to its tiled kernels
+    if (saved && !fill_words(dense_flag, (size_t)p->B * p->H * L.nqb * sizeof(int), 1u, st)) return ENTMAX_ATTN_LAUNCH_FAILED;
+    record(ev, ENTMAX_FWD_PHASE_PREPARE + 1, st);
+    record(ev, ENTMAX_FWD_PHASE_LISTS + 1, st);
+  }
+  record(ev, ENTMAX_FWD_PHASE_FINISH + 1, st);
+  {
+    TransposeJobs jobs{};
+    jobs.job[0] = transpose_job(V, L.kv_sb, L.kv_sh, L.kv_sn, p->Nk, L.npad_k, Vt);
+    if (!launch_transposes<T, D>(jobs, 1, p->B, p->H, st, lists ? head_flag : nullptr)) return ENTMAX_ATTN_LAUNCH_FAILED;
+  }
+  record(ev, ENTMAX_FWD_PHASE_TRANSPOSE + 1, st);
+  FwdArgs a;
+  a.g = make_geom(p, L, beta, gamma);
+  a.Q = Q;
+  a.K = K;
+  a.Vt = Vt;
+  a.O = O;
+  a.tau = tau;
+  a.stats = reinterpret_cast<unsigned long long*>(stats);
+  a.nqb = L.nqb;
+  a.mask_words = L.mask_words;
+  a.dense_flag = lists ? dense_flag : nullptr;
+  a.head_flag = lists ? head_flag : nullptr;
+  if (!launch_fwd_am<T, D>(a, alpha_mode(p->alpha), nblocks, st)) return ENTMAX_ATTN_LAUNCH_FAILED;
+  record(ev, ENTMAX_FWD_PHASE_TILED + 1, st);
+  return ENTMAX_ATTN_OK;
+}
+
+}  // namespace entmax

@@ -53,7 +53,7 @@ __global__ __launch_bounds__(kThreads) void transpose_perm_kernel(TransposeJobs 
 }
 
 // O = 0, tau = 0 for problems without keys (Nk = 0), or any plain fill.
-__global__ void fill_words_kernel(uint32_t* p, long long nwords, uint32_t value) {
+static __global__ void fill_words_kernel(uint32_t* p, long long nwords, uint32_t value) {
   long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < nwords) p[i] = value;
 }

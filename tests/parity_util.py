@@ -79,3 +79,28 @@ def compare(gpu, ref, bwd=True, tol_o=TOL_O, tol_tau=TOL_TAU, tol_grad=TOL_GRAD,
             errs[name] = rel_err(gpu[name], ref[name])
             assert errs[name] <= tol_grad, (label, name, errs)
     return errs
+
+
+def threshold_residual(sub, tau_rows, rows, alpha, causal=True, logn_mode=0, band=1e-4):
+    """For the given rows of ONE head (sub: Q,K [1,1,n,d], per-head beta/gamma or None), from the definition in
+    fp64 (numpy only): |f(tau)| with f(tau) = sum_j [(alpha-1) s_ij - tau]_+^(1/(alpha-1)) - 1 at the thresholds
+    `tau_rows`, and the number of visible scores within band * max(1, |tau|) of the threshold."""
+    Q, K = sub["Q"][0, 0].astype(np.float64), sub["K"][0, 0].astype(np.float64)
+    nq, d = Q.shape
+    nk = K.shape[0]
+    resid, near = [], 0
+    for i, t in zip(rows, tau_rows):
+        nvis = min(max(i + (nk - nq) + 1, 0), nk) if causal else nk
+        if nvis == 0:
+            continue
+        scale = sub["delta"]
+        if sub["beta"] is not None:
+            n_log = nk if logn_mode == 0 else nvis
+            if n_log > 1:
+                b, g = float(np.ravel(sub["beta"])[0]), float(np.ravel(sub["gamma"])[0])
+                scale = sub["delta"] + b * np.log(n_log) ** g
+        y = (alpha - 1.0) * scale * (K[:nvis] @ Q[i]) / np.sqrt(d)
+        x = np.maximum(y - t, 0.0)
+        resid.append(abs(float(np.sum(x ** (1.0 / (alpha - 1.0)))) - 1.0))
+        near += int(np.sum(np.abs(y - t) < band * max(1.0, abs(t))))
+    return (max(resid) if resid else 0.0), near

@@ -89,8 +89,12 @@ def test_entry_points_reject_bad_arguments_before_any_launch(binding):
     null = ctypes.c_void_p(None)
     fake = ctypes.c_void_p(4096)
     bad = ctypes.c_void_p(4100)  # not 16-byte aligned
-    args = lambda **kw: [kw.get(k, null if k == "saved" else fake)  # noqa
-                         for k in ("Q", "K", "V", "beta", "gamma", "O", "tau", "saved", "stats", "ws")]
+    def args(**kw):
+        a = [kw.get(k, null if k == "saved" else fake)
+             for k in ("Q", "K", "V", "beta", "gamma", "O", "tau", "saved", "stats", "ws")]
+        a.insert(8, ctypes.c_size_t(kw.get("saved_bytes", 0)))  # saved_bytes follows saved
+        return a
+
     call = lambda prm, a, wsb=1 << 30: lib.entmax_attn_fwd(ctypes.byref(prm), *a, ctypes.c_size_t(wsb), null, null)  # noqa
     assert call(_params(b, D=32), args()) == -2
     assert call(p, args(Q=null)) == -1
@@ -98,11 +102,46 @@ def test_entry_points_reject_bad_arguments_before_any_launch(binding):
     assert call(p, args(K=bad)) == -3
     assert call(p, args(stats=null), wsb=16) == -4
     assert call(p, args(saved=bad)) == -3
+    # a saved buffer smaller than the parameters need is refused like a small workspace
+    need = b.saved_bytes(p)
+    assert call(p, args(saved=fake, saved_bytes=need - 1)) == -4
+    assert call(p, args(saved=fake, saved_bytes=0)) == -4
     lib.entmax_attn_bwd.restype = ctypes.c_int
-    a = [fake] * 16
+    a = [fake] * 17
     a[6] = null  # saved is optional
+    a[7] = ctypes.c_size_t(0)
     assert lib.entmax_attn_bwd(ctypes.byref(_params(b, alpha=3.0)), *a, ctypes.c_size_t(1 << 30), null, null) == -1
     a[5] = null  # tau
     assert lib.entmax_attn_bwd(ctypes.byref(p), *a, ctypes.c_size_t(1 << 30), null, null) == -1
     a[5] = fake
     assert lib.entmax_attn_bwd(ctypes.byref(p), *a, ctypes.c_size_t(16), null, null) == -4
+    a[6], a[7] = fake, ctypes.c_size_t(need - 1)
+    assert lib.entmax_attn_bwd(ctypes.byref(p), *a, ctypes.c_size_t(1 << 30), null, null) == -4
+
+
+def test_binding_rejects_mismatched_tensors(binding):
+    """The Python layer raises (never asserts) on tensors the C ABI cannot describe; CPU tensors suffice because
+    the checks run before the library is called."""
+    import torch
+    b = binding
+    q = torch.zeros(1, 2, 16, 64, dtype=torch.bfloat16)
+    k = torch.zeros(1, 2, 16, 64, dtype=torch.bfloat16)
+    beta = torch.ones(2)
+    with pytest.raises(TypeError):
+        b.entmax_attn_fwd(q, k.float(), k.float())
+    with pytest.raises(ValueError):
+        b.entmax_attn_fwd(q, k, k[:, :, :8])
+    with pytest.raises(ValueError):
+        b.entmax_attn_fwd(q, k, k, beta=beta, gamma=None)
+    with pytest.raises(ValueError):
+        b.entmax_attn_fwd(q, k, k, beta=beta.double(), gamma=beta.double())
+    with pytest.raises(ValueError):
+        b.entmax_attn_fwd(q, k, k, beta=torch.ones(3), gamma=torch.ones(3))
+    with pytest.raises(ValueError):
+        b.entmax_attn_fwd(q, k, k, stats=torch.zeros(16, dtype=torch.int64))
+    with pytest.raises(ValueError):
+        b.entmax_attn_fwd(q, k, k, tau=torch.zeros(1, 2, 15))
+    with pytest.raises(ValueError):
+        b.entmax_attn_bwd(q, k, k, q, q[:, :, :8], torch.zeros(1, 2, 16))
+    with pytest.raises(TypeError):
+        b.make_params(q.half(), k.half(), 1.5, 1.0, True, None, 0)

@@ -120,6 +120,41 @@ def test_two_level_closed_form_on_gpu(alpha):
     assert np.abs(g["O"] - V[0, 0, hi].astype(np.float64).mean(0)).max() < 2e-2
 
 
+@pytest.mark.parametrize("alpha", [1.5, 1.25])
+def test_candidates_far_beyond_support(alpha):
+    """Two-level logits (the two-level lemma of the appendix) plus a middle band: 10 equal top keys carry the
+    whole mass, 50 more keys sit above the lower bound of the threshold that the list kernel can derive but
+    below the threshold itself.  Every row then lists 60 candidates for a support of 10, so the forward's
+    per-key candidate counts add up to more than the backward's key-major arrays hold per head; the backward
+    must notice and must not drop or misplace entries (all three path variants run this)."""
+    nq, nk, d = 128, 64, 64
+    if alpha == 1.5:
+        s_top, s_mid, s_low = 2.0, 1.0, -10.0  # tau = M/2 - 10^-1/2: support needs s > M - 0.63; candidates s > M - 1.41
+    else:
+        s_top, s_mid, s_low = 4.0, 1.0, -16.0  # tau = M/4 - 10^-1/4: support needs s > M - 2.25; candidates s > M - 4
+    rng = np.random.default_rng(3)
+    level = np.full(nk, s_low)
+    # lane half hh of a row holds the keys with (j % 8) // 4 == hh: 5 top and 25 middle keys in each half
+    for hh in (0, 1):
+        keys = np.array([j for j in range(nk) if (j % 8) // 4 == hh])
+        rng.shuffle(keys)
+        level[keys[:5]] = s_top
+        level[keys[5:30]] = s_mid
+    Q = np.zeros((1, 2, nq, d), np.float32)
+    Q[..., 0] = 2.0
+    # keys differ in the features the queries do not look at (so that dQ is not identically zero)
+    K = synth.bf16_round(rng.standard_normal((1, 2, nk, d)).astype(np.float32))
+    K[..., 0] = level * math.sqrt(d) / 2.0  # logits <q,k>/sqrt(d) = level, exactly representable in bf16
+    V = synth.bf16_round(rng.standard_normal((1, 2, nk, d)).astype(np.float32))
+    dO = synth.bf16_round(rng.standard_normal((1, 2, nq, d)).astype(np.float32))
+    data = dict(Q=Q, K=K, V=V, dO=dO, beta=None, gamma=None, delta=1.0)
+    g = gpu_run(data, alpha, "bf16", causal=False, stats=True)
+    r = oracle_run(data, alpha, causal=False)
+    assert int(r["support"].min()) == int(r["support"].max()) == 10
+    assert np.abs(g["tau"] - ((alpha - 1) * s_top - 10.0 ** (-(alpha - 1)))).max() < 1e-3
+    print(alpha, compare(g, r, label=f"mid band a{alpha}"), {k: v for k, v in g["stats"].items() if v})
+
+
 def test_empty_inputs():
     import torch
     from paper_2506_16640_amd import binding
