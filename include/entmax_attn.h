@@ -53,7 +53,9 @@ typedef enum {
   ENTMAX_ATTN_UNSUPPORTED_SHAPE = -2, /* D not in {64,128}, sizes beyond the index range */
   ENTMAX_ATTN_MISALIGNED = -3,        /* pointer or stride not 16-byte aligned */
   ENTMAX_ATTN_WORKSPACE_TOO_SMALL = -4, /* workspace_bytes or saved_bytes below what the parameters need */
-  ENTMAX_ATTN_LAUNCH_FAILED = -5      /* the HIP runtime refused a launch */
+  ENTMAX_ATTN_LAUNCH_FAILED = -5,     /* the HIP runtime refused a launch */
+  ENTMAX_ATTN_SCRATCH_LIMIT = -6      /* entmax_attn_fwd_noalloc: the problem needs more scratch than the library's
+                                         built-in buffer holds (use entmax_attn_fwd with a workspace) */
 } entmax_attn_status;
 
 enum { ENTMAX_ATTN_BF16 = 0, ENTMAX_ATTN_FP32 = 1 };
@@ -183,6 +185,29 @@ int entmax_attn_bwd(const entmax_attn_params* p, const void* Q, const void* K, c
                     const void* dO, const float* tau, const void* saved, size_t saved_bytes, const float* beta,
                     const float* gamma, void* dQ, void* dK, void* dV, float* dbeta, float* dgamma, uint64_t* stats,
                     void* workspace, size_t workspace_bytes, void* hip_stream, void* const* phase_events);
+
+/*
+ * Forward for callers that cannot allocate device memory and have no workspace to hand over: code that runs
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same operation, arguments
+ * and results as entmax_attn_fwd without `saved`, `workspace` and `phase_events`: the scratch is a buffer
+ * built into the library (device memory of entmax_attn_noalloc_scratch_bytes() bytes that every GPU the
+ * library runs on holds until the process ends).  The call allocates and frees nothing.
+ *   - Parameters with entmax_attn_workspace_bytes(p, 0) above that size are refused with
+ *     ENTMAX_ATTN_SCRATCH_LIMIT before anything is launched.
+ *   - All calls on one GPU share that GPU's buffer: calls that may overlap in time (different streams,
+ *     different host threads) race; calls on one stream are ordered and safe.  The buffer keeps the previous
+ *     call's contents; the kernels write every word they later read, so nothing needs clearing.
+ *   - The buffer's address is looked up once per device, at the first call there or by
+ *     entmax_attn_noalloc_init() (call it once per device, with that device current, before a capture).
+ */
+int entmax_attn_fwd_noalloc(const entmax_attn_params* p, const void* Q, const void* K, const void* V,
+                            const float* beta, const float* gamma, void* O, float* tau, uint64_t* stats,
+                            void* hip_stream);
+/* Looks up the built-in scratch buffer of the current device; 0 on success, ENTMAX_ATTN_LAUNCH_FAILED if the
+ * runtime cannot resolve it. */
+int entmax_attn_noalloc_init(void);
+/* Size of the built-in scratch buffer, a compile-time constant of the library. Host-only. */
+size_t entmax_attn_noalloc_scratch_bytes(void);
 
 /* Scratch bytes the forward (is_bwd = 0) or backward (is_bwd != 0) needs for
  * these parameters; 0 if the parameters are invalid. Host-only, no GPU call. */

@@ -56,6 +56,12 @@ _lib.entmax_attn_saved_bytes.restype = ctypes.c_size_t
 _lib.entmax_attn_saved_bytes.argtypes = [ctypes.POINTER(Params)]
 _lib.entmax_attn_check_params.restype = ctypes.c_int
 _lib.entmax_attn_check_params.argtypes = [ctypes.POINTER(Params)]
+_lib.entmax_attn_fwd_noalloc.restype = ctypes.c_int
+_lib.entmax_attn_fwd_noalloc.argtypes = [ctypes.POINTER(Params)] + [_vp] * 9
+_lib.entmax_attn_noalloc_init.restype = ctypes.c_int
+_lib.entmax_attn_noalloc_init.argtypes = []
+_lib.entmax_attn_noalloc_scratch_bytes.restype = ctypes.c_size_t
+_lib.entmax_attn_noalloc_scratch_bytes.argtypes = []
 _lib.entmax_attn_strerror.restype = ctypes.c_char_p
 _lib.entmax_attn_strerror.argtypes = [ctypes.c_int]
 
@@ -184,6 +190,36 @@ def entmax_attn_fwd(q, k, v, alpha=1.5, beta=None, gamma=None, delta=1.0, causal
     rc = _lib.entmax_attn_fwd(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(beta), _ptr(gamma), _ptr(out),
                               _ptr(tau), _ptr(saved), 0 if saved is None else saved.numel(), _ptr(stats),
                               _ptr(workspace), workspace.numel(), _stream(), ev)
+    if rc != 0:
+        raise EntmaxAttnError(rc)
+    return out, tau
+
+
+def noalloc_scratch_bytes():
+    return int(_lib.entmax_attn_noalloc_scratch_bytes())
+
+
+def noalloc_init():
+    rc = _lib.entmax_attn_noalloc_init()
+    if rc != 0:
+        raise EntmaxAttnError(rc)
+
+
+def entmax_attn_fwd_noalloc(q, k, v, out, tau, alpha=1.5, beta=None, gamma=None, delta=1.0, causal=True, logn_mode=0,
+                            path=0, stats=None):
+    """Forward through the entry point that allocates nothing: the caller brings `out` and `tau`, the scratch is
+    the library's built-in buffer (noalloc_scratch_bytes()).  Raises EntmaxAttnError(-6) for problems beyond it."""
+    p = make_params(q, k, alpha, delta, causal, beta, logn_mode, path)
+    if k.dtype != q.dtype or k.device != q.device:
+        raise TypeError("K must have the dtype and device of Q")
+    _check_like("V", v, k)
+    _check_like("out", out, q)
+    _check_scale(p, q, beta, gamma)
+    _check_aux(p, stats, None, None, False)
+    if tau.dtype != torch.float32 or not tau.is_contiguous() or tau.shape != q.shape[:3]:
+        raise ValueError("tau must be a contiguous float32 tensor [B,H,Nq]")
+    rc = _lib.entmax_attn_fwd_noalloc(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(beta), _ptr(gamma), _ptr(out),
+                                      _ptr(tau), _ptr(stats), _stream())
     if rc != 0:
         raise EntmaxAttnError(rc)
     return out, tau

@@ -5,6 +5,8 @@
 
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "launch.hip.h"
 
 using namespace entmax;
@@ -34,6 +36,30 @@ extern template int run_bwd<float, 128> ENTMAX_BWD_SIG;
 }  // namespace entmax
 
 namespace {
+
+// Built-in scratch of entmax_attn_fwd_noalloc.  Every device that loads the library holds its own copy of
+// the array at its own address; in host code the array's name is only a handle for hipGetSymbolAddress.
+constexpr size_t kNoallocScratchBytes = (size_t)32 << 20;
+constexpr int kNoallocMaxDevices = 64;
+static __device__ __align__(256) unsigned char noalloc_scratch[kNoallocScratchBytes];
+void* noalloc_ptr[kNoallocMaxDevices] = {};  // device address per device ordinal, filled on first use
+std::mutex noalloc_mutex;
+
+// Device address of the current device's scratch array (NULL if the runtime cannot resolve it).
+void* noalloc_scratch_ptr() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kNoallocMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(noalloc_mutex);
+  if (!noalloc_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(noalloc_scratch)) != hipSuccess) {
+      (void)hipGetLastError();
+      return nullptr;
+    }
+    noalloc_ptr[dev] = ptr;
+  }
+  return noalloc_ptr[dev];
+}
 
 int fwd_checked(const entmax_attn_params* p, const void* Q, const void* K, const void* V, const float* beta,
                 const float* gamma, void* O, float* tau, void* saved, size_t saved_bytes, uint64_t* stats,
@@ -81,6 +107,7 @@ const char* entmax_attn_strerror(int code) {
     case ENTMAX_ATTN_MISALIGNED: return "pointer or stride not 16-byte aligned";
     case ENTMAX_ATTN_WORKSPACE_TOO_SMALL: return "workspace or saved buffer too small";
     case ENTMAX_ATTN_LAUNCH_FAILED: return "kernel launch failed";
+    case ENTMAX_ATTN_SCRATCH_LIMIT: return "problem needs more scratch than the built-in buffer of the no-allocation entry point";
     default: return "unknown status";
   }
 }
@@ -90,6 +117,22 @@ int entmax_attn_fwd(const entmax_attn_params* p, const void* Q, const void* K, c
                     void* workspace, size_t workspace_bytes, void* hip_stream, void* const* phase_events) {
   return fwd_checked(p, Q, K, V, beta, gamma, O, tau, saved, saved_bytes, stats, workspace, workspace_bytes,
                      reinterpret_cast<hipStream_t>(hip_stream), phase_events);
+}
+
+size_t entmax_attn_noalloc_scratch_bytes(void) { return kNoallocScratchBytes; }
+
+int entmax_attn_noalloc_init(void) { return noalloc_scratch_ptr() ? ENTMAX_ATTN_OK : ENTMAX_ATTN_LAUNCH_FAILED; }
+
+int entmax_attn_fwd_noalloc(const entmax_attn_params* p, const void* Q, const void* K, const void* V,
+                            const float* beta, const float* gamma, void* O, float* tau, uint64_t* stats,
+                            void* hip_stream) {
+  int rc = check_params(p);
+  if (rc != ENTMAX_ATTN_OK) return rc;
+  if (workspace_bytes_of(p, 0) > kNoallocScratchBytes) return ENTMAX_ATTN_SCRATCH_LIMIT;
+  void* ws = noalloc_scratch_ptr();
+  if (!ws) return ENTMAX_ATTN_LAUNCH_FAILED;
+  return fwd_checked(p, Q, K, V, beta, gamma, O, tau, nullptr, 0, stats, ws, kNoallocScratchBytes,
+                     reinterpret_cast<hipStream_t>(hip_stream), nullptr);
 }
 
 int entmax_attn_bwd(const entmax_attn_params* p, const void* Q, const void* K, const void* V, const void* O,
