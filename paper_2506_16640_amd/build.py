@@ -47,7 +47,7 @@ def build_library(verbose=False, jobs=None):
     """Compile every HIP source into lib/libentmax_attn.so (always recompiles)."""
     os.makedirs(OBJ_DIR, exist_ok=True)
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    inc = ["-I", os.path.join(ROOT, "include"), "-I", CSRC]
+    inc = ["-I", os.path.join(ROOT, "include"), "-I", CSRC] + os.environ.get("ENTMAX_EXTRA_FLAGS", "").split()
     jobs = jobs or min(8, os.cpu_count() or 1)
     cmds = []
     objs = []

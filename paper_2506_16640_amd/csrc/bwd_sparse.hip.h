@@ -7,7 +7,8 @@
 // The Jacobian of eq. (entmax) vanishes off the support, so the whole backward
 // is a sparse problem once the support is known:
 //   bwd_lists_kernel   one Q K^T sweep on the matrix cores at the saved tau lists
-//                      each row's support (key index + raw score);
+//                      each row's support (key index + raw score) -- not launched when the forward
+//                      handed its own support lists over (`saved` buffer);
 //   key_offsets_kernel one workgroup per head: how many listed entries name each key, prefix sums
 //                      of these counts (every key gets a segment that can hold all its entries), and
 //                      the list of keys with long segments;
@@ -26,8 +27,6 @@
 namespace entmax {
 
 constexpr int kSortedKeyEntries = 8;        // a key with at most this many entries is summed by one lane pair
-constexpr int kListInWorkspace = 1 << 30;   // list length flag: the entries sit in the lane's own list (jlist)
-constexpr int kListCountMask = 0xffff;
 
 struct BwdSparseArgs {
   Geom g;
@@ -40,25 +39,20 @@ struct BwdSparseArgs {
   void* dK;
   void* dV;
   float* dscale;       // [B*H*Nq]
-  uint2* jlist;        // [B*H*nqb*4 waves][kBwdCap][64 lanes], see list_entry(): (key index, raw dot product bits)
+  // The rows' support lists, their lengths and the block flags: written by bwd_lists_kernel into the workspace,
+  // or the forward's (in the `saved` buffer, read only here).
+  uint2* list;         // [B*H*nqb*4 row groups][kBwdCap][64 lanes], see list_entry(): (key index, raw dot product bits)
+  int* lcnt;           // [B*H*Nq][2] entries per half row
+  int* block_flag;     // [B*H*nqb] 1 when the block cannot take the list path (a list too long, or no lists)
   void* cells;         // sweep scratch: one CellBuf<kBwdCap> per workgroup of the list sweep's grid
-  int* lcnt;           // [B*H*Nq][2] entries per half row, written by bwd_lists_kernel or bwd_prepare_kernel
-  const uint2* src_list;  // what bwd_rows_kernel reads: jlist, or the forward's candidate lists (`saved` buffer,
-                          // kCandCap entries per lane)
-  const int* src_lcnt;    // forward's list lengths   } only with the forward's lists,
-  const int* src_dense;   // forward's block flags    } read by bwd_prepare_kernel
-  int* kcount;         // [B*H*Nk] listed entries per key = size of the key's segment (key_offsets_kernel, or the
-                       // forward's counts in the `saved` buffer: then read only)
+  int* kcount;         // [B*H*Nk] listed entries per key = size of the key's segment (key_offsets_kernel)
   int* kcursor;        // [B*H*Nk] entries placed so far; after bwd_rows_kernel: the key's entries with p > 0
   int* koffs;          // [B*H*Nk] exclusive prefix sums of kcount within the head: segment starts
   int* csc_i;          // [B*H][Nq*2*kBwdCap] query row of each entry, key-major
   float2* csc_pw;      // same order: (p, c dS)
-  int* block_flag;     // [B*H*nqb] written by bwd_lists_kernel / bwd_prepare_kernel: 1 when the block cannot take
-                       // the list path (a list too long, or no lists from the forward)
-  int* head_flag;      // [B*H + kLongCountOffset + 1]; entries < B*H written by key_offsets_kernel: 1: head left to
-                       // the tiled kernels; entry B*H + kLongCountOffset (zeroed by the first kernel): number of
-                       // keys on the long-segment list
-  int* long_keys;      // [B*H*Nk] keys whose segment holds more than kSortedKeyEntries entries
+  int* head_flag;      // [2*B*H], written by key_offsets_kernel: entry bh: 1 when the head is left to the tiled
+                       // kernels; entry B*H + bh: number of the head's keys on the long-segment list
+  int* long_keys;      // [B*H][Nk] per head: its keys whose segment holds more than kSortedKeyEntries entries
   float* dbeta;        // per-head scale gradients, reduced by extra workgroups of the keys launch
   float* dgamma;       //   (scale_heads = 0: not here)
   int scale_heads;     // H for per-head scale parameters, else 0
@@ -80,14 +74,13 @@ __device__ __forceinline__ void bwd_lists_block(const BwdSparseArgs& A, int bh_,
   const long long row_idx = (long long)q.bh * g.Nq + (q.valid ? q.i : 0);
   const float tau = q.valid ? A.tau[row_idx] : 0.f;
   const bool live = q.valid && q.lim > 0;
-  uint2* mylist = A.jlist + list_entry<kBwdCap>(q.bh, A.nqb, q.qb, q.wave, q.lane);
+  uint2* mylist = A.list + list_entry<kBwdCap>(q.bh, A.nqb, q.qb, q.wave, q.lane);
   int cnt = 0;
   unsigned n_qk = 0, n_cand_tiles = 0;
   bool fits = true;
   if (q.block_lim > 0) fits = collect_sweep<C, T, D, kBwdCap>(q, g, A.K, smem, ovf, live, tau, A.cells, mylist, cnt, n_qk, n_cand_tiles);
   if (q.tid == 0) A.block_flag[q.bh * A.nqb + q.qb] = fits ? 0 : 1;
   if (fits && q.valid) A.lcnt[row_idx * 2 + q.hh] = cnt;
-  if (blockIdx.x == 0 && q.tid == 0) A.head_flag[g.B * g.H + kLongCountOffset] = 0;
   if (A.stats && q.lane == 0) {
     atomicAdd(&A.stats[ENTMAX_STAT_BWD_TILES_VISIBLE], (unsigned long long)n_qk);
     atomicAdd(&A.stats[ENTMAX_STAT_BWD_LIST_QK], (unsigned long long)n_qk);
@@ -106,48 +99,8 @@ __global__ __launch_bounds__(kThreads, 3) void bwd_lists_kernel(BwdSparseArgs A)
   }
 }
 
-// With the forward's lists there is no sweep: this kernel does the sweep kernel's bookkeeping.  One
-// workgroup per query block: the list lengths bwd_rows_kernel will use, the block's flag (a support
-// longer than kBwdCap, or a block the forward left to its tiled kernel), the long-key counter.  A candidate list longer than kBwdCap is rare: its entries
-// with non-zero probability at tau are copied to the lane's own list, and the length carries
-// kListInWorkspace to say so.
-template <int D>
-__global__ __launch_bounds__(kThreads) void bwd_prepare_kernel(BwdSparseArgs A) {
-  const Geom& g = A.g;
-  RowLane rl;
-  rl.init(g, A.nqb);
-  const long long row_idx = (long long)rl.bh * g.Nq + (rl.valid ? rl.i : 0);
-  const int lim = rl.valid ? row_limit(g, rl.i) : 0;
-  const bool dense = A.src_dense[rl.bh * A.nqb + rl.qb] != 0;  // (its list lengths mean nothing)
-  int cnt = (rl.valid && lim > 0 && !dense) ? A.src_lcnt[row_idx * 2 + rl.hh] : 0;
-  bool over = dense;
-  if (cnt > kBwdCap) {
-    const float scale = row_scale(g, rl.b, rl.h, rl.i, lim, nullptr, nullptr, nullptr);
-    const float a = (g.alpha - 1.0f) * fabsf(scale * (1.0f / sqrtf((float)D)));  // as in the kernels that made the lists
-    const float tau = A.tau[row_idx];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const uint2* src = A.src_list + list_entry<kCandCap>(rl.bh, A.nqb, rl.qb, wave, lane);
-    uint2* dst = A.jlist + list_entry<kBwdCap>(rl.bh, A.nqb, rl.qb, wave, lane);
-    int m = 0;
-    for (int e = 0; e < min(cnt, kCandCap); ++e) {
-      const uint2 en = src[e * kListStride];
-      if (fmaf(__uint_as_float(en.y), a, -tau) > 0.f) {
-        if (m < kBwdCap) dst[m * kListStride] = en;
-        ++m;
-      }
-    }
-    over = m > kBwdCap;
-    cnt = min(m, kBwdCap) | kListInWorkspace;
-  }
-  if (rl.valid) A.lcnt[row_idx * 2 + rl.hh] = cnt;
-  const int any_over = __syncthreads_or(over ? 1 : 0);
-  if (threadIdx.x == 0) A.block_flag[rl.bh * A.nqb + rl.qb] = any_over ? 1 : 0;
-  if (blockIdx.x == 0 && threadIdx.x == 0) A.head_flag[g.B * g.H + kLongCountOffset] = 0;
-}
-
 // Everything row-wise from the lists: one lane pair per row, each lane half of the features.
-// SRC_CAP: capacity (slot count) of the lists that are read.
-template <typename T, int D, int AM, int SRC_CAP>
+template <typename T, int D, int AM>
 __global__ __launch_bounds__(kThreads, D == 64 ? 2 : 1) void bwd_rows_kernel(BwdSparseArgs A) {
   const Geom& g = A.g;
   RowLane rl;
@@ -167,13 +120,10 @@ __global__ __launch_bounds__(kThreads, D == 64 ? 2 : 1) void bwd_rows_kernel(Bwd
   const float tau_raw = A.tau[row_idx];
   const int cnt_raw = A.lcnt[row_idx * 2 + rl.hh];
   const float tau = live ? tau_raw : 0.f;
-  const int cnt = live ? min(cnt_raw & kListCountMask, kBwdCap) : 0;
-  const bool in_ws = SRC_CAP != kBwdCap && live && (cnt_raw & kListInWorkspace) != 0;  // entries in this lane's own list
+  const int cnt = live ? min(cnt_raw, kBwdCap) : 0;
   const long long q_base = (long long)rl.b * g.q_sb + (long long)rl.h * g.q_sh;
   const long long kv_base = (long long)rl.b * g.kv_sb + (long long)rl.h * g.kv_sh;
-  const long long list0 = list_entry<kBwdCap>(rl.bh, A.nqb, rl.qb, threadIdx.x >> 6, threadIdx.x & 63);
-  const uint2* mylist = A.jlist + list0;
-  const uint2* srclist = A.src_list + list_entry<SRC_CAP>(rl.bh, A.nqb, rl.qb, threadIdx.x >> 6, threadIdx.x & 63);
+  const uint2* rdlist = A.list + list_entry<kBwdCap>(rl.bh, A.nqb, rl.qb, threadIdx.x >> 6, threadIdx.x & 63);
   const T* Kbh = reinterpret_cast<const T*>(A.K) + kv_base;
   const T* Vbh = reinterpret_cast<const T*>(A.V) + kv_base;
 
@@ -190,12 +140,7 @@ __global__ __launch_bounds__(kThreads, D == 64 ? 2 : 1) void bwd_rows_kernel(Bwd
   constexpr int kEarly = 4;
   uint2 early[kEarly];
 #pragma unroll
-  for (int e = 0; e < kEarly; ++e) early[e] = srclist[e * kListStride];
-  const uint2* rdlist = in_ws ? mylist : srclist;
-  if (SRC_CAP != kBwdCap && __ballot(in_ws) != 0ull) {
-#pragma unroll
-    for (int e = 0; e < kEarly; ++e) early[e] = rdlist[e * kListStride];
-  }
+  for (int e = 0; e < kEarly; ++e) early[e] = rdlist[e * kListStride];
   if (head_dense != 0) return;  // the tiled kernels own this head
 
   auto finish = [&](auto ne_tag) {
@@ -308,50 +253,47 @@ __global__ __launch_bounds__(kThreads, D == 64 ? 2 : 1) void bwd_rows_kernel(Bwd
 
 // ------------------------------------------------------------ key-major order
 
-// One workgroup per head, before the row kernel.  Counts, per key, the list entries that name it (a
-// superset of the entries with p > 0), and gives every key a segment of that size in the key-major
+// One workgroup per head, before the row kernel.  Counts, per key, the list entries that name it (the
+// entries with p > 0, and possibly a few whose p rounds to zero), and gives every key a segment of that size in the key-major
 // arrays: koffs = exclusive prefix sums of the counts.  The row kernel then places an entry at
 // koffs[key] + (arrival number from the key's cursor) -- no reordering pass.  Also: the head's flag (OR of
 // its block flags), zeroed cursors, and the list of keys whose segment exceeds kSortedKeyEntries.
 // counters: LDS when a head's keys fit (use_lds), else the kcount array itself.
 constexpr int kOffsThreads = 1024;
 
-// precounted: A.kcount already holds the counts (the forward's, read only): only the prefix sums are left.
-static __global__ __launch_bounds__(kOffsThreads) void key_offsets_kernel(BwdSparseArgs A, int src_cap, int use_lds,
-                                                                  int precounted) {
+static __global__ __launch_bounds__(kOffsThreads) void key_offsets_kernel(BwdSparseArgs A, int use_lds) {
   extern __shared__ int offs_lds[];
   int* part = offs_lds;                   // entries in the thread's range of keys
   int* partl = offs_lds + kOffsThreads;   // long segments in it
-  __shared__ int long_base;
   const Geom& g = A.g;
   const int bh = blockIdx.x, tid = threadIdx.x, Nk = g.Nk;
   {
     int any = 0;
     for (int k = tid; k < A.nqb; k += kOffsThreads) any |= A.block_flag[bh * A.nqb + k] != 0 ? 1 : 0;
     any = __syncthreads_or(any);
-    if (tid == 0) A.head_flag[bh] = any ? 1 : 0;
+    if (tid == 0) {
+      A.head_flag[bh] = any ? 1 : 0;
+      A.head_flag[g.B * g.H + bh] = 0;  // no long keys yet
+    }
     if (any) return;  // the tiled kernels own this head
   }
   int* gcount = A.kcount + (long long)bh * Nk;
-  int* cnt = (use_lds && !precounted) ? offs_lds + 2 * kOffsThreads : gcount;
-  if (!precounted) {
+  int* cnt = use_lds ? offs_lds + 2 * kOffsThreads : gcount;
   for (int j = tid; j < Nk; j += kOffsThreads) cnt[j] = 0;
   __syncthreads();
-  for (int hr = tid; hr < g.Nq * 2; hr += kOffsThreads) {
-    const int i = hr >> 1, hh = hr & 1;
-    const int v = A.lcnt[((long long)bh * g.Nq + i) * 2 + hh];
-    const int n = min(v & kListCountMask, kBwdCap);
-    const int qb = i / kBlockRows, wave = (i % kBlockRows) >> 5, lane = hh * 32 + (i & 31);
-    const uint2* src = (src_cap == kBwdCap || (v & kListInWorkspace) != 0)
-                           ? A.jlist + list_entry<kBwdCap>(bh, A.nqb, qb, wave, lane)
-                           : A.src_list + list_entry<kCandCap>(bh, A.nqb, qb, wave, lane);
+  // a lane of a row group per step: the 64 lanes of a slot are one 512-byte run of the list
+  for (int hr = tid; hr < A.nqb * kThreads; hr += kOffsThreads) {
+    const int qb = hr / kThreads, wave = (hr % kThreads) >> 6, lane = hr & 63;
+    const int i = qb * kBlockRows + wave * 32 + (lane & 31), hh = lane >> 5;
+    if (i >= g.Nq) continue;
+    const int n = min(A.lcnt[((long long)bh * g.Nq + i) * 2 + hh], kBwdCap);
+    const uint2* src = A.list + list_entry<kBwdCap>(bh, A.nqb, qb, wave, lane);
     for (int e = 0; e < n; ++e) {
       const unsigned key = src[e * kListStride].x;
       if (key < (unsigned)Nk) atomicAdd(&cnt[key], 1);
     }
   }
   __syncthreads();
-  }
   const int per = (Nk + kOffsThreads - 1) / kOffsThreads;
   const int beg = tid * per, end = min(Nk, beg + per);
   int s = 0, nl = 0;
@@ -372,19 +314,15 @@ static __global__ __launch_bounds__(kOffsThreads) void key_offsets_kernel(BwdSpa
     partl[tid] += vl;
     __syncthreads();
   }
-  // The key-major arrays hold kBwdCap entries per half row and head.  Counts taken from the rows' own
-  // support lists stay within that; the forward's candidate counts (precounted) can exceed it when the
-  // candidates far outnumber the supports: such a head is left to the tiled kernels.
+  // The key-major arrays hold kBwdCap entries per half row and head, and every list holds at most that many:
+  // the segments fit.  (Checked all the same: a head that would not fit is left to the tiled kernels.)
   if (part[kOffsThreads - 1] > g.Nq * 2 * kBwdCap) {
     if (tid == 0) A.head_flag[bh] = 1;
     return;
   }
-  // one list reservation per head
-  if (tid == kOffsThreads - 1)
-    long_base = partl[tid] > 0 ? atomicAdd(&A.head_flag[g.B * g.H + kLongCountOffset], partl[tid]) : 0;
-  __syncthreads();
+  if (tid == kOffsThreads - 1) A.head_flag[g.B * g.H + bh] = partl[tid];
   int run = part[tid] - s;
-  int lpos = long_base + partl[tid] - nl;
+  long long lpos = (long long)bh * Nk + partl[tid] - nl;
   for (int j = beg; j < end; ++j) {
     const int cj = cnt[j];
     A.koffs[(long long)bh * Nk + j] = run;
@@ -493,10 +431,26 @@ __device__ __forceinline__ void bwd_long_keys_part(const BwdSparseArgs& A, int v
   constexpr int PER = D / 64;
   const Geom& g = A.g;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-  // persistent workgroups: the waves share out the list key_offsets_kernel made
-  const int nlong = __builtin_amdgcn_readfirstlane(A.head_flag[g.B * g.H + kLongCountOffset]);
-  for (int idx = vblock * kWaves + wave; idx < nlong; idx += vgrid * kWaves) {
-  const long long key = __builtin_amdgcn_readfirstlane(A.long_keys[idx]);
+  // Persistent workgroups: the waves share out the per-head lists key_offsets_kernel made.  The heads' list
+  // lengths are fetched 64 at a time (one load per lane); their running sums number the long keys of these 64
+  // heads consecutively, and the waves take those numbers in turn.
+  const int nheads = g.B * g.H;
+  for (int h0 = 0; h0 < nheads; h0 += 64) {
+  const int my_count = (h0 + lane < nheads) ? A.head_flag[nheads + h0 + lane] : 0;
+  int my_end = my_count;  // inclusive running sum over the lanes
+#pragma unroll
+  for (int sft = 1; sft < 64; sft <<= 1) {
+    const int up = __shfl_up(my_end, sft);
+    if (lane >= sft) my_end += up;
+  }
+  const int ntotal = __builtin_amdgcn_readlane(my_end, 63);
+  for (int gidx = vblock * kWaves + wave; gidx < ntotal; gidx += vgrid * kWaves) {
+  {
+  // the head whose range holds gidx: the first lane whose running sum exceeds it
+  const int hu = __builtin_amdgcn_readfirstlane(__builtin_popcountll(__ballot(my_end <= gidx)));
+  const int lbh = h0 + hu;
+  const int idx = gidx - (__builtin_amdgcn_readlane(my_end, hu) - __builtin_amdgcn_readlane(my_count, hu));
+  const long long key = __builtin_amdgcn_readfirstlane(A.long_keys[(long long)lbh * g.Nk + idx]);
   const int n = __builtin_amdgcn_readfirstlane(min(A.kcursor[key], A.kcount[key]));
   const int bh = (int)(key / g.Nk), j = (int)(key % g.Nk);
   const int b = bh / g.H, h = bh % g.H;
@@ -553,6 +507,8 @@ __device__ __forceinline__ void bwd_long_keys_part(const BwdSparseArgs& A, int v
   for (int t = 0; t < PER; ++t) {
     Elem<T>::store(A.dV, o + lane + 64 * t, av[t]);
     Elem<T>::store(A.dK, o + lane + 64 * t, ak[t]);
+  }
+  }
   }
   }
 }

@@ -9,9 +9,8 @@ constexpr int kWaves = 4;
 constexpr int kBlockRows = 128;  // rows (queries or keys) owned by a workgroup: 32 per wave
 
 constexpr int kCandCap = 32;     // candidate entries per lane = per half row (forward lists)
-constexpr int kBwdCap = 16;      // support entries per lane = per half row (backward lists)
+constexpr int kBwdCap = 16;      // support entries per lane = per half row (the lists the backward works from)
 constexpr int kListStride = 64;  // lists are stored slot-major per wave: entry s of the 64 lanes together
-constexpr int kLongCountOffset = 64;  // the long-key counter sits in a cache line of its own, away from the flags
 
 // Sweep scratch of the list kernels: CAP cells of (4 raw scores, first key) per thread.
 constexpr int kCellGroups = 1;  // 4-key accumulator groups per cell

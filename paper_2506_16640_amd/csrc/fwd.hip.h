@@ -30,8 +30,7 @@ struct FwdArgs {
   unsigned long long* stats;
   int nqb;         // query blocks per head
   int mask_words;  // uint32 words of one wave's tile mask
-  const int* dense_flag;  // NULL: run every workgroup; else [B*H*nqb], run only where the flag is set
-  const int* head_flag;   // NULL, or [B*H]: 0 means no workgroup of the head is flagged
+  const int* dense_flag;  // NULL: run every block; else [B*H*nqb], run only the blocks whose flag is set
 };
 
 constexpr int kMaxSolveIters = 48;
@@ -154,7 +153,6 @@ __device__ __forceinline__ void fwd_block(const FwdArgs& A, int bh_, int blk_, c
   const float r = 1.0f / (g.alpha - 1.0f);
   float* tau_out = A.tau + (long long)q.bh * g.Nq;
   const long long o_base = (long long)q.b * g.q_sb + (long long)q.h * g.q_sh;
-  if (A.dense_flag && __builtin_amdgcn_readfirstlane(A.dense_flag[q.bh * A.nqb + q.qb]) == 0) return;
 
   if (q.block_lim == 0) {  // no row of this workgroup sees any key
     for (int e = q.tid; e < kBlockRows * D; e += kThreads) {
@@ -322,7 +320,7 @@ __device__ __forceinline__ void fwd_block(const FwdArgs& A, int bh_, int blk_, c
   if (q.valid && q.hh == 0) tau_out[q.i] = live ? tau : 0.f;
 
   if (A.stats && q.lane == 0) {
-    if (!A.dense_flag) atomicAdd(&A.stats[ENTMAX_STAT_FWD_TILES_VISIBLE], (unsigned long long)n_vis);
+    atomicAdd(&A.stats[ENTMAX_STAT_FWD_TILES_VISIBLE], (unsigned long long)n_vis);
     atomicAdd(&A.stats[ENTMAX_STAT_FWD_QK_MAX], (unsigned long long)n_vis);
     atomicAdd(&A.stats[ENTMAX_STAT_FWD_QK_SOLVE], (unsigned long long)n_qk_solve);
     atomicAdd(&A.stats[ENTMAX_STAT_FWD_QK_PV], (unsigned long long)n_qk_pv);
@@ -339,11 +337,11 @@ template <typename T, int D, int AM>
 __global__ __launch_bounds__(kThreads) void fwd_kernel(FwdArgs A) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const PairItem it = pair_item(A.nqb);
-  if (A.head_flag && __builtin_amdgcn_readfirstlane(A.head_flag[it.bh]) == 0) return;
   for (int part = 0; part < 2; ++part) {
     const int blk = part ? it.second : it.first;
     if (blk < 0) break;
-    if (part) __syncthreads();
+    if (A.dense_flag && __builtin_amdgcn_readfirstlane(A.dense_flag[it.bh * A.nqb + blk]) == 0) continue;
+    __syncthreads();
     fwd_block<T, D, AM>(A, it.bh, blk, smem);
   }
 }

@@ -16,10 +16,13 @@
 //     3. the threshold by the same safeguarded steps as the tiled kernel
 //        (closed-form local-model root for alpha 1.5 / 2, Halley / Newton
 //        otherwise), summing over the list instead of over key tiles;
-//     4. O_i = sum over the list of p_ij v_j, gathering the few value rows.
+//     4. O_i = sum over the list of p_ij v_j, gathering the few value rows; for the
+//        backward, the entries with p_ij > 0 are written out as the row's support list.
 // A workgroup that meets a row with more candidates than a list holds raises
 // its flag and leaves the whole block to the tiled kernel (fwd.hip.h), which
 // handles any density.
+// Also here: what the other list kernels share (bwd_sparse.hip.h, decode.hip.h): the
+// slot-major list layout, the collect sweep, row gather helpers.
 #pragma once
 #include "fwd.hip.h"
 
@@ -32,7 +35,8 @@ namespace entmax {
 template <int CAP>
 __device__ __forceinline__ long long list_entry(int bh, int nqb, int qb, int wave, int lane) {
   return (((long long)bh * nqb + qb) * kWaves + wave) * CAP * kListStride + lane;
-}  // candidates per lane = per half row; a row holds up to 2 * kCandCap
+}
+
 
 struct FwdSparseArgs {
   Geom g;
@@ -42,13 +46,13 @@ struct FwdSparseArgs {
   void* O;
   float* tau;
   uint2* cand;      // [B*H*nqb*4 waves][kCandCap][64 lanes] (key index, raw dot product bits), see list_entry()
-  int* kcand;       // NULL, or [B*H*Nk] pre-zeroed: per key, the number of list entries that name it (for the
-                    // backward's key-major layout), counted as the lists are written
+  uint2* list;      // NULL, or [B*H*nqb*4 waves][kBwdCap][64 lanes]: the rows' supports for the backward
+  int* slcnt;       // with list: [B*H*Nq][2] support entries per half row
+  int* bwd_flag;    // with list: [B*H*nqb] 1: the backward cannot take its list path for this block
   void* cells;      // sweep scratch: one CellBuf<kCandCap> per workgroup of the list sweep's grid
   int* lcnt;        // [B*H*Nq][2] list lengths
   float2* bounds;   // [B*H*Nq] (tau_lb, right end of the bracket)
   int* dense_flag;  // [B*H*nqb] 1: block left to the tiled kernel
-  int* head_flag;   // [B*H] written by fwd_finish_kernel: 1 when some block of the head is left to the tiled kernel
   unsigned long long* stats;
   int nqb;
 };
@@ -80,7 +84,7 @@ struct CellBuf {
 template <typename C, typename T, int D, int CAP>
 __device__ __forceinline__ bool collect_sweep(const C& q, const Geom& g, const void* K, char* tiles, int* ovf, bool live,
                                               float thr, void* cells, uint2* mylist, int& cnt, unsigned& n_qk,
-                                              unsigned& n_cand_tiles, int* kcand = nullptr) {
+                                              unsigned& n_cand_tiles) {
   constexpr int KT = C::KT, NSB = C::NSB;
   // candidates are the keys with a * dot > thr: in raw units, dot > cut.  Rounding may move a key that
   // sits on the threshold (probability ~ 0) in or out of the list; the consumers recompute its value.
@@ -176,7 +180,6 @@ __device__ __forceinline__ bool collect_sweep(const C& q, const Geom& g, const v
           for (int rr = 0; rr < 4; ++rr) {
             if (dv[rr] > cut && cnt < CAP) {
               mylist[cnt * kListStride] = make_uint2((unsigned)(jc + 8 * u + rr), __float_as_uint(dv[rr]));
-              if (kcand) atomicAdd(&kcand[(long long)q.bh * g.Nk + jc + 8 * u + rr], 1);
               ++cnt;
             }
           }
@@ -185,6 +188,33 @@ __device__ __forceinline__ bool collect_sweep(const C& q, const Geom& g, const v
     }
   }
   return fits;
+}
+
+// Lower bound of the threshold from the two-element sub-problem {y1 >= y2} (y = (alpha-1) s) and the left
+// end y1 - 1 of the bracket of App. A eq. (bounds).  alpha 1.5 and 2: closed forms.  Other alpha: Newton steps
+// on f(t) = (y1-t)^r + [y2-t]_+^r - 1 from t = y1 - 1, where f >= 0: f is convex and decreasing, so the
+// iterates rise towards the root and stay on its left -- each of them is a valid bound.
+template <int AM>
+__device__ __forceinline__ float two_key_bound(float y1, float y2, float r) {
+  float lo = y1 - 1.0f;
+  const float dlt = y1 - y2;
+  if (!(dlt < 1.0f)) return lo;  // y2 is zero already at the left end (also y2 = -inf)
+  if (AM == 2) return fmaxf(lo, 0.5f * (y1 + y2 - 1.0f));
+  float t = lo;
+  if (AM == 1) {
+    // closed form; the hardware square root is good to an ulp, which the step back below covers
+    t = 0.5f * (y1 + y2) - __builtin_amdgcn_sqrtf(0.5f * (1.0f - 0.5f * dlt * dlt));
+    return fmaxf(lo, t - 4e-6f * fmaxf(1.0f, fabsf(t)));
+  }
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    const float x1 = y1 - t, x2 = fmaxf(y2 - t, 0.f);
+    const float f = pow_r<AM>(x1, r) + pow_r<AM>(x2, r) - 1.0f;
+    const float fp = r * (pow_rm1<AM>(x1, r) + pow_rm1<AM>(x2, r));
+    t += fmaxf(f, 0.f) / fp;  // fp >= r x1^(r-1) > 0 while t < y1
+  }
+  // rounding may carry the last iterate a few ulps past the root: step back by more than that
+  return fmaxf(lo, t - 4e-6f * fmaxf(1.0f, fabsf(t)));
 }
 
 template <typename T, int D, int AM>
@@ -260,18 +290,14 @@ __device__ __forceinline__ void fwd_lists_block(const FwdSparseArgs& A, int bh_,
   const float y1 = live ? q.a * m1 : 0.f;
   float lo = y1 - 1.0f;  // App. A eq. (bounds), left end
   float hi = live ? y1 - __builtin_amdgcn_exp2f(-(g.alpha - 1.0f) * __builtin_amdgcn_logf((float)q.lim)) : 0.f;
-  if (live && m2 > -kInf) {
-    // two-element sub-problem {y1, y2}: its threshold is a lower bound of the row's
-    float y2 = q.a * m2, dlt = y1 - y2;
-    if (AM == 1 && dlt < 1.0f) lo = fmaxf(lo, 0.5f * (y1 + y2) - sqrtf(0.5f * (1.0f - 0.5f * dlt * dlt)));
-    if (AM == 2 && dlt < 1.0f) lo = fmaxf(lo, 0.5f * (y1 + y2 - 1.0f));
-  }
+  // two-element sub-problem {y1, y2}: its threshold is a lower bound of the row's
+  if (live && m2 > -kInf) lo = two_key_bound<AM>(y1, q.a * m2, 1.0f / (g.alpha - 1.0f));
   lo = fminf(lo, hi);
 
   // ---------------------------------------------- 2. candidate lists at tau_lb
   uint2* mylist = A.cand + list_entry<kCandCap>(q.bh, A.nqb, q.qb, q.wave, q.lane);
   int cnt = 0;
-  const bool fits = collect_sweep<C, T, D, kCandCap>(q, g, A.K, tiles, ovf, live, lo, A.cells, mylist, cnt, n_qk2, n_cand_tiles, A.kcand);
+  const bool fits = collect_sweep<C, T, D, kCandCap>(q, g, A.K, tiles, ovf, live, lo, A.cells, mylist, cnt, n_qk2, n_cand_tiles);
   if (!fits) {
     if (q.tid == 0) A.dense_flag[flag_idx] = 1;
   } else {
@@ -381,13 +407,6 @@ __global__ __launch_bounds__(kThreads) void fwd_finish_kernel(FwdSparseArgs A) {
   const Geom& g = A.g;
   RowLane rl;
   rl.init(g, A.nqb);
-  if (rl.qb == 0 && threadIdx.x < 64) {
-    // first workgroup of the head: OR of the head's block flags, for the kernels that follow
-    bool any = false;
-    for (int k = threadIdx.x; k < A.nqb; k += 64) any = any || A.dense_flag[rl.bh * A.nqb + k] != 0;
-    const bool head_any = __ballot(any) != 0ull;
-    if (threadIdx.x == 0) A.head_flag[rl.bh] = head_any ? 1 : 0;
-  }
   // (the flag is tested further down: every load that does not depend on another is issued first)
   const int block_dense = A.dense_flag[rl.bh * A.nqb + rl.qb];
   constexpr int DH = D / 2;
@@ -412,13 +431,18 @@ __global__ __launch_bounds__(kThreads) void fwd_finish_kernel(FwdSparseArgs A) {
   uint2 early[kEarly];
 #pragma unroll
   for (int e = 0; e < kEarly; ++e) early[e] = mylist[e * kListStride];
-  if (block_dense != 0) return;  // the tiled kernel owns this block
+  if (block_dense != 0) {  // the tiled kernel owns this block (and the backward's tiled kernels its head)
+    if (A.list && threadIdx.x == 0) A.bwd_flag[rl.bh * A.nqb + rl.qb] = 1;
+    return;
+  }
+  uint2* suplist = A.list ? A.list + list_entry<kBwdCap>(rl.bh, A.nqb, rl.qb, threadIdx.x >> 6, threadIdx.x & 63) : nullptr;
+  int scnt = 0;  // support entries of this half row
 
   // NE: list entries per lane held in registers; chosen per wave from the longest list it holds.
   // (Same sums in the same order whichever NE is chosen: entry order.)
   auto finish = [&](auto ne_tag) {
     constexpr int NE = decltype(ne_tag)::value;
-    float yv[NE];
+    float yv[NE], dvv[NE];
     unsigned jv[NE];
 #pragma unroll
     for (int e = 0; e < NE; ++e) {
@@ -428,7 +452,8 @@ __global__ __launch_bounds__(kThreads) void fwd_finish_kernel(FwdSparseArgs A) {
       else if (e < cnt)
         en = mylist[e * kListStride];
       jv[e] = (e < cnt) ? en.x : 0u;
-      yv[e] = (e < cnt) ? a * __uint_as_float(en.y) : -kInf;  // -inf: never positive
+      dvv[e] = __uint_as_float(en.y);
+      yv[e] = (e < cnt) ? a * dvv[e] : -kInf;  // -inf: never positive
     }
     // entries beyond the NE held in registers (few lanes) are read again wherever they are needed
     const bool has_tail = __ballot(cnt > NE) != 0ull;
@@ -451,10 +476,15 @@ __global__ __launch_bounds__(kThreads) void fwd_finish_kernel(FwdSparseArgs A) {
     for (int t = 0; t < DH; ++t) oacc[t] = 0.f;
 #pragma unroll
     for (int e = 0; e < NE; ++e) {
-      float p_own = live ? pow_r<AM>(fmaxf(yv[e] - tau, 0.f), r) : 0.f;
+      // (the same expression as the backward's row kernel, so that both sides agree on the support)
+      float p_own = (live && e < cnt) ? pow_r<AM>(fmaxf(fmaf(dvv[e], a, -tau), 0.f), r) : 0.f;
       float p_oth = __shfl_xor(p_own, 32);
       unsigned j_oth = (unsigned)__shfl_xor((int)jv[e], 32);
-      if (p_own > 0.f) ++n_support;
+      if (p_own > 0.f) {
+        ++n_support;
+        if (suplist && scnt < kBwdCap) suplist[scnt * kListStride] = make_uint2(jv[e], __float_as_uint(dvv[e]));
+        ++scnt;
+      }
 #pragma unroll
       for (int src = 0; src < 2; ++src) {
         // both lanes of the pair take the same entry: entry e of the lane whose half index is src
@@ -473,10 +503,14 @@ __global__ __launch_bounds__(kThreads) void fwd_finish_kernel(FwdSparseArgs A) {
       for (int e = NE; __ballot(e < cnt) != 0ull; ++e) {
         uint2 en = make_uint2(0u, 0u);
         if (e < cnt) en = mylist[e * kListStride];
-        float p_own = (live && e < cnt) ? pow_r<AM>(fmaxf(a * __uint_as_float(en.y) - tau, 0.f), r) : 0.f;
+        float p_own = (live && e < cnt) ? pow_r<AM>(fmaxf(fmaf(__uint_as_float(en.y), a, -tau), 0.f), r) : 0.f;
         float p_oth = __shfl_xor(p_own, 32);
         unsigned j_oth = (unsigned)__shfl_xor((int)en.x, 32);
-        if (p_own > 0.f) ++n_support;
+        if (p_own > 0.f) {
+          ++n_support;
+          if (suplist && scnt < kBwdCap) suplist[scnt * kListStride] = en;
+          ++scnt;
+        }
 #pragma unroll
         for (int src = 0; src < 2; ++src) {
           float p = (rl.hh == src) ? p_own : p_oth;
@@ -495,6 +529,7 @@ __global__ __launch_bounds__(kThreads) void fwd_finish_kernel(FwdSparseArgs A) {
                 (long long)rl.i * g.q_sn + rl.hh * DH;
       store_row<T>(orow, DH, oacc);
       if (rl.hh == 0) A.tau[row_idx] = live ? tau : 0.f;
+      if (A.list) A.slcnt[row_idx * 2 + rl.hh] = min(scnt, kBwdCap);
     }
   };
   if (__ballot(cnt > 4) == 0ull)
@@ -502,6 +537,11 @@ __global__ __launch_bounds__(kThreads) void fwd_finish_kernel(FwdSparseArgs A) {
   else
     finish(std::integral_constant<int, 8>());
 
+  if (A.list) {
+    // a support longer than the backward's lists hold sends the block's head to the backward's tiled kernels
+    const int any_long = __syncthreads_or(scnt > kBwdCap ? 1 : 0);
+    if (threadIdx.x == 0) A.bwd_flag[rl.bh * A.nqb + rl.qb] = any_long ? 1 : 0;
+  }
   if (A.stats) {
     unsigned sup = n_support, cands = (unsigned)cnt;
     for (int s = 32; s > 0; s >>= 1) {

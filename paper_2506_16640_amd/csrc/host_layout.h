@@ -23,9 +23,9 @@ struct Layout {
   int mask_words;     // uint32 words covering the 32-key blocks of a head
   long long q_sb, q_sh, q_sn, kv_sb, kv_sh, kv_sn;
   // workspace offsets
-  size_t off_vt, off_cand, off_flcnt, off_bounds, off_flags, off_kt, off_qt, off_dot, off_mu, off_crow, off_dscale, off_mask,
-      off_jlist, off_lcnt, off_kcount, off_koffs, off_kcursor, off_csc_i, off_csc_pw, off_hflag, off_longkeys, off_fcells, off_bcells, sv_cand, sv_lcnt, sv_flags, sv_kcand, total_saved, total_fwd,
-      total_bwd;
+  size_t off_vt, off_cand, off_flcnt, off_bounds, off_flags, off_fcells, off_kt, off_qt, off_dot, off_mu, off_crow, off_dscale, off_mask, off_jlist, off_lcnt,
+      off_kcount, off_koffs, off_kcursor, off_csc_i, off_csc_pw, off_hflag, off_longkeys, off_bcells, sv_list, sv_lcnt,
+      sv_flags, total_saved, total_fwd, total_bwd;
   size_t off_dec_cmax;  // decode kernels: score rows at offset 0, then the chunk maxima
   int dec_nks, dec_nchunks, dec_chunk;
   long long csc_cap;    // entries of the key-major arrays per head
@@ -83,22 +83,23 @@ inline Layout make_layout(const entmax_attn_params* p) {
   size_t qt_bytes = align_up(bh * p->D * (size_t)L.npad_q * L.esize);
   size_t row_bytes = align_up(bh * (size_t)p->Nq * sizeof(float));
   size_t mask_bytes = align_up(bh * (size_t)L.nqg * L.mask_words * sizeof(uint32_t));
-  // forward: V^T copy | candidate lists | per-workgroup and per-head fallback flags
+  // forward: V^T copy (tiled kernel only) | candidate lists (one per lane of the list grid), their lengths, the
+  // rows' brackets | per-block fallback flags | the list sweep's cell strips
+  const size_t list_groups = bh * (size_t)((L.nqb + 1) / 2);  // workgroups of the list sweeps
   L.off_vt = 0;
   L.off_cand = kt_bytes;
-  size_t cand_bytes = align_up(bh * (size_t)L.nqb * kThreads * kCandCap * 8);  // one list per lane of the list grid
-  // the `saved` buffer: the same three arrays, for the backward
-  L.sv_cand = 0;
-  L.sv_lcnt = cand_bytes;
-  L.sv_flags = L.sv_lcnt + align_up(bh * (size_t)p->Nq * 2 * sizeof(int));
-  L.sv_kcand = L.sv_flags + align_up(bh * (size_t)L.nqb * sizeof(int));
-  L.total_saved = L.sv_kcand + align_up(bh * (size_t)p->Nk * sizeof(int));
-  L.off_flcnt = L.off_cand + cand_bytes;
+  L.off_flcnt = L.off_cand + align_up(bh * (size_t)L.nqb * kThreads * kCandCap * 8);
   L.off_bounds = L.off_flcnt + align_up(bh * (size_t)p->Nq * 2 * sizeof(int));
   L.off_flags = L.off_bounds + align_up(bh * (size_t)p->Nq * 2 * sizeof(float));
-  L.off_fcells = L.off_flags + align_up((bh * (size_t)L.nqb + bh + 1) * sizeof(int));
-  const size_t list_groups = bh * (size_t)((L.nqb + 1) / 2);  // workgroups of the list sweeps
+  L.off_fcells = L.off_flags + align_up(bh * (size_t)L.nqb * sizeof(int));
   L.total_fwd = L.off_fcells + align_up(list_groups * cell_bytes_per_workgroup(kCandCap));
+  // the `saved` buffer: the rows' support lists (kBwdCap slots per lane of every 128-row block, slot-major per
+  // 32-row group), their lengths, and one flag per block for the backward
+  const size_t list_bytes = align_up(bh * (size_t)L.nqb * kThreads * kBwdCap * 8);
+  L.sv_list = 0;
+  L.sv_lcnt = list_bytes;
+  L.sv_flags = L.sv_lcnt + align_up(bh * (size_t)p->Nq * 2 * sizeof(int));
+  L.total_saved = L.sv_flags + align_up(bh * (size_t)L.nqb * sizeof(int));
   // the decode kernels' score rows take the place of everything above
   L.dec_nks = L.dec_nchunks = L.dec_chunk = 0;
   L.off_dec_cmax = 0;
@@ -128,7 +129,7 @@ inline Layout make_layout(const entmax_attn_params* p) {
   // support-list backward
   size_t rows = bh * (size_t)p->Nq;
   L.off_jlist = o;
-  o += align_up(bh * (size_t)L.nqb * kThreads * kBwdCap * 8);
+  o += list_bytes;
   L.off_lcnt = o;
   o += align_up(rows * 2 * sizeof(int));
   size_t key_bytes = align_up(bh * (size_t)p->Nk * sizeof(int));
@@ -145,7 +146,7 @@ inline Layout make_layout(const entmax_attn_params* p) {
   L.off_csc_pw = o;
   o += align_up(rows * 2 * kBwdCap * 2 * sizeof(float));
   L.off_hflag = o;
-  o += align_up((bh * (size_t)L.nqb + bh + kLongCountOffset + 1) * sizeof(int));  // block flags, head flags, counter
+  o += align_up((bh * (size_t)L.nqb + 2 * bh) * sizeof(int));  // block flags, head flags, long-key counts per head
   L.off_longkeys = o;
   o += key_bytes;
   L.off_bcells = o;

@@ -112,12 +112,13 @@ bool fill_words(void* p, size_t bytes, uint32_t value, hipStream_t st) {
 bool zero_words(void* p, size_t bytes, hipStream_t st) { return fill_words(p, bytes, 0u, st); }
 
 template <typename T, int D>
-bool launch_transposes(const TransposeJobs& jobs, int njobs, int B, int H, hipStream_t st, const int* head_flag = nullptr) {
+bool launch_transposes(const TransposeJobs& jobs, int njobs, int B, int H, hipStream_t st, const int* head_flag = nullptr,
+                       const int* block_flag = nullptr, int nqb = 0) {
   int npad = 0;
   for (int k = 0; k < njobs; ++k) npad = jobs.job[k].npad > npad ? jobs.job[k].npad : npad;
   if (npad == 0) return true;
   dim3 grid((unsigned)(npad / 64), (unsigned)(B * H), (unsigned)njobs);
-  hipLaunchKernelGGL((transpose_perm_kernel<T, D>), grid, dim3(kThreads), 0, st, jobs, H, head_flag);
+  hipLaunchKernelGGL((transpose_perm_kernel<T, D>), grid, dim3(kThreads), 0, st, jobs, H, head_flag, block_flag, nqb);
   return launch_ok();
 }
 

@@ -32,28 +32,24 @@ bool launch_bwd_kernels(const BwdArgs& a, const Layout& L, int B, int H, hipStre
 template <typename T, int D, int AM>
 bool launch_bwd_rows(const BwdSparseArgs& a, int nblocks, hipStream_t st, void* const* ev, bool from_saved) {
   const dim3 row_grid((unsigned)(a.g.B * a.g.H * a.nqb));
-  if (from_saved) {
-    hipLaunchKernelGGL(bwd_prepare_kernel<D>, row_grid, dim3(kThreads), 0, st, a);
-  } else {
+  if (!from_saved) {
+    // no lists from the forward: one Q K^T sweep at tau rebuilds the supports
     size_t smem = 2 * (size_t)QCtx<T, D, FwdTile<T>::value>::kTileBytes + 64;
     hipLaunchKernelGGL((bwd_lists_kernel<T, D, AM>), dim3((unsigned)nblocks), dim3(kThreads), smem, st, a);
+    if (!launch_ok()) return false;
   }
-  if (!launch_ok()) return false;
   record(ev, ENTMAX_BWD_PHASE_LISTS + 1, st);
   {
     // per-key counters in LDS when a head's keys fit beside the scan arrays
     const size_t scan_bytes = 2 * (size_t)kOffsThreads * sizeof(int);
-    const bool use_lds = !from_saved && scan_bytes + (size_t)a.g.Nk * sizeof(int) <= 150 * 1024;
+    const bool use_lds = scan_bytes + (size_t)a.g.Nk * sizeof(int) <= 150 * 1024;
     const size_t smem = scan_bytes + (use_lds ? (size_t)a.g.Nk * sizeof(int) : 0);
     if (!ensure_dynamic_lds<key_offsets_kernel>(smem)) return false;
     hipLaunchKernelGGL(key_offsets_kernel, dim3((unsigned)(a.g.B * a.g.H)), dim3(kOffsThreads), smem, st, a,
-                       from_saved ? kCandCap : kBwdCap, use_lds ? 1 : 0, from_saved ? 1 : 0);
+                       use_lds ? 1 : 0);
     if (!launch_ok()) return false;
   }
-  if (from_saved)
-    hipLaunchKernelGGL((bwd_rows_kernel<T, D, AM, kCandCap>), row_grid, dim3(kThreads), 0, st, a);
-  else
-    hipLaunchKernelGGL((bwd_rows_kernel<T, D, AM, kBwdCap>), row_grid, dim3(kThreads), 0, st, a);
+  hipLaunchKernelGGL((bwd_rows_kernel<T, D, AM>), row_grid, dim3(kThreads), 0, st, a);
   return launch_ok();
 }
 
@@ -100,19 +96,17 @@ int run_bwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
       sa.dK = dK;
       sa.dV = dV;
       sa.dscale = dscale;
-      sa.jlist = reinterpret_cast<uint2*>(ws + L.off_jlist);
+      // the forward's lists, lengths and flags are only read (the list kernel that writes them is not launched)
+      char* sv = const_cast<char*>(saved);
+      sa.list = reinterpret_cast<uint2*>(saved ? sv + L.sv_list : ws + L.off_jlist);
+      sa.lcnt = reinterpret_cast<int*>(saved ? sv + L.sv_lcnt : ws + L.off_lcnt);
+      sa.block_flag = saved ? reinterpret_cast<int*>(sv + L.sv_flags) : block_flag;
       sa.cells = ws + L.off_bcells;
       sa.kcursor = reinterpret_cast<int*>(ws + L.off_kcursor);
-      sa.lcnt = reinterpret_cast<int*>(ws + L.off_lcnt);
-      sa.src_list = saved ? reinterpret_cast<const uint2*>(saved + L.sv_cand) : sa.jlist;
-      sa.src_lcnt = saved ? reinterpret_cast<const int*>(saved + L.sv_lcnt) : nullptr;
-      sa.src_dense = saved ? reinterpret_cast<const int*>(saved + L.sv_flags) : nullptr;
-      // with the forward's lists come the forward's per-key counts (read only here)
-      sa.kcount = saved ? reinterpret_cast<int*>(const_cast<char*>(saved) + L.sv_kcand) : reinterpret_cast<int*>(ws + L.off_kcount);
+      sa.kcount = reinterpret_cast<int*>(ws + L.off_kcount);
       sa.koffs = reinterpret_cast<int*>(ws + L.off_koffs);
       sa.csc_i = reinterpret_cast<int*>(ws + L.off_csc_i);
       sa.csc_pw = reinterpret_cast<float2*>(ws + L.off_csc_pw);
-      sa.block_flag = block_flag;
       sa.head_flag = head_flag;
       sa.long_keys = reinterpret_cast<int*>(ws + L.off_longkeys);
       sa.stats = reinterpret_cast<unsigned long long*>(stats);

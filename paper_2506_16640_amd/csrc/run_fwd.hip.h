@@ -106,11 +106,10 @@ int run_fwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
     return ENTMAX_ATTN_OK;
   }
   void* Vt = ws + L.off_vt;
-  // with a `saved` buffer the lists, their lengths and the block flags are written there
-  int* dense_flag = reinterpret_cast<int*>(saved ? saved + L.sv_flags : ws + L.off_flags);
-  int* head_flag = reinterpret_cast<int*>(ws + L.off_flags) + (size_t)p->B * p->H * L.nqb;
-  const int nblocks = p->B * p->H * ((L.nqb + 1) / 2);  // workgroups take query blocks in pairs
+  int* dense_flag = reinterpret_cast<int*>(ws + L.off_flags);  // [B*H*nqb] blocks left to the tiled kernel
+  const int npairs = p->B * p->H * ((L.nqb + 1) / 2);  // workgroups that take query blocks in pairs
   const bool lists = p->path == 0;
+  record(ev, ENTMAX_FWD_PHASE_PREPARE + 1, st);
   if (lists) {
     FwdSparseArgs sa;
     sa.g = make_geom(p, L, beta, gamma);
@@ -119,29 +118,30 @@ int run_fwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
     sa.V = V;
     sa.O = O;
     sa.tau = tau;
-    sa.cand = reinterpret_cast<uint2*>(saved ? saved + L.sv_cand : ws + L.off_cand);
+    sa.cand = reinterpret_cast<uint2*>(ws + L.off_cand);
     sa.cells = ws + L.off_fcells;
-    sa.lcnt = reinterpret_cast<int*>(saved ? saved + L.sv_lcnt : ws + L.off_flcnt);
-    sa.kcand = saved ? reinterpret_cast<int*>(saved + L.sv_kcand) : nullptr;
-    if (sa.kcand && !zero_words(sa.kcand, (size_t)p->B * p->H * p->Nk * sizeof(int), st)) return ENTMAX_ATTN_LAUNCH_FAILED;
-    record(ev, ENTMAX_FWD_PHASE_PREPARE + 1, st);
+    sa.lcnt = reinterpret_cast<int*>(ws + L.off_flcnt);
     sa.bounds = reinterpret_cast<float2*>(ws + L.off_bounds);
+    // with a `saved` buffer the rows' supports are listed for the backward
+    sa.list = saved ? reinterpret_cast<uint2*>(saved + L.sv_list) : nullptr;
+    sa.slcnt = saved ? reinterpret_cast<int*>(saved + L.sv_lcnt) : nullptr;
+    sa.bwd_flag = saved ? reinterpret_cast<int*>(saved + L.sv_flags) : nullptr;
     sa.dense_flag = dense_flag;
-    sa.head_flag = head_flag;
     sa.stats = reinterpret_cast<unsigned long long*>(stats);
     sa.nqb = L.nqb;
-    if (!launch_fwd_sparse_am<T, D>(sa, alpha_mode(p->alpha), nblocks, st, ev)) return ENTMAX_ATTN_LAUNCH_FAILED;
+    if (!launch_fwd_sparse_am<T, D>(sa, alpha_mode(p->alpha), npairs, st, ev)) return ENTMAX_ATTN_LAUNCH_FAILED;
   } else {
     // no lists: tell the backward that every block belongs to its tiled kernels
-    if (saved && !fill_words(dense_flag, (size_t)p->B * p->H * L.nqb * sizeof(int), 1u, st)) return ENTMAX_ATTN_LAUNCH_FAILED;
-    record(ev, ENTMAX_FWD_PHASE_PREPARE + 1, st);
+    if (saved && !fill_words(saved + L.sv_flags, (size_t)p->B * p->H * L.nqb * sizeof(int), 1u, st))
+      return ENTMAX_ATTN_LAUNCH_FAILED;
     record(ev, ENTMAX_FWD_PHASE_LISTS + 1, st);
   }
   record(ev, ENTMAX_FWD_PHASE_FINISH + 1, st);
   {
     TransposeJobs jobs{};
     jobs.job[0] = transpose_job(V, L.kv_sb, L.kv_sh, L.kv_sn, p->Nk, L.npad_k, Vt);
-    if (!launch_transposes<T, D>(jobs, 1, p->B, p->H, st, lists ? head_flag : nullptr)) return ENTMAX_ATTN_LAUNCH_FAILED;
+    if (!launch_transposes<T, D>(jobs, 1, p->B, p->H, st, nullptr, lists ? dense_flag : nullptr, L.nqb))
+      return ENTMAX_ATTN_LAUNCH_FAILED;
   }
   record(ev, ENTMAX_FWD_PHASE_TRANSPOSE + 1, st);
   FwdArgs a;
@@ -155,8 +155,7 @@ int run_fwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
   a.nqb = L.nqb;
   a.mask_words = L.mask_words;
   a.dense_flag = lists ? dense_flag : nullptr;
-  a.head_flag = lists ? head_flag : nullptr;
-  if (!launch_fwd_am<T, D>(a, alpha_mode(p->alpha), nblocks, st)) return ENTMAX_ATTN_LAUNCH_FAILED;
+  if (!launch_fwd_am<T, D>(a, alpha_mode(p->alpha), npairs, st)) return ENTMAX_ATTN_LAUNCH_FAILED;
   record(ev, ENTMAX_FWD_PHASE_TILED + 1, st);
   return ENTMAX_ATTN_OK;
 }

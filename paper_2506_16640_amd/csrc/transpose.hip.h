@@ -22,12 +22,20 @@ struct TransposeJobs {
 };
 
 template <typename T, int D>
-__global__ __launch_bounds__(kThreads) void transpose_perm_kernel(TransposeJobs jobs, int H, const int* head_flag) {
+// head_flag (one per head) or block_flag (nqb per head), when given, say whether any consumer needs the
+// head's copies: without a set flag the workgroup returns at once.
+__global__ __launch_bounds__(kThreads) void transpose_perm_kernel(TransposeJobs jobs, int H, const int* head_flag,
+                                                                 const int* block_flag, int nqb) {
   constexpr int kPad = sizeof(T) == 2 ? 2 : 1;
   __shared__ T tile[64][D + kPad];
   const int tid = threadIdx.x;
   const int bh = blockIdx.y, b = bh / H, h = bh % H;
   if (head_flag && head_flag[bh] == 0) return;  // no consumer for this head's copy
+  if (block_flag) {
+    int any = 0;
+    for (int k = tid; k < nqb; k += kThreads) any |= block_flag[bh * nqb + k];
+    if (__syncthreads_or(any) == 0) return;
+  }
   const TransposeJob& jb = jobs.job[blockIdx.z];
   const int N = jb.N, npad = jb.npad;
   const long long sn = jb.sn;

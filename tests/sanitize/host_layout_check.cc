@@ -31,16 +31,23 @@ static void check_valid(const entmax_attn_params& p) {
                        L.off_lcnt, L.off_kcount, L.off_koffs, L.off_kcursor, L.off_csc_i, L.off_csc_pw, L.off_hflag,
                        L.off_longkeys, L.off_bcells, L.total_bwd};
   for (size_t k = 0; k + 1 < sizeof(bo) / sizeof(bo[0]); ++k) CHECK(bo[k] <= bo[k + 1] && bo[k] % kAlign == 0);
-  const size_t so[] = {L.sv_cand, L.sv_lcnt, L.sv_flags, L.sv_kcand, L.total_saved};
+  const size_t so[] = {L.sv_list, L.sv_lcnt, L.sv_flags, L.total_saved};
   for (size_t k = 0; k + 1 < sizeof(so) / sizeof(so[0]); ++k) CHECK(so[k] <= so[k + 1] && so[k] % kAlign == 0);
   const size_t bh = (size_t)p.B * p.H;
   // the key-major arrays hold kBwdCap entries per half row: that is the bound the kernels check segments against
   CHECK(L.csc_cap == (long long)p.Nq * 2 * kBwdCap);
   CHECK(L.off_csc_pw - L.off_csc_i >= bh * (size_t)L.csc_cap * sizeof(int));
   CHECK(L.off_hflag - L.off_csc_pw >= bh * (size_t)L.csc_cap * 2 * sizeof(float));
-  // candidate lists: kCandCap (key, score) slots per lane of every 128-row block
-  CHECK(L.sv_lcnt - L.sv_cand >= bh * (size_t)L.nqb * kThreads * kCandCap * 8);
-  CHECK(L.total_saved - L.sv_kcand >= bh * (size_t)p.Nk * sizeof(int));
+  // support lists: kBwdCap (key, score) slots per lane of every 128-row block, in `saved` and in the workspace
+  CHECK(L.sv_lcnt - L.sv_list >= bh * (size_t)L.nqb * kThreads * kBwdCap * 8);
+  CHECK(L.off_lcnt - L.off_jlist >= bh * (size_t)L.nqb * kThreads * kBwdCap * 8);
+  CHECK(L.sv_flags - L.sv_lcnt >= bh * (size_t)p.Nq * 2 * sizeof(int));
+  CHECK(L.total_saved - L.sv_flags >= bh * (size_t)L.nqb * sizeof(int));
+  CHECK(L.off_fcells - L.off_flags >= bh * (size_t)L.nqb * sizeof(int));
+  CHECK(L.off_flcnt - L.off_cand >= bh * (size_t)L.nqb * kThreads * kCandCap * 8);
+  CHECK(L.off_bounds - L.off_flcnt >= bh * (size_t)p.Nq * 2 * sizeof(int));
+  CHECK(L.off_flags - L.off_bounds >= bh * (size_t)p.Nq * 2 * sizeof(float));
+  CHECK(L.off_longkeys - L.off_hflag >= (bh * (size_t)L.nqb + 2 * bh) * sizeof(int));
   if (decode_shape(p.Nq, p.Nk)) {
     CHECK(L.off_dec_cmax >= bh * (size_t)p.Nq * (size_t)p.Nk * sizeof(float));
     CHECK(L.total_fwd >= L.off_dec_cmax + bh * (size_t)p.Nq * L.dec_nchunks * sizeof(float));

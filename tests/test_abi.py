@@ -66,11 +66,12 @@ def test_workspace_sizes(binding):
     b = binding
     p = _params(b, B=4, H=12, Nq=4096, Nk=4096)
     fwd, bwd = b.workspace_bytes(p, 0), b.workspace_bytes(p, 1)
-    assert fwd >= 48 * 64 * 4096 * 2  # one transposed copy of V plus candidate lists and flags
+    assert fwd >= 48 * 64 * 4096 * 2  # one transposed copy of V plus candidate lists, strips and flags
     assert bwd > 3 * 48 * 64 * 4096 * 2
     assert b.workspace_bytes(_params(b, D=32), 0) == 0
-    # the buffer that carries the forward's lists: 32 (key, score) slots per half row, lengths, block flags
-    assert b.saved_bytes(p) >= 48 * 4096 * 2 * 32 * 8 + 48 * 4096 * 2 * 4 + 48 * 32 * 4
+    # the buffer that carries the forward's support lists: 16 (key, score) slots per half row, lengths, block flags
+    assert b.saved_bytes(p) >= 48 * 4096 * 2 * 16 * 8 + 48 * 4096 * 2 * 4 + 48 * 32 * 4
+    assert b.saved_bytes(p) < 2 * 48 * 4096 * 64 * 2 + (1 << 21)  # at most twice the size of O
     assert b.saved_bytes(_params(b, D=32)) == 0
     # ragged lengths are padded to 128 rows in the transposed copies
     small = b.workspace_bytes(_params(b, B=1, H=1, Nq=65, Nk=65), 0)
