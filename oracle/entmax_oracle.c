@@ -17,6 +17,13 @@
  *     for alpha = 2 and alpha = 1.5; the support is found here by sorting.
  *   - Sec. 4.1 eq. (asentmax): logits are multiplied by delta + beta (log n)^gamma
  *     before entmax; beta, gamma per head (or per query), natural logarithm.
+ *   - Sec. 4.2, App. B and the ALiBi definition of the positional-encoding appendix:
+ *     an optional per-head linear distance bias b_ij = m_h (j - i) for keys at or
+ *     before the query's position (0 for later keys), added to the logit
+ *     z_ij = <q_i,k_j>/sqrt(d).  A slope of 0 is NoPE; NAPE is a slope array in which
+ *     half of the heads have slope 0.  The paper writes the bias as part of z, which
+ *     eq. (asentmax) then multiplies by the scale (bias_mode 0); the other reading adds
+ *     the bias after the scale (bias_mode 1).  Slopes are fixed numbers: no gradient.
  *   - The backward is the exact derivative of eq. (entmax): on the support
  *     p^(alpha-1) = (alpha-1) s - tau, hence dp = g (ds - dtau/(alpha-1)) with
  *     g = p^(2-alpha); sum_j dp_j = 0 gives dtau/(alpha-1) = sum g ds / sum g.
@@ -41,6 +48,7 @@ typedef struct {
   int32_t causal;       /* 1: key j visible to query i iff j <= i + (Nk - Nq) */
   int32_t scale_layout; /* 0: scale = delta; 1: beta,gamma [H]; 2: beta,gamma [B,H,Nq] */
   int32_t logn_mode;    /* 0: n = Nk for every row; 1: n = number of visible keys of the row */
+  int32_t bias_mode;    /* with slopes: 0: s = scale (z + b); 1: s = scale z + b */
   double alpha;         /* 1 < alpha <= 2 */
   double delta;
 } oracle_params;
@@ -176,6 +184,20 @@ static double row_scale(const oracle_params* P, const double* beta, const double
   return scale;
 }
 
+/* ALiBi bias of key j for query row i of head h: -m_h * distance, where the query sits at position
+ * i + (Nk - Nq) of the key sequence and keys after it get no bias. */
+static double alibi_bias(const oracle_params* P, const double* slopes, int h, int i, int j) {
+  if (!slopes) return 0.0;
+  int dist = i + (P->Nk - P->Nq) - j;
+  if (dist < 0) dist = 0;
+  return -slopes[h] * (double)dist;
+}
+
+/* Entmax input s_ij from the logit z_ij, the row's scale and the positional bias. */
+static double scaled_logit(const oracle_params* P, double scale, double z, double b) {
+  return P->bias_mode == 0 ? scale * (z + b) : scale * z + b;
+}
+
 static double dot(const double* a, const double* b, int d) {
   double acc = 0.0;
   for (int t = 0; t < d; ++t) acc += a[t] * b[t];
@@ -189,7 +211,8 @@ static double dot(const double* a, const double* b, int d) {
  * A row with no visible key gets O = 0, tau = 0, support = 0.
  */
 int oracle_attn_fwd(const oracle_params* P, const double* Q, const double* K, const double* V, const double* beta,
-                    const double* gamma, double* O, double* tau, int32_t* support, double* Pfull) {
+                    const double* gamma, const double* slopes, double* O, double* tau, int32_t* support,
+                    double* Pfull) {
   const int B = P->B, H = P->H, Nq = P->Nq, Nk = P->Nk, D = P->D;
   const double inv_sqrt_d = 1.0 / sqrt((double)D);
   const long rows = (long)B * H * Nq;
@@ -216,7 +239,8 @@ int oracle_attn_fwd(const oracle_params* P, const double* Q, const double* K, co
         continue;
       }
       double scale = row_scale(P, beta, gamma, b, h, i, NULL, NULL, NULL);
-      for (int j = 0; j < nv; ++j) s[j] = scale * (dot(q, Kh + (size_t)j * D, D) * inv_sqrt_d);
+      for (int j = 0; j < nv; ++j)
+        s[j] = scaled_logit(P, scale, dot(q, Kh + (size_t)j * D, D) * inv_sqrt_d, alibi_bias(P, slopes, h, i, j));
       double t;
       int cnt;
       oracle_entmax_row(s, nv, P->alpha, 0, p, &t, &cnt);
@@ -239,15 +263,16 @@ int oracle_attn_fwd(const oracle_params* P, const double* Q, const double* K, co
  *   g_j  = p_j^(2-alpha) on the support, 0 off it,
  *   dP_j = <dO_i, v_j>,  mu = sum g dP / sum g,  dS_j = g_j (dP_j - mu),
  *   dV_j += p_j dO_i,  dQ_i = (scale/sqrt d) sum_j dS_j k_j,
- *   dK_j += (scale/sqrt d) dS_j q_i,  dscale_i = sum_j dS_j z_j,
+ *   dK_j += (scale/sqrt d) dS_j q_i,  dscale_i = sum_j dS_j ds_j/dscale  (= z_j, or z_j + b_j when the
+ *   positional bias sits inside the scaled logit),
  *   dbeta = dscale L^gamma,  dgamma = dscale beta L^gamma ln L   (L = ln n),
  * the last two summed over (batch, row) for the per-head layout.
  * dQ,dK,dV as Q,K,V; dbeta,dgamma in beta/gamma's layout (ignored when the
  * layout is 0; may be NULL then); dscale [B,H,Nq] may be NULL.
  */
 int oracle_attn_bwd(const oracle_params* P, const double* Q, const double* K, const double* V, const double* beta,
-                    const double* gamma, const double* dO, double* dQ, double* dK, double* dV, double* dbeta,
-                    double* dgamma, double* dscale) {
+                    const double* gamma, const double* slopes, const double* dO, double* dQ, double* dK, double* dV,
+                    double* dbeta, double* dgamma, double* dscale) {
   const int B = P->B, H = P->H, Nq = P->Nq, Nk = P->Nk, D = P->D;
   const double inv_sqrt_d = 1.0 / sqrt((double)D);
   const double alpha = P->alpha;
@@ -283,8 +308,10 @@ int oracle_attn_bwd(const oracle_params* P, const double* Q, const double* K, co
         double Lg, lnL, bt;
         double scale = row_scale(P, beta, gamma, b, h, i, &Lg, &lnL, &bt);
         for (int j = 0; j < nv; ++j) {
-          z[j] = dot(q, Kh + (size_t)j * D, D) * inv_sqrt_d;
-          s[j] = scale * z[j];
+          double bj = alibi_bias(P, slopes, h, i, j);
+          double zj = dot(q, Kh + (size_t)j * D, D) * inv_sqrt_d;
+          s[j] = scaled_logit(P, scale, zj, bj);
+          z[j] = P->bias_mode == 0 ? zj + bj : zj; /* d s_j / d scale */
         }
         double t;
         oracle_entmax_row(s, nv, alpha, 0, p, &t, NULL);
@@ -348,7 +375,7 @@ int oracle_attn_bwd(const oracle_params* P, const double* Q, const double* K, co
  * Both arrays are [B,H,ceil(Nq/tq),ceil(Nk/tk)] bytes.
  */
 int oracle_tile_map(const oracle_params* P, const double* Q, const double* K, const double* beta,
-                    const double* gamma, int tq, int tk, uint8_t* map, uint8_t* visible) {
+                    const double* gamma, const double* slopes, int tq, int tk, uint8_t* map, uint8_t* visible) {
   const int B = P->B, H = P->H, Nq = P->Nq, Nk = P->Nk, D = P->D;
   const int nti = (Nq + tq - 1) / tq, ntj = (Nk + tk - 1) / tk;
   const double inv_sqrt_d = 1.0 / sqrt((double)D);
@@ -372,7 +399,8 @@ int oracle_tile_map(const oracle_params* P, const double* Q, const double* K, co
         int nv = visible_count(P, i);
         if (nv == 0) continue;
         double scale = row_scale(P, beta, gamma, b, h, i, NULL, NULL, NULL);
-        for (int j = 0; j < nv; ++j) s[j] = scale * (dot(q, Kh + (size_t)j * D, D) * inv_sqrt_d);
+        for (int j = 0; j < nv; ++j)
+          s[j] = scaled_logit(P, scale, dot(q, Kh + (size_t)j * D, D) * inv_sqrt_d, alibi_bias(P, slopes, h, i, j));
         double t;
         oracle_entmax_row(s, nv, P->alpha, 0, p, &t, NULL);
         for (int j = 0; j < nv; ++j) {

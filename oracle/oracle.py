@@ -26,6 +26,7 @@ class OracleParams(ctypes.Structure):
         ("causal", ctypes.c_int32),
         ("scale_layout", ctypes.c_int32),
         ("logn_mode", ctypes.c_int32),
+        ("bias_mode", ctypes.c_int32),
         ("alpha", ctypes.c_double),
         ("delta", ctypes.c_double),
     ]
@@ -73,7 +74,7 @@ def entmax_row(s, alpha, force_generic=False):
     return p, tau.value, sup.value
 
 
-def _params(Q, K, alpha, delta, causal, beta, logn_mode):
+def _params(Q, K, alpha, delta, causal, beta, logn_mode, bias_mode=0):
     B, H, Nq, D = Q.shape
     Nk = K.shape[2]
     if beta is None:
@@ -82,22 +83,24 @@ def _params(Q, K, alpha, delta, causal, beta, logn_mode):
         layout = 1
     else:
         layout = 2
-    return OracleParams(B, H, Nq, Nk, D, int(causal), layout, int(logn_mode), float(alpha), float(delta))
+    return OracleParams(B, H, Nq, Nk, D, int(causal), layout, int(logn_mode), int(bias_mode), float(alpha), float(delta))
 
 
-def attn_fwd(Q, K, V, alpha, beta=None, gamma=None, delta=1.0, causal=True, logn_mode=0, want_p=False):
+def attn_fwd(Q, K, V, alpha, beta=None, gamma=None, delta=1.0, causal=True, logn_mode=0, want_p=False, slopes=None,
+             bias_mode=0):
     """Exact entmax attention forward.  Q [B,H,Nq,D], K,V [B,H,Nk,D] (any float dtype, widened to fp64).
-    Returns dict(O, tau, support[, P])."""
+    slopes: optional ALiBi slopes [H] (0 = no positional bias for that head); bias_mode 0 puts the bias inside
+    the scaled logit, 1 adds it after the scale.  Returns dict(O, tau, support[, P])."""
     lib = _load()
-    Q, K, V, beta, gamma = _f64(Q), _f64(K), _f64(V), _f64(beta), _f64(gamma)
-    prm = _params(Q, K, alpha, delta, causal, beta, logn_mode)
+    Q, K, V, beta, gamma, slopes = _f64(Q), _f64(K), _f64(V), _f64(beta), _f64(gamma), _f64(slopes)
+    prm = _params(Q, K, alpha, delta, causal, beta, logn_mode, bias_mode)
     B, H, Nq, D = Q.shape
     Nk = K.shape[2]
     O = np.empty((B, H, Nq, D), dtype=np.float64)
     tau = np.empty((B, H, Nq), dtype=np.float64)
     sup = np.empty((B, H, Nq), dtype=np.int32)
     P = np.empty((B, H, Nq, Nk), dtype=np.float64) if want_p else None
-    lib.oracle_attn_fwd(ctypes.byref(prm), _dp(Q), _dp(K), _dp(V), _dp(beta), _dp(gamma), _dp(O), _dp(tau),
+    lib.oracle_attn_fwd(ctypes.byref(prm), _dp(Q), _dp(K), _dp(V), _dp(beta), _dp(gamma), _dp(slopes), _dp(O), _dp(tau),
                         sup.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), _dp(P))
     out = {"O": O, "tau": tau, "support": sup}
     if want_p:
@@ -105,11 +108,11 @@ def attn_fwd(Q, K, V, alpha, beta=None, gamma=None, delta=1.0, causal=True, logn
     return out
 
 
-def attn_bwd(Q, K, V, dO, alpha, beta=None, gamma=None, delta=1.0, causal=True, logn_mode=0):
+def attn_bwd(Q, K, V, dO, alpha, beta=None, gamma=None, delta=1.0, causal=True, logn_mode=0, slopes=None, bias_mode=0):
     """Exact entmax attention backward.  Returns dict(dQ, dK, dV, dbeta, dgamma, dscale)."""
     lib = _load()
-    Q, K, V, dO, beta, gamma = _f64(Q), _f64(K), _f64(V), _f64(dO), _f64(beta), _f64(gamma)
-    prm = _params(Q, K, alpha, delta, causal, beta, logn_mode)
+    Q, K, V, dO, beta, gamma, slopes = _f64(Q), _f64(K), _f64(V), _f64(dO), _f64(beta), _f64(gamma), _f64(slopes)
+    prm = _params(Q, K, alpha, delta, causal, beta, logn_mode, bias_mode)
     B, H, Nq, D = Q.shape
     dQ = np.empty_like(Q)
     dK = np.empty_like(K)
@@ -117,23 +120,23 @@ def attn_bwd(Q, K, V, dO, alpha, beta=None, gamma=None, delta=1.0, causal=True, 
     dscale = np.empty((B, H, Nq), dtype=np.float64)
     dbeta = np.zeros_like(beta) if beta is not None else None
     dgamma = np.zeros_like(gamma) if gamma is not None else None
-    lib.oracle_attn_bwd(ctypes.byref(prm), _dp(Q), _dp(K), _dp(V), _dp(beta), _dp(gamma), _dp(dO), _dp(dQ), _dp(dK),
+    lib.oracle_attn_bwd(ctypes.byref(prm), _dp(Q), _dp(K), _dp(V), _dp(beta), _dp(gamma), _dp(slopes), _dp(dO), _dp(dQ), _dp(dK),
                         _dp(dV), _dp(dbeta), _dp(dgamma), _dp(dscale))
     return {"dQ": dQ, "dK": dK, "dV": dV, "dbeta": dbeta, "dgamma": dgamma, "dscale": dscale}
 
 
-def tile_map(Q, K, alpha, tq, tk, beta=None, gamma=None, delta=1.0, causal=True, logn_mode=0):
+def tile_map(Q, K, alpha, tq, tk, beta=None, gamma=None, delta=1.0, causal=True, logn_mode=0, slopes=None, bias_mode=0):
     """Block sparsity of the exact attention matrix at tile shape tq x tk.
     Returns (nonzero, visible) uint8 arrays [B,H,ceil(Nq/tq),ceil(Nk/tk)]."""
     lib = _load()
-    Q, K, beta, gamma = _f64(Q), _f64(K), _f64(beta), _f64(gamma)
-    prm = _params(Q, K, alpha, delta, causal, beta, logn_mode)
+    Q, K, beta, gamma, slopes = _f64(Q), _f64(K), _f64(beta), _f64(gamma), _f64(slopes)
+    prm = _params(Q, K, alpha, delta, causal, beta, logn_mode, bias_mode)
     B, H, Nq, _ = Q.shape
     Nk = K.shape[2]
     nti, ntj = (Nq + tq - 1) // tq, (Nk + tk - 1) // tk
     nz = np.empty((B, H, nti, ntj), dtype=np.uint8)
     vis = np.empty((B, H, nti, ntj), dtype=np.uint8)
     u8 = ctypes.POINTER(ctypes.c_uint8)
-    lib.oracle_tile_map(ctypes.byref(prm), _dp(Q), _dp(K), _dp(beta), _dp(gamma), ctypes.c_int(tq), ctypes.c_int(tk),
+    lib.oracle_tile_map(ctypes.byref(prm), _dp(Q), _dp(K), _dp(beta), _dp(gamma), _dp(slopes), ctypes.c_int(tq), ctypes.c_int(tk),
                         nz.ctypes.data_as(u8), vis.ctypes.data_as(u8))
     return nz, vis

@@ -9,17 +9,17 @@
 
 typedef struct {
   int32_t B, H, Nq, Nk, D;
-  int32_t causal, scale_layout, logn_mode;
+  int32_t causal, scale_layout, logn_mode, bias_mode;
   double alpha, delta;
 } oracle_params;
 
 void oracle_entmax_row(const double*, int, double, int, double*, double*, int*);
 int oracle_attn_fwd(const oracle_params*, const double*, const double*, const double*, const double*, const double*,
-                    double*, double*, int32_t*, double*);
+                    const double*, double*, double*, int32_t*, double*);
 int oracle_attn_bwd(const oracle_params*, const double*, const double*, const double*, const double*, const double*,
-                    const double*, double*, double*, double*, double*, double*, double*);
-int oracle_tile_map(const oracle_params*, const double*, const double*, const double*, const double*, int, int,
-                    uint8_t*, uint8_t*);
+                    const double*, const double*, double*, double*, double*, double*, double*, double*);
+int oracle_tile_map(const oracle_params*, const double*, const double*, const double*, const double*, const double*,
+                    int, int, uint8_t*, uint8_t*);
 
 static uint64_t state = 88172645463325252ull;
 static double rnd(void) { /* xorshift in [-1, 1) */
@@ -47,13 +47,16 @@ int main(void) {
           P.Nk = shape == 0 ? 9 : shape == 1 ? 12 : shape == 2 ? 6 : 1;
           P.causal = causal; P.scale_layout = layout; P.logn_mode = (ai + shape) & 1;
           P.alpha = alphas[ai]; P.delta = layout == 0 ? 1.0 : 0.5;
+          P.bias_mode = (ai + layout) & 1;
+          double slopes_buf[2] = {0.25, 0.0};
+          const double* slopes = (shape + causal) & 1 ? slopes_buf : NULL; /* with and without the positional bias */
           size_t nq = (size_t)P.B * P.H * P.Nq, nk = (size_t)P.B * P.H * P.Nk;
           double *Q = fill(nq * P.D, 2.0), *K = fill(nk * P.D, 2.0), *V = fill(nk * P.D, 1.0), *dO = fill(nq * P.D, 1.0);
           size_t ns = layout == 1 ? (size_t)P.H : nq;
           double *beta = fill(ns, 1.0), *gamma = fill(ns, 1.0);
           double *O = fill(nq * P.D, 0.0), *tau = fill(nq, 0.0), *Pf = fill(nq * P.Nk, 0.0);
           int32_t* sup = (int32_t*)malloc(sizeof(int32_t) * nq);
-          oracle_attn_fwd(&P, Q, K, V, layout ? beta : NULL, layout ? gamma : NULL, O, tau, sup, Pf);
+          oracle_attn_fwd(&P, Q, K, V, layout ? beta : NULL, layout ? gamma : NULL, slopes, O, tau, sup, Pf);
           for (size_t r = 0; r < nq; ++r) {
             double s = 0.0;
             for (int j = 0; j < P.Nk; ++j) s += Pf[r * P.Nk + j];
@@ -61,12 +64,12 @@ int main(void) {
           }
           double *dQ = fill(nq * P.D, 0.0), *dK = fill(nk * P.D, 0.0), *dV = fill(nk * P.D, 0.0);
           double *db = fill(ns, 0.0), *dg = fill(ns, 0.0), *dsc = fill(nq, 0.0);
-          oracle_attn_bwd(&P, Q, K, V, layout ? beta : NULL, layout ? gamma : NULL, dO, dQ, dK, dV, layout ? db : NULL,
+          oracle_attn_bwd(&P, Q, K, V, layout ? beta : NULL, layout ? gamma : NULL, slopes, dO, dQ, dK, dV, layout ? db : NULL,
                           layout ? dg : NULL, dsc);
           int nti = (P.Nq + 3) / 4, ntj = (P.Nk + 3) / 4;
           uint8_t* map = (uint8_t*)malloc((size_t)P.B * P.H * nti * ntj + 1);
           uint8_t* vis = (uint8_t*)malloc((size_t)P.B * P.H * nti * ntj + 1);
-          oracle_tile_map(&P, Q, K, layout ? beta : NULL, layout ? gamma : NULL, 4, 4, map, vis);
+          oracle_tile_map(&P, Q, K, layout ? beta : NULL, layout ? gamma : NULL, slopes, 4, 4, map, vis);
           free(Q); free(K); free(V); free(dO); free(beta); free(gamma); free(O); free(tau); free(Pf); free(sup);
           free(dQ); free(dK); free(dV); free(db); free(dg); free(dsc); free(map); free(vis);
           ++runs;

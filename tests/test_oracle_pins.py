@@ -399,3 +399,133 @@ def test_tile_map_matches_full_matrix():
             assert np.array_equal(nz[:, :, ti, tj] > 0, (blk > 0).any(axis=(2, 3)))
             assert bool(vis[0, 0, ti, tj]) == (tj * 4 <= min(ti * 8 + 7, 36))
     assert 0 < nz.sum() < vis.sum()
+
+
+# ------------------------------------------------------------------ positional bias (ALiBi / NAPE)
+
+def _alibi(slopes, h, i, j, Nq, Nk):
+    """Bias of the ALiBi definition (positional-encoding appendix): -m_h * distance for keys at or before the
+    query's position i + (Nk - Nq), zero for later keys."""
+    return -slopes[h] * max(i + (Nk - Nq) - j, 0)
+
+
+@pytest.mark.parametrize("alpha", [1.5, 2.0, 1.3])
+@pytest.mark.parametrize("causal,Nq,Nk", [(True, 9, 9), (False, 9, 9), (True, 5, 11), (False, 7, 3)])
+@pytest.mark.parametrize("layout,bias_mode", [(0, 0), (1, 0), (1, 1), (2, 1)])
+def test_alibi_forward_composition(alpha, causal, Nq, Nk, layout, bias_mode):
+    """Sec. 4.2 / App. B: z_ij = <q,k>/sqrt(d) + m_h (j - i); bias_mode 0 multiplies the whole of it by the
+    ASEntmax scale (the bias is part of the logit of eq. (asentmax)), bias_mode 1 adds the bias after the
+    scale.  Scores are rebuilt with numpy and go through the pinned row routine."""
+    Q, K, V, _, beta, gamma = _rand_problem(11, Nq=Nq, Nk=Nk, layout=layout)
+    slopes = np.array([0.7, 0.0, 0.05])  # NAPE-like: the middle head has no positional bias
+    delta = 0.8
+    out = oracle.attn_fwd(Q, K, V, alpha, beta, gamma, delta=delta, causal=causal, want_p=True, slopes=slopes,
+                          bias_mode=bias_mode)
+    B, H, _, D = Q.shape
+    Z = np.einsum("bhid,bhjd->bhij", Q, K) / math.sqrt(D)
+    for b in range(B):
+        for h in range(H):
+            for i in range(Nq):
+                nv = min(Nk, i + Nk - Nq + 1) if causal else Nk
+                if layout == 0:
+                    sc = delta
+                else:
+                    bt = beta[h] if layout == 1 else beta[b, h, i]
+                    gm = gamma[h] if layout == 1 else gamma[b, h, i]
+                    sc = delta + bt * math.log(Nk) ** gm
+                bias = np.array([_alibi(slopes, h, i, j, Nq, Nk) for j in range(nv)])
+                s = sc * (Z[b, h, i, :nv] + bias) if bias_mode == 0 else sc * Z[b, h, i, :nv] + bias
+                p, tau, sup = oracle.entmax_row(s, alpha)
+                np.testing.assert_allclose(out["P"][b, h, i, :nv], p, atol=1e-13)
+                assert abs(out["tau"][b, h, i] - tau) < 1e-13 and out["support"][b, h, i] == sup
+    np.testing.assert_allclose(out["O"], out["P"] @ V, atol=1e-12)
+
+
+@pytest.mark.parametrize("bias_mode", [0, 1])
+def test_alibi_zero_slopes_are_nope_bit_for_bit(bias_mode):
+    Q, K, V, dO, beta, gamma = _rand_problem(12)
+    kw = dict(delta=0.9, causal=True)
+    a = oracle.attn_fwd(Q, K, V, 1.5, beta, gamma, **kw)
+    b = oracle.attn_fwd(Q, K, V, 1.5, beta, gamma, slopes=np.zeros(3), bias_mode=bias_mode, **kw)
+    ga = oracle.attn_bwd(Q, K, V, dO, 1.5, beta, gamma, **kw)
+    gb = oracle.attn_bwd(Q, K, V, dO, 1.5, beta, gamma, slopes=np.zeros(3), bias_mode=bias_mode, **kw)
+    for k in ("O", "tau"):
+        assert np.array_equal(a[k], b[k])
+    for k in ("dQ", "dK", "dV", "dbeta", "dgamma"):
+        assert np.array_equal(ga[k], gb[k])
+
+
+@pytest.mark.parametrize("alpha", [1.25, 1.5, 2.0])
+@pytest.mark.parametrize("m", [0.3, 1.0])
+def test_alibi_hard_window(alpha, m):
+    """Proposition on ALiBi with alpha-entmax: with raw logits in [z_min, z_max], a key further than
+    d_max = floor((z_max - z_min + 1/(alpha-1)) / m + 1) behind the query gets exactly zero weight."""
+    n, d = 96, 4
+    rng = np.random.default_rng(5)
+    Q = rng.normal(size=(1, 1, n, d))
+    K = rng.normal(size=(1, 1, n, d))
+    V = rng.normal(size=(1, 1, n, d))
+    out = oracle.attn_fwd(Q, K, V, alpha, causal=True, want_p=True, slopes=np.array([m]))
+    Z = (Q[0, 0] @ K[0, 0].T) / math.sqrt(d)
+    vis = np.tril(np.ones((n, n), bool))
+    zmax, zmin = Z[vis].max(), Z[vis].min()
+    dmax = math.floor((zmax - zmin + 1.0 / (alpha - 1.0)) / m + 1)
+    assert dmax < n - 1  # the bound bites at this size
+    P = out["P"][0, 0]
+    i, j = np.nonzero(P > 0)
+    assert (i - j).max() <= dmax
+    # and the window is not vacuous: without the bias the same rows reach further back
+    P0 = oracle.attn_fwd(Q, K, V, alpha, causal=True, want_p=True)["P"][0, 0]
+    i0, j0 = np.nonzero(P0 > 0)
+    assert (i0 - j0).max() > (i - j).max()
+
+
+def test_alibi_equal_content_is_entmax_of_a_ramp():
+    """All content logits equal (q = 0): row i is the entmax of the ramp -m * (i - j), whose alpha = 2 solution
+    is the textbook sparsemax of that ramp; keys after the query (non-causal call) carry no bias."""
+    n, d, m = 12, 4, 0.2
+    rng = np.random.default_rng(6)
+    Q = np.zeros((1, 1, n, d))
+    K = rng.normal(size=(1, 1, n, d))
+    V = rng.normal(size=(1, 1, n, d))
+    out = oracle.attn_fwd(Q, K, V, 2.0, causal=False, want_p=True, slopes=np.array([m]))
+    for i in range(n):
+        ramp = np.array([-m * max(i - j, 0) for j in range(n)])
+        p, tau = sparsemax_textbook(ramp)
+        np.testing.assert_allclose(out["P"][0, 0, i], p, atol=1e-13)
+        assert abs(out["tau"][0, 0, i] - tau) < 1e-13
+
+
+@pytest.mark.parametrize("alpha", [1.25, 1.5, 2.0])
+@pytest.mark.parametrize("causal,Nq,Nk,layout,bias_mode", [(True, 6, 6, 1, 0), (True, 6, 6, 1, 1), (False, 5, 7, 2, 0),
+                                                           (True, 4, 7, 2, 1), (True, 6, 6, 0, 0)])
+def test_alibi_backward_matches_finite_differences(alpha, causal, Nq, Nk, layout, bias_mode):
+    """With the bias inside the scaled logit the scale gradient sees z + b, outside it only z: central
+    differences of sum(O * dO) decide (slopes are fixed numbers and get no gradient)."""
+    B, H, D = 1, 2, 3
+    Q, K, V, dO, beta, gamma = _rand_problem(23, B=B, H=H, Nq=Nq, Nk=Nk, D=D, layout=layout)
+    kw = dict(delta=0.9, causal=causal, slopes=np.array([0.4, 0.05]), bias_mode=bias_mode)
+    g = oracle.attn_bwd(Q, K, V, dO, alpha, beta, gamma, **kw)
+    h = 1e-6
+
+    def fd(arr):
+        out = np.zeros_like(arr)
+        it = np.nditer(arr, flags=["multi_index"])
+        for _ in it:
+            idx = it.multi_index
+            old = arr[idx]
+            arr[idx] = old + h
+            fp = _loss(Q, K, V, dO, alpha, beta, gamma, **kw)
+            arr[idx] = old - h
+            fm = _loss(Q, K, V, dO, alpha, beta, gamma, **kw)
+            arr[idx] = old
+            out[idx] = (fp - fm) / (2 * h)
+        return out
+
+    tol = dict(atol=2e-6, rtol=1e-5)
+    np.testing.assert_allclose(g["dQ"], fd(Q), **tol)
+    np.testing.assert_allclose(g["dK"], fd(K), **tol)
+    np.testing.assert_allclose(g["dV"], fd(V), **tol)
+    if layout != 0:
+        np.testing.assert_allclose(g["dbeta"], fd(beta), **tol)
+        np.testing.assert_allclose(g["dgamma"], fd(gamma), **tol)
