@@ -5,9 +5,14 @@ A step is one forward + one backward of the whole path (C ABI calls
 entmax_attn_fwd and entmax_attn_bwd) over one batch of the headline workload:
 the 120M-class LM attention layer at training length (B=4, H=12, n=4096, d=64,
 bf16, causal, alpha=1.5, per-head ASEntmax scale, 5% planted keys), seeded and
-synthetic, resident in HBM before the timed region.  Prints ONE JSON line.
+synthetic, resident in HBM before the timed region.  Prints ONE JSON line whose
+`value` is that workload's tokens per second; the other benchmark configurations
+(n=1024 forward, n=32768 forward, the alpha sweep at d=128, the dense-regime
+companion, decode shapes) are timed the same way and reported as extra objects of
+the same line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3] [--alpha A] [--no-cpu-baseline] [--no-c4] [--no-decode]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3] [--alpha A]
+                  [--no-cpu-baseline] [--no-extra] [--no-decode]
 """
 import argparse
 import ctypes
@@ -21,12 +26,10 @@ import numpy as np
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak
-# HBM bytes per launch at the c3 workload, from rocprofv3 FETCH_SIZE + WRITE_SIZE runs of this same command scaled by
-# what the counters read for a conversion kernel of known size (profiles/pmc_c3_fwd_bwd.md).  Other workloads: null.
-MEASURED_HBM_BYTES_C3 = {
-    "fwd_lists": 141.1e6, "fwd_finish": 78.5e6, "bwd_rows": 177.2e6, "bwd_keys": 156.3e6,
-}
+PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak (data sheet)
+# HBM bytes per launch of the kernels of the c3 workload: written by `python -m paper_2506_16640_amd.profile_summary`
+# from rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this same command (calibrated on a copy kernel of known size)
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic_c3_fwd_bwd.txt")
 
 
 class HipEvents:
@@ -37,6 +40,7 @@ class HipEvents:
         self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
         self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
         self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        self.hip.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
         self.all = []
 
     def make(self, n):
@@ -49,6 +53,11 @@ class HipEvents:
             out.append(ev.value)
             self.all.append(ev.value)
         return out
+
+    def record(self, ev, stream):
+        rc = self.hip.hipEventRecord(ctypes.c_void_p(ev), ctypes.c_void_p(stream))
+        if rc != 0:
+            raise RuntimeError("hipEventRecord failed: %d" % rc)
 
     def elapsed_ms(self, a, b):
         ms = ctypes.c_float()
@@ -67,6 +76,21 @@ def tile_flops(d):
     return 2.0 * 32 * 32 * d  # one 32x32 tile of a product contracting over d (or d outputs over 32 keys)
 
 
+def read_traffic():
+    """kernel name -> HBM bytes per launch, from the committed profile summary (None if absent)."""
+    if not os.path.exists(TRAFFIC_FILE):
+        return None
+    out = {}
+    for line in open(TRAFFIC_FILE):
+        parts = line.split()
+        if len(parts) >= 2 and not line.startswith("#"):
+            try:
+                out[parts[0]] = float(parts[1])
+            except ValueError:
+                pass
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -75,7 +99,7 @@ def main():
     ap.add_argument("--workload", default="c3")
     ap.add_argument("--alpha", type=float, default=None, help="entmax alpha instead of the workload's own (1.5)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-c4", action="store_true", help="skip the n=32768 forward-only measurement")
+    ap.add_argument("--no-extra", action="store_true", help="skip the other benchmark configurations (c2, c4, c5, c3d)")
     ap.add_argument("--no-decode", action="store_true", help="skip the decode-shape (Nq = 1 and 8, Nk = 32768) measurement")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -89,6 +113,7 @@ def main():
     assert torch.cuda.is_available(), "needs an MI355X"
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    hev = HipEvents()
 
     def upload(name, want_dO=True):
         data = synth.make_config(name, seed=0)
@@ -101,99 +126,125 @@ def main():
         t["gamma"] = None if data["gamma"] is None else torch.from_numpy(data["gamma"]).to(dev)
         return data, cfg, t
 
-    data, cfg, t = upload(args.workload)
-    B, H, n, d, alpha = cfg["B"], cfg["H"], cfg["n"], cfg["d"], cfg["alpha"]
-    if args.alpha is not None:
-        alpha = args.alpha
-    do_bwd = bool(cfg["bwd"])
-    kw = dict(alpha=alpha, beta=t["beta"], gamma=t["gamma"], delta=data["delta"], causal=True, logn_mode=0)
-    prm = binding.make_params(t["Q"], t["K"], alpha, data["delta"], True, t["beta"], 0)
-    ws = torch.empty(max(binding.workspace_bytes(prm, 0), binding.workspace_bytes(prm, 1)), dtype=torch.uint8,
-                     device=dev)
-    out = torch.empty_like(t["Q"])
-    tau = torch.empty(B, H, n, dtype=torch.float32, device=dev)
-    # what a training step keeps between forward and backward: O, tau and the rows' candidate lists
-    saved = binding.new_saved(prm, dev) if do_bwd else None
+    def measure(name, steps, warmup, alpha=None, want_events=True):
+        """Times `steps` steps of workload `name` (forward, plus backward with the forward's saved buffer where the
+        workload has one) wall-clock with no events inside, then once more with the library's phase events."""
+        data, cfg, t = upload(name, want_dO=bool(synth.CONFIGS[name]["bwd"]))
+        B, H, n, d = cfg["B"], cfg["H"], cfg["n"], cfg["d"]
+        alpha = cfg["alpha"] if alpha is None else alpha
+        do_bwd = bool(cfg["bwd"])
+        kw = dict(alpha=alpha, beta=t["beta"], gamma=t["gamma"], delta=data["delta"], causal=True, logn_mode=0)
+        prm = binding.make_params(t["Q"], t["K"], alpha, data["delta"], True, t["beta"], 0)
+        ws = torch.empty(max(binding.workspace_bytes(prm, 0), binding.workspace_bytes(prm, 1) if do_bwd else 0),
+                         dtype=torch.uint8, device=dev)
+        out = torch.empty_like(t["Q"])
+        tau = torch.empty(B, H, n, dtype=torch.float32, device=dev)
+        # what a training step keeps between forward and backward: O, tau and the rows' support lists
+        saved = binding.new_saved(prm, dev) if do_bwd else None
 
-    def step(fwd_ev=None, bwd_ev=None, stats=None):
-        binding.entmax_attn_fwd(t["Q"], t["K"], t["V"], out=out, tau=tau, workspace=ws, stats=stats,
-                                phase_events=fwd_ev, saved=saved, **kw)
-        if do_bwd:
-            return binding.entmax_attn_bwd(t["Q"], t["K"], t["V"], out, t["dO"], tau, workspace=ws, stats=stats,
-                                           phase_events=bwd_ev, saved=saved, **kw)
-        return None
+        def step(fwd_ev=None, bwd_ev=None, stats=None):
+            binding.entmax_attn_fwd(t["Q"], t["K"], t["V"], out=out, tau=tau, workspace=ws, stats=stats,
+                                    phase_events=fwd_ev, saved=saved, **kw)
+            if do_bwd:
+                binding.entmax_attn_bwd(t["Q"], t["K"], t["V"], out, t["dO"], tau, workspace=ws, stats=stats,
+                                        phase_events=bwd_ev, saved=saved, **kw)
 
-    # tile counters (one untimed step): executed work and tile-skip rate
-    st = binding.new_stats(dev)
-    step(stats=st)
-    torch.cuda.synchronize()
-    sd = binding.stats_dict(st)
+        st = binding.new_stats(dev)  # tile counters (one untimed step): executed work and tile-skip rate
+        step(stats=st)
+        torch.cuda.synchronize()
+        sd = binding.stats_dict(st)
+        for _ in range(warmup):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()  # the timed region: exactly `steps` steps, no events inside
+        for _ in range(steps):
+            step()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / steps
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
+        F = tile_flops(d)
+        # algorithmic flops per launch: 2*32*32*D per 32x32 score tile, times the tiles the kernel's own counters
+        # report.  The finish / row / key kernels of the list path are gathers over a few entries per row: no tile work.
+        algo = {
+            "fwd_lists": F * sd["fwd_list_qk"], "fwd_finish": 0.0,
+            "fwd_tiled": F * (sd["fwd_qk_max"] + sd["fwd_qk_solve"] + sd["fwd_qk_pv"] + sd["fwd_pv_tiles"]),
+            "bwd_lists": F * sd["bwd_list_qk"], "bwd_rows": 0.0, "bwd_keys": 0.0, "bwd_mask": F * sd["bwd_qk_mask"],
+            "bwd_dq": F * 4 * sd["bwd_dq_tiles"], "bwd_dkv": F * 4 * sd["bwd_dkv_tiles"],
+        }
+        res = {"cfg": cfg, "alpha": alpha, "ms": ms, "stats": sd, "algo": algo, "do_bwd": do_bwd, "data": data}
+        if want_events:
+            fwd_sets = [hev.make(binding.FWD_NUM_PHASES + 1) for _ in range(steps)]
+            bwd_sets = [hev.make(binding.BWD_NUM_PHASES + 1) for _ in range(steps)] if do_bwd else [None] * steps
+            torch.cuda.synchronize()
+            for k in range(steps):
+                step(fwd_sets[k], bwd_sets[k])
+            torch.cuda.synchronize()
 
-    # the timed region: exactly K steps, no events inside
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for k in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
+            def phase_ms(sets, names):
+                return {nm: float(np.mean([hev.elapsed_ms(s[pi], s[pi + 1]) for s in sets])) for pi, nm in enumerate(names)}
 
-    # per-kernel durations: the same K steps again with hipEvents between the phases (on the launch stream)
-    hev = HipEvents()
-    fwd_sets = [hev.make(binding.FWD_NUM_PHASES + 1) for _ in range(args.steps)]
-    bwd_sets = [hev.make(binding.BWD_NUM_PHASES + 1) for _ in range(args.steps)] if do_bwd else [None] * args.steps
-    torch.cuda.synchronize()
-    for k in range(args.steps):
-        step(fwd_sets[k], bwd_sets[k])
-    torch.cuda.synchronize()
-
-    def phase_ms(sets, names):
-        res = {}
-        for pi, nm in enumerate(names):
-            res[nm] = float(np.mean([hev.elapsed_ms(s[pi], s[pi + 1]) for s in sets]))
+            fwd_ms = phase_ms(fwd_sets, binding.FWD_PHASES)
+            bwd_ms = phase_ms(bwd_sets, binding.BWD_PHASES) if do_bwd else {}
+            kernel_ms = {"fwd_lists": fwd_ms["lists"], "fwd_finish": fwd_ms["finish"], "fwd_tiled": fwd_ms["tiled"]}
+            if do_bwd:
+                kernel_ms.update(bwd_lists=bwd_ms["lists"], bwd_rows=bwd_ms["rows"], bwd_keys=bwd_ms["keys"],
+                                 bwd_mask=bwd_ms["mask"], bwd_dq=bwd_ms["dq"], bwd_dkv=bwd_ms["dkv"])
+            res.update(fwd_ms=float(np.mean([hev.elapsed_ms(s[0], s[-1]) for s in fwd_sets])),
+                       bwd_ms=float(np.mean([hev.elapsed_ms(s[0], s[-1]) for s in bwd_sets])) if do_bwd else 0.0,
+                       phase_ms={"fwd": fwd_ms, "bwd": bwd_ms}, kernel_ms=kernel_ms)
         return res
 
-    fwd_ms = phase_ms(fwd_sets, binding.FWD_PHASES)
-    bwd_ms = phase_ms(bwd_sets, binding.BWD_PHASES) if do_bwd else {}
-    fwd_total = float(np.mean([hev.elapsed_ms(s[0], s[-1]) for s in fwd_sets]))
-    bwd_total = float(np.mean([hev.elapsed_ms(s[0], s[-1]) for s in bwd_sets])) if do_bwd else 0.0
+    def summary(r):
+        """The figures every workload reports."""
+        cfg, sd, ms = r["cfg"], r["stats"], r["ms"]
+        B, H, n, d = cfg["B"], cfg["H"], cfg["n"], cfg["d"]
+        dense = synth.dense_equiv_flops(B, H, n, d, True, False) + (
+            synth.dense_equiv_flops(B, H, n, d, True, True) if r["do_bwd"] else 0.0)
+        executed = sum(r["algo"].values())
+        out = {
+            "workload": "%s B=%d H=%d n=%d d=%d %s causal alpha=%g, %s" % (
+                cfg.get("scale", ""), B, H, n, d, cfg["dtype"], r["alpha"], "fwd+bwd" if r["do_bwd"] else "fwd"),
+            "ms": ms, "tokens_per_s": B * n / (ms * 1e-3),
+            "executed_tflops": executed / (ms * 1e-3) / 1e12,
+            "frac_bf16_mfma_peak_executed": executed / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+            "dense_equiv_tflops": dense / (ms * 1e-3) / 1e12,
+            "list_blocks_fraction": sd["fwd_sparse_blocks"] / max(B * H * ((n + 127) // 128), 1),
+            # tiles that can hold a non-zero probability: candidate tiles of the list kernel (an upper bound of the
+            # non-zero tiles) plus the P.V tiles the tiled kernel executed
+            "tile_skip_rate_fwd": 1.0 - (sd["fwd_cand_tiles"] + sd["fwd_pv_tiles"]) / max(sd["fwd_tiles_visible"], 1),
+            "support_per_row": (sd["fwd_support"] if sd["fwd_support"] else sd["bwd_support"]) / max(B * H * n, 1),
+        }
+        if "kernel_ms" in r:
+            out["kernel_ms"] = r["kernel_ms"]
+        return out
 
-    F = tile_flops(d)
-    # algorithmic flops per launch: 2*32*32*D per 32x32 score tile, times the tiles the kernel's own counters report.
-    # The list kernels' finish / row / key kernels are gathers over a few entries per row: no tile work.
-    algo = {
-        "fwd_lists": F * sd["fwd_list_qk"],
-        "fwd_finish": 0.0,
-        "fwd_tiled": F * (sd["fwd_qk_max"] + sd["fwd_qk_solve"] + sd["fwd_qk_pv"] + sd["fwd_pv_tiles"]),
-        "bwd_lists": F * sd["bwd_list_qk"],
-        "bwd_rows": 0.0,
-        "bwd_keys": 0.0,
-        "bwd_mask": F * sd["bwd_qk_mask"],
-        "bwd_dq": F * 4 * sd["bwd_dq_tiles"],
-        "bwd_dkv": F * 4 * sd["bwd_dkv_tiles"],
-    }
-    kernel_ms = {"fwd_lists": fwd_ms["lists"], "fwd_finish": fwd_ms["finish"], "fwd_tiled": fwd_ms["tiled"]}
-    if do_bwd:
-        kernel_ms.update(bwd_lists=bwd_ms["lists"], bwd_rows=bwd_ms["rows"], bwd_keys=bwd_ms["keys"],
-                         bwd_mask=bwd_ms["mask"], bwd_dq=bwd_ms["dq"], bwd_dkv=bwd_ms["dkv"])
+    # ---------------------------------------------------------------- headline workload
+    main_r = measure(args.workload, args.steps, args.warmup, alpha=args.alpha)
+    cfg, sd, ms_per_step = main_r["cfg"], main_r["stats"], main_r["ms"]
+    B, H, n, d, alpha = cfg["B"], cfg["H"], cfg["n"], cfg["d"], main_r["alpha"]
+    kernel_ms, algo = main_r["kernel_ms"], main_r["algo"]
     # the roofline object describes the longest kernel among those that do tile (MFMA) work
     dominant = max((k for k in kernel_ms if algo[k] > 0), key=kernel_ms.get, default=max(kernel_ms, key=kernel_ms.get))
     achieved = algo[dominant] / (kernel_ms[dominant] * 1e-3) / 1e12
-    total_exec = sum(algo[k] for k in kernel_ms)
+    traffic = read_traffic() if args.workload == "c3" and args.alpha is None else None
+    s_main = summary(main_r)
 
-    dense_flops = synth.dense_equiv_flops(B, H, n, d, True, False) + (
-        synth.dense_equiv_flops(B, H, n, d, True, True) if do_bwd else 0.0)
-    value = dense_flops / (ms_per_step * 1e-3) / 1e12
-    vis = max(sd["fwd_tiles_visible"], 1)
+    # what the matrix pipeline sustains with nothing else in the way (measured beside the data-sheet peak)
+    sink = torch.zeros(1, dtype=torch.float32, device=dev)
+    stream = torch.cuda.current_stream().cuda_stream
+    binding.mfma_probe(2000, 2048, sink)
+    torch.cuda.synchronize()
+    e0, e1 = hev.make(2)
+    hev.record(e0, stream)
+    probe_flops = binding.mfma_probe(20000, 2048, sink)
+    hev.record(e1, stream)
+    torch.cuda.synchronize()
+    mfma_measured = probe_flops / (hev.elapsed_ms(e0, e1) * 1e-3) / 1e12
 
     result = {
-        "metric": "entmax attention fwd+bwd dense-equivalent TFLOP/s at n=4096 (tokens/s and fwd at n=32768 alongside)",
-        "value": value,
-        "unit": "TFLOP/s",
+        "metric": "entmax attention fwd+bwd tokens/s at n=4096 (TFLOP/s, %% of bf16 MFMA peak and fwd at n=32768 alongside)",
+        "value": s_main["tokens_per_s"],
+        "unit": "tokens/s",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
@@ -205,67 +256,52 @@ def main():
         "data": "synthetic",
         "config": {"workload": "%s: B=%d H=%d n=%d d=%d %s causal alpha=%g ASEntmax per-head scale, %g%% planted keys, %s"
                                % (args.workload, B, H, n, d, cfg["dtype"], alpha, 100 * cfg["planted"],
-                                  "fwd+bwd" if do_bwd else "fwd"),
+                                  "fwd+bwd" if main_r["do_bwd"] else "fwd"),
                    "B": B, "H": H, "n": n, "d": d, "alpha": alpha, "tile": "32x32"},
-        "tokens_per_s": B * n / (ms_per_step * 1e-3),
-        "fwd_ms": fwd_total,
-        "bwd_ms": bwd_total,
+        "tokens_per_s": s_main["tokens_per_s"],
+        # matrix-core work the kernels executed (their own tile counters) per second of the whole step, and the usual
+        # attention convention (4 B H n^2 d, half under the causal mask, backward 2.5x): work the method mostly skips
+        "executed_tflops": s_main["executed_tflops"],
+        "frac_bf16_mfma_peak_executed": s_main["frac_bf16_mfma_peak_executed"],
+        "dense_equiv_tflops": s_main["dense_equiv_tflops"],
+        "fwd_ms": main_r["fwd_ms"],
+        "bwd_ms": main_r["bwd_ms"],
         "kernel_ms": kernel_ms,
-        "phase_ms": {"fwd": fwd_ms, "bwd": bwd_ms},
-        "executed_tflops": total_exec / (sum(kernel_ms.values()) * 1e-3) / 1e12,
-        "frac_bf16_mfma_peak_executed": total_exec / (sum(kernel_ms.values()) * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
-        # tiles that can hold a non-zero probability: candidate tiles of the list kernel (an upper bound of the
-        # non-zero tiles) plus the P.V tiles the tiled kernel executed
-        "tile_skip_rate_fwd": 1.0 - (sd["fwd_cand_tiles"] + sd["fwd_pv_tiles"]) / vis,
-        "list_blocks_fraction": sd["fwd_sparse_blocks"] / max(B * H * ((n + 127) // 128), 1),
-        "support_per_row": sd["fwd_support"] / max(B * H * n, 1),
+        "phase_ms": main_r["phase_ms"],
+        "tile_skip_rate_fwd": s_main["tile_skip_rate_fwd"],
+        "list_blocks_fraction": s_main["list_blocks_fraction"],
+        "support_per_row": s_main["support_per_row"],
         "candidates_per_row": sd["fwd_candidates"] / max(B * H * n, 1),
         "solve_sweeps_per_tiled_block": sd["fwd_solve_sweeps"] / max(sd["fwd_blocks"], 1),
         "tile_stats": sd,
+        "mfma_peak_measured_tflops": mfma_measured,
         "roofline": {"bound": "mfma", "kernel": dominant, "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
-                     "traffic": MEASURED_HBM_BYTES_C3.get(dominant) if args.workload == "c3" else None},
+                     "frac_of_measured_peak": achieved / mfma_measured,
+                     "traffic": None if not traffic else traffic.get(dominant)},
     }
+    data_main = main_r.pop("data")
+    do_bwd = main_r["do_bwd"]
+    del main_r
+    torch.cuda.empty_cache()
 
-    if not args.no_c4 and args.workload == "c3":
-        # forward only at 8x the training length (n = 32768), same counters
-        del ws
-        data4, cfg4, t4 = upload("c4", want_dO=False)
-        kw4 = dict(alpha=cfg4["alpha"], beta=t4["beta"], gamma=t4["gamma"], delta=data4["delta"], causal=True)
-        prm4 = binding.make_params(t4["Q"], t4["K"], cfg4["alpha"], data4["delta"], True, t4["beta"], 0)
-        ws4 = torch.empty(binding.workspace_bytes(prm4, 0), dtype=torch.uint8, device=dev)
-        out4 = torch.empty_like(t4["Q"])
-        tau4 = torch.empty(cfg4["B"], cfg4["H"], cfg4["n"], dtype=torch.float32, device=dev)
-        st4 = binding.new_stats(dev)
-        binding.entmax_attn_fwd(t4["Q"], t4["K"], t4["V"], out=out4, tau=tau4, workspace=ws4, stats=st4, **kw4)
-        torch.cuda.synchronize()
-        sd4 = binding.stats_dict(st4)
+    if not args.no_extra and args.workload == "c3" and args.alpha is None:
         k4 = max(3, args.steps // 4)
-        ev4 = [hev.make(binding.FWD_NUM_PHASES + 1) for _ in range(k4)]
-        torch.cuda.synchronize()
-        ta = time.perf_counter()
-        for k in range(k4):
-            binding.entmax_attn_fwd(t4["Q"], t4["K"], t4["V"], out=out4, tau=tau4, workspace=ws4,
-                                    phase_events=ev4[k], **kw4)
-        torch.cuda.synchronize()
-        tb = time.perf_counter()
-        ms4 = (tb - ta) * 1e3 / k4
-        main4 = float(np.mean([hev.elapsed_ms(s[0], s[binding.FWD_NUM_PHASES]) for s in ev4]))
-        F4 = tile_flops(cfg4["d"])
-        algo4 = F4 * (sd4["fwd_list_qk"] + sd4["fwd_qk_max"] + sd4["fwd_qk_solve"] + sd4["fwd_qk_pv"] + sd4["fwd_pv_tiles"])
-        dense4 = synth.dense_equiv_flops(cfg4["B"], cfg4["H"], cfg4["n"], cfg4["d"], True, False)
-        result["fwd_n32768"] = {
-            "workload": "c4: B=1 H=12 n=32768 d=64 bf16 causal alpha=1.5 ASEntmax scale, 5% planted keys, fwd",
-            "steps": k4, "ms": ms4, "dense_equiv_tflops": dense4 / (ms4 * 1e-3) / 1e12,
-            "tokens_per_s": cfg4["B"] * cfg4["n"] / (ms4 * 1e-3),
-            "kernels_ms": main4, "executed_tflops": algo4 / (main4 * 1e-3) / 1e12,
-            "frac_bf16_mfma_peak_executed": algo4 / (main4 * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
-            "tile_skip_rate": 1.0 - (sd4["fwd_cand_tiles"] + sd4["fwd_pv_tiles"]) / max(sd4["fwd_tiles_visible"], 1),
-            "list_blocks_fraction": sd4["fwd_sparse_blocks"] / max(cfg4["B"] * cfg4["H"] * ((cfg4["n"] + 127) // 128), 1),
-            "support_per_row": sd4["fwd_support"] / max(cfg4["B"] * cfg4["H"] * cfg4["n"], 1),
-            "candidates_per_row": sd4["fwd_candidates"] / max(cfg4["B"] * cfg4["H"] * cfg4["n"], 1),
-            "tile_stats": {k: v for k, v in sd4.items() if k.startswith("fwd")},
-        }
+        extra = {}
+        extra["c2_n1024_fwd"] = summary(measure("c2", args.steps, args.warmup))
+        torch.cuda.empty_cache()
+        extra["c4_n32768_fwd"] = summary(measure("c4", k4, 1))
+        torch.cuda.empty_cache()
+        for a5 in (1.25, 1.5, 2.0):
+            extra["c5_n8192_d128_alpha%g" % a5] = summary(measure("c5", k4, 1, alpha=a5))
+            torch.cuda.empty_cache()
+        extra["c3d_dense_regime"] = summary(measure("c3d", k4, 1))
+        torch.cuda.empty_cache()
+        for v in extra.values():
+            v.pop("data", None)
+        result["other_workloads"] = extra
+        result["fwd_n32768"] = extra["c4_n32768_fwd"]
+
     if not args.no_decode and args.workload == "c3":
         # decode shapes: a few new query rows against a 32768-key cache; bound by one read of K from HBM
         result["decode_nk32768"] = {}
@@ -304,23 +340,42 @@ def main():
     hev.close()
 
     if not args.no_cpu_baseline:
-        # the fp64 oracle as it stands, on a bounded sample of the same workload (first batches only)
+        # the fp64 oracle as it stands, on a bounded sample of the same workload: the first batches on all host
+        # threads, and one head on a single thread
         from oracle import oracle
         bs = min(B, 2)
-        sub = {k: data[k][:bs] for k in ("Q", "K", "V", "dO")}
-        okw = dict(beta=data["beta"], gamma=data["gamma"], delta=data["delta"], causal=True)
-        c0 = time.perf_counter()
-        oracle.attn_fwd(sub["Q"], sub["K"], sub["V"], alpha, **okw)
-        if do_bwd:
-            oracle.attn_bwd(sub["Q"], sub["K"], sub["V"], sub["dO"], alpha, **okw)
-        c1 = time.perf_counter()
-        sample_flops = dense_flops * bs / B
+        sub = {k: data_main[k][:bs] for k in ("Q", "K", "V", "dO") if k in data_main}
+        okw = dict(beta=data_main["beta"], gamma=data_main["gamma"], delta=data_main["delta"], causal=True)
+
+        def run_oracle(s, kw):
+            c0 = time.perf_counter()
+            oracle.attn_fwd(s["Q"], s["K"], s["V"], alpha, **kw)
+            if do_bwd:
+                oracle.attn_bwd(s["Q"], s["K"], s["V"], s["dO"], alpha, **kw)
+            return time.perf_counter() - c0
+
+        t_all = run_oracle(sub, okw)
+        one = {k: v[:1, :1] for k, v in sub.items()}
+        okw1 = dict(okw)
+        if okw1["beta"] is not None:
+            okw1["beta"], okw1["gamma"] = okw1["beta"][:1], okw1["gamma"][:1]
+        t_one = None
+        try:
+            # the oracle library reads the thread count per call through OpenMP's runtime routine
+            omp = ctypes.CDLL("libgomp.so.1")
+            nthreads = oracle.num_threads()
+            omp.omp_set_num_threads(1)
+            t_one = run_oracle(one, okw1)
+            omp.omp_set_num_threads(nthreads)
+        except OSError:
+            pass
         result["cpu_baseline"] = {
-            "value": sample_flops / (c1 - c0) / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(),
-            "kind": "oracle",
+            "value": bs * n / t_all, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
             "sample": "fp64 oracle %s on the first %d of %d batches (%d heads, n=%d), %.1f s wall"
-                      % ("fwd+bwd" if do_bwd else "fwd", bs, B, bs * H, n, c1 - c0),
-            "tokens_per_s": bs * n / (c1 - c0),
+                      % ("fwd+bwd" if do_bwd else "fwd", bs, B, bs * H, n, t_all),
+            "one_core": None if t_one is None else {
+                "value": n / H / t_one, "unit": "tokens/s",
+                "sample": "one head (1/%d of a batch) on one thread, %.1f s wall" % (H, t_one)},
         }
     print(json.dumps(result))
 

@@ -209,6 +209,12 @@ int entmax_attn_noalloc_init(void);
 /* Size of the built-in scratch buffer, a compile-time constant of the library. Host-only. */
 size_t entmax_attn_noalloc_scratch_bytes(void);
 
+/* Measurement aid (the matrix-core roofline a benchmark reports beside the data-sheet figure): launches
+ * `blocks` workgroups of four waves that each issue 4 * iters independent-chain v_mfma_f32_32x32x16_bf16
+ * instructions (2 * 32 * 32 * 16 flops each) and nothing else.  `sink` is device memory for one float (never
+ * written in practice).  The caller times the launch. */
+int entmax_attn_mfma_probe(int iters, int blocks, float* sink, void* hip_stream);
+
 /* Scratch bytes the forward (is_bwd = 0) or backward (is_bwd != 0) needs for
  * these parameters; 0 if the parameters are invalid. Host-only, no GPU call. */
 size_t entmax_attn_workspace_bytes(const entmax_attn_params* p, int is_bwd);

@@ -62,6 +62,8 @@ _lib.entmax_attn_noalloc_init.restype = ctypes.c_int
 _lib.entmax_attn_noalloc_init.argtypes = []
 _lib.entmax_attn_noalloc_scratch_bytes.restype = ctypes.c_size_t
 _lib.entmax_attn_noalloc_scratch_bytes.argtypes = []
+_lib.entmax_attn_mfma_probe.restype = ctypes.c_int
+_lib.entmax_attn_mfma_probe.argtypes = [ctypes.c_int, ctypes.c_int, _vp, _vp]
 _lib.entmax_attn_strerror.restype = ctypes.c_char_p
 _lib.entmax_attn_strerror.argtypes = [ctypes.c_int]
 
@@ -193,6 +195,14 @@ def entmax_attn_fwd(q, k, v, alpha=1.5, beta=None, gamma=None, delta=1.0, causal
     if rc != 0:
         raise EntmaxAttnError(rc)
     return out, tau
+
+
+def mfma_probe(iters, blocks, sink):
+    """Enqueue the matrix-pipeline probe; returns the flops it issues (the caller times it)."""
+    rc = _lib.entmax_attn_mfma_probe(int(iters), int(blocks), _ptr(sink), _stream())
+    if rc != 0:
+        raise EntmaxAttnError(rc)
+    return float(blocks) * 4 * iters * 4 * 2 * 32 * 32 * 16
 
 
 def noalloc_scratch_bytes():

@@ -61,6 +61,22 @@ void* noalloc_scratch_ptr() {
   return noalloc_ptr[dev];
 }
 
+// Back-to-back matrix instructions on four independent accumulators per wave, nothing else: what the matrix
+// pipeline of this chip sustains, for the benchmark's measured roofline.
+__global__ __launch_bounds__(kThreads) void mfma_probe_kernel(int iters, float* sink) {
+  const bf16x8_t a = __builtin_bit_cast(bf16x8_t, u32x4_t{0x3f803f80u + threadIdx.x, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u});
+  const bf16x8_t b = __builtin_bit_cast(bf16x8_t, u32x4_t{0x3f803f80u, 0x3f803f80u + blockIdx.x, 0x3f803f80u, 0x3f803f80u});
+  f32x16_t c0 = {}, c1 = {}, c2 = {}, c3 = {};
+  for (int it = 0; it < iters; ++it) {
+    c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c0, 0, 0, 0);
+    c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c1, 0, 0, 0);
+    c2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c2, 0, 0, 0);
+    c3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c3, 0, 0, 0);
+  }
+  const float s = c0[0] + c1[1] + c2[2] + c3[3];
+  if (s == 12345.678f) sink[0] = s;  // never true for these operands; keeps the products alive
+}
+
 int fwd_checked(const entmax_attn_params* p, const void* Q, const void* K, const void* V, const float* beta,
                 const float* gamma, void* O, float* tau, void* saved, size_t saved_bytes, uint64_t* stats,
                 void* workspace, size_t workspace_bytes, hipStream_t st, void* const* phase_events) {
@@ -117,6 +133,13 @@ int entmax_attn_fwd(const entmax_attn_params* p, const void* Q, const void* K, c
                     void* workspace, size_t workspace_bytes, void* hip_stream, void* const* phase_events) {
   return fwd_checked(p, Q, K, V, beta, gamma, O, tau, saved, saved_bytes, stats, workspace, workspace_bytes,
                      reinterpret_cast<hipStream_t>(hip_stream), phase_events);
+}
+
+int entmax_attn_mfma_probe(int iters, int blocks, float* sink, void* hip_stream) {
+  if (iters <= 0 || blocks <= 0 || blocks > (1 << 20) || !sink) return ENTMAX_ATTN_INVALID_ARG;
+  hipLaunchKernelGGL(mfma_probe_kernel, dim3((unsigned)blocks), dim3(kThreads), 0,
+                     reinterpret_cast<hipStream_t>(hip_stream), iters, sink);
+  return launch_ok() ? ENTMAX_ATTN_OK : ENTMAX_ATTN_LAUNCH_FAILED;
 }
 
 size_t entmax_attn_noalloc_scratch_bytes(void) { return kNoallocScratchBytes; }
