@@ -7,6 +7,7 @@
  *
  *     z_ij  = <q_i, k_j> / sqrt(D)                      visible keys j only
  *     s_ij  = scale_i * z_ij,   scale_i = delta + beta * (ln n)^gamma
+ *             (with a positional bias, below: scale_i * (z_ij + b_ij) or scale_i * z_ij + b_ij)
  *     p_ij  = [ (alpha-1) s_ij - tau_i ]_+ ^ (1/(alpha-1)),   sum_j p_ij = 1
  *     o_i   = sum_j p_ij v_j
  *
@@ -28,6 +29,15 @@
  *   - tau is [B,H,Nq] fp32 contiguous, in the units of eq. (entmax).
  *   - beta, gamma: fp32, [H] (scale_layout 1) or [B,H,Nq] (scale_layout 2),
  *     ignored (may be NULL) for scale_layout 0 where scale_i = delta.
+ *   - alibi_slopes: NULL (no positional bias, "NoPE"), or fp32 [H] slopes m_h >= 0 of the linear distance
+ *     bias of Sec. 4.2 / App. B (ALiBi definition): b_ij = -m_h * max(0, i + (Nk - Nq) - j), i.e. m_h (j - i)
+ *     for the keys at or before the query's position and 0 after it.  A head with m_h = 0 has no bias
+ *     (NAPE, Sec. 4.2: half of the heads biased, the other half not).  `bias_mode` places b_ij inside or
+ *     outside the ASEntmax scale.  The slopes are constants: no gradient is returned for them.  The
+ *     backward must be given the same slopes and bias_mode as the forward.  With the bias, keys further
+ *     from the query than the window of App. B (ALiBi proposition; evaluated per row from
+ *     |z_ij| <= |q_i| max_j |k_j| / sqrt(D)) cannot be in the support, and the kernels do not visit their
+ *     tiles.  bias_mode 1 needs scale_i != 0 (a row whose scale is exactly 0 is computed without bias).
  *   - Return value: 0 on success, a negative entmax_attn_status otherwise.
  *     Arguments are validated on the host before anything is launched: with
  *     INVALID_ARG, UNSUPPORTED_SHAPE, MISALIGNED or WORKSPACE_TOO_SMALL nothing has
@@ -67,6 +77,8 @@ typedef struct {
   int32_t scale_layout;    /* 0: scale = delta; 1: beta,gamma per head [H]; 2: per query [B,H,Nq] */
   int32_t logn_mode;       /* n in (ln n)^gamma: 0 = Nk for every row, 1 = number of keys visible to the row.
                               A row with n <= 1 uses scale = delta and contributes no beta/gamma gradient. */
+  int32_t bias_mode;       /* with alibi_slopes: 0 = s_ij = scale_i (z_ij + b_ij), the bias is part of the logit that
+                              eq. (asentmax) scales; 1 = s_ij = scale_i z_ij + b_ij.  Ignored without slopes. */
   int32_t path;            /* forward path: 0 = automatic (candidate-list kernel first; workgroups that meet a row
                               with too many candidates fall back to the tiled kernel; with Nq <= 8, or Nq <= 64 and
                               Nk >= 64 Nq -- the decoding shape -- kernels that split the keys instead),
@@ -102,6 +114,8 @@ enum {
   ENTMAX_STAT_FWD_LIST_QK = 17,      /* candidate-list kernel: score tiles computed (both sweeps) */
   ENTMAX_STAT_BWD_LIST_QK = 18,      /* support-list backward: score tiles computed by its one sweep */
   ENTMAX_STAT_BWD_SUPPORT = 19,      /* support-list backward: (row, key) entries with p > 0 */
+  ENTMAX_STAT_FWD_WINDOW_SKIPPED = 20, /* with alibi_slopes: visible tiles (counted in FWD_TILES_VISIBLE) that no sweep
+                                          visited because they lie beyond the rows' distance window */
   ENTMAX_ATTN_NUM_STATS = 24
 };
 
@@ -110,7 +124,7 @@ enum {
  * one more entry than the call has phases; entry 0 is recorded on the stream
  * before the first kernel and entry k after the last kernel of phase k-1. */
 enum {
-  ENTMAX_FWD_PHASE_PREPARE = 0,   /* with `saved`: zero fill of its per-key counters (else empty) */
+  ENTMAX_FWD_PHASE_PREPARE = 0,   /* with alibi_slopes: the heads' largest key norms (else empty) */
   ENTMAX_FWD_PHASE_LISTS = 1,     /* candidate-list kernel: two Q K^T sweeps (row maximum, candidates);
                                      decoding shape: the score rows, one pass over K */
   ENTMAX_FWD_PHASE_FINISH = 2,    /* threshold and output from the candidate lists (decoding shape: from the
@@ -120,7 +134,8 @@ enum {
   ENTMAX_FWD_NUM_PHASES = 5
 };
 enum {
-  ENTMAX_BWD_PHASE_LISTS = 0,      /* one Q K^T sweep at the saved threshold, or with `saved` only bookkeeping */
+  ENTMAX_BWD_PHASE_LISTS = 0,      /* one Q K^T sweep at the saved threshold (not with `saved`); with alibi_slopes
+                                      the heads' largest key norms */
   ENTMAX_BWD_PHASE_ROWS = 1,       /* per-key segment offsets; mu, dscale, dQ and the per-entry (p, dS) from the lists */
   ENTMAX_BWD_PHASE_TRANSPOSE = 2,  /* tiled path (heads the list kernel left over): operand copies */
   ENTMAX_BWD_PHASE_MASK = 3,       /* tiled path: non-zero tile map */
@@ -133,14 +148,13 @@ enum {
 
 /*
  * Forward (Sec. 2.1 with pi = alpha-entmax on ASEntmax-scaled logits).
- *   in : Q, K, V, beta, gamma
+ *   in : Q, K, V, beta, gamma, alibi_slopes
  *   out: O (dtype, written for every row), tau [B,H,Nq] fp32 (saved for the backward).
  *        A row with no visible key gets O = 0, tau = 0.
  *   stats: NULL or device uint64[ENTMAX_ATTN_NUM_STATS], added to.
  *   saved: NULL, or device memory of entmax_attn_saved_bytes(p) bytes, 256-byte aligned, owned by the
- *        caller: receives the rows' candidate lists (key, raw score) -- a superset of each row's support
- *        (Sec. 2.2: the keys with non-zero probability) -- for the backward, which then skips its own
- *        Q K^T sweep.  Opaque; valid only together with this call's tau and the same params and inputs.
+ *        caller: receives the rows' support lists (key, raw score) -- Sec. 2.2: the keys with non-zero
+ *        probability -- for the backward, which then skips its own Q K^T sweep.  Opaque; valid only together with this call's tau and the same params and inputs.
  *   saved_bytes: size of `saved` (ignored when saved is NULL); less than entmax_attn_saved_bytes(p) is
  *        refused with WORKSPACE_TOO_SMALL before anything is launched.
  *   workspace: device scratch of at least entmax_attn_workspace_bytes(p, 0)
@@ -159,20 +173,19 @@ enum {
  * the supports itself.
  */
 int entmax_attn_fwd(const entmax_attn_params* p, const void* Q, const void* K, const void* V, const float* beta,
-                    const float* gamma, void* O, float* tau, void* saved, size_t saved_bytes, uint64_t* stats,
+                    const float* gamma, const float* alibi_slopes, void* O, float* tau, void* saved, size_t saved_bytes, uint64_t* stats,
                     void* workspace, size_t workspace_bytes, void* hip_stream, void* const* phase_events);
 
 /*
  * Backward (exact derivative of the forward; Jacobian of eq. (entmax)).
- *   in : Q, K, V, dO, tau (as written by the forward), beta, gamma
+ *   in : Q, K, V, dO, tau (as written by the forward), beta, gamma, alibi_slopes
  *   out: dQ, dK, dV (dtype; every element written);
  *        dbeta, dgamma fp32 in beta/gamma's layout, OVERWRITTEN (not
  *        accumulated); ignored (may be NULL) for scale_layout 0.
  *   O is accepted for symmetry with the usual attention backward and may be NULL
  *   (the row term is rebuilt from tau, not from O).
  *   saved: NULL, or the buffer the forward filled for these same inputs (read only).  With it the
- *        rows' supports are taken from the forward's lists (entries whose probability is zero at tau
- *        are dropped); without it one Q K^T sweep at tau rebuilds them.  Same results either way up
+ *        rows' supports are taken from the forward's lists; without it one Q K^T sweep at tau rebuilds them.  Same results either way up
  *        to the summation order inside a row.
  *   saved_bytes: size of `saved`, checked as in the forward.
  *   workspace: at least entmax_attn_workspace_bytes(p, 1) bytes, 256-byte aligned.
@@ -183,7 +196,7 @@ int entmax_attn_fwd(const entmax_attn_params* p, const void* Q, const void* K, c
  */
 int entmax_attn_bwd(const entmax_attn_params* p, const void* Q, const void* K, const void* V, const void* O,
                     const void* dO, const float* tau, const void* saved, size_t saved_bytes, const float* beta,
-                    const float* gamma, void* dQ, void* dK, void* dV, float* dbeta, float* dgamma, uint64_t* stats,
+                    const float* gamma, const float* alibi_slopes, void* dQ, void* dK, void* dV, float* dbeta, float* dgamma, uint64_t* stats,
                     void* workspace, size_t workspace_bytes, void* hip_stream, void* const* phase_events);
 
 /*
@@ -201,8 +214,8 @@ int entmax_attn_bwd(const entmax_attn_params* p, const void* Q, const void* K, c
  *     entmax_attn_noalloc_init() (call it once per device, with that device current, before a capture).
  */
 int entmax_attn_fwd_noalloc(const entmax_attn_params* p, const void* Q, const void* K, const void* V,
-                            const float* beta, const float* gamma, void* O, float* tau, uint64_t* stats,
-                            void* hip_stream);
+                            const float* beta, const float* gamma, const float* alibi_slopes, void* O, float* tau,
+                            uint64_t* stats, void* hip_stream);
 /* Looks up the built-in scratch buffer of the current device; 0 on success, ENTMAX_ATTN_LAUNCH_FAILED if the
  * runtime cannot resolve it. */
 int entmax_attn_noalloc_init(void);

@@ -25,6 +25,7 @@ STAT_NAMES = {
     "fwd_solve_sweeps": 5, "fwd_blocks": 6, "fwd_eval_tiles": 7,
     "bwd_tiles_visible": 8, "bwd_qk_mask": 9, "bwd_active_tiles": 10, "bwd_dq_tiles": 11, "bwd_dkv_tiles": 12,
     "fwd_cand_tiles": 13, "fwd_candidates": 14, "fwd_support": 15, "fwd_sparse_blocks": 16, "fwd_list_qk": 17, "bwd_list_qk": 18, "bwd_support": 19,
+    "fwd_window_skipped": 20,
 }
 FWD_NUM_PHASES = 5
 BWD_NUM_PHASES = 8
@@ -36,7 +37,8 @@ class Params(ctypes.Structure):
     _fields_ = [
         ("B", ctypes.c_int32), ("H", ctypes.c_int32), ("Nq", ctypes.c_int32), ("Nk", ctypes.c_int32),
         ("D", ctypes.c_int32), ("dtype", ctypes.c_int32), ("causal", ctypes.c_int32),
-        ("scale_layout", ctypes.c_int32), ("logn_mode", ctypes.c_int32), ("path", ctypes.c_int32),
+        ("scale_layout", ctypes.c_int32), ("logn_mode", ctypes.c_int32), ("bias_mode", ctypes.c_int32),
+        ("path", ctypes.c_int32),
         ("alpha", ctypes.c_float), ("delta", ctypes.c_float),
         ("q_stride_b", ctypes.c_int64), ("q_stride_h", ctypes.c_int64), ("q_stride_n", ctypes.c_int64),
         ("kv_stride_b", ctypes.c_int64), ("kv_stride_h", ctypes.c_int64), ("kv_stride_n", ctypes.c_int64),
@@ -45,10 +47,10 @@ class Params(ctypes.Structure):
 
 _vp = ctypes.c_void_p
 _lib.entmax_attn_fwd.restype = ctypes.c_int
-_lib.entmax_attn_fwd.argtypes = [ctypes.POINTER(Params), _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp,
-                                 _vp, ctypes.c_size_t, _vp, _vp]
+_lib.entmax_attn_fwd.argtypes = [ctypes.POINTER(Params)] + [_vp] * 9 + [ctypes.c_size_t, _vp, _vp, ctypes.c_size_t, _vp,
+                                                                     _vp]
 _lib.entmax_attn_bwd.restype = ctypes.c_int
-_lib.entmax_attn_bwd.argtypes = ([ctypes.POINTER(Params)] + [_vp] * 7 + [ctypes.c_size_t] + [_vp] * 9 +
+_lib.entmax_attn_bwd.argtypes = ([ctypes.POINTER(Params)] + [_vp] * 7 + [ctypes.c_size_t] + [_vp] * 10 +
                                  [ctypes.c_size_t, _vp, _vp])
 _lib.entmax_attn_workspace_bytes.restype = ctypes.c_size_t
 _lib.entmax_attn_workspace_bytes.argtypes = [ctypes.POINTER(Params), ctypes.c_int]
@@ -57,7 +59,7 @@ _lib.entmax_attn_saved_bytes.argtypes = [ctypes.POINTER(Params)]
 _lib.entmax_attn_check_params.restype = ctypes.c_int
 _lib.entmax_attn_check_params.argtypes = [ctypes.POINTER(Params)]
 _lib.entmax_attn_fwd_noalloc.restype = ctypes.c_int
-_lib.entmax_attn_fwd_noalloc.argtypes = [ctypes.POINTER(Params)] + [_vp] * 9
+_lib.entmax_attn_fwd_noalloc.argtypes = [ctypes.POINTER(Params)] + [_vp] * 10
 _lib.entmax_attn_noalloc_init.restype = ctypes.c_int
 _lib.entmax_attn_noalloc_init.argtypes = []
 _lib.entmax_attn_noalloc_scratch_bytes.restype = ctypes.c_size_t
@@ -82,7 +84,7 @@ def _ptr(t):
     return None if t is None else ctypes.c_void_p(t.data_ptr())
 
 
-def make_params(q, k, alpha, delta, causal, beta, logn_mode, path=0):
+def make_params(q, k, alpha, delta, causal, beta, logn_mode, path=0, bias_mode=0):
     if q.dim() != 4 or k.dim() != 4 or q.shape[:2] != k.shape[:2] or q.shape[3] != k.shape[3]:
         raise ValueError("Q must be [B,H,Nq,D] and K [B,H,Nk,D]")
     B, H, Nq, D = q.shape
@@ -94,7 +96,7 @@ def make_params(q, k, alpha, delta, causal, beta, logn_mode, path=0):
     else:
         raise TypeError("Q must be bfloat16 or float32")
     layout = 0 if beta is None else (1 if beta.dim() == 1 else 2)
-    p = Params(B, H, Nq, Nk, D, dt, int(bool(causal)), layout, int(logn_mode), int(path), float(alpha), float(delta),
+    p = Params(B, H, Nq, Nk, D, dt, int(bool(causal)), layout, int(logn_mode), int(bias_mode), int(path), float(alpha), float(delta),
                0, 0, 0, 0, 0, 0)
     if not q.is_contiguous():
         if q.stride(3) != 1:
@@ -124,6 +126,13 @@ def _check_scale(p, q, beta, gamma):
     for name, t in (("beta", beta), ("gamma", gamma)):
         if t.dtype != torch.float32 or not t.is_contiguous() or tuple(t.shape) != want or t.device != q.device:
             raise ValueError("%s must be a contiguous float32 tensor of shape %s on Q's device" % (name, want))
+
+
+def _check_slopes(p, q, slopes):
+    if slopes is None:
+        return
+    if slopes.dtype != torch.float32 or not slopes.is_contiguous() or tuple(slopes.shape) != (p.H,) or slopes.device != q.device:
+        raise ValueError("alibi_slopes must be a contiguous float32 tensor of shape (%d,) on Q's device" % p.H)
 
 
 def _check_aux(p, stats, saved, workspace, is_bwd):
@@ -166,12 +175,16 @@ def _stream():
 
 
 def entmax_attn_fwd(q, k, v, alpha=1.5, beta=None, gamma=None, delta=1.0, causal=True, logn_mode=0, path=0,
-                    out=None, tau=None, stats=None, workspace=None, phase_events=None, saved=None):
+                    out=None, tau=None, stats=None, workspace=None, phase_events=None, saved=None, alibi_slopes=None,
+                    bias_mode=0):
     """O, tau = entmax attention forward.  q [B,H,Nq,D], k,v [B,H,Nk,D] on the GPU, bf16 or fp32;
     beta,gamma fp32 [H] or [B,H,Nq] or None.  stats: optional uint64/int64 device tensor [NUM_STATS] (added to).
     path: 0 automatic, 1 tiled kernel only.  phase_events: optional list of FWD_NUM_PHASES + 1 hipEvent_t handles.
-    saved: optional uint8 device tensor of saved_bytes(params) bytes, filled for the backward."""
-    p = make_params(q, k, alpha, delta, causal, beta, logn_mode, path)
+    saved: optional uint8 device tensor of saved_bytes(params) bytes, filled for the backward.
+    alibi_slopes: optional fp32 [H] slopes of the linear distance bias (0 = head without bias); bias_mode 0 puts the
+    bias inside the ASEntmax scale, 1 outside."""
+    p = make_params(q, k, alpha, delta, causal, beta, logn_mode, path, bias_mode)
+    _check_slopes(p, q, alibi_slopes)
     if k.dtype != q.dtype or k.device != q.device:
         raise TypeError("K must have the dtype and device of Q")
     _check_like("V", v, k)
@@ -189,8 +202,9 @@ def entmax_attn_fwd(q, k, v, alpha=1.5, beta=None, gamma=None, delta=1.0, causal
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
     ev = _events_arg(phase_events, FWD_NUM_PHASES)
-    rc = _lib.entmax_attn_fwd(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(beta), _ptr(gamma), _ptr(out),
-                              _ptr(tau), _ptr(saved), 0 if saved is None else saved.numel(), _ptr(stats),
+    rc = _lib.entmax_attn_fwd(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(beta), _ptr(gamma),
+                              _ptr(alibi_slopes), _ptr(out), _ptr(tau), _ptr(saved),
+                              0 if saved is None else saved.numel(), _ptr(stats),
                               _ptr(workspace), workspace.numel(), _stream(), ev)
     if rc != 0:
         raise EntmaxAttnError(rc)
@@ -216,10 +230,11 @@ def noalloc_init():
 
 
 def entmax_attn_fwd_noalloc(q, k, v, out, tau, alpha=1.5, beta=None, gamma=None, delta=1.0, causal=True, logn_mode=0,
-                            path=0, stats=None):
+                            path=0, stats=None, alibi_slopes=None, bias_mode=0):
     """Forward through the entry point that allocates nothing: the caller brings `out` and `tau`, the scratch is
     the library's built-in buffer (noalloc_scratch_bytes()).  Raises EntmaxAttnError(-6) for problems beyond it."""
-    p = make_params(q, k, alpha, delta, causal, beta, logn_mode, path)
+    p = make_params(q, k, alpha, delta, causal, beta, logn_mode, path, bias_mode)
+    _check_slopes(p, q, alibi_slopes)
     if k.dtype != q.dtype or k.device != q.device:
         raise TypeError("K must have the dtype and device of Q")
     _check_like("V", v, k)
@@ -228,18 +243,19 @@ def entmax_attn_fwd_noalloc(q, k, v, out, tau, alpha=1.5, beta=None, gamma=None,
     _check_aux(p, stats, None, None, False)
     if tau.dtype != torch.float32 or not tau.is_contiguous() or tau.shape != q.shape[:3]:
         raise ValueError("tau must be a contiguous float32 tensor [B,H,Nq]")
-    rc = _lib.entmax_attn_fwd_noalloc(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(beta), _ptr(gamma), _ptr(out),
-                                      _ptr(tau), _ptr(stats), _stream())
+    rc = _lib.entmax_attn_fwd_noalloc(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(beta), _ptr(gamma),
+                                      _ptr(alibi_slopes), _ptr(out), _ptr(tau), _ptr(stats), _stream())
     if rc != 0:
         raise EntmaxAttnError(rc)
     return out, tau
 
 
 def entmax_attn_bwd(q, k, v, o, do, tau, alpha=1.5, beta=None, gamma=None, delta=1.0, causal=True, logn_mode=0, path=0,
-                    stats=None, workspace=None, phase_events=None, saved=None):
+                    stats=None, workspace=None, phase_events=None, saved=None, alibi_slopes=None, bias_mode=0):
     """dQ, dK, dV, dbeta, dgamma = entmax attention backward (dbeta/dgamma None without scale parameters).
-    saved: the buffer the forward filled for the same inputs, or None."""
-    p = make_params(q, k, alpha, delta, causal, beta, logn_mode, path)
+    saved: the buffer the forward filled for the same inputs, or None.  alibi_slopes, bias_mode: as in the forward."""
+    p = make_params(q, k, alpha, delta, causal, beta, logn_mode, path, bias_mode)
+    _check_slopes(p, q, alibi_slopes)
     if k.dtype != q.dtype or k.device != q.device:
         raise TypeError("K must have the dtype and device of Q")
     _check_like("V", v, k)
@@ -258,7 +274,8 @@ def entmax_attn_bwd(q, k, v, o, do, tau, alpha=1.5, beta=None, gamma=None, delta
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
     ev = _events_arg(phase_events, BWD_NUM_PHASES)
     rc = _lib.entmax_attn_bwd(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(do), _ptr(tau), _ptr(saved),
-                              0 if saved is None else saved.numel(), _ptr(beta), _ptr(gamma), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(dbeta), _ptr(dgamma), _ptr(stats),
+                              0 if saved is None else saved.numel(), _ptr(beta), _ptr(gamma),
+                              _ptr(alibi_slopes), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(dbeta), _ptr(dgamma), _ptr(stats),
                               _ptr(workspace), workspace.numel(), _stream(), ev)
     if rc != 0:
         raise EntmaxAttnError(rc)

@@ -1,7 +1,7 @@
 """Builds the C-ABI library (csrc/ -> lib/libentmax_attn.so) with hipcc for gfx950.
 
-The kernels of each (launcher, element type, head dimension) combination are a translation unit of
-their own (csrc/inst.hip compiled with different -D flags), so the units compile in parallel."""
+The kernels of each (launcher, element type, head dimension, with / without the distance-bias code)
+combination are a translation unit of their own (csrc/inst.hip compiled with different -D flags), so the units compile in parallel."""
 import concurrent.futures
 import os
 import subprocess
@@ -32,8 +32,10 @@ def translation_units():
     for leg in ("FWD", "BWD"):
         for tname, ctype in (("bf16", "bf16_t"), ("f32", "float")):
             for d in (64, 128):
-                units.append(("%s_%s_%d" % (leg.lower(), tname, d), "inst.hip",
-                              ["-DENTMAX_INST_%s" % leg, "-DENTMAX_INST_T=%s" % ctype, "-DENTMAX_INST_D=%d" % d]))
+                for bias in (0, 1):
+                    units.append(("%s_%s_%d%s" % (leg.lower(), tname, d, "_bias" if bias else ""), "inst.hip",
+                                  ["-DENTMAX_INST_%s" % leg, "-DENTMAX_INST_T=%s" % ctype, "-DENTMAX_INST_D=%d" % d,
+                                   "-DENTMAX_INST_BIAS=%d" % bias]))
     return units
 
 
@@ -47,7 +49,7 @@ def build_library(verbose=False, jobs=None):
     """Compile every HIP source into lib/libentmax_attn.so (always recompiles)."""
     os.makedirs(OBJ_DIR, exist_ok=True)
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    inc = ["-I", os.path.join(ROOT, "include"), "-I", CSRC] + os.environ.get("ENTMAX_EXTRA_FLAGS", "").split()
+    inc = ["-I", os.path.join(ROOT, "include"), "-I", CSRC]
     jobs = jobs or min(8, os.cpu_count() or 1)
     cmds = []
     objs = []

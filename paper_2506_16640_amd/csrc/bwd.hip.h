@@ -47,9 +47,9 @@ struct MaskTile {
   static constexpr int value = sizeof(T) == 2 ? 128 : 32;
 };
 
-template <typename T, int D, int AM>
+template <typename T, int D, int AM, bool BIAS>
 __device__ __forceinline__ void bwd_mask_block(const BwdArgs& A, int bh_, int blk_, char* smem) {
-  using C = QCtx<T, D, MaskTile<T>::value>;
+  using C = QCtx<T, D, MaskTile<T>::value, BIAS>;
   constexpr int KT = C::KT, NSB = C::NSB, TB = C::kTileBytes;
   const Geom& g = A.g;
   WaveMask wm;
@@ -58,6 +58,7 @@ __device__ __forceinline__ void bwd_mask_block(const BwdArgs& A, int bh_, int bl
   C q;
   q.init(g, A.Q, bh_, blk_);
   if (A.head_flag && __builtin_amdgcn_readfirstlane(A.head_flag[q.bh]) == 0) return;
+  q.init_window(g);
   for (int w = q.tid; w < kWaves * A.mask_words; w += kThreads) wm.words[w] = 0u;
   const float tau = q.valid ? A.tau[(long long)q.bh * g.Nq + q.i] : 0.f;
   const bool live = q.valid && q.lim > 0;
@@ -67,13 +68,14 @@ __device__ __forceinline__ void bwd_mask_block(const BwdArgs& A, int bh_, int bl
   slots[0].row_bytes = g.kv_sn * (long long)sizeof(T);
   unsigned n_vis = 0, n_act = 0;
   sweep_tiles<C, T, D, 1, 0>(
-      smem, slots, q.ntiles, g.Nk, q.tid, [](int) { return true; },
+      smem, slots, q.ntiles, g.Nk, q.tid, [&](int kt) { return q.tile_in_window(kt); },
       [&](int kt, const char* tl) {
+        if (!q.tile_in_wave_window(kt)) return;
         if ((kt + 1) * KT <= q.wave_lim_min) {
           // interior tile: every key is visible to every row of the wave
           f32x16_t acc[NSB];
 #pragma unroll
-          for (int sb = 0; sb < NSB; ++sb) acc[sb] = q.scores(tl, sb);
+          for (int sb = 0; sb < NSB; ++sb) acc[sb] = q.scores(tl, sb, kt);
 #pragma unroll
           for (int sb = 0; sb < NSB; ++sb) {
             float lm = max16(acc[sb]);
@@ -90,7 +92,7 @@ __device__ __forceinline__ void bwd_mask_block(const BwdArgs& A, int bh_, int bl
         f32x16_t acc[NSB];
 #pragma unroll
         for (int sb = 0; sb < NSB; ++sb)
-          if (act & (1u << sb)) acc[sb] = q.scores(tl, sb);
+          if (act & (1u << sb)) acc[sb] = q.scores(tl, sb, kt);
 #pragma unroll
         for (int sb = 0; sb < NSB; ++sb) {
           if (!(act & (1u << sb))) continue;
@@ -124,9 +126,9 @@ __device__ __forceinline__ void bwd_mask_block(const BwdArgs& A, int bh_, int bl
 
 // ------------------------------------------------- row scalars, dscale and dQ
 
-template <typename T, int D, int AM>
+template <typename T, int D, int AM, bool BIAS>
 __device__ __forceinline__ void bwd_dq_block(const BwdArgs& A, int bh_, int blk_, char* smem) {
-  using C = QCtx<T, D>;
+  using C = QCtx<T, D, Elem<T>::kTile, BIAS>;
   constexpr int KT = C::KT, NSB = C::NSB, NC = C::NC, NM = C::NM, TB = C::kTileBytes;
   const Geom& g = A.g;
   char* tiles = smem;  // 2 buffers x 3 slots: K, V, Kt
@@ -183,7 +185,7 @@ __device__ __forceinline__ void bwd_dq_block(const BwdArgs& A, int bh_, int blk_
     for (int sb = 0; sb < NSB; ++sb) {
       if (!(act & (1u << sb))) continue;
       int j0 = kt * KT + sb * 32;
-      f32x16_t acc = q.scores(tl, sb);
+      f32x16_t acc = q.scores(tl, sb, kt);
       const bool masked = j0 + 32 > q.wave_lim_min;
       const int rel = q.lim - j0;
       float x[16];
@@ -203,6 +205,15 @@ __device__ __forceinline__ void bwd_dq_block(const BwdArgs& A, int bh_, int blk_
 #pragma unroll
       for (int cc = 0; cc < NC; ++cc)
         dp = Elem<T>::mma(C::KTile::frag(tl + TB, sb * 32 + q.li, 2 * cc + q.hh), dof[cc], dp);
+      if constexpr (BIAS) {
+        // bias outside the scale: dscale_i = sum_j dS_ij z_ij needs the scores without their bias term
+        if (g.bias_mode == 1 && q.wave_bias) {
+          f32x16_t bb;
+          q.bias_block(bb, j0);
+#pragma unroll
+          for (int e = 0; e < 16; ++e) acc[e] -= bb[e];
+        }
+      }
       float w1[16], w2[16];
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
@@ -327,7 +338,8 @@ __device__ __forceinline__ void bwd_dkv_block(const BwdArgs& A, int bh_, int blk
   using TTile = typename C::XtTile;  // transposed: rows = features
   Stage<NTile> sq, sdo;
   Stage<TTile> sqt, sdot;
-  float rv[3] = {0.f, 0.f, 0.f};  // staged row values (threads < QT): tau, (alpha-1) c, mu
+  float rv[4] = {0.f, 0.f, 0.f, 0.f};  // staged row values (threads < QT): tau, (alpha-1) c, mu, bias per unit distance
+  const bool biased = g.slopes != nullptr && g.slopes[h] != 0.f;  // uniform
 
   const char* Qg = reinterpret_cast<const char*>(reinterpret_cast<const T*>(A.Q) + q_base);
   const char* dOg = reinterpret_cast<const char*>(reinterpret_cast<const T*>(A.dO) + q_base);
@@ -370,10 +382,13 @@ __device__ __forceinline__ void bwd_dkv_block(const BwdArgs& A, int bh_, int blk
         rv[0] = A.tau[ri];
         rv[1] = am1 * A.crow[ri];
         rv[2] = A.mu[ri];
+        // (alpha-1) s_ij = rv[1] <q_i,k_j> + rv[3] dist_ij: the same product a w as on the query side
+        if (biased) rv[3] = fabsf(rv[1]) * bias_w<D>(g, h, A.crow[ri], fabsf(rv[1]));
       } else {  // rows beyond Nq: x = -1 everywhere
         rv[0] = 1.f;
         rv[1] = 0.f;
         rv[2] = 0.f;
+        rv[3] = 0.f;
       }
     }
   };
@@ -388,6 +403,7 @@ __device__ __forceinline__ void bwd_dkv_block(const BwdArgs& A, int bh_, int blk
       rw[tid] = rv[0];
       rw[QT + tid] = rv[1];
       rw[2 * QT + tid] = rv[2];
+      rw[3 * QT + tid] = rv[3];
     }
   };
 
@@ -427,6 +443,7 @@ __device__ __forceinline__ void bwd_dkv_block(const BwdArgs& A, int bh_, int blk
           int i = i0 + 8 * gq + 4 * hh + rr;
           bool vis = jvalid && (!g.causal || (j <= i + off));
           float xp = fmaf(s[e], a4[rr], -t4[rr]);
+          if (biased) xp = fmaf(rw[3 * QT + rl + rr], (float)bias_dist(i + off, j), xp);
           x[e] = vis ? fmaxf(xp, 0.f) : 0.f;
           mur[e] = m4[rr];
           car[e] = a4[rr];
@@ -481,7 +498,7 @@ __device__ __forceinline__ void bwd_dkv_block(const BwdArgs& A, int bh_, int blk
 }
 
 #define ENTMAX_PAIRED_KERNEL(NAME, BLOCKFN, NBLK, OCC)                              \
-  template <typename T, int D, int AM>                                              \
+  template <typename T, int D, int AM, bool BIAS>                                   \
   __global__ __launch_bounds__(kThreads, OCC) void NAME(BwdArgs A) {                \
     extern __shared__ __attribute__((aligned(16))) char smem[];                     \
     const PairItem it = pair_item(NBLK);                                            \
@@ -490,19 +507,19 @@ __device__ __forceinline__ void bwd_dkv_block(const BwdArgs& A, int bh_, int blk
       const int blk = part ? it.second : it.first;                                  \
       if (blk < 0) break;                                                           \
       if (part) __syncthreads();                                                    \
-      BLOCKFN<T, D, AM>(A, it.bh, blk, smem);                                       \
+      BLOCKFN<T, D, AM, BIAS>(A, it.bh, blk, smem);                                 \
     }                                                                               \
   }
 ENTMAX_PAIRED_KERNEL(bwd_mask_kernel, bwd_mask_block, A.nqb, 3)
 #undef ENTMAX_PAIRED_KERNEL
 
 // The register-heavy kernels hold two workgroups per CU; one block per workgroup, long blocks first.
-template <typename T, int D, int AM>
+template <typename T, int D, int AM, bool BIAS>
 __global__ __launch_bounds__(kThreads) void bwd_dq_kernel(BwdArgs A) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int item = xcd_remap(blockIdx.x, gridDim.x);
   if (A.head_flag && __builtin_amdgcn_readfirstlane(A.head_flag[item / A.nqb]) == 0) return;
-  bwd_dq_block<T, D, AM>(A, item / A.nqb, A.nqb - 1 - item % A.nqb, smem);
+  bwd_dq_block<T, D, AM, BIAS>(A, item / A.nqb, A.nqb - 1 - item % A.nqb, smem);
 }
 template <typename T, int D, int AM>
 __global__ __launch_bounds__(kThreads) void bwd_dkv_kernel(BwdArgs A) {

@@ -63,14 +63,15 @@ struct BwdSparseArgs {
 // ------------------------------------------------------------------ rows
 
 // One Q K^T sweep at the saved threshold: the lists it writes are the rows' exact supports.
-template <typename T, int D, int AM>
+template <typename T, int D, int AM, bool BIAS>
 __device__ __forceinline__ void bwd_lists_block(const BwdSparseArgs& A, int bh_, int blk_, char* smem) {
-  using C = QCtx<T, D, FwdTile<T>::value>;
+  using C = QCtx<T, D, FwdTile<T>::value, BIAS>;
   constexpr int TB = C::kTileBytes;
   const Geom& g = A.g;
   int* ovf = reinterpret_cast<int*>(smem + 2 * TB);
   C q;
   q.init(g, A.Q, bh_, blk_);
+  q.init_window(g);
   const long long row_idx = (long long)q.bh * g.Nq + (q.valid ? q.i : 0);
   const float tau = q.valid ? A.tau[row_idx] : 0.f;
   const bool live = q.valid && q.lim > 0;
@@ -87,7 +88,7 @@ __device__ __forceinline__ void bwd_lists_block(const BwdSparseArgs& A, int bh_,
   }
 }
 
-template <typename T, int D, int AM>
+template <typename T, int D, int AM, bool BIAS>
 __global__ __launch_bounds__(kThreads, 3) void bwd_lists_kernel(BwdSparseArgs A) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const PairItem it = pair_item(A.nqb);
@@ -95,7 +96,7 @@ __global__ __launch_bounds__(kThreads, 3) void bwd_lists_kernel(BwdSparseArgs A)
     const int blk = part ? it.second : it.first;
     if (blk < 0) break;
     if (part) __syncthreads();
-    bwd_lists_block<T, D, AM>(A, it.bh, blk, smem);
+    bwd_lists_block<T, D, AM, BIAS>(A, it.bh, blk, smem);
   }
 }
 
@@ -115,6 +116,9 @@ __global__ __launch_bounds__(kThreads, D == 64 ? 2 : 1) void bwd_rows_kernel(Bwd
   const float c = scale * inv_sqrt_d;
   const float a = (g.alpha - 1.0f) * fabsf(c);  // same arithmetic as the sweep that made the lists
   const float sgn = (c < 0.f) ? -1.f : 1.f;
+  // distance bias outside the scale: dscale_i = sum_j dS_ij z_ij needs the listed scores without their bias term
+  const float w_out = (g.slopes && g.bias_mode == 1) ? bias_w<D>(g, rl.h, c, a) : 0.f;
+  const int pos = rl.i + (g.Nk - g.Nq);
   // every load that does not depend on another is issued before the first wait (the head's flags included)
   const int head_dense = A.head_flag[rl.bh];
   const float tau_raw = A.tau[row_idx];
@@ -204,8 +208,9 @@ __global__ __launch_bounds__(kThreads, D == 64 ? 2 : 1) void bwd_rows_kernel(Bwd
           float gdp = gg * dp;
           Z += gg;
           N += gdp;
-          sd1 = fmaf(gdp, d, sd1);
-          sd0 = fmaf(gg, d, sd0);
+          const float dz = (w_out != 0.f) ? fmaf(-w_out, (float)bias_dist(pos, (int)j), d) : d;
+          sd1 = fmaf(gdp, dz, sd1);
+          sd0 = fmaf(gg, dz, sd0);
 #pragma unroll
           for (int t = 0; t < DH; ++t) {
             const float kt = kk.get(t);

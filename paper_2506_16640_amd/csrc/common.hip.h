@@ -69,6 +69,16 @@ struct Elem<bf16_t> {
     f.v ^= u32x4_t{0x80008000u, 0x80008000u, 0x80008000u, 0x80008000u};
     return f;
   }
+  // sum of the squares of the fragment's 8 elements
+  static __device__ __forceinline__ float sumsq(const Frag<bf16_t>& f) {
+    float s = 0.f;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const float lo = __uint_as_float(f.v[k] << 16), hi = __uint_as_float(f.v[k] & 0xffff0000u);
+      s = fmaf(lo, lo, fmaf(hi, hi, s));
+    }
+    return s;
+  }
   // 8 fp32 values -> one fragment (round to nearest even)
   static __device__ __forceinline__ Frag<bf16_t> pack(const float* x) {
     bf16x8_t b;
@@ -118,6 +128,12 @@ struct Elem<float> {
     f.lo = -f.lo;
     f.hi = -f.hi;
     return f;
+  }
+  static __device__ __forceinline__ float sumsq(const Frag<float>& f) {
+    float s = 0.f;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) s = fmaf(f.lo[k], f.lo[k], fmaf(f.hi[k], f.hi[k], s));
+    return s;
   }
   static __device__ __forceinline__ Frag<float> pack(const float* x) {
     Frag<float> f;
@@ -273,6 +289,9 @@ struct Geom {
   int npad_k, npad_q;             // padded lengths (multiples of 64) of the transposed copies
   const float* beta;
   const float* gamma;
+  const float* slopes;  // NULL, or [H] slopes of the linear distance bias (Sec. 4.2, App. B ALiBi definition)
+  int bias_mode;        // 0: the bias is inside the ASEntmax scale, 1: outside
+  const float* knorm;   // with slopes: [B*H] largest key norm of the head (key_norm_kernel)
 };
 
 // Keys visible to query row i are j < row_limit(i) (Sec. 2.1: j <= i, shifted by
@@ -304,6 +323,24 @@ __device__ __forceinline__ float row_scale(const Geom& g, int b, int h, int i, i
   if (lnL) *lnL = ll;
   if (bt) *bt = be;
   return scale;
+}
+
+// Distance of key j from the position of query row i in the key sequence (App. B, ALiBi definition: the bias is
+// m_h (j - i) for keys at or before the query and 0 after it); pos = i + (Nk - Nq).
+__device__ __forceinline__ int bias_dist(int pos, int j) { return max(pos - j, 0); }
+
+// The kernels work on y_ij = a_i d_ij with a_i = (alpha-1) |scale_i| / sqrt(D) and d_ij the dot product with
+// the query negated when scale_i < 0.  The distance bias enters as d'_ij = d_ij + w_i dist_ij:
+//   bias_mode 0, s = scale (z + b):  (alpha-1) scale b = a w dist  =>  w = -sgn(scale) m sqrt(D)
+//   bias_mode 1, s = scale z + b:    (alpha-1) b       = a w dist  =>  w = -(alpha-1) m / a   (a = 0: no bias)
+// c = scale_i / sqrt(D).
+template <int D>
+__device__ __forceinline__ float bias_w(const Geom& g, int h, float c, float a) {
+  if (!g.slopes) return 0.f;
+  const float m = g.slopes[h];
+  if (m == 0.f || a == 0.f) return 0.f;
+  if (g.bias_mode == 0) return (c < 0.f ? m : -m) * sqrtf((float)D);
+  return -(g.alpha - 1.0f) * m / a;
 }
 
 // x^r and x^(r-1) for x >= 0, r = 1/(alpha-1) (eq. (entmax): p = x^r; its

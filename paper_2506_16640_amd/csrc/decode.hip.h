@@ -19,7 +19,7 @@
 namespace entmax {
 
 // dynamic LDS of decode_scores_kernel: Q rows as in memory, the groups' maxima, a coefficient and a limit per row
-inline size_t decode_scores_lds(int Nq, int D, size_t esize) { return (size_t)Nq * (D * esize + (kThreads / 8) * 4 + 8); }
+inline size_t decode_scores_lds(int Nq, int D, size_t esize) { return (size_t)Nq * (D * esize + (kThreads / 8) * 4 + 12); }
 constexpr int kDecodeSolveThreads = 1024;
 constexpr int kDecodeListCap = 4096;    // support candidates kept in LDS; longer ones are re-read from the score row
 
@@ -70,6 +70,7 @@ __global__ __launch_bounds__(kThreads) void decode_scores_kernel(DecodeArgs A) {
                                                                            // by the group's first lane only
   float* coef = group_max + g.Nq * kGroups;                                // [Nq]
   int* limit = reinterpret_cast<int*>(coef + g.Nq);                        // [Nq]
+  float* ybias = reinterpret_cast<float*>(limit + g.Nq);                   // [Nq] distance bias per unit distance, times (alpha-1)
   const int tid = threadIdx.x, bh = blockIdx.y, b = bh / g.H, h = bh % g.H;
   const int j0 = blockIdx.x * A.chunk;
   const T* Qh = reinterpret_cast<const T*>(A.Q) + (long long)b * g.q_sb + (long long)h * g.q_sh;
@@ -95,7 +96,10 @@ __global__ __launch_bounds__(kThreads) void decode_scores_kernel(DecodeArgs A) {
     const int lim = row_limit(g, tid);
     limit[tid] = lim;
     for (int w = 0; w < kGroups; ++w) group_max[tid * kGroups + w] = -kInf;
-    coef[tid] = (g.alpha - 1.0f) * row_scale(g, b, h, tid, lim, nullptr, nullptr, nullptr) * (1.0f / sqrtf((float)D));
+    const float cf = (g.alpha - 1.0f) * row_scale(g, b, h, tid, lim, nullptr, nullptr, nullptr) * (1.0f / sqrtf((float)D));
+    coef[tid] = cf;
+    // the same product a w as in the tiled kernels (bias_w(): sign taken from the scale)
+    ybias[tid] = fabsf(cf) * bias_w<D>(g, h, cf, fabsf(cf));
   }
   __syncthreads();
   for (int base = j0; base < jend; base += 128) {
@@ -111,6 +115,8 @@ __global__ __launch_bounds__(kThreads) void decode_scores_kernel(DecodeArgs A) {
         qv[w] = *reinterpret_cast<const u32x4_t*>(&qw[i * kRowWords + sub * (kRowWords / 8) + 4 * w]);
       const float c = coef[i];
       const int lim = limit[i];
+      const float yb = ybias[i];
+      const int pos = i + (g.Nk - g.Nq);
       float best = -kInf;
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
@@ -125,8 +131,8 @@ __global__ __launch_bounds__(kThreads) void decode_scores_kernel(DecodeArgs A) {
               dot = fmaf(__uint_as_float(kk[u].w[w][k]), __uint_as_float(qv[w][k]), dot);
           }
         }
-        const float zj = sum8(dot) * c;
         const int j = base + u * 32 + grp;
+        const float zj = fmaf(yb, (float)bias_dist(pos, j), sum8(dot) * c);
         if (j < lim) best = fmaxf(best, zj);
         if (sub == u && j < lim) A.scores[((long long)bh * g.Nq + i) * A.nks + j] = zj;
       }

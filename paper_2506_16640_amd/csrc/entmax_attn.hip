@@ -12,26 +12,24 @@
 using namespace entmax;
 
 namespace entmax {
-extern template int run_fwd<bf16_t, 64>(const entmax_attn_params*, const Layout&, const void*, const void*, const void*,
-                                        const float*, const float*, void*, float*, char*, uint64_t*, char*, hipStream_t,
-                                        void* const*);
-extern template int run_fwd<bf16_t, 128>(const entmax_attn_params*, const Layout&, const void*, const void*, const void*,
-                                         const float*, const float*, void*, float*, char*, uint64_t*, char*, hipStream_t,
-                                         void* const*);
-extern template int run_fwd<float, 64>(const entmax_attn_params*, const Layout&, const void*, const void*, const void*,
-                                       const float*, const float*, void*, float*, char*, uint64_t*, char*, hipStream_t,
-                                       void* const*);
-extern template int run_fwd<float, 128>(const entmax_attn_params*, const Layout&, const void*, const void*, const void*,
-                                        const float*, const float*, void*, float*, char*, uint64_t*, char*, hipStream_t,
-                                        void* const*);
+#define ENTMAX_FWD_SIG                                                                                                  \
+  (const entmax_attn_params*, const Layout&, const void*, const void*, const void*, const float*, const float*,        \
+   const float*, void*, float*, char*, uint64_t*, char*, hipStream_t, void* const*)
 #define ENTMAX_BWD_SIG                                                                                                  \
   (const entmax_attn_params*, const Layout&, const void*, const void*, const void*, const void*, const float*,         \
-   const char*, const float*, const float*, void*, void*, void*, float*, float*, uint64_t*, char*, hipStream_t,        \
-   void* const*)
-extern template int run_bwd<bf16_t, 64> ENTMAX_BWD_SIG;
-extern template int run_bwd<bf16_t, 128> ENTMAX_BWD_SIG;
-extern template int run_bwd<float, 64> ENTMAX_BWD_SIG;
-extern template int run_bwd<float, 128> ENTMAX_BWD_SIG;
+   const char*, const float*, const float*, const float*, void*, void*, void*, float*, float*, uint64_t*, char*,       \
+   hipStream_t, void* const*)
+#define ENTMAX_EXTERN(T, D)                                   \
+  extern template int run_fwd<T, D, false> ENTMAX_FWD_SIG;    \
+  extern template int run_fwd<T, D, true> ENTMAX_FWD_SIG;     \
+  extern template int run_bwd<T, D, false> ENTMAX_BWD_SIG;    \
+  extern template int run_bwd<T, D, true> ENTMAX_BWD_SIG;
+ENTMAX_EXTERN(bf16_t, 64)
+ENTMAX_EXTERN(bf16_t, 128)
+ENTMAX_EXTERN(float, 64)
+ENTMAX_EXTERN(float, 128)
+#undef ENTMAX_EXTERN
+#undef ENTMAX_FWD_SIG
 #undef ENTMAX_BWD_SIG
 }  // namespace entmax
 
@@ -77,8 +75,17 @@ __global__ __launch_bounds__(kThreads) void mfma_probe_kernel(int iters, float* 
   if (s == 12345.678f) sink[0] = s;  // never true for these operands; keeps the products alive
 }
 
+template <typename T, int D, typename... Args>
+int fwd_dispatch(bool bias, Args... args) {
+  return bias ? run_fwd<T, D, true>(args...) : run_fwd<T, D, false>(args...);
+}
+template <typename T, int D, typename... Args>
+int bwd_dispatch(bool bias, Args... args) {
+  return bias ? run_bwd<T, D, true>(args...) : run_bwd<T, D, false>(args...);
+}
+
 int fwd_checked(const entmax_attn_params* p, const void* Q, const void* K, const void* V, const float* beta,
-                const float* gamma, void* O, float* tau, void* saved, size_t saved_bytes, uint64_t* stats,
+                const float* gamma, const float* slopes, void* O, float* tau, void* saved, size_t saved_bytes, uint64_t* stats,
                 void* workspace, size_t workspace_bytes, hipStream_t st, void* const* phase_events) {
   int rc = check_params(p);
   if (rc != ENTMAX_ATTN_OK) return rc;
@@ -91,18 +98,23 @@ int fwd_checked(const entmax_attn_params* p, const void* Q, const void* K, const
   if (p->scale_layout != 0 && (!beta || !gamma)) return ENTMAX_ATTN_INVALID_ARG;
   if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O) || misaligned(workspace) || misaligned(saved))
     return ENTMAX_ATTN_MISALIGNED;
-  if ((reinterpret_cast<uintptr_t>(tau) & 3u) || (reinterpret_cast<uintptr_t>(stats) & 7u)) return ENTMAX_ATTN_MISALIGNED;
+  if ((reinterpret_cast<uintptr_t>(tau) & 3u) || (reinterpret_cast<uintptr_t>(stats) & 7u) ||
+      (reinterpret_cast<uintptr_t>(slopes) & 3u))
+    return ENTMAX_ATTN_MISALIGNED;
   if (workspace_bytes < workspace_bytes_of(p, 0)) return ENTMAX_ATTN_WORKSPACE_TOO_SMALL;
   if (saved && saved_bytes < saved_bytes_of(p)) return ENTMAX_ATTN_WORKSPACE_TOO_SMALL;
   Layout L = make_layout(p);
   char* ws = reinterpret_cast<char*>(workspace);
   char* sv = reinterpret_cast<char*>(saved);
+  const bool bias = slopes != nullptr;
   if (p->dtype == ENTMAX_ATTN_BF16) {
-    if (p->D == 64) return run_fwd<bf16_t, 64>(p, L, Q, K, V, beta, gamma, O, tau, sv, stats, ws, st, phase_events);
-    return run_fwd<bf16_t, 128>(p, L, Q, K, V, beta, gamma, O, tau, sv, stats, ws, st, phase_events);
+    if (p->D == 64)
+      return fwd_dispatch<bf16_t, 64>(bias, p, L, Q, K, V, beta, gamma, slopes, O, tau, sv, stats, ws, st, phase_events);
+    return fwd_dispatch<bf16_t, 128>(bias, p, L, Q, K, V, beta, gamma, slopes, O, tau, sv, stats, ws, st, phase_events);
   }
-  if (p->D == 64) return run_fwd<float, 64>(p, L, Q, K, V, beta, gamma, O, tau, sv, stats, ws, st, phase_events);
-  return run_fwd<float, 128>(p, L, Q, K, V, beta, gamma, O, tau, sv, stats, ws, st, phase_events);
+  if (p->D == 64)
+    return fwd_dispatch<float, 64>(bias, p, L, Q, K, V, beta, gamma, slopes, O, tau, sv, stats, ws, st, phase_events);
+  return fwd_dispatch<float, 128>(bias, p, L, Q, K, V, beta, gamma, slopes, O, tau, sv, stats, ws, st, phase_events);
 }
 
 }  // namespace
@@ -129,9 +141,10 @@ const char* entmax_attn_strerror(int code) {
 }
 
 int entmax_attn_fwd(const entmax_attn_params* p, const void* Q, const void* K, const void* V, const float* beta,
-                    const float* gamma, void* O, float* tau, void* saved, size_t saved_bytes, uint64_t* stats,
-                    void* workspace, size_t workspace_bytes, void* hip_stream, void* const* phase_events) {
-  return fwd_checked(p, Q, K, V, beta, gamma, O, tau, saved, saved_bytes, stats, workspace, workspace_bytes,
+                    const float* gamma, const float* alibi_slopes, void* O, float* tau, void* saved, size_t saved_bytes,
+                    uint64_t* stats, void* workspace, size_t workspace_bytes, void* hip_stream,
+                    void* const* phase_events) {
+  return fwd_checked(p, Q, K, V, beta, gamma, alibi_slopes, O, tau, saved, saved_bytes, stats, workspace, workspace_bytes,
                      reinterpret_cast<hipStream_t>(hip_stream), phase_events);
 }
 
@@ -147,21 +160,22 @@ size_t entmax_attn_noalloc_scratch_bytes(void) { return kNoallocScratchBytes; }
 int entmax_attn_noalloc_init(void) { return noalloc_scratch_ptr() ? ENTMAX_ATTN_OK : ENTMAX_ATTN_LAUNCH_FAILED; }
 
 int entmax_attn_fwd_noalloc(const entmax_attn_params* p, const void* Q, const void* K, const void* V,
-                            const float* beta, const float* gamma, void* O, float* tau, uint64_t* stats,
-                            void* hip_stream) {
+                            const float* beta, const float* gamma, const float* alibi_slopes, void* O, float* tau,
+                            uint64_t* stats, void* hip_stream) {
   int rc = check_params(p);
   if (rc != ENTMAX_ATTN_OK) return rc;
   if (workspace_bytes_of(p, 0) > kNoallocScratchBytes) return ENTMAX_ATTN_SCRATCH_LIMIT;
   void* ws = noalloc_scratch_ptr();
   if (!ws) return ENTMAX_ATTN_LAUNCH_FAILED;
-  return fwd_checked(p, Q, K, V, beta, gamma, O, tau, nullptr, 0, stats, ws, kNoallocScratchBytes,
+  return fwd_checked(p, Q, K, V, beta, gamma, alibi_slopes, O, tau, nullptr, 0, stats, ws, kNoallocScratchBytes,
                      reinterpret_cast<hipStream_t>(hip_stream), nullptr);
 }
 
 int entmax_attn_bwd(const entmax_attn_params* p, const void* Q, const void* K, const void* V, const void* O,
                     const void* dO, const float* tau, const void* saved, size_t saved_bytes, const float* beta,
-                    const float* gamma, void* dQ, void* dK, void* dV, float* dbeta, float* dgamma, uint64_t* stats,
-                    void* workspace, size_t workspace_bytes, void* hip_stream, void* const* phase_events) {
+                    const float* gamma, const float* alibi_slopes, void* dQ, void* dK, void* dV, float* dbeta,
+                    float* dgamma, uint64_t* stats, void* workspace, size_t workspace_bytes, void* hip_stream,
+                    void* const* phase_events) {
   (void)O;
   int rc = check_params(p);
   if (rc != ENTMAX_ATTN_OK) return rc;
@@ -183,18 +197,20 @@ int entmax_attn_bwd(const entmax_attn_params* p, const void* Q, const void* K, c
   Layout L = make_layout(p);
   char* ws = reinterpret_cast<char*>(workspace);
   const char* sv = reinterpret_cast<const char*>(saved);
+  const bool bias = alibi_slopes != nullptr;
+  if (reinterpret_cast<uintptr_t>(alibi_slopes) & 3u) return ENTMAX_ATTN_MISALIGNED;
   if (p->dtype == ENTMAX_ATTN_BF16) {
     if (p->D == 64)
-      return run_bwd<bf16_t, 64>(p, L, Q, K, V, dO, tau, sv, beta, gamma, dQ, dK, dV, dbeta, dgamma, stats, ws, st,
-                                 phase_events);
-    return run_bwd<bf16_t, 128>(p, L, Q, K, V, dO, tau, sv, beta, gamma, dQ, dK, dV, dbeta, dgamma, stats, ws, st,
-                                phase_events);
+      return bwd_dispatch<bf16_t, 64>(bias, p, L, Q, K, V, dO, tau, sv, beta, gamma, alibi_slopes, dQ, dK, dV, dbeta,
+                                      dgamma, stats, ws, st, phase_events);
+    return bwd_dispatch<bf16_t, 128>(bias, p, L, Q, K, V, dO, tau, sv, beta, gamma, alibi_slopes, dQ, dK, dV, dbeta,
+                                     dgamma, stats, ws, st, phase_events);
   }
   if (p->D == 64)
-    return run_bwd<float, 64>(p, L, Q, K, V, dO, tau, sv, beta, gamma, dQ, dK, dV, dbeta, dgamma, stats, ws, st,
-                              phase_events);
-  return run_bwd<float, 128>(p, L, Q, K, V, dO, tau, sv, beta, gamma, dQ, dK, dV, dbeta, dgamma, stats, ws, st,
-                             phase_events);
+    return bwd_dispatch<float, 64>(bias, p, L, Q, K, V, dO, tau, sv, beta, gamma, alibi_slopes, dQ, dK, dV, dbeta,
+                                   dgamma, stats, ws, st, phase_events);
+  return bwd_dispatch<float, 128>(bias, p, L, Q, K, V, dO, tau, sv, beta, gamma, alibi_slopes, dQ, dK, dV, dbeta,
+                                  dgamma, stats, ws, st, phase_events);
 }
 
 }  // extern "C"

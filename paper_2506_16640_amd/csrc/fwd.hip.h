@@ -138,9 +138,9 @@ struct FwdTile {
   static constexpr int value = sizeof(T) == 2 ? 128 : 32;
 };
 
-template <typename T, int D, int AM>
+template <typename T, int D, int AM, bool BIAS>
 __device__ __forceinline__ void fwd_block(const FwdArgs& A, int bh_, int blk_, char* smem) {
-  using C = QCtx<T, D, FwdTile<T>::value>;
+  using C = QCtx<T, D, FwdTile<T>::value, BIAS>;
   constexpr int KT = C::KT, NSB = C::NSB, NM = C::NM, TB = C::kTileBytes;
   const Geom& g = A.g;
   char* tiles = smem;  // 2 buffers x 2 slots
@@ -150,6 +150,7 @@ __device__ __forceinline__ void fwd_block(const FwdArgs& A, int bh_, int blk_, c
 
   C q;
   q.init(g, A.Q, bh_, blk_);
+  q.init_window(g);
   const float r = 1.0f / (g.alpha - 1.0f);
   float* tau_out = A.tau + (long long)q.bh * g.Nq;
   const long long o_base = (long long)q.b * g.q_sb + (long long)q.h * g.q_sh;
@@ -183,13 +184,14 @@ __device__ __forceinline__ void fwd_block(const FwdArgs& A, int bh_, int blk_, c
   // ------------------------------------------------------------ 1. row max
   float m = -kInf;
   sweep_tiles<C, T, D, 1, 0>(
-      tiles, slots, q.ntiles, g.Nk, q.tid, [](int) { return true; },
+      tiles, slots, q.ntiles, g.Nk, q.tid, [&](int kt) { return q.tile_in_window(kt); },
       [&](int kt, const char* tl) {
+        if (!q.tile_in_wave_window(kt)) return;
         const uint32_t act = q.visible_bits(kt);
         f32x16_t acc[NSB];
 #pragma unroll
         for (int sb = 0; sb < NSB; ++sb)
-          if (act & (1u << sb)) acc[sb] = q.scores(tl, sb);
+          if (act & (1u << sb)) acc[sb] = q.scores(tl, sb, kt);
 #pragma unroll
         for (int sb = 0; sb < NSB; ++sb) {
           if (!(act & (1u << sb))) continue;
@@ -215,15 +217,15 @@ __device__ __forceinline__ void fwd_block(const FwdArgs& A, int bh_, int blk_, c
     RowSums sums;
     sums.clear();
     const bool first = (iter == 0);
-    auto needed = [&](int kt) { return first || wm.tile_bits<NSB>(kWaves, kt) != 0u; };
+    auto needed = [&](int kt) { return first ? q.tile_in_window(kt) : wm.tile_bits<NSB>(kWaves, kt) != 0u; };
     sweep_tiles<C, T, D, 1, 0>(tiles, slots, q.ntiles, g.Nk, q.tid, needed, [&](int kt, const char* tl) {
-      if (!wave_on) return;
+      if (!wave_on || !q.tile_in_wave_window(kt)) return;
       uint32_t act = q.visible_bits(kt);
       if (!first) act &= wm.tile_bits<NSB>(q.wave, kt);
       f32x16_t acc[NSB];
 #pragma unroll
       for (int sb = 0; sb < NSB; ++sb)
-        if (act & (1u << sb)) acc[sb] = q.scores(tl, sb);
+        if (act & (1u << sb)) acc[sb] = q.scores(tl, sb, kt);
 #pragma unroll
       for (int sb = 0; sb < NSB; ++sb) {
         if (!(act & (1u << sb))) continue;
@@ -273,7 +275,7 @@ __device__ __forceinline__ void fwd_block(const FwdArgs& A, int bh_, int blk_, c
         f32x16_t acc[NSB];
 #pragma unroll
         for (int sb = 0; sb < NSB; ++sb)
-          if (act & (1u << sb)) acc[sb] = q.scores(tl, sb);
+          if (act & (1u << sb)) acc[sb] = q.scores(tl, sb, kt);
 #pragma unroll
         for (int sb = 0; sb < NSB; ++sb) {
           if (!(act & (1u << sb))) continue;
@@ -320,7 +322,9 @@ __device__ __forceinline__ void fwd_block(const FwdArgs& A, int bh_, int blk_, c
   if (q.valid && q.hh == 0) tau_out[q.i] = live ? tau : 0.f;
 
   if (A.stats && q.lane == 0) {
-    atomicAdd(&A.stats[ENTMAX_STAT_FWD_TILES_VISIBLE], (unsigned long long)n_vis);
+    const unsigned n_win = q.window_skipped_blocks();
+    atomicAdd(&A.stats[ENTMAX_STAT_FWD_TILES_VISIBLE], (unsigned long long)(n_vis + n_win));
+    if (BIAS) atomicAdd(&A.stats[ENTMAX_STAT_FWD_WINDOW_SKIPPED], (unsigned long long)n_win);
     atomicAdd(&A.stats[ENTMAX_STAT_FWD_QK_MAX], (unsigned long long)n_vis);
     atomicAdd(&A.stats[ENTMAX_STAT_FWD_QK_SOLVE], (unsigned long long)n_qk_solve);
     atomicAdd(&A.stats[ENTMAX_STAT_FWD_QK_PV], (unsigned long long)n_qk_pv);
@@ -333,7 +337,7 @@ __device__ __forceinline__ void fwd_block(const FwdArgs& A, int bh_, int blk_, c
   }
 }
 
-template <typename T, int D, int AM>
+template <typename T, int D, int AM, bool BIAS>
 __global__ __launch_bounds__(kThreads) void fwd_kernel(FwdArgs A) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const PairItem it = pair_item(A.nqb);
@@ -342,7 +346,7 @@ __global__ __launch_bounds__(kThreads) void fwd_kernel(FwdArgs A) {
     if (blk < 0) break;
     if (A.dense_flag && __builtin_amdgcn_readfirstlane(A.dense_flag[it.bh * A.nqb + blk]) == 0) continue;
     __syncthreads();
-    fwd_block<T, D, AM>(A, it.bh, blk, smem);
+    fwd_block<T, D, AM, BIAS>(A, it.bh, blk, smem);
   }
 }
 

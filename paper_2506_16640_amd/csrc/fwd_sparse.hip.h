@@ -99,17 +99,18 @@ __device__ __forceinline__ bool collect_sweep(const C& q, const Geom& g, const v
                                                 (long long)q.h * g.kv_sh);
   slots[0].row_bytes = g.kv_sn * (long long)sizeof(T);
   sweep_tiles<C, T, D, 1, 0>(
-      tiles, slots, q.ntiles, g.Nk, q.tid, [](int) { return true; },
+      tiles, slots, q.ntiles, g.Nk, q.tid, [&](int kt) { return q.tile_in_window(kt); },
       [&](int kt, const char* tl) {
+        if (!q.tile_in_wave_window(kt)) return;
         const bool interior = (kt + 1) * KT <= q.wave_lim_min;
         const uint32_t act = interior ? ((1u << NSB) - 1u) : q.visible_bits(kt);
         f32x16_t acc[NSB];
         if (interior) {
-          q.scores_all(tl, acc);
+          q.scores_all(tl, acc, kt);
         } else {
 #pragma unroll
           for (int sb = 0; sb < NSB; ++sb)
-            if (act & (1u << sb)) acc[sb] = q.scores(tl, sb);
+            if (act & (1u << sb)) acc[sb] = q.scores(tl, sb, kt);
         }
 #pragma unroll
         for (int sb = 0; sb < NSB; ++sb) {
@@ -217,9 +218,9 @@ __device__ __forceinline__ float two_key_bound(float y1, float y2, float r) {
   return fmaxf(lo, t - 4e-6f * fmaxf(1.0f, fabsf(t)));
 }
 
-template <typename T, int D, int AM>
+template <typename T, int D, int AM, bool BIAS>
 __device__ __forceinline__ void fwd_lists_block(const FwdSparseArgs& A, int bh_, int blk_, char* smem) {
-  using C = QCtx<T, D, FwdTile<T>::value>;
+  using C = QCtx<T, D, FwdTile<T>::value, BIAS>;
   constexpr int KT = C::KT, NSB = C::NSB, TB = C::kTileBytes;
   const Geom& g = A.g;
   char* tiles = smem;  // 2 buffers x 1 slot
@@ -227,6 +228,7 @@ __device__ __forceinline__ void fwd_lists_block(const FwdSparseArgs& A, int bh_,
 
   C q;
   q.init(g, A.Q, bh_, blk_);
+  q.init_window(g);
   const int flag_idx = q.bh * A.nqb + q.qb;
   const long long row_idx = (long long)q.bh * g.Nq + (q.valid ? q.i : 0);
   const bool live = q.valid && q.lim > 0;
@@ -250,11 +252,12 @@ __device__ __forceinline__ void fwd_lists_block(const FwdSparseArgs& A, int bh_,
   // m1 >= m2 are the two largest per-cell maxima seen by this lane: two distinct scores of the row
   float m1 = -kInf, m2 = -kInf;
   sweep_tiles<C, T, D, 1, 0>(
-      tiles, slots, q.ntiles, g.Nk, q.tid, [](int) { return true; },
+      tiles, slots, q.ntiles, g.Nk, q.tid, [&](int kt) { return q.tile_in_window(kt); },
       [&](int kt, const char* tl) {
+        if (!q.tile_in_wave_window(kt)) return;
         if ((kt + 1) * KT <= q.wave_lim_min) {
           f32x16_t acc[NSB];
-          q.scores_all(tl, acc);
+          q.scores_all(tl, acc, kt);
 #pragma unroll
           for (int sb = 0; sb < NSB; ++sb) {
             float lm = max16(acc[sb]);
@@ -269,7 +272,7 @@ __device__ __forceinline__ void fwd_lists_block(const FwdSparseArgs& A, int bh_,
         for (int sb = 0; sb < NSB; ++sb) {
           if (!(act & (1u << sb))) continue;
           int j0 = kt * KT + sb * 32;
-          f32x16_t acc = q.scores(tl, sb);
+          f32x16_t acc = q.scores(tl, sb, kt);
           ++n_vis;
           if (j0 + 32 > q.wave_lim_min) {
             int rel = q.lim - j0;
@@ -308,7 +311,9 @@ __device__ __forceinline__ void fwd_lists_block(const FwdSparseArgs& A, int bh_,
     }
   }
   if (A.stats && q.lane == 0) {
-    atomicAdd(&A.stats[ENTMAX_STAT_FWD_TILES_VISIBLE], (unsigned long long)n_vis);
+    const unsigned n_win = q.window_skipped_blocks();
+    atomicAdd(&A.stats[ENTMAX_STAT_FWD_TILES_VISIBLE], (unsigned long long)(n_vis + n_win));
+    if (BIAS) atomicAdd(&A.stats[ENTMAX_STAT_FWD_WINDOW_SKIPPED], (unsigned long long)n_win);
     atomicAdd(&A.stats[ENTMAX_STAT_FWD_LIST_QK], (unsigned long long)(n_vis + n_qk2));
     if (fits) {
       atomicAdd(&A.stats[ENTMAX_STAT_FWD_CAND_TILES], (unsigned long long)n_cand_tiles);
@@ -317,7 +322,7 @@ __device__ __forceinline__ void fwd_lists_block(const FwdSparseArgs& A, int bh_,
   }
 }
 
-template <typename T, int D, int AM>
+template <typename T, int D, int AM, bool BIAS>
 __global__ __launch_bounds__(kThreads, 3) void fwd_lists_kernel(FwdSparseArgs A) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const PairItem it = pair_item(A.nqb);
@@ -325,7 +330,7 @@ __global__ __launch_bounds__(kThreads, 3) void fwd_lists_kernel(FwdSparseArgs A)
     const int blk = part ? it.second : it.first;
     if (blk < 0) break;
     if (part) __syncthreads();
-    fwd_lists_block<T, D, AM>(A, it.bh, blk, smem);
+    fwd_lists_block<T, D, AM, BIAS>(A, it.bh, blk, smem);
   }
 }
 

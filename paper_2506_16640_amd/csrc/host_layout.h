@@ -24,7 +24,7 @@ struct Layout {
   long long q_sb, q_sh, q_sn, kv_sb, kv_sh, kv_sn;
   // workspace offsets
   size_t off_vt, off_cand, off_flcnt, off_bounds, off_flags, off_fcells, off_kt, off_qt, off_dot, off_mu, off_crow, off_dscale, off_mask, off_jlist, off_lcnt,
-      off_kcount, off_koffs, off_kcursor, off_csc_i, off_csc_pw, off_hflag, off_longkeys, off_bcells, sv_list, sv_lcnt,
+      off_kcount, off_koffs, off_kcursor, off_csc_i, off_csc_pw, off_hflag, off_longkeys, off_bcells, off_fknorm, off_bknorm, sv_list, sv_lcnt,
       sv_flags, total_saved, total_fwd, total_bwd;
   size_t off_dec_cmax;  // decode kernels: score rows at offset 0, then the chunk maxima
   int dec_nks, dec_nchunks, dec_chunk;
@@ -38,6 +38,7 @@ inline int check_params(const entmax_attn_params* p) {
   if (p->causal != 0 && p->causal != 1) return ENTMAX_ATTN_INVALID_ARG;
   if (p->scale_layout < 0 || p->scale_layout > 2) return ENTMAX_ATTN_INVALID_ARG;
   if (p->logn_mode != 0 && p->logn_mode != 1) return ENTMAX_ATTN_INVALID_ARG;
+  if (p->bias_mode != 0 && p->bias_mode != 1) return ENTMAX_ATTN_INVALID_ARG;
   if (p->path != 0 && p->path != 1) return ENTMAX_ATTN_INVALID_ARG;
   if (!(p->alpha > 1.0f) || !(p->alpha <= 2.0f)) return ENTMAX_ATTN_INVALID_ARG;
   if (!isfinite(p->delta)) return ENTMAX_ATTN_INVALID_ARG;
@@ -92,7 +93,8 @@ inline Layout make_layout(const entmax_attn_params* p) {
   L.off_bounds = L.off_flcnt + align_up(bh * (size_t)p->Nq * 2 * sizeof(int));
   L.off_flags = L.off_bounds + align_up(bh * (size_t)p->Nq * 2 * sizeof(float));
   L.off_fcells = L.off_flags + align_up(bh * (size_t)L.nqb * sizeof(int));
-  L.total_fwd = L.off_fcells + align_up(list_groups * cell_bytes_per_workgroup(kCandCap));
+  L.off_fknorm = L.off_fcells + align_up(list_groups * cell_bytes_per_workgroup(kCandCap));
+  L.total_fwd = L.off_fknorm + align_up(bh * sizeof(float));  // the heads' largest key norms (distance bias only)
   // the `saved` buffer: the rows' support lists (kBwdCap slots per lane of every 128-row block, slot-major per
   // 32-row group), their lengths, and one flag per block for the backward
   const size_t list_bytes = align_up(bh * (size_t)L.nqb * kThreads * kBwdCap * 8);
@@ -151,6 +153,8 @@ inline Layout make_layout(const entmax_attn_params* p) {
   o += key_bytes;
   L.off_bcells = o;
   o += align_up(list_groups * cell_bytes_per_workgroup(kBwdCap));
+  L.off_bknorm = o;
+  o += align_up(bh * sizeof(float));
   L.total_bwd = o;
   return L;
 }

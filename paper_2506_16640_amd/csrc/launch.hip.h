@@ -12,18 +12,22 @@
 namespace entmax {
 
 // Enqueues the forward / backward for validated parameters; returns an entmax_attn_status.
-template <typename T, int D>
+// BIAS: the kernels built for the linear distance bias (slopes must then be given); the entry points choose
+// by whether the caller passed slopes, so calls without them run exactly the kernels without the bias code.
+template <typename T, int D, bool BIAS>
 int run_fwd(const entmax_attn_params* p, const Layout& L, const void* Q, const void* K, const void* V,
-            const float* beta, const float* gamma, void* O, float* tau, char* saved, uint64_t* stats, char* ws,
-            hipStream_t st, void* const* ev);
-template <typename T, int D>
+            const float* beta, const float* gamma, const float* slopes, void* O, float* tau, char* saved,
+            uint64_t* stats, char* ws, hipStream_t st, void* const* ev);
+template <typename T, int D, bool BIAS>
 int run_bwd(const entmax_attn_params* p, const Layout& L, const void* Q, const void* K, const void* V, const void* dO,
-            const float* tau, const char* saved, const float* beta, const float* gamma, void* dQ, void* dK, void* dV,
-            float* dbeta, float* dgamma, uint64_t* stats, char* ws, hipStream_t st, void* const* ev);
+            const float* tau, const char* saved, const float* beta, const float* gamma, const float* slopes, void* dQ,
+            void* dK, void* dV, float* dbeta, float* dgamma, uint64_t* stats, char* ws, hipStream_t st,
+            void* const* ev);
 
 namespace {
 
-Geom make_geom(const entmax_attn_params* p, const Layout& L, const float* beta, const float* gamma) {
+Geom make_geom(const entmax_attn_params* p, const Layout& L, const float* beta, const float* gamma,
+               const float* slopes, const float* knorm) {
   Geom g;
   g.B = p->B;
   g.H = p->H;
@@ -44,6 +48,9 @@ Geom make_geom(const entmax_attn_params* p, const Layout& L, const float* beta, 
   g.npad_q = L.npad_q;
   g.beta = beta;
   g.gamma = gamma;
+  g.slopes = slopes;
+  g.bias_mode = p->bias_mode;
+  g.knorm = knorm;
   return g;
 }
 

@@ -15,8 +15,12 @@
 
 namespace entmax {
 
-template <typename T, int D, int KT_ = Elem<T>::kTile>
+// BIAS: the kernel was built for the linear distance bias (Sec. 4.2; App. B, ALiBi definition): the score
+// blocks start from w_i dist_ij instead of zero (the matrix instruction adds its products to it), and the
+// key tiles beyond every row's window (App. B, ALiBi proposition) are not visited.
+template <typename T, int D, int KT_ = Elem<T>::kTile, bool BIAS_ = false>
 struct QCtx {
+  static constexpr bool BIAS = BIAS_;
   static constexpr int KT = KT_;             // keys per LDS tile
   static constexpr int NSB = KT / 32;        // 32-key MFMA blocks per tile
   static constexpr int NC = D / 16;          // 16-wide k chunks of a Q.K product
@@ -39,6 +43,13 @@ struct QCtx {
   float c;            // scale_i / sqrt(D), signed
   Frag<T> qf[NC];     // the row's query fragments (negated when scale_i < 0 so that a >= 0)
   FragOff<T> koff[NC];  // lane offsets of the K-tile fragments of row (l%32)
+  // BIAS only
+  float w;            // d'_ij = d_ij + w dist_ij (see bias_w()); 0: this row has no bias
+  int pos;            // the row's position in the key sequence, i + (Nk - Nq): dist_ij = max(pos - j, 0)
+  int wave_pos_min;   // smallest pos of the wave
+  bool wave_bias;     // some row of the wave has w != 0
+  int kt_first;       // first key tile some row of the workgroup / of the wave can have a non-zero probability in
+  int kt_first_wave;
 
   __device__ __forceinline__ void init(const Geom& g, const void* Q, int bh_, int qb_) {
     tid = threadIdx.x;
@@ -73,12 +84,88 @@ struct QCtx {
       qf[cc] = (c < 0.f) ? Elem<T>::negate(f) : f;
       koff[cc] = FragOff<T>::template make<KTile>(li, 2 * cc + hh);
     }
+    if constexpr (BIAS) {
+      w = valid ? bias_w<D>(g, h, c, a) : 0.f;
+      pos = i + (g.Nk - g.Nq);
+      wave_pos_min = uni(q0 + (g.Nk - g.Nq));
+      wave_bias = __ballot(w != 0.f) != 0ull;
+      kt_first = kt_first_wave = 0;
+    }
+  }
+
+  // Window of the distance bias (App. B, ALiBi proposition, with the proposition's logit range taken per row
+  // from |d_ij| <= |q_i| max_j |k_j|): y_ij <= a (|q||k|max + w dist) for a penalising bias (w < 0), and the
+  // threshold is at least y_max - 1 >= -a |q||k|max - 1 (the key at distance 0 is visible to every live row).
+  // So a key with dist >= (2 |q||k|max + 1/a) / |w| has probability exactly zero and cannot be the row maximum.
+  // Sets kt_first / kt_first_wave: the key tiles before them are skipped by every sweep.
+  // All threads of the workgroup call this together (two barriers).
+  __device__ __forceinline__ void init_window(const Geom& g) {
+    if constexpr (BIAS) {
+      __shared__ int wg_first;
+      float s2 = 0.f;
+#pragma unroll
+      for (int cc = 0; cc < NC; ++cc) s2 += Elem<T>::sumsq(qf[cc]);
+      s2 += __shfl_xor(s2, 32);
+      int first = 0x7fffffff;  // rows beyond Nq, rows without visible keys: no constraint
+      if (valid && lim > 0) {
+        first = 0;
+        if (w < 0.f && a > 0.f) {
+          const float reach = (2.0002f * sqrtf(s2) * g.knorm[bh] + 1.0f / a) / (-w);
+          if (reach < 1.0e9f) first = max(0, pos - (int)reach - 2);
+        }
+      }
+#pragma unroll
+      for (int sft = 32; sft >= 1; sft >>= 1) first = min(first, __shfl_xor(first, sft));
+      __syncthreads();
+      if (tid == 0) wg_first = 0x7fffffff;
+      __syncthreads();
+      if (lane == 0) atomicMin(&wg_first, first);
+      __syncthreads();
+      kt_first_wave = __builtin_amdgcn_readfirstlane(min(first / KT, ntiles));
+      kt_first = __builtin_amdgcn_readfirstlane(min(wg_first / KT, ntiles));
+    }
+  }
+  // blocks (32 x 32) of this wave that are visible but lie before its first visited tile
+  __device__ __forceinline__ unsigned window_skipped_blocks() const {
+    if constexpr (BIAS) return (unsigned)min(kt_first_wave * NSB, (wave_lim_max + 31) >> 5);
+    return 0u;
+  }
+  // the sweeps' tile predicates: workgroup-uniform and wave-uniform
+  __device__ __forceinline__ bool tile_in_window(int kt) const {
+    if constexpr (BIAS) return kt >= kt_first;
+    return true;
+  }
+  __device__ __forceinline__ bool tile_in_wave_window(int kt) const {
+    if constexpr (BIAS) return kt >= kt_first_wave;
+    return true;
+  }
+
+  // accumulator start of the 32-key block at key j0: zero, or w dist for the lane's 16 (row, key) pairs
+  __device__ __forceinline__ f32x16_t block_start(int j0) const {
+    f32x16_t acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if constexpr (BIAS) {
+      if (wave_bias) bias_block(acc, j0);
+    }
+    return acc;
+  }
+  __device__ __forceinline__ void bias_block(f32x16_t& acc, int j0) const {
+    const int rel = pos - j0;
+    if (j0 + 31 <= wave_pos_min) {
+      // every key of the block is at or before every row's position: dist = rel - key_of(e) > = 0
+      const float base = w * (float)(rel - 4 * hh);
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[e] = fmaf(-w, (float)(8 * (e >> 2) + (e & 3)), base);
+    } else {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[e] = w * (float)max(rel - key_of(e), 0);
+    }
   }
 
   // S^T block: rows = 32 keys of sub-block sb of the K tile, cols = the wave's 32 queries.
   // acc[4g + r] of lane l is the raw dot product with key 8g + 4*(l/32) + r of the block.
-  __device__ __forceinline__ f32x16_t scores(const char* ktile, int sb) const {
-    f32x16_t acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  // kt: index of the tile in the key sequence (the distance bias needs the keys' positions)
+  __device__ __forceinline__ f32x16_t scores(const char* ktile, int sb, int kt) const {
+    f32x16_t acc = block_start(kt * KT + sb * 32);
 #pragma unroll
     for (int cc = 0; cc < NC; ++cc) acc = Elem<T>::mma(koff[cc].load(ktile, sb * 32 * KTile::kRowBytes), qf[cc], acc);
     return acc;
@@ -86,10 +173,10 @@ struct QCtx {
 
   // All NSB blocks of a tile.  The K fragments of block sb+1 are requested before the products of
   // block sb are issued, so that LDS latency overlaps the matrix pipeline inside one wave.
-  __device__ __forceinline__ void scores_all(const char* ktile, f32x16_t (&acc)[NSB]) const {
+  __device__ __forceinline__ void scores_all(const char* ktile, f32x16_t (&acc)[NSB], int kt) const {
     if constexpr (NC > 4) {  // two fragment sets would not fit the register budget
 #pragma unroll
-      for (int sb = 0; sb < NSB; ++sb) acc[sb] = scores(ktile, sb);
+      for (int sb = 0; sb < NSB; ++sb) acc[sb] = scores(ktile, sb, kt);
       return;
     }
     Frag<T> kf[2][NC];
@@ -101,7 +188,7 @@ struct QCtx {
 #pragma unroll
         for (int cc = 0; cc < NC; ++cc) kf[(sb + 1) & 1][cc] = koff[cc].load(ktile, (sb + 1) * 32 * KTile::kRowBytes);
       }
-      f32x16_t a0 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      f32x16_t a0 = block_start(kt * KT + sb * 32);
 #pragma unroll
       for (int cc = 0; cc < NC; ++cc) a0 = Elem<T>::mma(kf[sb & 1][cc], qf[cc], a0);
       acc[sb] = a0;

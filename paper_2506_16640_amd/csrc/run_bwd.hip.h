@@ -2,18 +2,19 @@
 #pragma once
 #include "bwd.hip.h"
 #include "bwd_sparse.hip.h"
+#include "key_norm.hip.h"
 #include "launch.hip.h"
 
 namespace entmax {
 namespace {
 
-template <typename T, int D, int AM>
+template <typename T, int D, int AM, bool BIAS>
 bool launch_bwd_kernels(const BwdArgs& a, const Layout& L, int B, int H, hipStream_t st, void* const* ev) {
   size_t smem_mask = 2 * (size_t)QCtx<T, D, MaskTile<T>::value>::kTileBytes + (size_t)(kWaves + 1) * a.mask_words * 4 + 64;
   size_t smem_dq = 6 * (size_t)QCtx<T, D>::kTileBytes + (size_t)(kWaves + 1) * a.mask_words * 4 + kWaves * 64 * 4 + 64;
   size_t smem_dkv = 8 * (size_t)QCtx<T, D>::kTileBytes + 2 * 4 * (size_t)QCtx<T, D>::KT * 4 + (size_t)a.nqg + 64;
-  constexpr auto k_mask = bwd_mask_kernel<T, D, AM>;
-  constexpr auto k_dq = bwd_dq_kernel<T, D, AM>;
+  constexpr auto k_mask = bwd_mask_kernel<T, D, AM, BIAS>;
+  constexpr auto k_dq = bwd_dq_kernel<T, D, AM, BIAS>;
   constexpr auto k_dkv = bwd_dkv_kernel<T, D, AM>;
   if (!ensure_dynamic_lds<k_mask>(smem_mask) || !ensure_dynamic_lds<k_dq>(smem_dq) || !ensure_dynamic_lds<k_dkv>(smem_dkv))
     return false;
@@ -29,13 +30,13 @@ bool launch_bwd_kernels(const BwdArgs& a, const Layout& L, int B, int H, hipStre
   return true;
 }
 
-template <typename T, int D, int AM>
+template <typename T, int D, int AM, bool BIAS>
 bool launch_bwd_rows(const BwdSparseArgs& a, int nblocks, hipStream_t st, void* const* ev, bool from_saved) {
   const dim3 row_grid((unsigned)(a.g.B * a.g.H * a.nqb));
   if (!from_saved) {
     // no lists from the forward: one Q K^T sweep at tau rebuilds the supports
     size_t smem = 2 * (size_t)QCtx<T, D, FwdTile<T>::value>::kTileBytes + 64;
-    hipLaunchKernelGGL((bwd_lists_kernel<T, D, AM>), dim3((unsigned)nblocks), dim3(kThreads), smem, st, a);
+    hipLaunchKernelGGL((bwd_lists_kernel<T, D, AM, BIAS>), dim3((unsigned)nblocks), dim3(kThreads), smem, st, a);
     if (!launch_ok()) return false;
   }
   record(ev, ENTMAX_BWD_PHASE_LISTS + 1, st);
@@ -53,25 +54,27 @@ bool launch_bwd_rows(const BwdSparseArgs& a, int nblocks, hipStream_t st, void* 
   return launch_ok();
 }
 
-template <typename T, int D>
+template <typename T, int D, bool BIAS>
 bool launch_bwd_rows_am(const BwdSparseArgs& a, int am, int nblocks, hipStream_t st, void* const* ev, bool from_saved) {
   switch (am) {
-    case 1: return launch_bwd_rows<T, D, 1>(a, nblocks, st, ev, from_saved);
-    case 2: return launch_bwd_rows<T, D, 2>(a, nblocks, st, ev, from_saved);
-    case 3: return launch_bwd_rows<T, D, 3>(a, nblocks, st, ev, from_saved);
-    default: return launch_bwd_rows<T, D, 0>(a, nblocks, st, ev, from_saved);
+    case 1: return launch_bwd_rows<T, D, 1, BIAS>(a, nblocks, st, ev, from_saved);
+    case 2: return launch_bwd_rows<T, D, 2, BIAS>(a, nblocks, st, ev, from_saved);
+    case 3: return launch_bwd_rows<T, D, 3, BIAS>(a, nblocks, st, ev, from_saved);
+    default: return launch_bwd_rows<T, D, 0, BIAS>(a, nblocks, st, ev, from_saved);
   }
 }
 
 }  // namespace
 
-template <typename T, int D>
+template <typename T, int D, bool BIAS>
 int run_bwd(const entmax_attn_params* p, const Layout& L, const void* Q, const void* K, const void* V, const void* dO,
-            const float* tau, const char* saved, const float* beta, const float* gamma, void* dQ, void* dK, void* dV,
-            float* dbeta, float* dgamma, uint64_t* stats, char* ws, hipStream_t st, void* const* ev) {
+            const float* tau, const char* saved, const float* beta, const float* gamma, const float* slopes, void* dQ,
+            void* dK, void* dV, float* dbeta, float* dgamma, uint64_t* stats, char* ws, hipStream_t st,
+            void* const* ev) {
   record(ev, 0, st);
   const int B = p->B, H = p->H;
-  Geom g = make_geom(p, L, beta, gamma);
+  float* knorm = BIAS ? reinterpret_cast<float*>(ws + L.off_bknorm) : nullptr;
+  Geom g = make_geom(p, L, beta, gamma, slopes, knorm);
   float* dscale = reinterpret_cast<float*>(ws + L.off_dscale);
   bool ok = true;
   if (p->Nk == 0 || p->Nq == 0) {
@@ -82,6 +85,7 @@ int run_bwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
     for (int k = 1; k <= ENTMAX_BWD_PHASE_KEYS + 1; ++k) record(ev, k, st);
   } else {
     const bool lists = p->path == 0;
+    if (BIAS && !launch_key_norms<T, D>(p, L, K, knorm, st)) return ENTMAX_ATTN_LAUNCH_FAILED;
     int* block_flag = reinterpret_cast<int*>(ws + L.off_hflag);
     int* head_flag = block_flag + (size_t)B * H * L.nqb;
     BwdSparseArgs sa;
@@ -114,7 +118,7 @@ int run_bwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
       sa.dbeta = dbeta;
       sa.dgamma = dgamma;
       sa.scale_heads = p->scale_layout == 1 ? H : 0;
-      ok = ok && launch_bwd_rows_am<T, D>(sa, alpha_mode(p->alpha), B * H * ((L.nqb + 1) / 2), st, ev, saved != nullptr);
+      ok = ok && launch_bwd_rows_am<T, D, BIAS>(sa, alpha_mode(p->alpha), B * H * ((L.nqb + 1) / 2), st, ev, saved != nullptr);
       if (!ok) return ENTMAX_ATTN_LAUNCH_FAILED;
     } else {
       record(ev, ENTMAX_BWD_PHASE_LISTS + 1, st);
@@ -157,10 +161,10 @@ int run_bwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
     a.nqg = L.nqg;
     a.mask_words = L.mask_words;
     switch (alpha_mode(p->alpha)) {
-      case 1: ok = launch_bwd_kernels<T, D, 1>(a, L, B, H, st, ev); break;
-      case 2: ok = launch_bwd_kernels<T, D, 2>(a, L, B, H, st, ev); break;
-      case 3: ok = launch_bwd_kernels<T, D, 3>(a, L, B, H, st, ev); break;
-      default: ok = launch_bwd_kernels<T, D, 0>(a, L, B, H, st, ev); break;
+      case 1: ok = launch_bwd_kernels<T, D, 1, BIAS>(a, L, B, H, st, ev); break;
+      case 2: ok = launch_bwd_kernels<T, D, 2, BIAS>(a, L, B, H, st, ev); break;
+      case 3: ok = launch_bwd_kernels<T, D, 3, BIAS>(a, L, B, H, st, ev); break;
+      default: ok = launch_bwd_kernels<T, D, 0, BIAS>(a, L, B, H, st, ev); break;
     }
     if (!ok) return ENTMAX_ATTN_LAUNCH_FAILED;
     if (lists) {

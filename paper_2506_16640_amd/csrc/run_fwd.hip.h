@@ -4,47 +4,48 @@
 #include "decode.hip.h"
 #include "fwd.hip.h"
 #include "fwd_sparse.hip.h"
+#include "key_norm.hip.h"
 #include "launch.hip.h"
 
 namespace entmax {
 namespace {
 
-template <typename T, int D, int AM>
+template <typename T, int D, int AM, bool BIAS>
 bool launch_fwd_main(const FwdArgs& a, int nblocks, hipStream_t st) {
   size_t smem = 4 * (size_t)QCtx<T, D, FwdTile<T>::value>::kTileBytes + (size_t)(kWaves + 1) * a.mask_words * 4 + 64;
-  constexpr auto kern = fwd_kernel<T, D, AM>;
+  constexpr auto kern = fwd_kernel<T, D, AM, BIAS>;
   if (!ensure_dynamic_lds<kern>(smem)) return false;
   hipLaunchKernelGGL(kern, dim3((unsigned)nblocks), dim3(kThreads), smem, st, a);
   return launch_ok();
 }
 
-template <typename T, int D>
+template <typename T, int D, bool BIAS>
 bool launch_fwd_am(const FwdArgs& a, int am, int nblocks, hipStream_t st) {
   switch (am) {
-    case 1: return launch_fwd_main<T, D, 1>(a, nblocks, st);
-    case 2: return launch_fwd_main<T, D, 2>(a, nblocks, st);
-    case 3: return launch_fwd_main<T, D, 3>(a, nblocks, st);
-    default: return launch_fwd_main<T, D, 0>(a, nblocks, st);
+    case 1: return launch_fwd_main<T, D, 1, BIAS>(a, nblocks, st);
+    case 2: return launch_fwd_main<T, D, 2, BIAS>(a, nblocks, st);
+    case 3: return launch_fwd_main<T, D, 3, BIAS>(a, nblocks, st);
+    default: return launch_fwd_main<T, D, 0, BIAS>(a, nblocks, st);
   }
 }
 
-template <typename T, int D, int AM>
+template <typename T, int D, int AM, bool BIAS>
 bool launch_fwd_sparse(const FwdSparseArgs& a, int nblocks, hipStream_t st, void* const* ev) {
   size_t smem = 2 * (size_t)QCtx<T, D, FwdTile<T>::value>::kTileBytes + 64;
-  hipLaunchKernelGGL((fwd_lists_kernel<T, D, AM>), dim3((unsigned)nblocks), dim3(kThreads), smem, st, a);
+  hipLaunchKernelGGL((fwd_lists_kernel<T, D, AM, BIAS>), dim3((unsigned)nblocks), dim3(kThreads), smem, st, a);
   if (!launch_ok()) return false;
   record(ev, ENTMAX_FWD_PHASE_LISTS + 1, st);
   hipLaunchKernelGGL((fwd_finish_kernel<T, D, AM>), dim3((unsigned)(a.g.B * a.g.H * a.nqb)), dim3(kThreads), 0, st, a);
   return launch_ok();
 }
 
-template <typename T, int D>
+template <typename T, int D, bool BIAS>
 bool launch_fwd_sparse_am(const FwdSparseArgs& a, int am, int nblocks, hipStream_t st, void* const* ev) {
   switch (am) {
-    case 1: return launch_fwd_sparse<T, D, 1>(a, nblocks, st, ev);
-    case 2: return launch_fwd_sparse<T, D, 2>(a, nblocks, st, ev);
-    case 3: return launch_fwd_sparse<T, D, 3>(a, nblocks, st, ev);
-    default: return launch_fwd_sparse<T, D, 0>(a, nblocks, st, ev);
+    case 1: return launch_fwd_sparse<T, D, 1, BIAS>(a, nblocks, st, ev);
+    case 2: return launch_fwd_sparse<T, D, 2, BIAS>(a, nblocks, st, ev);
+    case 3: return launch_fwd_sparse<T, D, 3, BIAS>(a, nblocks, st, ev);
+    default: return launch_fwd_sparse<T, D, 0, BIAS>(a, nblocks, st, ev);
   }
 }
 
@@ -67,11 +68,12 @@ bool launch_decode(const DecodeArgs& a, int am, hipStream_t st, void* const* ev)
 
 }  // namespace
 
-template <typename T, int D>
+template <typename T, int D, bool BIAS>
 int run_fwd(const entmax_attn_params* p, const Layout& L, const void* Q, const void* K, const void* V,
-            const float* beta, const float* gamma, void* O, float* tau, char* saved, uint64_t* stats, char* ws,
-            hipStream_t st, void* const* ev) {
+            const float* beta, const float* gamma, const float* slopes, void* O, float* tau, char* saved,
+            uint64_t* stats, char* ws, hipStream_t st, void* const* ev) {
   record(ev, 0, st);
+  float* knorm = BIAS ? reinterpret_cast<float*>(ws + L.off_fknorm) : nullptr;
   if (p->Nk == 0) {
     bool ok = zero_rows<T>(O, L.q_sb, L.q_sh, L.q_sn, p->B, p->H, p->Nq, p->D, st) &&
               zero_words(tau, (size_t)p->B * p->H * p->Nq * 4, st);
@@ -86,7 +88,7 @@ int run_fwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
         return ENTMAX_ATTN_LAUNCH_FAILED;
       record(ev, ENTMAX_FWD_PHASE_PREPARE + 1, st);
       DecodeArgs da;
-      da.g = make_geom(p, L, beta, gamma);
+      da.g = make_geom(p, L, beta, gamma, slopes, nullptr);
       da.Q = Q;
       da.K = K;
       da.V = V;
@@ -109,10 +111,11 @@ int run_fwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
   int* dense_flag = reinterpret_cast<int*>(ws + L.off_flags);  // [B*H*nqb] blocks left to the tiled kernel
   const int npairs = p->B * p->H * ((L.nqb + 1) / 2);  // workgroups that take query blocks in pairs
   const bool lists = p->path == 0;
+  if (BIAS && !launch_key_norms<T, D>(p, L, K, knorm, st)) return ENTMAX_ATTN_LAUNCH_FAILED;
   record(ev, ENTMAX_FWD_PHASE_PREPARE + 1, st);
   if (lists) {
     FwdSparseArgs sa;
-    sa.g = make_geom(p, L, beta, gamma);
+    sa.g = make_geom(p, L, beta, gamma, slopes, knorm);
     sa.Q = Q;
     sa.K = K;
     sa.V = V;
@@ -129,7 +132,7 @@ int run_fwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
     sa.dense_flag = dense_flag;
     sa.stats = reinterpret_cast<unsigned long long*>(stats);
     sa.nqb = L.nqb;
-    if (!launch_fwd_sparse_am<T, D>(sa, alpha_mode(p->alpha), npairs, st, ev)) return ENTMAX_ATTN_LAUNCH_FAILED;
+    if (!launch_fwd_sparse_am<T, D, BIAS>(sa, alpha_mode(p->alpha), npairs, st, ev)) return ENTMAX_ATTN_LAUNCH_FAILED;
   } else {
     // no lists: tell the backward that every block belongs to its tiled kernels
     if (saved && !fill_words(saved + L.sv_flags, (size_t)p->B * p->H * L.nqb * sizeof(int), 1u, st))
@@ -145,7 +148,7 @@ int run_fwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
   }
   record(ev, ENTMAX_FWD_PHASE_TRANSPOSE + 1, st);
   FwdArgs a;
-  a.g = make_geom(p, L, beta, gamma);
+  a.g = make_geom(p, L, beta, gamma, slopes, knorm);
   a.Q = Q;
   a.K = K;
   a.Vt = Vt;
@@ -155,7 +158,7 @@ int run_fwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
   a.nqb = L.nqb;
   a.mask_words = L.mask_words;
   a.dense_flag = lists ? dense_flag : nullptr;
-  if (!launch_fwd_am<T, D>(a, alpha_mode(p->alpha), npairs, st)) return ENTMAX_ATTN_LAUNCH_FAILED;
+  if (!launch_fwd_am<T, D, BIAS>(a, alpha_mode(p->alpha), npairs, st)) return ENTMAX_ATTN_LAUNCH_FAILED;
   record(ev, ENTMAX_FWD_PHASE_TILED + 1, st);
   return ENTMAX_ATTN_OK;
 }

@@ -112,6 +112,16 @@ def make_config(name, seed=0, **overrides):
     return data
 
 
+def nape_slopes(H, first_biased=True):
+    """Slopes of the distance bias for the NAPE arrangement of Sec. 4.2: every other head biased, the rest zero.
+    The biased heads take m = 2^(-k/K), k = 1..K (App. B, ALiBi definition, over the K biased heads)."""
+    m = np.zeros(H, dtype=np.float32)
+    idx = np.arange(0 if first_biased else 1, H, 2)
+    for k, h in enumerate(idx):
+        m[h] = 2.0 ** (-(k + 1) / len(idx))
+    return m
+
+
 def dense_equiv_flops(B, H, n, d, causal=True, bwd=False):
     """Usual attention convention: forward 4 B H n^2 d (half under a causal mask), backward 2.5x."""
     f = 4.0 * B * H * n * n * d * (0.5 if causal else 1.0)

@@ -18,7 +18,7 @@ def to_dev(x, dtype):
 
 
 def gpu_run(data, alpha, dtype, causal=True, logn_mode=0, bwd=True, stats=False, layout_bnhd=False, path=None,
-            use_saved=None):
+            use_saved=None, slopes=None, bias_mode=0):
     from paper_2506_16640_amd import binding
     path = DEFAULT_PATH if path is None else path
     use_saved = DEFAULT_SAVED if use_saved is None else use_saved
@@ -29,7 +29,8 @@ def gpu_run(data, alpha, dtype, causal=True, logn_mode=0, bwd=True, stats=False,
     gamma = None if data["gamma"] is None else torch.from_numpy(data["gamma"]).float().cuda()
     st = binding.new_stats() if stats else None
     kw = dict(alpha=alpha, beta=beta, gamma=gamma, delta=data["delta"], causal=causal, logn_mode=logn_mode, stats=st,
-              path=path)
+              path=path, alibi_slopes=None if slopes is None else torch.from_numpy(slopes).float().cuda(),
+              bias_mode=bias_mode)
     saved = None
     if use_saved:  # the forward's lists go to the backward, which then skips its own sweep
         prm = binding.make_params(q, k, alpha, data["delta"], causal, beta, logn_mode, path)
@@ -51,9 +52,10 @@ def gpu_run(data, alpha, dtype, causal=True, logn_mode=0, bwd=True, stats=False,
     return out
 
 
-def oracle_run(data, alpha, causal=True, logn_mode=0, bwd=True):
+def oracle_run(data, alpha, causal=True, logn_mode=0, bwd=True, slopes=None, bias_mode=0):
     from oracle import oracle
-    kw = dict(beta=data["beta"], gamma=data["gamma"], delta=data["delta"], causal=causal, logn_mode=logn_mode)
+    kw = dict(beta=data["beta"], gamma=data["gamma"], delta=data["delta"], causal=causal, logn_mode=logn_mode,
+              slopes=slopes, bias_mode=bias_mode)
     out = oracle.attn_fwd(data["Q"], data["K"], data["V"], alpha, **kw)
     if bwd:
         out.update(oracle.attn_bwd(data["Q"], data["K"], data["V"], data["dO"], alpha, **kw))

@@ -91,9 +91,9 @@ def test_entry_points_reject_bad_arguments_before_any_launch(binding):
     fake = ctypes.c_void_p(4096)
     bad = ctypes.c_void_p(4100)  # not 16-byte aligned
     def args(**kw):
-        a = [kw.get(k, null if k == "saved" else fake)
-             for k in ("Q", "K", "V", "beta", "gamma", "O", "tau", "saved", "stats", "ws")]
-        a.insert(8, ctypes.c_size_t(kw.get("saved_bytes", 0)))  # saved_bytes follows saved
+        a = [kw.get(k, null if k in ("saved", "slopes") else fake)
+             for k in ("Q", "K", "V", "beta", "gamma", "slopes", "O", "tau", "saved", "stats", "ws")]
+        a.insert(9, ctypes.c_size_t(kw.get("saved_bytes", 0)))  # saved_bytes follows saved
         return a
 
     call = lambda prm, a, wsb=1 << 30: lib.entmax_attn_fwd(ctypes.byref(prm), *a, ctypes.c_size_t(wsb), null, null)  # noqa
@@ -103,14 +103,17 @@ def test_entry_points_reject_bad_arguments_before_any_launch(binding):
     assert call(p, args(K=bad)) == -3
     assert call(p, args(stats=null), wsb=16) == -4
     assert call(p, args(saved=bad)) == -3
+    assert call(p, args(slopes=ctypes.c_void_p(4098))) == -3
+    assert call(_params(b, bias_mode=2), args()) == -1
     # a saved buffer smaller than the parameters need is refused like a small workspace
     need = b.saved_bytes(p)
     assert call(p, args(saved=fake, saved_bytes=need - 1)) == -4
     assert call(p, args(saved=fake, saved_bytes=0)) == -4
     lib.entmax_attn_bwd.restype = ctypes.c_int
-    a = [fake] * 17
+    a = [fake] * 18
     a[6] = null  # saved is optional
     a[7] = ctypes.c_size_t(0)
+    a[10] = null  # so are the slopes of the distance bias
     assert lib.entmax_attn_bwd(ctypes.byref(_params(b, alpha=3.0)), *a, ctypes.c_size_t(1 << 30), null, null) == -1
     a[5] = null  # tau
     assert lib.entmax_attn_bwd(ctypes.byref(p), *a, ctypes.c_size_t(1 << 30), null, null) == -1
