@@ -98,6 +98,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="c3")
     ap.add_argument("--alpha", type=float, default=None, help="entmax alpha instead of the workload's own (1.5)")
+    ap.add_argument("--nape", action="store_true", help="every other head with the linear distance bias (Sec. 4.2)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the other benchmark configurations (c2, c4, c5, c3d)")
     ap.add_argument("--no-decode", action="store_true", help="skip the decode-shape (Nq = 1 and 8, Nk = 32768) measurement")
@@ -126,7 +127,7 @@ def main():
         t["gamma"] = None if data["gamma"] is None else torch.from_numpy(data["gamma"]).to(dev)
         return data, cfg, t
 
-    def measure(name, steps, warmup, alpha=None, want_events=True):
+    def measure(name, steps, warmup, alpha=None, want_events=True, nape=False):
         """Times `steps` steps of workload `name` (forward, plus backward with the forward's saved buffer where the
         workload has one) wall-clock with no events inside, then once more with the library's phase events."""
         data, cfg, t = upload(name, want_dO=bool(synth.CONFIGS[name]["bwd"]))
@@ -134,6 +135,8 @@ def main():
         alpha = cfg["alpha"] if alpha is None else alpha
         do_bwd = bool(cfg["bwd"])
         kw = dict(alpha=alpha, beta=t["beta"], gamma=t["gamma"], delta=data["delta"], causal=True, logn_mode=0)
+        if nape:  # Sec. 4.2: every other head carries the linear distance bias, inside the ASEntmax scale
+            kw.update(alibi_slopes=torch.from_numpy(synth.nape_slopes(H)).to(dev), bias_mode=0)
         prm = binding.make_params(t["Q"], t["K"], alpha, data["delta"], True, t["beta"], 0)
         ws = torch.empty(max(binding.workspace_bytes(prm, 0), binding.workspace_bytes(prm, 1) if do_bwd else 0),
                          dtype=torch.uint8, device=dev)
@@ -214,19 +217,21 @@ def main():
             "tile_skip_rate_fwd": 1.0 - (sd["fwd_cand_tiles"] + sd["fwd_pv_tiles"]) / max(sd["fwd_tiles_visible"], 1),
             "support_per_row": (sd["fwd_support"] if sd["fwd_support"] else sd["bwd_support"]) / max(B * H * n, 1),
         }
+        if sd["fwd_window_skipped"]:  # distance bias: visible tiles beyond every row's window, never visited
+            out["window_skipped_fraction"] = sd["fwd_window_skipped"] / max(sd["fwd_tiles_visible"], 1)
         if "kernel_ms" in r:
             out["kernel_ms"] = r["kernel_ms"]
         return out
 
     # ---------------------------------------------------------------- headline workload
-    main_r = measure(args.workload, args.steps, args.warmup, alpha=args.alpha)
+    main_r = measure(args.workload, args.steps, args.warmup, alpha=args.alpha, nape=args.nape)
     cfg, sd, ms_per_step = main_r["cfg"], main_r["stats"], main_r["ms"]
     B, H, n, d, alpha = cfg["B"], cfg["H"], cfg["n"], cfg["d"], main_r["alpha"]
     kernel_ms, algo = main_r["kernel_ms"], main_r["algo"]
     # the roofline object describes the longest kernel among those that do tile (MFMA) work
     dominant = max((k for k in kernel_ms if algo[k] > 0), key=kernel_ms.get, default=max(kernel_ms, key=kernel_ms.get))
     achieved = algo[dominant] / (kernel_ms[dominant] * 1e-3) / 1e12
-    traffic = read_traffic() if args.workload == "c3" and args.alpha is None else None
+    traffic = read_traffic() if args.workload == "c3" and args.alpha is None and not args.nape else None
     s_main = summary(main_r)
 
     # what the matrix pipeline sustains with nothing else in the way (measured beside the data-sheet peak)
@@ -254,9 +259,9 @@ def main():
         "vs_baseline": None,
         "dtype": "bf16" if cfg["dtype"] == "bf16" else "f32",
         "data": "synthetic",
-        "config": {"workload": "%s: B=%d H=%d n=%d d=%d %s causal alpha=%g ASEntmax per-head scale, %g%% planted keys, %s"
+        "config": {"workload": "%s: B=%d H=%d n=%d d=%d %s causal alpha=%g ASEntmax per-head scale, %g%% planted keys, %s%s"
                                % (args.workload, B, H, n, d, cfg["dtype"], alpha, 100 * cfg["planted"],
-                                  "fwd+bwd" if main_r["do_bwd"] else "fwd"),
+                                  "fwd+bwd" if main_r["do_bwd"] else "fwd", ", NAPE distance bias" if args.nape else ""),
                    "B": B, "H": H, "n": n, "d": d, "alpha": alpha, "tile": "32x32"},
         "tokens_per_s": s_main["tokens_per_s"],
         # matrix-core work the kernels executed (their own tile counters) per second of the whole step, and the usual
@@ -285,7 +290,7 @@ def main():
     del main_r
     torch.cuda.empty_cache()
 
-    if not args.no_extra and args.workload == "c3" and args.alpha is None:
+    if not args.no_extra and args.workload == "c3" and args.alpha is None and not args.nape:
         k4 = max(3, args.steps // 4)
         extra = {}
         extra["c2_n1024_fwd"] = summary(measure("c2", args.steps, args.warmup))
@@ -296,6 +301,10 @@ def main():
             extra["c5_n8192_d128_alpha%g" % a5] = summary(measure("c5", k4, 1, alpha=a5))
             torch.cuda.empty_cache()
         extra["c3d_dense_regime"] = summary(measure("c3d", k4, 1))
+        torch.cuda.empty_cache()
+        extra["c3_nape_fwd_bwd"] = summary(measure("c3", args.steps, args.warmup, nape=True))
+        torch.cuda.empty_cache()
+        extra["c4_nape_fwd"] = summary(measure("c4", k4, 1, nape=True))
         torch.cuda.empty_cache()
         for v in extra.values():
             v.pop("data", None)

@@ -65,7 +65,7 @@ struct BwdSparseArgs {
 // One Q K^T sweep at the saved threshold: the lists it writes are the rows' exact supports.
 template <typename T, int D, int AM, bool BIAS>
 __device__ __forceinline__ void bwd_lists_block(const BwdSparseArgs& A, int bh_, int blk_, char* smem) {
-  using C = QCtx<T, D, FwdTile<T>::value, BIAS>;
+  using C = QCtx<T, D, ListCfg<T, D>::kTile, BIAS>;
   constexpr int TB = C::kTileBytes;
   const Geom& g = A.g;
   int* ovf = reinterpret_cast<int*>(smem + 2 * TB);
@@ -89,7 +89,7 @@ __device__ __forceinline__ void bwd_lists_block(const BwdSparseArgs& A, int bh_,
 }
 
 template <typename T, int D, int AM, bool BIAS>
-__global__ __launch_bounds__(kThreads, 3) void bwd_lists_kernel(BwdSparseArgs A) {
+__global__ __launch_bounds__(kThreads, (ListCfg<T, D>::kOcc)) void bwd_lists_kernel(BwdSparseArgs A) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const PairItem it = pair_item(A.nqb);
   for (int part = 0; part < 2; ++part) {

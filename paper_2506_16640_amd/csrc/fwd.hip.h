@@ -138,6 +138,15 @@ struct FwdTile {
   static constexpr int value = sizeof(T) == 2 ? 128 : 32;
 };
 
+// Keys per LDS tile and workgroups per CU of the list sweeps (fwd_sparse.hip.h, bwd_sparse.hip.h), as measured:
+// at D = 64 four 32-key blocks per tile and three workgroups per CU; at D = 128 the query fragments take twice
+// the registers, and two blocks per tile with four workgroups per CU run a quarter faster (no spills).
+template <typename T, int D>
+struct ListCfg {
+  static constexpr int kTile = sizeof(T) == 2 ? (D == 64 ? 128 : 64) : 32;
+  static constexpr int kOcc = (sizeof(T) == 2 && D == 128) ? 4 : 3;
+};
+
 template <typename T, int D, int AM, bool BIAS>
 __device__ __forceinline__ void fwd_block(const FwdArgs& A, int bh_, int blk_, char* smem) {
   using C = QCtx<T, D, FwdTile<T>::value, BIAS>;

@@ -220,7 +220,7 @@ __device__ __forceinline__ float two_key_bound(float y1, float y2, float r) {
 
 template <typename T, int D, int AM, bool BIAS>
 __device__ __forceinline__ void fwd_lists_block(const FwdSparseArgs& A, int bh_, int blk_, char* smem) {
-  using C = QCtx<T, D, FwdTile<T>::value, BIAS>;
+  using C = QCtx<T, D, ListCfg<T, D>::kTile, BIAS>;
   constexpr int KT = C::KT, NSB = C::NSB, TB = C::kTileBytes;
   const Geom& g = A.g;
   char* tiles = smem;  // 2 buffers x 1 slot
@@ -323,7 +323,7 @@ __device__ __forceinline__ void fwd_lists_block(const FwdSparseArgs& A, int bh_,
 }
 
 template <typename T, int D, int AM, bool BIAS>
-__global__ __launch_bounds__(kThreads, 3) void fwd_lists_kernel(FwdSparseArgs A) {
+__global__ __launch_bounds__(kThreads, (ListCfg<T, D>::kOcc)) void fwd_lists_kernel(FwdSparseArgs A) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const PairItem it = pair_item(A.nqb);
   for (int part = 0; part < 2; ++part) {

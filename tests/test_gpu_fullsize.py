@@ -205,6 +205,49 @@ def test_c5_alpha_sweep_d128_sampled_heads(alpha):
               "the sampled rows %.3g, without those rows %.3g" % (len(near_rows), len(rows), e_all, e_wo), flush=True)
 
 
+@pytest.mark.parametrize("bias_mode", [0, 1])
+def test_c3_nape_fwd_bwd_sampled_heads(bias_mode):
+    """The headline workload with the NAPE arrangement of Sec. 4.2 (every other head carries the linear distance
+    bias): biased and unbiased heads against the oracle, with the forward's lists handed to the backward, and
+    the parameter gradients of one head of each kind."""
+    data = synth.make_config("c3")
+    slopes = synth.nape_slopes(12)
+    g = gpu_run(data, 1.5, "bf16", stats=True, use_saved=True, slopes=slopes, bias_mode=bias_mode)
+    worst = {}
+    for (b, h) in ((0, 0), (1, 1), (2, 4), (3, 7), (0, 10), (3, 11)):
+        r = oracle_run(_head_slice(data, b, h), 1.5, slopes=slopes[h:h + 1], bias_mode=bias_mode)
+        _compare_head("c3 nape", g, r, b, h, True, worst)
+    print("c3 nape mode", bias_mode, "worst errors over 6 heads", worst, flush=True)
+    wg = {}
+    for h in (4, 7):
+        r = oracle_run(_heads_slice(data, h), 1.5, slopes=slopes[h:h + 1], bias_mode=bias_mode)
+        for t in ("dbeta", "dgamma"):
+            err = abs(g[t][h] - r[t][0]) / abs(r[t][0])
+            assert err <= TOL_GRAD, (h, t, err)
+            wg[t] = max(wg.get(t, 0.0), float(err))
+    st = g["stats"]
+    print("c3 nape mode", bias_mode, "d beta / d gamma", wg, "window-skipped fraction of visible tiles",
+          st["fwd_window_skipped"] / st["fwd_tiles_visible"], flush=True)
+    # half of the heads are biased with slopes >= 1/2: most of their tiles lie beyond the window (outside the
+    # scale -- mode 1 -- the bias is weaker relative to the scaled content scores, and the window wider)
+    assert st["fwd_window_skipped"] > (0.4 if bias_mode == 0 else 0.25) * st["fwd_tiles_visible"]
+
+
+def test_c4_nape_long_context_forward():
+    data = synth.make_config("c4")
+    slopes = synth.nape_slopes(12)
+    g = gpu_run(data, 1.5, "bf16", bwd=False, stats=True, slopes=slopes)
+    worst = {}
+    for h in (0, 5, 6, 11):
+        r = oracle_run(_head_slice(data, 0, h), 1.5, bwd=False, slopes=slopes[h:h + 1])
+        _compare_head("c4 nape", g, r, 0, h, False, worst)
+    st = g["stats"]
+    skip = 1.0 - (st["fwd_cand_tiles"] + st["fwd_pv_tiles"]) / st["fwd_tiles_visible"]
+    print("c4 nape worst errors", worst, "tile-skip rate", skip, "never visited (window)",
+          st["fwd_window_skipped"] / st["fwd_tiles_visible"], flush=True)
+    assert st["fwd_window_skipped"] > 0.4 * st["fwd_tiles_visible"]
+
+
 @pytest.mark.parametrize("nq", [1, 8])
 def test_decode_full_size(nq):
     """The decode workload bench.py times (B=4, H=12, Nk=32768, d=64, bf16): every row against the oracle,
