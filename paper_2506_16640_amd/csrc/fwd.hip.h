@@ -145,6 +145,13 @@ template <typename T, int D>
 struct ListCfg {
   static constexpr int kTile = sizeof(T) == 2 ? (D == 64 ? 128 : 64) : 32;
   static constexpr int kOcc = (sizeof(T) == 2 && D == 128) ? 4 : 3;
+  // cells per thread that the collecting sweep keeps in LDS (20 bytes each)
+#ifndef ENTMAX_LDS_CELLS
+#define ENTMAX_LDS_CELLS 4
+#endif
+  static constexpr int kLdsCells = kOcc == 4 ? 1 : ENTMAX_LDS_CELLS;
+  // dynamic LDS of a list-sweep kernel: two tile buffers, the flags, the cells
+  static constexpr size_t kLdsBytes = 2 * (size_t)kTile * D * sizeof(T) + 64 + (size_t)kLdsCells * kThreads * 20;
 };
 
 template <typename T, int D, int AM, bool BIAS>

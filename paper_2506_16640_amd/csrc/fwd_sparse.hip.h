@@ -57,33 +57,62 @@ struct FwdSparseArgs {
   int nqb;
 };
 
-// A cell is the group of kCellKeys consecutive accumulator registers of a lane (keys j, j+1, j+2, j+3 of
-// one row, and 8 keys further for each additional group).  During a sweep a lane appends whole cells
+// A cell is a group of four consecutive accumulator registers of a lane (keys j, j+1, j+2, j+3 of
+// one row).  During a sweep a lane appends whole cells
 // -- all their raw scores and the first key index -- to a private strip of scratch memory whenever the
 // cell maximum passes the cutoff: one short divergent region per cell instead of one per score.  After
 // the sweep each lane walks its own cells and writes the scores above the cutoff to its list.
-constexpr int kCellKeys = 4 * kCellGroups;
-constexpr int kCellsPerBlock = 16 / kCellKeys;
-
-template <int CAP>
+// The first LS cells of a thread stay in LDS (the common case: a row has a handful of candidates), the others go
+// to a strip of global scratch.  Addresses are formed where they are used: the struct holds two registers.
+template <int CAP, int LS>
 struct CellBuf {
-  // cell s of the 256 threads of a workgroup together (s-major), for the same reason as the row lists
-  f32x4_t* d;  // cell s, group u at d[(s * kCellGroups + u) * kThreads]: raw scores
-  int* j;      // cell s at j[s * kThreads]: key of the cell's first score
+  static_assert(kCellGroups == 1, "a cell is one group of four accumulator registers");
+  // cell s of the 256 threads of a workgroup together (s-major), for the same reason as the row lists:
+  //   LDS:    scores of cell s at lds + (s * kThreads + tid) * 16, its first key at lds + LS * kThreads * 16 + (s * kThreads + tid) * 4
+  //   global: the same with CAP in place of LS, in the workgroup's strip
+  char* lds;
+  char* strip;  // workgroup-uniform
+  int tid;
   static constexpr size_t kBytesPerWorkgroup = cell_bytes_per_workgroup(CAP);
-  __device__ __forceinline__ void init(void* base, int tid) {
-    char* wg = reinterpret_cast<char*>(base) + (size_t)blockIdx.x * kBytesPerWorkgroup;
-    d = reinterpret_cast<f32x4_t*>(wg) + tid;
-    j = reinterpret_cast<int*>(wg + (size_t)kThreads * CAP * 16 * kCellGroups) + tid;
+  static constexpr int kLdsBytes = LS * kThreads * 20;
+  __device__ __forceinline__ void init(void* base, char* lds_, int tid_) {
+    strip = reinterpret_cast<char*>(base) + (size_t)blockIdx.x * kBytesPerWorkgroup;
+    lds = lds_;
+    tid = tid_;
+  }
+  // n: cells this thread stored before.  A strip that is full keeps overwriting its last cell (the caller
+  // then discards the lists).
+  __device__ __forceinline__ void store(int n, const f32x4_t& v, int key) {
+    if (LS > 0 && n < LS) {
+      const int e = n * kThreads + tid;
+      *reinterpret_cast<f32x4_t*>(lds + e * 16) = v;
+      *reinterpret_cast<int*>(lds + LS * kThreads * 16 + e * 4) = key;
+    } else {
+      const int e = min(n, CAP - 1) * kThreads + tid;
+      *reinterpret_cast<f32x4_t*>(strip + (size_t)e * 16) = v;
+      *reinterpret_cast<int*>(strip + (size_t)CAP * kThreads * 16 + (size_t)e * 4) = key;
+    }
+  }
+  __device__ __forceinline__ void load(int n, f32x4_t& v, int& key) const {
+    if (LS > 0 && n < LS) {
+      const int e = n * kThreads + tid;
+      v = *reinterpret_cast<const f32x4_t*>(lds + e * 16);
+      key = *reinterpret_cast<const int*>(lds + LS * kThreads * 16 + e * 4);
+    } else {
+      const int e = n * kThreads + tid;
+      v = *reinterpret_cast<const f32x4_t*>(strip + (size_t)e * 16);
+      key = *reinterpret_cast<const int*>(strip + (size_t)CAP * kThreads * 16 + (size_t)e * 4);
+    }
   }
 };
 
 // One sweep over the visible key tiles of the block: every key whose shifted score
 // a * dot - thr is positive ends up in the lane's list.  Returns false (workgroup-uniform) if
-// some list overflowed; the sweep is abandoned early in that case.  ovf: three ints of LDS.
-template <typename C, typename T, int D, int CAP>
-__device__ __forceinline__ bool collect_sweep(const C& q, const Geom& g, const void* K, char* tiles, int* ovf, bool live,
-                                              float thr, void* cells, uint2* mylist, int& cnt, unsigned& n_qk,
+// some list overflowed; the sweep is abandoned early in that case.  ovf: three ints of LDS;
+// lds_cells: CellBuf<CAP, LS>::kLdsBytes bytes of LDS.
+template <typename C, typename T, int D, int CAP, int LS>
+__device__ __forceinline__ bool collect_sweep(const C& q, const Geom& g, const void* K, char* tiles, int* ovf, char* lds_cells,
+                                              bool live, float thr, void* cells, uint2* mylist, int& cnt, unsigned& n_qk,
                                               unsigned& n_cand_tiles) {
   constexpr int KT = C::KT, NSB = C::NSB;
   // candidates are the keys with a * dot > thr: in raw units, dot > cut.  Rounding may move a key that
@@ -91,8 +120,8 @@ __device__ __forceinline__ bool collect_sweep(const C& q, const Geom& g, const v
   // Scale 0 (a = 0): every visible key ties; they all qualify iff thr < 0.
   const float cut = !live ? kInf : (q.a > 0.f ? thr / q.a : (thr < 0.f ? -3.0e38f : kInf));
   if (q.tid < 3) ovf[q.tid] = 0;
-  CellBuf<CAP> cb;
-  cb.init(cells, q.tid);
+  CellBuf<CAP, LS> cb;
+  cb.init(cells, lds_cells, q.tid);
   int ncell = 0;
   Slot slots[1];
   slots[0].base = reinterpret_cast<const char*>(reinterpret_cast<const T*>(K) + (long long)q.b * g.kv_sb +
@@ -132,19 +161,10 @@ __device__ __forceinline__ bool collect_sweep(const C& q, const Geom& g, const v
           if (__ballot(lm > cut) == 0ull) continue;
           ++n_cand_tiles;
 #pragma unroll
-          for (int cl = 0; cl < kCellsPerBlock; ++cl) {
-            float cm = gm[cl * kCellGroups];
-#pragma unroll
-            for (int u = 1; u < kCellGroups; ++u) cm = fmaxf(cm, gm[cl * kCellGroups + u]);
-            if (cm > cut) {
-              // a strip that is full keeps overwriting its last cell; the flag below discards the lists
-              const int slot = min(ncell, CAP - 1);
-#pragma unroll
-              for (int u = 0; u < kCellGroups; ++u) {
-                const int e0 = 4 * (cl * kCellGroups + u);
-                cb.d[(slot * kCellGroups + u) * kThreads] = f32x4_t{acc[sb][e0], acc[sb][e0 + 1], acc[sb][e0 + 2], acc[sb][e0 + 3]};
-              }
-              cb.j[slot * kThreads] = j0 + q.key_of(4 * cl * kCellGroups);
+          for (int cl = 0; cl < 4; ++cl) {
+            if (gm[cl] > cut) {
+              cb.store(ncell, f32x4_t{acc[sb][4 * cl], acc[sb][4 * cl + 1], acc[sb][4 * cl + 2], acc[sb][4 * cl + 3]},
+                       j0 + q.key_of(4 * cl));
               ++ncell;
             }
           }
@@ -157,36 +177,28 @@ __device__ __forceinline__ bool collect_sweep(const C& q, const Geom& g, const v
   // the sweep ended on a barrier: both flags are final
   bool fits = (ovf[0] | ovf[1]) == 0;
   if (fits) {
-    // a cell holds at most kCellKeys candidates, so there are at least as many candidates as cells.
-    // First count: nothing is written (and no key counted) for a block one of whose lists is too long.
+    // a cell holds at most four candidates, so there are at least as many candidates as cells.  One pass: the
+    // scores above the cutoff go to the list; a list that would grow beyond CAP raises the third flag, and the
+    // block's lists are then discarded as a whole.
     int total = 0;
     for (int k = 0; k < ncell; ++k) {
+      f32x4_t dv;
+      int jc;
+      cb.load(k, dv, jc);
 #pragma unroll
-      for (int u = 0; u < kCellGroups; ++u) {
-        const f32x4_t dv = cb.d[(k * kCellGroups + u) * kThreads];
-#pragma unroll
-        for (int rr = 0; rr < 4; ++rr) total += dv[rr] > cut ? 1 : 0;
+      for (int rr = 0; rr < 4; ++rr) {
+        if (dv[rr] > cut) {
+          if (cnt < CAP) {
+            mylist[cnt * kListStride] = make_uint2((unsigned)(jc + rr), __float_as_uint(dv[rr]));
+            ++cnt;
+          }
+          ++total;
+        }
       }
     }
     if (total > CAP) ovf[2] = 1;
     __syncthreads();
     fits = ovf[2] == 0;
-    if (fits) {
-      for (int k = 0; k < ncell; ++k) {
-        const int jc = cb.j[k * kThreads];
-#pragma unroll
-        for (int u = 0; u < kCellGroups; ++u) {
-          const f32x4_t dv = cb.d[(k * kCellGroups + u) * kThreads];
-#pragma unroll
-          for (int rr = 0; rr < 4; ++rr) {
-            if (dv[rr] > cut && cnt < CAP) {
-              mylist[cnt * kListStride] = make_uint2((unsigned)(jc + 8 * u + rr), __float_as_uint(dv[rr]));
-              ++cnt;
-            }
-          }
-        }
-      }
-    }
   }
   return fits;
 }
@@ -225,6 +237,7 @@ __device__ __forceinline__ void fwd_lists_block(const FwdSparseArgs& A, int bh_,
   const Geom& g = A.g;
   char* tiles = smem;  // 2 buffers x 1 slot
   int* ovf = reinterpret_cast<int*>(smem + 2 * TB);  // sticky overflow flags: [0], [1] by tile parity, [2] list
+  char* lds_cells = smem + 2 * TB + 64;
 
   C q;
   q.init(g, A.Q, bh_, blk_);
@@ -300,7 +313,7 @@ __device__ __forceinline__ void fwd_lists_block(const FwdSparseArgs& A, int bh_,
   // ---------------------------------------------- 2. candidate lists at tau_lb
   uint2* mylist = A.cand + list_entry<kCandCap>(q.bh, A.nqb, q.qb, q.wave, q.lane);
   int cnt = 0;
-  const bool fits = collect_sweep<C, T, D, kCandCap>(q, g, A.K, tiles, ovf, live, lo, A.cells, mylist, cnt, n_qk2, n_cand_tiles);
+  const bool fits = collect_sweep<C, T, D, kCandCap, ListCfg<T, D>::kLdsCells>(q, g, A.K, tiles, ovf, lds_cells, live, lo, A.cells, mylist, cnt, n_qk2, n_cand_tiles);
   if (!fits) {
     if (q.tid == 0) A.dense_flag[flag_idx] = 1;
   } else {

@@ -35,7 +35,7 @@ bool launch_bwd_rows(const BwdSparseArgs& a, int nblocks, hipStream_t st, void* 
   const dim3 row_grid((unsigned)(a.g.B * a.g.H * a.nqb));
   if (!from_saved) {
     // no lists from the forward: one Q K^T sweep at tau rebuilds the supports
-    size_t smem = 2 * (size_t)QCtx<T, D, ListCfg<T, D>::kTile>::kTileBytes + 64;
+    size_t smem = ListCfg<T, D>::kLdsBytes;
     hipLaunchKernelGGL((bwd_lists_kernel<T, D, AM, BIAS>), dim3((unsigned)nblocks), dim3(kThreads), smem, st, a);
     if (!launch_ok()) return false;
   }

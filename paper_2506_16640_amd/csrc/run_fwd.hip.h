@@ -31,7 +31,7 @@ bool launch_fwd_am(const FwdArgs& a, int am, int nblocks, hipStream_t st) {
 
 template <typename T, int D, int AM, bool BIAS>
 bool launch_fwd_sparse(const FwdSparseArgs& a, int nblocks, hipStream_t st, void* const* ev) {
-  size_t smem = 2 * (size_t)QCtx<T, D, ListCfg<T, D>::kTile>::kTileBytes + 64;
+  size_t smem = ListCfg<T, D>::kLdsBytes;
   hipLaunchKernelGGL((fwd_lists_kernel<T, D, AM, BIAS>), dim3((unsigned)nblocks), dim3(kThreads), smem, st, a);
   if (!launch_ok()) return false;
   record(ev, ENTMAX_FWD_PHASE_LISTS + 1, st);
