@@ -134,8 +134,8 @@ enum {
   ENTMAX_FWD_NUM_PHASES = 5
 };
 enum {
-  ENTMAX_BWD_PHASE_LISTS = 0,      /* one Q K^T sweep at the saved threshold (not with `saved`); with alibi_slopes
-                                      the heads' largest key norms */
+  ENTMAX_BWD_PHASE_LISTS = 0,      /* without `saved`: one Q K^T sweep at the saved threshold, and with alibi_slopes
+                                      the heads' largest key norms before it */
   ENTMAX_BWD_PHASE_ROWS = 1,       /* per-key segment offsets; mu, dscale, dQ and the per-entry (p, dS) from the lists */
   ENTMAX_BWD_PHASE_TRANSPOSE = 2,  /* tiled path (heads the list kernel left over): operand copies */
   ENTMAX_BWD_PHASE_MASK = 3,       /* tiled path: non-zero tile map */

@@ -417,6 +417,55 @@ int oracle_tile_map(const oracle_params* P, const double* Q, const double* K, co
   return 0;
 }
 
+/* ---------------------------------------------------------------------------
+ * ASEntmax scale projections (Sec. 4.1, the two equations after eq. (asentmax)): for every token x_t of
+ * X [B,N,E] and every head h with projection vectors w_beta,h, w_gamma,h (rows of Wb, Wg [H,E]),
+ *     beta[b,h,i]  = softplus(<x_{b,i}, w_beta,h>)  = ln(1 + e^u)
+ *     gamma[b,h,i] = s * tanh(<x_{b,i}, w_gamma,h>)
+ * written in the per-query layout [B,H,N] the attention takes.  The paper gives no value for s: an argument.
+ * ------------------------------------------------------------------------- */
+int oracle_scale_proj_fwd(int B, int H, int N, int E, double s, const double* X, const double* Wb, const double* Wg,
+                          double* beta, double* gamma) {
+  for (int b = 0; b < B; ++b)
+    for (int h = 0; h < H; ++h)
+      for (int i = 0; i < N; ++i) {
+        const double* x = X + ((size_t)b * N + i) * E;
+        double u = dot(x, Wb + (size_t)h * E, E), v = dot(x, Wg + (size_t)h * E, E);
+        /* ln(1 + e^u) without overflow: max(u, 0) + ln(1 + e^-|u|) */
+        beta[((size_t)b * H + h) * N + i] = (u > 0 ? u : 0) + log1p(exp(-fabs(u)));
+        gamma[((size_t)b * H + h) * N + i] = s * tanh(v);
+      }
+  return 0;
+}
+
+/* Chain rule through the projections: with u = <x, w_beta>, v = <x, w_gamma>,
+ *     d beta / du = e^u / (1 + e^u),   d gamma / dv = s (1 - tanh^2 v),
+ * dWb[h] = sum_{b,i} dbeta du/.. x_{b,i},  dWg[h] likewise,  dX[b,i] = sum_h (du w_beta,h + dv w_gamma,h). */
+int oracle_scale_proj_bwd(int B, int H, int N, int E, double s, const double* X, const double* Wb, const double* Wg,
+                          const double* dbeta, const double* dgamma, double* dX, double* dWb, double* dWg) {
+  for (size_t k = 0; k < (size_t)B * N * E; ++k) dX[k] = 0.0;
+  for (size_t k = 0; k < (size_t)H * E; ++k) dWb[k] = dWg[k] = 0.0;
+  for (int b = 0; b < B; ++b)
+    for (int h = 0; h < H; ++h)
+      for (int i = 0; i < N; ++i) {
+        const double* x = X + ((size_t)b * N + i) * E;
+        double* dx = dX + ((size_t)b * N + i) * E;
+        const double* wb = Wb + (size_t)h * E;
+        const double* wg = Wg + (size_t)h * E;
+        double u = dot(x, wb, E), v = dot(x, wg, E);
+        double sig = u >= 0 ? 1.0 / (1.0 + exp(-u)) : exp(u) / (1.0 + exp(u));
+        double th = tanh(v);
+        double du = dbeta[((size_t)b * H + h) * N + i] * sig;
+        double dv = dgamma[((size_t)b * H + h) * N + i] * s * (1.0 - th * th);
+        for (int k = 0; k < E; ++k) {
+          dWb[(size_t)h * E + k] += du * x[k];
+          dWg[(size_t)h * E + k] += dv * x[k];
+          dx[k] += du * wb[k] + dv * wg[k];
+        }
+      }
+  return 0;
+}
+
 int oracle_num_threads(void) {
 #ifdef _OPENMP
   return omp_get_max_threads();

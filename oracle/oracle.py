@@ -140,3 +140,30 @@ def tile_map(Q, K, alpha, tq, tk, beta=None, gamma=None, delta=1.0, causal=True,
     lib.oracle_tile_map(ctypes.byref(prm), _dp(Q), _dp(K), _dp(beta), _dp(gamma), _dp(slopes), ctypes.c_int(tq), ctypes.c_int(tk),
                         nz.ctypes.data_as(u8), vis.ctypes.data_as(u8))
     return nz, vis
+
+
+def scale_proj_fwd(X, Wb, Wg, s):
+    """ASEntmax scale projections: X [B,N,E], Wb, Wg [H,E] -> beta, gamma [B,H,N] (per-query layout)."""
+    lib = _load()
+    X, Wb, Wg = _f64(X), _f64(Wb), _f64(Wg)
+    B, N, E = X.shape
+    H = Wb.shape[0]
+    beta = np.empty((B, H, N), dtype=np.float64)
+    gamma = np.empty((B, H, N), dtype=np.float64)
+    rc = lib.oracle_scale_proj_fwd(ctypes.c_int(B), ctypes.c_int(H), ctypes.c_int(N), ctypes.c_int(E), ctypes.c_double(s),
+                                   _dp(X), _dp(Wb), _dp(Wg), _dp(beta), _dp(gamma))
+    assert rc == 0
+    return beta, gamma
+
+
+def scale_proj_bwd(X, Wb, Wg, s, dbeta, dgamma):
+    """Gradients of the scale projections: returns dict(dX, dWb, dWg)."""
+    lib = _load()
+    X, Wb, Wg, dbeta, dgamma = _f64(X), _f64(Wb), _f64(Wg), _f64(dbeta), _f64(dgamma)
+    B, N, E = X.shape
+    H = Wb.shape[0]
+    dX, dWb, dWg = np.empty_like(X), np.empty_like(Wb), np.empty_like(Wg)
+    rc = lib.oracle_scale_proj_bwd(ctypes.c_int(B), ctypes.c_int(H), ctypes.c_int(N), ctypes.c_int(E), ctypes.c_double(s),
+                                   _dp(X), _dp(Wb), _dp(Wg), _dp(dbeta), _dp(dgamma), _dp(dX), _dp(dWb), _dp(dWg))
+    assert rc == 0
+    return dict(dX=dX, dWb=dWb, dWg=dWg)

@@ -73,7 +73,9 @@ int run_bwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
             void* const* ev) {
   record(ev, 0, st);
   const int B = p->B, H = p->H;
-  float* knorm = BIAS ? reinterpret_cast<float*>(ws + L.off_bknorm) : nullptr;
+  // the forward left the key norms in `saved`; without it they are computed again
+  const float* knorm = !BIAS ? nullptr
+                             : reinterpret_cast<const float*>(saved ? saved + L.sv_knorm : ws + L.off_bknorm);
   Geom g = make_geom(p, L, beta, gamma, slopes, knorm);
   float* dscale = reinterpret_cast<float*>(ws + L.off_dscale);
   bool ok = true;
@@ -85,7 +87,8 @@ int run_bwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
     for (int k = 1; k <= ENTMAX_BWD_PHASE_KEYS + 1; ++k) record(ev, k, st);
   } else {
     const bool lists = p->path == 0;
-    if (BIAS && !launch_key_norms<T, D>(p, L, K, knorm, st)) return ENTMAX_ATTN_LAUNCH_FAILED;
+    if (BIAS && !saved && !launch_key_norms<T, D>(p, L, K, reinterpret_cast<float*>(ws + L.off_bknorm), st))
+      return ENTMAX_ATTN_LAUNCH_FAILED;
     int* block_flag = reinterpret_cast<int*>(ws + L.off_hflag);
     int* head_flag = block_flag + (size_t)B * H * L.nqb;
     BwdSparseArgs sa;

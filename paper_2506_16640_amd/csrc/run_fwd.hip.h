@@ -73,7 +73,8 @@ int run_fwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
             const float* beta, const float* gamma, const float* slopes, void* O, float* tau, char* saved,
             uint64_t* stats, char* ws, hipStream_t st, void* const* ev) {
   record(ev, 0, st);
-  float* knorm = BIAS ? reinterpret_cast<float*>(ws + L.off_fknorm) : nullptr;
+  // with a `saved` buffer the key norms are written there: the backward needs them too
+  float* knorm = !BIAS ? nullptr : reinterpret_cast<float*>(saved ? saved + L.sv_knorm : ws + L.off_fknorm);
   if (p->Nk == 0) {
     bool ok = zero_rows<T>(O, L.q_sb, L.q_sh, L.q_sn, p->B, p->H, p->Nq, p->D, st) &&
               zero_words(tau, (size_t)p->B * p->H * p->Nq * 4, st);
@@ -86,6 +87,7 @@ int run_fwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
       // no lists for the backward: every block belongs to its tiled kernels
       if (saved && !fill_words(saved + L.sv_flags, (size_t)p->B * p->H * L.nqb * sizeof(int), 1u, st))
         return ENTMAX_ATTN_LAUNCH_FAILED;
+      if (BIAS && saved && !launch_key_norms<T, D>(p, L, K, knorm, st)) return ENTMAX_ATTN_LAUNCH_FAILED;
       record(ev, ENTMAX_FWD_PHASE_PREPARE + 1, st);
       DecodeArgs da;
       da.g = make_geom(p, L, beta, gamma, slopes, nullptr);

@@ -529,3 +529,90 @@ def test_alibi_backward_matches_finite_differences(alpha, causal, Nq, Nk, layout
     if layout != 0:
         np.testing.assert_allclose(g["dbeta"], fd(beta), **tol)
         np.testing.assert_allclose(g["dgamma"], fd(gamma), **tol)
+
+
+# ------------------------------------------------------------------ ASEntmax scale projections (Sec. 4.1)
+
+def _proj_case(seed, B=2, H=3, N=5, E=7, wscale=0.7):
+    rng = np.random.default_rng(seed)
+    return (rng.standard_normal((B, N, E)), wscale * rng.standard_normal((H, E)), wscale * rng.standard_normal((H, E)))
+
+
+def test_scale_projection_special_values():
+    """Zero projection vectors give beta = softplus(0) = ln 2 and gamma = 0 whatever X holds; a strongly positive
+    pre-activation gives beta = u (softplus is asymptotically the identity) and gamma = s, a strongly negative one
+    beta = e^u and gamma = -s."""
+    X, Wb, Wg = _proj_case(0)
+    beta, gamma = oracle.scale_proj_fwd(X, 0 * Wb, 0 * Wg, 1.5)
+    assert np.allclose(beta, math.log(2.0), rtol=0, atol=1e-15) and np.all(gamma == 0.0)
+    x = np.zeros((1, 2, 4))
+    x[0, 0, 0], x[0, 1, 0] = 50.0, -50.0
+    w = np.zeros((1, 4))
+    w[0, 0] = 1.0
+    beta, gamma = oracle.scale_proj_fwd(x, w, w, 0.8)
+    assert abs(beta[0, 0, 0] - 50.0) < 1e-12 and abs(beta[0, 0, 1] / math.exp(-50.0) - 1.0) < 1e-12
+    assert abs(gamma[0, 0, 0] - 0.8) < 1e-15 and abs(gamma[0, 0, 1] + 0.8) < 1e-15
+
+
+def test_scale_projection_composition():
+    # the projections through library routines: einsum for the inner products, logaddexp(0, u) = ln(1 + e^u), tanh
+    X, Wb, Wg = _proj_case(1, B=2, H=4, N=9, E=16)
+    beta, gamma = oracle.scale_proj_fwd(X, Wb, Wg, 2.0)
+    assert beta.shape == (2, 4, 9)
+    assert np.allclose(beta, np.logaddexp(0.0, np.einsum("bne,he->bhn", X, Wb)), rtol=1e-13, atol=1e-14)
+    assert np.allclose(gamma, 2.0 * np.tanh(np.einsum("bne,he->bhn", X, Wg)), rtol=1e-13, atol=1e-14)
+    assert (beta > 0).all() and (np.abs(gamma) < 2.0).all()  # the ranges the paper states
+
+
+def test_scale_projection_backward_finite_differences():
+    X, Wb, Wg = _proj_case(2)
+    s = 1.3
+    rng = np.random.default_rng(3)
+    dbeta, dgamma = rng.standard_normal((2, 3, 5)), rng.standard_normal((2, 3, 5))
+
+    def loss(X_, Wb_, Wg_):
+        b, g = oracle.scale_proj_fwd(X_, Wb_, Wg_, s)
+        return float((b * dbeta).sum() + (g * dgamma).sum())
+
+    grads = oracle.scale_proj_bwd(X, Wb, Wg, s, dbeta, dgamma)
+    h = 1e-6
+    for name, arr, idx in (("dX", X, (1, 2, 3)), ("dX", X, (0, 0, 6)), ("dWb", Wb, (2, 4)), ("dWb", Wb, (0, 0)),
+                           ("dWg", Wg, (1, 5)), ("dWg", Wg, (2, 1))):
+        args = {"dX": [X.copy(), Wb, Wg], "dWb": [X, Wb.copy(), Wg], "dWg": [X, Wb, Wg.copy()]}[name]
+        k = {"dX": 0, "dWb": 1, "dWg": 2}[name]
+        args[k][idx] += h
+        up = loss(*args)
+        args[k][idx] -= 2 * h
+        dn = loss(*args)
+        fd = (up - dn) / (2 * h)
+        assert abs(fd - grads[name][idx]) < 1e-7 * max(1.0, abs(fd)), (name, idx, fd, grads[name][idx])
+
+
+def test_scale_projection_chain_into_attention():
+    """The projections feed the attention's per-query beta, gamma: the derivative of sum(O * dO) with respect to a
+    projection weight, by finite differences through both oracles, equals the projection backward applied to the
+    attention backward's d beta, d gamma."""
+    rng = np.random.default_rng(4)
+    B, H, N, E, D = 1, 2, 6, 5, 4
+    X = rng.standard_normal((B, N, E))
+    Wb, Wg = 0.5 * rng.standard_normal((H, E)), 0.5 * rng.standard_normal((H, E))
+    Q, K, V, dO = (rng.standard_normal((B, H, N, D)) for _ in range(4))
+    s, alpha = 1.0, 1.5
+
+    def loss(Wb_, Wg_):
+        beta, gamma = oracle.scale_proj_fwd(X, Wb_, Wg_, s)
+        return float((oracle.attn_fwd(Q, K, V, alpha, beta=beta, gamma=gamma, logn_mode=1)["O"] * dO).sum())
+
+    beta, gamma = oracle.scale_proj_fwd(X, Wb, Wg, s)
+    g = oracle.attn_bwd(Q, K, V, dO, alpha, beta=beta, gamma=gamma, logn_mode=1)
+    grads = oracle.scale_proj_bwd(X, Wb, Wg, s, g["dbeta"], g["dgamma"])
+    h = 1e-6
+    for name, idx in (("dWb", (0, 1)), ("dWb", (1, 4)), ("dWg", (0, 0)), ("dWg", (1, 2))):
+        Wb2, Wg2 = Wb.copy(), Wg.copy()
+        tgt = Wb2 if name == "dWb" else Wg2
+        tgt[idx] += h
+        up = loss(Wb2, Wg2)
+        tgt[idx] -= 2 * h
+        dn = loss(Wb2, Wg2)
+        fd = (up - dn) / (2 * h)
+        assert abs(fd - grads[name][idx]) < 2e-6 * max(1.0, abs(fd)), (name, idx, fd, grads[name][idx])
