@@ -311,6 +311,44 @@ def main():
         result["other_workloads"] = extra
         result["fwd_n32768"] = extra["c4_n32768_fwd"]
 
+    if not args.no_extra and args.workload == "c3" and args.alpha is None and not args.nape:
+        # the step right before the attention: beta = softplus(X w), gamma = s tanh(X w) from the layer's token
+        # embeddings (hidden 768, the paper's model width), and its backward; bound by reading X / writing dX
+        Bp, Np, Ep, Hp = B, n, 768, H
+        rngp = np.random.Generator(np.random.Philox(key=[0, 77]))
+        xp = torch.from_numpy(rngp.standard_normal((Bp, Np, Ep)).astype(np.float32)).to(dev).to(torch.bfloat16)
+        wbp = torch.from_numpy((0.05 * rngp.standard_normal((Hp, Ep))).astype(np.float32)).to(dev)
+        wgp = torch.from_numpy((0.05 * rngp.standard_normal((Hp, Ep))).astype(np.float32)).to(dev)
+        dbp = torch.from_numpy(rngp.standard_normal((Bp, Hp, Np)).astype(np.float32)).to(dev)
+        wsp = torch.empty(64 << 20, dtype=torch.uint8, device=dev)
+        bp, gp = binding.scale_proj_fwd(xp, wbp, wgp, 1.0)
+        for _ in range(3):
+            binding.scale_proj_fwd(xp, wbp, wgp, 1.0)
+            binding.scale_proj_bwd(xp, wbp, wgp, bp, gp, dbp, dbp, 1.0, workspace=wsp)
+        evs = [hev.make(3) for _ in range(args.steps)]
+        torch.cuda.synchronize()
+        for e3 in evs:
+            hev.record(e3[0], stream)
+            binding.scale_proj_fwd(xp, wbp, wgp, 1.0)
+            hev.record(e3[1], stream)
+            binding.scale_proj_bwd(xp, wbp, wgp, bp, gp, dbp, dbp, 1.0, workspace=wsp)
+            hev.record(e3[2], stream)
+        torch.cuda.synchronize()
+        pf = float(np.mean([hev.elapsed_ms(e3[0], e3[1]) for e3 in evs]))
+        pb = float(np.mean([hev.elapsed_ms(e3[1], e3[2]) for e3 in evs]))
+        xbytes = Bp * Np * Ep * 2
+        obytes = Bp * Hp * Np * 4
+        result["scale_projection"] = {
+            "workload": "B=%d n=%d E=%d H=%d bf16 X, fp32 projection vectors" % (Bp, Np, Ep, Hp),
+            "fwd_ms": pf, "bwd_ms": pb,
+            # algorithmic bytes: forward reads X and writes beta, gamma; backward reads X, beta, gamma, dbeta, dgamma
+            # and writes dX
+            "fwd_hbm_frac": (xbytes + 2 * obytes) / (pf * 1e-3) / 1e9 / 8000.0,
+            "bwd_hbm_frac": (2 * xbytes + 4 * obytes) / (pb * 1e-3) / 1e9 / 8000.0,
+        }
+        del xp, wsp
+        torch.cuda.empty_cache()
+
     if not args.no_decode and args.workload == "c3":
         # decode shapes: a few new query rows against a 32768-key cache; bound by one read of K from HBM
         result["decode_nk32768"] = {}

@@ -228,6 +228,35 @@ size_t entmax_attn_noalloc_scratch_bytes(void);
  * written in practice).  The caller times the launch. */
 int entmax_attn_mfma_probe(int iters, int blocks, float* sink, void* hip_stream);
 
+/*
+ * ASEntmax scale projections (Sec. 4.1, the two equations after eq. (asentmax)): the step that produces the
+ * attention's per-query beta and gamma (scale_layout 2) from the layer's token embeddings.
+ *     beta[b,h,i]  = softplus(<x_{b,i}, w_beta,h>)          > 0
+ *     gamma[b,h,i] = gamma_scale * tanh(<x_{b,i}, w_gamma,h>)   in (-gamma_scale, gamma_scale)
+ *   X, dX: [B,N,E] contiguous, element type `dtype`, device memory, 16-byte aligned; E a multiple of 16.
+ *   Wb, Wg, dWb, dWg: [H,E] fp32 contiguous (row h = head h's projection vector), 16-byte aligned; H <= 16.
+ *   beta, gamma, dbeta, dgamma: [B,H,N] fp32 contiguous -- the layout entmax_attn_fwd / entmax_attn_bwd use.
+ *   gamma_scale: the constant the paper calls s and gives no value for; must be > 0.
+ * Forward: writes beta and gamma.  Backward: from d beta, d gamma (as entmax_attn_bwd returns them) and the
+ * forward's beta, gamma it OVERWRITES dX (the projections' contribution only: the caller adds the other paths
+ * into X), dWb and dWg.  The backward needs entmax_scale_proj_workspace_bytes(p) bytes of 256-byte aligned
+ * workspace (partial sums of dW, added in a fixed order: results are reproducible).
+ * Errors as for the attention entry points; nothing is launched when an error is returned before LAUNCH_FAILED.
+ */
+typedef struct {
+  int32_t B, H, N, E; /* batch, heads, tokens per sequence, embedding width */
+  int32_t dtype;      /* ENTMAX_ATTN_BF16 or ENTMAX_ATTN_FP32: type of X and dX */
+  float gamma_scale;  /* s in gamma = s tanh(.) */
+} entmax_scale_proj_params;
+
+int entmax_scale_proj_fwd(const entmax_scale_proj_params* p, const void* X, const float* Wb, const float* Wg, float* beta,
+                          float* gamma, void* hip_stream);
+int entmax_scale_proj_bwd(const entmax_scale_proj_params* p, const void* X, const float* Wb, const float* Wg,
+                          const float* beta, const float* gamma, const float* dbeta, const float* dgamma, void* dX,
+                          float* dWb, float* dWg, void* workspace, size_t workspace_bytes, void* hip_stream);
+/* Workspace bytes of entmax_scale_proj_bwd; 0 if the parameters are invalid. Host-only. */
+size_t entmax_scale_proj_workspace_bytes(const entmax_scale_proj_params* p);
+
 /* Scratch bytes the forward (is_bwd = 0) or backward (is_bwd != 0) needs for
  * these parameters; 0 if the parameters are invalid. Host-only, no GPU call. */
 size_t entmax_attn_workspace_bytes(const entmax_attn_params* p, int is_bwd);

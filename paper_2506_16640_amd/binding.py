@@ -66,6 +66,19 @@ _lib.entmax_attn_noalloc_scratch_bytes.restype = ctypes.c_size_t
 _lib.entmax_attn_noalloc_scratch_bytes.argtypes = []
 _lib.entmax_attn_mfma_probe.restype = ctypes.c_int
 _lib.entmax_attn_mfma_probe.argtypes = [ctypes.c_int, ctypes.c_int, _vp, _vp]
+
+
+class ProjParams(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("N", ctypes.c_int32), ("E", ctypes.c_int32),
+                ("dtype", ctypes.c_int32), ("gamma_scale", ctypes.c_float)]
+
+
+_lib.entmax_scale_proj_fwd.restype = ctypes.c_int
+_lib.entmax_scale_proj_fwd.argtypes = [ctypes.POINTER(ProjParams)] + [_vp] * 6
+_lib.entmax_scale_proj_bwd.restype = ctypes.c_int
+_lib.entmax_scale_proj_bwd.argtypes = [ctypes.POINTER(ProjParams)] + [_vp] * 11 + [ctypes.c_size_t, _vp]
+_lib.entmax_scale_proj_workspace_bytes.restype = ctypes.c_size_t
+_lib.entmax_scale_proj_workspace_bytes.argtypes = [ctypes.POINTER(ProjParams)]
 _lib.entmax_attn_strerror.restype = ctypes.c_char_p
 _lib.entmax_attn_strerror.argtypes = [ctypes.c_int]
 
@@ -289,3 +302,53 @@ def new_stats(device="cuda"):
 def stats_dict(stats):
     vals = stats.cpu().tolist()
     return {name: int(vals[i]) for name, i in STAT_NAMES.items()}
+
+
+def _proj_params(x, wb, wg, gamma_scale):
+    if x.dim() != 3 or not x.is_contiguous():
+        raise ValueError("X must be a contiguous [B,N,E] tensor")
+    if x.dtype == torch.bfloat16:
+        dt = 0
+    elif x.dtype == torch.float32:
+        dt = 1
+    else:
+        raise TypeError("X must be bfloat16 or float32")
+    B, N, E = x.shape
+    for name, w in (("Wb", wb), ("Wg", wg)):
+        if w.dtype != torch.float32 or not w.is_contiguous() or w.dim() != 2 or w.shape[1] != E or w.device != x.device:
+            raise ValueError("%s must be a contiguous float32 [H,E] tensor on X's device" % name)
+    if wb.shape != wg.shape:
+        raise ValueError("Wb and Wg must have the same shape")
+    return ProjParams(B, wb.shape[0], N, E, dt, float(gamma_scale))
+
+
+def scale_proj_fwd(x, wb, wg, gamma_scale=1.0):
+    """beta, gamma [B,H,N] fp32 = softplus(X Wb^T), gamma_scale * tanh(X Wg^T), in the attention's per-query layout."""
+    p = _proj_params(x, wb, wg, gamma_scale)
+    beta = torch.empty(p.B, p.H, p.N, dtype=torch.float32, device=x.device)
+    gamma = torch.empty_like(beta)
+    rc = _lib.entmax_scale_proj_fwd(ctypes.byref(p), _ptr(x), _ptr(wb), _ptr(wg), _ptr(beta), _ptr(gamma), _stream())
+    if rc != 0:
+        raise EntmaxAttnError(rc)
+    return beta, gamma
+
+
+def scale_proj_bwd(x, wb, wg, beta, gamma, dbeta, dgamma, gamma_scale=1.0, workspace=None):
+    """dX [B,N,E] (X's dtype), dWb, dWg [H,E] fp32 from the attention backward's d beta, d gamma."""
+    p = _proj_params(x, wb, wg, gamma_scale)
+    for name, t in (("beta", beta), ("gamma", gamma), ("dbeta", dbeta), ("dgamma", dgamma)):
+        if t.dtype != torch.float32 or not t.is_contiguous() or tuple(t.shape) != (p.B, p.H, p.N) or t.device != x.device:
+            raise ValueError("%s must be a contiguous float32 [B,H,N] tensor on X's device" % name)
+    need = int(_lib.entmax_scale_proj_workspace_bytes(ctypes.byref(p)))
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=x.device)
+    elif workspace.dtype != torch.uint8 or not workspace.is_contiguous():
+        raise ValueError("workspace must be a contiguous uint8 tensor")
+    dx = torch.empty_like(x)
+    dwb, dwg = torch.empty_like(wb), torch.empty_like(wg)
+    rc = _lib.entmax_scale_proj_bwd(ctypes.byref(p), _ptr(x), _ptr(wb), _ptr(wg), _ptr(beta), _ptr(gamma), _ptr(dbeta),
+                                    _ptr(dgamma), _ptr(dx), _ptr(dwb), _ptr(dwg), _ptr(workspace), workspace.numel(),
+                                    _stream())
+    if rc != 0:
+        raise EntmaxAttnError(rc)
+    return dx, dwb, dwg

@@ -28,7 +28,7 @@ HIPCC_FLAGS = [
 
 def translation_units():
     """(object name, source, extra flags) of every unit of the library."""
-    units = [("api", "entmax_attn.hip", [])]
+    units = [("api", "entmax_attn.hip", []), ("scale_proj", "scale_proj.hip", [])]
     for leg in ("FWD", "BWD"):
         for tname, ctype in (("bf16", "bf16_t"), ("f32", "float")):
             for d in (64, 128):

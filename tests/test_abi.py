@@ -23,9 +23,10 @@ def binding():
 def test_exports_every_declared_symbol(binding):
     text = open(HEADER).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    names = set(re.findall(r"\b(entmax_attn_[a-z_]+)\s*\(", text))
+    names = set(re.findall(r"\b(entmax_(?:attn|scale_proj)_[a-z_]+)\s*\(", text))
     assert {"entmax_attn_fwd", "entmax_attn_bwd", "entmax_attn_workspace_bytes", "entmax_attn_saved_bytes",
-            "entmax_attn_strerror", "entmax_attn_check_params"} <= names
+            "entmax_attn_strerror", "entmax_attn_check_params", "entmax_scale_proj_fwd", "entmax_scale_proj_bwd",
+            "entmax_scale_proj_workspace_bytes"} <= names
     lib = ctypes.CDLL(LIB)
     for n in names:
         assert hasattr(lib, n), n
