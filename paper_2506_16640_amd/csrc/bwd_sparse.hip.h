@@ -46,6 +46,7 @@ struct BwdSparseArgs {
   int* block_flag;     // [B*H*nqb] 1 when the block cannot take the list path (a list too long, or no lists)
   void* cells;         // sweep scratch: one CellBuf<kBwdCap> per workgroup of the list sweep's grid
   int* kcount;         // [B*H*Nk] listed entries per key = size of the key's segment (key_offsets_kernel)
+  const int* precount; // NULL, or the same counts as the forward left them in the `saved` buffer
   int* kcursor;        // [B*H*Nk] entries placed so far; after bwd_rows_kernel: the key's entries with p > 0
   int* koffs;          // [B*H*Nk] exclusive prefix sums of kcount within the head: segment starts
   int* csc_i;          // [B*H][Nq*2*kBwdCap] query row of each entry, key-major
@@ -283,8 +284,10 @@ static __global__ __launch_bounds__(kOffsThreads) void key_offsets_kernel(BwdSpa
     if (any) return;  // the tiled kernels own this head
   }
   int* gcount = A.kcount + (long long)bh * Nk;
-  int* cnt = use_lds ? offs_lds + 2 * kOffsThreads : gcount;
-  for (int j = tid; j < Nk; j += kOffsThreads) cnt[j] = 0;
+  const int* cnt = A.precount ? A.precount + (long long)bh * Nk : (use_lds ? offs_lds + 2 * kOffsThreads : gcount);
+  int* wcnt = use_lds ? offs_lds + 2 * kOffsThreads : gcount;  // counted here unless the forward did
+  if (!A.precount) {
+  for (int j = tid; j < Nk; j += kOffsThreads) wcnt[j] = 0;
   __syncthreads();
   // a lane of a row group per step: the 64 lanes of a slot are one 512-byte run of the list
   for (int hr = tid; hr < A.nqb * kThreads; hr += kOffsThreads) {
@@ -295,10 +298,11 @@ static __global__ __launch_bounds__(kOffsThreads) void key_offsets_kernel(BwdSpa
     const uint2* src = A.list + list_entry<kBwdCap>(bh, A.nqb, qb, wave, lane);
     for (int e = 0; e < n; ++e) {
       const unsigned key = src[e * kListStride].x;
-      if (key < (unsigned)Nk) atomicAdd(&cnt[key], 1);
+      if (key < (unsigned)Nk) atomicAdd(&wcnt[key], 1);
     }
   }
   __syncthreads();
+  }
   const int per = (Nk + kOffsThreads - 1) / kOffsThreads;
   const int beg = tid * per, end = min(Nk, beg + per);
   int s = 0, nl = 0;

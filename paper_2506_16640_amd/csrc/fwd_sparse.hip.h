@@ -49,6 +49,8 @@ struct FwdSparseArgs {
   uint2* list;      // NULL, or [B*H*nqb*4 waves][kBwdCap][64 lanes]: the rows' supports for the backward
   int* slcnt;       // with list: [B*H*Nq][2] support entries per half row
   int* bwd_flag;    // with list: [B*H*nqb] 1: the backward cannot take its list path for this block
+  int* kcount;      // with list: [B*H*Nk] support entries naming each key (zeroed by the list kernel, counted by
+                    // the finish kernel): the sizes of the backward's key-major segments
   void* cells;      // sweep scratch: one CellBuf<kCandCap> per workgroup of the list sweep's grid
   int* lcnt;        // [B*H*Nq][2] list lengths
   float2* bounds;   // [B*H*Nq] (tau_lb, right end of the bracket)
@@ -339,6 +341,13 @@ template <typename T, int D, int AM, bool BIAS>
 __global__ __launch_bounds__(kThreads, (ListCfg<T, D>::kOcc)) void fwd_lists_kernel(FwdSparseArgs A) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const PairItem it = pair_item(A.nqb);
+  if (A.kcount) {
+    // this workgroup's share of its head's per-key counters starts at zero for the finish kernel
+    const int npair = (A.nqb + 1) >> 1, pp = A.nqb - 1 - it.first;
+    const int chunk = (A.g.Nk + npair - 1) / npair;
+    int* dst = A.kcount + (long long)it.bh * A.g.Nk;
+    for (int j = pp * chunk + (int)threadIdx.x; j < min(A.g.Nk, (pp + 1) * chunk); j += kThreads) dst[j] = 0;
+  }
   for (int part = 0; part < 2; ++part) {
     const int blk = part ? it.second : it.first;
     if (blk < 0) break;
@@ -500,7 +509,10 @@ __global__ __launch_bounds__(kThreads) void fwd_finish_kernel(FwdSparseArgs A) {
       unsigned j_oth = (unsigned)__shfl_xor((int)jv[e], 32);
       if (p_own > 0.f) {
         ++n_support;
-        if (suplist && scnt < kBwdCap) suplist[scnt * kListStride] = make_uint2(jv[e], __float_as_uint(dvv[e]));
+        if (suplist && scnt < kBwdCap) {
+          suplist[scnt * kListStride] = make_uint2(jv[e], __float_as_uint(dvv[e]));
+          atomicAdd(&A.kcount[(long long)rl.bh * g.Nk + jv[e]], 1);
+        }
         ++scnt;
       }
 #pragma unroll
@@ -526,7 +538,10 @@ __global__ __launch_bounds__(kThreads) void fwd_finish_kernel(FwdSparseArgs A) {
         unsigned j_oth = (unsigned)__shfl_xor((int)en.x, 32);
         if (p_own > 0.f) {
           ++n_support;
-          if (suplist && scnt < kBwdCap) suplist[scnt * kListStride] = en;
+          if (suplist && scnt < kBwdCap) {
+            suplist[scnt * kListStride] = en;
+            atomicAdd(&A.kcount[(long long)rl.bh * g.Nk + en.x], 1);
+          }
           ++scnt;
         }
 #pragma unroll

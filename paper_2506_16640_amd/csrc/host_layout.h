@@ -25,7 +25,7 @@ struct Layout {
   // workspace offsets
   size_t off_vt, off_cand, off_flcnt, off_bounds, off_flags, off_fcells, off_kt, off_qt, off_dot, off_mu, off_crow, off_dscale, off_mask, off_jlist, off_lcnt,
       off_kcount, off_koffs, off_kcursor, off_csc_i, off_csc_pw, off_hflag, off_longkeys, off_bcells, off_fknorm, off_bknorm, sv_list, sv_lcnt,
-      sv_flags, sv_knorm, total_saved, total_fwd, total_bwd;
+      sv_flags, sv_knorm, sv_kcount, total_saved, total_fwd, total_bwd;
   size_t off_dec_cmax;  // decode kernels: score rows at offset 0, then the chunk maxima
   int dec_nks, dec_nchunks, dec_chunk;
   long long csc_cap;    // entries of the key-major arrays per head
@@ -96,13 +96,15 @@ inline Layout make_layout(const entmax_attn_params* p) {
   L.off_fknorm = L.off_fcells + align_up(list_groups * cell_bytes_per_workgroup(kCandCap));
   L.total_fwd = L.off_fknorm + align_up(bh * sizeof(float));  // the heads' largest key norms (distance bias only)
   // the `saved` buffer: the rows' support lists (kBwdCap slots per lane of every 128-row block, slot-major per
-  // 32-row group), their lengths, one flag per block for the backward, and the heads' key norms
+  // 32-row group), their lengths, one flag per block for the backward, the heads' key norms, and the number of
+  // support entries that name each key
   const size_t list_bytes = align_up(bh * (size_t)L.nqb * kThreads * kBwdCap * 8);
   L.sv_list = 0;
   L.sv_lcnt = list_bytes;
   L.sv_flags = L.sv_lcnt + align_up(bh * (size_t)p->Nq * 2 * sizeof(int));
   L.sv_knorm = L.sv_flags + align_up(bh * (size_t)L.nqb * sizeof(int));
-  L.total_saved = L.sv_knorm + align_up(bh * sizeof(float));  // the heads' largest key norms (distance bias only)
+  L.sv_kcount = L.sv_knorm + align_up(bh * sizeof(float));  // (the heads' largest key norms: distance bias only)
+  L.total_saved = L.sv_kcount + align_up(bh * (size_t)p->Nk * sizeof(int));  // support entries per key
   // the decode kernels' score rows take the place of everything above
   L.dec_nks = L.dec_nchunks = L.dec_chunk = 0;
   L.off_dec_cmax = 0;

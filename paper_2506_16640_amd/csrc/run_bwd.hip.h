@@ -43,7 +43,7 @@ bool launch_bwd_rows(const BwdSparseArgs& a, int nblocks, hipStream_t st, void* 
   {
     // per-key counters in LDS when a head's keys fit beside the scan arrays
     const size_t scan_bytes = 2 * (size_t)kOffsThreads * sizeof(int);
-    const bool use_lds = scan_bytes + (size_t)a.g.Nk * sizeof(int) <= 150 * 1024;
+    const bool use_lds = !a.precount && scan_bytes + (size_t)a.g.Nk * sizeof(int) <= 150 * 1024;
     const size_t smem = scan_bytes + (use_lds ? (size_t)a.g.Nk * sizeof(int) : 0);
     if (!ensure_dynamic_lds<key_offsets_kernel>(smem)) return false;
     hipLaunchKernelGGL(key_offsets_kernel, dim3((unsigned)(a.g.B * a.g.H)), dim3(kOffsThreads), smem, st, a,
@@ -111,6 +111,7 @@ int run_bwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
       sa.cells = ws + L.off_bcells;
       sa.kcursor = reinterpret_cast<int*>(ws + L.off_kcursor);
       sa.kcount = reinterpret_cast<int*>(ws + L.off_kcount);
+      sa.precount = saved ? reinterpret_cast<const int*>(saved + L.sv_kcount) : nullptr;
       sa.koffs = reinterpret_cast<int*>(ws + L.off_koffs);
       sa.csc_i = reinterpret_cast<int*>(ws + L.off_csc_i);
       sa.csc_pw = reinterpret_cast<float2*>(ws + L.off_csc_pw);

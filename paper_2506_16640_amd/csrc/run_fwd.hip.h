@@ -131,6 +131,7 @@ int run_fwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
     sa.list = saved ? reinterpret_cast<uint2*>(saved + L.sv_list) : nullptr;
     sa.slcnt = saved ? reinterpret_cast<int*>(saved + L.sv_lcnt) : nullptr;
     sa.bwd_flag = saved ? reinterpret_cast<int*>(saved + L.sv_flags) : nullptr;
+    sa.kcount = saved ? reinterpret_cast<int*>(saved + L.sv_kcount) : nullptr;
     sa.dense_flag = dense_flag;
     sa.stats = reinterpret_cast<unsigned long long*>(stats);
     sa.nqb = L.nqb;
