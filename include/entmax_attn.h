@@ -189,8 +189,8 @@ int entmax_attn_fwd(const entmax_attn_params* p, const void* Q, const void* K, c
  *        to the summation order inside a row.
  *   saved_bytes: size of `saved`, checked as in the forward.
  *   workspace: at least entmax_attn_workspace_bytes(p, 1) bytes, 256-byte aligned.
- * `path` selects as in the forward: 0 = support lists per row and per key for heads whose rows
- * have few non-zero probabilities, tiled kernels for the other heads; 1 = tiled kernels only.
+ * `path` selects as in the forward: 0 = support lists per row and per key for the 128-row query blocks
+ * whose rows have few non-zero probabilities, tiled kernels for the other blocks; 1 = tiled kernels only.
  * No floating-point atomics touch the outputs.  The tiled path is bitwise reproducible; the
  * list path sums each key's entries in query order whenever a key has at most 64 of them.
  */

@@ -36,8 +36,15 @@ struct BwdArgs {
   float* dscale;    // [B*H*Nq] gradient with respect to scale_i
   uint32_t* mask;   // [B*H][nqg][mask_words] bit jb of row ig: tile (ig, jb) holds some p > 0
   unsigned long long* stats;
-  const int* head_flag;  // NULL: every head; else [B*H], only heads whose flag is set
+  const int* head_flag;  // NULL: every head, whole; else [B*H]: 0 skip the head, 1 only its flagged query blocks,
+                         // 2 the whole head
+  const int* block_flag; // with head_flag: [B*H*nqb] the query blocks the list path left over
   int nqb, nkb, nqg, mask_words;
+  // whether query block qb of head bh is this path's (call only for heads whose flag is not 0)
+  __device__ __forceinline__ bool block_is_ours(int bh, int qb) const {
+    if (!head_flag) return true;
+    return __builtin_amdgcn_readfirstlane(head_flag[bh]) == 2 || __builtin_amdgcn_readfirstlane(block_flag[bh * nqb + qb]) != 0;
+  }
 };
 
 // --------------------------------------------------------------- tile mask
@@ -58,6 +65,15 @@ __device__ __forceinline__ void bwd_mask_block(const BwdArgs& A, int bh_, int bl
   C q;
   q.init(g, A.Q, bh_, blk_);
   if (A.head_flag && __builtin_amdgcn_readfirstlane(A.head_flag[q.bh]) == 0) return;
+  if (!A.block_is_ours(q.bh, q.qb)) {
+    // the list path owns this block: none of its tiles is the tiled kernels' business
+    const int ig = q.q0 >> 5;
+    if (ig < A.nqg) {
+      uint32_t* dst = A.mask + ((long long)q.bh * A.nqg + ig) * A.mask_words;
+      for (int w = q.lane; w < A.mask_words; w += 64) dst[w] = 0u;
+    }
+    return;
+  }
   q.init_window(g);
   for (int w = q.tid; w < kWaves * A.mask_words; w += kThreads) wm.words[w] = 0u;
   const float tau = q.valid ? A.tau[(long long)q.bh * g.Nq + q.i] : 0.f;
@@ -140,6 +156,7 @@ __device__ __forceinline__ void bwd_dq_block(const BwdArgs& A, int bh_, int blk_
   C q;
   q.init(g, A.Q, bh_, blk_);
   if (A.head_flag && __builtin_amdgcn_readfirstlane(A.head_flag[q.bh]) == 0) return;
+  if (!A.block_is_ours(q.bh, q.qb)) return;  // dQ and the row scalars of this block come from the list path
   const float r = 1.0f / (g.alpha - 1.0f);
   const long long row_idx = (long long)q.bh * g.Nq + q.i;
   const float tau = q.valid ? A.tau[row_idx] : 0.f;

@@ -18,14 +18,17 @@
 //                      place a returning atomic on the key's cursor hands out;
 //   bwd_keys_kernel    eight lanes per key (one wave per key for long segments): dV_j and dK_j as
 //                      sums over the key's entries, in query order.
-// A head in which some half row holds more than kBwdCap support entries is
-// flagged and left, as a whole, to the tiled kernels of bwd.hip.h.
+// A 128-row query block in which some half row holds more than kBwdCap support entries is flagged and
+// left to the tiled kernels of bwd.hip.h, which then run on the flagged blocks of that head only: dQ and the
+// row scalars of a block come from one path or the other, and dK, dV of such a head are the tiled kernels'
+// sums over the flagged blocks plus the key kernel's sums over the listed entries of the others.
 #pragma once
 #include "bwd.hip.h"
 #include "fwd_sparse.hip.h"
 
 namespace entmax {
 
+constexpr int kHeadMixed = 1, kHeadTiled = 2;  // values of a head's flag, see BwdSparseArgs::head_flag
 constexpr int kSortedKeyEntries = 8;        // a key with at most this many entries is summed by one lane pair
 
 struct BwdSparseArgs {
@@ -51,8 +54,9 @@ struct BwdSparseArgs {
   int* koffs;          // [B*H*Nk] exclusive prefix sums of kcount within the head: segment starts
   int* csc_i;          // [B*H][Nq*2*kBwdCap] query row of each entry, key-major
   float2* csc_pw;      // same order: (p, c dS)
-  int* head_flag;      // [2*B*H], written by key_offsets_kernel: entry bh: 1 when the head is left to the tiled
-                       // kernels; entry B*H + bh: number of the head's keys on the long-segment list
+  int* head_flag;      // [2*B*H], written by key_offsets_kernel: entry bh: 0 no block of the head needs the tiled
+                       // kernels, 1 its flagged blocks do (kHeadMixed), 2 the whole head does (kHeadTiled);
+                       // entry B*H + bh: number of the head's keys on the long-segment list
   int* long_keys;      // [B*H][Nk] per head: its keys whose segment holds more than kSortedKeyEntries entries
   float* dbeta;        // per-head scale gradients, reduced by extra workgroups of the keys launch
   float* dgamma;       //   (scale_heads = 0: not here)
@@ -121,7 +125,7 @@ __global__ __launch_bounds__(kThreads, D == 64 ? 2 : 1) void bwd_rows_kernel(Bwd
   const float w_out = (g.slopes && g.bias_mode == 1) ? bias_w<D>(g, rl.h, c, a) : 0.f;
   const int pos = rl.i + (g.Nk - g.Nq);
   // every load that does not depend on another is issued before the first wait (the head's flags included)
-  const int head_dense = A.head_flag[rl.bh];
+  const int head_dense = (A.head_flag[rl.bh] == kHeadTiled || A.block_flag[rl.bh * A.nqb + rl.qb] != 0) ? 1 : 0;
   const float tau_raw = A.tau[row_idx];
   const int cnt_raw = A.lcnt[row_idx * 2 + rl.hh];
   const float tau = live ? tau_raw : 0.f;
@@ -146,7 +150,7 @@ __global__ __launch_bounds__(kThreads, D == 64 ? 2 : 1) void bwd_rows_kernel(Bwd
   uint2 early[kEarly];
 #pragma unroll
   for (int e = 0; e < kEarly; ++e) early[e] = rdlist[e * kListStride];
-  if (head_dense != 0) return;  // the tiled kernels own this head
+  if (head_dense != 0) return;  // the tiled kernels own this block
 
   auto finish = [&](auto ne_tag) {
     constexpr int NE = decltype(ne_tag)::value;
@@ -274,14 +278,21 @@ static __global__ __launch_bounds__(kOffsThreads) void key_offsets_kernel(BwdSpa
   const Geom& g = A.g;
   const int bh = blockIdx.x, tid = threadIdx.x, Nk = g.Nk;
   {
-    int any = 0;
-    for (int k = tid; k < A.nqb; k += kOffsThreads) any |= A.block_flag[bh * A.nqb + k] != 0 ? 1 : 0;
-    any = __syncthreads_or(any);
+    int flagged = 0, unflagged = 0;
+    for (int k = tid; k < A.nqb; k += kOffsThreads) {
+      if (A.block_flag[bh * A.nqb + k] != 0)
+        ++flagged;
+      else
+        ++unflagged;
+    }
+    const int any = __syncthreads_or(flagged);
+    const int all = __syncthreads_and(unflagged == 0);
+    const int nflag = !any ? 0 : (all ? kHeadTiled : kHeadMixed);
     if (tid == 0) {
-      A.head_flag[bh] = any ? 1 : 0;
+      A.head_flag[bh] = nflag;          // 0, kHeadMixed, or kHeadTiled when every block is flagged
       A.head_flag[g.B * g.H + bh] = 0;  // no long keys yet
     }
-    if (any) return;  // the tiled kernels own this head
+    if (nflag == kHeadTiled) return;  // the tiled kernels own this head
   }
   int* gcount = A.kcount + (long long)bh * Nk;
   const int* cnt = A.precount ? A.precount + (long long)bh * Nk : (use_lds ? offs_lds + 2 * kOffsThreads : gcount);
@@ -293,7 +304,7 @@ static __global__ __launch_bounds__(kOffsThreads) void key_offsets_kernel(BwdSpa
   for (int hr = tid; hr < A.nqb * kThreads; hr += kOffsThreads) {
     const int qb = hr / kThreads, wave = (hr % kThreads) >> 6, lane = hr & 63;
     const int i = qb * kBlockRows + wave * 32 + (lane & 31), hh = lane >> 5;
-    if (i >= g.Nq) continue;
+    if (i >= g.Nq || A.block_flag[bh * A.nqb + qb] != 0) continue;  // (a flagged block has no lists)
     const int n = min(A.lcnt[((long long)bh * g.Nq + i) * 2 + hh], kBwdCap);
     const uint2* src = A.list + list_entry<kBwdCap>(bh, A.nqb, qb, wave, lane);
     for (int e = 0; e < n; ++e) {
@@ -326,7 +337,7 @@ static __global__ __launch_bounds__(kOffsThreads) void key_offsets_kernel(BwdSpa
   // The key-major arrays hold kBwdCap entries per half row and head, and every list holds at most that many:
   // the segments fit.  (Checked all the same: a head that would not fit is left to the tiled kernels.)
   if (part[kOffsThreads - 1] > g.Nq * 2 * kBwdCap) {
-    if (tid == 0) A.head_flag[bh] = 1;
+    if (tid == 0) A.head_flag[bh] = kHeadTiled;
     return;
   }
   if (tid == kOffsThreads - 1) A.head_flag[g.B * g.H + bh] = partl[tid];
@@ -377,7 +388,8 @@ __global__ __launch_bounds__(kThreads) void bwd_keys_kernel(BwdSparseArgs A) {
   bool on = key < nkeys;
   const int bh = on ? (int)(key / g.Nk) : 0;
   const int j = on ? (int)(key % g.Nk) : 0;
-  on = on && A.head_flag[bh] == 0;
+  const int hflag = on ? A.head_flag[bh] : 0;
+  on = on && hflag != kHeadTiled;
   const int b = bh / g.H, h = bh % g.H;
   const int seg = on ? A.kcount[key] : 0;            // size of the key's segment
   int n = on ? min(A.kcursor[key], seg) : 0;         // entries with p > 0 placed in it
@@ -426,6 +438,16 @@ __global__ __launch_bounds__(kThreads) void bwd_keys_kernel(BwdSparseArgs A) {
   }
   if (on) {
     const long long o = (long long)b * g.kv_sb + (long long)h * g.kv_sh + (long long)j * g.kv_sn + k * DL;
+    if (hflag == kHeadMixed) {  // the tiled kernels wrote the flagged blocks' share: add it
+      float ev[DL], ek[DL];
+      load_row_f32<T>(reinterpret_cast<const T*>(A.dV) + o, DL, ev);
+      load_row_f32<T>(reinterpret_cast<const T*>(A.dK) + o, DL, ek);
+#pragma unroll
+      for (int t = 0; t < DL; ++t) {
+        dv[t] += ev[t];
+        dk[t] += ek[t];
+      }
+    }
     store_row<T>(reinterpret_cast<T*>(A.dV) + o, DL, dv);
     store_row<T>(reinterpret_cast<T*>(A.dK) + o, DL, dk);
   }
@@ -512,8 +534,13 @@ __device__ __forceinline__ void bwd_long_keys_part(const BwdSparseArgs& A, int v
     }
   }
   const long long o = (long long)b * g.kv_sb + (long long)h * g.kv_sh + (long long)j * g.kv_sn;
+  const bool mixed = __builtin_amdgcn_readfirstlane(A.head_flag[bh]) == kHeadMixed;
 #pragma unroll
   for (int t = 0; t < PER; ++t) {
+    if (mixed) {  // the tiled kernels wrote the flagged blocks' share: add it
+      av[t] += Elem<T>::load_one(A.dV, o + lane + 64 * t);
+      ak[t] += Elem<T>::load_one(A.dK, o + lane + 64 * t);
+    }
     Elem<T>::store(A.dV, o + lane + 64 * t, av[t]);
     Elem<T>::store(A.dK, o + lane + 64 * t, ak[t]);
   }

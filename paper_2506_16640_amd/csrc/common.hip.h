@@ -107,6 +107,9 @@ struct Elem<bf16_t> {
   static __device__ __forceinline__ void store(void* base, long long idx, float v) {
     reinterpret_cast<__bf16*>(base)[idx] = (__bf16)v;
   }
+  static __device__ __forceinline__ float load_one(const void* base, long long idx) {
+    return __uint_as_float((uint32_t)reinterpret_cast<const uint16_t*>(base)[idx] << 16);
+  }
 };
 
 template <>
@@ -156,6 +159,9 @@ struct Elem<float> {
   }
   static __device__ __forceinline__ void store(void* base, long long idx, float v) {
     reinterpret_cast<float*>(base)[idx] = v;
+  }
+  static __device__ __forceinline__ float load_one(const void* base, long long idx) {
+    return reinterpret_cast<const float*>(base)[idx];
   }
 };
 

@@ -458,7 +458,7 @@ __global__ __launch_bounds__(kThreads) void fwd_finish_kernel(FwdSparseArgs A) {
   uint2 early[kEarly];
 #pragma unroll
   for (int e = 0; e < kEarly; ++e) early[e] = mylist[e * kListStride];
-  if (block_dense != 0) {  // the tiled kernel owns this block (and the backward's tiled kernels its head)
+  if (block_dense != 0) {  // the tiled kernel owns this block, and so do the backward's tiled kernels
     if (A.list && threadIdx.x == 0) A.bwd_flag[rl.bh * A.nqb + rl.qb] = 1;
     return;
   }
@@ -571,7 +571,7 @@ __global__ __launch_bounds__(kThreads) void fwd_finish_kernel(FwdSparseArgs A) {
     finish(std::integral_constant<int, 8>());
 
   if (A.list) {
-    // a support longer than the backward's lists hold sends the block's head to the backward's tiled kernels
+    // a support longer than the backward's lists hold sends the block to the backward's tiled kernels
     const int any_long = __syncthreads_or(scnt > kBwdCap ? 1 : 0);
     if (threadIdx.x == 0) A.bwd_flag[rl.bh * A.nqb + rl.qb] = any_long ? 1 : 0;
   }

@@ -160,6 +160,7 @@ int run_bwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
     a.mask = reinterpret_cast<uint32_t*>(ws + L.off_mask);
     a.stats = reinterpret_cast<unsigned long long*>(stats);
     a.head_flag = hf;
+    a.block_flag = lists ? sa.block_flag : nullptr;
     a.nqb = L.nqb;
     a.nkb = L.nkb;
     a.nqg = L.nqg;

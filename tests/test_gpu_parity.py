@@ -203,3 +203,22 @@ def test_bitwise_reproducible():
     # every key has fewer than 64 entries here, so the list path sums in a fixed order too
     for name in ("O", "tau", "dQ", "dK", "dV", "dbeta", "dgamma"):
         assert np.array_equal(a[name], b[name]), name
+
+
+@pytest.mark.parametrize("alpha,dtype", [(1.5, "bf16"), (1.25, "bf16"), (1.5, "fp32")])
+def test_backward_splits_a_head_between_the_paths(alpha, dtype, forward_path):
+    """One head whose early query blocks have short supports and whose late blocks have long ones (a scale that
+    shrinks along the sequence): the list kernels take the former, the tiled kernels the latter, and dK, dV are
+    the sum of both paths' contributions."""
+    n = 1024
+    data = _case(1, 1, n, n, 64, dtype, "query", seed=21)
+    ramp = np.linspace(3.0, 0.05, n, dtype=np.float32)
+    data["beta"] = (data["beta"] * 0 + ramp[None, None, :]).astype(np.float32)
+    data["gamma"] = (data["gamma"] * 0 + 1.0).astype(np.float32)
+    data["delta"] = 0.0
+    g = gpu_run(data, alpha, dtype, stats=True)
+    r = oracle_run(data, alpha)
+    print(alpha, dtype, compare(g, r, label=f"split head a{alpha} {dtype}"), {k: v for k, v in g["stats"].items() if v})
+    if forward_path == 0:
+        st = g["stats"]
+        assert st["bwd_support"] > 0 and st["bwd_dq_tiles"] > 0, st  # both paths worked on this one head
