@@ -129,7 +129,8 @@ enum {
                                      decoding shape: the score rows, one pass over K */
   ENTMAX_FWD_PHASE_FINISH = 2,    /* threshold and output from the candidate lists (decoding shape: from the
                                      score rows) */
-  ENTMAX_FWD_PHASE_TRANSPOSE = 3, /* V^T copy for the heads that need the tiled kernel */
+  ENTMAX_FWD_PHASE_TRANSPOSE = 3, /* path 1: V^T copy for the tiled kernel (path 0: made by extra workgroups of the
+                                     finish launch, for the heads that need it) */
   ENTMAX_FWD_PHASE_TILED = 4,     /* tiled kernel on the workgroups the list kernel left over */
   ENTMAX_FWD_NUM_PHASES = 5
 };
@@ -137,7 +138,8 @@ enum {
   ENTMAX_BWD_PHASE_LISTS = 0,      /* without `saved`: one Q K^T sweep at the saved threshold, and with alibi_slopes
                                       the heads' largest key norms before it */
   ENTMAX_BWD_PHASE_ROWS = 1,       /* per-key segment offsets; mu, dscale, dQ and the per-entry (p, dS) from the lists */
-  ENTMAX_BWD_PHASE_TRANSPOSE = 2,  /* tiled path (heads the list kernel left over): operand copies */
+  ENTMAX_BWD_PHASE_TRANSPOSE = 2,  /* path 1: operand copies for the tiled kernels (path 0: made by extra workgroups
+                                      of the row launch, for the heads that need them) */
   ENTMAX_BWD_PHASE_MASK = 3,       /* tiled path: non-zero tile map */
   ENTMAX_BWD_PHASE_DQ = 4,         /* tiled path: row scalars and dQ */
   ENTMAX_BWD_PHASE_DKV = 5,        /* tiled path: dK, dV */

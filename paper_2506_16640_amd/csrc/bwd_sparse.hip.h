@@ -63,6 +63,7 @@ struct BwdSparseArgs {
   int scale_heads;     // H for per-head scale parameters, else 0
   unsigned long long* stats;
   int nqb;
+  TransposeRide ride;  // operand copies for the tiled kernels, as extra workgroups of the row launch
 };
 
 // ------------------------------------------------------------------ rows
@@ -109,6 +110,10 @@ __global__ __launch_bounds__(kThreads, (ListCfg<T, D>::kOcc)) void bwd_lists_ker
 template <typename T, int D, int AM>
 __global__ __launch_bounds__(kThreads, D == 64 ? 2 : 1) void bwd_rows_kernel(BwdSparseArgs A) {
   const Geom& g = A.g;
+  if ((int)blockIdx.x >= g.B * g.H * A.nqb) {  // riders behind the row workgroups
+    transpose_ride<T, D>(A.ride, (int)blockIdx.x - g.B * g.H * A.nqb);
+    return;
+  }
   RowLane rl;
   rl.init(g, A.nqb);
   constexpr int DH = D / 2;

@@ -25,6 +25,7 @@
 // slot-major list layout, the collect sweep, row gather helpers.
 #pragma once
 #include "fwd.hip.h"
+#include "transpose.hip.h"
 
 namespace entmax {
 
@@ -57,6 +58,7 @@ struct FwdSparseArgs {
   int* dense_flag;  // [B*H*nqb] 1: block left to the tiled kernel
   unsigned long long* stats;
   int nqb;
+  TransposeRide ride;  // V^T copies for the tiled kernel, as extra workgroups of the finish launch
 };
 
 // A cell is a group of four consecutive accumulator registers of a lane (keys j, j+1, j+2, j+3 of
@@ -432,6 +434,10 @@ struct RowLane {
 template <typename T, int D, int AM>
 __global__ __launch_bounds__(kThreads) void fwd_finish_kernel(FwdSparseArgs A) {
   const Geom& g = A.g;
+  if ((int)blockIdx.x >= g.B * g.H * A.nqb) {  // riders behind the row workgroups
+    transpose_ride<T, D>(A.ride, (int)blockIdx.x - g.B * g.H * A.nqb);
+    return;
+  }
   RowLane rl;
   rl.init(g, A.nqb);
   // (the flag is tested further down: every load that does not depend on another is issued first)

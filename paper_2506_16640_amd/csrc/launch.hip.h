@@ -129,6 +129,23 @@ bool launch_transposes(const TransposeJobs& jobs, int njobs, int B, int H, hipSt
   return launch_ok();
 }
 
+// the same jobs as riders of another launch (see TransposeRide)
+inline TransposeRide transpose_ride_of(const TransposeJobs& jobs, int njobs, int B, int H, const int* head_flag,
+                                       const int* block_flag, int nqb) {
+  TransposeRide r{};
+  r.jobs = jobs;
+  int npad = 0;
+  for (int k = 0; k < njobs; ++k) npad = jobs.job[k].npad > npad ? jobs.job[k].npad : npad;
+  r.njobs = npad > 0 ? njobs : 0;
+  r.nx = npad / 64;
+  r.BH = B * H;
+  r.H = H;
+  r.head_flag = head_flag;
+  r.block_flag = block_flag;
+  r.nqb = nqb;
+  return r;
+}
+
 inline TransposeJob transpose_job(const void* X, long long sb, long long sh, long long sn, int N, int npad, void* Xt) {
   TransposeJob j;
   j.X = X;

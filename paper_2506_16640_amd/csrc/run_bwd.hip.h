@@ -32,7 +32,7 @@ bool launch_bwd_kernels(const BwdArgs& a, const Layout& L, int B, int H, hipStre
 
 template <typename T, int D, int AM, bool BIAS>
 bool launch_bwd_rows(const BwdSparseArgs& a, int nblocks, hipStream_t st, void* const* ev, bool from_saved) {
-  const dim3 row_grid((unsigned)(a.g.B * a.g.H * a.nqb));
+  const dim3 row_grid((unsigned)(a.g.B * a.g.H * a.nqb + a.ride.workgroups()));
   if (!from_saved) {
     // no lists from the forward: one Q K^T sweep at tau rebuilds the supports
     size_t smem = ListCfg<T, D>::kLdsBytes;
@@ -122,6 +122,13 @@ int run_bwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
       sa.dbeta = dbeta;
       sa.dgamma = dgamma;
       sa.scale_heads = p->scale_layout == 1 ? H : 0;
+      {
+        TransposeJobs jobs{};
+        jobs.job[0] = transpose_job(K, L.kv_sb, L.kv_sh, L.kv_sn, p->Nk, L.npad_k, ws + L.off_kt);
+        jobs.job[1] = transpose_job(Q, L.q_sb, L.q_sh, L.q_sn, p->Nq, L.npad_q, ws + L.off_qt);
+        jobs.job[2] = transpose_job(dO, L.q_sb, L.q_sh, L.q_sn, p->Nq, L.npad_q, ws + L.off_dot);
+        sa.ride = transpose_ride_of(jobs, 3, B, H, head_flag, nullptr, 0);
+      }
       ok = ok && launch_bwd_rows_am<T, D, BIAS>(sa, alpha_mode(p->alpha), B * H * ((L.nqb + 1) / 2), st, ev, saved != nullptr);
       if (!ok) return ENTMAX_ATTN_LAUNCH_FAILED;
     } else {
@@ -132,12 +139,12 @@ int run_bwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
     void* Kt = ws + L.off_kt;
     void* Qt = ws + L.off_qt;
     void* dOt = ws + L.off_dot;
-    {
+    if (!lists) {  // (with lists the copies rode in the row launch)
       TransposeJobs jobs{};
       jobs.job[0] = transpose_job(K, L.kv_sb, L.kv_sh, L.kv_sn, p->Nk, L.npad_k, Kt);
       jobs.job[1] = transpose_job(Q, L.q_sb, L.q_sh, L.q_sn, p->Nq, L.npad_q, Qt);
       jobs.job[2] = transpose_job(dO, L.q_sb, L.q_sh, L.q_sn, p->Nq, L.npad_q, dOt);
-      ok = ok && launch_transposes<T, D>(jobs, 3, B, H, st, hf);
+      ok = ok && launch_transposes<T, D>(jobs, 3, B, H, st);
     }
     if (!ok) return ENTMAX_ATTN_LAUNCH_FAILED;
     record(ev, ENTMAX_BWD_PHASE_TRANSPOSE + 1, st);

@@ -35,7 +35,8 @@ bool launch_fwd_sparse(const FwdSparseArgs& a, int nblocks, hipStream_t st, void
   hipLaunchKernelGGL((fwd_lists_kernel<T, D, AM, BIAS>), dim3((unsigned)nblocks), dim3(kThreads), smem, st, a);
   if (!launch_ok()) return false;
   record(ev, ENTMAX_FWD_PHASE_LISTS + 1, st);
-  hipLaunchKernelGGL((fwd_finish_kernel<T, D, AM>), dim3((unsigned)(a.g.B * a.g.H * a.nqb)), dim3(kThreads), 0, st, a);
+  hipLaunchKernelGGL((fwd_finish_kernel<T, D, AM>), dim3((unsigned)(a.g.B * a.g.H * a.nqb + a.ride.workgroups())),
+                     dim3(kThreads), 0, st, a);
   return launch_ok();
 }
 
@@ -135,6 +136,11 @@ int run_fwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
     sa.dense_flag = dense_flag;
     sa.stats = reinterpret_cast<unsigned long long*>(stats);
     sa.nqb = L.nqb;
+    {
+      TransposeJobs jobs{};
+      jobs.job[0] = transpose_job(V, L.kv_sb, L.kv_sh, L.kv_sn, p->Nk, L.npad_k, Vt);
+      sa.ride = transpose_ride_of(jobs, 1, p->B, p->H, nullptr, dense_flag, L.nqb);
+    }
     if (!launch_fwd_sparse_am<T, D, BIAS>(sa, alpha_mode(p->alpha), npairs, st, ev)) return ENTMAX_ATTN_LAUNCH_FAILED;
   } else {
     // no lists: tell the backward that every block belongs to its tiled kernels
@@ -143,11 +149,10 @@ int run_fwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
     record(ev, ENTMAX_FWD_PHASE_LISTS + 1, st);
   }
   record(ev, ENTMAX_FWD_PHASE_FINISH + 1, st);
-  {
+  if (!lists) {  // (with lists the copies rode in the finish launch)
     TransposeJobs jobs{};
     jobs.job[0] = transpose_job(V, L.kv_sb, L.kv_sh, L.kv_sn, p->Nk, L.npad_k, Vt);
-    if (!launch_transposes<T, D>(jobs, 1, p->B, p->H, st, nullptr, lists ? dense_flag : nullptr, L.nqb))
-      return ENTMAX_ATTN_LAUNCH_FAILED;
+    if (!launch_transposes<T, D>(jobs, 1, p->B, p->H, st)) return ENTMAX_ATTN_LAUNCH_FAILED;
   }
   record(ev, ENTMAX_FWD_PHASE_TRANSPOSE + 1, st);
   FwdArgs a;

@@ -21,25 +21,26 @@ struct TransposeJobs {
   TransposeJob job[3];  // blockIdx.z picks one
 };
 
-template <typename T, int D>
 // head_flag (one per head) or block_flag (nqb per head), when given, say whether any consumer needs the
 // head's copies: without a set flag the workgroup returns at once.
-__global__ __launch_bounds__(kThreads) void transpose_perm_kernel(TransposeJobs jobs, int H, const int* head_flag,
-                                                                 const int* block_flag, int nqb) {
+// bx: 64-row tile of the tensor, bh: (batch, head), bz: job.  All 256 threads of a workgroup call this together.
+template <typename T, int D>
+__device__ __forceinline__ void transpose_perm_part(const TransposeJobs& jobs, int H, const int* head_flag,
+                                                    const int* block_flag, int nqb, int bx, int bh, int bz) {
   constexpr int kPad = sizeof(T) == 2 ? 2 : 1;
   __shared__ T tile[64][D + kPad];
   const int tid = threadIdx.x;
-  const int bh = blockIdx.y, b = bh / H, h = bh % H;
+  const int b = bh / H, h = bh % H;
   if (head_flag && head_flag[bh] == 0) return;  // no consumer for this head's copy
   if (block_flag) {
     int any = 0;
     for (int k = tid; k < nqb; k += kThreads) any |= block_flag[bh * nqb + k];
     if (__syncthreads_or(any) == 0) return;
   }
-  const TransposeJob& jb = jobs.job[blockIdx.z];
+  const TransposeJob& jb = jobs.job[bz];
   const int N = jb.N, npad = jb.npad;
   const long long sn = jb.sn;
-  const int j0 = blockIdx.x * 64;
+  const int j0 = bx * 64;
   if (j0 >= npad) return;  // the grid covers the longest job
   const T* src = reinterpret_cast<const T*>(jb.X) + (long long)b * jb.sb + (long long)h * jb.sh;
   T* Xt = reinterpret_cast<T*>(jb.Xt);
@@ -58,6 +59,29 @@ __global__ __launch_bounds__(kThreads) void transpose_perm_kernel(TransposeJobs 
     int srow = (pos & ~15) + 8 * ((p & 7) >> 2) + 4 * (p >> 3) + (p & 3);
     dst[(long long)dc * npad + pos] = tile[srow][dc];
   }
+}
+
+template <typename T, int D>
+__global__ __launch_bounds__(kThreads) void transpose_perm_kernel(TransposeJobs jobs, int H, const int* head_flag,
+                                                                 const int* block_flag, int nqb) {
+  transpose_perm_part<T, D>(jobs, H, head_flag, block_flag, nqb, blockIdx.x, blockIdx.y, blockIdx.z);
+}
+
+// The same work as extra workgroups of another kernel's launch (the copies are only needed by the tiled kernels
+// that follow, and a launch of their own would cost more than the copies of the few heads that need them):
+// workgroup `idx` of the nx * BH * njobs riders.
+struct TransposeRide {
+  TransposeJobs jobs;
+  int njobs, nx, BH, H;     // nx: 64-row tiles of the longest job; njobs = 0: no riders
+  const int* head_flag;
+  const int* block_flag;
+  int nqb;
+  __host__ __device__ int workgroups() const { return njobs * nx * BH; }
+};
+template <typename T, int D>
+__device__ __forceinline__ void transpose_ride(const TransposeRide& r, int idx) {
+  const int bx = idx % r.nx, bh = (idx / r.nx) % r.BH, bz = idx / (r.nx * r.BH);
+  transpose_perm_part<T, D>(r.jobs, r.H, r.head_flag, r.block_flag, r.nqb, bx, bh, bz);
 }
 
 // O = 0, tau = 0 for problems without keys (Nk = 0), or any plain fill.
