@@ -127,17 +127,26 @@ def main():
         t["gamma"] = None if data["gamma"] is None else torch.from_numpy(data["gamma"]).to(dev)
         return data, cfg, t
 
-    def measure(name, steps, warmup, alpha=None, want_events=True, nape=False):
+    def measure(name, steps, warmup, alpha=None, want_events=True, nape=False, per_query=False):
         """Times `steps` steps of workload `name` (forward, plus backward with the forward's saved buffer where the
         workload has one) wall-clock with no events inside, then once more with the library's phase events."""
         data, cfg, t = upload(name, want_dO=bool(synth.CONFIGS[name]["bwd"]))
         B, H, n, d = cfg["B"], cfg["H"], cfg["n"], cfg["d"]
         alpha = cfg["alpha"] if alpha is None else alpha
         do_bwd = bool(cfg["bwd"])
-        kw = dict(alpha=alpha, beta=t["beta"], gamma=t["gamma"], delta=data["delta"], causal=True, logn_mode=0)
+        logn_mode = 0
+        if per_query:
+            # beta, gamma per query (what the scale projections produce) with n = keys visible to the row: the
+            # per-head values spread over the rows with a seeded +-10 % variation
+            rq = np.random.Generator(np.random.Philox(key=[0, 99]))
+            for nm in ("beta", "gamma"):
+                base = data[nm][None, :, None] * (1.0 + 0.1 * rq.uniform(-1, 1, size=(B, H, n)))
+                t[nm] = torch.from_numpy(base.astype(np.float32)).to(dev)
+            logn_mode = 1
+        kw = dict(alpha=alpha, beta=t["beta"], gamma=t["gamma"], delta=data["delta"], causal=True, logn_mode=logn_mode)
         if nape:  # Sec. 4.2: every other head carries the linear distance bias, inside the ASEntmax scale
             kw.update(alibi_slopes=torch.from_numpy(synth.nape_slopes(H)).to(dev), bias_mode=0)
-        prm = binding.make_params(t["Q"], t["K"], alpha, data["delta"], True, t["beta"], 0)
+        prm = binding.make_params(t["Q"], t["K"], alpha, data["delta"], True, t["beta"], logn_mode)
         ws = torch.empty(max(binding.workspace_bytes(prm, 0), binding.workspace_bytes(prm, 1) if do_bwd else 0),
                          dtype=torch.uint8, device=dev)
         out = torch.empty_like(t["Q"])
@@ -301,6 +310,10 @@ def main():
             extra["c5_n8192_d128_alpha%g" % a5] = summary(measure("c5", k4, 1, alpha=a5))
             torch.cuda.empty_cache()
         extra["c3d_dense_regime"] = summary(measure("c3d", k4, 1))
+        torch.cuda.empty_cache()
+        extra["c3_per_query_scale_logn_visible"] = summary(measure("c3", args.steps, args.warmup, per_query=True))
+        torch.cuda.empty_cache()
+        extra["c3_alpha1.25"] = summary(measure("c3", k4, 1, alpha=1.25))
         torch.cuda.empty_cache()
         extra["c3_nape_fwd_bwd"] = summary(measure("c3", args.steps, args.warmup, nape=True))
         torch.cuda.empty_cache()

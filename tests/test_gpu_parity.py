@@ -222,3 +222,32 @@ def test_backward_splits_a_head_between_the_paths(alpha, dtype, forward_path):
     if forward_path == 0:
         st = g["stats"]
         assert st["bwd_support"] > 0 and st["bwd_dq_tiles"] > 0, st  # both paths worked on this one head
+
+
+def test_randomised_small_configurations():
+    """Forty seeded draws over the whole parameter space of the entry points (shapes with ragged tails, both
+    element types and head dimensions, every alpha path, scale layouts, log-n modes, causal or not, distance bias
+    in both placements): each against the oracle, with the bars of this file."""
+    rng = np.random.Generator(np.random.Philox(key=[2024, 5]))
+    for case in range(40):
+        nq = int(rng.integers(1, 400))
+        nk = nq if rng.random() < 0.5 else int(rng.integers(1, 400))
+        d = int(rng.choice([64, 128]))
+        dtype = str(rng.choice(["bf16", "fp32"]))
+        alpha = float(rng.choice([1.5, 2.0, 1.25, 1.1, 1.4, 1.75]))
+        scale = str(rng.choice(["none", "head", "query", "dense"]))
+        causal = bool(rng.random() < 0.7)
+        logn_mode = int(rng.integers(0, 2))
+        H = int(rng.integers(1, 4))
+        B = int(rng.integers(1, 3))
+        data = _case(B, H, nq, nk, d, dtype, scale, seed=100 + case)
+        slopes, bias_mode = None, 0
+        if rng.random() < 0.4:
+            slopes = (2.0 ** -rng.integers(0, 8, size=H)).astype(np.float32) * (rng.random(H) < 0.7)
+            slopes = slopes.astype(np.float32)
+            bias_mode = int(rng.integers(0, 2))
+        label = f"case {case}: B{B} H{H} nq{nq} nk{nk} d{d} {dtype} a{alpha} {scale} causal{causal} logn{logn_mode} bias{bias_mode} {slopes}"
+        print(label, flush=True)
+        g = gpu_run(data, alpha, dtype, causal=causal, logn_mode=logn_mode, slopes=slopes, bias_mode=bias_mode)
+        r = oracle_run(data, alpha, causal=causal, logn_mode=logn_mode, slopes=slopes, bias_mode=bias_mode)
+        compare(g, r, label=label)
