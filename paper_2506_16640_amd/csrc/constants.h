@@ -20,6 +20,8 @@ constexpr size_t cell_bytes_per_workgroup(int cap) { return (size_t)kThreads * c
 // when the keys are at least kDecodeLongRatio times as many.
 constexpr int kDecodeRows = 8;
 constexpr int kDecodeRowsLong = 64;
+constexpr int kDecodeMfmaRows = 16;  // from this many rows on the scores come from the matrix cores (measured: 9 rows
+                                     // 91 us with per-row dot products against 114 us, 16 rows 131 against 121)
 constexpr int kDecodeLongRatio = 64;
 constexpr int kDecodeChunk = 512;  // keys per workgroup of the score kernel (64 to 128 KB of K); 256 to 2048 measured alike
 inline bool decode_shape(int Nq, int Nk) {

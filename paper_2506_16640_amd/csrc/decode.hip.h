@@ -150,6 +150,94 @@ __global__ __launch_bounds__(kThreads) void decode_scores_kernel(DecodeArgs A) {
   }
 }
 
+// The same scores for 9 to 64 query rows, where the per-row dot products of the kernel above (about 5 us per
+// row at Nk = 32768 and 48 heads) outweigh the read of K: S = Q K_chunk^T on the matrix cores, one or two
+// 32-query blocks against 32-key blocks whose fragments come straight from global memory (every K row is read
+// once by one lane pair, 16 bytes at a time along the row).  In the accumulator layout the 32 lanes of a half
+// wave hold 32 consecutive keys of one query: the score rows are written in 128-byte runs.
+template <typename T, int D>
+__global__ __launch_bounds__(kThreads) void decode_scores_mfma_kernel(DecodeArgs A) {
+  constexpr int NC = D / 16;
+  __shared__ f32x4_t rowinfo[64];  // per query row: coefficient, bias per unit distance, limit, position (as bits)
+  __shared__ float wmax[kWaves][64];
+  const Geom& g = A.g;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 31, hh = lane >> 5;
+  const int bh = blockIdx.y, b = bh / g.H, h = bh % g.H;
+  const int jc0 = blockIdx.x * A.chunk, jend = min(jc0 + A.chunk, g.Nk);
+  const T* Qh = reinterpret_cast<const T*>(A.Q) + (long long)b * g.q_sb + (long long)h * g.q_sh;
+  const T* Kh = reinterpret_cast<const T*>(A.K) + (long long)b * g.kv_sb + (long long)h * g.kv_sh;
+  const int nqblk = (g.Nq + 31) >> 5;  // 1 or 2
+  if (tid < 64) {
+    const bool valid = tid < g.Nq;
+    const int lim = valid ? row_limit(g, tid) : 0;
+    const float cf = valid ? (g.alpha - 1.0f) * row_scale(g, b, h, tid, lim, nullptr, nullptr, nullptr) * (1.0f / sqrtf((float)D))
+                           : 0.f;
+    rowinfo[tid] = f32x4_t{cf, valid ? fabsf(cf) * bias_w<D>(g, h, cf, fabsf(cf)) : 0.f, __int_as_float(lim),
+                           __int_as_float(tid + (g.Nk - g.Nq))};
+  }
+  // query fragments (A operand: row = query, 8 features per lane half)
+  Frag<T> qf[2][NC];
+#pragma unroll
+  for (int qb = 0; qb < 2; ++qb) {
+    const int row = qb * 32 + li;
+#pragma unroll
+    for (int cc = 0; cc < NC; ++cc)
+      qf[qb][cc] = row < g.Nq ? Elem<T>::load(Qh + (long long)row * g.q_sn + 16 * cc + 8 * hh) : Elem<T>::zero();
+  }
+  __syncthreads();
+  float rmax[2][16];
+#pragma unroll
+  for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) rmax[qb][e] = -kInf;
+  const int per_wave = A.chunk / kWaves;  // a multiple of 32 (the chunk is a multiple of 256)
+  for (int j0 = jc0 + wave * per_wave; j0 < min(jc0 + (wave + 1) * per_wave, jend); j0 += 32) {
+    const int key = j0 + li;  // this lane's key (B operand column, accumulator column)
+    const bool kvalid = key < g.Nk;
+    const T* krow = Kh + (long long)min(key, g.Nk - 1) * g.kv_sn;
+    Frag<T> kf[NC];
+#pragma unroll
+    for (int cc = 0; cc < NC; ++cc) kf[cc] = Elem<T>::load(krow + 16 * cc + 8 * hh);
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+      if (qb >= nqblk) break;
+      f32x16_t acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int cc = 0; cc < NC; ++cc) acc = Elem<T>::mma(qf[qb][cc], kf[cc], acc);
+      // acc[4 q + r] of lane l: query qb*32 + 8 q + 4 (l/32) + r, key j0 + l%32
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int i = qb * 32 + 8 * (e >> 2) + 4 * hh + (e & 3);
+        const f32x4_t ri = rowinfo[i];
+        const int lim = __float_as_int(ri[2]), pos = __float_as_int(ri[3]);
+        const float zj = fmaf(ri[1], (float)bias_dist(pos, key), acc[e] * ri[0]);
+        if (kvalid && key < lim) {  // (lim = 0 for rows beyond Nq)
+          A.scores[((long long)bh * g.Nq + i) * A.nks + key] = zj;
+          rmax[qb][e] = fmaxf(rmax[qb][e], zj);
+        }
+      }
+    }
+  }
+  // a query's maximum over the keys this wave saw: across the 32 lanes of its half wave
+#pragma unroll
+  for (int qb = 0; qb < 2; ++qb) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      float v = rmax[qb][e];
+#pragma unroll
+      for (int sft = 16; sft >= 1; sft >>= 1) v = fmaxf(v, __shfl_xor(v, sft));
+      if (li == 0) wmax[wave][qb * 32 + 8 * (e >> 2) + 4 * hh + (e & 3)] = v;
+    }
+  }
+  __syncthreads();
+  if (tid < g.Nq) {
+    float mx = wmax[0][tid];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) mx = fmaxf(mx, wmax[w][tid]);
+    A.cmax[((long long)bh * g.Nq + tid) * A.nchunks + blockIdx.x] = mx;
+  }
+}
+
 // Sum of two values over the workgroup; every thread gets the totals.  `buf` holds 2 * 2 * 16
 // floats: calls alternate between its halves (parity), so one barrier per call is enough.
 __device__ __forceinline__ float2 decode_block_sum(float a, float b, float* buf, int parity) {

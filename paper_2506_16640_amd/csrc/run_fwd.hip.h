@@ -53,8 +53,11 @@ bool launch_fwd_sparse_am(const FwdSparseArgs& a, int am, int nblocks, hipStream
 template <typename T, int D>
 bool launch_decode(const DecodeArgs& a, int am, hipStream_t st, void* const* ev) {
   const Geom& g = a.g;
-  hipLaunchKernelGGL((decode_scores_kernel<T, D>), dim3((unsigned)a.nchunks, (unsigned)(g.B * g.H)),
-                     dim3(kThreads), decode_scores_lds(g.Nq, D, sizeof(T)), st, a);
+  const dim3 sgrid((unsigned)a.nchunks, (unsigned)(g.B * g.H));
+  if (g.Nq >= kDecodeMfmaRows)  // more rows than the per-row dot products are worth: matrix cores
+    hipLaunchKernelGGL((decode_scores_mfma_kernel<T, D>), sgrid, dim3(kThreads), 0, st, a);
+  else
+    hipLaunchKernelGGL((decode_scores_kernel<T, D>), sgrid, dim3(kThreads), decode_scores_lds(g.Nq, D, sizeof(T)), st, a);
   if (!launch_ok()) return false;
   record(ev, ENTMAX_FWD_PHASE_LISTS + 1, st);
   const dim3 grid((unsigned)(g.B * g.H * g.Nq)), block(kDecodeSolveThreads);

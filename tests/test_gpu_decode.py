@@ -24,7 +24,7 @@ def test_decode_forward(nq, nk, alpha):
     print(nq, nk, alpha, compare(g, r, bwd=False, label=f"decode {nq}x{nk} a{alpha}"))
 
 
-@pytest.mark.parametrize("nq,nk,decode", [(9, 600, True), (33, 2200, True), (64, 4133, True), (64, 4000, False),
+@pytest.mark.parametrize("nq,nk,decode", [(9, 600, True), (15, 1000, True), (16, 1100, True), (17, 1100, True), (33, 2200, True), (64, 4133, True), (64, 4000, False),
                                           (65, 5000, False)])
 def test_decode_more_rows_against_long_keys(nq, nk, decode):
     # up to 64 rows take the split-key kernels when the keys are at least 64 times as many; the tile counters
