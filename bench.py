@@ -101,7 +101,10 @@ def main():
     ap.add_argument("--nape", action="store_true", help="every other head with the linear distance bias (Sec. 4.2)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the other benchmark configurations (c2, c4, c5, c3d)")
-    ap.add_argument("--no-decode", action="store_true", help="skip the decode-shape (Nq = 1 and 8, Nk = 32768) measurement")
+    ap.add_argument("--no-decode", action="store_true", help="skip the decode-shape (Nk = 32768) measurements")
+    ap.add_argument("--decode-rows", default="1,8,64", help="query rows of the decode-shape measurements")
+    ap.add_argument("--projection-only", action="store_true",
+                    help="of the extra measurements run only the scale projections (for profiling them alone)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); --gpus %d is not supported"
@@ -299,7 +302,7 @@ def main():
     del main_r
     torch.cuda.empty_cache()
 
-    if not args.no_extra and args.workload == "c3" and args.alpha is None and not args.nape:
+    if not args.no_extra and not args.projection_only and args.workload == "c3" and args.alpha is None and not args.nape:
         k4 = max(3, args.steps // 4)
         extra = {}
         extra["c2_n1024_fwd"] = summary(measure("c2", args.steps, args.warmup))
@@ -365,7 +368,7 @@ def main():
     if not args.no_decode and args.workload == "c3":
         # decode shapes: a few new query rows against a 32768-key cache; bound by one read of K from HBM
         result["decode_nk32768"] = {}
-        for nq in (1, 8):
+        for nq in [int(x) for x in args.decode_rows.split(",") if x]:  # from 16 rows on the scores come from the matrix cores
             dd = synth.make_inputs(B=4, H=12, n=nq, nk=32768, d=64, dtype="bf16", scale="head", seed=0, want_dO=False)
             td = {k: torch.from_numpy(dd[k]).to(dev).to(torch.bfloat16) for k in ("Q", "K", "V")}
             bd, gd = (torch.from_numpy(dd[k]).to(dev) for k in ("beta", "gamma"))
@@ -393,7 +396,7 @@ def main():
             result["decode_nk32768"]["nq%d" % nq] = {
                 "workload": "B=4 H=12 Nq=%d Nk=32768 d=64 bf16 causal alpha=1.5 ASEntmax scale, fwd" % nq,
                 "steps": kd, "ms": (tb - ta) * 1e3 / kd, "scores_kernel_ms": scores_ms, "solve_kernel_ms": solve_ms,
-                "roofline": {"bound": "hbm", "kernel": "decode_scores", "achieved": algo_bytes / (scores_ms * 1e-3) / 1e9,
+                "roofline": {"bound": "hbm", "kernel": "decode_scores" if nq < 16 else "decode_scores_mfma", "achieved": algo_bytes / (scores_ms * 1e-3) / 1e9,
                              "peak": 8000.0, "unit": "GB/s", "frac": algo_bytes / (scores_ms * 1e-3) / 1e9 / 8000.0},
             }
             del td, wsd, kcopies

@@ -24,13 +24,19 @@ BENCH_NAMES = collections.OrderedDict([
     ("bwd_lists_kernel", "bwd_lists"), ("bwd_rows_kernel", "bwd_rows"), ("bwd_keys_kernel", "bwd_keys"),
     ("bwd_mask_kernel", "bwd_mask"), ("bwd_dq_kernel", "bwd_dq"), ("bwd_dkv_kernel", "bwd_dkv"),
     ("key_offsets_kernel", "key_offsets"), ("decode_scores_kernel", "decode_scores"),
+    ("decode_scores_mfma_kernel", "decode_scores_mfma"), ("scale_proj_fwd_kernel", "scale_proj_fwd"),
+    ("scale_proj_bwd_kernel", "scale_proj_bwd"), ("scale_proj_reduce_kernel", "scale_proj_reduce"),
     ("decode_solve_kernel", "decode_solve"),
 ])
 CALIBRATION_KERNEL = "bfloat16_copy_kernel"
 
 
 def short(name):
-    return name.split("(")[0].replace("void ", "")
+    return name.replace("(anonymous namespace)::", "").split("(")[0].replace("void ", "")
+
+
+def ours(kernel):
+    return "entmax::" in kernel or "scale_proj_" in kernel
 
 
 def bench_name(kernel):
@@ -49,12 +55,19 @@ def read_stats(path):
 
 
 def collect_counters(dirs):
+    """Mean counter values per kernel, and for the calibration kernel (torch's fp32 -> bf16 conversion: a thread
+    converts eight elements) the totals of counter value and element count per counter."""
     acc = collections.defaultdict(lambda: collections.defaultdict(list))
+    cal = collections.defaultdict(lambda: [0.0, 0.0])
     for d in dirs:
         for f in glob.glob(os.path.join(d, "**", "*counter_collection.csv"), recursive=True):
             for row in csv.DictReader(open(f)):
-                acc[short(row["Kernel_Name"])][row["Counter_Name"]].append(float(row["Counter_Value"]))
-    return {k: {c: sum(v) / len(v) for c, v in cs.items()} for k, cs in acc.items()}
+                name = short(row["Kernel_Name"])
+                acc[name][row["Counter_Name"]].append(float(row["Counter_Value"]))
+                if CALIBRATION_KERNEL in name:
+                    cal[row["Counter_Name"]][0] += float(row["Counter_Value"])
+                    cal[row["Counter_Name"]][1] += 8.0 * float(row["Grid_Size"])
+    return {k: {c: sum(v) / len(v) for c, v in cs.items()} for k, cs in acc.items()}, cal
 
 
 def cmd_trace(a):
@@ -66,7 +79,7 @@ def cmd_trace(a):
         f.write("Workload: " + b["config"]["workload"] + "\n\n")
         f.write("| kernel | calls | avg us | min us | max us | % |\n|---|---|---|---|---|---|\n")
         for r in rows:
-            if "entmax::" in r["name"]:
+            if ours(r["name"]):
                 f.write("| `%s` | %d | %.1f | %.1f | %.1f | %s |\n" % (r["name"], r["calls"], r["avg_us"], r["min_us"],
                                                                      r["max_us"], r["pct"]))
         f.write("\nbench.py's own figures in the same (profiled) run, from hipEvents recorded between the phases:\n\n")
@@ -75,14 +88,14 @@ def cmd_trace(a):
         f.write("    roofline = " + json.dumps(b["roofline"]) + "\n")
         f.write("    mfma_peak_measured_tflops = %.1f\n" % b.get("mfma_peak_measured_tflops", float("nan")))
         f.write("    tile_stats = " + json.dumps(b["tile_stats"]) + "\n")
-        for key in ("other_workloads", "decode_nk32768"):
+        for key in ("other_workloads", "decode_nk32768", "scale_projection"):
             if key in b:
                 f.write("    %s = %s\n" % (key, json.dumps(b[key])))
 
 
 def cmd_pmc(a):
     dur = {r["name"]: r["avg_us"] for r in read_stats(a.stats)}
-    ctr = collect_counters(a.counters)
+    ctr, calsum = collect_counters(a.counters)
     with open(a.out, "w") as f:
         f.write("# rocprofv3 counter summary: %s\n\n" % a.title)
         f.write("Commands (repository root, one MI355X, `export TMPDIR=/tmp`), one counter set per run:\n\n")
@@ -96,7 +109,7 @@ def cmd_pmc(a):
                 "cycles | active / wave cycles | LDS bank conflicts |\n|---|---|---|---|---|---|---|---|---|---|---|\n")
         for k in sorted(ctr, key=lambda k: -dur.get(k, 0)):
             c = ctr[k]
-            if "entmax::" not in k or k not in dur or "SQ_WAVE_CYCLES" not in c:
+            if not ours(k) or k not in dur or "SQ_WAVE_CYCLES" not in c:
                 continue
             m = c.get("SQ_INSTS_MFMA", 0)
             util = c.get("SQ_VALU_MFMA_BUSY_CYCLES", 0) / (dur[k] * 1e-6 * 2.4e9 * 1024)
@@ -105,23 +118,21 @@ def cmd_pmc(a):
                 k, dur[k], m, util, c.get("SQ_INSTS_VALU", 0) / m if m else 0, c.get("SQ_INSTS_SALU", 0) / m if m else 0,
                 c.get("SQ_INSTS_LDS", 0), c.get("SQ_INSTS_VMEM", 0), c.get("SQ_WAIT_ANY", 0) / wc,
                 c.get("SQ_ACTIVE_INST_ANY", 0) / wc, c.get("SQ_LDS_BANK_CONFLICT", 0)))
-        cal = [k for k in ctr if CALIBRATION_KERNEL in k and "FETCH_SIZE" in ctr[k] and "WRITE_SIZE" in ctr[k]]
-        if cal:
-            cal = cal[0]
-            elems = a.calibration_elements
-            ff = elems * 4 / 1024.0 / ctr[cal]["FETCH_SIZE"]
-            wf = elems * 2 / 1024.0 / ctr[cal]["WRITE_SIZE"]
+        if calsum.get("FETCH_SIZE", [0, 0])[0] > 0 and calsum.get("WRITE_SIZE", [0, 0])[0] > 0:
+            ff = calsum["FETCH_SIZE"][1] * 4 / 1024.0 / calsum["FETCH_SIZE"][0]
+            wf = calsum["WRITE_SIZE"][1] * 2 / 1024.0 / calsum["WRITE_SIZE"][0]
             f.write("\n## HBM traffic per launch\n\n")
             f.write("Calibration: the same runs contain bench.py's upload conversions (`at::native::bfloat16_copy_kernel_cuda`, "
-                    "%d elements fp32 -> bf16: %.0f KiB read, %.0f KiB written).  FETCH_SIZE reads %.1f for it (factor %.3f), "
-                    "WRITE_SIZE %.1f (factor %.3f).\n\n" % (elems, elems * 4 / 1024.0, elems * 2 / 1024.0,
-                                                            ctr[cal]["FETCH_SIZE"], ff, ctr[cal]["WRITE_SIZE"], wf))
+                    "fp32 -> bf16, eight elements per thread of its grid: 4 bytes read and 2 written per element).  Over all of "
+                    "them FETCH_SIZE reads %.0f for %.0f KiB (factor %.3f), WRITE_SIZE %.0f for %.0f KiB (factor %.3f).\n\n"
+                    % (calsum["FETCH_SIZE"][0], calsum["FETCH_SIZE"][1] * 4 / 1024.0, ff, calsum["WRITE_SIZE"][0],
+                       calsum["WRITE_SIZE"][1] * 2 / 1024.0, wf))
             f.write("| kernel | FETCH_SIZE | WRITE_SIZE | read MB | written MB | total MB | avg us | HBM GB/s |\n"
                     "|---|---|---|---|---|---|---|---|\n")
             table = []
             for k in sorted(ctr, key=lambda k: -dur.get(k, 0)):
                 c = ctr[k]
-                if "entmax::" not in k or k not in dur or "FETCH_SIZE" not in c or "WRITE_SIZE" not in c:
+                if not ours(k) or k not in dur or "FETCH_SIZE" not in c or "WRITE_SIZE" not in c:
                     continue
                 rd = c["FETCH_SIZE"] * ff * 1024 / 1e6
                 wr = c["WRITE_SIZE"] * wf * 1024 / 1e6
@@ -154,7 +165,6 @@ def main():
     p.add_argument("--traffic-out", default=None)
     p.add_argument("--title", required=True)
     p.add_argument("--command", action="append", default=[])
-    p.add_argument("--calibration-elements", type=int, default=4 * 12 * 4096 * 64)
     a = ap.parse_args()
     (cmd_trace if a.cmd == "trace" else cmd_pmc)(a)
 
