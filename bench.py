@@ -183,8 +183,9 @@ def main():
         algo = {
             "fwd_lists": F * sd["fwd_list_qk"], "fwd_finish": 0.0,
             "fwd_tiled": F * (sd["fwd_qk_max"] + sd["fwd_qk_solve"] + sd["fwd_qk_pv"] + sd["fwd_pv_tiles"]),
-            "bwd_lists": F * sd["bwd_list_qk"], "bwd_rows": 0.0, "bwd_keys": 0.0, "bwd_mask": F * sd["bwd_qk_mask"],
-            "bwd_dq": F * 4 * sd["bwd_dq_tiles"], "bwd_dkv": F * 4 * sd["bwd_dkv_tiles"],
+            "bwd_lists": F * sd["bwd_list_qk"], "bwd_rows": 0.0, "bwd_keys": 0.0, "bwd_mask": 0.0,
+            # the dQ kernel forms the scores of every tile it visits and three more products on the active ones
+            "bwd_dq": F * (sd["bwd_qk_mask"] + 3 * sd["bwd_dq_tiles"]), "bwd_dkv": F * 4 * sd["bwd_dkv_tiles"],
         }
         res = {"cfg": cfg, "alpha": alpha, "ms": ms, "stats": sd, "algo": algo, "do_bwd": do_bwd, "data": data}
         if want_events:

@@ -103,7 +103,7 @@ enum {
   ENTMAX_STAT_FWD_BLOCKS = 6,        /* workgroups */
   ENTMAX_STAT_FWD_EVAL_TILES = 7,    /* tiles on which the threshold function was evaluated element by element */
   ENTMAX_STAT_BWD_TILES_VISIBLE = 8,
-  ENTMAX_STAT_BWD_QK_MASK = 9,       /* score tiles computed to find the non-zero tiles */
+  ENTMAX_STAT_BWD_QK_MASK = 9,       /* score tiles the dQ kernel computed (it finds the non-zero tiles on the way) */
   ENTMAX_STAT_BWD_ACTIVE_TILES = 10, /* tiles with some p_ij > 0 */
   ENTMAX_STAT_BWD_DQ_TILES = 11,     /* tiles processed by the dQ / row-scalar kernel */
   ENTMAX_STAT_BWD_DKV_TILES = 12,    /* tiles processed by the dK / dV kernel */
@@ -140,8 +140,8 @@ enum {
   ENTMAX_BWD_PHASE_ROWS = 1,       /* per-key segment offsets; mu, dscale, dQ and the per-entry (p, dS) from the lists */
   ENTMAX_BWD_PHASE_TRANSPOSE = 2,  /* path 1: operand copies for the tiled kernels (path 0: made by extra workgroups
                                       of the row launch, for the heads that need them) */
-  ENTMAX_BWD_PHASE_MASK = 3,       /* tiled path: non-zero tile map */
-  ENTMAX_BWD_PHASE_DQ = 4,         /* tiled path: row scalars and dQ */
+  ENTMAX_BWD_PHASE_MASK = 3,       /* (empty: the non-zero tile map is a by-product of the dQ kernel) */
+  ENTMAX_BWD_PHASE_DQ = 4,         /* tiled path: row scalars, dQ and the non-zero tile map */
   ENTMAX_BWD_PHASE_DKV = 5,        /* tiled path: dK, dV */
   ENTMAX_BWD_PHASE_KEYS = 6,       /* support-list path: dK and dV per key (and d beta, d gamma per head) */
   ENTMAX_BWD_PHASE_SCALE_GRAD = 7,

@@ -6,8 +6,8 @@
 // and d beta, d gamma by the chain rule through eq. (asentmax).
 // Everything is multiplied by p or g, which vanish off the support, so only the
 // 32x32 tiles that hold some positive x are visited:
-//   bwd_mask_kernel  one Q K^T sweep that records those tiles (bit per tile);
-//   bwd_dq_kernel    query-block outer loop: row scalars mu_i, dscale_i and dQ.
+//   bwd_dq_kernel    query-block outer loop: row scalars mu_i, dscale_i and dQ; records the tiles with some
+//                    positive x (bit per tile) for the key-side kernel.
 //                    dQ is linear in mu:  dQ_i = c_i (sum_j g dP k_j - mu_i sum_j g k_j),
 //                    so both sums are accumulated in the same pass and combined
 //                    once mu is known -- no second pass and no atomics;
@@ -47,99 +47,6 @@ struct BwdArgs {
   }
 };
 
-// --------------------------------------------------------------- tile mask
-
-template <typename T>
-struct MaskTile {
-  static constexpr int value = sizeof(T) == 2 ? 128 : 32;
-};
-
-template <typename T, int D, int AM, bool BIAS>
-__device__ __forceinline__ void bwd_mask_block(const BwdArgs& A, int bh_, int blk_, char* smem) {
-  using C = QCtx<T, D, MaskTile<T>::value, BIAS>;
-  constexpr int KT = C::KT, NSB = C::NSB, TB = C::kTileBytes;
-  const Geom& g = A.g;
-  WaveMask wm;
-  wm.words = reinterpret_cast<uint32_t*>(smem + 2 * TB);
-  wm.nwords = A.mask_words;
-  C q;
-  q.init(g, A.Q, bh_, blk_);
-  if (A.head_flag && __builtin_amdgcn_readfirstlane(A.head_flag[q.bh]) == 0) return;
-  if (!A.block_is_ours(q.bh, q.qb)) {
-    // the list path owns this block: none of its tiles is the tiled kernels' business
-    const int ig = q.q0 >> 5;
-    if (ig < A.nqg) {
-      uint32_t* dst = A.mask + ((long long)q.bh * A.nqg + ig) * A.mask_words;
-      for (int w = q.lane; w < A.mask_words; w += 64) dst[w] = 0u;
-    }
-    return;
-  }
-  q.init_window(g);
-  for (int w = q.tid; w < kWaves * A.mask_words; w += kThreads) wm.words[w] = 0u;
-  const float tau = q.valid ? A.tau[(long long)q.bh * g.Nq + q.i] : 0.f;
-  const bool live = q.valid && q.lim > 0;
-  Slot slots[1];
-  slots[0].base = reinterpret_cast<const char*>(reinterpret_cast<const T*>(A.K) + (long long)q.b * g.kv_sb +
-                                                (long long)q.h * g.kv_sh);
-  slots[0].row_bytes = g.kv_sn * (long long)sizeof(T);
-  unsigned n_vis = 0, n_act = 0;
-  sweep_tiles<C, T, D, 1, 0>(
-      smem, slots, q.ntiles, g.Nk, q.tid, [&](int kt) { return q.tile_in_window(kt); },
-      [&](int kt, const char* tl) {
-        if (!q.tile_in_wave_window(kt)) return;
-        if ((kt + 1) * KT <= q.wave_lim_min) {
-          // interior tile: every key is visible to every row of the wave
-          f32x16_t acc[NSB];
-#pragma unroll
-          for (int sb = 0; sb < NSB; ++sb) acc[sb] = q.scores(tl, sb, kt);
-#pragma unroll
-          for (int sb = 0; sb < NSB; ++sb) {
-            float lm = max16(acc[sb]);
-            bool cand = live && (fmaf(lm, q.a, -tau) > 0.f);
-            if (__ballot(cand) != 0ull) {
-              ++n_act;
-              if (q.lane == 0) wm.set(q.wave, kt * NSB + sb);
-            }
-          }
-          n_vis += NSB;
-          return;
-        }
-        const uint32_t act = q.visible_bits(kt);
-        f32x16_t acc[NSB];
-#pragma unroll
-        for (int sb = 0; sb < NSB; ++sb)
-          if (act & (1u << sb)) acc[sb] = q.scores(tl, sb, kt);
-#pragma unroll
-        for (int sb = 0; sb < NSB; ++sb) {
-          if (!(act & (1u << sb))) continue;
-          int j0 = kt * KT + sb * 32;
-          ++n_vis;
-          if (j0 + 32 > q.wave_lim_min) {
-            int rel = q.lim - j0;
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[sb][e] = (q.key_of(e) < rel) ? acc[sb][e] : -kInf;
-          }
-          float lm = max16(acc[sb]);
-          bool cand = live && (lm > -kInf) && (fmaf(lm, q.a, -tau) > 0.f);
-          if (__ballot(cand) != 0ull) {
-            ++n_act;
-            if (q.lane == 0) wm.set(q.wave, kt * NSB + sb);
-          }
-        }
-      });
-  // sweep_tiles ends on a barrier: all bits are in LDS
-  int ig = q.q0 >> 5;
-  if (ig < A.nqg) {
-    uint32_t* dst = A.mask + ((long long)q.bh * A.nqg + ig) * A.mask_words;
-    for (int w = q.lane; w < A.mask_words; w += 64) dst[w] = wm.words[q.wave * A.mask_words + w];
-  }
-  if (A.stats && q.lane == 0) {
-    atomicAdd(&A.stats[ENTMAX_STAT_BWD_TILES_VISIBLE], (unsigned long long)n_vis);
-    atomicAdd(&A.stats[ENTMAX_STAT_BWD_QK_MASK], (unsigned long long)n_vis);
-    atomicAdd(&A.stats[ENTMAX_STAT_BWD_ACTIVE_TILES], (unsigned long long)n_act);
-  }
-}
-
 // ------------------------------------------------- row scalars, dscale and dQ
 
 template <typename T, int D, int AM, bool BIAS>
@@ -156,7 +63,16 @@ __device__ __forceinline__ void bwd_dq_block(const BwdArgs& A, int bh_, int blk_
   C q;
   q.init(g, A.Q, bh_, blk_);
   if (A.head_flag && __builtin_amdgcn_readfirstlane(A.head_flag[q.bh]) == 0) return;
-  if (!A.block_is_ours(q.bh, q.qb)) return;  // dQ and the row scalars of this block come from the list path
+  if (!A.block_is_ours(q.bh, q.qb)) {
+    // dQ and the row scalars of this block come from the list path: none of its tiles is the key-side kernel's
+    const int ig = q.q0 >> 5;
+    if (ig < A.nqg) {
+      uint32_t* dst = A.mask + ((long long)q.bh * A.nqg + ig) * A.mask_words;
+      for (int w = q.lane; w < A.mask_words; w += 64) dst[w] = 0u;
+    }
+    return;
+  }
+  q.init_window(g);
   const float r = 1.0f / (g.alpha - 1.0f);
   const long long row_idx = (long long)q.bh * g.Nq + q.i;
   const float tau = q.valid ? A.tau[row_idx] : 0.f;
@@ -169,13 +85,9 @@ __device__ __forceinline__ void bwd_dq_block(const BwdArgs& A, int bh_, int blk_
 #pragma unroll
     for (int cc = 0; cc < NC; ++cc) dof[cc] = q.valid ? Elem<T>::load(drow + 16 * cc + 8 * q.hh) : Elem<T>::zero();
   }
-  {
-    int ig = q.q0 >> 5;
-    for (int w = q.lane; w < A.mask_words; w += 64)
-      wm.words[q.wave * A.mask_words + w] =
-          (ig < A.nqg) ? A.mask[((long long)q.bh * A.nqg + ig) * A.mask_words + w] : 0u;
-  }
-  wm.merge(q.tid);
+  // the map of the tiles that hold some p > 0 is a by-product of this pass (the key-side kernel reads it)
+  for (int w = q.tid; w < kWaves * A.mask_words; w += kThreads) wm.words[w] = 0u;
+  __syncthreads();
 
   const long long kv_base = (long long)q.b * g.kv_sb + (long long)q.h * g.kv_sh;
   Slot slots[3];
@@ -193,15 +105,17 @@ __device__ __forceinline__ void bwd_dq_block(const BwdArgs& A, int bh_, int blk_
     acc2[mm] = acc1[mm];
   }
   float Z = 0.f, N = 0.f, Aq = 0.f, Cq = 0.f;
-  unsigned n_tiles = 0;
+  unsigned n_tiles = 0, n_vis = 0;
 
-  auto needed = [&](int kt) { return wm.tile_bits<NSB>(kWaves, kt) != 0u; };
+  auto needed = [&](int kt) { return q.tile_in_window(kt); };
   sweep_tiles<C, T, D, 3, 4>(tiles, slots, q.ntiles, g.Nk, q.tid, needed, [&](int kt, const char* tl) {
-    const uint32_t act = q.visible_bits(kt) & wm.tile_bits<NSB>(q.wave, kt);
+    if (!q.tile_in_wave_window(kt)) return;
+    const uint32_t act = q.visible_bits(kt);
 #pragma unroll
     for (int sb = 0; sb < NSB; ++sb) {
       if (!(act & (1u << sb))) continue;
       int j0 = kt * KT + sb * 32;
+      ++n_vis;
       f32x16_t acc = q.scores(tl, sb, kt);
       const bool masked = j0 + 32 > q.wave_lim_min;
       const int rel = q.lim - j0;
@@ -217,6 +131,7 @@ __device__ __forceinline__ void bwd_dq_block(const BwdArgs& A, int bh_, int blk_
       }
       if (__ballot(any) == 0ull) continue;
       ++n_tiles;
+      if (q.lane == 0) wm.set(q.wave, kt * NSB + sb);
       // dP^T = V_tile dO^T, same lane layout as the scores
       f32x16_t dp = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -287,7 +202,20 @@ __device__ __forceinline__ void bwd_dq_block(const BwdArgs& A, int bh_, int blk_
         Elem<T>::store(A.dQ, q_base + (long long)row * g.q_sn + mm * 32 + q.li, cr * (acc1[mm][e] - mur * acc2[mm][e]));
     }
   }
-  if (A.stats && q.lane == 0) atomicAdd(&A.stats[ENTMAX_STAT_BWD_DQ_TILES], (unsigned long long)n_tiles);
+  // (the sweep ended on a barrier: all bits are in LDS)
+  {
+    const int ig = q.q0 >> 5;
+    if (ig < A.nqg) {
+      uint32_t* dst = A.mask + ((long long)q.bh * A.nqg + ig) * A.mask_words;
+      for (int w = q.lane; w < A.mask_words; w += 64) dst[w] = wm.words[q.wave * A.mask_words + w];
+    }
+  }
+  if (A.stats && q.lane == 0) {
+    atomicAdd(&A.stats[ENTMAX_STAT_BWD_DQ_TILES], (unsigned long long)n_tiles);
+    atomicAdd(&A.stats[ENTMAX_STAT_BWD_TILES_VISIBLE], (unsigned long long)n_vis);
+    atomicAdd(&A.stats[ENTMAX_STAT_BWD_QK_MASK], (unsigned long long)n_vis);
+    atomicAdd(&A.stats[ENTMAX_STAT_BWD_ACTIVE_TILES], (unsigned long long)n_tiles);
+  }
 }
 
 // ------------------------------------------------------------------ dK, dV
@@ -513,22 +441,6 @@ __device__ __forceinline__ void bwd_dkv_block(const BwdArgs& A, int bh_, int blk
   }
   if (A.stats && lane == 0) atomicAdd(&A.stats[ENTMAX_STAT_BWD_DKV_TILES], (unsigned long long)n_tiles);
 }
-
-#define ENTMAX_PAIRED_KERNEL(NAME, BLOCKFN, NBLK, OCC)                              \
-  template <typename T, int D, int AM, bool BIAS>                                   \
-  __global__ __launch_bounds__(kThreads, OCC) void NAME(BwdArgs A) {                \
-    extern __shared__ __attribute__((aligned(16))) char smem[];                     \
-    const PairItem it = pair_item(NBLK);                                            \
-    if (A.head_flag && __builtin_amdgcn_readfirstlane(A.head_flag[it.bh]) == 0) return; \
-    for (int part = 0; part < 2; ++part) {                                          \
-      const int blk = part ? it.second : it.first;                                  \
-      if (blk < 0) break;                                                           \
-      if (part) __syncthreads();                                                    \
-      BLOCKFN<T, D, AM, BIAS>(A, it.bh, blk, smem);                                 \
-    }                                                                               \
-  }
-ENTMAX_PAIRED_KERNEL(bwd_mask_kernel, bwd_mask_block, A.nqb, 3)
-#undef ENTMAX_PAIRED_KERNEL
 
 // The register-heavy kernels hold two workgroups per CU; one block per workgroup, long blocks first.
 template <typename T, int D, int AM, bool BIAS>

@@ -10,16 +10,12 @@ namespace {
 
 template <typename T, int D, int AM, bool BIAS>
 bool launch_bwd_kernels(const BwdArgs& a, const Layout& L, int B, int H, hipStream_t st, void* const* ev) {
-  size_t smem_mask = 2 * (size_t)QCtx<T, D, MaskTile<T>::value>::kTileBytes + (size_t)(kWaves + 1) * a.mask_words * 4 + 64;
   size_t smem_dq = 6 * (size_t)QCtx<T, D>::kTileBytes + (size_t)(kWaves + 1) * a.mask_words * 4 + kWaves * 64 * 4 + 64;
   size_t smem_dkv = 8 * (size_t)QCtx<T, D>::kTileBytes + 2 * 4 * (size_t)QCtx<T, D>::KT * 4 + (size_t)a.nqg + 64;
-  constexpr auto k_mask = bwd_mask_kernel<T, D, AM, BIAS>;
   constexpr auto k_dq = bwd_dq_kernel<T, D, AM, BIAS>;
   constexpr auto k_dkv = bwd_dkv_kernel<T, D, AM>;
-  if (!ensure_dynamic_lds<k_mask>(smem_mask) || !ensure_dynamic_lds<k_dq>(smem_dq) || !ensure_dynamic_lds<k_dkv>(smem_dkv))
+  if (!ensure_dynamic_lds<k_dq>(smem_dq) || !ensure_dynamic_lds<k_dkv>(smem_dkv))
     return false;
-  hipLaunchKernelGGL(k_mask, dim3((unsigned)(B * H * ((L.nqb + 1) / 2))), dim3(kThreads), smem_mask, st, a);
-  if (!launch_ok()) return false;
   record(ev, ENTMAX_BWD_PHASE_MASK + 1, st);
   hipLaunchKernelGGL(k_dq, dim3((unsigned)(B * H * L.nqb)), dim3(kThreads), smem_dq, st, a);
   if (!launch_ok()) return false;

@@ -22,7 +22,7 @@ import os
 BENCH_NAMES = collections.OrderedDict([
     ("fwd_lists_kernel", "fwd_lists"), ("fwd_finish_kernel", "fwd_finish"), ("fwd_kernel", "fwd_tiled"),
     ("bwd_lists_kernel", "bwd_lists"), ("bwd_rows_kernel", "bwd_rows"), ("bwd_keys_kernel", "bwd_keys"),
-    ("bwd_mask_kernel", "bwd_mask"), ("bwd_dq_kernel", "bwd_dq"), ("bwd_dkv_kernel", "bwd_dkv"),
+    ("bwd_dq_kernel", "bwd_dq"), ("bwd_dkv_kernel", "bwd_dkv"),
     ("key_offsets_kernel", "key_offsets"), ("decode_scores_kernel", "decode_scores"),
     ("decode_scores_mfma_kernel", "decode_scores_mfma"), ("scale_proj_fwd_kernel", "scale_proj_fwd"),
     ("scale_proj_bwd_kernel", "scale_proj_bwd"), ("scale_proj_reduce_kernel", "scale_proj_reduce"),
