@@ -244,11 +244,13 @@ struct FragOff<float> {
 // issues the global loads of a ragged tile (rows at or beyond valid_rows repeat the last valid row),
 // fetch_full() does the same for a tile known to lie wholly inside the tensor,
 // commit() writes the staged chunks to LDS.
-template <typename TileT, int NT = kThreads>
+// NSET register sets let that many tiles be in flight at once (`set` must be a compile-time constant
+// after inlining).
+template <typename TileT, int NT = kThreads, int NSET = 1>
 struct Stage {
   static_assert(TileT::kChunks % NT == 0, "every thread must move the same number of chunks");
   static constexpr int kPer = TileT::kChunks / NT;
-  u32x4_t r[kPer];
+  u32x4_t r[NSET][kPer];
   uint32_t goff[kPer];
   int loff[kPer];
   int row0;  // row of the first chunk; chunk `it` sits NT / kCpr rows further per step
@@ -262,25 +264,25 @@ struct Stage {
       loff[it] = TileT::off(row, ch);
     }
   }
-  __device__ __forceinline__ void fetch_full(const char* gtile) {
+  __device__ __forceinline__ void fetch_full(const char* gtile, int set = 0) {
 #pragma unroll
-    for (int it = 0; it < kPer; ++it) r[it] = *reinterpret_cast<const u32x4_t*>(gtile + goff[it]);
+    for (int it = 0; it < kPer; ++it) r[set][it] = *reinterpret_cast<const u32x4_t*>(gtile + goff[it]);
   }
   // Ragged last tile: rows at or beyond valid_rows re-read the last valid row instead of being
   // zero-filled.  Every consumer masks those rows (they lie beyond the tensor), and a finite
   // stand-in keeps "0 x value" products finite; above all the loads stay unconditional, so the
   // compiler has no reason to wait for them before the tile that is computed meanwhile.
-  __device__ __forceinline__ void fetch(const char* gtile, int valid_rows, long long grow_bytes) {
+  __device__ __forceinline__ void fetch(const char* gtile, int valid_rows, long long grow_bytes, int set = 0) {
 #pragma unroll
     for (int it = 0; it < kPer; ++it) {
       int row = min(row0 + it * (NT / TileT::kCpr), valid_rows - 1);
       uint32_t off = (uint32_t)row * (uint32_t)grow_bytes + (goff[0] - (uint32_t)row0 * (uint32_t)grow_bytes);
-      r[it] = *reinterpret_cast<const u32x4_t*>(gtile + off);
+      r[set][it] = *reinterpret_cast<const u32x4_t*>(gtile + off);
     }
   }
-  __device__ __forceinline__ void commit(char* tile) const {
+  __device__ __forceinline__ void commit(char* tile, int set = 0) const {
 #pragma unroll
-    for (int it = 0; it < kPer; ++it) *reinterpret_cast<u32x4_t*>(tile + loff[it]) = r[it];
+    for (int it = 0; it < kPer; ++it) *reinterpret_cast<u32x4_t*>(tile + loff[it]) = r[set][it];
   }
 };
 

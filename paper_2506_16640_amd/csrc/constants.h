@@ -12,6 +12,10 @@ constexpr int kCandCap = 32;     // candidate entries per lane = per half row (f
 constexpr int kBwdCap = 16;      // support entries per lane = per half row (the lists the backward works from)
 constexpr int kListStride = 64;  // lists are stored slot-major per wave: entry s of the 64 lanes together
 
+// Tiled forward behind the list kernels: up to this many flagged blocks run four workgroups to a block (a few long
+// blocks alone on the chip are bound by their own serial length), more run as block pairs (bound by throughput).
+constexpr int kSplitMaxBlocks = 256;
+
 // Sweep scratch of the list kernels: CAP cells of (4 raw scores, first key) per thread.
 constexpr int kCellGroups = 1;  // 4-key accumulator groups per cell
 constexpr size_t cell_bytes_per_workgroup(int cap) { return (size_t)kThreads * cap * (16 * kCellGroups + 4); }

@@ -31,6 +31,8 @@ struct FwdArgs {
   int nqb;         // query blocks per head
   int mask_words;  // uint32 words of one wave's tile mask
   const int* dense_flag;  // NULL: run every block; else [B*H*nqb], run only the blocks whose flag is set
+  const int* dense_count; // with dense_flag: the number of set flags, then the first kSplitMaxBlocks flagged blocks'
+                          // numbers bh * nqb + qb in any order (decides how the blocks are shared out, see fwd_kernel)
 };
 
 constexpr int kMaxSolveIters = 48;
@@ -82,6 +84,42 @@ __device__ __forceinline__ void accumulate(RowSums& s, float xp, float r) {
       float l = __builtin_amdgcn_logf(xp);
       s.s1 += __builtin_amdgcn_exp2f(r * l);
       s.s0 += __builtin_amdgcn_exp2f((r - 1.f) * l);
+    }
+  }
+}
+
+// accumulate() over the 16 scores a lane holds of one 32 x 32 block: xp_e = a acc_e - tau; with `masked`
+// (wave-uniform) entries equal to -inf stand for keys the row does not see.
+// AM 1 and 2 spend fewer instructions per score than 16 accumulate() calls: the sign bits are shifted into one
+// word and counted once, and the smallest positive xp is an unsigned-integer minimum over the bit patterns
+// (positive floats order like unsigned integers, and every negative one lies above them).  A score with
+// xp = +0 counts as positive here; it then also makes xmin zero, which only ever withholds the `exact`
+// verdict of solve_step().
+template <int AM>
+__device__ __forceinline__ void accumulate_block(RowSums& s, const f32x16_t& acc, float a, float tau, float r, bool masked) {
+  if constexpr (AM == 1 || AM == 2) {
+    uint32_t signs = 0u, xm = __float_as_uint(s.xmin);
+    auto one = [&](float xp) {
+      signs = __builtin_amdgcn_alignbit(signs, __float_as_uint(xp), 31);  // signs << 1 | sign of xp
+      xm = min(xm, __float_as_uint(xp));
+      float x = fmaxf(xp, 0.f);
+      s.s1 += x;
+      if (AM == 1) s.s2 = fmaf(x, x, s.s2);
+    };
+    if (masked) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) one(acc[e] == -kInf ? -1.f : fmaf(acc[e], a, -tau));
+    } else {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) one(fmaf(acc[e], a, -tau));
+    }
+    s.s0 += (float)(16 - __popc(signs));
+    s.xmin = __uint_as_float(xm);
+  } else {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      float xp = (masked && acc[e] == -kInf) ? -1.f : fmaf(acc[e], a, -tau);
+      accumulate<AM>(s, xp, r);
     }
   }
 }
@@ -154,29 +192,62 @@ struct ListCfg {
   static constexpr size_t kLdsBytes = 2 * (size_t)kTile * D * sizeof(T) + 64 + (size_t)kLdsCells * kThreads * 20;
 };
 
-template <typename T, int D, int AM, bool BIAS>
-__device__ __forceinline__ void fwd_block(const FwdArgs& A, int bh_, int blk_, char* smem) {
+// SPLIT: the workgroup takes one 32-row group (rg_) of the block instead of four, and its four waves share out
+// the 32-key blocks of every tile (block number mod 4 = wave); row maxima, the partial sums of the threshold
+// function and the partial outputs are combined across the waves through LDS.  A block then runs as four
+// workgroups with a quarter of the serial work each: for the case where only a few blocks need this kernel.
+template <typename T, int D, int AM, bool BIAS, bool SPLIT>
+__device__ __forceinline__ void fwd_block(const FwdArgs& A, int bh_, int blk_, int rg_, char* smem) {
   using C = QCtx<T, D, FwdTile<T>::value, BIAS>;
   constexpr int KT = C::KT, NSB = C::NSB, NM = C::NM, TB = C::kTileBytes;
+  // key tiles in flight (sweep_tiles): a split block has its compute unit nearly to itself
+  constexpr int kFwdDepth = SPLIT ? 2 : 1;
   const Geom& g = A.g;
   char* tiles = smem;  // 2 buffers x 2 slots
   WaveMask wm;
   wm.words = reinterpret_cast<uint32_t*>(smem + 4 * TB);
   wm.nwords = A.mask_words;
+  float* xch = reinterpret_cast<float*>(wm.words + (kWaves + 1) * A.mask_words);  // SPLIT: [kWaves][64][4]
 
   C q;
-  q.init(g, A.Q, bh_, blk_);
+  q.init(g, A.Q, bh_, blk_, SPLIT ? rg_ : -1);
   q.init_window(g);
+  // SPLIT: 32-key block number (kt NSB + sb) mod 4 = wave is this wave's, which is block sb_own of every NSB-th,
+  // or of every, tile; own_bits(kt): the blocks of tile kt that are this wave's (all of them unless SPLIT)
+  static_assert(!SPLIT || NSB == 1 || NSB == 2 || NSB == 4, "the split shares out 4 consecutive blocks");
+  const int sb_own = __builtin_amdgcn_readfirstlane(q.wave % NSB);
+  auto own_bits = [&](int kt) -> uint32_t {
+    if constexpr (!SPLIT) return (1u << NSB) - 1u;
+    return (((kt * NSB + sb_own) & (kWaves - 1)) == q.wave) ? (1u << sb_own) : 0u;
+  };
+  // fn(acc, sb) on the score block of every set bit of act.  All of a tile's blocks are computed before the
+  // first is used (the matrix pipeline stays busy); a split wave has at most one.
+  auto each_block = [&](int kt, const char* tl, uint32_t act, auto&& fn) {
+    if constexpr (SPLIT) {
+      if (act == 0u) return;
+      f32x16_t acc = q.scores(tl, sb_own, kt);
+      fn(acc, sb_own);
+    } else {
+      f32x16_t acc[NSB];
+#pragma unroll
+      for (int sb = 0; sb < NSB; ++sb)
+        if (act & (1u << sb)) acc[sb] = q.scores(tl, sb, kt);
+#pragma unroll
+      for (int sb = 0; sb < NSB; ++sb)
+        if (act & (1u << sb)) fn(acc[sb], sb);
+    }
+  };
   const float r = 1.0f / (g.alpha - 1.0f);
   float* tau_out = A.tau + (long long)q.bh * g.Nq;
   const long long o_base = (long long)q.b * g.q_sb + (long long)q.h * g.q_sh;
 
   if (q.block_lim == 0) {  // no row of this workgroup sees any key
-    for (int e = q.tid; e < kBlockRows * D; e += kThreads) {
-      int row = q.qb * kBlockRows + e / D;
+    const int row0 = SPLIT ? q.q0 : q.qb * kBlockRows, nrows = SPLIT ? 32 : kBlockRows;
+    for (int e = q.tid; e < nrows * D; e += kThreads) {
+      int row = row0 + e / D;
       if (row < g.Nq) Elem<T>::store(A.O, o_base + (long long)row * g.q_sn + e % D, 0.f);
     }
-    if (q.tid < kBlockRows && q.qb * kBlockRows + q.tid < g.Nq) tau_out[q.qb * kBlockRows + q.tid] = 0.f;
+    if (q.tid < nrows && row0 + q.tid < g.Nq) tau_out[row0 + q.tid] = 0.f;
     return;
   }
   for (int w = q.tid; w < (kWaves + 1) * A.mask_words; w += kThreads) wm.words[w] = 0u;
@@ -199,25 +270,25 @@ __device__ __forceinline__ void fwd_block(const FwdArgs& A, int bh_, int blk_, c
 
   // ------------------------------------------------------------ 1. row max
   float m = -kInf;
-  sweep_tiles<C, T, D, 1, 0>(
+  sweep_tiles<C, T, D, 1, 0, kFwdDepth>(
       tiles, slots, q.ntiles, g.Nk, q.tid, [&](int kt) { return q.tile_in_window(kt); },
       [&](int kt, const char* tl) {
         if (!q.tile_in_wave_window(kt)) return;
-        const uint32_t act = q.visible_bits(kt);
-        f32x16_t acc[NSB];
-#pragma unroll
-        for (int sb = 0; sb < NSB; ++sb)
-          if (act & (1u << sb)) acc[sb] = q.scores(tl, sb, kt);
-#pragma unroll
-        for (int sb = 0; sb < NSB; ++sb) {
-          if (!(act & (1u << sb))) continue;
+        each_block(kt, tl, q.visible_bits(kt) & own_bits(kt), [&](f32x16_t& acc, int sb) {
           int j0 = kt * KT + sb * 32;
           ++n_vis;
-          if (j0 + 32 > q.wave_lim_min) mask_block(acc[sb], j0);
-          m = fmaxf(m, max16(acc[sb]));
-        }
+          if (j0 + 32 > q.wave_lim_min) mask_block(acc, j0);
+          m = fmaxf(m, max16(acc));
+        });
       });
   m = fmaxf(m, __shfl_xor(m, 32));
+  if constexpr (SPLIT) {  // the row maximum over all waves' keys
+    xch[(q.wave * 64 + q.lane) * 4] = m;
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) m = fmaxf(m, xch[(w * 64 + q.lane) * 4]);
+    __syncthreads();
+  }
 
   // ------------------------------------------------------------ 2. threshold
   const bool live = q.valid && q.lim > 0;
@@ -234,22 +305,16 @@ __device__ __forceinline__ void fwd_block(const FwdArgs& A, int bh_, int blk_, c
     sums.clear();
     const bool first = (iter == 0);
     auto needed = [&](int kt) { return first ? q.tile_in_window(kt) : wm.tile_bits<NSB>(kWaves, kt) != 0u; };
-    sweep_tiles<C, T, D, 1, 0>(tiles, slots, q.ntiles, g.Nk, q.tid, needed, [&](int kt, const char* tl) {
+    sweep_tiles<C, T, D, 1, 0, kFwdDepth>(tiles, slots, q.ntiles, g.Nk, q.tid, needed, [&](int kt, const char* tl) {
       if (!wave_on || !q.tile_in_wave_window(kt)) return;
-      uint32_t act = q.visible_bits(kt);
+      uint32_t act = q.visible_bits(kt) & own_bits(kt);
       if (!first) act &= wm.tile_bits<NSB>(q.wave, kt);
-      f32x16_t acc[NSB];
-#pragma unroll
-      for (int sb = 0; sb < NSB; ++sb)
-        if (act & (1u << sb)) acc[sb] = q.scores(tl, sb, kt);
-#pragma unroll
-      for (int sb = 0; sb < NSB; ++sb) {
-        if (!(act & (1u << sb))) continue;
+      each_block(kt, tl, act, [&](f32x16_t& acc, int sb) {
         int j0 = kt * KT + sb * 32;
         ++n_qk_solve;
         const bool masked = j0 + 32 > q.wave_lim_min;
-        if (masked) mask_block(acc[sb], j0);
-        float lm = max16(acc[sb]);
+        if (masked) mask_block(acc, j0);
+        float lm = max16(acc);
         // masked entries are -inf: a = 0 (scale 0) must not turn them into NaN
         bool cand = (lm > -kInf) && (fmaf(lm, q.a, -tau) > 0.f) && !done;
         if (first) {
@@ -257,17 +322,31 @@ __device__ __forceinline__ void fwd_block(const FwdArgs& A, int bh_, int blk_, c
           bool cand_any = (lm > -kInf) && (fmaf(lm, q.a, -tau) > 0.f) && live;
           if (__ballot(cand_any) != 0ull && q.lane == 0) wm.set(q.wave, kt * NSB + sb);
         }
-        if (__ballot(cand) == 0ull) continue;
+        if (__ballot(cand) == 0ull) return;
         ++n_eval;
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          float xp = (masked && acc[sb][e] == -kInf) ? -1.f : fmaf(acc[sb][e], q.a, -tau);
-          accumulate<AM>(sums, xp, r);
-        }
-      }
+        accumulate_block<AM>(sums, acc, q.a, tau, r, masked);
+      });
     });
     if (first) wm.merge(q.tid);
     sums.combine_halves();
+    if constexpr (SPLIT) {  // the sums over all waves' keys, added in wave order: every wave then takes the same step
+      float* mine = xch + (q.wave * 64 + q.lane) * 4;
+      mine[0] = sums.s0;
+      mine[1] = sums.s1;
+      mine[2] = sums.s2;
+      mine[3] = sums.xmin;
+      __syncthreads();
+      sums.clear();
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w) {
+        const float* o = xch + (w * 64 + q.lane) * 4;
+        sums.s0 += o[0];
+        sums.s1 += o[1];
+        sums.s2 += o[2];
+        sums.xmin = fminf(sums.xmin, o[3]);
+      }
+      __syncthreads();
+    }
     if (!done) done = solve_step<AM>(sums, r, tau, lo, hi);
     ++iter;
     ++n_sweeps;
@@ -280,33 +359,30 @@ __device__ __forceinline__ void fwd_block(const FwdArgs& A, int bh_, int blk_, c
   for (int mm = 0; mm < NM; ++mm)
     oacc[mm] = f32x16_t{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   // lane offsets of the V^T fragments: row (l%32) of a 32-feature block, key chunk 2 sb + cc
-  FragOff<T> voff[2 * NSB];
+  // (a split wave keeps those of its one block)
+  constexpr int NVB = SPLIT ? 1 : NSB;
+  FragOff<T> voff[2 * NVB];
 #pragma unroll
-  for (int k = 0; k < 2 * NSB; ++k) voff[k] = FragOff<T>::template make<typename C::XtTile>(q.li, 2 * k + q.hh);
+  for (int k = 0; k < 2 * NVB; ++k)
+    voff[k] = FragOff<T>::template make<typename C::XtTile>(q.li, 2 * ((SPLIT ? 2 * sb_own : 0) + k) + q.hh);
 
-  sweep_tiles<C, T, D, 2, 2>(
+  sweep_tiles<C, T, D, 2, 2, kFwdDepth>(
       tiles, slots, q.ntiles, g.Nk, q.tid, [&](int kt) { return wm.tile_bits<NSB>(kWaves, kt) != 0u; },
       [&](int kt, const char* tl) {
-        const uint32_t act = q.visible_bits(kt) & wm.tile_bits<NSB>(q.wave, kt);
-        f32x16_t acc[NSB];
-#pragma unroll
-        for (int sb = 0; sb < NSB; ++sb)
-          if (act & (1u << sb)) acc[sb] = q.scores(tl, sb, kt);
-#pragma unroll
-        for (int sb = 0; sb < NSB; ++sb) {
-          if (!(act & (1u << sb))) continue;
+        const uint32_t act = q.visible_bits(kt) & wm.tile_bits<NSB>(q.wave, kt) & own_bits(kt);
+        each_block(kt, tl, act, [&](f32x16_t& acc, int sb) {
           int j0 = kt * KT + sb * 32;
           ++n_qk_pv;
           const bool masked = j0 + 32 > q.wave_lim_min;
-          if (masked) mask_block(acc[sb], j0);
-          float lm = max16(acc[sb]);
+          if (masked) mask_block(acc, j0);
+          float lm = max16(acc);
           bool cand = live && (lm > -kInf) && (fmaf(lm, q.a, -tau) > 0.f);
-          if (__ballot(cand) == 0ull) continue;  // every probability of this tile is exactly zero
+          if (__ballot(cand) == 0ull) return;  // every probability of this tile is exactly zero
           ++n_pv;
           float p[16];
 #pragma unroll
           for (int e = 0; e < 16; ++e) {
-            float xp = (masked && acc[sb][e] == -kInf) ? 0.f : fmaf(acc[sb][e], q.a, -tau);
+            float xp = (masked && acc[e] == -kInf) ? 0.f : fmaf(acc[e], q.a, -tau);
             p[e] = live ? pow_r<AM>(fmaxf(xp, 0.f), r) : 0.f;
           }
           const char* vt = tl + TB;
@@ -318,14 +394,34 @@ __device__ __forceinline__ void fwd_block(const FwdArgs& A, int bh_, int blk_, c
             Elem<T>::pack_split(p + 8 * cc, pf, pl);
 #pragma unroll
             for (int mm = 0; mm < NM; ++mm) {
-              Frag<T> vfr = voff[2 * sb + cc].load(vt, mm * 32 * C::XtTile::kRowBytes);
+              Frag<T> vfr = voff[(SPLIT ? 0 : 2 * sb) + cc].load(vt, mm * 32 * C::XtTile::kRowBytes);
               oacc[mm] = Elem<T>::mma(pf, vfr, oacc[mm]);
               if (Elem<T>::kSplit) oacc[mm] = Elem<T>::mma(pl, vfr, oacc[mm]);
             }
           }
-        }
+        });
       });
 
+  if constexpr (SPLIT) {
+    // the waves' partial outputs, added in wave order by wave 0 (the tile buffers are free: the sweep ended on a
+    // barrier)
+    float* red = reinterpret_cast<float*>(smem);  // [kWaves][NM * 16][64]
+#pragma unroll
+    for (int mm = 0; mm < NM; ++mm)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) red[(q.wave * NM * 16 + mm * 16 + e) * 64 + q.lane] = oacc[mm][e];
+    __syncthreads();
+    if (q.wave != 0) return;
+#pragma unroll
+    for (int mm = 0; mm < NM; ++mm)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        float v = 0.f;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) v += red[(w * NM * 16 + mm * 16 + e) * 64 + q.lane];
+        oacc[mm][e] = v;
+      }
+  }
   // oacc[mm][4g + r] of lane l is O[q0 + 8g + 4*(l/32) + r][32 mm + l%32]
 #pragma unroll
   for (int mm = 0; mm < NM; ++mm) {
@@ -346,23 +442,42 @@ __device__ __forceinline__ void fwd_block(const FwdArgs& A, int bh_, int blk_, c
     atomicAdd(&A.stats[ENTMAX_STAT_FWD_QK_PV], (unsigned long long)n_qk_pv);
     atomicAdd(&A.stats[ENTMAX_STAT_FWD_PV_TILES], (unsigned long long)n_pv);
     atomicAdd(&A.stats[ENTMAX_STAT_FWD_EVAL_TILES], (unsigned long long)n_eval);
-    if (q.wave == 0) {
+    if (q.wave == 0 && (!SPLIT || rg_ == 0)) {
       atomicAdd(&A.stats[ENTMAX_STAT_FWD_SOLVE_SWEEPS], (unsigned long long)n_sweeps);
       atomicAdd(&A.stats[ENTMAX_STAT_FWD_BLOCKS], 1ull);
     }
   }
 }
 
+// workgroups that cover either way of sharing the blocks out
+inline int fwd_workgroups(int nheads, int nqb, bool flags) {
+  const int npairs = nheads * ((nqb + 1) >> 1);
+  if (!flags) return npairs;
+  const long long split = (long long)kWaves * (nheads * (long long)nqb < kSplitMaxBlocks ? nheads * nqb : kSplitMaxBlocks);
+  return npairs > split ? npairs : (int)split;
+}
+
 template <typename T, int D, int AM, bool BIAS>
 __global__ __launch_bounds__(kThreads) void fwd_kernel(FwdArgs A) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  const PairItem it = pair_item(A.nqb);
+  const int nheads = A.g.B * A.g.H, npairs = nheads * ((A.nqb + 1) >> 1);
+  const int nflagged = A.dense_count ? __builtin_amdgcn_readfirstlane(A.dense_count[0]) : kSplitMaxBlocks + 1;
+  if (nflagged <= kSplitMaxBlocks) {
+    // one workgroup per (flagged block, 32-row group); the blocks' numbers follow the count
+    const int slot = blockIdx.x / kWaves;
+    if (slot >= nflagged) return;
+    const int item = __builtin_amdgcn_readfirstlane(A.dense_count[1 + slot]);
+    fwd_block<T, D, AM, BIAS, true>(A, item / A.nqb, item % A.nqb, blockIdx.x % kWaves, smem);
+    return;
+  }
+  if ((int)blockIdx.x >= npairs) return;
+  const PairItem it = pair_item(A.nqb, blockIdx.x, npairs);
   for (int part = 0; part < 2; ++part) {
     const int blk = part ? it.second : it.first;
     if (blk < 0) break;
     if (A.dense_flag && __builtin_amdgcn_readfirstlane(A.dense_flag[it.bh * A.nqb + blk]) == 0) continue;
     __syncthreads();
-    fwd_block<T, D, AM, BIAS>(A, it.bh, blk, smem);
+    fwd_block<T, D, AM, BIAS, false>(A, it.bh, blk, 0, smem);
   }
 }
 

@@ -55,7 +55,8 @@ struct FwdSparseArgs {
   void* cells;      // sweep scratch: one CellBuf<kCandCap> per workgroup of the list sweep's grid
   int* lcnt;        // [B*H*Nq][2] list lengths
   float2* bounds;   // [B*H*Nq] (tau_lb, right end of the bracket)
-  int* dense_flag;  // [B*H*nqb] 1: block left to the tiled kernel
+  int* dense_flag;  // [B*H*nqb] 1: block left to the tiled kernel; behind them: how many are set (zeroed by the
+                    // list kernel, counted by the finish kernel), then the first kSplitMaxBlocks flagged blocks' numbers
   unsigned long long* stats;
   int nqb;
   TransposeRide ride;  // V^T copies for the tiled kernel, as extra workgroups of the finish launch
@@ -343,6 +344,7 @@ template <typename T, int D, int AM, bool BIAS>
 __global__ __launch_bounds__(kThreads, (ListCfg<T, D>::kOcc)) void fwd_lists_kernel(FwdSparseArgs A) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const PairItem it = pair_item(A.nqb);
+  if (blockIdx.x == 0 && threadIdx.x == 0) A.dense_flag[A.g.B * A.g.H * A.nqb] = 0;
   if (A.kcount) {
     // this workgroup's share of its head's per-key counters starts at zero for the finish kernel
     const int npair = (A.nqb + 1) >> 1, pp = A.nqb - 1 - it.first;
@@ -466,6 +468,11 @@ __global__ __launch_bounds__(kThreads) void fwd_finish_kernel(FwdSparseArgs A) {
   for (int e = 0; e < kEarly; ++e) early[e] = mylist[e * kListStride];
   if (block_dense != 0) {  // the tiled kernel owns this block, and so do the backward's tiled kernels
     if (A.list && threadIdx.x == 0) A.bwd_flag[rl.bh * A.nqb + rl.qb] = 1;
+    if (threadIdx.x == 0) {
+      int* count = A.dense_flag + g.B * g.H * A.nqb;
+      const int slot = atomicAdd(count, 1);
+      if (slot < kSplitMaxBlocks) count[1 + slot] = rl.bh * A.nqb + rl.qb;
+    }
     return;
   }
   uint2* suplist = A.list ? A.list + list_entry<kBwdCap>(rl.bh, A.nqb, rl.qb, threadIdx.x >> 6, threadIdx.x & 63) : nullptr;

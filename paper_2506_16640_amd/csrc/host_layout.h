@@ -92,7 +92,7 @@ inline Layout make_layout(const entmax_attn_params* p) {
   L.off_flcnt = L.off_cand + align_up(bh * (size_t)L.nqb * kThreads * kCandCap * 8);
   L.off_bounds = L.off_flcnt + align_up(bh * (size_t)p->Nq * 2 * sizeof(int));
   L.off_flags = L.off_bounds + align_up(bh * (size_t)p->Nq * 2 * sizeof(float));
-  L.off_fcells = L.off_flags + align_up(bh * (size_t)L.nqb * sizeof(int));
+  L.off_fcells = L.off_flags + align_up((bh * (size_t)L.nqb + 1 + kSplitMaxBlocks) * sizeof(int));  // flags, their count, flagged blocks
   L.off_fknorm = L.off_fcells + align_up(list_groups * cell_bytes_per_workgroup(kCandCap));
   L.total_fwd = L.off_fknorm + align_up(bh * sizeof(float));  // the heads' largest key norms (distance bias only)
   // the `saved` buffer: the rows' support lists (kBwdCap slots per lane of every 128-row block, slot-major per

@@ -51,7 +51,9 @@ struct QCtx {
   int kt_first;       // first key tile some row of the workgroup / of the wave can have a non-zero probability in
   int kt_first_wave;
 
-  __device__ __forceinline__ void init(const Geom& g, const void* Q, int bh_, int qb_) {
+  // rg >= 0: every wave of the workgroup takes row group rg (rows 32 rg .. 32 rg + 31) of the block -- the waves
+  // then share out the keys (split mode of the tiled forward); rg < 0: wave w takes row group w
+  __device__ __forceinline__ void init(const Geom& g, const void* Q, int bh_, int qb_, int rg = -1) {
     tid = threadIdx.x;
     wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps everything derived from it scalar
     lane = tid & 63;
@@ -64,12 +66,12 @@ struct QCtx {
     qb = uni(qb_);
     b = uni(bh / g.H);
     h = uni(bh % g.H);
-    q0 = uni(qb * kBlockRows + wave * 32);
+    q0 = uni(qb * kBlockRows + (rg >= 0 ? rg : wave) * 32);
     i = q0 + li;
     valid = i < g.Nq;
     lim = valid ? row_limit(g, i) : 0;
-    int last_blk = min(g.Nq, (qb + 1) * kBlockRows) - 1;
-    block_lim = uni(row_limit(g, last_blk));
+    int last_blk = min(g.Nq, rg >= 0 ? q0 + 32 : (qb + 1) * kBlockRows) - 1;
+    block_lim = uni(last_blk >= q0 || rg < 0 ? row_limit(g, last_blk) : 0);
     ntiles = uni((block_lim + KT - 1) / KT);
     wave_lim_min = uni(q0 < g.Nq ? row_limit(g, q0) : 0);
     wave_lim_max = uni(q0 < g.Nq ? row_limit(g, min(g.Nq, q0 + 32) - 1) : 0);
@@ -224,9 +226,9 @@ struct QCtx {
 struct PairItem {
   int bh, first, second;
 };
-__device__ __forceinline__ PairItem pair_item(int nblk) {
+__device__ __forceinline__ PairItem pair_item(int nblk, int block = blockIdx.x, int total = gridDim.x) {
   const int npair = (nblk + 1) >> 1;
-  const int item = xcd_remap(blockIdx.x, gridDim.x);
+  const int item = xcd_remap(block, total);
   PairItem it;
   it.bh = __builtin_amdgcn_readfirstlane(item / npair);
   const int pp = __builtin_amdgcn_readfirstlane(item % npair);
@@ -244,6 +246,9 @@ struct Slot {
 // double-buffered LDS ring and calls body(kt, tiles) on each; `tiles` points at
 // NSLOT consecutive tiles.  Bit s of TMASK says slot s is a transposed copy.
 // All threads of the workgroup must call this together.
+template <int S>
+using Set = std::integral_constant<int, S>;  // a register set of the staging (see Stage), as a compile-time argument
+
 struct NeverAbort {
   __device__ __forceinline__ bool operator()(int) const { return false; }
 };
@@ -251,17 +256,23 @@ struct NeverAbort {
 // abort(kt), evaluated by every thread at the start of the iteration that processes tile kt, may end
 // the sweep after that tile.  It must be workgroup-uniform: it may only read state that was complete
 // before the barrier that ended the previous iteration.
-template <typename C, typename T, int D, int NSLOT, int TMASK, class Needed, class Body, class Abort = NeverAbort>
+// DEPTH: tiles in flight from global memory while one is computed on (register sets per thread).  One is
+// enough where several workgroups share a compute unit and hide each other's waits; a workgroup that has a
+// compute unit (nearly) to itself needs two, or every tile costs a full memory round trip.  DEPTH 2 takes no
+// abort predicate.
+template <typename C, typename T, int D, int NSLOT, int TMASK, int DEPTH = 1, class Needed, class Body,
+          class Abort = NeverAbort>
 __device__ __forceinline__ void sweep_tiles(char* smem, const Slot* slots, int ntiles, int Nk, int tid, Needed needed,
                                             Body body, Abort abort = Abort()) {
+  static_assert(DEPTH == 1 || (DEPTH == 2 && std::is_same<Abort, NeverAbort>::value), "see above");
   constexpr int KT = C::KT;
   constexpr int TB = C::kTileBytes;
   using Tile0 = typename std::conditional<(TMASK & 1) != 0, typename C::XtTile, typename C::KTile>::type;
   using Tile1 = typename std::conditional<(TMASK & 2) != 0, typename C::XtTile, typename C::KTile>::type;
   using Tile2 = typename std::conditional<(TMASK & 4) != 0, typename C::XtTile, typename C::KTile>::type;
-  Stage<Tile0> s0;
-  Stage<Tile1> s1;
-  Stage<Tile2> s2;
+  Stage<Tile0, kThreads, DEPTH> s0;
+  Stage<Tile1, kThreads, DEPTH> s1;
+  Stage<Tile2, kThreads, DEPTH> s2;
   s0.init(slots[0].row_bytes, tid);
   if constexpr (NSLOT > 1) s1.init(slots[1].row_bytes, tid);
   if constexpr (NSLOT > 2) s2.init(slots[2].row_bytes, tid);
@@ -270,33 +281,38 @@ __device__ __forceinline__ void sweep_tiles(char* smem, const Slot* slots, int n
   auto tile_ptr = [&](int s, bool tr, int kt) {
     return slots[s].base + (tr ? (long long)kt * KT * (long long)sizeof(T) : (long long)kt * KT * slots[s].row_bytes);
   };
-  auto fetch = [&](int kt) {
+  auto fetch = [&](int kt, auto set_) {
+    constexpr int set = decltype(set_)::value;
     const int rows_left = Nk - kt * KT;
     const bool full = rows_left >= KT;  // uniform
     if constexpr ((TMASK & 1) != 0) {
-      s0.fetch_full(tile_ptr(0, true, kt));
+      s0.fetch_full(tile_ptr(0, true, kt), set);
     } else {
-      if (full) s0.fetch_full(tile_ptr(0, false, kt)); else s0.fetch(tile_ptr(0, false, kt), rows_left, slots[0].row_bytes);
+      if (full) s0.fetch_full(tile_ptr(0, false, kt), set);
+      else s0.fetch(tile_ptr(0, false, kt), rows_left, slots[0].row_bytes, set);
     }
     if constexpr (NSLOT > 1) {
       if constexpr ((TMASK & 2) != 0) {
-        s1.fetch_full(tile_ptr(1, true, kt));
+        s1.fetch_full(tile_ptr(1, true, kt), set);
       } else {
-        if (full) s1.fetch_full(tile_ptr(1, false, kt)); else s1.fetch(tile_ptr(1, false, kt), rows_left, slots[1].row_bytes);
+        if (full) s1.fetch_full(tile_ptr(1, false, kt), set);
+        else s1.fetch(tile_ptr(1, false, kt), rows_left, slots[1].row_bytes, set);
       }
     }
     if constexpr (NSLOT > 2) {
       if constexpr ((TMASK & 4) != 0) {
-        s2.fetch_full(tile_ptr(2, true, kt));
+        s2.fetch_full(tile_ptr(2, true, kt), set);
       } else {
-        if (full) s2.fetch_full(tile_ptr(2, false, kt)); else s2.fetch(tile_ptr(2, false, kt), rows_left, slots[2].row_bytes);
+        if (full) s2.fetch_full(tile_ptr(2, false, kt), set);
+        else s2.fetch(tile_ptr(2, false, kt), rows_left, slots[2].row_bytes, set);
       }
     }
   };
-  auto commit = [&](char* buf) {
-    s0.commit(buf);
-    if constexpr (NSLOT > 1) s1.commit(buf + TB);
-    if constexpr (NSLOT > 2) s2.commit(buf + 2 * TB);
+  auto commit = [&](char* buf, auto set_) {
+    constexpr int set = decltype(set_)::value;
+    s0.commit(buf, set);
+    if constexpr (NSLOT > 1) s1.commit(buf + TB, set);
+    if constexpr (NSLOT > 2) s2.commit(buf + 2 * TB, set);
   };
   auto next_needed = [&](int kt) {
     while (kt < ntiles && !needed(kt)) ++kt;
@@ -304,20 +320,49 @@ __device__ __forceinline__ void sweep_tiles(char* smem, const Slot* slots, int n
   };
 
   int kt = next_needed(0);
-  if (kt < ntiles) {
-    fetch(kt);
-    commit(smem);
-  }
-  __syncthreads();
-  int cur = 0;
-  while (kt < ntiles) {
-    int nxt = abort(kt) ? ntiles : next_needed(kt + 1);
-    if (nxt < ntiles) fetch(nxt);
-    body(kt, smem + cur * (NSLOT * TB));
-    if (nxt < ntiles) commit(smem + (cur ^ 1) * (NSLOT * TB));
+  if constexpr (DEPTH == 1) {
+    if (kt < ntiles) {
+      fetch(kt, Set<0>());
+      commit(smem, Set<0>());
+    }
     __syncthreads();
-    cur ^= 1;
-    kt = nxt;
+    int cur = 0;
+    while (kt < ntiles) {
+      int nxt = abort(kt) ? ntiles : next_needed(kt + 1);
+      if (nxt < ntiles) fetch(nxt, Set<0>());
+      body(kt, smem + cur * (NSLOT * TB));
+      if (nxt < ntiles) commit(smem + (cur ^ 1) * (NSLOT * TB), Set<0>());
+      __syncthreads();
+      cur ^= 1;
+      kt = nxt;
+    }
+  } else {
+    // tile kt is in LDS, tile nxt on its way in one register set; the other set takes the tile after that
+    // before the work on kt starts, and set `arrived` goes to LDS when that work is done
+    int nxt = ntiles;
+    if (kt < ntiles) {
+      fetch(kt, Set<0>());
+      nxt = next_needed(kt + 1);
+      if (nxt < ntiles) fetch(nxt, Set<1>());
+      commit(smem, Set<0>());
+    }
+    __syncthreads();
+    int cur = 0;
+    auto step = [&](auto arrived, auto free_set) {
+      const int nxt2 = nxt < ntiles ? next_needed(nxt + 1) : ntiles;
+      if (nxt2 < ntiles) fetch(nxt2, free_set);
+      body(kt, smem + cur * (NSLOT * TB));
+      if (nxt < ntiles) commit(smem + (cur ^ 1) * (NSLOT * TB), arrived);
+      __syncthreads();
+      cur ^= 1;
+      kt = nxt;
+      nxt = nxt2;
+    };
+    while (kt < ntiles) {
+      step(Set<1>(), Set<0>());
+      if (kt >= ntiles) break;
+      step(Set<0>(), Set<1>());
+    }
   }
 }
 

@@ -12,7 +12,8 @@ namespace {
 
 template <typename T, int D, int AM, bool BIAS>
 bool launch_fwd_main(const FwdArgs& a, int nblocks, hipStream_t st) {
-  size_t smem = 4 * (size_t)QCtx<T, D, FwdTile<T>::value>::kTileBytes + (size_t)(kWaves + 1) * a.mask_words * 4 + 64;
+  size_t smem = 4 * (size_t)QCtx<T, D, FwdTile<T>::value>::kTileBytes + (size_t)(kWaves + 1) * a.mask_words * 4 +
+                kWaves * 64 * 4 * sizeof(float) + 64;
   constexpr auto kern = fwd_kernel<T, D, AM, BIAS>;
   if (!ensure_dynamic_lds<kern>(smem)) return false;
   hipLaunchKernelGGL(kern, dim3((unsigned)nblocks), dim3(kThreads), smem, st, a);
@@ -169,7 +170,9 @@ int run_fwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
   a.nqb = L.nqb;
   a.mask_words = L.mask_words;
   a.dense_flag = lists ? dense_flag : nullptr;
-  if (!launch_fwd_am<T, D, BIAS>(a, alpha_mode(p->alpha), npairs, st)) return ENTMAX_ATTN_LAUNCH_FAILED;
+  a.dense_count = lists ? dense_flag + (size_t)p->B * p->H * L.nqb : nullptr;
+  const int nwg = fwd_workgroups(p->B * p->H, L.nqb, lists);
+  if (!launch_fwd_am<T, D, BIAS>(a, alpha_mode(p->alpha), nwg, st)) return ENTMAX_ATTN_LAUNCH_FAILED;
   record(ev, ENTMAX_FWD_PHASE_TILED + 1, st);
   return ENTMAX_ATTN_OK;
 }
