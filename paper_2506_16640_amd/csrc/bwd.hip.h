@@ -108,6 +108,7 @@ __device__ __forceinline__ void bwd_dq_block(const BwdArgs& A, int bh_, int blk_
   unsigned n_tiles = 0, n_vis = 0;
 
   auto needed = [&](int kt) { return q.tile_in_window(kt); };
+  const bool plain = __ballot(!live) == 0ull;  // every row of the wave exists and sees a key
   sweep_tiles<C, T, D, 3, 4>(tiles, slots, q.ntiles, g.Nk, q.tid, needed, [&](int kt, const char* tl) {
     if (!q.tile_in_wave_window(kt)) return;
     const uint32_t act = q.visible_bits(kt);
@@ -120,14 +121,25 @@ __device__ __forceinline__ void bwd_dq_block(const BwdArgs& A, int bh_, int blk_
       const bool masked = j0 + 32 > q.wave_lim_min;
       const int rel = q.lim - j0;
       float x[16];
-      bool any = false;
+      bool any;
+      if (plain && !masked) {
+        // every row of the wave sees every key of the block: no select per score
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        bool vis = live && (!masked || q.key_of(e) < rel);
-        float xp = fmaf(acc[e], q.a, -tau);
-        x[e] = vis ? fmaxf(xp, 0.f) : 0.f;
-        acc[e] = vis ? acc[e] : 0.f;
-        any = any || (x[e] > 0.f);
+        for (int e = 0; e < 16; ++e) x[e] = fmaxf(fmaf(acc[e], q.a, -tau), 0.f);
+        float xm = fmaxf(x[0], x[1]);
+#pragma unroll
+        for (int e = 2; e < 16; e += 2) xm = fmaxf(fmaxf(xm, x[e]), x[e + 1]);
+        any = xm > 0.f;
+      } else {
+        any = false;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          bool vis = live && (!masked || q.key_of(e) < rel);
+          float xp = fmaf(acc[e], q.a, -tau);
+          x[e] = vis ? fmaxf(xp, 0.f) : 0.f;
+          acc[e] = vis ? acc[e] : 0.f;
+          any = any || (x[e] > 0.f);
+        }
       }
       if (__ballot(any) == 0ull) continue;
       ++n_tiles;
@@ -150,7 +162,8 @@ __device__ __forceinline__ void bwd_dq_block(const BwdArgs& A, int bh_, int blk_
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
         float gg = pow_rm1<AM>(x[e], r);
-        float gd = (x[e] > 0.f) ? gg * dp[e] : 0.f;
+        // (g = 0 where x = 0, except for alpha = 2 whose g is the support indicator)
+        float gd = (AM == 2) ? ((x[e] > 0.f) ? dp[e] : 0.f) : gg * dp[e];
         Z += gg;
         N += gd;
         Aq = fmaf(gd, acc[e], Aq);
@@ -375,24 +388,48 @@ __device__ __forceinline__ void bwd_dkv_block(const BwdArgs& A, int bh_, int blk
 #pragma unroll
       for (int cc = 0; cc < NC; ++cc) s = Elem<T>::mma(NTile::frag(tl, sg * 32 + li, 2 * cc + hh), kf[cc], s);
       float x[16], mur[16], car[16];
-      bool any = false;
+      bool any;
+      // every key of the wave exists and lies at or before the group's first query: no select per score
+      const bool full = (jw0 + 32 <= g.Nk) && (!g.causal || jw0 + 31 <= i0 + off);
+      if (full && !biased) {
 #pragma unroll
-      for (int gq = 0; gq < 4; ++gq) {
-        int rl = sg * 32 + 8 * gq + 4 * hh;
-        f32x4_t t4 = *reinterpret_cast<const f32x4_t*>(rw + rl);
-        f32x4_t a4 = *reinterpret_cast<const f32x4_t*>(rw + QT + rl);
-        f32x4_t m4 = *reinterpret_cast<const f32x4_t*>(rw + 2 * QT + rl);
+        for (int gq = 0; gq < 4; ++gq) {
+          int rl = sg * 32 + 8 * gq + 4 * hh;
+          f32x4_t t4 = *reinterpret_cast<const f32x4_t*>(rw + rl);
+          f32x4_t a4 = *reinterpret_cast<const f32x4_t*>(rw + QT + rl);
+          f32x4_t m4 = *reinterpret_cast<const f32x4_t*>(rw + 2 * QT + rl);
 #pragma unroll
-        for (int rr = 0; rr < 4; ++rr) {
-          int e = 4 * gq + rr;
-          int i = i0 + 8 * gq + 4 * hh + rr;
-          bool vis = jvalid && (!g.causal || (j <= i + off));
-          float xp = fmaf(s[e], a4[rr], -t4[rr]);
-          if (biased) xp = fmaf(rw[3 * QT + rl + rr], (float)bias_dist(i + off, j), xp);
-          x[e] = vis ? fmaxf(xp, 0.f) : 0.f;
-          mur[e] = m4[rr];
-          car[e] = a4[rr];
-          any = any || (x[e] > 0.f);
+          for (int rr = 0; rr < 4; ++rr) {
+            int e = 4 * gq + rr;
+            x[e] = fmaxf(fmaf(s[e], a4[rr], -t4[rr]), 0.f);
+            mur[e] = m4[rr];
+            car[e] = a4[rr];
+          }
+        }
+        float xm = fmaxf(x[0], x[1]);
+#pragma unroll
+        for (int e = 2; e < 16; e += 2) xm = fmaxf(fmaxf(xm, x[e]), x[e + 1]);
+        any = xm > 0.f;
+      } else {
+        any = false;
+#pragma unroll
+        for (int gq = 0; gq < 4; ++gq) {
+          int rl = sg * 32 + 8 * gq + 4 * hh;
+          f32x4_t t4 = *reinterpret_cast<const f32x4_t*>(rw + rl);
+          f32x4_t a4 = *reinterpret_cast<const f32x4_t*>(rw + QT + rl);
+          f32x4_t m4 = *reinterpret_cast<const f32x4_t*>(rw + 2 * QT + rl);
+#pragma unroll
+          for (int rr = 0; rr < 4; ++rr) {
+            int e = 4 * gq + rr;
+            int i = i0 + 8 * gq + 4 * hh + rr;
+            bool vis = jvalid && (!g.causal || (j <= i + off));
+            float xp = fmaf(s[e], a4[rr], -t4[rr]);
+            if (biased) xp = fmaf(rw[3 * QT + rl + rr], (float)bias_dist(i + off, j), xp);
+            x[e] = vis ? fmaxf(xp, 0.f) : 0.f;
+            mur[e] = m4[rr];
+            car[e] = a4[rr];
+            any = any || (x[e] > 0.f);
+          }
         }
       }
       if (__ballot(any) == 0ull) continue;
@@ -400,13 +437,14 @@ __device__ __forceinline__ void bwd_dkv_block(const BwdArgs& A, int bh_, int blk
       f32x16_t dp = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int cc = 0; cc < NC; ++cc) dp = Elem<T>::mma(NTile::frag(tl + TB, sg * 32 + li, 2 * cc + hh), vf[cc], dp);
+      // ds = (alpha-1) dS: car holds (alpha-1) c_i; the factor goes into dK once, at the end.  g = 0 where x = 0,
+      // except for alpha = 2 whose g is the support indicator.
       float pp[16], ds[16];
-      const float inv_am1 = 1.0f / am1;
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
         pp[e] = pow_r<AM>(x[e], r);
         float gg = pow_rm1<AM>(x[e], r);
-        ds[e] = (x[e] > 0.f) ? gg * (dp[e] - mur[e]) * (car[e] * inv_am1) : 0.f;
+        ds[e] = gg * (dp[e] - mur[e]) * car[e];
       }
 #pragma unroll
       for (int cc = 0; cc < 2; ++cc) {
@@ -427,6 +465,7 @@ __device__ __forceinline__ void bwd_dkv_block(const BwdArgs& A, int bh_, int blk
   }
 
   // dk/dv[mm][4g + r] of lane l belongs to key jw0 + 8g + 4*(l/32) + r, feature 32 mm + l%32
+  const float inv_am1 = 1.0f / am1;
 #pragma unroll
   for (int mm = 0; mm < NM; ++mm) {
 #pragma unroll
@@ -434,7 +473,7 @@ __device__ __forceinline__ void bwd_dkv_block(const BwdArgs& A, int bh_, int blk
       int row = jw0 + 8 * (e >> 2) + 4 * hh + (e & 3);
       if (row < g.Nk) {
         long long idx = kv_base + (long long)row * g.kv_sn + mm * 32 + li;
-        Elem<T>::store(A.dK, idx, dk[mm][e]);
+        Elem<T>::store(A.dK, idx, dk[mm][e] * inv_am1);
         Elem<T>::store(A.dV, idx, dv[mm][e]);
       }
     }

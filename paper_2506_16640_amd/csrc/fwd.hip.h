@@ -183,11 +183,11 @@ template <typename T, int D>
 struct ListCfg {
   static constexpr int kTile = sizeof(T) == 2 ? (D == 64 ? 128 : 64) : 32;
   static constexpr int kOcc = (sizeof(T) == 2 && D == 128) ? 4 : 3;
+  // key tiles in flight (sweep_tiles).  Measured at B 4, H 12, n 4096, D 64: two in flight cost registers
+  // (spills at three workgroups per CU: 145 us against 139; no spills at two per CU: 188 us)
+  static constexpr int kDepth = 1;
   // cells per thread that the collecting sweep keeps in LDS (20 bytes each)
-#ifndef ENTMAX_LDS_CELLS
-#define ENTMAX_LDS_CELLS 4
-#endif
-  static constexpr int kLdsCells = kOcc == 4 ? 1 : ENTMAX_LDS_CELLS;
+  static constexpr int kLdsCells = kOcc == 4 ? 1 : 4;
   // dynamic LDS of a list-sweep kernel: two tile buffers, the flags, the cells
   static constexpr size_t kLdsBytes = 2 * (size_t)kTile * D * sizeof(T) + 64 + (size_t)kLdsCells * kThreads * 20;
 };

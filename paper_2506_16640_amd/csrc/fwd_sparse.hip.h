@@ -132,7 +132,7 @@ __device__ __forceinline__ bool collect_sweep(const C& q, const Geom& g, const v
   slots[0].base = reinterpret_cast<const char*>(reinterpret_cast<const T*>(K) + (long long)q.b * g.kv_sb +
                                                 (long long)q.h * g.kv_sh);
   slots[0].row_bytes = g.kv_sn * (long long)sizeof(T);
-  sweep_tiles<C, T, D, 1, 0>(
+  sweep_tiles<C, T, D, 1, 0, ListCfg<T, D>::kDepth>(
       tiles, slots, q.ntiles, g.Nk, q.tid, [&](int kt) { return q.tile_in_window(kt); },
       [&](int kt, const char* tl) {
         if (!q.tile_in_wave_window(kt)) return;
@@ -269,7 +269,7 @@ __device__ __forceinline__ void fwd_lists_block(const FwdSparseArgs& A, int bh_,
   // ---------------------------------------------- 1. row max and runner-up
   // m1 >= m2 are the two largest per-cell maxima seen by this lane: two distinct scores of the row
   float m1 = -kInf, m2 = -kInf;
-  sweep_tiles<C, T, D, 1, 0>(
+  sweep_tiles<C, T, D, 1, 0, ListCfg<T, D>::kDepth>(
       tiles, slots, q.ntiles, g.Nk, q.tid, [&](int kt) { return q.tile_in_window(kt); },
       [&](int kt, const char* tl) {
         if (!q.tile_in_wave_window(kt)) return;

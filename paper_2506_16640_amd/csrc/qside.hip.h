@@ -258,13 +258,13 @@ struct NeverAbort {
 // before the barrier that ended the previous iteration.
 // DEPTH: tiles in flight from global memory while one is computed on (register sets per thread).  One is
 // enough where several workgroups share a compute unit and hide each other's waits; a workgroup that has a
-// compute unit (nearly) to itself needs two, or every tile costs a full memory round trip.  DEPTH 2 takes no
-// abort predicate.
+// compute unit (nearly) to itself needs two, or every tile costs a full memory round trip.  With DEPTH 2 the
+// tile already on its way when abort(kt) turns true is still processed.
 template <typename C, typename T, int D, int NSLOT, int TMASK, int DEPTH = 1, class Needed, class Body,
           class Abort = NeverAbort>
 __device__ __forceinline__ void sweep_tiles(char* smem, const Slot* slots, int ntiles, int Nk, int tid, Needed needed,
                                             Body body, Abort abort = Abort()) {
-  static_assert(DEPTH == 1 || (DEPTH == 2 && std::is_same<Abort, NeverAbort>::value), "see above");
+  static_assert(DEPTH == 1 || DEPTH == 2, "one or two tiles in flight");
   constexpr int KT = C::KT;
   constexpr int TB = C::kTileBytes;
   using Tile0 = typename std::conditional<(TMASK & 1) != 0, typename C::XtTile, typename C::KTile>::type;
@@ -349,7 +349,7 @@ __device__ __forceinline__ void sweep_tiles(char* smem, const Slot* slots, int n
     __syncthreads();
     int cur = 0;
     auto step = [&](auto arrived, auto free_set) {
-      const int nxt2 = nxt < ntiles ? next_needed(nxt + 1) : ntiles;
+      const int nxt2 = (nxt < ntiles && !abort(kt)) ? next_needed(nxt + 1) : ntiles;
       if (nxt2 < ntiles) fetch(nxt2, free_set);
       body(kt, smem + cur * (NSLOT * TB));
       if (nxt < ntiles) commit(smem + (cur ^ 1) * (NSLOT * TB), arrived);
