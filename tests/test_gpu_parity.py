@@ -224,6 +224,22 @@ def test_backward_splits_a_head_between_the_paths(alpha, dtype, forward_path):
         assert st["bwd_support"] > 0 and st["bwd_dq_tiles"] > 0, st  # both paths worked on this one head
 
 
+@pytest.mark.parametrize("dtype,d,alpha", [("bf16", 64, 1.5), ("bf16", 128, 1.25), ("fp32", 64, 2.0), ("bf16", 64, 1.7)])
+@pytest.mark.parametrize("heads", [3, 70])
+def test_tiled_forward_shares_blocks_out_both_ways(dtype, d, alpha, heads, forward_path):
+    """Dense rows send every block to the tiled forward.  With 3 heads x 5 blocks it runs four workgroups to a
+    block (the waves of a workgroup share out the keys of one 32-row group and combine maxima, threshold sums and
+    outputs); with 70 x 5 = 350 blocks, more than the limit for that, it runs the blocks whole, in pairs.  Both
+    against the oracle, forward only (the backward does not depend on how the forward was shared out)."""
+    n = 577  # five blocks, a ragged last one; 18.03 key blocks of 32: the split's wave shares differ
+    data = _case(1, heads, n, n, d, dtype, "dense", seed=31)
+    g = gpu_run(data, alpha, dtype, bwd=False, stats=True)
+    r = oracle_run(data, alpha, bwd=False)
+    print(dtype, d, alpha, heads, compare(g, r, bwd=False, label=f"share-out {dtype} d{d} a{alpha} H{heads}"))
+    if forward_path == 0 and alpha <= 1.5:
+        assert g["stats"]["fwd_blocks"] == heads * 5, g["stats"]  # every block took the tiled kernel
+
+
 def test_randomised_small_configurations():
     """Forty seeded draws over the whole parameter space of the entry points (shapes with ragged tails, both
     element types and head dimensions, every alpha path, scale layouts, log-n modes, causal or not, distance bias
