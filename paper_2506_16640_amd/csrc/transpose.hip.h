@@ -44,20 +44,34 @@ __device__ __forceinline__ void transpose_perm_part(const TransposeJobs& jobs, i
   if (j0 >= npad) return;  // the grid covers the longest job
   const T* src = reinterpret_cast<const T*>(jb.X) + (long long)b * jb.sb + (long long)h * jb.sh;
   T* Xt = reinterpret_cast<T*>(jb.Xt);
-  for (int e = tid; e < 64 * D; e += kThreads) {
-    int row = e / D, col = e % D;
-    int j = j0 + row;
-    T v{};
-    if (j < N) v = src[(long long)j * sn + col];
-    tile[row][col] = v;
+  // 16-byte chunks both ways: rows of X come in whole chunks (the strides are multiples of 16 bytes), and a chunk
+  // of a row of Xt is kEpc consecutive positions, gathered from one column of the tile
+  constexpr int kEpc = 16 / (int)sizeof(T), kCpr = D / kEpc, kCpo = 64 / kEpc;
+  for (int c = tid; c < 64 * kCpr; c += kThreads) {
+    const int row = c / kCpr, ch = c % kCpr;
+    const int j = j0 + row;
+    u32x4_t v = {0u, 0u, 0u, 0u};
+    if (j < N) v = *reinterpret_cast<const u32x4_t*>(src + (long long)j * sn + ch * kEpc);
+    uint32_t* t = reinterpret_cast<uint32_t*>(&tile[row][ch * kEpc]);  // rows are 4-byte, not 16-byte, aligned
+    t[0] = v[0];
+    t[1] = v[1];
+    t[2] = v[2];
+    t[3] = v[3];
   }
   __syncthreads();
   T* dst = Xt + (long long)bh * D * npad + j0;
-  for (int e = tid; e < D * 64; e += kThreads) {
-    int dc = e >> 6, pos = e & 63;
-    int p = pos & 15;
-    int srow = (pos & ~15) + 8 * ((p & 7) >> 2) + 4 * (p >> 3) + (p & 3);
-    dst[(long long)dc * npad + pos] = tile[srow][dc];
+  for (int c = tid; c < D * kCpo; c += kThreads) {
+    const int dc = c / kCpo, pos0 = (c % kCpo) * kEpc;  // neighbouring lanes: neighbouring chunks of one row of Xt
+    T vals[kEpc];
+#pragma unroll
+    for (int e = 0; e < kEpc; ++e) {
+      const int pos = pos0 + e, p = pos & 15;
+      const int srow = (pos & ~15) + 8 * ((p & 7) >> 2) + 4 * (p >> 3) + (p & 3);
+      vals[e] = tile[srow][dc];
+    }
+    u32x4_t o;
+    __builtin_memcpy(&o, vals, 16);
+    *reinterpret_cast<u32x4_t*>(dst + (long long)dc * npad + pos0) = o;
   }
 }
 
