@@ -170,10 +170,15 @@ __device__ __forceinline__ bool solve_step(const RowSums& s, float r, float& tau
   return fin;
 }
 
-// keys per LDS tile of the forward kernel
-template <typename T>
+// Keys per LDS tile and waves per SIMD of the tiled forward kernel, as measured on a dense-regime workload
+// (B 4, H 12, n 4096, every block on this kernel): at D = 64, 64-key tiles leave room for three workgroups per CU
+// (168 registers, no spills) and run the threshold sweeps -- vector-ALU bound, so a third wave per SIMD fills the
+// gaps -- a fifth faster than 128-key tiles with two (0.88 against 1.10 ms); at D = 128 the register bound would
+// spill (1.83 against 1.11 ms at n 16384), so that case keeps 128-key tiles and one workgroup per CU.
+template <typename T, int D>
 struct FwdTile {
-  static constexpr int value = sizeof(T) == 2 ? 128 : 32;
+  static constexpr int value = sizeof(T) == 2 ? (D == 64 ? 64 : 128) : 32;
+  static constexpr int kOcc = (sizeof(T) == 2 && D == 64) ? 3 : 1;
 };
 
 // Keys per LDS tile and workgroups per CU of the list sweeps (fwd_sparse.hip.h, bwd_sparse.hip.h), as measured:
@@ -198,7 +203,7 @@ struct ListCfg {
 // workgroups with a quarter of the serial work each: for the case where only a few blocks need this kernel.
 template <typename T, int D, int AM, bool BIAS, bool SPLIT>
 __device__ __forceinline__ void fwd_block(const FwdArgs& A, int bh_, int blk_, int rg_, char* smem) {
-  using C = QCtx<T, D, FwdTile<T>::value, BIAS>;
+  using C = QCtx<T, D, FwdTile<T, D>::value, BIAS>;
   constexpr int KT = C::KT, NSB = C::NSB, NM = C::NM, TB = C::kTileBytes;
   // key tiles in flight (sweep_tiles): a split block has its compute unit nearly to itself
   constexpr int kFwdDepth = SPLIT ? 2 : 1;
@@ -458,7 +463,7 @@ inline int fwd_workgroups(int nheads, int nqb, bool flags) {
 }
 
 template <typename T, int D, int AM, bool BIAS>
-__global__ __launch_bounds__(kThreads) void fwd_kernel(FwdArgs A) {
+__global__ __launch_bounds__(kThreads, (FwdTile<T, D>::kOcc)) void fwd_kernel(FwdArgs A) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int nheads = A.g.B * A.g.H, npairs = nheads * ((A.nqb + 1) >> 1);
   const int nflagged = A.dense_count ? __builtin_amdgcn_readfirstlane(A.dense_count[0]) : kSplitMaxBlocks + 1;

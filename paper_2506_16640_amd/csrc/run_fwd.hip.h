@@ -12,7 +12,7 @@ namespace {
 
 template <typename T, int D, int AM, bool BIAS>
 bool launch_fwd_main(const FwdArgs& a, int nblocks, hipStream_t st) {
-  size_t smem = 4 * (size_t)QCtx<T, D, FwdTile<T>::value>::kTileBytes + (size_t)(kWaves + 1) * a.mask_words * 4 +
+  size_t smem = 4 * (size_t)QCtx<T, D, FwdTile<T, D>::value>::kTileBytes + (size_t)(kWaves + 1) * a.mask_words * 4 +
                 kWaves * 64 * 4 * sizeof(float) + 64;
   constexpr auto kern = fwd_kernel<T, D, AM, BIAS>;
   if (!ensure_dynamic_lds<kern>(smem)) return false;
