@@ -154,9 +154,15 @@ enum {
  *   out: O (dtype, written for every row), tau [B,H,Nq] fp32 (saved for the backward).
  *        A row with no visible key gets O = 0, tau = 0.
  *   stats: NULL or device uint64[ENTMAX_ATTN_NUM_STATS], added to.
- *   saved: NULL, or device memory of entmax_attn_saved_bytes(p) bytes, 256-byte aligned, owned by the
+ *   saved: NULL, or device memory of at least entmax_attn_saved_bytes(p) bytes, 256-byte aligned, owned by the
  *        caller: receives the rows' support lists (key, raw score) -- Sec. 2.2: the keys with non-zero
- *        probability -- for the backward, which then skips its own Q K^T sweep.  Opaque; valid only together with this call's tau and the same params and inputs.
+ *        probability -- for the backward, which then skips its own Q K^T sweep.  The lists are packed into a
+ *        pool that runs to the end of the buffer; the size the library asks for holds six entries per row on
+ *        average (under half the size of O at D = 64), and a larger buffer gives a larger pool.  A 128-row query
+ *        block that finds the pool used up, or has a half row with more than 16 support entries, is marked for
+ *        the backward's tiled kernels instead (same results up to rounding; slower).  When the pool runs out,
+ *        which blocks are marked depends on the order the workgroups arrive in.  Opaque; valid only together
+ *        with this call's tau and the same params, inputs and saved_bytes.
  *   saved_bytes: size of `saved` (ignored when saved is NULL); less than entmax_attn_saved_bytes(p) is
  *        refused with WORKSPACE_TOO_SMALL before anything is launched.
  *   workspace: device scratch of at least entmax_attn_workspace_bytes(p, 0)
@@ -189,7 +195,7 @@ int entmax_attn_fwd(const entmax_attn_params* p, const void* Q, const void* K, c
  *   saved: NULL, or the buffer the forward filled for these same inputs (read only).  With it the
  *        rows' supports are taken from the forward's lists; without it one Q K^T sweep at tau rebuilds them.  Same results either way up
  *        to the summation order inside a row.
- *   saved_bytes: size of `saved`, checked as in the forward.
+ *   saved_bytes: size of `saved`, checked as in the forward; pass the value the forward was given.
  *   workspace: at least entmax_attn_workspace_bytes(p, 1) bytes, 256-byte aligned.
  * `path` selects as in the forward: 0 = support lists per row and per key for the 128-row query blocks
  * whose rows have few non-zero probabilities, tiled kernels for the other blocks; 1 = tiled kernels only.
@@ -263,8 +269,8 @@ size_t entmax_scale_proj_workspace_bytes(const entmax_scale_proj_params* p);
  * these parameters; 0 if the parameters are invalid. Host-only, no GPU call. */
 size_t entmax_attn_workspace_bytes(const entmax_attn_params* p, int is_bwd);
 
-/* Bytes of the optional `saved` buffer that carries the forward's lists to the backward;
- * 0 if the parameters are invalid. Host-only, no GPU call. */
+/* Smallest size of the optional `saved` buffer that carries the forward's lists to the backward (a larger
+ * one holds longer lists, see entmax_attn_fwd); 0 if the parameters are invalid. Host-only, no GPU call. */
 size_t entmax_attn_saved_bytes(const entmax_attn_params* p);
 
 /* Validates parameters without touching the GPU: returns the status the

@@ -166,7 +166,8 @@ def saved_bytes(params):
 
 
 def new_saved(params, device="cuda"):
-    """Buffer that carries the forward's lists to the backward (pass it to both as `saved`)."""
+    """Buffer that carries the forward's lists to the backward (pass it to both as `saved`), of the size the library
+    asks for; a larger uint8 tensor holds longer lists."""
     return torch.empty(max(saved_bytes(params), 256), dtype=torch.uint8, device=device)
 
 
@@ -193,7 +194,7 @@ def entmax_attn_fwd(q, k, v, alpha=1.5, beta=None, gamma=None, delta=1.0, causal
     """O, tau = entmax attention forward.  q [B,H,Nq,D], k,v [B,H,Nk,D] on the GPU, bf16 or fp32;
     beta,gamma fp32 [H] or [B,H,Nq] or None.  stats: optional uint64/int64 device tensor [NUM_STATS] (added to).
     path: 0 automatic, 1 tiled kernel only.  phase_events: optional list of FWD_NUM_PHASES + 1 hipEvent_t handles.
-    saved: optional uint8 device tensor of saved_bytes(params) bytes, filled for the backward.
+    saved: optional uint8 device tensor of at least saved_bytes(params) bytes, filled for the backward.
     alibi_slopes: optional fp32 [H] slopes of the linear distance bias (0 = head without bias); bias_mode 0 puts the
     bias inside the ASEntmax scale, 1 outside."""
     p = make_params(q, k, alpha, delta, causal, beta, logn_mode, path, bias_mode)

@@ -44,8 +44,12 @@ struct BwdSparseArgs {
   float* dscale;       // [B*H*Nq]
   // The rows' support lists, their lengths and the block flags: written by bwd_lists_kernel into the workspace,
   // or the forward's (in the `saved` buffer, read only here).
-  uint2* list;         // [B*H*nqb*4 row groups][kBwdCap][64 lanes], see list_entry(): (key index, raw dot product bits)
-  int* lcnt;           // [B*H*Nq][2] entries per half row
+  uint2* list;         // (key index, raw dot product bits) of the listed entries.  Workspace lists:
+                       // [B*H*nqb*4 row groups][kBwdCap][64 lanes], see list_entry().  The forward's (packed = 1): the
+                       // pool of the `saved` buffer, a half row's entries next to each other.
+  int* lcnt;           // [B*H*Nq][2] entries per half row; packed: (place of the first entry in the pool) << 5 | entries
+  int packed;
+  long long pool_cap;  // packed: entries the pool holds (places beyond it are never followed)
   int* block_flag;     // [B*H*nqb] 1 when the block cannot take the list path (a list too long, or no lists)
   void* cells;         // sweep scratch: one CellBuf<kBwdCap> per workgroup of the list sweep's grid
   int* kcount;         // [B*H*Nk] listed entries per key = size of the key's segment (key_offsets_kernel)
@@ -134,10 +138,26 @@ __global__ __launch_bounds__(kThreads, D == 64 ? 2 : 1) void bwd_rows_kernel(Bwd
   const float tau_raw = A.tau[row_idx];
   const int cnt_raw = A.lcnt[row_idx * 2 + rl.hh];
   const float tau = live ? tau_raw : 0.f;
-  const int cnt = live ? min(cnt_raw, kBwdCap) : 0;
   const long long q_base = (long long)rl.b * g.q_sb + (long long)rl.h * g.q_sh;
   const long long kv_base = (long long)rl.b * g.kv_sb + (long long)rl.h * g.kv_sh;
-  const uint2* rdlist = A.list + list_entry<kBwdCap>(rl.bh, A.nqb, rl.qb, threadIdx.x >> 6, threadIdx.x & 63);
+  // where this half row's entries are, and how far apart
+  const uint2* rdlist;
+  int cnt_list, lstride;
+  if (A.packed) {
+    long long off = (long long)((unsigned)cnt_raw >> 5);
+    cnt_list = cnt_raw & 31;
+    if (off + cnt_list > A.pool_cap) {  // not a place the forward wrote (a flagged block's words hold anything)
+      off = 0;
+      cnt_list = 0;
+    }
+    rdlist = A.list + off;
+    lstride = 1;
+  } else {
+    rdlist = A.list + list_entry<kBwdCap>(rl.bh, A.nqb, rl.qb, threadIdx.x >> 6, threadIdx.x & 63);
+    cnt_list = cnt_raw;
+    lstride = kListStride;
+  }
+  const int cnt = live ? min(cnt_list, kBwdCap) : 0;
   const T* Kbh = reinterpret_cast<const T*>(A.K) + kv_base;
   const T* Vbh = reinterpret_cast<const T*>(A.V) + kv_base;
 
@@ -150,11 +170,12 @@ __global__ __launch_bounds__(kThreads, D == 64 ? 2 : 1) void bwd_rows_kernel(Bwd
     for (int t = 0; t < DH; ++t) dov[t] = 0.f;
   }
   unsigned n_entries = 0;
-  // the first entries are requested before the list length is known (the slots exist whatever they hold)
+  // the first entries are requested whatever the list length is (the slots exist whatever they hold; the
+  // pool ends on kSavedPoolPad spare entries)
   constexpr int kEarly = 4;
   uint2 early[kEarly];
 #pragma unroll
-  for (int e = 0; e < kEarly; ++e) early[e] = rdlist[e * kListStride];
+  for (int e = 0; e < kEarly; ++e) early[e] = rdlist[e * lstride];
   if (head_dense != 0) return;  // the tiled kernels own this block
 
   auto finish = [&](auto ne_tag) {
@@ -167,7 +188,7 @@ __global__ __launch_bounds__(kThreads, D == 64 ? 2 : 1) void bwd_rows_kernel(Bwd
       if (e < kEarly)
         en = early[e];
       else if (e < cnt)
-        en = rdlist[e * kListStride];
+        en = rdlist[e * lstride];
       jv[e] = (e < cnt) ? en.x : 0u;
       dv[e] = (e < cnt) ? __uint_as_float(en.y) : -kInf;
     }

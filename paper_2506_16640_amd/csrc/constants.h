@@ -11,6 +11,25 @@ constexpr int kBlockRows = 128;  // rows (queries or keys) owned by a workgroup:
 constexpr int kCandCap = 32;     // candidate entries per lane = per half row (forward lists)
 constexpr int kBwdCap = 16;      // support entries per lane = per half row (the lists the backward works from)
 constexpr int kListStride = 64;  // lists are stored slot-major per wave: entry s of the 64 lanes together
+// The `saved` buffer packs the rows' support lists into a pool: the size the library asks for holds this many
+// entries per row on average (a larger buffer gives a larger pool), at least kSavedPoolFloor (one block's worst
+// case), plus kSavedPoolPad entries behind the end that speculative reads may touch.
+constexpr int kSavedPerRow = 6;
+constexpr int kSavedPoolFloor = kThreads * kBwdCap;
+constexpr int kSavedPoolPad = 4;
+// The pool is cut into up to kSavedSubPools equal parts with a cursor each, and the 32-row groups take their part
+// in turn (group number modulo the number of parts): pieces are handed out by a returning atomic, and atomics on
+// one address queue up behind each other (one cursor for the 6144 groups of a 4 x 12 x 4096 problem doubled the
+// time of the kernel that fills the pool).  The cursors sit kSavedCursorStride bytes apart so that they do not
+// share a memory channel either.  Every part serves at least kSavedGroupsPerPart groups.
+constexpr int kSavedSubPools = 64;
+constexpr int kSavedCursorStride = 4352;
+constexpr int kSavedGroupsPerPart = 16;
+inline int saved_pool_parts(long long groups) {
+  int n = 1;
+  while (n < kSavedSubPools && groups / (2 * n) >= kSavedGroupsPerPart) n *= 2;
+  return n;
+}
 
 // Tiled forward behind the list kernels: up to this many flagged blocks run four workgroups to a block (a few long
 // blocks alone on the chip are bound by their own serial length), more run as block pairs (bound by throughput).

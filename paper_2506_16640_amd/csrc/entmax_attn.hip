@@ -14,11 +14,11 @@ using namespace entmax;
 namespace entmax {
 #define ENTMAX_FWD_SIG                                                                                                  \
   (const entmax_attn_params*, const Layout&, const void*, const void*, const void*, const float*, const float*,        \
-   const float*, void*, float*, char*, uint64_t*, char*, hipStream_t, void* const*)
+   const float*, void*, float*, char*, size_t, uint64_t*, char*, hipStream_t, void* const*)
 #define ENTMAX_BWD_SIG                                                                                                  \
   (const entmax_attn_params*, const Layout&, const void*, const void*, const void*, const void*, const float*,         \
-   const char*, const float*, const float*, const float*, void*, void*, void*, float*, float*, uint64_t*, char*,       \
-   hipStream_t, void* const*)
+   const char*, size_t, const float*, const float*, const float*, void*, void*, void*, float*, float*, uint64_t*,      \
+   char*, hipStream_t, void* const*)
 #define ENTMAX_EXTERN(T, D)                                   \
   extern template int run_fwd<T, D, false> ENTMAX_FWD_SIG;    \
   extern template int run_fwd<T, D, true> ENTMAX_FWD_SIG;     \
@@ -109,12 +109,12 @@ int fwd_checked(const entmax_attn_params* p, const void* Q, const void* K, const
   const bool bias = slopes != nullptr;
   if (p->dtype == ENTMAX_ATTN_BF16) {
     if (p->D == 64)
-      return fwd_dispatch<bf16_t, 64>(bias, p, L, Q, K, V, beta, gamma, slopes, O, tau, sv, stats, ws, st, phase_events);
-    return fwd_dispatch<bf16_t, 128>(bias, p, L, Q, K, V, beta, gamma, slopes, O, tau, sv, stats, ws, st, phase_events);
+      return fwd_dispatch<bf16_t, 64>(bias, p, L, Q, K, V, beta, gamma, slopes, O, tau, sv, saved_bytes, stats, ws, st, phase_events);
+    return fwd_dispatch<bf16_t, 128>(bias, p, L, Q, K, V, beta, gamma, slopes, O, tau, sv, saved_bytes, stats, ws, st, phase_events);
   }
   if (p->D == 64)
-    return fwd_dispatch<float, 64>(bias, p, L, Q, K, V, beta, gamma, slopes, O, tau, sv, stats, ws, st, phase_events);
-  return fwd_dispatch<float, 128>(bias, p, L, Q, K, V, beta, gamma, slopes, O, tau, sv, stats, ws, st, phase_events);
+    return fwd_dispatch<float, 64>(bias, p, L, Q, K, V, beta, gamma, slopes, O, tau, sv, saved_bytes, stats, ws, st, phase_events);
+  return fwd_dispatch<float, 128>(bias, p, L, Q, K, V, beta, gamma, slopes, O, tau, sv, saved_bytes, stats, ws, st, phase_events);
 }
 
 }  // namespace
@@ -201,15 +201,15 @@ int entmax_attn_bwd(const entmax_attn_params* p, const void* Q, const void* K, c
   if (reinterpret_cast<uintptr_t>(alibi_slopes) & 3u) return ENTMAX_ATTN_MISALIGNED;
   if (p->dtype == ENTMAX_ATTN_BF16) {
     if (p->D == 64)
-      return bwd_dispatch<bf16_t, 64>(bias, p, L, Q, K, V, dO, tau, sv, beta, gamma, alibi_slopes, dQ, dK, dV, dbeta,
+      return bwd_dispatch<bf16_t, 64>(bias, p, L, Q, K, V, dO, tau, sv, saved_bytes, beta, gamma, alibi_slopes, dQ, dK, dV, dbeta,
                                       dgamma, stats, ws, st, phase_events);
-    return bwd_dispatch<bf16_t, 128>(bias, p, L, Q, K, V, dO, tau, sv, beta, gamma, alibi_slopes, dQ, dK, dV, dbeta,
+    return bwd_dispatch<bf16_t, 128>(bias, p, L, Q, K, V, dO, tau, sv, saved_bytes, beta, gamma, alibi_slopes, dQ, dK, dV, dbeta,
                                      dgamma, stats, ws, st, phase_events);
   }
   if (p->D == 64)
-    return bwd_dispatch<float, 64>(bias, p, L, Q, K, V, dO, tau, sv, beta, gamma, alibi_slopes, dQ, dK, dV, dbeta,
+    return bwd_dispatch<float, 64>(bias, p, L, Q, K, V, dO, tau, sv, saved_bytes, beta, gamma, alibi_slopes, dQ, dK, dV, dbeta,
                                    dgamma, stats, ws, st, phase_events);
-  return bwd_dispatch<float, 128>(bias, p, L, Q, K, V, dO, tau, sv, beta, gamma, alibi_slopes, dQ, dK, dV, dbeta,
+  return bwd_dispatch<float, 128>(bias, p, L, Q, K, V, dO, tau, sv, saved_bytes, beta, gamma, alibi_slopes, dQ, dK, dV, dbeta,
                                   dgamma, stats, ws, st, phase_events);
 }
 

@@ -47,8 +47,13 @@ struct FwdSparseArgs {
   void* O;
   float* tau;
   uint2* cand;      // [B*H*nqb*4 waves][kCandCap][64 lanes] (key index, raw dot product bits), see list_entry()
-  uint2* list;      // NULL, or [B*H*nqb*4 waves][kBwdCap][64 lanes]: the rows' supports for the backward
-  int* slcnt;       // with list: [B*H*Nq][2] support entries per half row
+  uint2* list;      // NULL, or the pool of the `saved` buffer the rows' supports are packed into for the backward:
+                    // every 32-row group takes one contiguous piece (lane after lane, entry after entry)
+  char* pool_cursor;       // with list: the pool's parts each have a 64-bit cursor (entries handed out so far, zeroed
+                           // by the list kernel), kSavedCursorStride bytes apart
+  int pool_parts;          // with list: parts the pool is cut into (a power of two)
+  long long pool_part_cap; // with list: entries a part holds
+  int* slcnt;       // with list: [B*H*Nq][2] per half row: (place of its first entry in the pool) << 5 | entries
   int* bwd_flag;    // with list: [B*H*nqb] 1: the backward cannot take its list path for this block
   int* kcount;      // with list: [B*H*Nk] support entries naming each key (zeroed by the list kernel, counted by
                     // the finish kernel): the sizes of the backward's key-major segments
@@ -344,7 +349,11 @@ template <typename T, int D, int AM, bool BIAS>
 __global__ __launch_bounds__(kThreads, (ListCfg<T, D>::kOcc)) void fwd_lists_kernel(FwdSparseArgs A) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const PairItem it = pair_item(A.nqb);
-  if (blockIdx.x == 0 && threadIdx.x == 0) A.dense_flag[A.g.B * A.g.H * A.nqb] = 0;
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    A.dense_flag[A.g.B * A.g.H * A.nqb] = 0;
+  }
+  if (blockIdx.x == 0 && A.pool_cursor && (int)threadIdx.x < A.pool_parts)
+    *reinterpret_cast<unsigned long long*>(A.pool_cursor + (size_t)threadIdx.x * kSavedCursorStride) = 0ull;
   if (A.kcount) {
     // this workgroup's share of its head's per-key counters starts at zero for the finish kernel
     const int npair = (A.nqb + 1) >> 1, pp = A.nqb - 1 - it.first;
@@ -475,7 +484,34 @@ __global__ __launch_bounds__(kThreads) void fwd_finish_kernel(FwdSparseArgs A) {
     }
     return;
   }
-  uint2* suplist = A.list ? A.list + list_entry<kBwdCap>(rl.bh, A.nqb, rl.qb, threadIdx.x >> 6, threadIdx.x & 63) : nullptr;
+  // The 32-row group's piece of the pool, sized before the supports are known: a half row's support is part of
+  // its candidate list, and a half row with more than kBwdCap support entries sends the block to the backward's
+  // tiled kernels anyway.  One returning atomic per wave, in flight together with the first list entries.
+  uint2* suplist = nullptr;
+  int sup_off = 0;
+  bool pool_full = false;
+  if (A.list) {
+    const int lane = threadIdx.x & 63;
+    const int want = min(cnt, kBwdCap);
+    int incl = want;  // inclusive running sum over the lanes
+#pragma unroll
+    for (int sft = 1; sft < 64; sft <<= 1) {
+      const int up = __shfl_up(incl, sft);
+      if (lane >= sft) incl += up;
+    }
+    const int total = __builtin_amdgcn_readlane(incl, 63);
+    // the groups take the pool's parts in turn
+    const int part = (int)(((unsigned)blockIdx.x * kWaves + (threadIdx.x >> 6)) & (unsigned)(A.pool_parts - 1));
+    unsigned long long base = 0ull;
+    if (lane == 0 && total > 0)
+      base = atomicAdd(reinterpret_cast<unsigned long long*>(A.pool_cursor + (size_t)part * kSavedCursorStride),
+                       (unsigned long long)total);
+    base = ((unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)(base >> 32)) << 32) |
+           (unsigned)__builtin_amdgcn_readfirstlane((int)base);
+    pool_full = total > 0 && base + (unsigned long long)total > (unsigned long long)A.pool_part_cap;
+    sup_off = pool_full ? 0 : (int)(part * A.pool_part_cap + (long long)base) + incl - want;
+    if (!pool_full) suplist = A.list + sup_off;
+  }
   int scnt = 0;  // support entries of this half row
 
   // NE: list entries per lane held in registers; chosen per wave from the longest list it holds.
@@ -523,7 +559,7 @@ __global__ __launch_bounds__(kThreads) void fwd_finish_kernel(FwdSparseArgs A) {
       if (p_own > 0.f) {
         ++n_support;
         if (suplist && scnt < kBwdCap) {
-          suplist[scnt * kListStride] = make_uint2(jv[e], __float_as_uint(dvv[e]));
+          suplist[scnt] = make_uint2(jv[e], __float_as_uint(dvv[e]));
           atomicAdd(&A.kcount[(long long)rl.bh * g.Nk + jv[e]], 1);
         }
         ++scnt;
@@ -552,7 +588,7 @@ __global__ __launch_bounds__(kThreads) void fwd_finish_kernel(FwdSparseArgs A) {
         if (p_own > 0.f) {
           ++n_support;
           if (suplist && scnt < kBwdCap) {
-            suplist[scnt * kListStride] = en;
+            suplist[scnt] = en;
             atomicAdd(&A.kcount[(long long)rl.bh * g.Nk + en.x], 1);
           }
           ++scnt;
@@ -575,7 +611,7 @@ __global__ __launch_bounds__(kThreads) void fwd_finish_kernel(FwdSparseArgs A) {
                 (long long)rl.i * g.q_sn + rl.hh * DH;
       store_row<T>(orow, DH, oacc);
       if (rl.hh == 0) A.tau[row_idx] = live ? tau : 0.f;
-      if (A.list) A.slcnt[row_idx * 2 + rl.hh] = min(scnt, kBwdCap);
+      if (A.list) A.slcnt[row_idx * 2 + rl.hh] = (int)(((unsigned)sup_off << 5) | (unsigned)(pool_full ? 0 : min(scnt, kBwdCap)));
     }
   };
   if (__ballot(cnt > 4) == 0ull)
@@ -584,8 +620,9 @@ __global__ __launch_bounds__(kThreads) void fwd_finish_kernel(FwdSparseArgs A) {
     finish(std::integral_constant<int, 8>());
 
   if (A.list) {
-    // a support longer than the backward's lists hold sends the block to the backward's tiled kernels
-    const int any_long = __syncthreads_or(scnt > kBwdCap ? 1 : 0);
+    // a support longer than the backward's lists hold, or no room left in the pool, sends the block to the
+    // backward's tiled kernels
+    const int any_long = __syncthreads_or((scnt > kBwdCap || pool_full) ? 1 : 0);
     if (threadIdx.x == 0) A.bwd_flag[rl.bh * A.nqb + rl.qb] = any_long ? 1 : 0;
   }
   if (A.stats) {

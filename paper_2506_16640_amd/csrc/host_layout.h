@@ -12,6 +12,7 @@
 namespace entmax {
 
 constexpr size_t kAlign = 256;
+constexpr unsigned long long kSavedPoolMost = (1ull << 27) - 1;  // entries a `saved` pool can address
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
@@ -24,8 +25,8 @@ struct Layout {
   long long q_sb, q_sh, q_sn, kv_sb, kv_sh, kv_sn;
   // workspace offsets
   size_t off_vt, off_cand, off_flcnt, off_bounds, off_flags, off_fcells, off_kt, off_qt, off_dot, off_mu, off_crow, off_dscale, off_mask, off_jlist, off_lcnt,
-      off_kcount, off_koffs, off_kcursor, off_csc_i, off_csc_pw, off_hflag, off_longkeys, off_bcells, off_fknorm, off_bknorm, sv_list, sv_lcnt,
-      sv_flags, sv_knorm, sv_kcount, total_saved, total_fwd, total_bwd;
+      off_kcount, off_koffs, off_kcursor, off_csc_i, off_csc_pw, off_hflag, off_longkeys, off_bcells, off_fknorm, off_bknorm, sv_cursor, sv_lcnt,
+      sv_flags, sv_knorm, sv_kcount, sv_pool, total_saved, total_fwd, total_bwd;
   size_t off_dec_cmax;  // decode kernels: score rows at offset 0, then the chunk maxima
   int dec_nks, dec_nchunks, dec_chunk;
   long long csc_cap;    // entries of the key-major arrays per head
@@ -95,16 +96,21 @@ inline Layout make_layout(const entmax_attn_params* p) {
   L.off_fcells = L.off_flags + align_up((bh * (size_t)L.nqb + 1 + kSplitMaxBlocks) * sizeof(int));  // flags, their count, flagged blocks
   L.off_fknorm = L.off_fcells + align_up(list_groups * cell_bytes_per_workgroup(kCandCap));
   L.total_fwd = L.off_fknorm + align_up(bh * sizeof(float));  // the heads' largest key norms (distance bias only)
-  // the `saved` buffer: the rows' support lists (kBwdCap slots per lane of every 128-row block, slot-major per
-  // 32-row group), their lengths, one flag per block for the backward, the heads' key norms, and the number of
-  // support entries that name each key
-  const size_t list_bytes = align_up(bh * (size_t)L.nqb * kThreads * kBwdCap * 8);
-  L.sv_list = 0;
-  L.sv_lcnt = list_bytes;
+  // the `saved` buffer: the pool's cursors, per half row (place, length) of its support list, one flag per block for the
+  // backward, the heads' key norms, the number of support entries that name each key, and behind them the pool
+  // the lists themselves are packed into (each 32-row group takes one contiguous piece, sized by its candidate
+  // counts).  The pool runs to the end of the caller's buffer; the size asked for holds kSavedPerRow entries per
+  // row on average.  A block whose group finds the pool used up is flagged and left to the backward's tiled kernels.
+  const size_t list_bytes = align_up(bh * (size_t)L.nqb * kThreads * kBwdCap * 8);  // (fixed-slot lists of the workspace)
+  L.sv_cursor = 0;
+  L.sv_lcnt = align_up((size_t)kSavedSubPools * kSavedCursorStride);
   L.sv_flags = L.sv_lcnt + align_up(bh * (size_t)p->Nq * 2 * sizeof(int));
   L.sv_knorm = L.sv_flags + align_up(bh * (size_t)L.nqb * sizeof(int));
   L.sv_kcount = L.sv_knorm + align_up(bh * sizeof(float));  // (the heads' largest key norms: distance bias only)
-  L.total_saved = L.sv_kcount + align_up(bh * (size_t)p->Nk * sizeof(int));  // support entries per key
+  L.sv_pool = L.sv_kcount + align_up(bh * (size_t)p->Nk * sizeof(int));  // support entries per key
+  size_t pool_entries = bh * (size_t)p->Nq * kSavedPerRow + kSavedPoolFloor;
+  if (pool_entries > kSavedPoolMost) pool_entries = kSavedPoolMost;  // places are 27-bit numbers
+  L.total_saved = L.sv_pool + align_up((pool_entries + kSavedPoolPad) * 8);
   // the decode kernels' score rows take the place of everything above
   L.dec_nks = L.dec_nchunks = L.dec_chunk = 0;
   L.off_dec_cmax = 0;
@@ -160,6 +166,14 @@ inline Layout make_layout(const entmax_attn_params* p) {
   o += align_up(bh * sizeof(float));
   L.total_bwd = o;
   return L;
+}
+
+// Entries the pool of a `saved` buffer of `bytes` bytes holds (beyond them: kSavedPoolPad entries that may be read
+// but never hold anything).  Places are packed into 27 bits next to the 5-bit length.
+inline long long saved_pool_entries(const Layout& L, size_t bytes) {
+  if (bytes < L.sv_pool + (size_t)kSavedPoolPad * 8) return 0;
+  const unsigned long long n = (bytes - L.sv_pool) / 8 - kSavedPoolPad;
+  return (long long)(n < kSavedPoolMost ? n : kSavedPoolMost);
 }
 
 inline size_t saved_bytes_of(const entmax_attn_params* p) {

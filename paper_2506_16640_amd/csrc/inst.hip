@@ -7,14 +7,14 @@ namespace entmax {
 template int run_fwd<ENTMAX_INST_T, ENTMAX_INST_D, ENTMAX_INST_BIAS != 0>(const entmax_attn_params*, const Layout&, const void*,
                                                                          const void*, const void*, const float*,
                                                                          const float*, const float*, void*, float*, char*,
-                                                                         uint64_t*, char*, hipStream_t, void* const*);
+                                                                         size_t, uint64_t*, char*, hipStream_t, void* const*);
 }
 #elif defined(ENTMAX_INST_BWD)
 #include "run_bwd.hip.h"
 namespace entmax {
 template int run_bwd<ENTMAX_INST_T, ENTMAX_INST_D, ENTMAX_INST_BIAS != 0>(const entmax_attn_params*, const Layout&, const void*,
                                                                          const void*, const void*, const void*,
-                                                                         const float*, const char*, const float*,
+                                                                         const float*, const char*, size_t, const float*,
                                                                          const float*, const float*, void*, void*, void*,
                                                                          float*, float*, uint64_t*, char*, hipStream_t,
                                                                          void* const*);

@@ -17,12 +17,12 @@ namespace entmax {
 template <typename T, int D, bool BIAS>
 int run_fwd(const entmax_attn_params* p, const Layout& L, const void* Q, const void* K, const void* V,
             const float* beta, const float* gamma, const float* slopes, void* O, float* tau, char* saved,
-            uint64_t* stats, char* ws, hipStream_t st, void* const* ev);
+            size_t saved_bytes, uint64_t* stats, char* ws, hipStream_t st, void* const* ev);
 template <typename T, int D, bool BIAS>
 int run_bwd(const entmax_attn_params* p, const Layout& L, const void* Q, const void* K, const void* V, const void* dO,
-            const float* tau, const char* saved, const float* beta, const float* gamma, const float* slopes, void* dQ,
-            void* dK, void* dV, float* dbeta, float* dgamma, uint64_t* stats, char* ws, hipStream_t st,
-            void* const* ev);
+            const float* tau, const char* saved, size_t saved_bytes, const float* beta, const float* gamma,
+            const float* slopes, void* dQ, void* dK, void* dV, float* dbeta, float* dgamma, uint64_t* stats, char* ws,
+            hipStream_t st, void* const* ev);
 
 namespace {
 

@@ -64,9 +64,9 @@ bool launch_bwd_rows_am(const BwdSparseArgs& a, int am, int nblocks, hipStream_t
 
 template <typename T, int D, bool BIAS>
 int run_bwd(const entmax_attn_params* p, const Layout& L, const void* Q, const void* K, const void* V, const void* dO,
-            const float* tau, const char* saved, const float* beta, const float* gamma, const float* slopes, void* dQ,
-            void* dK, void* dV, float* dbeta, float* dgamma, uint64_t* stats, char* ws, hipStream_t st,
-            void* const* ev) {
+            const float* tau, const char* saved, size_t saved_bytes, const float* beta, const float* gamma,
+            const float* slopes, void* dQ, void* dK, void* dV, float* dbeta, float* dgamma, uint64_t* stats, char* ws,
+            hipStream_t st, void* const* ev) {
   record(ev, 0, st);
   const int B = p->B, H = p->H;
   // the forward left the key norms in `saved`; without it they are computed again
@@ -101,7 +101,9 @@ int run_bwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
       sa.dscale = dscale;
       // the forward's lists, lengths and flags are only read (the list kernel that writes them is not launched)
       char* sv = const_cast<char*>(saved);
-      sa.list = reinterpret_cast<uint2*>(saved ? sv + L.sv_list : ws + L.off_jlist);
+      sa.list = reinterpret_cast<uint2*>(saved ? sv + L.sv_pool : ws + L.off_jlist);
+      sa.packed = saved ? 1 : 0;
+      sa.pool_cap = saved ? saved_pool_entries(L, saved_bytes) : 0;
       sa.lcnt = reinterpret_cast<int*>(saved ? sv + L.sv_lcnt : ws + L.off_lcnt);
       sa.block_flag = saved ? reinterpret_cast<int*>(sv + L.sv_flags) : block_flag;
       sa.cells = ws + L.off_bcells;

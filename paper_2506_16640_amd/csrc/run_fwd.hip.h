@@ -76,7 +76,7 @@ bool launch_decode(const DecodeArgs& a, int am, hipStream_t st, void* const* ev)
 template <typename T, int D, bool BIAS>
 int run_fwd(const entmax_attn_params* p, const Layout& L, const void* Q, const void* K, const void* V,
             const float* beta, const float* gamma, const float* slopes, void* O, float* tau, char* saved,
-            uint64_t* stats, char* ws, hipStream_t st, void* const* ev) {
+            size_t saved_bytes, uint64_t* stats, char* ws, hipStream_t st, void* const* ev) {
   record(ev, 0, st);
   // with a `saved` buffer the key norms are written there: the backward needs them too
   float* knorm = !BIAS ? nullptr : reinterpret_cast<float*>(saved ? saved + L.sv_knorm : ws + L.off_fknorm);
@@ -133,7 +133,10 @@ int run_fwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
     sa.lcnt = reinterpret_cast<int*>(ws + L.off_flcnt);
     sa.bounds = reinterpret_cast<float2*>(ws + L.off_bounds);
     // with a `saved` buffer the rows' supports are listed for the backward
-    sa.list = saved ? reinterpret_cast<uint2*>(saved + L.sv_list) : nullptr;
+    sa.list = saved ? reinterpret_cast<uint2*>(saved + L.sv_pool) : nullptr;
+    sa.pool_cursor = saved ? saved + L.sv_cursor : nullptr;
+    sa.pool_parts = saved_pool_parts((long long)p->B * p->H * L.nqg);
+    sa.pool_part_cap = saved ? saved_pool_entries(L, saved_bytes) / sa.pool_parts : 0;
     sa.slcnt = saved ? reinterpret_cast<int*>(saved + L.sv_lcnt) : nullptr;
     sa.bwd_flag = saved ? reinterpret_cast<int*>(saved + L.sv_flags) : nullptr;
     sa.kcount = saved ? reinterpret_cast<int*>(saved + L.sv_kcount) : nullptr;

@@ -18,7 +18,7 @@ def to_dev(x, dtype):
 
 
 def gpu_run(data, alpha, dtype, causal=True, logn_mode=0, bwd=True, stats=False, layout_bnhd=False, path=None,
-            use_saved=None, slopes=None, bias_mode=0):
+            use_saved=None, slopes=None, bias_mode=0, saved_factor=1):
     from paper_2506_16640_amd import binding
     path = DEFAULT_PATH if path is None else path
     use_saved = DEFAULT_SAVED if use_saved is None else use_saved
@@ -35,6 +35,8 @@ def gpu_run(data, alpha, dtype, causal=True, logn_mode=0, bwd=True, stats=False,
     if use_saved:  # the forward's lists go to the backward, which then skips its own sweep
         prm = binding.make_params(q, k, alpha, data["delta"], causal, beta, logn_mode, path)
         saved = binding.new_saved(prm)
+        if saved_factor != 1:  # a roomier pool for the support lists than the size the library asks for
+            saved = torch.empty(saved.numel() * saved_factor, dtype=torch.uint8, device="cuda")
     o, tau = binding.entmax_attn_fwd(q, k, v, saved=saved, **kw)
     out = {"O": o.float().cpu().numpy().astype(np.float64), "tau": tau.cpu().numpy().astype(np.float64)}
     if bwd:

@@ -31,15 +31,27 @@ static void check_valid(const entmax_attn_params& p) {
                        L.off_lcnt, L.off_kcount, L.off_koffs, L.off_kcursor, L.off_csc_i, L.off_csc_pw, L.off_hflag,
                        L.off_longkeys, L.off_bcells, L.total_bwd};
   for (size_t k = 0; k + 1 < sizeof(bo) / sizeof(bo[0]); ++k) CHECK(bo[k] <= bo[k + 1] && bo[k] % kAlign == 0);
-  const size_t so[] = {L.sv_list, L.sv_lcnt, L.sv_flags, L.total_saved};
+  const size_t so[] = {L.sv_cursor, L.sv_lcnt, L.sv_flags, L.sv_knorm, L.sv_kcount, L.sv_pool, L.total_saved};
   for (size_t k = 0; k + 1 < sizeof(so) / sizeof(so[0]); ++k) CHECK(so[k] <= so[k + 1] && so[k] % kAlign == 0);
   const size_t bh = (size_t)p.B * p.H;
   // the key-major arrays hold kBwdCap entries per half row: that is the bound the kernels check segments against
   CHECK(L.csc_cap == (long long)p.Nq * 2 * kBwdCap);
   CHECK(L.off_csc_pw - L.off_csc_i >= bh * (size_t)L.csc_cap * sizeof(int));
   CHECK(L.off_hflag - L.off_csc_pw >= bh * (size_t)L.csc_cap * 2 * sizeof(float));
-  // support lists: kBwdCap (key, score) slots per lane of every 128-row block, in `saved` and in the workspace
-  CHECK(L.sv_lcnt - L.sv_list >= bh * (size_t)L.nqb * kThreads * kBwdCap * 8);
+  // support lists: kBwdCap (key, score) slots per lane of every 128-row block in the workspace; in `saved` a pool
+  // behind the cursors of its parts, cut into parts that each hold at least one 32-row group's worst case
+  CHECK(L.sv_lcnt - L.sv_cursor >= (size_t)kSavedSubPools * kSavedCursorStride);
+  CHECK(L.sv_pool - L.sv_kcount >= bh * (size_t)p.Nk * sizeof(int));
+  {
+    const long long cap = saved_pool_entries(L, sv);
+    const int parts = saved_pool_parts((long long)bh * L.nqg);
+    CHECK(parts >= 1 && parts <= kSavedSubPools && (parts & (parts - 1)) == 0);
+    const long long want = (long long)bh * p.Nq * kSavedPerRow + kSavedPoolFloor;
+    CHECK(cap >= (want < (long long)kSavedPoolMost ? want : (long long)kSavedPoolMost) && cap < (1ll << 27));
+    CHECK(L.sv_pool + ((size_t)cap + kSavedPoolPad) * 8 <= sv);
+    CHECK(cap / parts >= (p.Nq < 32 ? p.Nq : 32) * 2 * kBwdCap);  // one 32-row group's worst case
+    CHECK(saved_pool_entries(L, 0) == 0 && saved_pool_entries(L, L.sv_pool) == 0);
+  }
   CHECK(L.off_lcnt - L.off_jlist >= bh * (size_t)L.nqb * kThreads * kBwdCap * 8);
   CHECK(L.sv_flags - L.sv_lcnt >= bh * (size_t)p.Nq * 2 * sizeof(int));
   CHECK(L.total_saved - L.sv_flags >= bh * (size_t)L.nqb * sizeof(int));

@@ -120,14 +120,10 @@ def test_two_level_closed_form_on_gpu(alpha):
     assert np.abs(g["O"] - V[0, 0, hi].astype(np.float64).mean(0)).max() < 2e-2
 
 
-@pytest.mark.parametrize("alpha", [1.5, 1.25])
-def test_candidates_far_beyond_support(alpha):
+def _mid_band_case(alpha, nq=128, nk=64, d=64):
     """Two-level logits (the two-level lemma of the appendix) plus a middle band: 10 equal top keys carry the
     whole mass, 50 more keys sit above the lower bound of the threshold that the list kernel can derive but
-    below the threshold itself.  Every row then lists 60 candidates for a support of 10, so the forward's
-    per-key candidate counts add up to more than the backward's key-major arrays hold per head; the backward
-    must notice and must not drop or misplace entries (all three path variants run this)."""
-    nq, nk, d = 128, 64, 64
+    below the threshold itself: every row lists 60 candidates for a support of 10 (non-causal)."""
     if alpha == 1.5:
         s_top, s_mid, s_low = 2.0, 1.0, -10.0  # tau = M/2 - 10^-1/2: support needs s > M - 0.63; candidates s > M - 1.41
     else:
@@ -147,12 +143,38 @@ def test_candidates_far_beyond_support(alpha):
     K[..., 0] = level * math.sqrt(d) / 2.0  # logits <q,k>/sqrt(d) = level, exactly representable in bf16
     V = synth.bf16_round(rng.standard_normal((1, 2, nk, d)).astype(np.float32))
     dO = synth.bf16_round(rng.standard_normal((1, 2, nq, d)).astype(np.float32))
-    data = dict(Q=Q, K=K, V=V, dO=dO, beta=None, gamma=None, delta=1.0)
+    return dict(Q=Q, K=K, V=V, dO=dO, beta=None, gamma=None, delta=1.0), s_top
+
+
+@pytest.mark.parametrize("alpha", [1.5, 1.25])
+def test_candidates_far_beyond_support(alpha):
+    """With 60 candidates for a support of 10 per row the forward's per-key candidate counts add up to more than
+    the backward's key-major arrays hold per head; the backward must notice and must not drop or misplace
+    entries (all three path variants run this)."""
+    data, s_top = _mid_band_case(alpha)
     g = gpu_run(data, alpha, "bf16", causal=False, stats=True)
     r = oracle_run(data, alpha, causal=False)
     assert int(r["support"].min()) == int(r["support"].max()) == 10
     assert np.abs(g["tau"] - ((alpha - 1) * s_top - 10.0 ** (-(alpha - 1)))).max() < 1e-3
     print(alpha, compare(g, r, label=f"mid band a{alpha}"), {k: v for k, v in g["stats"].items() if v})
+
+
+@pytest.mark.parametrize("roomy", [False, True])
+def test_saved_pool_runs_out(roomy):
+    """The `saved` buffer packs the rows' support lists into a pool sized for six entries per row on average; a
+    32-row group reserves its piece by its candidate counts (at most 16 per half row).  Here every half row lists
+    30 candidates, so a buffer of the size the library asks for cannot hold every group: the blocks that find the
+    pool used up must go to the backward's tiled kernels, and a roomier buffer must keep them all on the lists.
+    Either way the gradients match the oracle."""
+    data, _ = _mid_band_case(1.5)
+    g = gpu_run(data, 1.5, "bf16", causal=False, stats=True, path=0, use_saved=True, saved_factor=4 if roomy else 1)
+    r = oracle_run(data, 1.5, causal=False)
+    st = g["stats"]
+    print(roomy, compare(g, r, label=f"saved pool roomy={roomy}"), {k: v for k, v in st.items() if v})
+    if roomy:
+        assert st["bwd_support"] == 2 * 128 * 10 and st["bwd_dq_tiles"] == 0, st
+    else:
+        assert st["bwd_dq_tiles"] > 0, st
 
 
 def test_empty_inputs():
