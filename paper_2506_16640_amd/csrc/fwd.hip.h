@@ -170,6 +170,49 @@ __device__ __forceinline__ bool solve_step(const RowSums& s, float r, float& tau
   return fin;
 }
 
+// Where the tiled forward starts its threshold search.  The closed-form / Halley steps converge in two or three
+// sweeps from a nearby point but need five or six from the bracket's left end when a row keeps hundreds of keys
+// (every sweep recomputes Q K^T).  The row-max sweep therefore also sums the scores and their squares over the
+// key blocks the whole wave sees, and the row's threshold is estimated as if its n scores were normal with that
+// mean and deviation: n sigma^r G_r(t) = 1 for t = (tau - mu) / sigma, with
+//   G_r(t) = E[(z - t)_+^r], z ~ N(0,1):  G_1 = phi - t Q,  G_2 = (1 + t^2) Q - t phi,
+//   G_4 = (t^4 + 6 t^2 + 3) Q - (t^3 + 5 t) phi        (Q = upper tail, phi = density),
+// solved by bisection once per row.  Only a starting point: the search itself stays safeguarded inside the
+// bracket of App. A, and a row whose estimate keeps fewer than kGaussMinSupport keys starts at the left end as before
+// (there the top few scores decide, not the bulk).  Measured on dense-regime workloads (B 4, H 12, n 4096, delta 0,
+// gamma -1/2): alpha 1.5: 5.3 -> 3.0 sweeps per block, 919 -> 650 us; alpha 1.25: 6.3 -> 2.9, 1120 -> 684 us; alpha 2:
+// 8.2 -> 7.0.  At alpha 1.25 with supports of 10 to 60 keys the estimate cost a sweep (3.9 -> 4.4 to 5.2 per block,
+// also when aimed to the left of the root), hence the larger minimum for the Halley steps.
+constexpr float kGaussMinSupport = 8.f;
+constexpr float kGaussMinSupportHalley = 100.f;
+template <int AM>
+__device__ __forceinline__ float gauss_mass(float t) {
+  const float Qt = 0.5f * erfcf(t * 0.70710678f);
+  const float ph = 0.39894228f * __expf(-0.5f * t * t);
+  const float t2 = t * t;
+  if (AM == 1) return fmaf(1.f + t2, Qt, -t * ph);
+  if (AM == 2) return fmaf(-t, Qt, ph);
+  return (t2 * t2 + 6.f * t2 + 3.f) * Qt - (t2 + 5.f) * t * ph;
+}
+// mu, sigma: of y = (alpha-1) s over the sample; n: keys the row sees.  Returns false when there is no usable estimate.
+template <int AM>
+__device__ __forceinline__ bool gauss_start(float mu, float sigma, float n, float& tau0) {
+  if (AM == 0) return false;
+  if (!(sigma > 0.f) || !(n >= 2.f * kGaussMinSupport)) return false;
+  const float s2 = sigma * sigma;
+  const float c = 1.0f / (n * (AM == 1 ? s2 : (AM == 2 ? sigma : s2 * s2)));  // G_r(t) = c
+  float tl = -6.f, th = 4.f;  // beyond t = 4 the two terms of G_r cancel in single precision
+  if (!(gauss_mass<AM>(tl) > c) || !(gauss_mass<AM>(th) < c)) return false;
+  for (int it = 0; it < 18; ++it) {
+    const float tm = 0.5f * (tl + th);
+    if (gauss_mass<AM>(tm) > c) tl = tm; else th = tm;
+  }
+  const float t = 0.5f * (tl + th);
+  if (n * 0.5f * erfcf(t * 0.70710678f) < (AM == 3 ? kGaussMinSupportHalley : kGaussMinSupport)) return false;
+  tau0 = fmaf(sigma, t, mu);
+  return true;
+}
+
 // Keys per LDS tile and waves per SIMD of the tiled forward kernel, as measured on a dense-regime workload
 // (B 4, H 12, n 4096, every block on this kernel): at D = 64, 64-key tiles leave room for three workgroups per CU
 // (168 registers, no spills) and run the threshold sweeps -- vector-ALU bound, so a third wave per SIMD fills the
@@ -275,6 +318,8 @@ __device__ __forceinline__ void fwd_block(const FwdArgs& A, int bh_, int blk_, i
 
   // ------------------------------------------------------------ 1. row max
   float m = -kInf;
+  // sums of the raw scores and of their squares over the blocks every row of the wave sees in full (gauss_start)
+  float ms1 = 0.f, ms2 = 0.f, msn = 0.f;
   sweep_tiles<C, T, D, 1, 0, kFwdDepth>(
       tiles, slots, q.ntiles, g.Nk, q.tid, [&](int kt) { return q.tile_in_window(kt); },
       [&](int kt, const char* tl) {
@@ -282,16 +327,38 @@ __device__ __forceinline__ void fwd_block(const FwdArgs& A, int bh_, int blk_, i
         each_block(kt, tl, q.visible_bits(kt) & own_bits(kt), [&](f32x16_t& acc, int sb) {
           int j0 = kt * KT + sb * 32;
           ++n_vis;
-          if (j0 + 32 > q.wave_lim_min) mask_block(acc, j0);
+          if (j0 + 32 > q.wave_lim_min) {
+            mask_block(acc, j0);
+          } else if (AM != 0) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+              ms1 += acc[e];
+              ms2 = fmaf(acc[e], acc[e], ms2);
+            }
+            msn += 32.f;
+          }
           m = fmaxf(m, max16(acc));
         });
       });
   m = fmaxf(m, __shfl_xor(m, 32));
-  if constexpr (SPLIT) {  // the row maximum over all waves' keys
-    xch[(q.wave * 64 + q.lane) * 4] = m;
+  ms1 += __shfl_xor(ms1, 32);
+  ms2 += __shfl_xor(ms2, 32);
+  if constexpr (SPLIT) {  // the row maximum and the sums over all waves' keys
+    float* mine = xch + (q.wave * 64 + q.lane) * 4;
+    mine[0] = m;
+    mine[1] = ms1;
+    mine[2] = ms2;
+    mine[3] = msn;
     __syncthreads();
+    ms1 = ms2 = msn = 0.f;
 #pragma unroll
-    for (int w = 0; w < kWaves; ++w) m = fmaxf(m, xch[(w * 64 + q.lane) * 4]);
+    for (int w = 0; w < kWaves; ++w) {
+      const float* o = xch + (w * 64 + q.lane) * 4;
+      m = fmaxf(m, o[0]);
+      ms1 += o[1];
+      ms2 += o[2];
+      msn += o[3];
+    }
     __syncthreads();
   }
 
@@ -300,7 +367,13 @@ __device__ __forceinline__ void fwd_block(const FwdArgs& A, int bh_, int blk_, i
   float my = live ? q.a * m : 0.f;
   float lo = my - 1.0f;
   float hi = live ? my - __builtin_amdgcn_exp2f(-(g.alpha - 1.0f) * __builtin_amdgcn_logf((float)q.lim)) : 0.f;
+  const float lo0 = lo;  // the tiles without a positive term at the left end are zero for good
   float tau = lo;
+  if (live && msn >= 64.f) {
+    const float mean = ms1 / msn, var = ms2 / msn - mean * mean;
+    float t0;
+    if (var > 0.f && gauss_start<AM>(q.a * mean, q.a * sqrtf(var), (float)q.lim, t0)) tau = fminf(fmaxf(t0, lo), hi);
+  }
   bool done = !live;
   int iter = 0;
   int more;
@@ -324,7 +397,7 @@ __device__ __forceinline__ void fwd_block(const FwdArgs& A, int bh_, int blk_, i
         bool cand = (lm > -kInf) && (fmaf(lm, q.a, -tau) > 0.f) && !done;
         if (first) {
           // at the bracket's left end: a tile without a positive term here never gets one later
-          bool cand_any = (lm > -kInf) && (fmaf(lm, q.a, -tau) > 0.f) && live;
+          bool cand_any = (lm > -kInf) && (fmaf(lm, q.a, -lo0) > 0.f) && live;
           if (__ballot(cand_any) != 0ull && q.lane == 0) wm.set(q.wave, kt * NSB + sb);
         }
         if (__ballot(cand) == 0ull) return;
