@@ -89,7 +89,7 @@ __device__ __forceinline__ void bwd_lists_block(const BwdSparseArgs& A, int bh_,
   int cnt = 0;
   unsigned n_qk = 0, n_cand_tiles = 0;
   bool fits = true;
-  if (q.block_lim > 0) fits = collect_sweep<C, T, D, kBwdCap, ListCfg<T, D>::kLdsCells>(q, g, A.K, smem, ovf, smem + 2 * TB + 64, live, tau, A.cells, mylist, cnt, n_qk, n_cand_tiles);
+  if (q.block_lim > 0) fits = collect_sweep<C, T, D, kBwdCap, ListCfg<T, D>::kLdsCells>(q, g, A.K, smem, ovf, smem + 2 * TB + 16, live, tau, A.cells, mylist, cnt, n_qk, n_cand_tiles);
   if (q.tid == 0) A.block_flag[q.bh * A.nqb + q.qb] = fits ? 0 : 1;
   if (fits && q.valid) A.lcnt[row_idx * 2 + q.hh] = cnt;
   if (A.stats && q.lane == 0) {

@@ -236,8 +236,18 @@ struct ListCfg {
   static constexpr int kDepth = 1;
   // cells per thread that the collecting sweep keeps in LDS (20 bytes each)
   static constexpr int kLdsCells = kOcc == 4 ? 1 : 4;
-  // dynamic LDS of a list-sweep kernel: two tile buffers, the flags, the cells
-  static constexpr size_t kLdsBytes = 2 * (size_t)kTile * D * sizeof(T) + 64 + (size_t)kLdsCells * kThreads * 20;
+  // Per wave, one bit per 32-key block of the head: set by the forward's first sweep where a key of the block can
+  // still be a candidate (fwd_sparse.hip.h), so that the second sweep skips the others; blocks beyond the words'
+  // range are always visited.  LDS is handed out in pieces of 1280 bytes (measured: 53760 bytes per workgroup run
+  // three to a CU, 54080 only two, which costs the sweeps 40 %), so at D = 64 the words take what is left of the
+  // 42nd piece: 30 per wave, 30720 keys.  At D = 128 (four workgroups of 32 pieces) there is room for 128.
+  static constexpr int kFlagWords = (sizeof(T) == 2 && D == 64) ? 30 : 128;
+  // sequences shorter than this do not keep the bits: nearly every block of a wave has some lane that passes
+  // (measured at n = 4096: 97 %), so there is nothing to skip
+  static constexpr int kFlagMinKeys = 16384;
+  // dynamic LDS of a list-sweep kernel: two tile buffers, the overflow flags, the cells, the block bits
+  static constexpr size_t kLdsBytes = 2 * (size_t)kTile * D * sizeof(T) + 16 + (size_t)kLdsCells * kThreads * 20 +
+                                      (size_t)kWaves * kFlagWords * 4;
 };
 
 // SPLIT: the workgroup takes one 32-row group (rg_) of the block instead of four, and its four waves share out

@@ -119,11 +119,13 @@ struct CellBuf {
 // One sweep over the visible key tiles of the block: every key whose shifted score
 // a * dot - thr is positive ends up in the lane's list.  Returns false (workgroup-uniform) if
 // some list overflowed; the sweep is abandoned early in that case.  ovf: three ints of LDS;
-// lds_cells: CellBuf<CAP, LS>::kLdsBytes bytes of LDS.
+// lds_cells: CellBuf<CAP, LS>::kLdsBytes bytes of LDS.  blockbits: NULL, or this wave's ListCfg::kFlagWords words
+// of LDS with one bit per 32-key block of the head: a block whose bit is clear holds no candidate of any row of
+// the wave and is not computed (blocks beyond the words' range always are).
 template <typename C, typename T, int D, int CAP, int LS>
 __device__ __forceinline__ bool collect_sweep(const C& q, const Geom& g, const void* K, char* tiles, int* ovf, char* lds_cells,
                                               bool live, float thr, void* cells, uint2* mylist, int& cnt, unsigned& n_qk,
-                                              unsigned& n_cand_tiles) {
+                                              unsigned& n_cand_tiles, const uint32_t* blockbits = nullptr) {
   constexpr int KT = C::KT, NSB = C::NSB;
   // candidates are the keys with a * dot > thr: in raw units, dot > cut.  Rounding may move a key that
   // sits on the threshold (probability ~ 0) in or out of the list; the consumers recompute its value.
@@ -142,9 +144,14 @@ __device__ __forceinline__ bool collect_sweep(const C& q, const Geom& g, const v
       [&](int kt, const char* tl) {
         if (!q.tile_in_wave_window(kt)) return;
         const bool interior = (kt + 1) * KT <= q.wave_lim_min;
-        const uint32_t act = interior ? ((1u << NSB) - 1u) : q.visible_bits(kt);
+        uint32_t act = interior ? ((1u << NSB) - 1u) : q.visible_bits(kt);
+        if (blockbits && (kt + 1) * NSB <= ListCfg<T, D>::kFlagWords * 32) {
+          const int jb = kt * NSB;
+          act &= __builtin_amdgcn_readfirstlane(blockbits[jb >> 5]) >> (jb & 31);
+          if (act == 0u) return;
+        }
         f32x16_t acc[NSB];
-        if (interior) {
+        if (interior && act == (1u << NSB) - 1u) {
           q.scores_all(tl, acc, kt);
         } else {
 #pragma unroll
@@ -156,7 +163,7 @@ __device__ __forceinline__ bool collect_sweep(const C& q, const Geom& g, const v
           if (!(act & (1u << sb))) continue;
           int j0 = kt * KT + sb * 32;
           ++n_qk;
-          if (!interior && j0 + 32 > q.wave_lim_min) {
+          if (j0 + 32 > q.wave_lim_min) {
             int rel = q.lim - j0;
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[sb][e] = (q.key_of(e) < rel) ? acc[sb][e] : -kInf;
@@ -240,18 +247,33 @@ __device__ __forceinline__ float two_key_bound(float y1, float y2, float r) {
   return fmaxf(lo, t - 4e-6f * fmaxf(1.0f, fabsf(t)));
 }
 
-template <typename T, int D, int AM, bool BIAS>
+// BITS: the kernel for long sequences (Nk >= ListCfg::kFlagMinKeys), which keeps the block bits described below
+template <typename T, int D, int AM, bool BIAS, bool BITS>
 __device__ __forceinline__ void fwd_lists_block(const FwdSparseArgs& A, int bh_, int blk_, char* smem) {
   using C = QCtx<T, D, ListCfg<T, D>::kTile, BIAS>;
   constexpr int KT = C::KT, NSB = C::NSB, TB = C::kTileBytes;
   const Geom& g = A.g;
   char* tiles = smem;  // 2 buffers x 1 slot
   int* ovf = reinterpret_cast<int*>(smem + 2 * TB);  // sticky overflow flags: [0], [1] by tile parity, [2] list
-  char* lds_cells = smem + 2 * TB + 64;
+  char* lds_cells = smem + 2 * TB + 16;
+  using Cfg = ListCfg<T, D>;
+  uint32_t* allbits = reinterpret_cast<uint32_t*>(lds_cells + (size_t)Cfg::kLdsCells * kThreads * 20);
+  // Long sequences: the first sweep notes, per wave, the 32-key blocks in which some lane's largest score comes
+  // within the bracket's width of that lane's running maximum.  The final cutoff is at least (final maximum) - 1/a
+  // in raw units (App. A eq. (bounds), left end), and the running maximum never exceeds the final one: a block
+  // that fails this test for every lane holds no candidate, and the second sweep does not compute it.
+  // At n = 32768 (B 1, H 12) 44 % of the blocks keep their bit against 12 % that hold a candidate: a lane's
+  // running maximum is beaten O(log n) times along the sweep, and a block stays if any of its 64 lanes passes.
+  // Neither the running two-key bound as the cutoff (42 %) nor a first pass over every eighth tile to raise the
+  // running maxima early (44 %) changed that.
+  constexpr bool keep_bits = BITS;
+  if (keep_bits)
+    for (int w = threadIdx.x; w < kWaves * Cfg::kFlagWords; w += kThreads) allbits[w] = 0u;  // (first barrier: the sweep's)
 
   C q;
   q.init(g, A.Q, bh_, blk_);
   q.init_window(g);
+  uint32_t* mybits = allbits + q.wave * Cfg::kFlagWords;
   const int flag_idx = q.bh * A.nqb + q.qb;
   const long long row_idx = (long long)q.bh * g.Nq + (q.valid ? q.i : 0);
   const bool live = q.valid && q.lim > 0;
@@ -274,10 +296,11 @@ __device__ __forceinline__ void fwd_lists_block(const FwdSparseArgs& A, int bh_,
   // ---------------------------------------------- 1. row max and runner-up
   // m1 >= m2 are the two largest per-cell maxima seen by this lane: two distinct scores of the row
   float m1 = -kInf, m2 = -kInf;
-  sweep_tiles<C, T, D, 1, 0, ListCfg<T, D>::kDepth>(
-      tiles, slots, q.ntiles, g.Nk, q.tid, [&](int kt) { return q.tile_in_window(kt); },
-      [&](int kt, const char* tl) {
+  // BITS: the bracket's width in raw units, a little wider than needed (rounding); lanes without a live row never pass
+  const float reach = (q.valid && q.lim > 0) ? (q.a > 0.f ? 1.0001f / q.a : 3.0e38f) : -kInf;
+  auto max_body = [&](int kt, const char* tl) {
         if (!q.tile_in_wave_window(kt)) return;
+        uint32_t bits = 0u;
         if ((kt + 1) * KT <= q.wave_lim_min) {
           f32x16_t acc[NSB];
           q.scores_all(tl, acc, kt);
@@ -286,27 +309,33 @@ __device__ __forceinline__ void fwd_lists_block(const FwdSparseArgs& A, int bh_,
             float lm = max16(acc[sb]);
             m2 = fmaxf(m2, fminf(m1, lm));
             m1 = fmaxf(m1, lm);
+            if (keep_bits && __ballot(lm + reach > m1) != 0ull) bits |= 1u << sb;
           }
           n_vis += NSB;
-          return;
-        }
-        const uint32_t act = q.visible_bits(kt);
+        } else {
+          const uint32_t act = q.visible_bits(kt);
 #pragma unroll
-        for (int sb = 0; sb < NSB; ++sb) {
-          if (!(act & (1u << sb))) continue;
-          int j0 = kt * KT + sb * 32;
-          f32x16_t acc = q.scores(tl, sb, kt);
-          ++n_vis;
-          if (j0 + 32 > q.wave_lim_min) {
-            int rel = q.lim - j0;
+          for (int sb = 0; sb < NSB; ++sb) {
+            if (!(act & (1u << sb))) continue;
+            int j0 = kt * KT + sb * 32;
+            f32x16_t acc = q.scores(tl, sb, kt);
+            ++n_vis;
+            if (j0 + 32 > q.wave_lim_min) {
+              int rel = q.lim - j0;
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc[e] = (q.key_of(e) < rel) ? acc[e] : -kInf;
+              for (int e = 0; e < 16; ++e) acc[e] = (q.key_of(e) < rel) ? acc[e] : -kInf;
+            }
+            float lm = max16(acc);
+            m2 = fmaxf(m2, fminf(m1, lm));
+            m1 = fmaxf(m1, lm);
+            if (keep_bits && __ballot(lm + reach > m1) != 0ull) bits |= 1u << sb;
           }
-          float lm = max16(acc);
-          m2 = fmaxf(m2, fminf(m1, lm));
-          m1 = fmaxf(m1, lm);
         }
-      });
+        // (each wave writes only its own words)
+        if (bits != 0u && (kt + 1) * NSB <= Cfg::kFlagWords * 32 && q.lane == 0) mybits[(kt * NSB) >> 5] |= bits << ((kt * NSB) & 31);
+      };
+  sweep_tiles<C, T, D, 1, 0, ListCfg<T, D>::kDepth>(
+      tiles, slots, q.ntiles, g.Nk, q.tid, [&](int kt) { return q.tile_in_window(kt); }, max_body);
   {
     float p1 = __shfl_xor(m1, 32), p2 = __shfl_xor(m2, 32);
     float hi1 = fmaxf(m1, p1);
@@ -323,7 +352,8 @@ __device__ __forceinline__ void fwd_lists_block(const FwdSparseArgs& A, int bh_,
   // ---------------------------------------------- 2. candidate lists at tau_lb
   uint2* mylist = A.cand + list_entry<kCandCap>(q.bh, A.nqb, q.qb, q.wave, q.lane);
   int cnt = 0;
-  const bool fits = collect_sweep<C, T, D, kCandCap, ListCfg<T, D>::kLdsCells>(q, g, A.K, tiles, ovf, lds_cells, live, lo, A.cells, mylist, cnt, n_qk2, n_cand_tiles);
+  const bool fits = collect_sweep<C, T, D, kCandCap, ListCfg<T, D>::kLdsCells>(q, g, A.K, tiles, ovf, lds_cells, live, lo, A.cells, mylist, cnt, n_qk2, n_cand_tiles,
+                                                                                     keep_bits ? mybits : nullptr);
   if (!fits) {
     if (q.tid == 0) A.dense_flag[flag_idx] = 1;
   } else {
@@ -345,7 +375,7 @@ __device__ __forceinline__ void fwd_lists_block(const FwdSparseArgs& A, int bh_,
   }
 }
 
-template <typename T, int D, int AM, bool BIAS>
+template <typename T, int D, int AM, bool BIAS, bool BITS>
 __global__ __launch_bounds__(kThreads, (ListCfg<T, D>::kOcc)) void fwd_lists_kernel(FwdSparseArgs A) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const PairItem it = pair_item(A.nqb);
@@ -365,7 +395,7 @@ __global__ __launch_bounds__(kThreads, (ListCfg<T, D>::kOcc)) void fwd_lists_ker
     const int blk = part ? it.second : it.first;
     if (blk < 0) break;
     if (part) __syncthreads();
-    fwd_lists_block<T, D, AM, BIAS>(A, it.bh, blk, smem);
+    fwd_lists_block<T, D, AM, BIAS, BITS>(A, it.bh, blk, smem);
   }
 }
 

@@ -33,7 +33,10 @@ bool launch_fwd_am(const FwdArgs& a, int am, int nblocks, hipStream_t st) {
 template <typename T, int D, int AM, bool BIAS>
 bool launch_fwd_sparse(const FwdSparseArgs& a, int nblocks, hipStream_t st, void* const* ev) {
   size_t smem = ListCfg<T, D>::kLdsBytes;
-  hipLaunchKernelGGL((fwd_lists_kernel<T, D, AM, BIAS>), dim3((unsigned)nblocks), dim3(kThreads), smem, st, a);
+  if (a.g.Nk >= ListCfg<T, D>::kFlagMinKeys)  // long sequences: the second sweep skips blocks the first cleared
+    hipLaunchKernelGGL((fwd_lists_kernel<T, D, AM, BIAS, true>), dim3((unsigned)nblocks), dim3(kThreads), smem, st, a);
+  else
+    hipLaunchKernelGGL((fwd_lists_kernel<T, D, AM, BIAS, false>), dim3((unsigned)nblocks), dim3(kThreads), smem, st, a);
   if (!launch_ok()) return false;
   record(ev, ENTMAX_FWD_PHASE_LISTS + 1, st);
   hipLaunchKernelGGL((fwd_finish_kernel<T, D, AM>), dim3((unsigned)(a.g.B * a.g.H * a.nqb + a.ride.workgroups())),

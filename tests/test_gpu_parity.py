@@ -177,6 +177,30 @@ def test_saved_pool_runs_out(roomy):
         assert st["bwd_dq_tiles"] > 0, st
 
 
+def test_long_sequence_skips_blocks_in_the_second_sweep():
+    """From 16384 keys on, the list kernel's first sweep keeps one bit per (32-row group, 32-key block) and the
+    second sweep computes only the marked blocks.  Ragged length beyond the range the bits cover is not needed
+    for that (the full-size n = 32768 tests cover it); here every row of one head is compared, and two rows get a
+    late maximum preceded by near ties early in the sequence, which must all stay on their lists."""
+    n = 16384 + 37
+    data = _case(1, 1, n, n, 64, "bf16", "head", seed=5, planted=0.05)
+    data["beta"][:] = 1.0
+    data["gamma"][:] = 1.0
+    q, k = data["Q"][0, 0], data["K"][0, 0]
+    for early, row in ((3, n - 1), (9, n - 700)):
+        unit = q[row] / np.linalg.norm(q[row]) ** 2
+        for key in (early, early + 37, row - 5):  # three equal logits <q,k>/sqrt(d) (up to bf16 rounding) well above the background
+            k[key] = synth.bf16_round((5.6 * 8.0 * unit).astype(np.float32))
+    g = gpu_run(data, 1.5, "bf16", stats=True)
+    r = oracle_run(data, 1.5)
+    st = g["stats"]
+    print(compare(g, r, label="long sequence"), {k_: v for k_, v in st.items() if v})
+    for row in (n - 1, n - 700):
+        assert r["support"][0, 0, row] >= 3
+    if st["fwd_sparse_blocks"] > 0:  # (the tiled variant of this test makes no lists)
+        assert st["fwd_list_qk"] < 2 * st["fwd_tiles_visible"] * 0.9, st  # the second sweep skipped blocks
+
+
 def test_empty_inputs():
     import torch
     from paper_2506_16640_amd import binding
