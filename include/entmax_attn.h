@@ -82,7 +82,8 @@ typedef struct {
   int32_t path;            /* forward path: 0 = automatic (candidate-list kernel first; workgroups that meet a row
                               with too many candidates fall back to the tiled kernel; with Nq <= 8, or Nq <= 64 and
                               Nk >= 64 Nq -- the decoding shape -- kernels that split the keys instead),
-                              1 = tiled kernel only */
+                              1 = tiled kernel only, 2 = as 0 without the decoding-shape kernels and with the list
+                              kernels for long sequences (Nk >= 16384) whatever the sizes: a test aid */
   float alpha;             /* 1 < alpha <= 2; 1.5, 2.0 and 1.25 run on integer-power fast paths */
   float delta;             /* ASEntmax delta (1.0 in the paper's experiments) */
   int64_t q_stride_b, q_stride_h, q_stride_n;    /* strides of Q,O,dO,dQ in elements; all 0 = contiguous */

@@ -8,6 +8,10 @@ constexpr int kThreads = 256;    // 4 wave64 per workgroup
 constexpr int kWaves = 4;
 constexpr int kBlockRows = 128;  // rows (queries or keys) owned by a workgroup: 32 per wave
 
+// The long-sequence list kernel that takes two adjacent query blocks per workgroup runs only where its launch has
+// at least this many workgroups (three for each of the 256 CUs).
+constexpr int kPairMinWorkgroups = 768;
+
 constexpr int kCandCap = 32;     // candidate entries per lane = per half row (forward lists)
 constexpr int kBwdCap = 16;      // support entries per lane = per half row (the lists the backward works from)
 constexpr int kListStride = 64;  // lists are stored slot-major per wave: entry s of the 64 lanes together

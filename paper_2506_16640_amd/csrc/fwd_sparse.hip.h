@@ -64,6 +64,7 @@ struct FwdSparseArgs {
                     // list kernel, counted by the finish kernel), then the first kSplitMaxBlocks flagged blocks' numbers
   unsigned long long* stats;
   int nqb;
+  int force_long;      // run the long-sequence kernels whatever the sizes (params.path = 2: test aid)
   TransposeRide ride;  // V^T copies for the tiled kernel, as extra workgroups of the finish launch
 };
 
@@ -85,8 +86,8 @@ struct CellBuf {
   int tid;
   static constexpr size_t kBytesPerWorkgroup = cell_bytes_per_workgroup(CAP);
   static constexpr int kLdsBytes = LS * kThreads * 20;
-  __device__ __forceinline__ void init(void* base, char* lds_, int tid_) {
-    strip = reinterpret_cast<char*>(base) + (size_t)blockIdx.x * kBytesPerWorkgroup;
+  __device__ __forceinline__ void init(void* base, char* lds_, int tid_, int strip_no = blockIdx.x) {
+    strip = reinterpret_cast<char*>(base) + (size_t)strip_no * kBytesPerWorkgroup;
     lds = lds_;
     tid = tid_;
   }
@@ -125,7 +126,8 @@ struct CellBuf {
 template <typename C, typename T, int D, int CAP, int LS>
 __device__ __forceinline__ bool collect_sweep(const C& q, const Geom& g, const void* K, char* tiles, int* ovf, char* lds_cells,
                                               bool live, float thr, void* cells, uint2* mylist, int& cnt, unsigned& n_qk,
-                                              unsigned& n_cand_tiles, const uint32_t* blockbits = nullptr) {
+                                              unsigned& n_cand_tiles, const uint32_t* blockbits = nullptr,
+                                              int strip_no = -1) {
   constexpr int KT = C::KT, NSB = C::NSB;
   // candidates are the keys with a * dot > thr: in raw units, dot > cut.  Rounding may move a key that
   // sits on the threshold (probability ~ 0) in or out of the list; the consumers recompute its value.
@@ -133,7 +135,7 @@ __device__ __forceinline__ bool collect_sweep(const C& q, const Geom& g, const v
   const float cut = !live ? kInf : (q.a > 0.f ? thr / q.a : (thr < 0.f ? -3.0e38f : kInf));
   if (q.tid < 3) ovf[q.tid] = 0;
   CellBuf<CAP, LS> cb;
-  cb.init(cells, lds_cells, q.tid);
+  cb.init(cells, lds_cells, q.tid, strip_no < 0 ? (int)blockIdx.x : strip_no);  // (which of the scratch strips is this workgroup's)
   int ncell = 0;
   Slot slots[1];
   slots[0].base = reinterpret_cast<const char*>(reinterpret_cast<const T*>(K) + (long long)q.b * g.kv_sb +
@@ -249,7 +251,7 @@ __device__ __forceinline__ float two_key_bound(float y1, float y2, float r) {
 
 // BITS: the kernel for long sequences (Nk >= ListCfg::kFlagMinKeys), which keeps the block bits described below
 template <typename T, int D, int AM, bool BIAS, bool BITS>
-__device__ __forceinline__ void fwd_lists_block(const FwdSparseArgs& A, int bh_, int blk_, char* smem) {
+__device__ __forceinline__ void fwd_lists_block(const FwdSparseArgs& A, int bh_, int blk_, char* smem, int strip_no = -1) {
   using C = QCtx<T, D, ListCfg<T, D>::kTile, BIAS>;
   constexpr int KT = C::KT, NSB = C::NSB, TB = C::kTileBytes;
   const Geom& g = A.g;
@@ -353,7 +355,7 @@ __device__ __forceinline__ void fwd_lists_block(const FwdSparseArgs& A, int bh_,
   uint2* mylist = A.cand + list_entry<kCandCap>(q.bh, A.nqb, q.qb, q.wave, q.lane);
   int cnt = 0;
   const bool fits = collect_sweep<C, T, D, kCandCap, ListCfg<T, D>::kLdsCells>(q, g, A.K, tiles, ovf, lds_cells, live, lo, A.cells, mylist, cnt, n_qk2, n_cand_tiles,
-                                                                                     keep_bits ? mybits : nullptr);
+                                                                                     keep_bits ? mybits : nullptr, strip_no);
   if (!fits) {
     if (q.tid == 0) A.dense_flag[flag_idx] = 1;
   } else {
@@ -396,6 +398,296 @@ __global__ __launch_bounds__(kThreads, (ListCfg<T, D>::kOcc)) void fwd_lists_ker
     if (blk < 0) break;
     if (part) __syncthreads();
     fwd_lists_block<T, D, AM, BIAS, BITS>(A, it.bh, blk, smem);
+  }
+}
+
+// ------------------------------------------------- long sequences: two query blocks per workgroup
+// The same two sweeps as fwd_lists_block<.., BITS = true> for the adjacent blocks 2 sblk and 2 sblk + 1 at once:
+// every wave holds its 32-row group of both blocks (64 query rows), so that a K fragment read from LDS feeds two
+// matrix instructions and a K tile staged through LDS serves 256 rows.  Each block keeps its own lists, flags,
+// bounds and block bits, exactly as if it had run alone.  Used where the launch still fills the chip with half as
+// many workgroups (Nk >= ListCfg::kFlagMinKeys).
+template <typename T, int D>
+struct PairCfg {
+  using Cfg = ListCfg<T, D>;
+  static constexpr int kLdsCells = 1;   // cells per thread and block kept in LDS
+  static constexpr int kFlagWords = 64; // block bits per wave and block: 65536 keys
+  static constexpr size_t kLdsBytes = 2 * (size_t)Cfg::kTile * D * sizeof(T) + 32 + 2 * (size_t)kLdsCells * kThreads * 20 +
+                                      2 * (size_t)kWaves * kFlagWords * 4;
+};
+
+template <typename T, int D, int AM, bool BIAS>
+__device__ __forceinline__ void fwd_lists_pair(const FwdSparseArgs& A, int bh_, int sblk, char* smem) {
+  using C = QCtx<T, D, ListCfg<T, D>::kTile, BIAS>;
+  using P = PairCfg<T, D>;
+  using KTile = typename C::KTile;
+  constexpr int KT = C::KT, NSB = C::NSB, NC = C::NC, TB = C::kTileBytes, LS = P::kLdsCells, W = P::kFlagWords;
+  constexpr uint32_t kAll = (1u << NSB) - 1u;
+  const Geom& g = A.g;
+  char* tiles = smem;
+  int* ovf = reinterpret_cast<int*>(smem + 2 * TB);  // [2 blocks][3], see collect_sweep
+  char* lds_cells = smem + 2 * TB + 32;
+  uint32_t* allbits = reinterpret_cast<uint32_t*>(lds_cells + 2 * (size_t)LS * kThreads * 20);  // [2][kWaves][W]
+  for (int w = threadIdx.x; w < 2 * kWaves * W; w += kThreads) allbits[w] = 0u;
+  if (threadIdx.x < 6) ovf[threadIdx.x] = 0;  // (first barrier: init_window's or the first sweep's)
+
+  C q[2];
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    q[k].init(g, A.Q, bh_, 2 * sblk + k);
+    q[k].init_window(g);
+  }
+  const int tid = q[0].tid, wave = q[0].wave, lane = q[0].lane;
+  uint32_t* mybits[2] = {allbits + wave * W, allbits + (kWaves + wave) * W};
+  const int ntiles = q[1].ntiles;  // the later block sees at least the keys of the earlier one
+  bool live[2];
+  long long row_idx[2];
+  int flag_idx[2];
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    live[k] = q[k].valid && q[k].lim > 0;
+    row_idx[k] = (long long)q[k].bh * g.Nq + (q[k].valid ? q[k].i : 0);
+    flag_idx[k] = q[k].bh * A.nqb + q[k].qb;
+  }
+  if (q[1].block_lim == 0) {  // no row of either block sees any key: the finish kernel writes the zeros
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+      if (q[k].valid) {
+        A.lcnt[row_idx[k] * 2 + q[k].hh] = 0;
+        if (q[k].hh == 0) A.bounds[row_idx[k]] = make_float2(0.f, 0.f);
+      }
+      if (tid == 0) A.dense_flag[flag_idx[k]] = 0;
+    }
+    return;
+  }
+  Slot slots[1];
+  slots[0].base = reinterpret_cast<const char*>(reinterpret_cast<const T*>(A.K) + (long long)q[0].b * g.kv_sb +
+                                                (long long)q[0].h * g.kv_sh);
+  slots[0].row_bytes = g.kv_sn * (long long)sizeof(T);
+  auto needed = [&](int kt) { return q[0].tile_in_window(kt) || q[1].tile_in_window(kt); };
+  // 32-key blocks of tile kt some row of the wave's group of block k sees
+  auto visible = [&](int k, int kt) -> uint32_t { return q[k].tile_in_wave_window(kt) ? q[k].visible_bits(kt) : 0u; };
+  auto mask_block = [&](int k, f32x16_t& acc, int j0) {
+    const int rel = q[k].lim - j0;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[e] = (q[k].key_of(e) < rel) ? acc[e] : -kInf;
+  };
+  // the K fragments of a 32-key block, shared by both groups
+  auto load_k = [&](const char* tl, int sb, Frag<T> (&kf)[NC]) {
+#pragma unroll
+    for (int cc = 0; cc < NC; ++cc) kf[cc] = q[0].koff[cc].load(tl, sb * 32 * KTile::kRowBytes);
+  };
+  auto product = [&](int k, const Frag<T> (&kf)[NC], int j0) -> f32x16_t {
+    f32x16_t acc = q[k].block_start(j0);
+#pragma unroll
+    for (int cc = 0; cc < NC; ++cc) acc = Elem<T>::mma(kf[cc], q[k].qf[cc], acc);
+    return acc;
+  };
+  unsigned n_vis[2] = {0u, 0u}, n_qk2[2] = {0u, 0u}, n_cand_tiles[2] = {0u, 0u};
+
+  // ---------------------------------------------- 1. row maxima, runners-up and the block bits
+  float m1[2] = {-kInf, -kInf}, m2[2] = {-kInf, -kInf}, reach[2];
+#pragma unroll
+  for (int k = 0; k < 2; ++k) reach[k] = live[k] ? (q[k].a > 0.f ? 1.0001f / q[k].a : 3.0e38f) : -kInf;
+  sweep_tiles<C, T, D, 1, 0, ListCfg<T, D>::kDepth>(tiles, slots, ntiles, g.Nk, tid, needed, [&](int kt, const char* tl) {
+    uint32_t act[2] = {visible(0, kt), visible(1, kt)};
+    if ((act[0] | act[1]) == 0u) return;
+    uint32_t bits[2] = {0u, 0u};
+    auto take = [&](int k, f32x16_t& acc, int sb) {
+      const int j0 = kt * KT + sb * 32;
+      ++n_vis[k];
+      if (j0 + 32 > q[k].wave_lim_min) mask_block(k, acc, j0);
+      const float lm = max16(acc);
+      m2[k] = fmaxf(m2[k], fminf(m1[k], lm));
+      m1[k] = fmaxf(m1[k], lm);
+      if (__ballot(lm + reach[k] > m1[k]) != 0ull) bits[k] |= 1u << sb;
+    };
+    if (act[0] == kAll && act[1] == kAll) {
+      // every block for both groups: the fragments of block sb + 1 are requested before the products of block sb
+      Frag<T> kf[2][NC];
+      load_k(tl, 0, kf[0]);
+#pragma unroll
+      for (int sb = 0; sb < NSB; ++sb) {
+        if (sb + 1 < NSB) load_k(tl, sb + 1, kf[(sb + 1) & 1]);
+        const int j0 = kt * KT + sb * 32;
+        f32x16_t a0 = q[0].block_start(j0), a1 = q[1].block_start(j0);
+#pragma unroll
+        for (int cc = 0; cc < NC; ++cc) {
+          a0 = Elem<T>::mma(kf[sb & 1][cc], q[0].qf[cc], a0);
+          a1 = Elem<T>::mma(kf[sb & 1][cc], q[1].qf[cc], a1);
+        }
+        take(0, a0, sb);
+        take(1, a1, sb);
+      }
+    } else {
+#pragma unroll
+      for (int sb = 0; sb < NSB; ++sb) {
+        if (((act[0] | act[1]) & (1u << sb)) == 0u) continue;
+        Frag<T> kf[NC];
+        load_k(tl, sb, kf);
+        f32x16_t acc[2];  // (both products before the vector work on either)
+#pragma unroll
+        for (int k = 0; k < 2; ++k)
+          if ((act[k] & (1u << sb)) != 0u) acc[k] = product(k, kf, kt * KT + sb * 32);
+#pragma unroll
+        for (int k = 0; k < 2; ++k)
+          if ((act[k] & (1u << sb)) != 0u) take(k, acc[k], sb);
+      }
+    }
+    if ((kt + 1) * NSB <= W * 32 && lane == 0) {  // (each wave writes only its own words)
+#pragma unroll
+      for (int k = 0; k < 2; ++k)
+        if (bits[k] != 0u) mybits[k][(kt * NSB) >> 5] |= bits[k] << ((kt * NSB) & 31);
+    }
+  });
+  float lo[2], hi[2];
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    const float p1 = __shfl_xor(m1[k], 32), p2 = __shfl_xor(m2[k], 32);
+    const float top = fmaxf(m1[k], p1);
+    m2[k] = fmaxf(fminf(m1[k], p1), fmaxf(m2[k], p2));
+    m1[k] = top;
+    const float y1 = live[k] ? q[k].a * m1[k] : 0.f;
+    lo[k] = y1 - 1.0f;  // App. A eq. (bounds), left end
+    hi[k] = live[k] ? y1 - __builtin_amdgcn_exp2f(-(g.alpha - 1.0f) * __builtin_amdgcn_logf((float)q[k].lim)) : 0.f;
+    if (live[k] && m2[k] > -kInf) lo[k] = two_key_bound<AM>(y1, q[k].a * m2[k], 1.0f / (g.alpha - 1.0f));
+    lo[k] = fminf(lo[k], hi[k]);
+  }
+
+  // ---------------------------------------------- 2. candidate lists at tau_lb (see collect_sweep)
+  float cut[2];
+  CellBuf<kCandCap, LS> cb[2];
+  int ncell[2] = {0, 0};
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    cut[k] = !live[k] ? kInf : (q[k].a > 0.f ? lo[k] / q[k].a : (lo[k] < 0.f ? -3.0e38f : kInf));
+    cb[k].init(A.cells, lds_cells + k * CellBuf<kCandCap, LS>::kLdsBytes, tid, 2 * (int)blockIdx.x + k);
+  }
+  sweep_tiles<C, T, D, 1, 0, ListCfg<T, D>::kDepth>(
+      tiles, slots, ntiles, g.Nk, tid, needed,
+      [&](int kt, const char* tl) {
+        uint32_t act[2] = {visible(0, kt), visible(1, kt)};
+        if ((kt + 1) * NSB <= W * 32) {
+          const int jb = kt * NSB;
+#pragma unroll
+          for (int k = 0; k < 2; ++k) act[k] &= __builtin_amdgcn_readfirstlane(mybits[k][jb >> 5]) >> (jb & 31);
+        }
+        // a block whose strip overflowed is lost to the tiled kernel anyway (flags of the previous tile's parity
+        // were final before the barrier that ended that tile)
+#pragma unroll
+        for (int k = 0; k < 2; ++k)
+          if (kt > 0 && ovf[3 * k + ((kt - 1) & 1)] != 0) act[k] = 0u;
+        if ((act[0] | act[1]) == 0u) return;
+#pragma unroll
+        for (int sb = 0; sb < NSB; ++sb) {
+          if (((act[0] | act[1]) & (1u << sb)) == 0u) continue;
+          Frag<T> kf[NC];
+          load_k(tl, sb, kf);
+          const int j0 = kt * KT + sb * 32;
+          f32x16_t accs[2];  // (both products before the vector work on either)
+#pragma unroll
+          for (int k = 0; k < 2; ++k)
+            if ((act[k] & (1u << sb)) != 0u) accs[k] = product(k, kf, j0);
+#pragma unroll
+          for (int k = 0; k < 2; ++k) {
+            if ((act[k] & (1u << sb)) == 0u) continue;
+            f32x16_t& acc = accs[k];
+            ++n_qk2[k];
+            if (j0 + 32 > q[k].wave_lim_min) mask_block(k, acc, j0);
+            float gm[4];
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq)
+              gm[gq] = fmaxf(fmaxf(acc[4 * gq], acc[4 * gq + 1]), fmaxf(acc[4 * gq + 2], acc[4 * gq + 3]));
+            const float lm = fmaxf(fmaxf(gm[0], gm[1]), fmaxf(gm[2], gm[3]));
+            if (__ballot(lm > cut[k]) == 0ull) continue;
+            ++n_cand_tiles[k];
+#pragma unroll
+            for (int cl = 0; cl < 4; ++cl) {
+              if (gm[cl] > cut[k]) {
+                cb[k].store(ncell[k], f32x4_t{acc[4 * cl], acc[4 * cl + 1], acc[4 * cl + 2], acc[4 * cl + 3]},
+                            j0 + q[k].key_of(4 * cl));
+                ++ncell[k];
+              }
+            }
+          }
+        }
+#pragma unroll
+        for (int k = 0; k < 2; ++k)
+          if (__ballot(ncell[k] > kCandCap) != 0ull && lane == 0) ovf[3 * k + (kt & 1)] = 1;
+      },
+      [&](int kt) { return kt > 0 && ovf[(kt - 1) & 1] != 0 && ovf[3 + ((kt - 1) & 1)] != 0; });
+  // the sweep ended on a barrier: the strips' flags are final
+  int cnt[2] = {0, 0};
+  bool fits[2];
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    fits[k] = (ovf[3 * k] | ovf[3 * k + 1]) == 0;
+    if (fits[k]) {
+      uint2* mylist = A.cand + list_entry<kCandCap>(q[k].bh, A.nqb, q[k].qb, wave, lane);
+      int total = 0;
+      for (int c = 0; c < ncell[k]; ++c) {
+        f32x4_t dv;
+        int jc;
+        cb[k].load(c, dv, jc);
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) {
+          if (dv[rr] > cut[k]) {
+            if (cnt[k] < kCandCap) {
+              mylist[cnt[k] * kListStride] = make_uint2((unsigned)(jc + rr), __float_as_uint(dv[rr]));
+              ++cnt[k];
+            }
+            ++total;
+          }
+        }
+      }
+      if (total > kCandCap) ovf[3 * k + 2] = 1;
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    fits[k] = fits[k] && ovf[3 * k + 2] == 0;
+    if (tid == 0) A.dense_flag[flag_idx[k]] = fits[k] ? 0 : 1;
+    if (fits[k] && q[k].valid) {
+      A.lcnt[row_idx[k] * 2 + q[k].hh] = cnt[k];
+      if (q[k].hh == 0) A.bounds[row_idx[k]] = make_float2(lo[k], hi[k]);
+    }
+    if (A.stats && lane == 0) {
+      const unsigned n_win = q[k].window_skipped_blocks();
+      atomicAdd(&A.stats[ENTMAX_STAT_FWD_TILES_VISIBLE], (unsigned long long)(n_vis[k] + n_win));
+      if (BIAS) atomicAdd(&A.stats[ENTMAX_STAT_FWD_WINDOW_SKIPPED], (unsigned long long)n_win);
+      atomicAdd(&A.stats[ENTMAX_STAT_FWD_LIST_QK], (unsigned long long)(n_vis[k] + n_qk2[k]));
+      if (fits[k]) {
+        atomicAdd(&A.stats[ENTMAX_STAT_FWD_CAND_TILES], (unsigned long long)n_cand_tiles[k]);
+        if (wave == 0) atomicAdd(&A.stats[ENTMAX_STAT_FWD_SPARSE_BLOCKS], 1ull);
+      }
+    }
+  }
+}
+
+template <typename T, int D, int AM, bool BIAS>
+__global__ __launch_bounds__(kThreads, (ListCfg<T, D>::kOcc)) void fwd_lists_pair_kernel(FwdSparseArgs A) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const int nsb = (A.nqb + 1) >> 1;  // pairs of adjacent blocks per head
+  const PairItem it = pair_item(nsb);
+  if (blockIdx.x == 0 && threadIdx.x == 0) A.dense_flag[A.g.B * A.g.H * A.nqb] = 0;
+  if (blockIdx.x == 0 && A.pool_cursor && (int)threadIdx.x < A.pool_parts)
+    *reinterpret_cast<unsigned long long*>(A.pool_cursor + (size_t)threadIdx.x * kSavedCursorStride) = 0ull;
+  if (A.kcount) {
+    // this workgroup's share of its head's per-key counters starts at zero for the finish kernel
+    const int npair = (nsb + 1) >> 1, pp = nsb - 1 - it.first;
+    const int chunk = (A.g.Nk + npair - 1) / npair;
+    int* dst = A.kcount + (long long)it.bh * A.g.Nk;
+    for (int j = pp * chunk + (int)threadIdx.x; j < min(A.g.Nk, (pp + 1) * chunk); j += kThreads) dst[j] = 0;
+  }
+  for (int part = 0; part < 2; ++part) {
+    const int sblk = part ? it.second : it.first;
+    if (sblk < 0) break;
+    if (part) __syncthreads();
+    if (2 * sblk + 1 < A.nqb)
+      fwd_lists_pair<T, D, AM, BIAS>(A, it.bh, sblk, smem);
+    else  // a head's odd last block
+      fwd_lists_block<T, D, AM, BIAS, true>(A, it.bh, 2 * sblk, smem, 2 * (int)blockIdx.x);
   }
 }
 

@@ -40,7 +40,7 @@ inline int check_params(const entmax_attn_params* p) {
   if (p->scale_layout < 0 || p->scale_layout > 2) return ENTMAX_ATTN_INVALID_ARG;
   if (p->logn_mode != 0 && p->logn_mode != 1) return ENTMAX_ATTN_INVALID_ARG;
   if (p->bias_mode != 0 && p->bias_mode != 1) return ENTMAX_ATTN_INVALID_ARG;
-  if (p->path != 0 && p->path != 1) return ENTMAX_ATTN_INVALID_ARG;
+  if (p->path < 0 || p->path > 2) return ENTMAX_ATTN_INVALID_ARG;
   if (!(p->alpha > 1.0f) || !(p->alpha <= 2.0f)) return ENTMAX_ATTN_INVALID_ARG;
   if (!isfinite(p->delta)) return ENTMAX_ATTN_INVALID_ARG;
   if (p->D != 64 && p->D != 128) return ENTMAX_ATTN_UNSUPPORTED_SHAPE;
@@ -87,7 +87,9 @@ inline Layout make_layout(const entmax_attn_params* p) {
   size_t mask_bytes = align_up(bh * (size_t)L.nqg * L.mask_words * sizeof(uint32_t));
   // forward: V^T copy (tiled kernel only) | candidate lists (one per lane of the list grid), their lengths, the
   // rows' brackets | per-block fallback flags | the list sweep's cell strips
-  const size_t list_groups = bh * (size_t)((L.nqb + 1) / 2);  // workgroups of the list sweeps
+  // cell strips of the list sweeps: one per workgroup (a pair of blocks), or two per workgroup of the
+  // long-sequence kernel (two pairs of adjacent blocks)
+  const size_t list_groups = bh * (size_t)(2 * ((L.nqb + 3) / 4));
   L.off_vt = 0;
   L.off_cand = kt_bytes;
   L.off_flcnt = L.off_cand + align_up(bh * (size_t)L.nqb * kThreads * kCandCap * 8);

@@ -82,7 +82,7 @@ int run_bwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
     ok = ok && zero_words(dscale, (size_t)B * H * p->Nq * 4, st);
     for (int k = 1; k <= ENTMAX_BWD_PHASE_KEYS + 1; ++k) record(ev, k, st);
   } else {
-    const bool lists = p->path == 0;
+    const bool lists = p->path != 1;
     if (BIAS && !saved && !launch_key_norms<T, D>(p, L, K, reinterpret_cast<float*>(ws + L.off_bknorm), st))
       return ENTMAX_ATTN_LAUNCH_FAILED;
     int* block_flag = reinterpret_cast<int*>(ws + L.off_hflag);
@@ -187,7 +187,7 @@ int run_bwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
     record(ev, ENTMAX_BWD_PHASE_KEYS + 1, st);
   }
   if (!ok) return ENTMAX_ATTN_LAUNCH_FAILED;
-  if (p->scale_layout == 1 && !(p->path == 0 && p->Nk > 0 && p->Nq > 0)) {  // (else done inside the keys launch)
+  if (p->scale_layout == 1 && !(p->path != 1 && p->Nk > 0 && p->Nq > 0)) {  // (else done inside the keys launch)
     hipLaunchKernelGGL(scale_grad_head_kernel, dim3((unsigned)H), dim3(kScaleGradThreads), 0, st, g, dscale, dbeta,
                        dgamma);
     ok = launch_ok();

@@ -33,7 +33,16 @@ bool launch_fwd_am(const FwdArgs& a, int am, int nblocks, hipStream_t st) {
 template <typename T, int D, int AM, bool BIAS>
 bool launch_fwd_sparse(const FwdSparseArgs& a, int nblocks, hipStream_t st, void* const* ev) {
   size_t smem = ListCfg<T, D>::kLdsBytes;
-  if (a.g.Nk >= ListCfg<T, D>::kFlagMinKeys)  // long sequences: the second sweep skips blocks the first cleared
+  const int nsb = (a.nqb + 1) / 2;
+  const long long pair_grid = (long long)a.g.B * a.g.H * ((nsb + 1) / 2);
+  const bool long_seq = a.g.Nk >= ListCfg<T, D>::kFlagMinKeys;
+  if (sizeof(T) == 2 && D == 64 && (a.force_long || (long_seq && pair_grid >= kPairMinWorkgroups))) {
+    // long sequences: the second sweep skips blocks the first cleared, and a workgroup takes two adjacent blocks
+    // where that still leaves three workgroups for every CU (measured at B 4, H 12, n 4096, where it leaves 1.5:
+    // 221 us against 139 us with one block per workgroup)
+    const size_t smem2 = PairCfg<T, D>::kLdsBytes > smem ? PairCfg<T, D>::kLdsBytes : smem;
+    hipLaunchKernelGGL((fwd_lists_pair_kernel<T, D, AM, BIAS>), dim3((unsigned)pair_grid), dim3(kThreads), smem2, st, a);
+  } else if (long_seq || a.force_long)
     hipLaunchKernelGGL((fwd_lists_kernel<T, D, AM, BIAS, true>), dim3((unsigned)nblocks), dim3(kThreads), smem, st, a);
   else
     hipLaunchKernelGGL((fwd_lists_kernel<T, D, AM, BIAS, false>), dim3((unsigned)nblocks), dim3(kThreads), smem, st, a);
@@ -120,7 +129,7 @@ int run_fwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
   void* Vt = ws + L.off_vt;
   int* dense_flag = reinterpret_cast<int*>(ws + L.off_flags);  // [B*H*nqb] blocks left to the tiled kernel
   const int npairs = p->B * p->H * ((L.nqb + 1) / 2);  // workgroups that take query blocks in pairs
-  const bool lists = p->path == 0;
+  const bool lists = p->path != 1;
   if (BIAS && !launch_key_norms<T, D>(p, L, K, knorm, st)) return ENTMAX_ATTN_LAUNCH_FAILED;
   record(ev, ENTMAX_FWD_PHASE_PREPARE + 1, st);
   if (lists) {
@@ -146,6 +155,7 @@ int run_fwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
     sa.dense_flag = dense_flag;
     sa.stats = reinterpret_cast<unsigned long long*>(stats);
     sa.nqb = L.nqb;
+    sa.force_long = p->path == 2;
     {
       TransposeJobs jobs{};
       jobs.job[0] = transpose_job(V, L.kv_sb, L.kv_sh, L.kv_sn, p->Nk, L.npad_k, Vt);

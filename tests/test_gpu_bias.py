@@ -24,7 +24,8 @@ def _case(B, H, nq, nk, d, dtype, scale, seed=0):
 
 
 def _run(data, alpha, dtype, slopes, bias_mode, label, **kw):
-    g = gpu_run(data, alpha, dtype, slopes=slopes, bias_mode=bias_mode, stats=True, **kw)
+    gpu_only = {k: kw.pop(k) for k in ("path", "use_saved") if k in kw}  # how the library runs it, not what is computed
+    g = gpu_run(data, alpha, dtype, slopes=slopes, bias_mode=bias_mode, stats=True, **kw, **gpu_only)
     r = oracle_run(data, alpha, slopes=slopes, bias_mode=bias_mode, **kw)
     errs = compare(g, r, label=label)
     print(label, errs, {k: v for k, v in g["stats"].items() if v and k in ("fwd_tiles_visible", "fwd_window_skipped")})
@@ -38,6 +39,16 @@ def test_nape_small_causal(alpha, d, bias_mode):
     # four heads, every other one biased; several query blocks and key tiles, ragged tail
     data = _case(2, 4, 300, 300, d, "bf16", "head", seed=11)
     _run(data, alpha, "bf16", synth.nape_slopes(4), bias_mode, f"nape a{alpha} d{d} m{bias_mode}")
+
+
+@pytest.mark.parametrize("bias_mode", [0, 1])
+@pytest.mark.parametrize("nq,nk,causal", [(641, 641, True), (200, 333, False), (333, 200, True)])
+def test_nape_long_sequence_kernels_at_small_sizes(nq, nk, causal, bias_mode):
+    # params.path = 2: the list kernels made for long sequences (two adjacent query blocks per workgroup, block
+    # bits), here with the bias as the accumulator's start and the distance window
+    data = _case(2, 4, nq, nk, 64, "bf16", "head", seed=14)
+    _run(data, 1.5, "bf16", synth.nape_slopes(4), bias_mode, f"nape long kernels {nq} {nk} {causal} m{bias_mode}",
+         causal=causal, path=2, use_saved=True)
 
 
 @pytest.mark.parametrize("bias_mode", [0, 1])

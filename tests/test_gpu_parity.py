@@ -201,6 +201,23 @@ def test_long_sequence_skips_blocks_in_the_second_sweep():
         assert st["fwd_list_qk"] < 2 * st["fwd_tiles_visible"] * 0.9, st  # the second sweep skipped blocks
 
 
+@pytest.mark.parametrize("causal,nq,nk,alpha,scale", [(True, 300, 300, 1.5, "head"), (True, 641, 641, 1.5, "head"),
+                                                      (False, 200, 333, 1.5, "head"), (True, 333, 200, 2.0, "head"),
+                                                      (True, 200, 333, 1.25, "head"), (True, 1, 70, 1.5, "head"),
+                                                      (True, 520, 520, 1.7, "none"), (True, 257, 257, 1.5, "dense")])
+@pytest.mark.parametrize("d", [64, 128])
+def test_long_sequence_kernels_at_small_sizes(causal, nq, nk, alpha, scale, d):
+    """params.path = 2 runs the list kernels made for long sequences at any size: at D = 64 the kernel that takes
+    two adjacent query blocks per workgroup (odd numbers of blocks end on a single one; 641 rows are five blocks
+    and a ragged sixth), at D = 128 the one-block kernel with the block bits.  Same bar as everywhere; the
+    backward gets the forward's lists."""
+    data = _case(2, 3, nq, nk, d, "bf16", scale, seed=13)
+    g = gpu_run(data, alpha, "bf16", causal=causal, path=2, use_saved=True, stats=True)
+    r = oracle_run(data, alpha, causal=causal)
+    print(causal, nq, nk, alpha, scale, d, compare(g, r, label=f"long kernels {causal} {nq} {nk} a{alpha} {scale} d{d}"),
+          {k: v for k, v in g["stats"].items() if v})
+
+
 def test_empty_inputs():
     import torch
     from paper_2506_16640_amd import binding
