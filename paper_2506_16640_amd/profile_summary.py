@@ -20,7 +20,7 @@ import os
 
 # bench.py's name of each kernel
 BENCH_NAMES = collections.OrderedDict([
-    ("fwd_lists_kernel", "fwd_lists"), ("fwd_finish_kernel", "fwd_finish"), ("fwd_kernel", "fwd_tiled"),
+    ("fwd_lists_kernel", "fwd_lists"), ("fwd_lists_pair_kernel", "fwd_lists"), ("fwd_finish_kernel", "fwd_finish"), ("fwd_kernel", "fwd_tiled"),
     ("bwd_lists_kernel", "bwd_lists"), ("bwd_rows_kernel", "bwd_rows"), ("bwd_keys_kernel", "bwd_keys"),
     ("bwd_dq_kernel", "bwd_dq"), ("bwd_dkv_kernel", "bwd_dkv"),
     ("key_offsets_kernel", "key_offsets"), ("decode_scores_kernel", "decode_scores"),
