@@ -110,17 +110,30 @@ __global__ __launch_bounds__(kThreads, (ListCfg<T, D>::kOcc)) void bwd_lists_ker
   }
 }
 
-// Everything row-wise from the lists: one lane pair per row, each lane half of the features.
+// Everything row-wise from the lists: D / 32 lanes per row, each with 32 of the features (a lane pair per row at
+// D = 64; at D = 128 two lanes per list half, which both read that half's entries -- with 64 features per lane the
+// kernel needed 388 registers and ran one wave per SIMD: 234 against 174 us at B 2, H 16, n 8192).
+// Measured and not kept: 16 features per lane (twice the waves at 146 registers: same time at both head
+// dimensions), eight consecutive lanes per row so that a gathered row is one load instruction (D = 64: 78 -> 82 us),
+// all gathers of a short row requested before the first is used (-> 101 us), a head's keys on its rows' XCD in the
+// key kernel (no change).
+template <int D>
+struct RowsCfg {
+  static constexpr int kFH = D / 64;  // lanes per list half
+};
 template <typename T, int D, int AM>
-__global__ __launch_bounds__(kThreads, D == 64 ? 2 : 1) void bwd_rows_kernel(BwdSparseArgs A) {
+__global__ __launch_bounds__(kThreads, 2) void bwd_rows_kernel(BwdSparseArgs A) {
   const Geom& g = A.g;
-  if ((int)blockIdx.x >= g.B * g.H * A.nqb) {  // riders behind the row workgroups
-    transpose_ride<T, D>(A.ride, (int)blockIdx.x - g.B * g.H * A.nqb);
+  constexpr int FH = RowsCfg<D>::kFH;
+  if ((int)blockIdx.x >= g.B * g.H * A.nqb * FH) {  // riders behind the row workgroups
+    transpose_ride<T, D>(A.ride, (int)blockIdx.x - g.B * g.H * A.nqb * FH);
     return;
   }
   RowLane rl;
-  rl.init(g, A.nqb);
-  constexpr int DH = D / 2;
+  rl.init<FH>(g, A.nqb);
+  constexpr int DH = 32;  // features per lane
+  const int feat0 = (rl.hh * FH + rl.f) * DH;  // the lane's first feature
+  const bool owner_lane = rl.f == 0;           // the lane of its list half that places the entries and writes the row scalars
   const float r = 1.0f / (g.alpha - 1.0f);
   const long long row_idx = (long long)rl.bh * g.Nq + (rl.valid ? rl.i : 0);
   const int lim = rl.valid ? row_limit(g, rl.i) : 0;
@@ -153,7 +166,7 @@ __global__ __launch_bounds__(kThreads, D == 64 ? 2 : 1) void bwd_rows_kernel(Bwd
     rdlist = A.list + off;
     lstride = 1;
   } else {
-    rdlist = A.list + list_entry<kBwdCap>(rl.bh, A.nqb, rl.qb, threadIdx.x >> 6, threadIdx.x & 63);
+    rdlist = A.list + list_entry<kBwdCap>(rl.bh, A.nqb, rl.qb, rl.w32, rl.hh * 32 + rl.li);
     cnt_list = cnt_raw;
     lstride = kListStride;
   }
@@ -164,7 +177,7 @@ __global__ __launch_bounds__(kThreads, D == 64 ? 2 : 1) void bwd_rows_kernel(Bwd
   // the row's dO, this lane's half of the features, widened to fp32
   float dov[DH];
   if (rl.valid) {
-    load_row_f32<T>(reinterpret_cast<const T*>(A.dO) + q_base + (long long)rl.i * g.q_sn + rl.hh * DH, DH, dov);
+    load_row_f32<T>(reinterpret_cast<const T*>(A.dO) + q_base + (long long)rl.i * g.q_sn + feat0, DH, dov);
   } else {
 #pragma unroll
     for (int t = 0; t < DH; ++t) dov[t] = 0.f;
@@ -222,10 +235,10 @@ __global__ __launch_bounds__(kThreads, D == 64 ? 2 : 1) void bwd_rows_kernel(Bwd
         RawRow<T, DH> kk;
         if (x > 0.f) {
           RawRow<T, DH> vv;
-          vv.load(Vbh + (long long)j * g.kv_sn + rl.hh * DH);
-          kk.load(Kbh + (long long)j * g.kv_sn + rl.hh * DH);
+          vv.load(Vbh + (long long)j * g.kv_sn + feat0);
+          kk.load(Kbh + (long long)j * g.kv_sn + feat0);
           // the entry's owner takes its arrival number among the key's entries: its place in the key's segment
-          if (rl.hh == src) {
+          if (rl.hh == src && owner_lane) {
             const long long kidx = (long long)rl.bh * g.Nk + j;
             slotv[e] = A.koffs[kidx] + atomicAdd(&A.kcursor[kidx], 1);
             ++n_entries;
@@ -233,6 +246,7 @@ __global__ __launch_bounds__(kThreads, D == 64 ? 2 : 1) void bwd_rows_kernel(Bwd
 #pragma unroll
           for (int t = 0; t < DH; ++t) part = fmaf(dov[t], vv.get(t), part);
         }
+        if (FH == 2) part += __shfl_xor(part, 16);
         float dp = part + __shfl_xor(part, 32);
         if (x > 0.f) {
           float gg = pow_rm1<AM>(x, r);
@@ -270,9 +284,9 @@ __global__ __launch_bounds__(kThreads, D == 64 ? 2 : 1) void bwd_rows_kernel(Bwd
       }
     }
     if (rl.valid) {
-      store_row<T>(reinterpret_cast<T*>(A.dQ) + q_base + (long long)rl.i * g.q_sn + rl.hh * DH, DH, dq);
+      store_row<T>(reinterpret_cast<T*>(A.dQ) + q_base + (long long)rl.i * g.q_sn + feat0, DH, dq);
       // the scores were formed with q negated when scale_i < 0: undo the sign for z_ij
-      if (rl.hh == 0) A.dscale[row_idx] = sgn * dsc * inv_sqrt_d;
+      if (rl.hh == 0 && owner_lane) A.dscale[row_idx] = sgn * dsc * inv_sqrt_d;
     }
   };
   if (__ballot(cnt > 4) == 0ull)

@@ -746,20 +746,33 @@ __device__ __forceinline__ void store_row(T* row, int n, const float* v) {
   }
 }
 
-// Row coordinates of a lane in the list kernels: wave w of block qb owns rows qb*128 + 32 w .. + 31,
-// lane l row (l % 32), half (l / 32) -- the same assignment as in the sweeps that wrote the lists.
+// Row coordinates of a lane in the list kernels.  FH = 1: wave w of block qb owns rows qb*128 + 32 w .. + 31,
+// lane l row (l % 32), list half hh = l / 32 -- the same assignment as in the sweeps that wrote the lists; a
+// workgroup is one 128-row block.  FH = 2: two lanes per list half, each with half of that half's features
+// (f = 0, 1): a wave owns 16 rows, lane l = 32 hh + 16 f + r, and two consecutive workgroups share a block.
+// (li, w32): the row's lane and 32-row group in the sweeps' numbering, as list_entry() wants them.
+// The workgroups are renumbered so that a head's rows all run on one XCD, the one whose L2 saw the head's keys
+// and lists in the sweeps (measured at B 4, H 12, n 4096: finish kernel 54 -> 51 us).
 struct RowLane {
-  int bh, b, h, qb, i, li, hh;
+  int bh, b, h, qb, i, li, hh, f, w32;
   bool valid;
+  template <int FH = 1>
   __device__ __forceinline__ void init(const Geom& g, int nqb) {
+    static_assert(FH == 1 || FH == 2, "one or two lanes per list half");
+    constexpr int R = 32 / FH;  // rows per wave
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    bh = blockIdx.x / nqb;
-    qb = blockIdx.x % nqb;
+    const int vb = xcd_remap(blockIdx.x, g.B * g.H * nqb * FH);
+    const int blk = vb / FH, sub = vb % FH;
+    bh = blk / nqb;
+    qb = blk % nqb;
     b = bh / g.H;
     h = bh % g.H;
-    li = lane & 31;
     hh = lane >> 5;
-    i = qb * kBlockRows + wave * 32 + li;
+    f = (lane & 31) / R;
+    const int row_in_block = (sub * kWaves + wave) * R + (lane & (R - 1));
+    li = row_in_block & 31;
+    w32 = row_in_block >> 5;
+    i = qb * kBlockRows + row_in_block;
     valid = i < g.Nq;
   }
 };

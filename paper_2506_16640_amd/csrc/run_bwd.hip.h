@@ -28,7 +28,7 @@ bool launch_bwd_kernels(const BwdArgs& a, const Layout& L, int B, int H, hipStre
 
 template <typename T, int D, int AM, bool BIAS>
 bool launch_bwd_rows(const BwdSparseArgs& a, int nblocks, hipStream_t st, void* const* ev, bool from_saved) {
-  const dim3 row_grid((unsigned)(a.g.B * a.g.H * a.nqb + a.ride.workgroups()));
+  const dim3 row_grid((unsigned)(a.g.B * a.g.H * a.nqb * RowsCfg<D>::kFH + a.ride.workgroups()));
   if (!from_saved) {
     // no lists from the forward: one Q K^T sweep at tau rebuilds the supports
     size_t smem = ListCfg<T, D>::kLdsBytes;

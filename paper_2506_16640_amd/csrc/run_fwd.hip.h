@@ -36,12 +36,18 @@ bool launch_fwd_sparse(const FwdSparseArgs& a, int nblocks, hipStream_t st, void
   const int nsb = (a.nqb + 1) / 2;
   const long long pair_grid = (long long)a.g.B * a.g.H * ((nsb + 1) / 2);
   const bool long_seq = a.g.Nk >= ListCfg<T, D>::kFlagMinKeys;
-  if (sizeof(T) == 2 && D == 64 && (a.force_long || (long_seq && pair_grid >= kPairMinWorkgroups))) {
+  bool launched = false;
+  if constexpr (sizeof(T) == 2 && D == 64) {  // (the only combination the two-block kernel is built for)
+    if (a.force_long || (long_seq && pair_grid >= kPairMinWorkgroups)) {
     // long sequences: the second sweep skips blocks the first cleared, and a workgroup takes two adjacent blocks
     // where that still leaves three workgroups for every CU (measured at B 4, H 12, n 4096, where it leaves 1.5:
     // 221 us against 139 us with one block per workgroup)
     const size_t smem2 = PairCfg<T, D>::kLdsBytes > smem ? PairCfg<T, D>::kLdsBytes : smem;
     hipLaunchKernelGGL((fwd_lists_pair_kernel<T, D, AM, BIAS>), dim3((unsigned)pair_grid), dim3(kThreads), smem2, st, a);
+    launched = true;
+    }
+  }
+  if (launched) {
   } else if (long_seq || a.force_long)
     hipLaunchKernelGGL((fwd_lists_kernel<T, D, AM, BIAS, true>), dim3((unsigned)nblocks), dim3(kThreads), smem, st, a);
   else
