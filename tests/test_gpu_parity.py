@@ -201,6 +201,21 @@ def test_long_sequence_skips_blocks_in_the_second_sweep():
         assert st["fwd_list_qk"] < 2 * st["fwd_tiles_visible"] * 0.9, st  # the second sweep skipped blocks
 
 
+@pytest.mark.parametrize("n,path", [(30720 + 300, 0), (65536 + 200, 2)])
+def test_block_bits_end_before_the_sequence(n, path, forward_path):
+    """The block bits of the long-sequence list kernels cover 30720 keys (one block per workgroup) or 65536 keys
+    (two blocks per workgroup, forced here with params.path = 2); key blocks beyond that range must always be
+    computed in the second sweep.  One head, forward, every row against the oracle."""
+    if forward_path == 1:
+        pytest.skip("the list kernels are the subject")
+    data = synth.make_inputs(B=1, H=1, n=n, d=64, dtype="bf16", scale="head", planted=0.05, seed=17, want_dO=False)
+    g = gpu_run(data, 1.5, "bf16", bwd=False, stats=True, path=path)
+    r = oracle_run(data, 1.5, bwd=False)
+    st = g["stats"]
+    print(n, path, compare(g, r, bwd=False, label=f"bits range n{n}"), {k_: v for k_, v in st.items() if v})
+    assert st["fwd_sparse_blocks"] == (n + 127) // 128 and st["fwd_list_qk"] < 2 * st["fwd_tiles_visible"], st
+
+
 @pytest.mark.parametrize("causal,nq,nk,alpha,scale", [(True, 300, 300, 1.5, "head"), (True, 641, 641, 1.5, "head"),
                                                       (False, 200, 333, 1.5, "head"), (True, 333, 200, 2.0, "head"),
                                                       (True, 200, 333, 1.25, "head"), (True, 1, 70, 1.5, "head"),
