@@ -751,8 +751,9 @@ __device__ __forceinline__ void store_row(T* row, int n, const float* v) {
 // workgroup is one 128-row block.  FH = 2: two lanes per list half, each with half of that half's features
 // (f = 0, 1): a wave owns 16 rows, lane l = 32 hh + 16 f + r, and two consecutive workgroups share a block.
 // (li, w32): the row's lane and 32-row group in the sweeps' numbering, as list_entry() wants them.
-// The workgroups are renumbered so that a head's rows all run on one XCD, the one whose L2 saw the head's keys
-// and lists in the sweeps (measured at B 4, H 12, n 4096: finish kernel 54 -> 51 us).
+// Where the heads divide evenly over the eight XCDs the workgroups are renumbered so that a head's rows all run on
+// one XCD, the one whose L2 saw the head's keys and lists in the sweeps (finish kernel, measured on one box:
+// B 4, H 12, n 4096: 54 -> 50 us; with 12 heads at n 32768, one and a half heads per XCD, it was 60 -> 73 us).
 struct RowLane {
   int bh, b, h, qb, i, li, hh, f, w32;
   bool valid;
@@ -761,7 +762,7 @@ struct RowLane {
     static_assert(FH == 1 || FH == 2, "one or two lanes per list half");
     constexpr int R = 32 / FH;  // rows per wave
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int vb = xcd_remap(blockIdx.x, g.B * g.H * nqb * FH);
+    const int vb = (g.B * g.H) % 8 == 0 ? xcd_remap(blockIdx.x, g.B * g.H * nqb * FH) : (int)blockIdx.x;
     const int blk = vb / FH, sub = vb % FH;
     bh = blk / nqb;
     qb = blk % nqb;
