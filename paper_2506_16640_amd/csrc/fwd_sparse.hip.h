@@ -272,6 +272,8 @@ __device__ __forceinline__ void fwd_lists_block(const FwdSparseArgs& A, int bh_,
   if (keep_bits)
     for (int w = threadIdx.x; w < kWaves * Cfg::kFlagWords; w += kThreads) allbits[w] = 0u;  // (first barrier: the sweep's)
 
+  if (threadIdx.x < kWaves) ovf[threadIdx.x] = 0;  // during the first sweep: the waves' votes (see `votes` below)
+
   C q;
   q.init(g, A.Q, bh_, blk_);
   q.init_window(g);
@@ -300,6 +302,14 @@ __device__ __forceinline__ void fwd_lists_block(const FwdSparseArgs& A, int bh_,
   float m1 = -kInf, m2 = -kInf;
   // BITS: the bracket's width in raw units, a little wider than needed (rounding); lanes without a live row never pass
   const float reach = (q.valid && q.lim > 0) ? (q.a > 0.f ? 1.0001f / q.a : 3.0e38f) : -kInf;
+  // Dense rows are found out on the first tile: where, for three quarters of a wave's rows, half of the keys of
+  // the tile's first block come within the bracket's width of the block's largest score, the lists would overflow anyway (a row of
+  // the paper's sparse setting has a handful of such keys).  A block all of whose waves vote so is handed to the
+  // tiled kernel after two tiles instead of after a full sweep (a matter of time only: the tiled kernel handles
+  // any row).  votes: one word per wave in the overflow flags' place, which the second sweep zeroes again.
+  int* votes = ovf;
+  int kt_vote = 0;  // the first tile of the sweep
+  if constexpr (BIAS) kt_vote = q.kt_first;
   auto max_body = [&](int kt, const char* tl) {
         if (!q.tile_in_wave_window(kt)) return;
         uint32_t bits = 0u;
@@ -309,6 +319,12 @@ __device__ __forceinline__ void fwd_lists_block(const FwdSparseArgs& A, int bh_,
 #pragma unroll
           for (int sb = 0; sb < NSB; ++sb) {
             float lm = max16(acc[sb]);
+            if (sb == 0 && kt == kt_vote) {  // the vote, on the lane's 16 keys of the tile's first block
+              int near = 0;
+#pragma unroll
+              for (int e = 0; e < 16; ++e) near += (acc[0][e] + reach > lm) ? 1 : 0;
+              if (__popcll(__ballot(near >= 8)) >= 48 && q.lane == 0) votes[q.wave] = 1;
+            }
             m2 = fmaxf(m2, fminf(m1, lm));
             m1 = fmaxf(m1, lm);
             if (keep_bits && __ballot(lm + reach > m1) != 0ull) bits |= 1u << sb;
@@ -336,8 +352,17 @@ __device__ __forceinline__ void fwd_lists_block(const FwdSparseArgs& A, int bh_,
         // (each wave writes only its own words)
         if (bits != 0u && (kt + 1) * NSB <= Cfg::kFlagWords * 32 && q.lane == 0) mybits[(kt * NSB) >> 5] |= bits << ((kt * NSB) & 31);
       };
+  auto all_dense = [&]() { return (votes[0] & votes[1] & votes[2] & votes[3]) != 0; };
   sweep_tiles<C, T, D, 1, 0, ListCfg<T, D>::kDepth>(
-      tiles, slots, q.ntiles, g.Nk, q.tid, [&](int kt) { return q.tile_in_window(kt); }, max_body);
+      tiles, slots, q.ntiles, g.Nk, q.tid, [&](int kt) { return q.tile_in_window(kt); }, max_body,
+      // (the votes of a tile are final before the barrier that ends it)
+      [&](int kt) { return kt == kt_vote + 1 && all_dense(); });
+  if (all_dense()) {  // (the sweep ended on a barrier)
+    __syncthreads();  // every thread has read the votes before the next block's zeroes them
+    if (q.tid == 0) A.dense_flag[flag_idx] = 1;
+    if (A.stats && q.lane == 0) atomicAdd(&A.stats[ENTMAX_STAT_FWD_LIST_QK], (unsigned long long)n_vis);
+    return;
+  }
   {
     float p1 = __shfl_xor(m1, 32), p2 = __shfl_xor(m2, 32);
     float hi1 = fmaxf(m1, p1);

@@ -56,6 +56,23 @@ def test_bf16_dense_regime(alpha):
     print(alpha, compare(g, r, label=f"dense a{alpha}"))
 
 
+def test_dense_blocks_leave_the_list_kernel_early(forward_path):
+    """Rows that keep most of their keys (delta = 0, gamma = -1/2) are recognised on the list kernel's first key
+    tile, and the block goes to the tiled kernel after two tiles instead of a full sweep: same results, and the
+    list kernel computes only a fraction of the visible tiles."""
+    if forward_path == 1:
+        pytest.skip("the list kernel is the subject")
+    n = 1536
+    data = _case(1, 2, n, n, 64, "bf16", "dense", seed=4)
+    g = gpu_run(data, 1.5, "bf16", stats=True)
+    r = oracle_run(data, 1.5)
+    st = g["stats"]
+    print(compare(g, r, label="dense early exit"), {k: v for k, v in st.items() if v})
+    assert st["fwd_sparse_blocks"] == 0 and st["fwd_blocks"] > 0
+    # 12 blocks a head: the first has one tile and makes no verdict, the others stop after two tiles (8 blocks of 32 keys)
+    assert st["fwd_list_qk"] <= 2 * 4 * (4 + 11 * 8) + 64, st
+
+
 @pytest.mark.parametrize("scale,alpha,dtype", [("none", 1.5, "bf16"), ("none", 1.7, "bf16"), ("head", 1.25, "bf16"),
                                                ("none", 1.7, "fp32")])
 def test_moderate_support(scale, alpha, dtype):
