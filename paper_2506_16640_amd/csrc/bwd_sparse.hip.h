@@ -202,7 +202,8 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_rows_kernel(BwdSparseArgs A) 
         en = early[e];
       else if (e < cnt)
         en = rdlist[e * lstride];
-      jv[e] = (e < cnt) ? en.x : 0u;
+      // (a key index is never followed outside the tensors, whatever a stale or foreign `saved` buffer holds)
+      jv[e] = (e < cnt) ? min(en.x, (unsigned)(g.Nk - 1)) : 0u;
       dv[e] = (e < cnt) ? __uint_as_float(en.y) : -kInf;
     }
     // One gather pass over the entries of the row (both halves): dP = <dO, v_j> and, because dQ and dscale
