@@ -162,7 +162,7 @@ enum {
  *        average (under half the size of O at D = 64), and a larger buffer gives a larger pool.  A 128-row query
  *        block that finds the pool used up, or has a half row with more than 16 support entries, is marked for
  *        the backward's tiled kernels instead (same results up to rounding; slower).  When the pool runs out,
- *        which blocks are marked depends on the order the workgroups arrive in.  Opaque; valid only together
+ *        which blocks are marked depends on the order the workgroups arrive in.  Needs Nk <= 2^22 (as everything).  Opaque; valid only together
  *        with this call's tau and the same params, inputs and saved_bytes.
  *   saved_bytes: size of `saved` (ignored when saved is NULL); less than entmax_attn_saved_bytes(p) is
  *        refused with WORKSPACE_TOO_SMALL before anything is launched.

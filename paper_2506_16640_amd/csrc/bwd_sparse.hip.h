@@ -189,11 +189,29 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_rows_kernel(BwdSparseArgs A) 
   uint2 early[kEarly];
 #pragma unroll
   for (int e = 0; e < kEarly; ++e) early[e] = rdlist[e * lstride];
-  if (head_dense != 0) return;  // the tiled kernels own this block
+  if (head_dense != 0) {  // the tiled kernels own this block
+    // The forward numbered this block's entries among their keys' entries before it knew that the block would
+    // not take the list path: in a head whose other blocks do, those places must not stay undefined.  They get
+    // records that add nothing.
+    if (A.packed && owner_lane && A.block_flag[rl.bh * A.nqb + rl.qb] == kBlockListsUnused && A.head_flag[rl.bh] == kHeadMixed) {
+      const long long cap = (long long)g.Nq * 2 * kBwdCap;
+      for (int e = 0; e < cnt; ++e) {
+        const uint2 en = rdlist[e];
+        const unsigned key = min(en.x & ((1u << kSavedKeyBits) - 1u), (unsigned)(g.Nk - 1)), rank = en.x >> kSavedKeyBits;
+        const long long kidx = (long long)rl.bh * g.Nk + key;
+        const int slot = A.koffs[kidx] + (rank < kSavedRankMost ? (int)rank : (int)kSavedRankMost + atomicAdd(&A.kcursor[kidx], 1));
+        if (slot >= 0 && slot < cap) {
+          A.csc_i[rl.bh * cap + slot] = min(rl.i, g.Nq - 1);
+          A.csc_pw[rl.bh * cap + slot] = make_float2(0.f, 0.f);
+        }
+      }
+    }
+    return;
+  }
 
   auto finish = [&](auto ne_tag) {
     constexpr int NE = decltype(ne_tag)::value;
-    unsigned jv[NE];
+    unsigned jv[NE], rkv[NE];
     float dv[NE];  // raw dot products (sign-folded), -inf for empty slots
 #pragma unroll
     for (int e = 0; e < NE; ++e) {
@@ -202,6 +220,9 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_rows_kernel(BwdSparseArgs A) 
         en = early[e];
       else if (e < cnt)
         en = rdlist[e * lstride];
+      // the forward's entries carry their arrival number among their key's entries above the key index
+      rkv[e] = A.packed ? en.x >> kSavedKeyBits : kSavedRankMost;
+      if (A.packed) en.x &= (1u << kSavedKeyBits) - 1u;
       // (a key index is never followed outside the tensors, whatever a stale or foreign `saved` buffer holds)
       jv[e] = (e < cnt) ? min(en.x, (unsigned)(g.Nk - 1)) : 0u;
       dv[e] = (e < cnt) ? __uint_as_float(en.y) : -kInf;
@@ -241,7 +262,10 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_rows_kernel(BwdSparseArgs A) 
           // the entry's owner takes its arrival number among the key's entries: its place in the key's segment
           if (rl.hh == src && owner_lane) {
             const long long kidx = (long long)rl.bh * g.Nk + j;
-            slotv[e] = A.koffs[kidx] + atomicAdd(&A.kcursor[kidx], 1);
+            // its arrival number: the forward's, or (lists made here, and a key's entries beyond the numbers
+            // the forward can write) from the key's cursor
+            slotv[e] = A.koffs[kidx] +
+                       (rkv[e] < kSavedRankMost ? (int)rkv[e] : (A.packed ? (int)kSavedRankMost : 0) + atomicAdd(&A.kcursor[kidx], 1));
             ++n_entries;
           }
 #pragma unroll
@@ -433,7 +457,8 @@ __global__ __launch_bounds__(kThreads) void bwd_keys_kernel(BwdSparseArgs A) {
   on = on && hflag != kHeadTiled;
   const int b = bh / g.H, h = bh % g.H;
   const int seg = on ? A.kcount[key] : 0;            // size of the key's segment
-  int n = on ? min(A.kcursor[key], seg) : 0;         // entries with p > 0 placed in it
+  // entries with p > 0 placed in it: with the forward's numbers all of them, but for what the cursor counted beyond
+  int n = on ? (A.packed ? min(seg, (int)kSavedRankMost + A.kcursor[key]) : min(A.kcursor[key], seg)) : 0;
   if (seg > kSortedKeyEntries) {  // on the long-key list
     on = false;
     n = 0;
@@ -523,7 +548,8 @@ __device__ __forceinline__ void bwd_long_keys_part(const BwdSparseArgs& A, int v
   const int lbh = h0 + hu;
   const int idx = gidx - (__builtin_amdgcn_readlane(my_end, hu) - __builtin_amdgcn_readlane(my_count, hu));
   const long long key = __builtin_amdgcn_readfirstlane(A.long_keys[(long long)lbh * g.Nk + idx]);
-  const int n = __builtin_amdgcn_readfirstlane(min(A.kcursor[key], A.kcount[key]));
+  const int n = __builtin_amdgcn_readfirstlane(
+      A.packed ? min(A.kcount[key], (int)kSavedRankMost + A.kcursor[key]) : min(A.kcursor[key], A.kcount[key]));
   const int bh = (int)(key / g.Nk), j = (int)(key % g.Nk);
   const int b = bh / g.H, h = bh % g.H;
   const long long base = (long long)bh * g.Nq * 2 * kBwdCap + __builtin_amdgcn_readfirstlane(A.koffs[key]);

@@ -18,6 +18,16 @@ constexpr int kListStride = 64;  // lists are stored slot-major per wave: entry 
 // The `saved` buffer packs the rows' support lists into a pool: the size the library asks for holds this many
 // entries per row on average (a larger buffer gives a larger pool), at least kSavedPoolFloor (one block's worst
 // case), plus kSavedPoolPad entries behind the end that speculative reads may touch.
+// A packed entry's first word is the key index (22 bits: Nk <= 2^22) with, above it, the entry's arrival number
+// among its key's entries, so that the backward knows its place in the key's segment without asking; the largest
+// value stands for "later than that" (those entries take their place from a cursor in the backward).
+constexpr int kSavedKeyBits = 22;
+constexpr unsigned kSavedRankMost = (1u << (32 - kSavedKeyBits)) - 1u;  // 1023
+// Values of a block's flag in the `saved` buffer besides 0 (the backward takes its list path): the forward wrote
+// lists for the block's rows and numbered their entries before it found a list too long (the backward's tiled
+// kernels take the block, and the entries' places in the key-major arrays are filled with zeros), or it wrote none.
+constexpr int kBlockListsUnused = 1;
+constexpr int kBlockNoLists = 2;
 constexpr int kSavedPerRow = 6;
 constexpr int kSavedPoolFloor = kThreads * kBwdCap;
 constexpr int kSavedPoolPad = 4;

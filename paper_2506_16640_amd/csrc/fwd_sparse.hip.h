@@ -54,7 +54,8 @@ struct FwdSparseArgs {
   int pool_parts;          // with list: parts the pool is cut into (a power of two)
   long long pool_part_cap; // with list: entries a part holds
   int* slcnt;       // with list: [B*H*Nq][2] per half row: (place of its first entry in the pool) << 5 | entries
-  int* bwd_flag;    // with list: [B*H*nqb] 1: the backward cannot take its list path for this block
+  int* bwd_flag;    // with list: [B*H*nqb] not 0: the backward cannot take its list path for this block
+                    // (kBlockListsUnused, kBlockNoLists)
   int* kcount;      // with list: [B*H*Nk] support entries naming each key (zeroed by the list kernel, counted by
                     // the finish kernel): the sizes of the backward's key-major segments
   void* cells;      // sweep scratch: one CellBuf<kCandCap> per workgroup of the list sweep's grid
@@ -837,7 +838,7 @@ __global__ __launch_bounds__(kThreads) void fwd_finish_kernel(FwdSparseArgs A) {
 #pragma unroll
   for (int e = 0; e < kEarly; ++e) early[e] = mylist[e * kListStride];
   if (block_dense != 0) {  // the tiled kernel owns this block, and so do the backward's tiled kernels
-    if (A.list && threadIdx.x == 0) A.bwd_flag[rl.bh * A.nqb + rl.qb] = 1;
+    if (A.list && threadIdx.x == 0) A.bwd_flag[rl.bh * A.nqb + rl.qb] = kBlockNoLists;
     if (threadIdx.x == 0) {
       int* count = A.dense_flag + g.B * g.H * A.nqb;
       const int slot = atomicAdd(count, 1);
@@ -920,8 +921,9 @@ __global__ __launch_bounds__(kThreads) void fwd_finish_kernel(FwdSparseArgs A) {
       if (p_own > 0.f) {
         ++n_support;
         if (suplist && scnt < kBwdCap) {
-          suplist[scnt] = make_uint2(jv[e], __float_as_uint(dvv[e]));
-          atomicAdd(&A.kcount[(long long)rl.bh * g.Nk + jv[e]], 1);
+          // (writing the entries after the gathers, so that the counter's answer is not waited for here, gained nothing)
+          const unsigned rank = (unsigned)atomicAdd(&A.kcount[(long long)rl.bh * g.Nk + jv[e]], 1);
+          suplist[scnt] = make_uint2(jv[e] | (min(rank, kSavedRankMost) << kSavedKeyBits), __float_as_uint(dvv[e]));
         }
         ++scnt;
       }
@@ -949,8 +951,8 @@ __global__ __launch_bounds__(kThreads) void fwd_finish_kernel(FwdSparseArgs A) {
         if (p_own > 0.f) {
           ++n_support;
           if (suplist && scnt < kBwdCap) {
-            suplist[scnt] = en;
-            atomicAdd(&A.kcount[(long long)rl.bh * g.Nk + en.x], 1);
+            const unsigned rank = (unsigned)atomicAdd(&A.kcount[(long long)rl.bh * g.Nk + en.x], 1);
+            suplist[scnt] = make_uint2(en.x | (min(rank, kSavedRankMost) << kSavedKeyBits), en.y);
           }
           ++scnt;
         }
@@ -984,7 +986,7 @@ __global__ __launch_bounds__(kThreads) void fwd_finish_kernel(FwdSparseArgs A) {
     // a support longer than the backward's lists hold, or no room left in the pool, sends the block to the
     // backward's tiled kernels
     const int any_long = __syncthreads_or((scnt > kBwdCap || pool_full) ? 1 : 0);
-    if (threadIdx.x == 0) A.bwd_flag[rl.bh * A.nqb + rl.qb] = any_long ? 1 : 0;
+    if (threadIdx.x == 0) A.bwd_flag[rl.bh * A.nqb + rl.qb] = any_long ? kBlockListsUnused : 0;
   }
   if (A.stats) {
     unsigned sup = n_support, cands = (unsigned)cnt;

@@ -108,7 +108,7 @@ int run_fwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
     // a few query rows against the whole key sequence: split the keys over the chip
     if (p->Nq > 0 && p->B * p->H > 0) {
       // no lists for the backward: every block belongs to its tiled kernels
-      if (saved && !fill_words(saved + L.sv_flags, (size_t)p->B * p->H * L.nqb * sizeof(int), 1u, st))
+      if (saved && !fill_words(saved + L.sv_flags, (size_t)p->B * p->H * L.nqb * sizeof(int), (unsigned)kBlockNoLists, st))
         return ENTMAX_ATTN_LAUNCH_FAILED;
       if (BIAS && saved && !launch_key_norms<T, D>(p, L, K, knorm, st)) return ENTMAX_ATTN_LAUNCH_FAILED;
       record(ev, ENTMAX_FWD_PHASE_PREPARE + 1, st);
@@ -170,7 +170,7 @@ int run_fwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
     if (!launch_fwd_sparse_am<T, D, BIAS>(sa, alpha_mode(p->alpha), npairs, st, ev)) return ENTMAX_ATTN_LAUNCH_FAILED;
   } else {
     // no lists: tell the backward that every block belongs to its tiled kernels
-    if (saved && !fill_words(saved + L.sv_flags, (size_t)p->B * p->H * L.nqb * sizeof(int), 1u, st))
+    if (saved && !fill_words(saved + L.sv_flags, (size_t)p->B * p->H * L.nqb * sizeof(int), (unsigned)kBlockNoLists, st))
       return ENTMAX_ATTN_LAUNCH_FAILED;
     record(ev, ENTMAX_FWD_PHASE_LISTS + 1, st);
   }

@@ -194,6 +194,20 @@ def test_saved_pool_runs_out(roomy):
         assert st["bwd_dq_tiles"] > 0, st
 
 
+def test_hot_keys_beyond_the_forward_numbering():
+    """The forward numbers each support entry among its key's entries (the backward places it in the key's segment
+    by that number), in 10 bits next to the key index.  Here ten keys are in the support of all 1300 rows: their
+    entries beyond the 1023rd take their place from the backward's cursor instead.  With the forward's lists
+    (roomy buffer, so that every block stays on the list path) and without."""
+    data, _ = _mid_band_case(1.5, nq=1300)
+    r = oracle_run(data, 1.5, causal=False)
+    for use_saved in (True, False):
+        g = gpu_run(data, 1.5, "bf16", causal=False, stats=True, path=0, use_saved=use_saved, saved_factor=8)
+        st = g["stats"]
+        print(use_saved, compare(g, r, label=f"hot keys saved={use_saved}"), {k: v for k, v in st.items() if v})
+        assert st["bwd_support"] == 2 * 1300 * 10 and st["bwd_dq_tiles"] == 0, st
+
+
 def test_long_sequence_skips_blocks_in_the_second_sweep():
     """From 16384 keys on, the list kernel's first sweep keeps one bit per (32-row group, 32-key block) and the
     second sweep computes only the marked blocks.  Ragged length beyond the range the bits cover is not needed
