@@ -485,20 +485,36 @@ __global__ __launch_bounds__(kThreads) void bwd_keys_kernel(BwdSparseArgs A) {
   float dv[DL], dk[DL];
 #pragma unroll
   for (int t = 0; t < DL; ++t) dv[t] = dk[t] = 0.f;
+  // kB entries at a time: their rows are all requested before the first is used (one memory round trip for most
+  // keys instead of one per entry); the sums still run in query order.  Four where a lane's share of a row is one
+  // 16-byte word (B 4, H 12, n 4096, D 64: 47 -> 38 us); with 32 bytes per lane the registers of four cost more
+  // than the round trips (B 2, H 16, n 8192, D 128: 83 -> 93 us), so one.
+  constexpr int kB = DL * (int)sizeof(T) <= 16 ? 4 : 1;
 #pragma unroll
-  for (int t = 0; t < 8; ++t) {
-    if (__ballot(t < n) == 0ull) break;
-    int i = __shfl(si, group0 + t);
-    const float p = __shfl(sp, group0 + t), w = __shfl(sw, group0 + t);
-    if (t < n) {
-      i = min(max(i, 0), g.Nq - 1);  // a valid row by construction; never index outside the tensor
-      RawRow<T, DL> rd, rq;
-      rd.load(dObh + (long long)i * g.q_sn);
-      rq.load(Qbh + (long long)i * g.q_sn);
+  for (int t0 = 0; t0 < 8; t0 += kB) {
+    if (__ballot(t0 < n) == 0ull) break;
+    RawRow<T, DL> rd[kB], rq[kB];
+    float pe[kB], we[kB];
 #pragma unroll
-      for (int u = 0; u < DL; ++u) {
-        dv[u] = fmaf(p, rd.get(u), dv[u]);
-        dk[u] = fmaf(w, rq.get(u), dk[u]);
+    for (int u = 0; u < kB; ++u) {
+      const int t = t0 + u;
+      int i = __shfl(si, group0 + t);
+      pe[u] = __shfl(sp, group0 + t);
+      we[u] = __shfl(sw, group0 + t);
+      if (t < n) {
+        i = min(max(i, 0), g.Nq - 1);  // a valid row by construction; never index outside the tensor
+        rd[u].load(dObh + (long long)i * g.q_sn);
+        rq[u].load(Qbh + (long long)i * g.q_sn);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < kB; ++u) {
+      if (t0 + u < n) {
+#pragma unroll
+        for (int f = 0; f < DL; ++f) {
+          dv[f] = fmaf(pe[u], rd[u].get(f), dv[f]);
+          dk[f] = fmaf(we[u], rq[u].get(f), dk[f]);
+        }
       }
     }
   }
