@@ -318,6 +318,25 @@ __device__ __forceinline__ void fwd_block(const FwdArgs& A, int bh_, int blk_, i
   slots[1].row_bytes = (long long)g.npad_k * (long long)sizeof(T);
 
   unsigned n_vis = 0, n_qk_solve = 0, n_eval = 0, n_qk_pv = 0, n_pv = 0, n_sweeps = 0;
+  // The sweeps over K alone (row maximum, threshold).  SPLIT with two 32-key blocks per tile (D = 64): two key tiles
+  // between barriers -- with one, half of the waves have no block of their own in it, and every tile costs a
+  // barrier and a wait for the staged copy whatever the work (B 4, H 12, n 4096, alpha 1.25, 183 flagged blocks:
+  // 351 -> 275 us).  With four blocks per tile (D = 128) every wave has one already, and pairs were slower
+  // (B 2, H 16, n 8192: 1042 -> 1106 us).
+  auto sweep_k = [&](auto needed, auto body) {
+    if constexpr (SPLIT && NSB < kWaves) {
+      Slot kk[2] = {slots[0], slots[0]};
+      sweep_tiles<C, T, D, 2, 0, kFwdDepth, 2>(
+          tiles, kk, q.ntiles, g.Nk, q.tid,
+          [&](int kp) { return needed(2 * kp) || (2 * kp + 1 < q.ntiles && needed(2 * kp + 1)); },
+          [&](int kp, const char* tl) {
+            body(2 * kp, tl);
+            if (2 * kp + 1 < q.ntiles) body(2 * kp + 1, tl + TB);
+          });
+    } else {
+      sweep_tiles<C, T, D, 1, 0, kFwdDepth>(tiles, slots, q.ntiles, g.Nk, q.tid, needed, body);
+    }
+  };
 
   // mask of a 32-key block whose keys are not all visible to all rows of the wave
   auto mask_block = [&](f32x16_t& acc, int j0) {
@@ -330,8 +349,8 @@ __device__ __forceinline__ void fwd_block(const FwdArgs& A, int bh_, int blk_, i
   float m = -kInf;
   // sums of the raw scores and of their squares over the blocks every row of the wave sees in full (gauss_start)
   float ms1 = 0.f, ms2 = 0.f, msn = 0.f;
-  sweep_tiles<C, T, D, 1, 0, kFwdDepth>(
-      tiles, slots, q.ntiles, g.Nk, q.tid, [&](int kt) { return q.tile_in_window(kt); },
+  sweep_k(
+      [&](int kt) { return q.tile_in_window(kt); },
       [&](int kt, const char* tl) {
         if (!q.tile_in_wave_window(kt)) return;
         each_block(kt, tl, q.visible_bits(kt) & own_bits(kt), [&](f32x16_t& acc, int sb) {
@@ -393,7 +412,7 @@ __device__ __forceinline__ void fwd_block(const FwdArgs& A, int bh_, int blk_, i
     sums.clear();
     const bool first = (iter == 0);
     auto needed = [&](int kt) { return first ? q.tile_in_window(kt) : wm.tile_bits<NSB>(kWaves, kt) != 0u; };
-    sweep_tiles<C, T, D, 1, 0, kFwdDepth>(tiles, slots, q.ntiles, g.Nk, q.tid, needed, [&](int kt, const char* tl) {
+    sweep_k(needed, [&](int kt, const char* tl) {
       if (!wave_on || !q.tile_in_wave_window(kt)) return;
       uint32_t act = q.visible_bits(kt) & own_bits(kt);
       if (!first) act &= wm.tile_bits<NSB>(q.wave, kt);
@@ -541,7 +560,9 @@ __device__ __forceinline__ void fwd_block(const FwdArgs& A, int bh_, int blk_, i
 inline int fwd_workgroups(int nheads, int nqb, bool flags) {
   const int npairs = nheads * ((nqb + 1) >> 1);
   if (!flags) return npairs;
-  const long long split = (long long)kWaves * (nheads * (long long)nqb < kSplitMaxBlocks ? nheads * nqb : kSplitMaxBlocks);
+  // (split: the flagged blocks are dealt out in eights, one to each XCD -- see fwd_kernel)
+  const long long nsplit = nheads * (long long)nqb < kSplitMaxBlocks ? nheads * (long long)nqb : kSplitMaxBlocks;
+  const long long split = (long long)kWaves * ((nsplit + 7) / 8 * 8);
   return npairs > split ? npairs : (int)split;
 }
 
@@ -551,11 +572,14 @@ __global__ __launch_bounds__(kThreads, (FwdTile<T, D>::kOcc)) void fwd_kernel(Fw
   const int nheads = A.g.B * A.g.H, npairs = nheads * ((A.nqb + 1) >> 1);
   const int nflagged = A.dense_count ? __builtin_amdgcn_readfirstlane(A.dense_count[0]) : kSplitMaxBlocks + 1;
   if (nflagged <= kSplitMaxBlocks) {
-    // one workgroup per (flagged block, 32-row group); the blocks' numbers follow the count
-    const int slot = blockIdx.x / kWaves;
+    // one workgroup per (flagged block, 32-row group); the blocks' numbers follow the count.  Consecutive
+    // workgroups go to the eight XCDs in turn: the four row groups of a block take four consecutive places on
+    // one XCD, so that the block's key tiles pass through one L2 instead of four.
+    const int xcd = blockIdx.x & 7, place = blockIdx.x >> 3;
+    const int slot = (place / kWaves) * 8 + xcd;
     if (slot >= nflagged) return;
     const int item = __builtin_amdgcn_readfirstlane(A.dense_count[1 + slot]);
-    fwd_block<T, D, AM, BIAS, true>(A, item / A.nqb, item % A.nqb, blockIdx.x % kWaves, smem);
+    fwd_block<T, D, AM, BIAS, true>(A, item / A.nqb, item % A.nqb, place % kWaves, smem);
     return;
   }
   if ((int)blockIdx.x >= npairs) return;

@@ -260,12 +260,19 @@ struct NeverAbort {
 // enough where several workgroups share a compute unit and hide each other's waits; a workgroup that has a
 // compute unit (nearly) to itself needs two, or every tile costs a full memory round trip.  With DEPTH 2 the
 // tile already on its way when abort(kt) turns true is still processed.
-template <typename C, typename T, int D, int NSLOT, int TMASK, int DEPTH = 1, class Needed, class Body,
+// STEP 2: the slots are two copies of one natural-layout tensor and step kt brings its tiles 2 kt and 2 kt + 1 (slot
+// 0 and slot 1) between the same two barriers; ntiles still counts single tiles, needed(kt) and body(kt, tiles) count
+// pairs, and the second tile of the last pair may lie beyond the sweep (it is then a copy of the last tile, which the
+// body leaves alone).  For a workgroup whose waves share out the keys of a tile: twice the work per barrier.
+template <typename C, typename T, int D, int NSLOT, int TMASK, int DEPTH = 1, int STEP = 1, class Needed, class Body,
           class Abort = NeverAbort>
 __device__ __forceinline__ void sweep_tiles(char* smem, const Slot* slots, int ntiles, int Nk, int tid, Needed needed,
                                             Body body, Abort abort = Abort()) {
   static_assert(DEPTH == 1 || DEPTH == 2, "one or two tiles in flight");
+  static_assert(STEP == 1 || (STEP == 2 && NSLOT == 2 && TMASK == 0), "pairs of natural tiles of one tensor");
   constexpr int KT = C::KT;
+  const int last_tile = ntiles - 1;
+  ntiles = (ntiles + STEP - 1) / STEP;  // from here on: steps
   constexpr int TB = C::kTileBytes;
   using Tile0 = typename std::conditional<(TMASK & 1) != 0, typename C::XtTile, typename C::KTile>::type;
   using Tile1 = typename std::conditional<(TMASK & 2) != 0, typename C::XtTile, typename C::KTile>::type;
@@ -281,8 +288,9 @@ __device__ __forceinline__ void sweep_tiles(char* smem, const Slot* slots, int n
   auto tile_ptr = [&](int s, bool tr, int kt) {
     return slots[s].base + (tr ? (long long)kt * KT * (long long)sizeof(T) : (long long)kt * KT * slots[s].row_bytes);
   };
-  auto fetch = [&](int kt, auto set_) {
+  auto fetch = [&](int step, auto set_) {
     constexpr int set = decltype(set_)::value;
+    const int kt = STEP == 1 ? step : min(STEP * step, last_tile);
     const int rows_left = Nk - kt * KT;
     const bool full = rows_left >= KT;  // uniform
     if constexpr ((TMASK & 1) != 0) {
@@ -292,7 +300,12 @@ __device__ __forceinline__ void sweep_tiles(char* smem, const Slot* slots, int n
       else s0.fetch(tile_ptr(0, false, kt), rows_left, slots[0].row_bytes, set);
     }
     if constexpr (NSLOT > 1) {
-      if constexpr ((TMASK & 2) != 0) {
+      if constexpr (STEP == 2) {
+        const int kt1 = min(STEP * step + 1, last_tile);
+        const int rows_left1 = Nk - kt1 * KT;
+        if (rows_left1 >= KT) s1.fetch_full(tile_ptr(1, false, kt1), set);
+        else s1.fetch(tile_ptr(1, false, kt1), rows_left1, slots[1].row_bytes, set);
+      } else if constexpr ((TMASK & 2) != 0) {
         s1.fetch_full(tile_ptr(1, true, kt), set);
       } else {
         if (full) s1.fetch_full(tile_ptr(1, false, kt), set);
