@@ -73,6 +73,21 @@ def test_dense_blocks_leave_the_list_kernel_early(forward_path):
     assert st["fwd_list_qk"] <= 2 * 4 * (4 + 11 * 8) + 64, st
 
 
+@pytest.mark.parametrize("causal,nq,nk", [(True, 273, 273), (False, 130, 337), (True, 448, 448), (False, 64, 65),
+                                           (True, 100, 1100)])
+@pytest.mark.parametrize("alpha", [1.5, 1.25])
+def test_split_blocks_take_key_tiles_in_pairs(causal, nq, nk, alpha):
+    """A few dense blocks run split in the tiled forward, whose K-only sweeps at D = 64 stage two 64-key tiles per
+    step: odd tile counts (the second tile of the last step lies beyond the sweep), a ragged last tile, a single
+    tile, and a causal window that ends inside a pair."""
+    data = _case(1, 2, nq, nk, 64, "bf16", "dense", seed=11)
+    g = gpu_run(data, alpha, "bf16", causal=causal, stats=True)
+    r = oracle_run(data, alpha, causal=causal)
+    st = g["stats"]
+    print(causal, nq, nk, alpha, compare(g, r, label=f"split pairs {causal} {nq} {nk} a{alpha}"), {k: v for k, v in st.items() if v})
+    assert st["fwd_blocks"] > 0  # the tiled kernel did run
+
+
 @pytest.mark.parametrize("scale,alpha,dtype", [("none", 1.5, "bf16"), ("none", 1.7, "bf16"), ("head", 1.25, "bf16"),
                                                ("none", 1.7, "fp32")])
 def test_moderate_support(scale, alpha, dtype):
