@@ -11,6 +11,15 @@ constexpr int kBlockRows = 128;  // rows (queries or keys) owned by a workgroup:
 // The long-sequence list kernel that takes two adjacent query blocks per workgroup runs only where its launch has
 // at least this many workgroups (three for each of the 256 CUs).
 constexpr int kPairMinWorkgroups = 768;
+// The forward's list kernel takes one query block per workgroup instead of a causal pair where the pairs would
+// leave the chip short of workgroups (fewer than three per CU; B 8, H 12, n 1024: 51 -> 47 us).  Launches of less
+// than half a workgroup per CU are as long as their longest block either way and keep the pairs.
+constexpr int kUnpairedBelowWorkgroups = 768;
+constexpr int kUnpairedFromWorkgroups = 128;
+inline bool fwd_lists_unpaired(long long heads, int nqb) {
+  const long long pairs = heads * ((nqb + 1) / 2);
+  return nqb >= 2 && pairs >= kUnpairedFromWorkgroups && pairs < kUnpairedBelowWorkgroups;
+}
 
 constexpr int kCandCap = 32;     // candidate entries per lane = per half row (forward lists)
 constexpr int kBwdCap = 16;      // support entries per lane = per half row (the lists the backward works from)

@@ -66,6 +66,7 @@ struct FwdSparseArgs {
   unsigned long long* stats;
   int nqb;
   int force_long;      // run the long-sequence kernels whatever the sizes (params.path = 2: test aid)
+  int unpaired;        // fwd_lists_kernel: one query block per workgroup (see fwd_lists_unpaired())
   TransposeRide ride;  // V^T copies for the tiled kernel, as extra workgroups of the finish launch
 };
 
@@ -406,7 +407,15 @@ __device__ __forceinline__ void fwd_lists_block(const FwdSparseArgs& A, int bh_,
 template <typename T, int D, int AM, bool BIAS, bool BITS>
 __global__ __launch_bounds__(kThreads, (ListCfg<T, D>::kOcc)) void fwd_lists_kernel(FwdSparseArgs A) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  const PairItem it = pair_item(A.nqb);
+  PairItem it;
+  if (A.unpaired) {  // a head's blocks on one XCD, the longest first
+    const int item = xcd_remap(blockIdx.x, gridDim.x);
+    it.bh = __builtin_amdgcn_readfirstlane(item / A.nqb);
+    it.first = A.nqb - 1 - __builtin_amdgcn_readfirstlane(item % A.nqb);
+    it.second = -1;
+  } else {
+    it = pair_item(A.nqb);
+  }
   if (blockIdx.x == 0 && threadIdx.x == 0) {
     A.dense_flag[A.g.B * A.g.H * A.nqb] = 0;
   }
@@ -414,7 +423,7 @@ __global__ __launch_bounds__(kThreads, (ListCfg<T, D>::kOcc)) void fwd_lists_ker
     *reinterpret_cast<unsigned long long*>(A.pool_cursor + (size_t)threadIdx.x * kSavedCursorStride) = 0ull;
   if (A.kcount) {
     // this workgroup's share of its head's per-key counters starts at zero for the finish kernel
-    const int npair = (A.nqb + 1) >> 1, pp = A.nqb - 1 - it.first;
+    const int npair = A.unpaired ? A.nqb : (A.nqb + 1) >> 1, pp = A.nqb - 1 - it.first;
     const int chunk = (A.g.Nk + npair - 1) / npair;
     int* dst = A.kcount + (long long)it.bh * A.g.Nk;
     for (int j = pp * chunk + (int)threadIdx.x; j < min(A.g.Nk, (pp + 1) * chunk); j += kThreads) dst[j] = 0;

@@ -90,13 +90,15 @@ inline Layout make_layout(const entmax_attn_params* p) {
   // cell strips of the list sweeps: one per workgroup (a pair of blocks), or two per workgroup of the
   // long-sequence kernel (two pairs of adjacent blocks)
   const size_t list_groups = bh * (size_t)(2 * ((L.nqb + 3) / 4));
+  // (the forward's strips: one per block where its list kernel takes the blocks one by one)
+  const size_t fwd_groups = fwd_lists_unpaired((long long)bh, L.nqb) ? bh * (size_t)L.nqb : list_groups;
   L.off_vt = 0;
   L.off_cand = kt_bytes;
   L.off_flcnt = L.off_cand + align_up(bh * (size_t)L.nqb * kThreads * kCandCap * 8);
   L.off_bounds = L.off_flcnt + align_up(bh * (size_t)p->Nq * 2 * sizeof(int));
   L.off_flags = L.off_bounds + align_up(bh * (size_t)p->Nq * 2 * sizeof(float));
   L.off_fcells = L.off_flags + align_up((bh * (size_t)L.nqb + 1 + kSplitMaxBlocks) * sizeof(int));  // flags, their count, flagged blocks
-  L.off_fknorm = L.off_fcells + align_up(list_groups * cell_bytes_per_workgroup(kCandCap));
+  L.off_fknorm = L.off_fcells + align_up(fwd_groups * cell_bytes_per_workgroup(kCandCap));
   L.total_fwd = L.off_fknorm + align_up(bh * sizeof(float));  // the heads' largest key norms (distance bias only)
   // the `saved` buffer: the pool's cursors, per half row (place, length) of its support list, one flag per block for the
   // backward, the heads' key norms, the number of support entries that name each key, and behind them the pool

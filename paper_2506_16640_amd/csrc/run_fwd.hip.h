@@ -47,6 +47,7 @@ bool launch_fwd_sparse(const FwdSparseArgs& a, int nblocks, hipStream_t st, void
     launched = true;
     }
   }
+  if (a.unpaired) nblocks = a.g.B * a.g.H * a.nqb;
   if (launched) {
   } else if (long_seq || a.force_long)
     hipLaunchKernelGGL((fwd_lists_kernel<T, D, AM, BIAS, true>), dim3((unsigned)nblocks), dim3(kThreads), smem, st, a);
@@ -162,6 +163,7 @@ int run_fwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
     sa.stats = reinterpret_cast<unsigned long long*>(stats);
     sa.nqb = L.nqb;
     sa.force_long = p->path == 2;
+    sa.unpaired = fwd_lists_unpaired((long long)p->B * p->H, L.nqb) ? 1 : 0;
     {
       TransposeJobs jobs{};
       jobs.job[0] = transpose_job(V, L.kv_sb, L.kv_sh, L.kv_sn, p->Nk, L.npad_k, Vt);

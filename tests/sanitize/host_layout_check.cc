@@ -56,6 +56,10 @@ static void check_valid(const entmax_attn_params& p) {
   CHECK(L.sv_flags - L.sv_lcnt >= bh * (size_t)p.Nq * 2 * sizeof(int));
   CHECK(L.total_saved - L.sv_flags >= bh * (size_t)L.nqb * sizeof(int));
   CHECK(L.off_fcells - L.off_flags >= bh * (size_t)L.nqb * sizeof(int));
+  {  // a cell strip for every workgroup of whichever list launch the forward picks
+    const size_t pairs = bh * (size_t)((L.nqb + 1) / 2), strips = fwd_lists_unpaired((long long)bh, L.nqb) ? bh * (size_t)L.nqb : pairs;
+    CHECK(L.off_fknorm - L.off_fcells >= strips * cell_bytes_per_workgroup(kCandCap));
+  }
   CHECK(L.off_flcnt - L.off_cand >= bh * (size_t)L.nqb * kThreads * kCandCap * 8);
   CHECK(L.off_bounds - L.off_flcnt >= bh * (size_t)p.Nq * 2 * sizeof(int));
   CHECK(L.off_flags - L.off_bounds >= bh * (size_t)p.Nq * 2 * sizeof(float));

@@ -88,6 +88,16 @@ def test_split_blocks_take_key_tiles_in_pairs(causal, nq, nk, alpha):
     assert st["fwd_blocks"] > 0  # the tiled kernel did run
 
 
+@pytest.mark.parametrize("n", [256, 300])
+def test_many_heads_take_query_blocks_one_by_one(n):
+    """From 128 causal pairs of query blocks up to 767 the forward's list kernel runs one block per workgroup
+    (B 8, H 16: 128 heads of two or three blocks); smaller launches, as in the other cases here, keep the pairs."""
+    data = _case(8, 16, n, n, 64, "bf16", "head", seed=21, planted=0.05)
+    g = gpu_run(data, 1.5, "bf16", stats=True)
+    r = oracle_run(data, 1.5)
+    print(n, compare(g, r, label=f"unpaired n{n}"), {k: v for k, v in g["stats"].items() if v})
+
+
 @pytest.mark.parametrize("scale,alpha,dtype", [("none", 1.5, "bf16"), ("none", 1.7, "bf16"), ("head", 1.25, "bf16"),
                                                ("none", 1.7, "fp32")])
 def test_moderate_support(scale, alpha, dtype):
