@@ -152,3 +152,43 @@ def test_binding_rejects_mismatched_tensors(binding):
         b.entmax_attn_bwd(q, k, k, q, q[:, :, :8], torch.zeros(1, 2, 16))
     with pytest.raises(TypeError):
         b.make_params(q.half(), k.half(), 1.5, 1.0, True, None, 0)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The benchmark measures one GPU's share; asked for more it says so and exits without touching a device."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_forward_list_launch_shapes():
+    """Host arithmetic of the forward's list launch, seen through the workspace size: causal pairs of query blocks
+    by default (one scratch strip per pair), single blocks from 128 pairs up to 767 (one strip per block)."""
+    import ctypes
+    from paper_2506_16640_amd import binding as b
+    lib = b._lib
+
+    def ws(B, H, n):
+        p = b.Params()
+        p.B, p.H, p.Nq, p.Nk, p.D = B, H, n, n, 64
+        p.dtype, p.causal, p.alpha, p.delta = 0, 1, 1.5, 1.0
+        p.q_stride_b = p.kv_stride_b = H * n * 64
+        p.q_stride_h = p.kv_stride_h = n * 64
+        p.q_stride_n = p.kv_stride_n = 64
+        assert lib.entmax_attn_check_params(ctypes.byref(p)) == 0
+        return int(lib.entmax_attn_workspace_bytes(ctypes.byref(p), 0))
+
+    strip = 256 * 32 * 20  # threads x cells per thread x bytes per cell
+    # n = 1024: 8 blocks, 4 pairs per head.  12 and 24 heads (48, 96 pairs) keep the pairs, 48 heads (192 pairs) do not
+    w12, w24, w48 = ws(1, 12, 1024), ws(2, 12, 1024), ws(4, 12, 1024)
+    extra = (w48 - w24) - 2 * (w24 - w12)
+    assert abs(extra - 48 * 4 * strip) < 65536, extra
+    # from 768 pairs on the pairs are back: 192 and 384 heads (768, 1536 pairs)
+    w192, w384, w96 = ws(16, 12, 1024), ws(32, 12, 1024), ws(8, 12, 1024)
+    assert abs((w384 - w192) - 192 * ((w24 - w12) // 12)) < 65536
+    assert w96 > w192 // 2 + 96 * 3 * strip  # 96 heads (384 pairs) carry a strip per block
