@@ -361,7 +361,7 @@ __device__ __forceinline__ void fwd_lists_block(const FwdSparseArgs& A, int bh_,
       [&](int kt) { return kt == kt_vote + 1 && all_dense(); });
   if (all_dense()) {  // (the sweep ended on a barrier)
     __syncthreads();  // every thread has read the votes before the next block's zeroes them
-    if (q.tid == 0) A.dense_flag[flag_idx] = 1;
+    if (q.tid == 0) A.dense_flag[flag_idx] = kFlagDense;
     if (A.stats && q.lane == 0) atomicAdd(&A.stats[ENTMAX_STAT_FWD_LIST_QK], (unsigned long long)n_vis);
     return;
   }
@@ -384,7 +384,9 @@ __device__ __forceinline__ void fwd_lists_block(const FwdSparseArgs& A, int bh_,
   const bool fits = collect_sweep<C, T, D, kCandCap, ListCfg<T, D>::kLdsCells>(q, g, A.K, tiles, ovf, lds_cells, live, lo, A.cells, mylist, cnt, n_qk2, n_cand_tiles,
                                                                                      keep_bits ? mybits : nullptr, strip_no);
   if (!fits) {
-    if (q.tid == 0) A.dense_flag[flag_idx] = 1;
+    // the tiled kernel takes the block, and with it what the first sweep found out about every row
+    if (q.tid == 0) A.dense_flag[flag_idx] = kFlagWithBounds;
+    if (q.valid && q.hh == 0) A.bounds[row_idx] = make_float2(lo, y1);
   } else {
     if (q.tid == 0) A.dense_flag[flag_idx] = 0;
     if (q.valid) {

@@ -195,6 +195,7 @@ int run_fwd(const entmax_attn_params* p, const Layout& L, const void* Q, const v
   a.mask_words = L.mask_words;
   a.dense_flag = lists ? dense_flag : nullptr;
   a.dense_count = lists ? dense_flag + (size_t)p->B * p->H * L.nqb : nullptr;
+  a.bounds = lists ? reinterpret_cast<const float2*>(ws + L.off_bounds) : nullptr;
   const int nwg = fwd_workgroups(p->B * p->H, L.nqb, lists);
   if (!launch_fwd_am<T, D, BIAS>(a, alpha_mode(p->alpha), nwg, st)) return ENTMAX_ATTN_LAUNCH_FAILED;
   record(ev, ENTMAX_FWD_PHASE_TILED + 1, st);
