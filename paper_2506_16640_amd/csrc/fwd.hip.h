@@ -222,12 +222,14 @@ __device__ __forceinline__ bool gauss_start(float mu, float sigma, float n, floa
 // Keys per LDS tile and waves per SIMD of the tiled forward kernel, as measured on a dense-regime workload
 // (B 4, H 12, n 4096, every block on this kernel): at D = 64, 64-key tiles leave room for three workgroups per CU
 // (168 registers, no spills) and run the threshold sweeps -- vector-ALU bound, so a third wave per SIMD fills the
-// gaps -- a fifth faster than 128-key tiles with two (0.88 against 1.10 ms); at D = 128 the register bound would
-// spill (1.83 against 1.11 ms at n 16384), so that case keeps 128-key tiles and one workgroup per CU.
+// gaps -- a fifth faster than 128-key tiles with two (0.88 against 1.10 ms); at D = 128 three would spill badly
+// (1.83 against 1.11 ms at n 16384), but 64-key tiles (64 KB of LDS) with two workgroups per CU (256 registers, a
+// dozen spilled) beat 128-key tiles with one: B 2, H 16, n 8192, every block here: 3.87 -> 2.61 ms; 162 split
+// blocks (alpha 1.25): 0.89 -> 0.70 ms.
 template <typename T, int D>
 struct FwdTile {
-  static constexpr int value = sizeof(T) == 2 ? (D == 64 ? 64 : 128) : 32;
-  static constexpr int kOcc = (sizeof(T) == 2 && D == 64) ? 3 : 1;
+  static constexpr int value = sizeof(T) == 2 ? 64 : 32;
+  static constexpr int kOcc = sizeof(T) == 2 ? (D == 64 ? 3 : 2) : 1;
 };
 
 // Keys per LDS tile and workgroups per CU of the list sweeps (fwd_sparse.hip.h, bwd_sparse.hip.h), as measured:
@@ -327,8 +329,8 @@ __device__ __forceinline__ void fwd_block(const FwdArgs& A, int bh_, int blk_, i
   // The sweeps over K alone (row maximum, threshold).  SPLIT with two 32-key blocks per tile (D = 64): two key tiles
   // between barriers -- with one, half of the waves have no block of their own in it, and every tile costs a
   // barrier and a wait for the staged copy whatever the work (B 4, H 12, n 4096, alpha 1.25, 183 flagged blocks:
-  // 351 -> 275 us).  With four blocks per tile (D = 128) every wave has one already, and pairs were slower
-  // (B 2, H 16, n 8192: 1042 -> 1106 us).
+  // 351 -> 275 us).  With four blocks per tile (128-key tiles) every wave has one already, and pairs were slower
+  // (D 128, B 2, H 16, n 8192: 1042 -> 1106 us).
   auto sweep_k = [&](auto needed, auto body) {
     if constexpr (SPLIT && NSB < kWaves) {
       Slot kk[2] = {slots[0], slots[0]};

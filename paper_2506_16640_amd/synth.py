@@ -23,6 +23,7 @@ CONFIGS = {
     "c5": dict(B=2, H=16, n=8192, d=128, dtype="bf16", alpha=1.5, scale="head", planted=0.0, bwd=True),
     "c3d": dict(B=4, H=12, n=4096, d=64, dtype="bf16", alpha=1.5, scale="dense", planted=0.05, bwd=True),
     "c4d": dict(B=1, H=12, n=32768, d=64, dtype="bf16", alpha=1.5, scale="dense", planted=0.05, bwd=False),
+    "c5d": dict(B=2, H=16, n=8192, d=128, dtype="bf16", alpha=1.5, scale="dense", planted=0.0, bwd=True),
 }
 
 
