@@ -326,11 +326,11 @@ __device__ __forceinline__ void fwd_block(const FwdArgs& A, int bh_, int blk_, i
   slots[1].row_bytes = (long long)g.npad_k * (long long)sizeof(T);
 
   unsigned n_vis = 0, n_qk_solve = 0, n_eval = 0, n_qk_pv = 0, n_pv = 0, n_sweeps = 0;
-  // The sweeps over K alone (row maximum, threshold).  SPLIT with two 32-key blocks per tile (D = 64): two key tiles
-  // between barriers -- with one, half of the waves have no block of their own in it, and every tile costs a
-  // barrier and a wait for the staged copy whatever the work (B 4, H 12, n 4096, alpha 1.25, 183 flagged blocks:
-  // 351 -> 275 us).  With four blocks per tile (128-key tiles) every wave has one already, and pairs were slower
-  // (D 128, B 2, H 16, n 8192: 1042 -> 1106 us).
+  // The sweeps over K alone (row maximum, threshold).  SPLIT with two 32-key blocks per tile (64-key tiles): two
+  // key tiles between barriers -- with one, half of the waves have no block of their own in it, and every tile
+  // costs a barrier and a wait for the staged copy whatever the work (B 4, H 12, n 4096, alpha 1.25, 183 flagged
+  // blocks: 351 -> 275 us).  With four blocks per tile (128-key tiles, as D = 128 once had) every wave has one
+  // already, and pairs were slower (B 2, H 16, n 8192: 1042 -> 1106 us).
   auto sweep_k = [&](auto needed, auto body) {
     if constexpr (SPLIT && NSB < kWaves) {
       Slot kk[2] = {slots[0], slots[0]};
@@ -366,8 +366,7 @@ __device__ __forceinline__ void fwd_block(const FwdArgs& A, int bh_, int blk_, i
     have_bounds = A.bounds != nullptr && __builtin_amdgcn_readfirstlane(A.dense_flag[q.bh * A.nqb + q.qb]) == kFlagWithBounds;
     if (have_bounds && q.valid) given = A.bounds[(long long)q.bh * g.Nq + q.i];
   }
-  if (!have_bounds)
-  sweep_k(
+  if (!have_bounds) sweep_k(
       [&](int kt) { return q.tile_in_window(kt); },
       [&](int kt, const char* tl) {
         if (!q.tile_in_wave_window(kt)) return;
