@@ -598,7 +598,9 @@ __global__ __launch_bounds__(kThreads, (FwdTile<T, D>::kOcc)) void fwd_kernel(Fw
     const int xcd = blockIdx.x & 7, place = blockIdx.x >> 3;
     const int slot = (place / kWaves) * 8 + xcd;
     if (slot >= nflagged) return;
-    const int item = __builtin_amdgcn_readfirstlane(A.dense_count[1 + slot]);
+    // (the list grows roughly in launch order of the finish kernel, a head's short early blocks first: taken from
+    // its end, the long blocks start first)
+    const int item = __builtin_amdgcn_readfirstlane(A.dense_count[nflagged - slot]);
     fwd_block<T, D, AM, BIAS, true>(A, item / A.nqb, item % A.nqb, place % kWaves, smem);
     return;
   }
