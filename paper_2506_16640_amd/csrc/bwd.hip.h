@@ -40,6 +40,7 @@ struct BwdArgs {
                          // 2 the whole head
   const int* block_flag; // with head_flag: [B*H*nqb] the query blocks the list path left over
   int nqb, nkb, nqg, mask_words;
+  int xcd_room;  // workgroups of the kernel being launched that one XCD holds at a time (see bwd_tiled_item)
   // whether query block qb of head bh is this path's (call only for heads whose flag is not 0)
   __device__ __forceinline__ bool block_is_ours(int bh, int qb) const {
     if (!head_flag) return true;
@@ -481,18 +482,36 @@ __device__ __forceinline__ void bwd_dkv_block(const BwdArgs& A, int bh_, int blk
   if (A.stats && lane == 0) atomicAdd(&A.stats[ENTMAX_STAT_BWD_DKV_TILES], (unsigned long long)n_tiles);
 }
 
+// Which (head, block) item a workgroup of the tiled backward kernels takes.  When most heads are here, a head's
+// blocks share an XCD (xcd_remap: one L2 for the head's K and V).  When only a few heads are -- the others went
+// down the list path -- that order would queue a whole head's long-running workgroups on one XCD's 32 CUs while
+// seven XCDs idle (B 2, H 16, n 8192, D 128, two heads of 32 flagged: 64 workgroups at one per CU ran as two rounds,
+// 0.79 ms for work that takes 0.40), so where a head has more blocks than an XCD holds at a time the items are then
+// dealt out to the XCDs in turn (0.79 -> 0.59 ms, dK/dV 0.83 -> 0.70 ms).  Every workgroup makes the same choice
+// from the heads' flags (up to 1024 heads are counted; more keep the head-per-XCD order).
+__device__ __forceinline__ int bwd_tiled_item(const BwdArgs& A, int per_head) {
+  const int nheads = A.g.B * A.g.H;
+  if (A.head_flag == nullptr || nheads > 4 * kThreads || per_head <= A.xcd_room) return xcd_remap(blockIdx.x, gridDim.x);
+  int flagged = 0;
+  for (int k0 = 0; k0 < nheads; k0 += kThreads) {
+    const int k = k0 + (int)threadIdx.x;
+    flagged += __syncthreads_count(k < nheads && A.head_flag[k] != 0);
+  }
+  return 4 * flagged <= nheads ? (int)blockIdx.x : xcd_remap(blockIdx.x, gridDim.x);
+}
+
 // The register-heavy kernels hold two workgroups per CU; one block per workgroup, long blocks first.
 template <typename T, int D, int AM, bool BIAS>
 __global__ __launch_bounds__(kThreads) void bwd_dq_kernel(BwdArgs A) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  const int item = xcd_remap(blockIdx.x, gridDim.x);
+  const int item = bwd_tiled_item(A, A.nqb);
   if (A.head_flag && __builtin_amdgcn_readfirstlane(A.head_flag[item / A.nqb]) == 0) return;
   bwd_dq_block<T, D, AM, BIAS>(A, item / A.nqb, A.nqb - 1 - item % A.nqb, smem);
 }
 template <typename T, int D, int AM>
 __global__ __launch_bounds__(kThreads) void bwd_dkv_kernel(BwdArgs A) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  const int item = xcd_remap(blockIdx.x, gridDim.x);
+  const int item = bwd_tiled_item(A, A.nkb);
   if (A.head_flag && __builtin_amdgcn_readfirstlane(A.head_flag[item / A.nkb]) == 0) return;
   bwd_dkv_block<T, D, AM>(A, item / A.nkb, item % A.nkb, smem);
 }

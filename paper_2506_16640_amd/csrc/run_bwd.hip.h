@@ -9,7 +9,10 @@ namespace entmax {
 namespace {
 
 template <typename T, int D, int AM, bool BIAS>
-bool launch_bwd_kernels(const BwdArgs& a, const Layout& L, int B, int H, hipStream_t st, void* const* ev) {
+bool launch_bwd_kernels(const BwdArgs& a_in, const Layout& L, int B, int H, hipStream_t st, void* const* ev) {
+  BwdArgs a = a_in;
+  // workgroups one XCD (32 CUs, 160 KB of LDS each) holds at a time: the registers allow two per CU
+  auto xcd_room = [](size_t smem) { return 32 * (int)(smem * 2 <= 160 * 1024 ? 2 : 1); };
   size_t smem_dq = 6 * (size_t)QCtx<T, D>::kTileBytes + (size_t)(kWaves + 1) * a.mask_words * 4 + kWaves * 64 * 4 + 64;
   size_t smem_dkv = 8 * (size_t)QCtx<T, D>::kTileBytes + 2 * 4 * (size_t)QCtx<T, D>::KT * 4 + (size_t)a.nqg + 64;
   constexpr auto k_dq = bwd_dq_kernel<T, D, AM, BIAS>;
@@ -17,9 +20,11 @@ bool launch_bwd_kernels(const BwdArgs& a, const Layout& L, int B, int H, hipStre
   if (!ensure_dynamic_lds<k_dq>(smem_dq) || !ensure_dynamic_lds<k_dkv>(smem_dkv))
     return false;
   record(ev, ENTMAX_BWD_PHASE_MASK + 1, st);
+  a.xcd_room = xcd_room(smem_dq);
   hipLaunchKernelGGL(k_dq, dim3((unsigned)(B * H * L.nqb)), dim3(kThreads), smem_dq, st, a);
   if (!launch_ok()) return false;
   record(ev, ENTMAX_BWD_PHASE_DQ + 1, st);
+  a.xcd_room = xcd_room(smem_dkv);
   hipLaunchKernelGGL(k_dkv, dim3((unsigned)(B * H * L.nkb)), dim3(kThreads), smem_dkv, st, a);
   if (!launch_ok()) return false;
   record(ev, ENTMAX_BWD_PHASE_DKV + 1, st);
